@@ -1,0 +1,498 @@
+/*
+ * CPU oracle for cache-aware CNN inference over a video stream (DeepCache).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is a plain, slow, obviously-correct
+ * implementation used to check the HIP library and to report a CPU baseline.
+ * It shares no code with the HIP path and nothing in the product path may
+ * call it.  Every function follows the paper's steps in the paper's order.
+ *
+ * Floating point: feature maps are *stored* in the path's storage type
+ * (fp32, or bf16 kept in a float whose low 16 bits are zero); every sum is
+ * accumulated in fp64 and rounded once when stored.
+ *
+ * Conventions (readings of points the paper leaves open are marked "reading"):
+ *  - frames: uint8 [H][W][C], interleaved channels, left-top origin;
+ *  - feature maps: float [H][W][C] (channels last);
+ *  - conv weights: float [cout][k][k][cin];
+ *  - a motion vector (dx,dy) points from a block of the current frame to its
+ *    match in the previous frame: source = current + (dx,dy)  (Section 4,
+ *    Step 2: (x',y') is the position in the previous frame, Step 3 averages
+ *    x'-x and y'-y).
+ *
+ * Pins (tests/test_oracle_*.py): the worked propagation example of Section 5
+ * ((100,100,100,40) under conv k11 s2 p5 -> (53,53,45,15)), the erosion
+ * arithmetic of Section 4 (two 5x5 -> 18 px, merged 5x10 -> 24 px), the 5x5
+ * example of Section 2.2, brute-force window containment for the region rule,
+ * closed-form matching results on constructed frame pairs, scipy's correlate
+ * for the convolution, and the three invariants (zero reuse == full forward,
+ * identical frames -> full reuse, exact shifted copy == full forward).
+ * Unpinned by the paper (pinned only by hand cases of the stated reading):
+ * the merge decomposition, the rounding of fractional motion, and the source
+ * offset when the motion is not a multiple of the cumulative stride.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct { int32_t x, y, w, h; } oc_rect;
+
+enum { OC_CONV = 0, OC_MAXPOOL = 1, OC_RELU = 2, OC_ADD = 3 };
+
+typedef struct {
+    int32_t type;          /* OC_* */
+    int32_t k, s, p;       /* kernel, stride, padding (conv, pool) */
+    int32_t cin, cout;
+    int32_t relu;          /* fused ReLU after conv / add */
+    int32_t in0, in1;      /* producer tensor ids; tensor 0 = network input, tensor i+1 = layer i output */
+} oc_layer;
+
+/* ------------------------------------------------------------------ */
+/* Section 4, Steps 1-4: block matching                               */
+/* ------------------------------------------------------------------ */
+
+/* Sum of squared differences between the BxB block of `cur` at (x,y) and the
+ * BxB block of `prev` at (x+dx, y+dy), over all C channels.  PSNR of Section 4
+ * is a decreasing function of this sum, so "PSNR > T" is "SSD <= bound"
+ * (reading: the bound is passed as a per-block total). */
+static uint32_t block_ssd(const uint8_t* cur, const uint8_t* prev, int W, int C,
+                          int B, int x, int y, int dx, int dy)
+{
+    uint32_t s = 0;
+    for (int r = 0; r < B; ++r)
+        for (int c = 0; c < B; ++c)
+            for (int ch = 0; ch < C; ++ch) {
+                int a = cur[((size_t)(y + r) * W + (x + c)) * C + ch];
+                int b = prev[((size_t)(y + dy + r) * W + (x + dx + c)) * C + ch];
+                s += (uint32_t)((a - b) * (a - b));
+            }
+    return s;
+}
+
+static int iabs(int v) { return v < 0 ? -v : v; }
+
+/* round(num/den) to nearest, halves away from zero; den > 0 (reading) */
+static int32_t round_div(int64_t num, int64_t den)
+{
+    int64_t a = num < 0 ? -num : num;
+    int64_t q = (2 * a + den) / (2 * den);
+    return (int32_t)(num < 0 ? -q : q);
+}
+
+/*
+ * Steps 1-4 for one frame pair.
+ *   mv        [gh][gw][2]  best vector (dx,dy) per block (exhaustive search,
+ *                          Section 7.6 "ES"), candidates |dx|,|dy|<=R whose
+ *                          window lies inside the previous frame (reading);
+ *                          ties: smallest (ssd, |dx|+|dy|, dy, dx) (reading)
+ *   best_ssd  [gh][gw]
+ *   gmv       [2]          Step 3 mean motion over blocks with best_ssd<=max_ssd
+ *   n_pass    [1]          K of Step 3
+ *   mask      [gh][gw]     Step 4: 1 iff block at +gmv is in-frame and SSD<=max_ssd
+ * gh = H/B, gw = W/B (integer division; a remainder strip is never reusable).
+ */
+void oc_match_blocks(const uint8_t* cur, const uint8_t* prev, int H, int W, int C,
+                     int B, int R, uint32_t max_ssd,
+                     int16_t* mv, uint32_t* best_ssd, int32_t* gmv, int32_t* n_pass,
+                     uint8_t* mask)
+{
+    int gh = H / B, gw = W / B;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int by = 0; by < gh; ++by)
+        for (int bx = 0; bx < gw; ++bx) {
+            int x = bx * B, y = by * B;
+            int have = 0, bdx = 0, bdy = 0;
+            uint32_t bs = 0;
+            for (int dy = -R; dy <= R; ++dy)
+                for (int dx = -R; dx <= R; ++dx) {
+                    if (x + dx < 0 || y + dy < 0 || x + dx + B > W || y + dy + B > H) continue;
+                    uint32_t s = block_ssd(cur, prev, W, C, B, x, y, dx, dy);
+                    int better;
+                    if (!have) better = 1;
+                    else if (s != bs) better = s < bs;
+                    else if (iabs(dx) + iabs(dy) != iabs(bdx) + iabs(bdy))
+                        better = iabs(dx) + iabs(dy) < iabs(bdx) + iabs(bdy);
+                    else if (dy != bdy) better = dy < bdy;
+                    else better = dx < bdx;
+                    if (better) { have = 1; bs = s; bdx = dx; bdy = dy; }
+                }
+            mv[(by * gw + bx) * 2 + 0] = (int16_t)bdx;
+            mv[(by * gw + bx) * 2 + 1] = (int16_t)bdy;
+            best_ssd[by * gw + bx] = bs;
+        }
+    /* Step 3 */
+    int64_t sx = 0, sy = 0;
+    int K = 0;
+    for (int i = 0; i < gh * gw; ++i)
+        if (best_ssd[i] <= max_ssd) { sx += mv[2 * i]; sy += mv[2 * i + 1]; ++K; }
+    *n_pass = K;
+    if (K == 0) {                      /* nothing matched: no reuse in this frame */
+        gmv[0] = gmv[1] = 0;
+        memset(mask, 0, (size_t)gh * gw);
+        return;
+    }
+    int mx = round_div(sx, K), my = round_div(sy, K);
+    gmv[0] = mx; gmv[1] = my;
+    /* Step 4 */
+    for (int by = 0; by < gh; ++by)
+        for (int bx = 0; bx < gw; ++bx) {
+            int x = bx * B, y = by * B;
+            int ok = !(x + mx < 0 || y + my < 0 || x + mx + B > W || y + my + B > H);
+            if (ok) ok = block_ssd(cur, prev, W, C, B, x, y, mx, my) <= max_ssd;
+            mask[by * gw + bx] = (uint8_t)ok;
+        }
+}
+
+/* ------------------------------------------------------------------ */
+/* Section 4, Step 5: merge properly matched blocks into rectangles   */
+/* ------------------------------------------------------------------ */
+
+/* Reading: scan blocks row-major; at the first set, unclaimed block grow a
+ * run to the right over set, unclaimed blocks, then grow the run downwards
+ * while the whole run is set and unclaimed; emit it in pixel units.
+ * Returns the number of rectangles (writes at most `cap`). */
+int oc_merge_blocks(const uint8_t* mask, int gh, int gw, int B, oc_rect* out, int cap)
+{
+    uint8_t* used = (uint8_t*)calloc((size_t)gh * gw, 1);
+    int n = 0;
+    for (int by = 0; by < gh; ++by)
+        for (int bx = 0; bx < gw; ++bx) {
+            if (!mask[by * gw + bx] || used[by * gw + bx]) continue;
+            int w = 0;
+            while (bx + w < gw && mask[by * gw + bx + w] && !used[by * gw + bx + w]) ++w;
+            int h = 1;
+            for (;;) {
+                if (by + h >= gh) break;
+                int all = 1;
+                for (int i = 0; i < w; ++i)
+                    if (!mask[(by + h) * gw + bx + i] || used[(by + h) * gw + bx + i]) { all = 0; break; }
+                if (!all) break;
+                ++h;
+            }
+            for (int j = 0; j < h; ++j)
+                for (int i = 0; i < w; ++i) used[(by + j) * gw + bx + i] = 1;
+            if (n < cap) { out[n].x = bx * B; out[n].y = by * B; out[n].w = w * B; out[n].h = h * B; }
+            ++n;
+        }
+    free(used);
+    return n;
+}
+
+/* ------------------------------------------------------------------ */
+/* Section 5, Table 2: region transformation D_t                      */
+/* ------------------------------------------------------------------ */
+
+static int floor_div(int a, int b) { int q = a / b; if ((a % b != 0) && ((a < 0) != (b < 0))) --q; return q; }
+static int ceil_div(int a, int b) { return -floor_div(-a, b); }
+
+/* Conv / pool row of Table 2.  The left-top corner is the table's
+ * ceil((x+p)/s).  The size printed in the table disagrees with both worked
+ * examples of the paper; the reading used here is the largest output
+ * rectangle whose kxk windows lie wholly inside the input rectangle, which
+ * reproduces both examples: last output column = floor((x+w-k+p)/s).
+ * Returns 0 if nothing is left. */
+int oc_dt_window(oc_rect in, int k, int s, int p, oc_rect* out)
+{
+    int x0 = ceil_div(in.x + p, s), x1 = floor_div(in.x + in.w - k + p, s);
+    int y0 = ceil_div(in.y + p, s), y1 = floor_div(in.y + in.h - k + p, s);
+    if (x1 < x0 || y1 < y0) return 0;
+    out->x = x0; out->y = y0; out->w = x1 - x0 + 1; out->h = y1 - y0 + 1;
+    return 1;
+}
+
+/* Concat row of Table 2, used for a residual add: overlap of two rectangles. */
+int oc_dt_overlap(oc_rect a, oc_rect b, oc_rect* out)
+{
+    int x0 = a.x > b.x ? a.x : b.x, y0 = a.y > b.y ? a.y : b.y;
+    int x1 = (a.x + a.w < b.x + b.w) ? a.x + a.w : b.x + b.w;
+    int y1 = (a.y + a.h < b.y + b.h) ? a.y + a.h : b.y + b.h;
+    if (x1 <= x0 || y1 <= y0) return 0;
+    out->x = x0; out->y = y0; out->w = x1 - x0; out->h = y1 - y0;
+    return 1;
+}
+
+/* Keep the part of r whose source r+(dx,dy) lies inside a WxH map. */
+static int clip_to_source(oc_rect r, int dx, int dy, int W, int H, oc_rect* out)
+{
+    int x0 = r.x, x1 = r.x + r.w, y0 = r.y, y1 = r.y + r.h;
+    if (x0 < -dx) x0 = -dx;
+    if (y0 < -dy) y0 = -dy;
+    if (x1 > W - dx) x1 = W - dx;
+    if (y1 > H - dy) y1 = H - dy;
+    if (x0 < 0) x0 = 0;
+    if (y0 < 0) y0 = 0;
+    if (x1 > W) x1 = W;
+    if (y1 > H) y1 = H;
+    if (x1 <= x0 || y1 <= y0) return 0;
+    out->x = x0; out->y = y0; out->w = x1 - x0; out->h = y1 - y0;
+    return 1;
+}
+
+/*
+ * Propagate the reusable rectangles of the input frame through the stack
+ * (Section 5 "Propagation").  For tensor t (0 = input, i+1 = output of layer i):
+ *   rects[t*cap .. t*cap+n_rects[t])  reusable rectangles in that tensor's pixels
+ *   dxy[2t], dxy[2t+1]                source offset in that tensor's pixels
+ *   cum_stride[t]                     product of the strides on the way there
+ * Reading (paper silent when the motion is not a multiple of the stride): one
+ * offset per tensor, round(M / cum_stride) halves away from zero; a rectangle
+ * is clipped so that its source stays inside the map.
+ * Returns 0, or -1 if some list overflowed `cap` (counts are still exact).
+ */
+int oc_propagate(const oc_layer* L, int n_layers, int H, int W,
+                 const oc_rect* rects0, int n0, int mx, int my,
+                 oc_rect* rects, int cap, int32_t* n_rects, int32_t* dxy,
+                 int32_t* cum_stride, int32_t* hw /* [2*(n_layers+1)] heights, widths */)
+{
+    int overflow = 0;
+    hw[0] = H; hw[1] = W; cum_stride[0] = 1; dxy[0] = mx; dxy[1] = my;
+    int n = 0;
+    for (int i = 0; i < n0; ++i) {
+        oc_rect r;
+        if (!clip_to_source(rects0[i], mx, my, W, H, &r)) continue;
+        if (n < cap) rects[n] = r; else overflow = 1;
+        ++n;
+    }
+    n_rects[0] = n;
+    for (int li = 0; li < n_layers; ++li) {
+        const oc_layer* l = &L[li];
+        int t = li + 1, a = l->in0;
+        int ha = hw[2 * a], wa = hw[2 * a + 1];
+        int na = n_rects[a] < cap ? n_rects[a] : cap;
+        const oc_rect* ra = rects + (size_t)a * cap;
+        oc_rect* ro = rects + (size_t)t * cap;
+        int ho = ha, wo = wa, S = cum_stride[a];
+        if (l->type == OC_CONV || l->type == OC_MAXPOOL) {
+            ho = (ha + 2 * l->p - l->k) / l->s + 1;
+            wo = (wa + 2 * l->p - l->k) / l->s + 1;
+            S *= l->s;
+        }
+        hw[2 * t] = ho; hw[2 * t + 1] = wo; cum_stride[t] = S;
+        int dx = round_div(mx, S), dy = round_div(my, S);
+        dxy[2 * t] = dx; dxy[2 * t + 1] = dy;
+        n = 0;
+        if (l->type == OC_CONV || l->type == OC_MAXPOOL) {
+            for (int i = 0; i < na; ++i) {
+                oc_rect r, c;
+                if (!oc_dt_window(ra[i], l->k, l->s, l->p, &r)) continue;
+                if (!clip_to_source(r, dx, dy, wo, ho, &c)) continue;
+                if (n < cap) ro[n] = c; else overflow = 1;
+                ++n;
+            }
+        } else if (l->type == OC_ADD) {
+            int b = l->in1;
+            int nb = n_rects[b] < cap ? n_rects[b] : cap;
+            const oc_rect* rb = rects + (size_t)b * cap;
+            for (int i = 0; i < na; ++i)
+                for (int j = 0; j < nb; ++j) {
+                    oc_rect r, c;
+                    if (!oc_dt_overlap(ra[i], rb[j], &r)) continue;
+                    if (!clip_to_source(r, dx, dy, wo, ho, &c)) continue;
+                    if (n < cap) ro[n] = c; else overflow = 1;
+                    ++n;
+                }
+        } else {                       /* "Others" row: unchanged */
+            for (int i = 0; i < na; ++i) {
+                oc_rect c;
+                if (!clip_to_source(ra[i], dx, dy, wo, ho, &c)) continue;
+                if (n < cap) ro[n] = c; else overflow = 1;
+                ++n;
+            }
+        }
+        n_rects[t] = n;
+    }
+    return overflow ? -1 : 0;
+}
+
+/* Boolean map of Section 5 "Reuse", step 2: 1 where the pixel lies in a rectangle. */
+void oc_rasterize(const oc_rect* rects, int n, int H, int W, uint8_t* mask)
+{
+    memset(mask, 0, (size_t)H * W);
+    for (int i = 0; i < n; ++i)
+        for (int y = rects[i].y; y < rects[i].y + rects[i].h; ++y)
+            for (int x = rects[i].x; x < rects[i].x + rects[i].w; ++x)
+                mask[(size_t)y * W + x] = 1;
+}
+
+/* ------------------------------------------------------------------ */
+/* storage rounding                                                   */
+/* ------------------------------------------------------------------ */
+
+/* fp32 -> bf16 (round to nearest, ties to even), returned as a float whose low
+ * 16 bits are zero.  Finite inputs only (NaN is passed through quietly). */
+float oc_round_bf16(float v)
+{
+    uint32_t u;
+    memcpy(&u, &v, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) { u &= 0xffff0000u; if (v != v) u |= 0x00400000u; }
+    else {
+        uint32_t lsb = (u >> 16) & 1u;
+        u += 0x7fffu + lsb;
+        u &= 0xffff0000u;
+    }
+    float r;
+    memcpy(&r, &u, 4);
+    return r;
+}
+
+static float store_val(double acc, int bf16)
+{
+    float f = (float)acc;
+    return bf16 ? oc_round_bf16(f) : f;
+}
+
+void oc_round_bf16_array(float* a, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) a[i] = oc_round_bf16(a[i]);
+}
+
+/* network input: (u8 - 128) / 128, exact in fp32 and in bf16 */
+void oc_frame_to_tensor(const uint8_t* frame, size_t n, float* out)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = (float)((int)frame[i] - 128) / 128.0f;
+}
+
+/* ------------------------------------------------------------------ */
+/* Section 5 "Reuse": cache-aware convolution                         */
+/* ------------------------------------------------------------------ */
+
+/*
+ * out[y][x][:] = cache_prev[y+dy][x+dx][:]                 where mask[y][x] = 1   (step 1)
+ *              = bias + sum_{ky,kx,ci} in * w  (+ReLU)     elsewhere              (step 3)
+ * mask == NULL (or cache_prev == NULL) means: compute every pixel.
+ * in [Hin][Win][cin], out [Hout][Wout][cout], w [cout][k][k][cin].
+ */
+void oc_conv_cached(const float* in, int Hin, int Win, int cin,
+                    const float* w, const float* bias, int cout, int k, int s, int p, int relu,
+                    const float* cache_prev, const uint8_t* mask, int dx, int dy,
+                    int bf16, float* out)
+{
+    int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
+#pragma omp parallel for schedule(dynamic)
+    for (int y = 0; y < Hout; ++y)
+        for (int x = 0; x < Wout; ++x) {
+            float* o = out + ((size_t)y * Wout + x) * cout;
+            if (mask && cache_prev && mask[(size_t)y * Wout + x]) {
+                const float* c = cache_prev + ((size_t)(y + dy) * Wout + (x + dx)) * cout;
+                for (int co = 0; co < cout; ++co) o[co] = c[co];
+                continue;
+            }
+            for (int co = 0; co < cout; ++co) {
+                double acc = bias ? (double)bias[co] : 0.0;
+                for (int ky = 0; ky < k; ++ky) {
+                    int iy = y * s - p + ky;
+                    if (iy < 0 || iy >= Hin) continue;
+                    for (int kx = 0; kx < k; ++kx) {
+                        int ix = x * s - p + kx;
+                        if (ix < 0 || ix >= Win) continue;
+                        const float* ip = in + ((size_t)iy * Win + ix) * cin;
+                        const float* wp = w + (((size_t)co * k + ky) * k + kx) * cin;
+                        for (int ci = 0; ci < cin; ++ci) acc += (double)ip[ci] * (double)wp[ci];
+                    }
+                }
+                if (relu && acc < 0.0) acc = 0.0;
+                o[co] = store_val(acc, bf16);
+            }
+        }
+}
+
+/* max pooling over the in-bounds part of each window (never cached: Section 5) */
+void oc_maxpool(const float* in, int Hin, int Win, int C, int k, int s, int p, float* out)
+{
+    int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
+#pragma omp parallel for schedule(static)
+    for (int y = 0; y < Hout; ++y)
+        for (int x = 0; x < Wout; ++x)
+            for (int c = 0; c < C; ++c) {
+                float m = -INFINITY;
+                for (int ky = 0; ky < k; ++ky) {
+                    int iy = y * s - p + ky;
+                    if (iy < 0 || iy >= Hin) continue;
+                    for (int kx = 0; kx < k; ++kx) {
+                        int ix = x * s - p + kx;
+                        if (ix < 0 || ix >= Win) continue;
+                        float v = in[((size_t)iy * Win + ix) * C + c];
+                        if (v > m) m = v;
+                    }
+                }
+                out[((size_t)y * Wout + x) * C + c] = m;
+            }
+}
+
+void oc_add(const float* a, const float* b, size_t n, int relu, int bf16, float* out)
+{
+    for (size_t i = 0; i < n; ++i) {
+        double v = (double)a[i] + (double)b[i];
+        if (relu && v < 0.0) v = 0.0;
+        out[i] = store_val(v, bf16);
+    }
+}
+
+void oc_relu(const float* a, size_t n, float* out)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = a[i] > 0.0f ? a[i] : 0.0f;
+}
+
+/* ------------------------------------------------------------------ */
+/* whole frame through the stack (Section 3 workflow)                 */
+/* ------------------------------------------------------------------ */
+
+/*
+ * One frame of one stream.
+ *   frame        uint8 [H][W][C]
+ *   weights/bias per layer (NULL for layers without); weights already in the
+ *                storage type (the caller rounds them for bf16)
+ *   rects0,n0    reusable input rectangles (Step 5 output); n0 < 0: no cache
+ *                (first frame, expiry, reset) -> every pixel is computed
+ *   mx,my        global motion
+ *   cur[t]       tensor t of this frame (written), t = 0..n_layers
+ *   prev[t]      tensor t of the previous frame (read for conv outputs only)
+ *   rects,cap,n_rects,dxy,cum_stride,hw: as oc_propagate (outputs)
+ * Returns 0, -1 on rect overflow.
+ */
+int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
+                 const float* const* bias, const uint8_t* frame, int H, int W, int C,
+                 int bf16, const oc_rect* rects0, int n0, int mx, int my,
+                 float* const* cur, const float* const* prev,
+                 oc_rect* rects, int cap, int32_t* n_rects, int32_t* dxy,
+                 int32_t* cum_stride, int32_t* hw)
+{
+    int cached = n0 >= 0;
+    int rc = oc_propagate(L, n_layers, H, W, rects0, cached ? n0 : 0, cached ? mx : 0,
+                          cached ? my : 0, rects, cap, n_rects, dxy, cum_stride, hw);
+    if (rc) return rc;
+    oc_frame_to_tensor(frame, (size_t)H * W * C, cur[0]);
+    for (int li = 0; li < n_layers; ++li) {
+        const oc_layer* l = &L[li];
+        int t = li + 1, a = l->in0;
+        int ha = hw[2 * a], wa = hw[2 * a + 1], ho = hw[2 * t], wo = hw[2 * t + 1];
+        if (l->type == OC_CONV) {
+            uint8_t* mask = NULL;
+            if (cached && n_rects[t] > 0) {
+                mask = (uint8_t*)malloc((size_t)ho * wo);
+                oc_rasterize(rects + (size_t)t * cap, n_rects[t], ho, wo, mask);
+            }
+            oc_conv_cached(cur[a], ha, wa, l->cin, weights[li], bias ? bias[li] : NULL, l->cout,
+                           l->k, l->s, l->p, l->relu, mask ? prev[t] : NULL, mask,
+                           dxy[2 * t], dxy[2 * t + 1], bf16, cur[t]);
+            free(mask);
+        } else if (l->type == OC_MAXPOOL) {
+            oc_maxpool(cur[a], ha, wa, l->cin, l->k, l->s, l->p, cur[t]);
+        } else if (l->type == OC_ADD) {
+            oc_add(cur[a], cur[l->in1], (size_t)ho * wo * l->cout, l->relu, bf16, cur[t]);
+        } else {
+            oc_relu(cur[a], (size_t)ho * wo * l->cout, cur[t]);
+        }
+    }
+    return 0;
+}
+
+int oc_num_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

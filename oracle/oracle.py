@@ -1,0 +1,253 @@
+"""ctypes wrapper around the CPU oracle (deepcache_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py.  It imports nothing from the HIP package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "deepcache_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force=False):
+    """Compile the oracle with gcc (-O2 -fopenmp)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-std=c99", "-shared", "-fPIC",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+class Rect(C.Structure):
+    _fields_ = [("x", C.c_int32), ("y", C.c_int32), ("w", C.c_int32), ("h", C.c_int32)]
+
+
+class Layer(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("type", "k", "s", "p", "cin", "cout", "relu", "in0", "in1")]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.oc_round_bf16.restype = C.c_float
+        _lib.oc_round_bf16.argtypes = [C.c_float]
+        _lib.oc_round_bf16_array.argtypes = [C.c_void_p, C.c_size_t]
+        _lib.oc_conv_cached.restype = None
+        _lib.oc_maxpool.restype = None
+        _lib.oc_add.restype = None
+        _lib.oc_add.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]
+        _lib.oc_frame_to_tensor.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def num_threads():
+    return int(lib().oc_num_threads())
+
+
+def layers_to_c(layers):
+    arr = (Layer * len(layers))()
+    for i, L in enumerate(layers):
+        for f, _ in Layer._fields_:
+            setattr(arr[i], f, int(L[f]))
+    return arr
+
+
+def rects_to_np(rects):
+    """list of (x,y,w,h) -> int32 [n][4]"""
+    return np.ascontiguousarray(np.array(rects, dtype=np.int32).reshape(-1, 4))
+
+
+def match_blocks(cur, prev, block, radius, max_ssd):
+    """Section 4, Steps 1-4.  Returns dict(mv, best_ssd, gmv, n_pass, mask)."""
+    H, W, Ch = cur.shape
+    gh, gw = H // block, W // block
+    mv = np.zeros((gh, gw, 2), np.int16)
+    best = np.zeros((gh, gw), np.uint32)
+    gmv = np.zeros(2, np.int32)
+    npass = np.zeros(1, np.int32)
+    mask = np.zeros((gh, gw), np.uint8)
+    cur = np.ascontiguousarray(cur, np.uint8)
+    prev = np.ascontiguousarray(prev, np.uint8)
+    lib().oc_match_blocks(_p(cur), _p(prev), H, W, Ch, block, radius, C.c_uint32(max_ssd),
+                          _p(mv), _p(best), _p(gmv), _p(npass), _p(mask))
+    return dict(mv=mv, best_ssd=best, gmv=gmv, n_pass=int(npass[0]), mask=mask)
+
+
+def merge_blocks(mask, block, cap=4096):
+    """Section 4, Step 5.  Returns int32 [n][4] rectangles (x,y,w,h) in pixels."""
+    mask = np.ascontiguousarray(mask, np.uint8)
+    gh, gw = mask.shape
+    out = np.zeros((cap, 4), np.int32)
+    n = lib().oc_merge_blocks(_p(mask), gh, gw, block, _p(out), cap)
+    assert n <= cap
+    return out[:n].copy()
+
+
+def dt_window(rect, k, s, p):
+    """Table 2 conv/pool row.  Returns (x,y,w,h) or None."""
+    out = Rect()
+    ok = lib().oc_dt_window(Rect(*[int(v) for v in rect]), int(k), int(s), int(p), C.byref(out))
+    return (out.x, out.y, out.w, out.h) if ok else None
+
+
+def dt_overlap(a, b):
+    out = Rect()
+    ok = lib().oc_dt_overlap(Rect(*[int(v) for v in a]), Rect(*[int(v) for v in b]), C.byref(out))
+    return (out.x, out.y, out.w, out.h) if ok else None
+
+
+def propagate(layers, H, W, rects0, mx, my, cap=1024):
+    """Section 5 propagation.  Returns dict(rects=[per tensor int32 [n][4]], dxy, cum_stride, hw)."""
+    n = len(layers)
+    Lc = layers_to_c(layers)
+    r0 = rects_to_np(rects0)
+    rects = np.zeros((n + 1, cap, 4), np.int32)
+    n_rects = np.zeros(n + 1, np.int32)
+    dxy = np.zeros((n + 1, 2), np.int32)
+    cs = np.zeros(n + 1, np.int32)
+    hw = np.zeros((n + 1, 2), np.int32)
+    rc = lib().oc_propagate(Lc, n, int(H), int(W), _p(r0), len(r0), int(mx), int(my), _p(rects), cap,
+                            _p(n_rects), _p(dxy), _p(cs), _p(hw))
+    assert rc == 0, "rect capacity exceeded"
+    return dict(rects=[rects[t, :n_rects[t]].copy() for t in range(n + 1)], dxy=dxy,
+                cum_stride=cs, hw=hw)
+
+
+def rasterize(rects, H, W):
+    r = rects_to_np(rects)
+    H, W = int(H), int(W)
+    mask = np.zeros((H, W), np.uint8)
+    lib().oc_rasterize(_p(r), len(r), int(H), int(W), _p(mask))
+    return mask
+
+
+def round_bf16(a):
+    a = np.array(a, dtype=np.float32, copy=True, order="C")
+    lib().oc_round_bf16_array(_p(a), a.size)
+    return a
+
+
+def frame_to_tensor(frame):
+    frame = np.ascontiguousarray(frame, np.uint8)
+    out = np.zeros(frame.shape, np.float32)
+    lib().oc_frame_to_tensor(_p(frame), frame.size, _p(out))
+    return out
+
+
+def conv_cached(x, w, bias, k, s, p, relu, cache_prev=None, mask=None, dxy=(0, 0), bf16=False):
+    """Section 5 "Reuse".  x [H][W][cin] fp32, w [cout][k][k][cin]."""
+    x = np.ascontiguousarray(x, np.float32)
+    w = np.ascontiguousarray(w, np.float32)
+    Hin, Win, cin = x.shape
+    cout = w.shape[0]
+    assert w.shape == (cout, k, k, cin)
+    Ho, Wo = (Hin + 2 * p - k) // s + 1, (Win + 2 * p - k) // s + 1
+    out = np.zeros((Ho, Wo, cout), np.float32)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, np.float32)
+    if mask is not None:
+        mask = np.ascontiguousarray(mask, np.uint8)
+        cache_prev = np.ascontiguousarray(cache_prev, np.float32)
+        assert mask.shape == (Ho, Wo) and cache_prev.shape == out.shape
+    lib().oc_conv_cached(_p(x), Hin, Win, cin, _p(w), _p(bias), cout, k, s, p, int(relu),
+                         _p(cache_prev), _p(mask), int(dxy[0]), int(dxy[1]), int(bf16), _p(out))
+    return out
+
+
+def maxpool(x, k, s, p):
+    x = np.ascontiguousarray(x, np.float32)
+    H, W, Ch = x.shape
+    out = np.zeros(((H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1, Ch), np.float32)
+    lib().oc_maxpool(_p(x), H, W, Ch, k, s, p, _p(out))
+    return out
+
+
+def add(a, b, relu, bf16=False):
+    a = np.ascontiguousarray(a, np.float32)
+    b = np.ascontiguousarray(b, np.float32)
+    out = np.zeros_like(a)
+    lib().oc_add(_p(a), _p(b), a.size, int(relu), int(bf16), _p(out))
+    return out
+
+
+class Stream:
+    """One video stream through one stack: holds the previous frame (cache key) and
+    the previous feature maps (cache values), Section 3."""
+
+    def __init__(self, layers, weights, biases, H, W, Ch=3, block=16, radius=16, max_ssd=None,
+                 bf16=False, expiry=0, cap=1024):
+        self.layers, self.H, self.W, self.Ch = layers, H, W, Ch
+        self.block, self.radius, self.bf16, self.expiry, self.cap = block, radius, bf16, expiry, cap
+        self.max_ssd = max_ssd if max_ssd is not None else 20 * block * block * Ch
+        self.Lc = layers_to_c(layers)
+        n = len(layers)
+        self.w = [None if w is None else (round_bf16(w) if bf16 else np.ascontiguousarray(w, np.float32))
+                  for w in weights]
+        self.b = [None if b is None else np.ascontiguousarray(b, np.float32) for b in biases]
+        self._wp = (C.c_void_p * n)(*[None if w is None else w.ctypes.data for w in self.w])
+        self._bp = (C.c_void_p * n)(*[None if b is None else b.ctypes.data for b in self.b])
+        # tensor shapes
+        shapes = [(H, W, Ch)]
+        for L in layers:
+            h, w_, _ = shapes[L["in0"]]
+            if L["type"] in (0, 1):
+                shapes.append(((h + 2 * L["p"] - L["k"]) // L["s"] + 1,
+                               (w_ + 2 * L["p"] - L["k"]) // L["s"] + 1, L["cout"]))
+            else:
+                shapes.append((h, w_, L["cout"]))
+        self.shapes = shapes
+        self.bufs = [[np.zeros(s, np.float32) for s in shapes] for _ in range(2)]
+        self.prev_frame = None
+        self.age = 0  # frames since the last full computation
+
+    def reset(self):
+        self.prev_frame = None
+        self.age = 0
+
+    def step(self, frame):
+        """Process one frame.  Returns dict with tensors (list, current frame), match
+        results (or None on a full frame), per-tensor rects / dxy."""
+        frame = np.ascontiguousarray(frame, np.uint8)
+        n = len(self.layers)
+        full = self.prev_frame is None or (self.expiry > 0 and self.age >= self.expiry)
+        cur, prev = self.bufs[0], self.bufs[1]
+        m = None
+        if full:
+            r0 = np.zeros((0, 4), np.int32)
+            n0, mx, my = -1, 0, 0
+            self.age = 1
+        else:
+            m = match_blocks(frame, self.prev_frame, self.block, self.radius, self.max_ssd)
+            r0 = merge_blocks(m["mask"], self.block)
+            n0, mx, my = len(r0), int(m["gmv"][0]), int(m["gmv"][1])
+            self.age += 1
+        rects = np.zeros((n + 1, self.cap, 4), np.int32)
+        n_rects = np.zeros(n + 1, np.int32)
+        dxy = np.zeros((n + 1, 2), np.int32)
+        cs = np.zeros(n + 1, np.int32)
+        hw = np.zeros((n + 1, 2), np.int32)
+        curp = (C.c_void_p * (n + 1))(*[t.ctypes.data for t in cur])
+        prevp = (C.c_void_p * (n + 1))(*[t.ctypes.data for t in prev])
+        rc = lib().oc_run_stack(self.Lc, n, self._wp, self._bp, _p(frame), self.H, self.W, self.Ch,
+                                int(self.bf16), _p(r0), n0, mx, my, curp, prevp, _p(rects),
+                                self.cap, _p(n_rects), _p(dxy), _p(cs), _p(hw))
+        assert rc == 0
+        self.bufs = [prev, cur]  # cur becomes next frame's prev
+        self.prev_frame = frame.copy()
+        return dict(tensors=cur, match=m, rects0=r0, full=full,
+                    rects=[rects[t, :n_rects[t]].copy() for t in range(n + 1)],
+                    dxy=dxy, cum_stride=cs, hw=hw)

@@ -1,0 +1,303 @@
+"""Seeded synthetic inputs: video frames, layer tables and weights.
+
+This module feeds both the HIP path and the CPU oracle.  It holds none of the
+method's arithmetic (no matching, no region logic, no convolution): it only
+draws frames, describes network stacks as plain data and draws weights.
+
+The videos stand in for the paper's phone-camera clips (Section 7.1 uses UCF101
+and a driving set, neither of which can be shipped): a textured background
+that pans by a few pixels per frame (camera motion) with rigid foreground
+rectangles that move on their own (moving objects), which is the structure
+Section 4 designs the matcher for.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# layer types (plain data; each side maps them to its own C enum)
+CONV, MAXPOOL, RELU, ADD = 0, 1, 2, 3
+
+
+# --------------------------------------------------------------------------- #
+# layer tables                                                                #
+# --------------------------------------------------------------------------- #
+def _conv(cin, cout, k, s, p, relu, in0):
+    return dict(type=CONV, k=k, s=s, p=p, cin=cin, cout=cout, relu=int(relu), in0=in0, in1=-1)
+
+
+def _pool(c, k, s, p, in0):
+    return dict(type=MAXPOOL, k=k, s=s, p=p, cin=c, cout=c, relu=0, in0=in0, in1=-1)
+
+
+def _add(c, in0, in1, relu):
+    return dict(type=ADD, k=1, s=1, p=0, cin=c, cout=c, relu=int(relu), in0=in0, in1=in1)
+
+
+def _chain(spec, cin):
+    """spec: list of ('c', cout, k, s, p) or ('p', k, s, p).  Tensor 0 is the input."""
+    layers = []
+    c = cin
+    for item in spec:
+        t = len(layers)  # producer tensor id of the next layer's input
+        if item[0] == "c":
+            _, cout, k, s, p = item
+            layers.append(_conv(c, cout, k, s, p, True, t))
+            c = cout
+        else:
+            _, k, s, p = item
+            layers.append(_pool(c, k, s, p, t))
+    return layers
+
+
+def tiny_net():
+    """3 conv layers: 3->16 s1, 16->32 s2, 32->32 s1, all 3x3 p1 + ReLU."""
+    return _chain([("c", 16, 3, 1, 1), ("c", 32, 3, 2, 1), ("c", 32, 3, 1, 1)], 3)
+
+
+def vgg16():
+    """VGG-16-style trunk: 13 conv3x3 p1 ReLU and 4 maxpool 2x2 s2."""
+    spec = []
+    for block, (c, n) in enumerate([(64, 2), (128, 2), (256, 3), (512, 3), (512, 3)]):
+        spec += [("c", c, 3, 1, 1)] * n
+        if block < 4:
+            spec.append(("p", 2, 2, 0))
+    return _chain(spec, 3)
+
+
+def darknet19():
+    """Darknet-19-style stack: 3x3 convs with 1x1 bottlenecks, 5 maxpools, 1x1 head."""
+    spec = [("c", 32, 3, 1, 1), ("p", 2, 2, 0), ("c", 64, 3, 1, 1), ("p", 2, 2, 0)]
+    for c, n in [(128, 3), (256, 3)]:
+        for i in range(n):
+            spec.append(("c", c, 3, 1, 1) if i % 2 == 0 else ("c", c // 2, 1, 1, 0))
+        spec.append(("p", 2, 2, 0))
+    for i in range(5):
+        spec.append(("c", 512, 3, 1, 1) if i % 2 == 0 else ("c", 256, 1, 1, 0))
+    spec.append(("p", 2, 2, 0))
+    for i in range(5):
+        spec.append(("c", 1024, 3, 1, 1) if i % 2 == 0 else ("c", 512, 1, 1, 0))
+    spec.append(("c", 1024, 1, 1, 0))
+    return _chain(spec, 3)
+
+
+def resnet50_trunk():
+    """ResNet-50-style conv trunk (no BN): 7x7 s2 stem, maxpool 3x3 s2, stages [3,4,6,3]
+    of 1x1/3x3/1x1 bottlenecks, projection shortcut on each stage's first block,
+    add then ReLU."""
+    layers = [_conv(3, 64, 7, 2, 3, True, 0)]
+    layers.append(_pool(64, 3, 2, 1, 1))
+    x = 2  # tensor id of the running block input
+    cin = 64
+    for stage, (width, n) in enumerate([(64, 3), (128, 4), (256, 6), (512, 3)]):
+        for b in range(n):
+            s = 2 if (b == 0 and stage > 0) else 1
+            cout = 4 * width
+            layers.append(_conv(cin, width, 1, 1, 0, True, x))
+            a = len(layers)
+            layers.append(_conv(width, width, 3, s, 1, True, a))
+            bb = len(layers)
+            layers.append(_conv(width, cout, 1, 1, 0, False, bb))
+            main = len(layers)
+            if b == 0:
+                layers.append(_conv(cin, cout, 1, s, 0, False, x))
+                short = len(layers)
+            else:
+                short = x
+            layers.append(_add(cout, main, short, True))
+            x = len(layers)
+            cin = cout
+    return layers
+
+
+def tensor_shapes(layers, H, W, C):
+    """(H, W, C) of every tensor; tensor 0 is the input, tensor i+1 is layer i's output."""
+    shapes = [(H, W, C)]
+    for L in layers:
+        h, w, _ = shapes[L["in0"]]
+        if L["type"] in (CONV, MAXPOOL):
+            ho = (h + 2 * L["p"] - L["k"]) // L["s"] + 1
+            wo = (w + 2 * L["p"] - L["k"]) // L["s"] + 1
+            shapes.append((ho, wo, L["cout"]))
+        else:
+            shapes.append((h, w, L["cout"]))
+    return shapes
+
+
+def he_weights(layers, seed, bias_scale=0.0, residual_scale=1.0):
+    """He-normal weights N(0, 2/(cin*k*k)) in [cout][k][k][cin] order and biases.
+
+    `residual_scale` multiplies the conv that feeds in0 of every ADD layer (keeps
+    activations of deep residual stacks in a tame range without normalisation layers).
+    Returns two lists indexed by layer (None for layers without weights)."""
+    rng = np.random.default_rng(seed)
+    feeds_add = {L["in0"] - 1 for L in layers if L["type"] == ADD}
+    ws, bs = [], []
+    for i, L in enumerate(layers):
+        if L["type"] != CONV:
+            ws.append(None)
+            bs.append(None)
+            continue
+        k, cin, cout = L["k"], L["cin"], L["cout"]
+        w = rng.standard_normal((cout, k, k, cin)) * np.sqrt(2.0 / (cin * k * k))
+        if i in feeds_add:
+            w = w * residual_scale
+        b = rng.standard_normal(cout) * bias_scale
+        ws.append(np.ascontiguousarray(w, dtype=np.float32))
+        bs.append(np.ascontiguousarray(b, dtype=np.float32))
+    return ws, bs
+
+
+# --------------------------------------------------------------------------- #
+# frames                                                                      #
+# --------------------------------------------------------------------------- #
+def _box_blur5(img):
+    """5x5 box blur, edge-replicated, integer rounding (sum+12)//25, per channel."""
+    H, W, _ = img.shape
+    pad = np.pad(img.astype(np.int64), ((2, 2), (2, 2), (0, 0)), mode="edge")
+    acc = np.zeros(img.shape, dtype=np.int64)
+    for dy in range(5):
+        for dx in range(5):
+            acc += pad[dy:dy + H, dx:dx + W]
+    return ((acc + 12) // 25).astype(np.uint8)
+
+
+def tiny_pair(seed=0, H=64, W=64, shift=(3, -2), sigma=2.0, patch=(24, 24, 16)):
+    """Two frames: a blurred-noise image, and the same content moved by `shift`
+    (+x right, +y down) with sensor noise and one square patch of fresh noise.
+
+    Returns (frame1, frame2) as uint8 [H][W][3]."""
+    rng = np.random.default_rng(seed)
+    f1 = _box_blur5(rng.integers(0, 256, size=(H, W, 3), dtype=np.int64).astype(np.uint8))
+    sx, sy = shift
+    ys = np.clip(np.arange(H) - sy, 0, H - 1)
+    xs = np.clip(np.arange(W) - sx, 0, W - 1)
+    moved = f1[ys][:, xs].astype(np.float64)
+    noisy = np.rint(moved + rng.normal(0.0, sigma, size=moved.shape))
+    f2 = np.clip(noisy, 0, 255).astype(np.uint8)
+    px, py, ps = patch
+    if ps > 0:
+        f2[py:py + ps, px:px + ps] = rng.integers(0, 256, size=(ps, ps, 3), dtype=np.int64).astype(np.uint8)
+    return f1, f2
+
+
+def shifted_pair(seed, H, W, shift, C=3):
+    """Noise-free pair: frame2 is frame1's content moved by `shift` (edge-replicated)."""
+    rng = np.random.default_rng(seed)
+    f1 = _box_blur5(rng.integers(0, 256, size=(H, W, C), dtype=np.int64).astype(np.uint8))
+    sx, sy = shift
+    ys = np.clip(np.arange(H) - sy, 0, H - 1)
+    xs = np.clip(np.arange(W) - sx, 0, W - 1)
+    return f1, np.ascontiguousarray(f1[ys][:, xs])
+
+
+def _value_noise(rng, size, lattices=(64, 32, 16, 8, 4)):
+    """Multi-octave value noise, `size` x `size` x 3, amplitude halving per octave,
+    smoothstep interpolation, channels independent, quantised to uint8."""
+    out = np.zeros((size, size, 3), dtype=np.float64)
+    amp, total = 1.0, 0.0
+    coords = np.arange(size, dtype=np.float64)
+    for lat in lattices:
+        n = size // lat + 2
+        grid = rng.random((n, n, 3))
+        g = coords / lat
+        i0 = np.floor(g).astype(np.int64)
+        t = g - i0
+        t = t * t * (3.0 - 2.0 * t)
+        ty = t[:, None, None]
+        tx = t[None, :, None]
+        a = grid[i0][:, i0]
+        b = grid[i0][:, i0 + 1]
+        c = grid[i0 + 1][:, i0]
+        d = grid[i0 + 1][:, i0 + 1]
+        out += amp * ((a * (1 - tx) + b * tx) * (1 - ty) + (c * (1 - tx) + d * tx) * ty)
+        total += amp
+        amp *= 0.5
+    out /= total
+    return np.clip(np.rint(out * 255.0), 0, 255).astype(np.uint8)
+
+
+_DIRS = [(1, 0), (1, 1), (0, 1), (-1, 1), (-1, 0), (-1, -1), (0, -1), (1, -1)]
+
+
+def panning_video(seed, n_frames=30, H=224, W=224, fg=((48, 48), (32, 64)),
+                  pan_speeds=(1, 2, 3), fg_speeds=(4, 5, 6), redraw_every=10,
+                  margin=96):
+    """Value-noise background panning `pan_speeds` px/frame in a compass direction that
+    is redrawn every `redraw_every` frames, plus rigid uniform-noise rectangles
+    (h, w) moving `fg_speeds` px/frame and bouncing at the edges.  No sensor noise.
+
+    Returns uint8 [n_frames][H][W][3]."""
+    rng = np.random.default_rng(seed)
+    size = ((max(H, W) + 2 * margin + 63) // 64) * 64
+    canvas = _value_noise(rng, size)
+    ox, oy = (size - W) // 2, (size - H) // 2
+    objs = []
+    for (h, w) in fg:
+        tex = rng.integers(0, 256, size=(h, w, 3), dtype=np.int64).astype(np.uint8)
+        x = int(rng.integers(0, W - w + 1))
+        y = int(rng.integers(0, H - h + 1))
+        sp = int(rng.choice(fg_speeds))
+        dx, dy = _DIRS[int(rng.integers(0, 8))]
+        objs.append([tex, x, y, dx * sp, dy * sp])
+    frames = np.empty((n_frames, H, W, 3), dtype=np.uint8)
+    vx = vy = 0
+    for f in range(n_frames):
+        if f % redraw_every == 0:
+            sp = int(rng.choice(pan_speeds))
+            dx, dy = _DIRS[int(rng.integers(0, 8))]
+            vx, vy = dx * sp, dy * sp
+        if f > 0:
+            ox = int(np.clip(ox + vx, 0, size - W))
+            oy = int(np.clip(oy + vy, 0, size - H))
+        img = canvas[oy:oy + H, ox:ox + W].copy()
+        for o in objs:
+            tex, x, y, ux, uy = o
+            if f > 0:
+                x += ux
+                y += uy
+                if x < 0 or x + tex.shape[1] > W:
+                    ux = -ux
+                    x = int(np.clip(x, 0, W - tex.shape[1]))
+                if y < 0 or y + tex.shape[0] > H:
+                    uy = -uy
+                    y = int(np.clip(y, 0, H - tex.shape[0]))
+                o[1], o[2], o[3], o[4] = x, y, ux, uy
+            img[y:y + tex.shape[0], x:x + tex.shape[1]] = tex
+        frames[f] = img
+    return frames
+
+
+def reuse_sweep_video(seed, target_reuse, n_frames=60, H=416, W=416, block=16,
+                      pan=(2, 0), cut_at=30):
+    """Background panning `pan` px/frame with a band of fresh noise redrawn every
+    frame whose height (in whole block rows) sets the non-reusable fraction to
+    about 1 - target_reuse; a new background (scene cut) starts at frame `cut_at`.
+
+    Returns uint8 [n_frames][H][W][3]."""
+    rng = np.random.default_rng(seed)
+    margin = abs(pan[0]) * n_frames + abs(pan[1]) * n_frames + 8
+    size = ((max(H, W) + 2 * margin + 63) // 64) * 64
+    gh = H // block
+    dirty_rows = int(round((1.0 - target_reuse) * gh))
+    frames = np.empty((n_frames, H, W, 3), dtype=np.uint8)
+    canvas = None
+    ox = oy = 0
+    for f in range(n_frames):
+        if f == 0 or f == cut_at:
+            canvas = _value_noise(rng, size)
+            ox, oy = (size - W) // 2, (size - H) // 2
+        else:
+            ox += pan[0]
+            oy += pan[1]
+        img = canvas[oy:oy + H, ox:ox + W].copy()
+        if dirty_rows > 0:
+            y0 = (gh - dirty_rows) // 2 * block
+            img[y0:y0 + dirty_rows * block] = rng.integers(
+                0, 256, size=(dirty_rows * block, W, 3), dtype=np.int64).astype(np.uint8)
+        frames[f] = img
+    return frames
+
+
+def max_block_ssd(block, channels=3, tau=20):
+    """Total per-block SSD bound for a mean squared error of `tau` per sample."""
+    return int(tau * block * block * channels)

@@ -1,0 +1,188 @@
+"""Pins for the oracle's region logic: Section 4 Step 5 (merge) and Section 5 Table 2
+(region transformation), against the paper's worked examples and brute force."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from paper_1712_01670_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "region_examples.txt")
+
+
+def _golden():
+    rows = []
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, rin, ksp, rout, _ = [f.strip() for f in line.split("|")]
+        rows.append((name, tuple(map(int, rin.split())), tuple(map(int, ksp.split())),
+                     tuple(map(int, rout.split()))))
+    return rows
+
+
+@pytest.mark.parametrize("name,rin,ksp,rout", _golden())
+def test_paper_worked_examples(oracle, name, rin, ksp, rout):
+    assert oracle.dt_window(rin, *ksp) == rout
+
+
+def test_paper_example_source_rect_keeps_offset(oracle):
+    # Section 5: the previous-frame block (120,120,100,40) goes through the same rule;
+    # the offset 20 px becomes 10 px after the stride-2 layer and the sizes agree.
+    cur = oracle.dt_window((100, 100, 100, 40), 11, 2, 5)
+    src = oracle.dt_window((120, 120, 100, 40), 11, 2, 5)
+    assert src == (cur[0] + 10, cur[1] + 10, cur[2], cur[3])
+    # following pooling layer k3 s2 p1 shrinks it again
+    assert oracle.dt_window(cur, 3, 2, 1) == (27, 27, 22, 7)
+
+
+def test_erosion_pixel_counts(oracle):
+    # Section 4: two separate 5x5 blocks keep 18 px, the merged 5x10 keeps 24 px
+    a = oracle.dt_window((0, 0, 5, 5), 3, 1, 1)
+    b = oracle.dt_window((0, 0, 10, 5), 3, 1, 1)
+    assert 2 * a[2] * a[3] == 18
+    assert b[2] * b[3] == 24
+
+
+def _brute(rect, k, s, p, Win, Hin):
+    """All output pixels whose k x k window lies wholly inside rect (padding never does)."""
+    x, y, w, h = rect
+    Wo, Ho = (Win + 2 * p - k) // s + 1, (Hin + 2 * p - k) // s + 1
+    ok = np.zeros((Ho, Wo), bool)
+    for Y in range(Ho):
+        for X in range(Wo):
+            x0, y0 = X * s - p, Y * s - p
+            ok[Y, X] = (x0 >= x and x0 + k <= x + w and y0 >= y and y0 + k <= y + h)
+    return ok
+
+
+@pytest.mark.parametrize("k,s", [(1, 1), (1, 2), (2, 2), (3, 1), (3, 2), (7, 2), (11, 2), (3, 3), (5, 1)])
+def test_dt_window_is_exact_window_containment(oracle, k, s):
+    rng = np.random.default_rng(k * 10 + s)
+    Win, Hin = 37, 29
+    for p in range(0, 6):
+        if Win + 2 * p < k:
+            continue
+        for _ in range(40):
+            x = int(rng.integers(0, Win - 1)); y = int(rng.integers(0, Hin - 1))
+            w = int(rng.integers(1, Win - x + 1)); h = int(rng.integers(1, Hin - y + 1))
+            ok = _brute((x, y, w, h), k, s, p, Win, Hin)
+            r = oracle.dt_window((x, y, w, h), k, s, p)
+            got = np.zeros_like(ok)
+            if r is not None:
+                got[r[1]:r[1] + r[3], r[0]:r[0] + r[2]] = True
+                assert r[0] >= 0 and r[1] >= 0 and r[0] + r[2] <= ok.shape[1] and r[1] + r[3] <= ok.shape[0]
+            assert np.array_equal(ok, got), (x, y, w, h, k, s, p)
+
+
+def test_table2_other_rows(oracle):
+    # activation: unchanged; overlap of rectangles for multi-input layers
+    L = [dict(type=synth.RELU, k=1, s=1, p=0, cin=4, cout=4, relu=0, in0=0, in1=-1)]
+    out = oracle.propagate(L, 32, 32, [(4, 6, 10, 12)], 0, 0)
+    assert out["rects"][1].tolist() == [[4, 6, 10, 12]]
+    assert oracle.dt_overlap((0, 0, 10, 10), (5, 6, 10, 10)) == (5, 6, 5, 4)
+    assert oracle.dt_overlap((0, 0, 5, 5), (5, 0, 5, 5)) is None
+
+
+def _check_merge(oracle, mask, B):
+    rects = oracle.merge_blocks(mask, B)
+    cover = np.zeros((mask.shape[0] * B, mask.shape[1] * B), np.int32)
+    for x, y, w, h in rects:
+        assert x % B == 0 and y % B == 0 and w % B == 0 and h % B == 0 and w > 0 and h > 0
+        cover[y:y + h, x:x + w] += 1
+    want = np.kron(mask, np.ones((B, B), np.int32))
+    assert np.array_equal(cover, want)  # disjoint and union == mask
+    return rects
+
+
+def test_merge_invariants_random(oracle):
+    rng = np.random.default_rng(7)
+    for trial in range(200):
+        gh, gw = int(rng.integers(1, 12)), int(rng.integers(1, 12))
+        mask = (rng.random((gh, gw)) < rng.random()).astype(np.uint8)
+        _check_merge(oracle, mask, int(rng.integers(1, 5)))
+
+
+def test_merge_hand_cases(oracle):
+    # full grid -> one rectangle
+    assert oracle.merge_blocks(np.ones((3, 4), np.uint8), 8).tolist() == [[0, 0, 32, 24]]
+    assert oracle.merge_blocks(np.zeros((3, 4), np.uint8), 8).tolist() == []
+    # L shape: the first run claims the top row, then extends while the whole run is set
+    m = np.array([[1, 1, 1],
+                  [1, 1, 0],
+                  [1, 1, 0]], np.uint8)
+    assert oracle.merge_blocks(m, 2).tolist() == [[0, 0, 6, 2], [0, 2, 4, 4]]
+    # a hole splits rows
+    m = np.array([[1, 1, 1],
+                  [1, 0, 1],
+                  [1, 1, 1]], np.uint8)
+    assert oracle.merge_blocks(m, 1).tolist() == [[0, 0, 3, 1], [0, 1, 1, 2], [2, 1, 1, 2], [1, 2, 1, 1]]
+
+
+def test_adjacent_blocks_merge_beats_separate(oracle):
+    # Section 4: adjacent properly-matched blocks share the offset and merge into one
+    m = np.array([[1, 1]], np.uint8)
+    r = oracle.merge_blocks(m, 5)
+    assert r.tolist() == [[0, 0, 10, 5]]
+
+
+def test_propagate_vgg_against_rasterized_brute_force(oracle):
+    """Chain of convs and pools: the propagated rectangles of every tensor must equal,
+    pixel for pixel, the set found by testing each output window against the input
+    reusable set layer by layer (motion 0, so no clipping interferes)."""
+    L = synth.vgg16()[:7]
+    H = W = 64
+    rects0 = [(0, 0, 32, 48), (32, 16, 32, 16), (48, 48, 16, 16)]
+    out = oracle.propagate(L, H, W, rects0, 0, 0)
+    for li, layer in enumerate(L):
+        a, t = layer["in0"], li + 1
+        ha, wa = out["hw"][a]
+        ho, wo = out["hw"][t]
+        want = np.zeros((ho, wo), bool)
+        for r in out["rects"][a]:
+            want |= _brute(tuple(r), layer["k"], layer["s"], layer["p"], wa, ha)
+        got = oracle.rasterize(out["rects"][t], ho, wo).astype(bool)
+        assert np.array_equal(want, got), li
+    assert out["cum_stride"].tolist() == [1, 1, 1, 2, 2, 2, 4, 4]
+
+
+def test_propagate_offsets_and_clipping(oracle):
+    L = synth.tiny_net()
+    # motion (4,-2): a multiple of the total stride 2 in x and y
+    out = oracle.propagate(L, 64, 64, [(0, 8, 56, 48)], 4, -2)
+    assert out["dxy"].tolist() == [[4, -2], [4, -2], [2, -1], [2, -1]]
+    # every source rectangle stays inside its map
+    for t, rects in enumerate(out["rects"]):
+        h, w = out["hw"][t]
+        dx, dy = out["dxy"][t]
+        for x, y, ww, hh in rects:
+            assert 0 <= x + dx and x + dx + ww <= w and 0 <= y + dy and y + dy + hh <= h
+    # rounding of a misaligned motion: halves away from zero
+    out = oracle.propagate(L, 64, 64, [(8, 8, 40, 40)], 3, -1)
+    assert out["dxy"].tolist() == [[3, -1], [3, -1], [2, -1], [2, -1]]
+    out = oracle.propagate(L, 64, 64, [(8, 8, 40, 40)], -3, 1)
+    assert out["dxy"].tolist() == [[-3, 1], [-3, 1], [-2, 1], [-2, 1]]
+    out = oracle.propagate(L, 64, 64, [(8, 8, 40, 40)], 1, -5)
+    assert out["dxy"].tolist() == [[1, -5], [1, -5], [1, -3], [1, -3]]
+    # a rectangle whose source would leave the map is clipped at the input
+    out = oracle.propagate(L, 64, 64, [(56, 0, 8, 64)], 4, 0)
+    assert out["rects"][0].tolist() == [[56, 0, 4, 64]]
+
+
+def test_propagate_residual_intersection(oracle):
+    # branch a: conv3x3 p1 (erodes), branch b: identity shortcut; add -> overlap
+    L = [dict(type=synth.CONV, k=3, s=1, p=1, cin=4, cout=4, relu=1, in0=0, in1=-1),
+         dict(type=synth.ADD, k=1, s=1, p=0, cin=4, cout=4, relu=1, in0=1, in1=0)]
+    out = oracle.propagate(L, 32, 32, [(8, 8, 16, 16)], 0, 0)
+    assert out["rects"][1].tolist() == [[9, 9, 14, 14]]
+    assert out["rects"][2].tolist() == [[9, 9, 14, 14]]
+    # resnet trunk: both inputs of every add have the same cumulative stride
+    R = synth.resnet50_trunk()
+    out = oracle.propagate(R, 224, 224, [(0, 0, 224, 224)], 0, 0)
+    for i, l in enumerate(R):
+        if l["type"] == synth.ADD:
+            assert out["cum_stride"][l["in0"]] == out["cum_stride"][l["in1"]]
+            assert tuple(out["hw"][l["in0"]]) == tuple(out["hw"][l["in1"]])
+    assert out["cum_stride"][-1] == 32
