@@ -1,0 +1,213 @@
+/*
+ * deepcache.h -- C ABI of the MI355X (gfx950) library for cache-aware CNN
+ * inference over a video stream (DeepCache, arXiv 1712.01670).
+ *
+ * Per frame the library (1) matches blocks of the new frame against the previous
+ * frame (Section 4), (2) propagates the reusable rectangles through the layer stack
+ * (Section 5, Table 2) and (3) runs every convolution only on the non-reusable
+ * output pixels while the rest is copied from the previous frame's cached output
+ * at the matched offset (Section 5, "Reuse").
+ *
+ * General rules
+ *  - Every function returns a status: DC_OK (0) or a negative DC_ERR_*.  Nothing
+ *    throws or aborts across this boundary.  Argument errors are detected before
+ *    any kernel is launched.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are host memory.
+ *    The caller owns all memory.  The library keeps no state between calls and
+ *    allocates no device memory; scratch comes in as caller-provided workspaces.
+ *  - All GPU work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and is asynchronous unless stated otherwise.
+ *  - Frames are uint8 [n_streams][H][W][C] with interleaved channels, left-top
+ *    origin.  Feature maps are [n_streams][H][W][C] channels-last in the storage
+ *    type `dtype` (DC_F32 or DC_BF16; bf16 sums are accumulated in fp32 and rounded
+ *    to nearest-even once when stored).  Convolution weights are
+ *    [cout][k][k][cin] in the storage type, biases are fp32 [cout].
+ *  - A motion vector (dx,dy) points from a block of the current frame to its match
+ *    in the previous frame: source = current + (dx,dy)  (Section 4, Steps 2-4).
+ */
+#ifndef DEEPCACHE_H
+#define DEEPCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    DC_OK = 0,
+    DC_ERR_INVALID_ARG = -1,   /* a scalar argument is out of range */
+    DC_ERR_NULL_PTR = -2,      /* a required pointer is NULL */
+    DC_ERR_BAD_SHAPE = -3,     /* shapes are inconsistent with each other or the layer table */
+    DC_ERR_UNSUPPORTED = -4,   /* valid request the kernels do not implement */
+    DC_ERR_WORKSPACE = -5,     /* a workspace is too small */
+    DC_ERR_CAPACITY = -6,      /* a caller-provided list is too short (counts are still reported) */
+    DC_ERR_HIP = -7            /* a HIP runtime call failed */
+};
+
+enum { DC_F32 = 0, DC_BF16 = 1 };
+enum { DC_CONV = 0, DC_MAXPOOL = 1, DC_RELU = 2, DC_ADD = 3 };
+
+/* Rectangle in the pixel grid of one tensor, left-top origin (Section 3). */
+typedef struct { int32_t x, y, w, h; } dc_rect;
+
+/* One layer of the stack.  Tensor 0 is the network input (the frame mapped to
+ * (u8-128)/128); tensor i+1 is the output of layer i.  in0 (and in1 for DC_ADD)
+ * name producer tensors, so the table describes a DAG in topological order. */
+typedef struct {
+    int32_t type;          /* DC_CONV, DC_MAXPOOL, DC_RELU, DC_ADD */
+    int32_t k, s, p;       /* kernel size, stride, zero padding (conv, pool) */
+    int32_t cin, cout;
+    int32_t relu;          /* fused ReLU after a conv or an add */
+    int32_t in0, in1;
+} dc_layer;
+
+/* Reusable regions of one tensor of one stream (Section 5 "Propagation"):
+ * pixels inside `rects` equal the previous frame's tensor at +(dx,dy). */
+typedef struct {
+    dc_rect* rects;        /* host, caller-provided storage */
+    int32_t capacity;      /* length of `rects` */
+    int32_t n;             /* out: number of rectangles (may exceed capacity on DC_ERR_CAPACITY) */
+    int32_t dx, dy;        /* out: source offset in this tensor's pixels */
+    int32_t cum_stride;    /* out: product of strides from the input to this tensor */
+    int32_t h, w;          /* out: spatial size of this tensor */
+} dc_regions;
+
+/* Work counters of one dc_run_stack call, summed over streams. */
+typedef struct {
+    int32_t full;               /* 1: every pixel was computed (no cache used) */
+    int32_t n_blocks;           /* blocks in the grid, all streams */
+    int32_t n_reusable_blocks;  /* blocks that passed Step 4 */
+    int64_t macs_full;          /* conv multiply-adds of a full frame */
+    int64_t macs_needed;        /* multiply-adds of the non-reusable output pixels */
+    int64_t macs_issued;        /* multiply-adds of every pixel of every dirty tile (what ran) */
+    int64_t copy_bytes;         /* bytes read plus bytes written by the shifted copies */
+    int64_t* layer_reused_px;   /* optional host [n_layers]: reused output pixels per conv layer */
+    int64_t* layer_issued_macs; /* optional host [n_layers] */
+} dc_stack_stats;
+
+const char* dc_status_string(int32_t status);
+
+/*
+ * Section 4, Steps 1-4 (block grid, exhaustive search of Section 7.6, mean motion,
+ * re-test) for n_streams independent frame pairs.
+ *   cur, prev      dev u8 [n_streams][H][W][C]
+ *   block          block edge B in pixels; the grid is gh x gw = H/B x W/B (integer
+ *                  division; a remainder strip is never reusable)
+ *   radius         R: candidates |dx|,|dy| <= R whose window lies inside the previous frame
+ *   max_block_ssd  a block matches iff its sum of squared differences over all
+ *                  B*B*C samples is <= this bound (PSNR above a threshold, Section 4)
+ *   mv             dev i16 [n_streams][gh][gw][2]  best (dx,dy); ties go to the smallest
+ *                  (ssd, |dx|+|dy|, dy, dx)
+ *   best_ssd       dev u32 [n_streams][gh][gw]
+ *   global_mv      dev i32 [n_streams][2]  mean of the passing blocks' vectors per axis,
+ *                  rounded to nearest, halves away from zero; (0,0) if none passes
+ *   n_pass         dev i32 [n_streams]     number of passing blocks (K of Step 3)
+ *   block_mask     dev u8  [n_streams][gh][gw]  1 iff the block at +global_mv is inside
+ *                  the previous frame and within the bound (Step 4); all 0 if K = 0
+ * Limits: B*C <= 256, R <= 127, (B+2R)*((B+2R)*C+16) <= 60 KiB.
+ */
+int32_t dc_match_blocks(const uint8_t* cur, const uint8_t* prev, int32_t n_streams,
+                        int32_t H, int32_t W, int32_t C, int32_t block, int32_t radius,
+                        uint32_t max_block_ssd, int16_t* mv, uint32_t* best_ssd,
+                        int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask,
+                        void* stream);
+
+/*
+ * Section 4 Step 5 and Section 5 "Propagation" for one stream; pure host integer code.
+ *   block_mask     host u8 [gh][gw] (Step 4 result)
+ *   mx, my         global motion of the stream
+ *   regions        host [n_layers+1], one entry per tensor; `rects`/`capacity` are
+ *                  inputs, the rest is written
+ * Merge: row-major scan; at the first set unclaimed block grow right over set unclaimed
+ * blocks, then down while the whole run is set and unclaimed.  Conv and pool map a
+ * rectangle to the largest output rectangle whose k x k windows lie inside it
+ * (Table 2; x' = ceil((x+p)/s), last column floor((x+w-k+p)/s)); DC_ADD takes pairwise
+ * overlaps (Table 2, concat row); DC_RELU leaves rectangles unchanged.  Every tensor has
+ * one source offset round(M / cum_stride) (halves away from zero) and rectangles are
+ * clipped so that their source stays inside the map.
+ * Returns DC_ERR_CAPACITY if a list overflowed (n is exact, stored rects are truncated).
+ */
+int32_t dc_propagate_regions(const dc_layer* layers, int32_t n_layers, int32_t H, int32_t W,
+                             int32_t block, const uint8_t* block_mask, int32_t gh, int32_t gw,
+                             int32_t mx, int32_t my, dc_regions* regions);
+
+/* Bytes of device / host workspace dc_cached_conv_layer needs for the given shape. */
+int32_t dc_conv_workspace_bytes(const dc_layer* layer, int32_t n_streams, int32_t Hin,
+                                int32_t Win, int32_t max_rects_per_stream,
+                                size_t* dev_bytes, size_t* host_bytes);
+
+/*
+ * Section 5 "Reuse": cache-aware forward of one convolution layer (the paper's
+ * c_forward(top, bottom, c_blob, c_regions)).
+ *   in          dev [n_streams][Hin][Win][cin]       current input map (complete)
+ *   weights     dev [cout][k][k][cin], bias dev fp32 [cout] or NULL
+ *   cache_prev  dev [n_streams][Hout][Wout][cout]    this layer's output for the previous frame
+ *   out         dev [n_streams][Hout][Wout][cout]    written completely; must not alias cache_prev
+ *   regions     host [n_streams]: reusable rectangles of the OUTPUT tensor and their source
+ *               offset; NULL (or cache_prev NULL) computes every pixel
+ * Pixels inside a rectangle receive cache_prev at +(dx,dy); every other pixel receives
+ * conv(+bias)(+ReLU).  The GEMM runs over a compacted list of tiles that contain at
+ * least one non-reusable pixel; reusable pixels inside such tiles still get the copy.
+ *   ws_dev      dev workspace, ws_host host staging (pinned memory recommended); the
+ *               staging must stay untouched until the stream has passed this call
+ */
+int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* weights,
+                             const float* bias, const void* cache_prev, void* out,
+                             int32_t n_streams, int32_t Hin, int32_t Win,
+                             const dc_regions* regions, int32_t dtype,
+                             void* ws_dev, size_t ws_dev_bytes,
+                             void* ws_host, size_t ws_host_bytes, void* stream);
+
+/* Un-cached layers (Section 5: only convolutions use the cache), whole map every frame. */
+int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n_samples, int32_t dtype,
+                           void* stream);
+int32_t dc_maxpool_layer(const void* in, void* out, int32_t n_streams, int32_t Hin, int32_t Win,
+                         int32_t C, int32_t k, int32_t s, int32_t p, int32_t dtype, void* stream);
+int32_t dc_add_layer(const void* a, const void* b, void* out, size_t n, int32_t relu,
+                     int32_t dtype, void* stream);
+
+/* Workspace sizes for dc_run_stack. */
+int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32_t n_streams,
+                                 int32_t H, int32_t W, int32_t C, int32_t block,
+                                 int32_t max_rects_per_stream,
+                                 size_t* dev_bytes, size_t* host_bytes);
+
+/*
+ * One frame of every stream through the whole path (Section 3 workflow): match,
+ * merge, propagate, then per layer shifted copy + convolution of dirty tiles, with
+ * pooling / add / ReLU layers computed in full.
+ *   weights, bias   host arrays [n_layers] of dev pointers (NULL for non-conv layers)
+ *   frames_cur      dev u8 [n_streams][H][W][C]
+ *   frames_prev     dev u8, previous frames (cache keys); ignored when force_full
+ *   tensors_cur     host array [n_layers+1] of dev pointers, every tensor of this frame
+ *                   (written).  Conv outputs are the cache values of the next frame.
+ *   tensors_prev    host array [n_layers+1] of dev pointers: the previous frame's tensors;
+ *                   only conv-layer outputs are read.  Must not alias tensors_cur for them.
+ *   force_full      nonzero: first frame, cache expiry (Section 5) or reset: skip matching
+ *                   and compute everything
+ *   mv .. block_mask  dev buffers as in dc_match_blocks (written unless force_full)
+ *   max_rects       capacity of each per-tensor rectangle list
+ *   regions_out     optional host [n_streams][n_layers+1] with caller-provided rect storage,
+ *                   receives every tensor's regions (for inspection); may be NULL
+ *   ws_dev, ws_host workspaces of at least dc_stack_workspace_bytes; ws_host should be pinned
+ *   stats           optional host
+ * The call synchronises the stream once after matching (the region logic runs on the
+ * host); everything after that is asynchronous.
+ */
+int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers,
+                     const void* const* weights, const float* const* bias,
+                     const uint8_t* frames_cur, const uint8_t* frames_prev,
+                     void* const* tensors_cur, const void* const* tensors_prev,
+                     int32_t n_streams, int32_t H, int32_t W, int32_t C, int32_t dtype,
+                     int32_t block, int32_t radius, uint32_t max_block_ssd, int32_t force_full,
+                     int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
+                     uint8_t* block_mask, int32_t max_rects, dc_regions* regions_out,
+                     void* ws_dev, size_t ws_dev_bytes, void* ws_host, size_t ws_host_bytes,
+                     dc_stack_stats* stats, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEEPCACHE_H */

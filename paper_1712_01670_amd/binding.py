@@ -1,0 +1,325 @@
+"""Thin ctypes binding of libdeepcache.so: argument marshalling only.
+
+Every step of the path runs inside the library's kernels; torch is used for device
+memory and the HIP stream.  There is no CPU fallback: importing the library fails
+loudly if it has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+from . import synth
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdeepcache.so")
+
+DC_F32, DC_BF16 = 0, 1
+STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_ERR_BAD_SHAPE",
+          -4: "DC_ERR_UNSUPPORTED", -5: "DC_ERR_WORKSPACE", -6: "DC_ERR_CAPACITY", -7: "DC_ERR_HIP"}
+
+EXPORTS = ["dc_status_string", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
+           "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
+           "dc_stack_workspace_bytes", "dc_run_stack"]
+
+
+class DcError(RuntimeError):
+    def __init__(self, fn, status):
+        super().__init__(f"{fn} returned {STATUS.get(status, status)}")
+        self.status = status
+
+
+class Rect(C.Structure):
+    _fields_ = [("x", C.c_int32), ("y", C.c_int32), ("w", C.c_int32), ("h", C.c_int32)]
+
+
+class Layer(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("type", "k", "s", "p", "cin", "cout", "relu", "in0", "in1")]
+
+
+class Regions(C.Structure):
+    _fields_ = [("rects", C.POINTER(Rect)), ("capacity", C.c_int32), ("n", C.c_int32),
+                ("dx", C.c_int32), ("dy", C.c_int32), ("cum_stride", C.c_int32),
+                ("h", C.c_int32), ("w", C.c_int32)]
+
+
+class StackStats(C.Structure):
+    _fields_ = [("full", C.c_int32), ("n_blocks", C.c_int32), ("n_reusable_blocks", C.c_int32),
+                ("macs_full", C.c_int64), ("macs_needed", C.c_int64), ("macs_issued", C.c_int64),
+                ("copy_bytes", C.c_int64), ("layer_reused_px", C.POINTER(C.c_int64)),
+                ("layer_issued_macs", C.POINTER(C.c_int64))]
+
+
+_lib = None
+
+
+def lib():
+    """Load libdeepcache.so (raises if it is missing: there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_1712_01670_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.dc_status_string.restype = C.c_char_p
+        vp, i32, u32, sz = C.c_void_p, C.c_int32, C.c_uint32, C.c_size_t
+        L.dc_match_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
+        L.dc_propagate_regions.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, vp]
+        L.dc_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
+        L.dc_cached_conv_layer.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp, sz, vp, sz, vp]
+        L.dc_frame_to_tensor.argtypes = [vp, vp, sz, i32, vp]
+        L.dc_maxpool_layer.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+        L.dc_add_layer.argtypes = [vp, vp, vp, sz, i32, i32, vp]
+        L.dc_stack_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
+        L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, i32,
+                                   vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp]
+        for name in EXPORTS:
+            if name != "dc_status_string":
+                getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(fn, status):
+    if status != 0:
+        raise DcError(fn, status)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def layers_to_c(layers):
+    arr = (Layer * len(layers))()
+    for i, L in enumerate(layers):
+        for f, _ in Layer._fields_:
+            setattr(arr[i], f, int(L[f]))
+    return arr
+
+
+def torch_dtype(dtype):
+    return torch.bfloat16 if dtype == DC_BF16 else torch.float32
+
+
+# --------------------------------------------------------------------------- #
+# entry points (same names as the C ABI)                                      #
+# --------------------------------------------------------------------------- #
+def dc_match_blocks(cur, prev, block, radius, max_block_ssd):
+    """cur, prev: uint8 cuda tensors [n][H][W][C].  Returns dict of cuda tensors."""
+    assert cur.is_cuda and cur.dtype == torch.uint8 and cur.is_contiguous() and cur.dim() == 4
+    assert prev.shape == cur.shape and prev.is_cuda and prev.dtype == torch.uint8 and prev.is_contiguous()
+    n, H, W, Ch = cur.shape
+    gh, gw = H // block, W // block
+    dev = cur.device
+    out = dict(mv=torch.empty((n, gh, gw, 2), dtype=torch.int16, device=dev),
+               best_ssd=torch.empty((n, gh, gw), dtype=torch.int32, device=dev),
+               gmv=torch.empty((n, 2), dtype=torch.int32, device=dev),
+               n_pass=torch.empty((n,), dtype=torch.int32, device=dev),
+               mask=torch.empty((n, gh, gw), dtype=torch.uint8, device=dev))
+    _check("dc_match_blocks", lib().dc_match_blocks(
+        _ptr(cur), _ptr(prev), n, H, W, Ch, block, radius, max_block_ssd, _ptr(out["mv"]),
+        _ptr(out["best_ssd"]), _ptr(out["gmv"]), _ptr(out["n_pass"]), _ptr(out["mask"]), _stream()))
+    return out
+
+
+def _alloc_regions(n, cap):
+    regs = (Regions * n)()
+    store = [(Rect * cap)() for _ in range(n)]
+    for i in range(n):
+        regs[i].rects = C.cast(store[i], C.POINTER(Rect))
+        regs[i].capacity = cap
+    return regs, store
+
+
+def _regions_to_py(r):
+    n = min(r.n, r.capacity)
+    rects = np.array([[r.rects[i].x, r.rects[i].y, r.rects[i].w, r.rects[i].h] for i in range(n)],
+                     dtype=np.int32).reshape(-1, 4)
+    return dict(rects=rects, n=r.n, dxy=(r.dx, r.dy), cum_stride=r.cum_stride, hw=(r.h, r.w))
+
+
+def dc_propagate_regions(layers, H, W, block, block_mask, mx, my, cap=1024):
+    """Host call.  block_mask: numpy uint8 [gh][gw].  Returns a list (per tensor) of dicts."""
+    mask = np.ascontiguousarray(block_mask, np.uint8)
+    gh, gw = mask.shape
+    Lc = layers_to_c(layers)
+    regs, store = _alloc_regions(len(layers) + 1, cap)
+    _check("dc_propagate_regions", lib().dc_propagate_regions(
+        Lc, len(layers), H, W, block, mask.ctypes.data_as(C.c_void_p), gh, gw, int(mx), int(my), regs))
+    return [_regions_to_py(regs[t]) for t in range(len(layers) + 1)]
+
+
+class _Workspace:
+    """Device + pinned host scratch, grown on demand and kept per device."""
+
+    def __init__(self):
+        self.dev = None
+        self.host = None
+        self.busy = None   # event recorded after the last call that read the host staging
+
+    def get(self, dev_bytes, host_bytes, device):
+        if self.busy is not None:
+            self.busy.synchronize()   # the previous upload must have left the staging buffer
+            self.busy = None
+        if self.dev is None or self.dev.numel() < dev_bytes or self.dev.device != device:
+            self.dev = torch.empty(max(int(dev_bytes), 256), dtype=torch.uint8, device=device)
+        if self.host is None or self.host.numel() < host_bytes:
+            self.host = torch.empty(max(int(host_bytes), 256), dtype=torch.uint8, pin_memory=True)
+        return self.dev, self.host
+
+
+_conv_ws = _Workspace()
+
+
+def dc_cached_conv_layer(layer, x, weights, bias, cache_prev=None, regions=None, out=None):
+    """x [n][Hin][Win][cin] cuda (fp32 or bf16); weights [cout][k][k][cin] same dtype; bias fp32 or None.
+    regions: list (per stream) of (rects int32 [m][4], (dx, dy)) for the output tensor, or None."""
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 4
+    dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
+    assert weights.dtype == x.dtype and weights.is_contiguous()
+    n, Hin, Win, cin = x.shape
+    k, s, p = layer["k"], layer["s"], layer["p"]
+    Ho, Wo = (Hin + 2 * p - k) // s + 1, (Win + 2 * p - k) // s + 1
+    if out is None:
+        out = torch.empty((n, Ho, Wo, layer["cout"]), dtype=x.dtype, device=x.device)
+    Lc = layers_to_c([layer])
+    regs = None
+    keep = None
+    max_rects = 1
+    if regions is not None:
+        assert len(regions) == n
+        max_rects = max(1, max(len(r[0]) for r in regions))
+        regs, keep = _alloc_regions(n, max_rects)
+        for i, (rects, dxy) in enumerate(regions):
+            regs[i].n = len(rects)
+            regs[i].dx, regs[i].dy = int(dxy[0]), int(dxy[1])
+            for j, r in enumerate(rects):
+                keep[i][j] = Rect(*[int(v) for v in r])
+    db, hb = C.c_size_t(), C.c_size_t()
+    _check("dc_conv_workspace_bytes", lib().dc_conv_workspace_bytes(Lc, n, Hin, Win, max_rects, C.byref(db), C.byref(hb)))
+    wd, wh = _conv_ws.get(db.value, hb.value, x.device)
+    _check("dc_cached_conv_layer", lib().dc_cached_conv_layer(
+        Lc, _ptr(x), _ptr(weights), _ptr(bias), _ptr(cache_prev), _ptr(out), n, Hin, Win, regs, dtype,
+        _ptr(wd), wd.numel(), C.c_void_p(wh.data_ptr()), wh.numel(), _stream()))
+    _conv_ws.busy = torch.cuda.Event()
+    _conv_ws.busy.record()
+    return out
+
+
+def dc_frame_to_tensor(frames, dtype=DC_F32):
+    out = torch.empty(frames.shape, dtype=torch_dtype(dtype), device=frames.device)
+    _check("dc_frame_to_tensor", lib().dc_frame_to_tensor(_ptr(frames), _ptr(out), frames.numel(), dtype, _stream()))
+    return out
+
+
+def dc_maxpool_layer(x, k, s, p):
+    n, H, W, Ch = x.shape
+    dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
+    out = torch.empty((n, (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1, Ch), dtype=x.dtype, device=x.device)
+    _check("dc_maxpool_layer", lib().dc_maxpool_layer(_ptr(x), _ptr(out), n, H, W, Ch, k, s, p, dtype, _stream()))
+    return out
+
+
+def dc_add_layer(a, b, relu):
+    dtype = DC_BF16 if a.dtype == torch.bfloat16 else DC_F32
+    out = torch.empty_like(a)
+    _check("dc_add_layer", lib().dc_add_layer(_ptr(a), _ptr(b), _ptr(out), a.numel(), int(relu), dtype, _stream()))
+    return out
+
+
+class StackRunner:
+    """Owns the device buffers of n_streams video streams through one layer stack and
+    calls dc_run_stack once per time step.  The cache policy (first frame, expiry every
+    `expiry` frames, explicit reset) is decided here and passed down as force_full."""
+
+    def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
+                 max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
+                 want_regions=False):
+        self.layers, self.n, self.H, self.W, self.Ch = layers, n_streams, H, W, Ch
+        self.block, self.radius, self.dtype, self.expiry = block, radius, dtype, expiry
+        self.max_block_ssd = int(max_block_ssd if max_block_ssd is not None else synth.max_block_ssd(block, Ch))
+        self.max_rects = max_rects
+        self.device = torch.device(device)
+        td = torch_dtype(dtype)
+        self.Lc = layers_to_c(layers)
+        nl = len(layers)
+        self.w = [None if w is None else torch.from_numpy(w).to(self.device).to(td).contiguous() for w in weights]
+        self.b = [None if b is None else torch.from_numpy(b).to(self.device).float().contiguous() for b in biases]
+        self._wp = (C.c_void_p * nl)(*[None if w is None else w.data_ptr() for w in self.w])
+        self._bp = (C.c_void_p * nl)(*[None if b is None else b.data_ptr() for b in self.b])
+        self.shapes = synth.tensor_shapes(layers, H, W, Ch)
+        # conv outputs are cache values: two copies (previous / current frame); the rest is shared
+        is_conv = [False] + [L["type"] == synth.CONV for L in layers]
+        self.bufs = [[], []]
+        for t, (h, w, c) in enumerate(self.shapes):
+            a = torch.empty((n_streams, h, w, c), dtype=td, device=self.device)
+            b = torch.empty_like(a) if is_conv[t] else a
+            self.bufs[0].append(a)
+            self.bufs[1].append(b)
+        self._tp = [(C.c_void_p * (nl + 1))(*[t.data_ptr() for t in self.bufs[i]]) for i in range(2)]
+        gh, gw = H // block, W // block
+        dev = self.device
+        self.mv = torch.zeros((n_streams, gh, gw, 2), dtype=torch.int16, device=dev)
+        self.best_ssd = torch.zeros((n_streams, gh, gw), dtype=torch.int32, device=dev)
+        self.gmv = torch.zeros((n_streams, 2), dtype=torch.int32, device=dev)
+        self.n_pass = torch.zeros((n_streams,), dtype=torch.int32, device=dev)
+        self.mask = torch.zeros((n_streams, gh, gw), dtype=torch.uint8, device=dev)
+        db, hb = C.c_size_t(), C.c_size_t()
+        _check("dc_stack_workspace_bytes", lib().dc_stack_workspace_bytes(
+            self.Lc, nl, n_streams, H, W, Ch, block, max_rects, C.byref(db), C.byref(hb)))
+        self.ws_dev = torch.empty(max(db.value, 256), dtype=torch.uint8, device=dev)
+        self.ws_host = torch.empty(max(hb.value, 256), dtype=torch.uint8, pin_memory=True)
+        self.prev_frames = None   # the caller's tensor of the previous step (cache key), kept by reference
+        self.cur = 0          # index of the buffer set that receives the next frame
+        self.have_prev = False
+        self.age = 0
+        self.stats = StackStats()
+        self._reused = (C.c_int64 * nl)()
+        self._issued = (C.c_int64 * nl)()
+        self.stats.layer_reused_px = C.cast(self._reused, C.POINTER(C.c_int64))
+        self.stats.layer_issued_macs = C.cast(self._issued, C.POINTER(C.c_int64))
+        self.regs = None
+        if want_regions:
+            self.regs, self._regs_store = _alloc_regions(n_streams * (nl + 1), max_rects)
+
+    def reset(self):
+        """Drop the cache (scene cut): the next frame is computed in full."""
+        self.have_prev = False
+        self.prev_frames = None
+        self.age = 0
+
+    def step(self, frames, force_full=False):
+        """frames: uint8 cuda tensor [n][H][W][C], resident and contiguous; it is kept by reference as
+        the next step's previous frame, so the caller must not overwrite it before that step has run.
+        Returns the list of this frame's tensors."""
+        assert frames.is_cuda and frames.dtype == torch.uint8 and frames.is_contiguous()
+        assert tuple(frames.shape) == (self.n, self.H, self.W, self.Ch)
+        c, p = self.cur, 1 - self.cur
+        full = force_full or not self.have_prev or (self.expiry > 0 and self.age >= self.expiry)
+        _check("dc_run_stack", lib().dc_run_stack(
+            self.Lc, len(self.layers), self._wp, self._bp, _ptr(frames), _ptr(self.prev_frames),
+            self._tp[c], self._tp[p], self.n, self.H, self.W, self.Ch, self.dtype, self.block, self.radius,
+            self.max_block_ssd, int(full), _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
+            _ptr(self.mask), self.max_rects, self.regs, _ptr(self.ws_dev), self.ws_dev.numel(),
+            C.c_void_p(self.ws_host.data_ptr()), self.ws_host.numel(), C.byref(self.stats), _stream()))
+        self.age = 1 if full else self.age + 1
+        self.have_prev = True
+        self.prev_frames = frames
+        self.cur = p
+        self.last_full = full
+        return self.bufs[c]
+
+    def regions(self, stream=0):
+        """Regions of every tensor of `stream` for the last step (needs want_regions=True)."""
+        nl = len(self.layers)
+        return [_regions_to_py(self.regs[stream * (nl + 1) + t]) for t in range(nl + 1)]
+
+    def layer_stats(self):
+        nl = len(self.layers)
+        return dict(reused_px=[self._reused[i] for i in range(nl)], issued_macs=[self._issued[i] for i in range(nl)])

@@ -1,0 +1,434 @@
+// C ABI entry points: argument validation, host-side planning, kernel sequencing.
+#include <cstring>
+#include <new>
+
+#include "dc_internal.h"
+
+using namespace dc;
+
+namespace {
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+#define DC_TRY_HIP(expr)                      \
+    do {                                      \
+        hipError_t e__ = (expr);              \
+        if (e__ != hipSuccess) return DC_ERR_HIP; \
+    } while (0)
+
+bool rects_disjoint_inside(const dc_rect* r, int n, int W, int H, int dx, int dy) {
+    for (int i = 0; i < n; ++i) {
+        if (r[i].w <= 0 || r[i].h <= 0 || r[i].x < 0 || r[i].y < 0 || r[i].x + r[i].w > W ||
+            r[i].y + r[i].h > H)
+            return false;
+        if (r[i].x + dx < 0 || r[i].y + dy < 0 || r[i].x + dx + r[i].w > W || r[i].y + dy + r[i].h > H)
+            return false;
+        for (int j = 0; j < i; ++j) {
+            bool apart = r[i].x + r[i].w <= r[j].x || r[j].x + r[j].w <= r[i].x ||
+                         r[i].y + r[i].h <= r[j].y || r[j].y + r[j].h <= r[i].y;
+            if (!apart) return false;
+        }
+    }
+    return true;
+}
+
+// Bytes of plan data for one conv layer, worst case.
+size_t plan_bytes(int n_streams, int Hout, int Wout, const ConvTiling& t, int max_rects) {
+    size_t tiles = (size_t)n_streams * ((Hout + t.th - 1) / t.th) * ((Wout + t.tw - 1) / t.tw);
+    return align_up(tiles * sizeof(TileDev), 256) + align_up((size_t)n_streams * max_rects * sizeof(RectDev), 256) +
+           align_up((size_t)n_streams * sizeof(RangeDev), 256);
+}
+
+// Serialise a plan into host staging at `host` and return the three device addresses
+// it will have once copied to `dev` (same offsets).
+struct PlanAddr {
+    const TileDev* tiles;
+    const RectDev* rects;
+    const RangeDev* ranges;
+    size_t bytes;
+};
+PlanAddr pack_plan(const LayerPlan& plan, unsigned char* host, unsigned char* dev) {
+    size_t off = 0;
+    PlanAddr a;
+    a.tiles = reinterpret_cast<const TileDev*>(dev + off);
+    if (!plan.tiles.empty()) std::memcpy(host + off, plan.tiles.data(), plan.tiles.size() * sizeof(TileDev));
+    off += align_up(plan.tiles.size() * sizeof(TileDev), 256);
+    a.rects = reinterpret_cast<const RectDev*>(dev + off);
+    if (!plan.rects.empty()) std::memcpy(host + off, plan.rects.data(), plan.rects.size() * sizeof(RectDev));
+    off += align_up(plan.rects.size() * sizeof(RectDev), 256);
+    a.ranges = reinterpret_cast<const RangeDev*>(dev + off);
+    if (!plan.ranges.empty()) std::memcpy(host + off, plan.ranges.data(), plan.ranges.size() * sizeof(RangeDev));
+    off += align_up(plan.ranges.size() * sizeof(RangeDev), 256);
+    a.bytes = off;
+    return a;
+}
+
+int check_conv_layer(const dc_layer* l) {
+    if (l->type != DC_CONV) return DC_ERR_INVALID_ARG;
+    if (l->k < 1 || l->s < 1 || l->p < 0 || l->p >= l->k || l->cin < 1 || l->cout < 1) return DC_ERR_INVALID_ARG;
+    return DC_OK;
+}
+
+// Copy + conv launches of one layer given its packed plan on the device.
+int run_conv_planned(const dc_layer& l, const void* in, const void* w, const float* bias,
+                     const void* cache_prev, void* out, int n_streams, int Hin, int Win, int dtype,
+                     const ConvTiling& tiling, const LayerPlan* plan, const PlanAddr* addr, hipStream_t st) {
+    const int Hout = (Hin + 2 * l.p - l.k) / l.s + 1, Wout = (Win + 2 * l.p - l.k) / l.s + 1;
+    ConvLaunch c;
+    c.in = in; c.w = w; c.bias = bias; c.out = out;
+    c.n_streams = n_streams; c.Hin = Hin; c.Win = Win; c.Cin = l.cin;
+    c.Hout = Hout; c.Wout = Wout; c.Cout = l.cout; c.k = l.k; c.s = l.s; c.p = l.p; c.relu = l.relu;
+    c.dtype = dtype; c.tiling = tiling;
+    if (!plan) {
+        c.tiles = nullptr; c.n_tiles = 0; c.rects = nullptr; c.ranges = nullptr;
+        DC_TRY_HIP(launch_conv(c, st));
+        return DC_OK;
+    }
+    int mw = 0, mh = 0;
+    for (const RectDev& r : plan->rects) { mw = r.w > mw ? r.w : mw; mh = r.h > mh ? r.h : mh; }
+    DC_TRY_HIP(launch_shifted_copy(addr->rects, (int)plan->rects.size(), mw, mh, cache_prev, out, Hout, Wout,
+                                   l.cout, dtype, st));
+    if (!plan->tiles.empty()) {
+        c.tiles = addr->tiles; c.n_tiles = (int)plan->tiles.size(); c.rects = addr->rects; c.ranges = addr->ranges;
+        DC_TRY_HIP(launch_conv(c, st));
+    }
+    return DC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dc_status_string(int32_t s) {
+    switch (s) {
+        case DC_OK: return "ok";
+        case DC_ERR_INVALID_ARG: return "invalid argument";
+        case DC_ERR_NULL_PTR: return "null pointer";
+        case DC_ERR_BAD_SHAPE: return "inconsistent shapes";
+        case DC_ERR_UNSUPPORTED: return "unsupported configuration";
+        case DC_ERR_WORKSPACE: return "workspace too small";
+        case DC_ERR_CAPACITY: return "list capacity exceeded";
+        case DC_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int32_t dc_match_blocks(const uint8_t* cur, const uint8_t* prev, int32_t n_streams, int32_t H, int32_t W,
+                        int32_t C, int32_t block, int32_t radius, uint32_t max_block_ssd, int16_t* mv,
+                        uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask,
+                        void* stream) {
+    if (!cur || !prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask) return DC_ERR_NULL_PTR;
+    if (n_streams < 1 || n_streams > 65535 || H < 1 || W < 1 || C < 1 || block < 1 || radius < 0) return DC_ERR_INVALID_ARG;
+    if (block > H || block > W) return DC_ERR_BAD_SHAPE;
+    if (radius > 127 || block * C > 256) return DC_ERR_UNSUPPORTED;
+    const long rows = block + 2 * radius;
+    if (rows * (rows * C + 16) > 60 * 1024) return DC_ERR_UNSUPPORTED;
+    // 32-bit sums: B*B*C*255^2 must fit
+    if ((double)block * block * C * 65025.0 * 2.0 > 4.0e9) return DC_ERR_UNSUPPORTED;
+    DC_TRY_HIP(launch_match(cur, prev, n_streams, H, W, C, block, radius, max_block_ssd, mv, best_ssd, global_mv,
+                            n_pass, block_mask, as_stream(stream)));
+    return DC_OK;
+}
+
+int32_t dc_propagate_regions(const dc_layer* layers, int32_t n_layers, int32_t H, int32_t W, int32_t block,
+                             const uint8_t* block_mask, int32_t gh, int32_t gw, int32_t mx, int32_t my,
+                             dc_regions* regions) {
+    if (!layers || !block_mask || !regions) return DC_ERR_NULL_PTR;
+    if (n_layers < 0 || H < 1 || W < 1 || block < 1 || gh < 0 || gw < 0) return DC_ERR_INVALID_ARG;
+    if (gh != H / block || gw != W / block) return DC_ERR_BAD_SHAPE;
+    int rc = validate_layers(layers, n_layers, H, W, n_layers ? layers[0].cin : 1, nullptr, nullptr, nullptr);
+    if (rc != DC_OK) return rc;
+    for (int t = 0; t <= n_layers; ++t)
+        if (regions[t].capacity < 0 || (regions[t].capacity > 0 && !regions[t].rects)) return DC_ERR_NULL_PTR;
+    std::vector<dc_rect> rects0;
+    std::vector<TensorRegions> out;
+    try {
+        merge_blocks(block_mask, gh, gw, block, rects0);
+        rc = propagate(layers, n_layers, H, W, rects0, mx, my, out);
+    } catch (const std::bad_alloc&) {
+        return DC_ERR_WORKSPACE;
+    }
+    if (rc != DC_OK) return rc;
+    int status = DC_OK;
+    for (int t = 0; t <= n_layers; ++t) {
+        dc_regions& r = regions[t];
+        r.n = (int)out[t].rects.size();
+        r.dx = out[t].dx; r.dy = out[t].dy; r.cum_stride = out[t].cum_stride; r.h = out[t].h; r.w = out[t].w;
+        int keep = r.n < r.capacity ? r.n : r.capacity;
+        if (keep) std::memcpy(r.rects, out[t].rects.data(), keep * sizeof(dc_rect));
+        if (r.n > r.capacity) status = DC_ERR_CAPACITY;
+    }
+    return status;
+}
+
+int32_t dc_conv_workspace_bytes(const dc_layer* layer, int32_t n_streams, int32_t Hin, int32_t Win,
+                                int32_t max_rects, size_t* dev_bytes, size_t* host_bytes) {
+    if (!layer || !dev_bytes || !host_bytes) return DC_ERR_NULL_PTR;
+    int rc = check_conv_layer(layer);
+    if (rc) return rc;
+    if (n_streams < 1 || Hin < 1 || Win < 1 || max_rects < 0) return DC_ERR_INVALID_ARG;
+    if (Hin + 2 * layer->p < layer->k || Win + 2 * layer->p < layer->k) return DC_ERR_BAD_SHAPE;
+    const int Hout = (Hin + 2 * layer->p - layer->k) / layer->s + 1, Wout = (Win + 2 * layer->p - layer->k) / layer->s + 1;
+    size_t worst = 0;
+    for (int dtype = 0; dtype < 2; ++dtype) {
+        size_t b = plan_bytes(n_streams, Hout, Wout, pick_tiling(*layer, Hout, Wout, n_streams, dtype), max_rects);
+        worst = b > worst ? b : worst;
+    }
+    *dev_bytes = worst;
+    *host_bytes = worst;
+    return DC_OK;
+}
+
+int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* weights, const float* bias,
+                             const void* cache_prev, void* out, int32_t n_streams, int32_t Hin, int32_t Win,
+                             const dc_regions* regions, int32_t dtype, void* ws_dev, size_t ws_dev_bytes,
+                             void* ws_host, size_t ws_host_bytes, void* stream) {
+    if (!layer || !in || !weights || !out) return DC_ERR_NULL_PTR;
+    int rc = check_conv_layer(layer);
+    if (rc) return rc;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (n_streams < 1 || Hin < 1 || Win < 1) return DC_ERR_INVALID_ARG;
+    if (Hin + 2 * layer->p < layer->k || Win + 2 * layer->p < layer->k) return DC_ERR_BAD_SHAPE;
+    const int Hout = (Hin + 2 * layer->p - layer->k) / layer->s + 1, Wout = (Win + 2 * layer->p - layer->k) / layer->s + 1;
+    const ConvTiling tiling = pick_tiling(*layer, Hout, Wout, n_streams, dtype);
+    hipStream_t st = as_stream(stream);
+    if (!regions || !cache_prev)
+        return run_conv_planned(*layer, in, weights, bias, nullptr, out, n_streams, Hin, Win, dtype, tiling, nullptr,
+                                nullptr, st);
+    if (out == cache_prev) return DC_ERR_INVALID_ARG;
+    int max_rects = 0;
+    for (int s = 0; s < n_streams; ++s) {
+        if (regions[s].n < 0 || (regions[s].n > 0 && !regions[s].rects)) return DC_ERR_NULL_PTR;
+        if (!rects_disjoint_inside(regions[s].rects, regions[s].n, Wout, Hout, regions[s].dx, regions[s].dy))
+            return DC_ERR_BAD_SHAPE;
+        max_rects = regions[s].n > max_rects ? regions[s].n : max_rects;
+    }
+    size_t need = plan_bytes(n_streams, Hout, Wout, tiling, max_rects);
+    if (!ws_dev || !ws_host) return DC_ERR_NULL_PTR;
+    if (ws_dev_bytes < need || ws_host_bytes < need) return DC_ERR_WORKSPACE;
+    LayerPlan plan;
+    try {
+        for (int s = 0; s < n_streams; ++s)
+            plan_stream(regions[s].rects, regions[s].n, regions[s].dx, regions[s].dy, s, Hout, Wout, tiling.th,
+                        tiling.tw, plan);
+    } catch (const std::bad_alloc&) {
+        return DC_ERR_WORKSPACE;
+    }
+    PlanAddr addr = pack_plan(plan, static_cast<unsigned char*>(ws_host), static_cast<unsigned char*>(ws_dev));
+    DC_TRY_HIP(hipMemcpyAsync(ws_dev, ws_host, addr.bytes, hipMemcpyHostToDevice, st));
+    return run_conv_planned(*layer, in, weights, bias, cache_prev, out, n_streams, Hin, Win, dtype, tiling, &plan,
+                            &addr, st);
+}
+
+int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n, int32_t dtype, void* stream) {
+    if (!frames || !out) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    DC_TRY_HIP(launch_frame_to_tensor(frames, out, n, dtype, as_stream(stream)));
+    return DC_OK;
+}
+
+int32_t dc_maxpool_layer(const void* in, void* out, int32_t n_streams, int32_t Hin, int32_t Win, int32_t C,
+                         int32_t k, int32_t s, int32_t p, int32_t dtype, void* stream) {
+    if (!in || !out) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (n_streams < 1 || Hin < 1 || Win < 1 || C < 1 || k < 1 || s < 1 || p < 0 || p >= k) return DC_ERR_INVALID_ARG;
+    if (Hin + 2 * p < k || Win + 2 * p < k) return DC_ERR_BAD_SHAPE;
+    DC_TRY_HIP(launch_maxpool(in, out, n_streams, Hin, Win, C, k, s, p, dtype, as_stream(stream)));
+    return DC_OK;
+}
+
+int32_t dc_add_layer(const void* a, const void* b, void* out, size_t n, int32_t relu, int32_t dtype, void* stream) {
+    if (!a || !b || !out) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    DC_TRY_HIP(launch_add(a, b, out, n, relu, dtype, as_stream(stream)));
+    return DC_OK;
+}
+
+int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32_t n_streams, int32_t H, int32_t W,
+                                 int32_t C, int32_t block, int32_t max_rects, size_t* dev_bytes, size_t* host_bytes) {
+    if (!layers || !dev_bytes || !host_bytes) return DC_ERR_NULL_PTR;
+    if (n_layers < 1 || n_streams < 1 || block < 1 || max_rects < 1) return DC_ERR_INVALID_ARG;
+    std::vector<int> hs, ws, cs;
+    int rc = validate_layers(layers, n_layers, H, W, C, &hs, &ws, &cs);
+    if (rc) return rc;
+    size_t total = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        if (layers[i].type != DC_CONV) continue;
+        size_t worst = 0;
+        for (int dtype = 0; dtype < 2; ++dtype) {
+            size_t b = plan_bytes(n_streams, hs[i + 1], ws[i + 1],
+                                  pick_tiling(layers[i], hs[i + 1], ws[i + 1], n_streams, dtype), max_rects);
+            worst = b > worst ? b : worst;
+        }
+        total += worst;
+    }
+    const size_t nb = (size_t)n_streams * (H / block) * (W / block);
+    size_t match_host = align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
+    *dev_bytes = total;
+    *host_bytes = total + match_host;
+    return DC_OK;
+}
+
+int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const* weights, const float* const* bias,
+                     const uint8_t* frames_cur, const uint8_t* frames_prev, void* const* tensors_cur,
+                     const void* const* tensors_prev, int32_t n_streams, int32_t H, int32_t W, int32_t C,
+                     int32_t dtype, int32_t block, int32_t radius, uint32_t max_block_ssd, int32_t force_full,
+                     int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask,
+                     int32_t max_rects, dc_regions* regions_out, void* ws_dev, size_t ws_dev_bytes, void* ws_host,
+                     size_t ws_host_bytes, dc_stack_stats* stats, void* stream) {
+    if (!layers || !weights || !frames_cur || !tensors_cur) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (n_layers < 1 || n_streams < 1 || n_streams > 65535 || block < 1 || radius < 0 || max_rects < 1) return DC_ERR_INVALID_ARG;
+    std::vector<int> hs, ws, cs;
+    int rc = validate_layers(layers, n_layers, H, W, C, &hs, &ws, &cs);
+    if (rc) return rc;
+    for (int t = 0; t <= n_layers; ++t)
+        if (!tensors_cur[t]) return DC_ERR_NULL_PTR;
+    for (int i = 0; i < n_layers; ++i)
+        if (layers[i].type == DC_CONV && !weights[i]) return DC_ERR_NULL_PTR;
+    const bool cached = !force_full;
+    if (cached) {
+        if (!frames_prev || !tensors_prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask || !ws_dev || !ws_host)
+            return DC_ERR_NULL_PTR;
+        if (block > H || block > W) return DC_ERR_BAD_SHAPE;
+        for (int i = 0; i < n_layers; ++i)
+            if (layers[i].type == DC_CONV && (!tensors_prev[i + 1] || tensors_prev[i + 1] == tensors_cur[i + 1]))
+                return DC_ERR_NULL_PTR;
+        size_t need_dev = 0, need_host = 0;
+        rc = dc_stack_workspace_bytes(layers, n_layers, n_streams, H, W, C, block, max_rects, &need_dev, &need_host);
+        if (rc) return rc;
+        if (ws_dev_bytes < need_dev || ws_host_bytes < need_host) return DC_ERR_WORKSPACE;
+    }
+    hipStream_t st = as_stream(stream);
+    const int gh = H / block, gw = W / block;
+    const size_t nb = (size_t)n_streams * gh * gw;
+
+    dc_stack_stats local;
+    std::memset(&local, 0, sizeof(local));
+    if (stats) { local.layer_reused_px = stats->layer_reused_px; local.layer_issued_macs = stats->layer_issued_macs; }
+    local.full = cached ? 0 : 1;
+    local.n_blocks = (int32_t)nb;
+
+    std::vector<std::vector<TensorRegions>> regs;  // [stream][tensor]
+    unsigned char* hbase = static_cast<unsigned char*>(ws_host);
+    if (cached) {
+        rc = dc_match_blocks(frames_cur, frames_prev, n_streams, H, W, C, block, radius, max_block_ssd, mv, best_ssd,
+                             global_mv, n_pass, block_mask, stream);
+        if (rc) return rc;
+        // the network input does not depend on the match: overlap its conversion with the readback
+        DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W * C, dtype, st));
+        uint8_t* h_mask = hbase;
+        int32_t* h_gmv = reinterpret_cast<int32_t*>(hbase + align_up(nb, 256));
+        DC_TRY_HIP(hipMemcpyAsync(h_mask, block_mask, nb, hipMemcpyDeviceToHost, st));
+        DC_TRY_HIP(hipMemcpyAsync(h_gmv, global_mv, (size_t)n_streams * 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        DC_TRY_HIP(hipStreamSynchronize(st));
+        try {
+            regs.resize(n_streams);
+            std::vector<dc_rect> rects0;
+            for (int s = 0; s < n_streams; ++s) {
+                const uint8_t* m = h_mask + (size_t)s * gh * gw;
+                for (int i = 0; i < gh * gw; ++i) local.n_reusable_blocks += m[i] ? 1 : 0;
+                merge_blocks(m, gh, gw, block, rects0);
+                rc = propagate(layers, n_layers, H, W, rects0, h_gmv[2 * s], h_gmv[2 * s + 1], regs[s]);
+                if (rc) return rc;
+                for (int t = 0; t <= n_layers; ++t)
+                    if ((int)regs[s][t].rects.size() > max_rects) return DC_ERR_CAPACITY;
+            }
+        } catch (const std::bad_alloc&) {
+            return DC_ERR_WORKSPACE;
+        }
+        hbase += align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
+    } else {
+        DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W * C, dtype, st));
+    }
+    if (regions_out) {
+        int status = DC_OK;
+        for (int s = 0; s < n_streams; ++s)
+            for (int t = 0; t <= n_layers; ++t) {
+                dc_regions& r = regions_out[(size_t)s * (n_layers + 1) + t];
+                if (cached) {
+                    const TensorRegions& g = regs[s][t];
+                    r.n = (int)g.rects.size(); r.dx = g.dx; r.dy = g.dy; r.cum_stride = g.cum_stride; r.h = g.h; r.w = g.w;
+                    int keep = r.n < r.capacity ? r.n : r.capacity;
+                    if (keep && r.rects) std::memcpy(r.rects, g.rects.data(), keep * sizeof(dc_rect));
+                    if (r.n > r.capacity) status = DC_ERR_CAPACITY;
+                } else {
+                    r.n = 0; r.dx = r.dy = 0; r.cum_stride = 0; r.h = hs[t]; r.w = ws[t];
+                }
+            }
+        if (status) return status;
+    }
+
+    // ---- plans of all conv layers, one upload ----
+    std::vector<LayerPlan> plans(n_layers);
+    std::vector<PlanAddr> addrs(n_layers);
+    std::vector<ConvTiling> tilings(n_layers);
+    size_t off = 0;
+    try {
+        for (int i = 0; i < n_layers; ++i) {
+            const dc_layer& l = layers[i];
+            if (l.type != DC_CONV) continue;
+            tilings[i] = pick_tiling(l, hs[i + 1], ws[i + 1], n_streams, dtype);
+            const int64_t px = (int64_t)hs[i + 1] * ws[i + 1] * n_streams;
+            const int64_t mac_px = (int64_t)l.k * l.k * l.cin * l.cout;
+            local.macs_full += px * mac_px;
+            if (!cached) {
+                local.macs_needed += px * mac_px;
+                int64_t tiles = (int64_t)n_streams * ((hs[i + 1] + tilings[i].th - 1) / tilings[i].th) *
+                                ((ws[i + 1] + tilings[i].tw - 1) / tilings[i].tw);
+                int64_t issued = tiles * tilings[i].th * tilings[i].tw * mac_px;
+                local.macs_issued += issued;
+                if (local.layer_reused_px) local.layer_reused_px[i] = 0;
+                if (local.layer_issued_macs) local.layer_issued_macs[i] = issued;
+                continue;
+            }
+            LayerPlan& plan = plans[i];
+            for (int s = 0; s < n_streams; ++s) {
+                const TensorRegions& g = regs[s][i + 1];
+                plan_stream(g.rects.data(), (int)g.rects.size(), g.dx, g.dy, s, hs[i + 1], ws[i + 1], tilings[i].th,
+                            tilings[i].tw, plan);
+            }
+            addrs[i] = pack_plan(plan, hbase + off, static_cast<unsigned char*>(ws_dev) + off);
+            off += addrs[i].bytes;
+            int64_t issued = (int64_t)plan.tiles.size() * tilings[i].th * tilings[i].tw * mac_px;
+            local.macs_needed += (px - plan.reused_px) * mac_px;
+            local.macs_issued += issued;
+            local.copy_bytes += 2 * plan.reused_px * l.cout * (int64_t)dtype_size(dtype);
+            if (local.layer_reused_px) local.layer_reused_px[i] = plan.reused_px;
+            if (local.layer_issued_macs) local.layer_issued_macs[i] = issued;
+        }
+    } catch (const std::bad_alloc&) {
+        return DC_ERR_WORKSPACE;
+    }
+    if (cached && off) DC_TRY_HIP(hipMemcpyAsync(ws_dev, hbase, off, hipMemcpyHostToDevice, st));
+
+    // ---- layers ----
+    for (int i = 0; i < n_layers; ++i) {
+        const dc_layer& l = layers[i];
+        const int a = l.in0, t = i + 1;
+        switch (l.type) {
+            case DC_CONV:
+                rc = run_conv_planned(l, tensors_cur[a], weights[i], bias ? bias[i] : nullptr,
+                                      cached ? tensors_prev[t] : nullptr, tensors_cur[t], n_streams, hs[a], ws[a], dtype,
+                                      tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st);
+                if (rc) return rc;
+                break;
+            case DC_MAXPOOL:
+                DC_TRY_HIP(launch_maxpool(tensors_cur[a], tensors_cur[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
+                                          dtype, st));
+                break;
+            case DC_ADD:
+                DC_TRY_HIP(launch_add(tensors_cur[a], tensors_cur[l.in1], tensors_cur[t],
+                                      (size_t)n_streams * hs[t] * ws[t] * cs[t], l.relu, dtype, st));
+                break;
+            default:
+                DC_TRY_HIP(launch_add(tensors_cur[a], nullptr, tensors_cur[t], (size_t)n_streams * hs[t] * ws[t] * cs[t],
+                                      1, dtype, st));
+                break;
+        }
+    }
+    if (stats) *stats = local;
+    return DC_OK;
+}
+
+}  // extern "C"

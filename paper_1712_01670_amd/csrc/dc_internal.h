@@ -1,0 +1,88 @@
+// Internal declarations shared by the translation units of libdeepcache.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "deepcache.h"
+
+namespace dc {
+
+// ---- device-side plan records -------------------------------------------------
+// One reusable rectangle of a conv layer's output, with its stream and source offset.
+struct RectDev {
+    int32_t x, y, w, h;
+    int32_t stream, dx, dy, pad;
+};
+// One output tile that holds at least one non-reusable pixel.
+struct TileDev {
+    int32_t stream, ty, tx;
+    int32_t mixed;  // 1: some pixels of the tile are reusable (per-pixel test needed)
+};
+// Per-stream slice of the rectangle table.
+struct RangeDev {
+    int32_t begin, count;
+};
+
+// ---- tile geometry ------------------------------------------------------------
+struct ConvTiling {
+    int cfg;     // index into the kernel table
+    int th, tw;  // output pixels per tile (rows, columns)
+    int nt;      // output channels per workgroup
+};
+ConvTiling pick_tiling(const dc_layer& L, int Hout, int Wout, int n_streams, int dtype);
+
+// ---- host region logic (dc_regions.cpp) ---------------------------------------
+struct TensorRegions {
+    std::vector<dc_rect> rects;
+    int dx = 0, dy = 0, cum_stride = 1, h = 0, w = 0;
+};
+void merge_blocks(const uint8_t* mask, int gh, int gw, int B, std::vector<dc_rect>& out);
+int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<dc_rect>& rects0,
+              int mx, int my, std::vector<TensorRegions>& out);
+int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C,
+                    std::vector<int>* hs, std::vector<int>* ws, std::vector<int>* cs);
+
+struct LayerPlan {
+    std::vector<RectDev> rects;    // all streams
+    std::vector<RangeDev> ranges;  // [n_streams]
+    std::vector<TileDev> tiles;    // dirty tiles, all streams
+    int64_t reused_px = 0;
+};
+// Classify the tiles of one stream's output map against its rectangles and append.
+void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Hout, int Wout,
+                 int th, int tw, LayerPlan& plan);
+
+// ---- kernel launchers -----------------------------------------------------------
+struct ConvLaunch {
+    const void* in;
+    const void* w;
+    const float* bias;
+    void* out;
+    int n_streams, Hin, Win, Cin, Hout, Wout, Cout, k, s, p, relu, dtype;
+    ConvTiling tiling;
+    const TileDev* tiles;  // device; nullptr: every tile of every stream
+    int n_tiles;           // ignored when tiles == nullptr
+    const RectDev* rects;  // device
+    const RangeDev* ranges;
+};
+hipError_t launch_conv(const ConvLaunch& c, hipStream_t st);
+
+hipError_t launch_shifted_copy(const RectDev* rects_dev, int n_rects, int max_rect_w, int max_rect_h,
+                               const void* prev, void* out, int Hout, int Wout, int Cout,
+                               int dtype, hipStream_t st);
+hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, int H, int W, int C,
+                        int B, int R, uint32_t max_ssd, int16_t* mv, uint32_t* best_ssd,
+                        int32_t* gmv, int32_t* n_pass, uint8_t* mask, hipStream_t st);
+hipError_t launch_frame_to_tensor(const uint8_t* f, void* out, size_t n, int dtype, hipStream_t st);
+hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k,
+                          int s, int p, int dtype, hipStream_t st);
+hipError_t launch_add(const void* a, const void* b, void* out, size_t n, int relu, int dtype,
+                      hipStream_t st);
+
+inline size_t dtype_size(int dtype) { return dtype == DC_BF16 ? 2 : 4; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace dc

@@ -1,0 +1,177 @@
+// Host integer logic: merging matched blocks into rectangles (Section 4, Step 5),
+// propagating rectangles through the layer table (Section 5, Table 2) and sorting the
+// output tiles of a conv layer into clean / mixed / dirty for the GEMM tile list.
+#include <algorithm>
+
+#include "dc_internal.h"
+
+namespace dc {
+
+namespace {
+
+struct Span {  // half-open interval [lo, hi)
+    int lo, hi;
+    bool empty() const { return hi <= lo; }
+};
+
+inline int fdiv(int a, int b) {  // floor(a / b), b > 0
+    int q = a / b, r = a % b;
+    return (r < 0) ? q - 1 : q;
+}
+inline int cdiv(int a, int b) { return fdiv(a + b - 1, b); }
+
+// Outputs whose window [o*s-p, o*s-p+k) lies inside `in` (one axis of Table 2's conv/pool row).
+inline Span window_span(Span in, int k, int s, int p) {
+    return Span{cdiv(in.lo + p, s), fdiv(in.hi - k + p, s) + 1};
+}
+
+inline Span intersect(Span a, Span b) { return Span{std::max(a.lo, b.lo), std::min(a.hi, b.hi)}; }
+
+// Part of `cur` whose source cur+d lies inside [0, size).
+inline Span keep_source_inside(Span cur, int d, int size) {
+    return intersect(intersect(cur, Span{0, size}), Span{-d, size - d});
+}
+
+inline int round_half_away(long long num, long long den) {
+    long long mag = num < 0 ? -num : num;
+    long long q = (2 * mag + den) / (2 * den);
+    return (int)(num < 0 ? -q : q);
+}
+
+inline void push_clipped(std::vector<dc_rect>& out, Span xs, Span ys, const TensorRegions& t) {
+    xs = keep_source_inside(xs, t.dx, t.w);
+    ys = keep_source_inside(ys, t.dy, t.h);
+    if (xs.empty() || ys.empty()) return;
+    out.push_back(dc_rect{xs.lo, ys.lo, xs.hi - xs.lo, ys.hi - ys.lo});
+}
+
+}  // namespace
+
+void merge_blocks(const uint8_t* mask, int gh, int gw, int B, std::vector<dc_rect>& out) {
+    out.clear();
+    std::vector<uint8_t> open(mask, mask + (size_t)gh * gw);  // set and not yet claimed
+    for (int by = 0; by < gh; ++by) {
+        for (int bx = 0; bx < gw; ++bx) {
+            if (!open[by * gw + bx]) continue;
+            int x1 = bx;
+            while (x1 < gw && open[by * gw + x1]) ++x1;
+            int y1 = by + 1;
+            while (y1 < gh && std::all_of(open.begin() + y1 * gw + bx, open.begin() + y1 * gw + x1,
+                                          [](uint8_t v) { return v != 0; }))
+                ++y1;
+            for (int y = by; y < y1; ++y) std::fill(open.begin() + y * gw + bx, open.begin() + y * gw + x1, 0);
+            out.push_back(dc_rect{bx * B, by * B, (x1 - bx) * B, (y1 - by) * B});
+        }
+    }
+}
+
+int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C, std::vector<int>* hs,
+                    std::vector<int>* ws, std::vector<int>* cs) {
+    std::vector<int> h(n_layers + 1), w(n_layers + 1), c(n_layers + 1);
+    h[0] = H; w[0] = W; c[0] = C;
+    for (int i = 0; i < n_layers; ++i) {
+        const dc_layer& l = L[i];
+        if (l.in0 < 0 || l.in0 > i) return DC_ERR_BAD_SHAPE;
+        int a = l.in0;
+        switch (l.type) {
+            case DC_CONV:
+            case DC_MAXPOOL:
+                if (l.k < 1 || l.s < 1 || l.p < 0 || l.p >= l.k) return DC_ERR_INVALID_ARG;
+                if (l.cin != c[a] || l.cout < 1) return DC_ERR_BAD_SHAPE;
+                if (l.type == DC_MAXPOOL && l.cout != l.cin) return DC_ERR_BAD_SHAPE;
+                if (h[a] + 2 * l.p < l.k || w[a] + 2 * l.p < l.k) return DC_ERR_BAD_SHAPE;
+                h[i + 1] = (h[a] + 2 * l.p - l.k) / l.s + 1;
+                w[i + 1] = (w[a] + 2 * l.p - l.k) / l.s + 1;
+                c[i + 1] = l.cout;
+                break;
+            case DC_ADD:
+                if (l.in1 < 0 || l.in1 > i) return DC_ERR_BAD_SHAPE;
+                if (h[a] != h[l.in1] || w[a] != w[l.in1] || c[a] != c[l.in1] || l.cin != c[a] ||
+                    l.cout != c[a])
+                    return DC_ERR_BAD_SHAPE;
+                h[i + 1] = h[a]; w[i + 1] = w[a]; c[i + 1] = c[a];
+                break;
+            case DC_RELU:
+                if (l.cin != c[a] || l.cout != c[a]) return DC_ERR_BAD_SHAPE;
+                h[i + 1] = h[a]; w[i + 1] = w[a]; c[i + 1] = c[a];
+                break;
+            default:
+                return DC_ERR_INVALID_ARG;
+        }
+    }
+    if (hs) *hs = h;
+    if (ws) *ws = w;
+    if (cs) *cs = c;
+    return DC_OK;
+}
+
+int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<dc_rect>& rects0,
+              int mx, int my, std::vector<TensorRegions>& out) {
+    out.assign(n_layers + 1, TensorRegions());
+    TensorRegions& t0 = out[0];
+    t0.h = H; t0.w = W; t0.dx = mx; t0.dy = my; t0.cum_stride = 1;
+    for (const dc_rect& r : rects0) push_clipped(t0.rects, Span{r.x, r.x + r.w}, Span{r.y, r.y + r.h}, t0);
+    for (int i = 0; i < n_layers; ++i) {
+        const dc_layer& l = L[i];
+        const TensorRegions& a = out[l.in0];
+        TensorRegions& t = out[i + 1];
+        const bool windowed = (l.type == DC_CONV || l.type == DC_MAXPOOL);
+        t.h = windowed ? (a.h + 2 * l.p - l.k) / l.s + 1 : a.h;
+        t.w = windowed ? (a.w + 2 * l.p - l.k) / l.s + 1 : a.w;
+        t.cum_stride = windowed ? a.cum_stride * l.s : a.cum_stride;
+        t.dx = round_half_away(mx, t.cum_stride);
+        t.dy = round_half_away(my, t.cum_stride);
+        if (windowed) {
+            for (const dc_rect& r : a.rects) {
+                Span xs = window_span(Span{r.x, r.x + r.w}, l.k, l.s, l.p);
+                Span ys = window_span(Span{r.y, r.y + r.h}, l.k, l.s, l.p);
+                if (xs.empty() || ys.empty()) continue;
+                push_clipped(t.rects, xs, ys, t);
+            }
+        } else if (l.type == DC_ADD) {
+            const TensorRegions& b = out[l.in1];
+            if (b.cum_stride != a.cum_stride) return DC_ERR_BAD_SHAPE;
+            for (const dc_rect& ra : a.rects)
+                for (const dc_rect& rb : b.rects) {
+                    Span xs = intersect(Span{ra.x, ra.x + ra.w}, Span{rb.x, rb.x + rb.w});
+                    Span ys = intersect(Span{ra.y, ra.y + ra.h}, Span{rb.y, rb.y + rb.h});
+                    if (xs.empty() || ys.empty()) continue;
+                    push_clipped(t.rects, xs, ys, t);
+                }
+        } else {
+            for (const dc_rect& r : a.rects) push_clipped(t.rects, Span{r.x, r.x + r.w}, Span{r.y, r.y + r.h}, t);
+        }
+    }
+    return DC_OK;
+}
+
+void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Hout, int Wout, int th,
+                 int tw, LayerPlan& plan) {
+    const int tiles_y = (Hout + th - 1) / th, tiles_x = (Wout + tw - 1) / tw;
+    std::vector<int> covered((size_t)tiles_y * tiles_x, 0);
+    RangeDev range{(int)plan.rects.size(), 0};
+    for (int i = 0; i < n; ++i) {
+        const dc_rect& r = rects[i];
+        if (r.w <= 0 || r.h <= 0) continue;
+        plan.rects.push_back(RectDev{r.x, r.y, r.w, r.h, stream, dx, dy, 0});
+        ++range.count;
+        plan.reused_px += (int64_t)r.w * r.h;
+        for (int ty = r.y / th; ty <= (r.y + r.h - 1) / th; ++ty) {
+            int oy = std::min(r.y + r.h, (ty + 1) * th) - std::max(r.y, ty * th);
+            for (int tx = r.x / tw; tx <= (r.x + r.w - 1) / tw; ++tx) {
+                int ox = std::min(r.x + r.w, (tx + 1) * tw) - std::max(r.x, tx * tw);
+                covered[(size_t)ty * tiles_x + tx] += oy * ox;
+            }
+        }
+    }
+    plan.ranges.push_back(range);
+    for (int ty = 0; ty < tiles_y; ++ty)
+        for (int tx = 0; tx < tiles_x; ++tx) {
+            int area = std::min(th, Hout - ty * th) * std::min(tw, Wout - tx * tw);
+            int cov = covered[(size_t)ty * tiles_x + tx];
+            if (cov >= area) continue;  // every pixel is served by the copy
+            plan.tiles.push_back(TileDev{stream, ty, tx, cov > 0 ? 1 : 0});
+        }
+}
+
+}  // namespace dc

@@ -1,0 +1,123 @@
+"""GPU parity of the per-layer entry points against the oracle (Section 5 "Reuse")."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1712_01670_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _to_dev(a, bf16):
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+def _to_np(t):
+    return t.float().cpu().numpy()
+
+
+def _rel_err(got, want):
+    scale = max(float(np.abs(want).max()), 1e-30)
+    return float(np.abs(got - want).max()) / scale
+
+
+def _layer(cin, cout, k, s, p, relu):
+    return dict(type=synth.CONV, k=k, s=s, p=p, cin=cin, cout=cout, relu=int(relu), in0=0, in1=-1)
+
+
+CONV_CASES = [
+    # H, W, cin, cout, k, s, p, relu
+    (20, 37, 3, 16, 3, 1, 1, True),      # first-layer shape, ragged tiles
+    (33, 18, 16, 32, 3, 2, 1, True),     # stride 2
+    (16, 16, 32, 32, 3, 1, 1, False),
+    (29, 31, 64, 64, 3, 1, 1, True),     # 64-channel, several tiles and a ragged tail
+    (14, 14, 128, 256, 3, 1, 1, True),   # small map, wide
+    (28, 28, 64, 128, 1, 1, 0, True),    # 1x1
+    (28, 28, 128, 64, 1, 2, 0, False),   # 1x1 stride 2 (projection shortcut)
+    (40, 40, 3, 64, 7, 2, 3, True),      # stem
+    (9, 11, 5, 7, 3, 1, 0, True),        # odd channel counts: scalar load path
+    (10, 10, 40, 136, 3, 1, 1, True),    # cin not a multiple of the chunk, cout ragged
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_full_conv_matches_oracle(oracle, case, bf16):
+    H, W, cin, cout, k, s, p, relu = case
+    print(f"[conv] case={case} bf16={bf16}", flush=True)
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 31)
+    x = rng.standard_normal((2, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, k, k, cin)) * np.sqrt(2.0 / (cin * k * k))).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    if bf16:
+        x, w = oracle.round_bf16(x), oracle.round_bf16(w)
+    got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, k, s, p, relu), _to_dev(x, bf16), _to_dev(w, bf16),
+                                              torch.from_numpy(b).to(DEV)))
+    for n in range(2):
+        want = oracle.conv_cached(x[n], w, b, k, s, p, relu, bf16=bf16)
+        assert got[n].shape == want.shape
+        assert _rel_err(got[n], want) <= (2e-2 if bf16 else 1e-4), (case, n)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("case", [(40, 52, 16, 64, 3, 1, 1), (31, 45, 32, 32, 3, 2, 1), (24, 24, 64, 160, 1, 1, 0)])
+def test_cached_conv_matches_oracle(oracle, case, bf16):
+    H, W, cin, cout, k, s, p = case
+    print(f"[cached conv] case={case} bf16={bf16}", flush=True)
+    rng = np.random.default_rng(sum(case))
+    n = 3
+    x = rng.standard_normal((n, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, k, k, cin)) * np.sqrt(2.0 / (cin * k * k))).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    Ho, Wo = (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1
+    cache = rng.standard_normal((n, Ho, Wo, cout)).astype(np.float32)
+    if bf16:
+        x, w, cache = oracle.round_bf16(x), oracle.round_bf16(w), oracle.round_bf16(cache)
+    # per-stream regions: stream 0 large rect + sliver, stream 1 nothing, stream 2 everything that fits
+    regions = [
+        (np.array([[2, 1, Wo - 9, Ho - 9], [Wo - 6, 3, 2, 5]], np.int32), (3, -1)),
+        (np.zeros((0, 4), np.int32), (0, 0)),
+        (np.array([[0, 0, Wo - 2, Ho - 1]], np.int32), (2, 1)),
+    ]
+    got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, k, s, p, True), _to_dev(x, bf16), _to_dev(w, bf16),
+                                              torch.from_numpy(b).to(DEV), cache_prev=_to_dev(cache, bf16),
+                                              regions=regions))
+    for i in range(n):
+        mask = oracle.rasterize(regions[i][0], Ho, Wo)
+        want = oracle.conv_cached(x[i], w, b, k, s, p, True, cache_prev=cache[i], mask=mask, dxy=regions[i][1], bf16=bf16)
+        m = mask.astype(bool)
+        assert np.array_equal(got[i][m], want[m]), "copied pixels must be bit-identical"
+        assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
+
+
+def test_cached_conv_everything_reusable_launches_no_gemm(oracle):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((1, 16, 16, 16)).astype(np.float32)
+    w = rng.standard_normal((32, 3, 3, 16)).astype(np.float32)
+    cache = rng.standard_normal((1, 16, 16, 32)).astype(np.float32)
+    got = _to_np(binding.dc_cached_conv_layer(_layer(16, 32, 3, 1, 1, True), _to_dev(x, False), _to_dev(w, False), None,
+                                              cache_prev=_to_dev(cache, False),
+                                              regions=[(np.array([[0, 0, 16, 16]], np.int32), (0, 0))]))
+    assert np.array_equal(got, cache)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_uncached_layers(oracle, bf16):
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((2, 23, 30, 24)).astype(np.float32)
+    y = rng.standard_normal((2, 23, 30, 24)).astype(np.float32)
+    if bf16:
+        x, y = oracle.round_bf16(x), oracle.round_bf16(y)
+    for k, s, p in [(2, 2, 0), (3, 2, 1)]:
+        got = _to_np(binding.dc_maxpool_layer(_to_dev(x, bf16), k, s, p))
+        for n in range(2):
+            assert np.array_equal(got[n], oracle.maxpool(x[n], k, s, p))
+    for relu in (0, 1):
+        got = _to_np(binding.dc_add_layer(_to_dev(x, bf16), _to_dev(y, bf16), relu))
+        assert np.array_equal(got, oracle.add(x, y, relu, bf16=bf16))
+    f = rng.integers(0, 256, (2, 9, 11, 3)).astype(np.uint8)
+    dt = binding.DC_BF16 if bf16 else binding.DC_F32
+    got = _to_np(binding.dc_frame_to_tensor(torch.from_numpy(f).to(DEV), dt))
+    assert np.array_equal(got, oracle.frame_to_tensor(f))

@@ -1,0 +1,119 @@
+"""GPU parity of dc_run_stack (whole per-frame path) against the oracle: match results,
+reuse masks and propagated rectangles bit-exact; every tensor within 1e-4 (fp32) or
+2e-2 (bf16) of the oracle, relative to the tensor's largest magnitude."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1712_01670_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _rel_err(got, want):
+    scale = max(float(np.abs(want).max()), 1e-30)
+    return float(np.abs(got - want).max()) / scale
+
+
+def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
+              residual_scale=1.0, check_tensors=None, resets=()):
+    """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
+    n, T, H, W, C = videos.shape
+    ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale)
+    tol = 2e-2 if bf16 else 1e-4
+    dt = binding.DC_BF16 if bf16 else binding.DC_F32
+    runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
+                                 want_regions=True)
+    streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry)
+               for _ in range(n)]
+    dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
+    worst = 0.0
+    reuse = []
+    for t in range(T):
+        print(f"[stack] frame {t}/{T} n={n} {H}x{W} bf16={bf16}", flush=True)
+        if t in resets:
+            runner.reset()
+            for s in streams:
+                s.reset()
+        tensors = runner.step(dev_video[t])
+        torch.cuda.synchronize()
+        got = [x.float().cpu().numpy() for x in tensors]
+        for s in range(n):
+            want = streams[s].step(videos[s, t])
+            assert bool(runner.last_full) == bool(want["full"])
+            if not want["full"]:
+                m = want["match"]
+                assert np.array_equal(runner.mv[s].cpu().numpy(), m["mv"])
+                assert np.array_equal(runner.best_ssd[s].cpu().numpy().view(np.uint32), m["best_ssd"])
+                assert runner.gmv[s].cpu().numpy().tolist() == m["gmv"].tolist()
+                assert int(runner.n_pass[s]) == m["n_pass"]
+                assert np.array_equal(runner.mask[s].cpu().numpy(), m["mask"])
+                regs = runner.regions(s)
+                for ti in range(len(layers) + 1):
+                    assert regs[ti]["rects"].tolist() == want["rects"][ti].tolist(), (t, s, ti)
+                    assert list(regs[ti]["dxy"]) == want["dxy"][ti].tolist()
+                reuse.append(float(m["mask"].mean()))
+            for ti in (check_tensors or range(len(layers) + 1)):
+                e = _rel_err(got[ti][s], want["tensors"][ti])
+                worst = max(worst, e)
+                assert e <= tol, (t, s, ti, e)
+    print(f"[stack] worst rel err {worst:.3e}, mean block reuse {np.mean(reuse) if reuse else 0:.3f}", flush=True)
+    return runner, reuse
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_tiny_config(oracle, bf16):
+    f1, f2 = synth.tiny_pair(0)
+    video = np.stack([f1, f2, f2, f1])[None]
+    runner, reuse = _run_both(oracle, synth.tiny_net(), video, 8, 8, bf16)
+    assert abs(reuse[0] - 45 / 64) < 1e-9
+    assert reuse[1] == 1.0
+
+
+def test_tiny_exact_shift_equals_full_forward_on_gpu(oracle):
+    # the invariant of the oracle also holds for the HIP path: with an exact shift by a multiple of
+    # the total stride the cached frame reproduces the full forward (copies are bit copies; recomputed
+    # pixels go through the same kernel)
+    layers = synth.tiny_net()
+    f1, f2 = synth.shifted_pair(10, 64, 64, (4, -2))
+    ws, bs = synth.he_weights(layers, 1, bias_scale=0.05)
+    r = binding.StackRunner(layers, ws, bs, 1, 64, 64, 3, block=8, radius=8)
+    d1, d2 = torch.from_numpy(f1[None]).to(DEV), torch.from_numpy(f2[None]).to(DEV)
+    r.step(d1)
+    cached = [t.clone() for t in r.step(d2)]
+    assert r.stats.n_reusable_blocks >= 40
+    r.reset()
+    full = r.step(d2)
+    for a, b in zip(cached, full):
+        assert torch.equal(a, b)
+
+
+def test_vgg16_224_first_frames(oracle):
+    video = synth.panning_video(2000, n_frames=3)[None]
+    _run_both(oracle, synth.vgg16(), video, 16, 16, False, bias_scale=0.0)
+
+
+def test_vgg16_two_streams_bf16_small(oracle):
+    # batch mode: per-stream caches, per-stream motion, one launch per layer
+    v = np.stack([synth.panning_video(5000 + s, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
+    _run_both(oracle, synth.vgg16(), v, 16, 16, True, bias_scale=0.0)
+
+
+def test_expiry_and_reset(oracle):
+    f1, f2 = synth.tiny_pair(3)
+    video = np.stack([f1, f2, f2, f1, f1, f2])[None]
+    _run_both(oracle, synth.tiny_net(), video, 8, 8, False, expiry=3, resets=(4,))
+
+
+def test_resnet_stage_small(oracle):
+    layers = synth.resnet50_trunk()[:23]     # stem, pool, stage 1 (3 blocks), first block of stage 2
+    v = synth.panning_video(3000, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32)[None]
+    _run_both(oracle, layers, v, 16, 16, True, bias_scale=0.0, residual_scale=0.5)
+    _run_both(oracle, layers, v, 16, 16, False, bias_scale=0.0, residual_scale=0.5)
+
+
+def test_darknet_head_small(oracle):
+    layers = synth.darknet19()[:12]
+    v = synth.reuse_sweep_video(4001, 0.75, n_frames=3, H=128, W=128, cut_at=2)[None]
+    _run_both(oracle, layers, v, 16, 16, True, bias_scale=0.0, resets=(2,))

@@ -1,0 +1,95 @@
+"""CPU-only checks of libdeepcache.so: it loads, exports every symbol the header
+declares, rejects bad arguments before touching the GPU, and its host region logic
+(merge + propagation) equals the oracle bit for bit."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1712_01670_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "deepcache.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dc_[a-z_]+)\s*\(", body))
+    assert {"dc_match_blocks", "dc_propagate_regions", "dc_cached_conv_layer", "dc_run_stack"} <= declared
+    L = binding.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(binding.EXPORTS)
+    assert L.dc_status_string(0) == b"ok"
+    assert L.dc_status_string(-5) == b"workspace too small"
+
+
+def test_no_torch_types_in_the_header():
+    header = open(os.path.join(ROOT, "include", "deepcache.h")).read()
+    assert "torch" not in header and "at::" not in header and "hip/" not in header
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    L = binding.lib()
+    # null pointers
+    assert L.dc_match_blocks(None, None, 1, 64, 64, 3, 8, 8, 0, None, None, None, None, None, None) == -2
+    one = C.c_void_p(16)  # never dereferenced: validation fails first
+    assert L.dc_match_blocks(one, one, 0, 64, 64, 3, 8, 8, 0, one, one, one, one, one, None) == -1
+    assert L.dc_match_blocks(one, one, 1, 64, 64, 3, 128, 8, 0, one, one, one, one, one, None) == -3
+    assert L.dc_match_blocks(one, one, 1, 64, 64, 3, 8, 200, 0, one, one, one, one, one, None) == -4
+    bad = binding.layers_to_c([dict(type=0, k=3, s=0, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
+    assert L.dc_cached_conv_layer(bad, one, one, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -1
+    ok = binding.layers_to_c([dict(type=0, k=3, s=1, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
+    assert L.dc_cached_conv_layer(ok, one, one, None, None, one, 1, 8, 8, None, 7, None, 0, None, 0, None) == -1
+    assert L.dc_cached_conv_layer(ok, None, one, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -2
+    # overlapping rectangles are rejected
+    regs, keep = binding._alloc_regions(1, 2)
+    keep[0][0] = binding.Rect(0, 0, 4, 4)
+    keep[0][1] = binding.Rect(2, 2, 4, 4)
+    regs[0].n = 2
+    assert L.dc_cached_conv_layer(ok, one, one, None, one, C.c_void_p(32), 1, 8, 8, regs, 0, one, 1 << 20, one,
+                                  1 << 20, None) == -3
+    # a layer table whose channel counts do not chain
+    layers = synth.tiny_net()
+    layers[1] = dict(layers[1], cin=17)
+    with pytest.raises(binding.DcError) as e:
+        binding.dc_propagate_regions(layers, 64, 64, 8, np.ones((8, 8), np.uint8), 0, 0)
+    assert e.value.status == -3
+    with pytest.raises(binding.DcError) as e:
+        binding.dc_propagate_regions(synth.tiny_net(), 64, 64, 8, np.ones((4, 8), np.uint8), 0, 0)
+    assert e.value.status == -3
+    with pytest.raises(binding.DcError) as e:
+        binding.dc_propagate_regions(synth.tiny_net(), 64, 64, 8, np.ones((8, 8), np.uint8), 0, 0, cap=0)
+    assert e.value.status in (-2, -6)
+
+
+def _compare(oracle, layers, H, W, B, mask, mx, my):
+    got = binding.dc_propagate_regions(layers, H, W, B, mask, mx, my)
+    r0 = oracle.merge_blocks(mask, B)
+    want = oracle.propagate(layers, H, W, r0, mx, my)
+    for t in range(len(layers) + 1):
+        assert got[t]["rects"].tolist() == want["rects"][t].tolist(), t
+        assert list(got[t]["dxy"]) == want["dxy"][t].tolist(), t
+        assert got[t]["cum_stride"] == want["cum_stride"][t]
+        assert list(got[t]["hw"]) == want["hw"][t].tolist()
+
+
+@pytest.mark.parametrize("net,H,W,B", [("tiny", 64, 64, 8), ("vgg", 224, 224, 16), ("resnet", 224, 224, 16),
+                                       ("darknet", 416, 416, 16), ("vgg", 100, 132, 10)])
+def test_host_regions_equal_oracle(oracle, net, H, W, B):
+    layers = dict(tiny=synth.tiny_net, vgg=synth.vgg16, resnet=synth.resnet50_trunk, darknet=synth.darknet19)[net]()
+    rng = np.random.default_rng(len(net) * 100 + H)
+    gh, gw = H // B, W // B
+    for trial in range(25):
+        dens = rng.choice([0.0, 0.3, 0.7, 0.9, 0.97, 1.0])
+        mask = (rng.random((gh, gw)) < dens).astype(np.uint8)
+        if trial % 3 == 0:   # a solid region with a hole: the typical panning-background case
+            mask[:] = 1
+            y, x = int(rng.integers(0, gh - 2)), int(rng.integers(0, gw - 2))
+            mask[y:y + 3, x:x + 2] = 0
+        mx, my = int(rng.integers(-B, B + 1)), int(rng.integers(-B, B + 1))
+        _compare(oracle, layers, H, W, B, mask, mx, my)
+    _compare(oracle, layers, H, W, B, np.ones((gh, gw), np.uint8), 0, 0)
+    _compare(oracle, layers, H, W, B, np.zeros((gh, gw), np.uint8), 3, -2)
