@@ -85,9 +85,33 @@ typedef struct {
     int64_t copy_bytes;         /* bytes read plus bytes written by the shifted copies */
     int64_t* layer_reused_px;   /* optional host [n_layers]: reused output pixels per conv layer */
     int64_t* layer_issued_macs; /* optional host [n_layers] */
+    int32_t* layer_kernel_id;   /* optional host [n_layers]: which GEMM instantiation ran (-1: none) */
+    void* profile;              /* optional dc_profile handle with >= 2*n_layers slots: slot i brackets
+                                   the GEMM kernel of conv layer i, slot n_layers+i its shifted copy */
 } dc_stack_stats;
 
 const char* dc_status_string(int32_t status);
+
+/*
+ * Kernel timing with HIP events (measurement aid, not part of the method).  A profile
+ * owns 2*n_slots events; a slot that brackets a kernel launch is recorded on the launch
+ * stream.  dc_profile_elapsed_ms may be called after the stream has been synchronised;
+ * it returns DC_ERR_INVALID_ARG for a slot that was not recorded since the last
+ * dc_profile_reset.
+ */
+int32_t dc_profile_create(int32_t n_slots, void** profile);
+int32_t dc_profile_destroy(void* profile);
+int32_t dc_profile_reset(void* profile);
+int32_t dc_profile_elapsed_ms(void* profile, int32_t slot, float* ms);
+
+/* Name of a GEMM kernel instantiation (as a profiler prints it, without namespace and
+ * argument list) for an id reported in dc_stack_stats.layer_kernel_id. */
+int32_t dc_conv_kernel_name(int32_t kernel_id, char* buf, size_t n);
+
+/* Granularity of the dirty-tile list of a conv layer: th x tw output pixels per list entry
+ * (nt and cfg are informational). */
+int32_t dc_conv_tile_shape(const dc_layer* layer, int32_t n_streams, int32_t Hin, int32_t Win,
+                           int32_t dtype, int32_t* th, int32_t* tw, int32_t* nt, int32_t* cfg);
 
 /*
  * Section 4, Steps 1-4 (block grid, exhaustive search of Section 7.6, mean motion,

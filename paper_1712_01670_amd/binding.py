@@ -21,7 +21,8 @@ DC_F32, DC_BF16 = 0, 1
 STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_ERR_BAD_SHAPE",
           -4: "DC_ERR_UNSUPPORTED", -5: "DC_ERR_WORKSPACE", -6: "DC_ERR_CAPACITY", -7: "DC_ERR_HIP"}
 
-EXPORTS = ["dc_status_string", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
+EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
+           "dc_profile_elapsed_ms", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
            "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
@@ -50,7 +51,8 @@ class StackStats(C.Structure):
     _fields_ = [("full", C.c_int32), ("n_blocks", C.c_int32), ("n_reusable_blocks", C.c_int32),
                 ("macs_full", C.c_int64), ("macs_needed", C.c_int64), ("macs_issued", C.c_int64),
                 ("copy_bytes", C.c_int64), ("layer_reused_px", C.POINTER(C.c_int64)),
-                ("layer_issued_macs", C.POINTER(C.c_int64))]
+                ("layer_issued_macs", C.POINTER(C.c_int64)), ("layer_kernel_id", C.POINTER(C.c_int32)),
+                ("profile", C.c_void_p)]
 
 
 _lib = None
@@ -65,6 +67,12 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.dc_status_string.restype = C.c_char_p
         vp, i32, u32, sz = C.c_void_p, C.c_int32, C.c_uint32, C.c_size_t
+        L.dc_profile_create.argtypes = [i32, C.POINTER(vp)]
+        L.dc_profile_destroy.argtypes = [vp]
+        L.dc_profile_reset.argtypes = [vp]
+        L.dc_profile_elapsed_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
+        L.dc_conv_kernel_name.argtypes = [i32, C.c_char_p, sz]
+        L.dc_conv_tile_shape.argtypes = [vp, i32, i32, i32, i32] + [C.POINTER(i32)] * 4
         L.dc_match_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
         L.dc_propagate_regions.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, vp]
         L.dc_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
@@ -284,6 +292,8 @@ class StackRunner:
         self._issued = (C.c_int64 * nl)()
         self.stats.layer_reused_px = C.cast(self._reused, C.POINTER(C.c_int64))
         self.stats.layer_issued_macs = C.cast(self._issued, C.POINTER(C.c_int64))
+        self._kid = (C.c_int32 * nl)()
+        self.stats.layer_kernel_id = C.cast(self._kid, C.POINTER(C.c_int32))
         self.regs = None
         if want_regions:
             self.regs, self._regs_store = _alloc_regions(n_streams * (nl + 1), max_rects)
@@ -315,6 +325,40 @@ class StackRunner:
         self.last_full = full
         return self.bufs[c]
 
+    def enable_profile(self, on=True):
+        """Attach (or detach) HIP-event brackets around every conv GEMM and copy launch."""
+        if on and not self.stats.profile:
+            h = C.c_void_p()
+            _check("dc_profile_create", lib().dc_profile_create(2 * len(self.layers), C.byref(h)))
+            self.stats.profile = h
+        elif not on and self.stats.profile:
+            lib().dc_profile_destroy(self.stats.profile)
+            self.stats.profile = None
+
+    def profile_ms(self):
+        """After a synchronised step: dict layer -> (gemm_ms or None, copy_ms or None)."""
+        nl = len(self.layers)
+        out = {}
+        for i, L in enumerate(self.layers):
+            if L["type"] != synth.CONV:
+                continue
+            vals = []
+            for slot in (i, nl + i):
+                ms = C.c_float()
+                rc = lib().dc_profile_elapsed_ms(self.stats.profile, slot, C.byref(ms))
+                vals.append(ms.value if rc == 0 else None)
+            out[i] = tuple(vals)
+        lib().dc_profile_reset(self.stats.profile)
+        return out
+
+    def tile_shape(self, i):
+        """(th, tw, nt, cfg) of conv layer i."""
+        h, w, _ = self.shapes[self.layers[i]["in0"]]
+        v = [C.c_int32() for _ in range(4)]
+        _check("dc_conv_tile_shape", lib().dc_conv_tile_shape(layers_to_c([self.layers[i]]), self.n, h, w, self.dtype,
+                                                            *[C.byref(x) for x in v]))
+        return tuple(x.value for x in v)
+
     def regions(self, stream=0):
         """Regions of every tensor of `stream` for the last step (needs want_regions=True)."""
         nl = len(self.layers)
@@ -322,4 +366,11 @@ class StackRunner:
 
     def layer_stats(self):
         nl = len(self.layers)
-        return dict(reused_px=[self._reused[i] for i in range(nl)], issued_macs=[self._issued[i] for i in range(nl)])
+        return dict(reused_px=[self._reused[i] for i in range(nl)], issued_macs=[self._issued[i] for i in range(nl)],
+                    kernel_id=[self._kid[i] for i in range(nl)])
+
+
+def conv_kernel_name(kernel_id):
+    buf = C.create_string_buffer(160)
+    _check("dc_conv_kernel_name", lib().dc_conv_kernel_name(int(kernel_id), buf, 160))
+    return buf.value.decode()

@@ -1,4 +1,5 @@
 // C ABI entry points: argument validation, host-side planning, kernel sequencing.
+#include <algorithm>
 #include <cstring>
 #include <new>
 
@@ -70,25 +71,44 @@ int check_conv_layer(const dc_layer* l) {
 }
 
 // Copy + conv launches of one layer given its packed plan on the device.
+struct Bracket {   // records a profile slot around a launch when a profile is attached
+    Profile* p; int slot; hipStream_t st;
+    Bracket(Profile* p_, int slot_, hipStream_t st_) : p(p_), slot(slot_), st(st_) {
+        if (p && slot >= 0 && (size_t)slot < p->used.size()) { hipEventRecord(p->ev[2 * slot], st); }
+        else p = nullptr;
+    }
+    ~Bracket() {
+        if (p) { hipEventRecord(p->ev[2 * slot + 1], st); p->used[slot] = 1; }
+    }
+};
+
 int run_conv_planned(const dc_layer& l, const void* in, const void* w, const float* bias,
                      const void* cache_prev, void* out, int n_streams, int Hin, int Win, int dtype,
-                     const ConvTiling& tiling, const LayerPlan* plan, const PlanAddr* addr, hipStream_t st) {
+                     const ConvTiling& tiling, const LayerPlan* plan, const PlanAddr* addr, hipStream_t st,
+                     Profile* prof = nullptr, int gemm_slot = -1, int copy_slot = -1, int* kernel_id = nullptr) {
     const int Hout = (Hin + 2 * l.p - l.k) / l.s + 1, Wout = (Win + 2 * l.p - l.k) / l.s + 1;
     ConvLaunch c;
+    c.kernel_id = kernel_id;
+    if (kernel_id) *kernel_id = -1;
     c.in = in; c.w = w; c.bias = bias; c.out = out;
     c.n_streams = n_streams; c.Hin = Hin; c.Win = Win; c.Cin = l.cin;
     c.Hout = Hout; c.Wout = Wout; c.Cout = l.cout; c.k = l.k; c.s = l.s; c.p = l.p; c.relu = l.relu;
     c.dtype = dtype; c.tiling = tiling;
     if (!plan) {
         c.tiles = nullptr; c.n_tiles = 0; c.rects = nullptr; c.ranges = nullptr;
+        Bracket b(prof, gemm_slot, st);
         DC_TRY_HIP(launch_conv(c, st));
         return DC_OK;
     }
     int mw = 0, mh = 0;
     for (const RectDev& r : plan->rects) { mw = r.w > mw ? r.w : mw; mh = r.h > mh ? r.h : mh; }
-    DC_TRY_HIP(launch_shifted_copy(addr->rects, (int)plan->rects.size(), mw, mh, cache_prev, out, Hout, Wout,
-                                   l.cout, dtype, st));
+    if (!plan->rects.empty()) {
+        Bracket b(prof, copy_slot, st);
+        DC_TRY_HIP(launch_shifted_copy(addr->rects, (int)plan->rects.size(), mw, mh, cache_prev, out, Hout, Wout,
+                                       l.cout, dtype, st));
+    }
     if (!plan->tiles.empty()) {
+        Bracket b(prof, gemm_slot, st);
         c.tiles = addr->tiles; c.n_tiles = (int)plan->tiles.size(); c.rects = addr->rects; c.ranges = addr->ranges;
         DC_TRY_HIP(launch_conv(c, st));
     }
@@ -111,6 +131,66 @@ const char* dc_status_string(int32_t s) {
         case DC_ERR_HIP: return "HIP runtime error";
         default: return "unknown status";
     }
+}
+
+int32_t dc_profile_create(int32_t n_slots, void** profile) {
+    if (!profile) return DC_ERR_NULL_PTR;
+    if (n_slots < 1 || n_slots > (1 << 20)) return DC_ERR_INVALID_ARG;
+    Profile* p = new (std::nothrow) Profile();
+    if (!p) return DC_ERR_WORKSPACE;
+    p->ev.resize(2 * (size_t)n_slots, nullptr);
+    p->used.assign(n_slots, 0);
+    for (size_t i = 0; i < p->ev.size(); ++i)
+        if (hipEventCreate(&p->ev[i]) != hipSuccess) {
+            for (size_t j = 0; j < i; ++j) hipEventDestroy(p->ev[j]);
+            delete p;
+            return DC_ERR_HIP;
+        }
+    *profile = p;
+    return DC_OK;
+}
+
+int32_t dc_profile_destroy(void* profile) {
+    if (!profile) return DC_ERR_NULL_PTR;
+    Profile* p = static_cast<Profile*>(profile);
+    for (hipEvent_t e : p->ev) hipEventDestroy(e);
+    delete p;
+    return DC_OK;
+}
+
+int32_t dc_profile_reset(void* profile) {
+    if (!profile) return DC_ERR_NULL_PTR;
+    Profile* p = static_cast<Profile*>(profile);
+    std::fill(p->used.begin(), p->used.end(), 0);
+    return DC_OK;
+}
+
+int32_t dc_profile_elapsed_ms(void* profile, int32_t slot, float* ms) {
+    if (!profile || !ms) return DC_ERR_NULL_PTR;
+    Profile* p = static_cast<Profile*>(profile);
+    if (slot < 0 || (size_t)slot >= p->used.size() || !p->used[slot]) return DC_ERR_INVALID_ARG;
+    DC_TRY_HIP(hipEventElapsedTime(ms, p->ev[2 * slot], p->ev[2 * slot + 1]));
+    return DC_OK;
+}
+
+int32_t dc_conv_kernel_name(int32_t kernel_id, char* buf, size_t n) {
+    if (!buf) return DC_ERR_NULL_PTR;
+    if (n < 2 || kernel_id < 0 || kernel_id >= 24) return DC_ERR_INVALID_ARG;
+    conv_kernel_name(kernel_id, buf, n);
+    return DC_OK;
+}
+
+int32_t dc_conv_tile_shape(const dc_layer* layer, int32_t n_streams, int32_t Hin, int32_t Win, int32_t dtype,
+                           int32_t* th, int32_t* tw, int32_t* nt, int32_t* cfg) {
+    if (!layer || !th || !tw || !nt || !cfg) return DC_ERR_NULL_PTR;
+    int rc = check_conv_layer(layer);
+    if (rc) return rc;
+    if (n_streams < 1 || Hin < 1 || Win < 1) return DC_ERR_INVALID_ARG;
+    if (Hin + 2 * layer->p < layer->k || Win + 2 * layer->p < layer->k) return DC_ERR_BAD_SHAPE;
+    const int Hout = (Hin + 2 * layer->p - layer->k) / layer->s + 1, Wout = (Win + 2 * layer->p - layer->k) / layer->s + 1;
+    ConvTiling t = pick_tiling(*layer, Hout, Wout, n_streams, dtype);
+    *th = t.th; *tw = t.tw; *nt = t.nt; *cfg = t.cfg;
+    return DC_OK;
 }
 
 int32_t dc_match_blocks(const uint8_t* cur, const uint8_t* prev, int32_t n_streams, int32_t H, int32_t W,
@@ -305,7 +385,12 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
 
     dc_stack_stats local;
     std::memset(&local, 0, sizeof(local));
-    if (stats) { local.layer_reused_px = stats->layer_reused_px; local.layer_issued_macs = stats->layer_issued_macs; }
+    if (stats) {
+        local.layer_reused_px = stats->layer_reused_px;
+        local.layer_issued_macs = stats->layer_issued_macs;
+        local.profile = stats->profile;
+        local.layer_kernel_id = stats->layer_kernel_id;
+    }
     local.full = cached ? 0 : 1;
     local.n_blocks = (int32_t)nb;
 
@@ -410,7 +495,9 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             case DC_CONV:
                 rc = run_conv_planned(l, tensors_cur[a], weights[i], bias ? bias[i] : nullptr,
                                       cached ? tensors_prev[t] : nullptr, tensors_cur[t], n_streams, hs[a], ws[a], dtype,
-                                      tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st);
+                                      tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st,
+                                      stats ? static_cast<Profile*>(stats->profile) : nullptr, i, n_layers + i,
+                                      local.layer_kernel_id ? &local.layer_kernel_id[i] : nullptr);
                 if (rc) return rc;
                 break;
             case DC_MAXPOOL:

@@ -16,7 +16,7 @@ struct RectDev {
     int32_t x, y, w, h;
     int32_t stream, dx, dy, pad;
 };
-// One output tile that holds at least one non-reusable pixel.
+// One output tile (ty, tx in tile units) that holds at least one non-reusable pixel.
 struct TileDev {
     int32_t stream, ty, tx;
     int32_t mixed;  // 1: some pixels of the tile are reusable (per-pixel test needed)
@@ -67,7 +67,9 @@ struct ConvLaunch {
     int n_tiles;           // ignored when tiles == nullptr
     const RectDev* rects;  // device
     const RangeDev* ranges;
+    int* kernel_id = nullptr;  // out (host): which instantiation ran
 };
+void conv_kernel_name(int id, char* buf, size_t n);
 hipError_t launch_conv(const ConvLaunch& c, hipStream_t st);
 
 hipError_t launch_shifted_copy(const RectDev* rects_dev, int n_rects, int max_rect_w, int max_rect_h,
@@ -81,6 +83,12 @@ hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int
                           int s, int p, int dtype, hipStream_t st);
 hipError_t launch_add(const void* a, const void* b, void* out, size_t n, int relu, int dtype,
                       hipStream_t st);
+
+// Event pairs for kernel timing (measurement aid).
+struct Profile {
+    std::vector<hipEvent_t> ev;   // 2 per slot: start, stop
+    std::vector<uint8_t> used;
+};
 
 inline size_t dtype_size(int dtype) { return dtype == DC_BF16 ? 2 : 4; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
