@@ -74,11 +74,11 @@ int check_conv_layer(const dc_layer* l) {
 struct Bracket {   // records a profile slot around a launch when a profile is attached
     Profile* p; int slot; hipStream_t st;
     Bracket(Profile* p_, int slot_, hipStream_t st_) : p(p_), slot(slot_), st(st_) {
-        if (p && slot >= 0 && (size_t)slot < p->used.size()) { hipEventRecord(p->ev[2 * slot], st); }
+        if (p && slot >= 0 && (size_t)slot < p->used.size()) { (void)hipEventRecord(p->ev[2 * slot], st); }
         else p = nullptr;
     }
     ~Bracket() {
-        if (p) { hipEventRecord(p->ev[2 * slot + 1], st); p->used[slot] = 1; }
+        if (p) { (void)hipEventRecord(p->ev[2 * slot + 1], st); p->used[slot] = 1; }
     }
 };
 
@@ -142,7 +142,7 @@ int32_t dc_profile_create(int32_t n_slots, void** profile) {
     p->used.assign(n_slots, 0);
     for (size_t i = 0; i < p->ev.size(); ++i)
         if (hipEventCreate(&p->ev[i]) != hipSuccess) {
-            for (size_t j = 0; j < i; ++j) hipEventDestroy(p->ev[j]);
+            for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(p->ev[j]);
             delete p;
             return DC_ERR_HIP;
         }
@@ -153,7 +153,7 @@ int32_t dc_profile_create(int32_t n_slots, void** profile) {
 int32_t dc_profile_destroy(void* profile) {
     if (!profile) return DC_ERR_NULL_PTR;
     Profile* p = static_cast<Profile*>(profile);
-    for (hipEvent_t e : p->ev) hipEventDestroy(e);
+    for (hipEvent_t e : p->ev) (void)hipEventDestroy(e);
     delete p;
     return DC_OK;
 }
