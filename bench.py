@@ -115,7 +115,7 @@ def main():
             if c_ms is not None:
                 copy_ms += c_ms
                 copy_launches += 1
-                copy_bytes += 2.0 * reused * co * (2 if args.dtype == "bf16" else 4)
+        copy_bytes += st.copy_bytes
 
     run_steps(args.steps, args.warmup + args.steps, collect)
     runner.enable_profile(False)

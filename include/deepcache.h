@@ -53,7 +53,10 @@ enum { DC_CONV = 0, DC_MAXPOOL = 1, DC_RELU = 2, DC_ADD = 3 };
 typedef struct { int32_t x, y, w, h; } dc_rect;
 
 /* One layer of the stack.  Tensor 0 is the network input (the frame mapped to
- * (u8-128)/128); tensor i+1 is the output of layer i.  in0 (and in1 for DC_ADD)
+ * (u8-128)/128; it has the cin of the layers that read it, which may exceed the frame's
+ * channel count: the extra channels are zero, so that a 3-channel frame can feed a first
+ * layer whose weights are laid out with a 16-byte channel run); tensor i+1 is the output
+ * of layer i.  in0 (and in1 for DC_ADD)
  * name producer tensors, so the table describes a DAG in topological order. */
 typedef struct {
     int32_t type;          /* DC_CONV, DC_MAXPOOL, DC_RELU, DC_ADD */
@@ -87,7 +90,8 @@ typedef struct {
     int64_t* layer_issued_macs; /* optional host [n_layers] */
     int32_t* layer_kernel_id;   /* optional host [n_layers]: which GEMM instantiation ran (-1: none) */
     void* profile;              /* optional dc_profile handle with >= 2*n_layers slots: slot i brackets
-                                   the GEMM kernel of conv layer i, slot n_layers+i its shifted copy */
+                                   the GEMM kernel of conv layer i, slot n_layers+i its shifted copy; when the copies
+                                   of all layers run as one launch, slot n_layers brackets that launch */
 } dc_stack_stats;
 
 const char* dc_status_string(int32_t status);
@@ -185,8 +189,9 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
                              void* ws_host, size_t ws_host_bytes, void* stream);
 
 /* Un-cached layers (Section 5: only convolutions use the cache), whole map every frame. */
-int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n_samples, int32_t dtype,
-                           void* stream);
+/* out[pixel][c] = (frames[pixel][c] - 128) / 128 for c < c_frame, 0 for c_frame <= c < c_tensor. */
+int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n_pixels, int32_t c_frame,
+                           int32_t c_tensor, int32_t dtype, void* stream);
 int32_t dc_maxpool_layer(const void* in, void* out, int32_t n_streams, int32_t Hin, int32_t Win,
                          int32_t C, int32_t k, int32_t s, int32_t p, int32_t dtype, void* stream);
 int32_t dc_add_layer(const void* a, const void* b, void* out, size_t n, int32_t relu,

@@ -77,7 +77,7 @@ def lib():
         L.dc_propagate_regions.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, vp]
         L.dc_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
         L.dc_cached_conv_layer.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp, sz, vp, sz, vp]
-        L.dc_frame_to_tensor.argtypes = [vp, vp, sz, i32, vp]
+        L.dc_frame_to_tensor.argtypes = [vp, vp, sz, i32, i32, i32, vp]
         L.dc_maxpool_layer.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
         L.dc_add_layer.argtypes = [vp, vp, vp, sz, i32, i32, vp]
         L.dc_stack_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
@@ -220,10 +220,34 @@ def dc_cached_conv_layer(layer, x, weights, bias, cache_prev=None, regions=None,
     return out
 
 
-def dc_frame_to_tensor(frames, dtype=DC_F32):
-    out = torch.empty(frames.shape, dtype=torch_dtype(dtype), device=frames.device)
-    _check("dc_frame_to_tensor", lib().dc_frame_to_tensor(_ptr(frames), _ptr(out), frames.numel(), dtype, _stream()))
+def dc_frame_to_tensor(frames, dtype=DC_F32, c_tensor=None):
+    cf = frames.shape[-1]
+    ct = cf if c_tensor is None else int(c_tensor)
+    out = torch.empty(tuple(frames.shape[:-1]) + (ct,), dtype=torch_dtype(dtype), device=frames.device)
+    _check("dc_frame_to_tensor", lib().dc_frame_to_tensor(_ptr(frames), _ptr(out), frames.numel() // cf, cf, ct, dtype,
+                                                          _stream()))
     return out
+
+
+def pad_input_channels(layers, weights, Ch, dtype):
+    """Give the layers that read tensor 0 a channel run of whole 16-byte vectors: cin is rounded up
+    and their weights get zero input channels (the library zero-fills the extra channels of tensor 0).
+    Returns (layers, weights, padded channel count)."""
+    ve = 8 if dtype == DC_BF16 else 4
+    cp = (Ch + ve - 1) // ve * ve
+    if cp == Ch:
+        return layers, weights, Ch
+    layers = [dict(L) for L in layers]
+    weights = list(weights)
+    for i, L in enumerate(layers):
+        if L["in0"] == 0 and L["type"] == synth.CONV:
+            w = np.zeros(weights[i].shape[:3] + (cp,), np.float32)
+            w[..., :Ch] = weights[i]
+            weights[i] = w
+            L["cin"] = cp
+        elif L["in0"] == 0 or L["in1"] == 0:
+            return [dict(L) for L in layers], weights, Ch   # a non-conv layer reads the input: leave it alone
+    return layers, weights, cp
 
 
 def dc_maxpool_layer(x, k, s, p):
@@ -248,7 +272,10 @@ class StackRunner:
 
     def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
-                 want_regions=False):
+                 want_regions=False, pad_input=True):
+        self.Ch_tensor = Ch
+        if pad_input:
+            layers, weights, self.Ch_tensor = pad_input_channels(layers, weights, Ch, dtype)
         self.layers, self.n, self.H, self.W, self.Ch = layers, n_streams, H, W, Ch
         self.block, self.radius, self.dtype, self.expiry = block, radius, dtype, expiry
         self.max_block_ssd = int(max_block_ssd if max_block_ssd is not None else synth.max_block_ssd(block, Ch))
@@ -261,7 +288,7 @@ class StackRunner:
         self.b = [None if b is None else torch.from_numpy(b).to(self.device).float().contiguous() for b in biases]
         self._wp = (C.c_void_p * nl)(*[None if w is None else w.data_ptr() for w in self.w])
         self._bp = (C.c_void_p * nl)(*[None if b is None else b.data_ptr() for b in self.b])
-        self.shapes = synth.tensor_shapes(layers, H, W, Ch)
+        self.shapes = synth.tensor_shapes(layers, H, W, self.Ch_tensor)
         # conv outputs are cache values: two copies (previous / current frame); the rest is shared
         is_conv = [False] + [L["type"] == synth.CONV for L in layers]
         self.bufs = [[], []]

@@ -64,6 +64,19 @@ PlanAddr pack_plan(const LayerPlan& plan, unsigned char* host, unsigned char* de
     return a;
 }
 
+// Channel count of tensor 0: the cin of the layers that read it (they must agree); it may exceed the
+// frame's channel count, the extra channels are zero.
+int input_channels(const dc_layer* L, int n_layers, int c_frame) {
+    int c = -1;
+    for (int i = 0; i < n_layers; ++i) {
+        if (L[i].in0 == 0 || (L[i].type == DC_ADD && L[i].in1 == 0)) {
+            if (c >= 0 && L[i].cin != c) return -1;
+            c = L[i].cin;
+        }
+    }
+    return c < 0 ? c_frame : c;
+}
+
 int check_conv_layer(const dc_layer* l) {
     if (l->type != DC_CONV) return DC_ERR_INVALID_ARG;
     if (l->k < 1 || l->s < 1 || l->p < 0 || l->p >= l->k || l->cin < 1 || l->cout < 1) return DC_ERR_INVALID_ARG;
@@ -85,7 +98,8 @@ struct Bracket {   // records a profile slot around a launch when a profile is a
 int run_conv_planned(const dc_layer& l, const void* in, const void* w, const float* bias,
                      const void* cache_prev, void* out, int n_streams, int Hin, int Win, int dtype,
                      const ConvTiling& tiling, const LayerPlan* plan, const PlanAddr* addr, hipStream_t st,
-                     Profile* prof = nullptr, int gemm_slot = -1, int copy_slot = -1, int* kernel_id = nullptr) {
+                     Profile* prof = nullptr, int gemm_slot = -1, int copy_slot = -1, int* kernel_id = nullptr,
+                     bool copy_done = false) {
     const int Hout = (Hin + 2 * l.p - l.k) / l.s + 1, Wout = (Win + 2 * l.p - l.k) / l.s + 1;
     ConvLaunch c;
     c.kernel_id = kernel_id;
@@ -102,7 +116,7 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
     }
     int mw = 0, mh = 0;
     for (const RectDev& r : plan->rects) { mw = r.w > mw ? r.w : mw; mh = r.h > mh ? r.h : mh; }
-    if (!plan->rects.empty()) {
+    if (!plan->rects.empty() && !copy_done) {
         Bracket b(prof, copy_slot, st);
         DC_TRY_HIP(launch_shifted_copy(addr->rects, (int)plan->rects.size(), mw, mh, cache_prev, out, Hout, Wout,
                                        l.cout, dtype, st));
@@ -300,10 +314,12 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
                             &addr, st);
 }
 
-int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n, int32_t dtype, void* stream) {
+int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n_pixels, int32_t c_frame, int32_t c_tensor,
+                           int32_t dtype, void* stream) {
     if (!frames || !out) return DC_ERR_NULL_PTR;
     if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
-    DC_TRY_HIP(launch_frame_to_tensor(frames, out, n, dtype, as_stream(stream)));
+    if (c_frame < 1 || c_tensor < c_frame) return DC_ERR_INVALID_ARG;
+    DC_TRY_HIP(launch_frame_to_tensor(frames, out, n_pixels, c_frame, c_tensor, dtype, as_stream(stream)));
     return DC_OK;
 }
 
@@ -329,7 +345,9 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
     if (!layers || !dev_bytes || !host_bytes) return DC_ERR_NULL_PTR;
     if (n_layers < 1 || n_streams < 1 || block < 1 || max_rects < 1) return DC_ERR_INVALID_ARG;
     std::vector<int> hs, ws, cs;
-    int rc = validate_layers(layers, n_layers, H, W, C, &hs, &ws, &cs);
+    const int c_tensor = input_channels(layers, n_layers, C);
+    if (c_tensor < C) return DC_ERR_BAD_SHAPE;
+    int rc = validate_layers(layers, n_layers, H, W, c_tensor, &hs, &ws, &cs);
     if (rc) return rc;
     size_t total = 0;
     for (int i = 0; i < n_layers; ++i) {
@@ -341,7 +359,9 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
             worst = b > worst ? b : worst;
         }
         total += worst;
+        total += align_up((size_t)n_streams * max_rects * sizeof(RectDev), 256);   // all-layers copy table
     }
+    total += align_up((size_t)n_layers * sizeof(CopyLayerDev), 256);
     const size_t nb = (size_t)n_streams * (H / block) * (W / block);
     size_t match_host = align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
     *dev_bytes = total;
@@ -360,7 +380,9 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
     if (n_layers < 1 || n_streams < 1 || n_streams > 65535 || block < 1 || radius < 0 || max_rects < 1) return DC_ERR_INVALID_ARG;
     std::vector<int> hs, ws, cs;
-    int rc = validate_layers(layers, n_layers, H, W, C, &hs, &ws, &cs);
+    const int c_tensor = input_channels(layers, n_layers, C);
+    if (c_tensor < C) return DC_ERR_BAD_SHAPE;
+    int rc = validate_layers(layers, n_layers, H, W, c_tensor, &hs, &ws, &cs);
     if (rc) return rc;
     for (int t = 0; t <= n_layers; ++t)
         if (!tensors_cur[t]) return DC_ERR_NULL_PTR;
@@ -401,7 +423,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                              global_mv, n_pass, block_mask, stream);
         if (rc) return rc;
         // the network input does not depend on the match: overlap its conversion with the readback
-        DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W * C, dtype, st));
+        DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
         uint8_t* h_mask = hbase;
         int32_t* h_gmv = reinterpret_cast<int32_t*>(hbase + align_up(nb, 256));
         DC_TRY_HIP(hipMemcpyAsync(h_mask, block_mask, nb, hipMemcpyDeviceToHost, st));
@@ -424,7 +446,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         }
         hbase += align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
     } else {
-        DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W * C, dtype, st));
+        DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
     }
     if (regions_out) {
         int status = DC_OK;
@@ -485,7 +507,48 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     } catch (const std::bad_alloc&) {
         return DC_ERR_WORKSPACE;
     }
+    // ---- the shifted copies of all layers in one launch (16-byte vector path only) ----
+    std::vector<char> copy_fused(n_layers, 0);
+    size_t all_rects_off = 0, copy_layers_off = 0, n_all_rects = 0, max_vec = 0;
+    if (cached) {
+        try {
+            std::vector<RectDev> all_rects;
+            std::vector<CopyLayerDev> copy_layers;
+            for (int i = 0; i < n_layers; ++i) {
+                if (layers[i].type != DC_CONV || plans[i].rects.empty()) continue;
+                const size_t px_bytes = (size_t)layers[i].cout * dtype_size(dtype);
+                if (px_bytes % 16 || reinterpret_cast<uintptr_t>(tensors_prev[i + 1]) % 16 ||
+                    reinterpret_cast<uintptr_t>(tensors_cur[i + 1]) % 16)
+                    continue;
+                copy_fused[i] = 1;
+                const int pv = (int)(px_bytes / 16);
+                for (RectDev r : plans[i].rects) {
+                    r.pad = (int)copy_layers.size();
+                    all_rects.push_back(r);
+                    max_vec = std::max(max_vec, (size_t)r.w * r.h * pv);
+                }
+                copy_layers.push_back(CopyLayerDev{tensors_prev[i + 1], tensors_cur[i + 1], hs[i + 1], ws[i + 1], pv, 0});
+            }
+            n_all_rects = all_rects.size();
+            if (n_all_rects) {
+                all_rects_off = off;
+                std::memcpy(hbase + off, all_rects.data(), n_all_rects * sizeof(RectDev));
+                off += align_up(n_all_rects * sizeof(RectDev), 256);
+                copy_layers_off = off;
+                std::memcpy(hbase + off, copy_layers.data(), copy_layers.size() * sizeof(CopyLayerDev));
+                off += align_up(copy_layers.size() * sizeof(CopyLayerDev), 256);
+            }
+        } catch (const std::bad_alloc&) {
+            return DC_ERR_WORKSPACE;
+        }
+    }
     if (cached && off) DC_TRY_HIP(hipMemcpyAsync(ws_dev, hbase, off, hipMemcpyHostToDevice, st));
+    if (n_all_rects) {
+        unsigned char* d = static_cast<unsigned char*>(ws_dev);
+        Bracket b(stats ? static_cast<Profile*>(stats->profile) : nullptr, n_layers, st);   // first copy slot
+        DC_TRY_HIP(launch_shifted_copy_all(reinterpret_cast<const RectDev*>(d + all_rects_off), (int)n_all_rects,
+                                           reinterpret_cast<const CopyLayerDev*>(d + copy_layers_off), max_vec, st));
+    }
 
     // ---- layers ----
     for (int i = 0; i < n_layers; ++i) {
@@ -497,7 +560,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                                       cached ? tensors_prev[t] : nullptr, tensors_cur[t], n_streams, hs[a], ws[a], dtype,
                                       tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st,
                                       stats ? static_cast<Profile*>(stats->profile) : nullptr, i, n_layers + i,
-                                      local.layer_kernel_id ? &local.layer_kernel_id[i] : nullptr);
+                                      local.layer_kernel_id ? &local.layer_kernel_id[i] : nullptr, copy_fused[i] != 0);
                 if (rc) return rc;
                 break;
             case DC_MAXPOOL:

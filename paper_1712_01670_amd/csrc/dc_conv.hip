@@ -715,9 +715,16 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     // shape by the amount of work: largest tile that still fills the chip
     int shape;
     {
+        static int t0 = -1, t1 = -1;
+        if (t0 < 0) {
+            const char* e0 = getenv("DC_CONV_T0");
+            const char* e1 = getenv("DC_CONV_T1");
+            t0 = e0 ? atoi(e0) : 160;
+            t1 = e1 ? atoi(e1) : 160;
+        }
         const long r64 = (c.Cout + 63) / 64, r32 = (c.Cout + 31) / 32;
-        if (c.Cout > 32 && ((n_units + 3) / 4) * r64 >= 384) shape = 0;
-        else if (((n_units + 1) / 2) * r32 >= 256) shape = 1;
+        if (c.Cout > 32 && ((n_units + 3) / 4) * r64 >= t0) shape = 0;
+        else if (((n_units + 1) / 2) * r32 >= t1) shape = 1;
         else shape = 2;
     }
     const int ph = 3 * c.s + c.k, pw = ph;

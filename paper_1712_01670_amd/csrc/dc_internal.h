@@ -75,10 +75,19 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st);
 hipError_t launch_shifted_copy(const RectDev* rects_dev, int n_rects, int max_rect_w, int max_rect_h,
                                const void* prev, void* out, int Hout, int Wout, int Cout,
                                int dtype, hipStream_t st);
+// Per-layer operands of the all-layers copy; RectDev::pad indexes this table.
+struct CopyLayerDev {
+    const void* prev;
+    void* out;
+    int32_t Hout, Wout, pv, pad;   // pv: 16-byte vectors per pixel
+};
+hipError_t launch_shifted_copy_all(const RectDev* rects_dev, int n_rects, const CopyLayerDev* layers_dev,
+                                   size_t max_vec_per_rect, hipStream_t st);
 hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, int H, int W, int C,
                         int B, int R, uint32_t max_ssd, int16_t* mv, uint32_t* best_ssd,
                         int32_t* gmv, int32_t* n_pass, uint8_t* mask, hipStream_t st);
-hipError_t launch_frame_to_tensor(const uint8_t* f, void* out, size_t n, int dtype, hipStream_t st);
+hipError_t launch_frame_to_tensor(const uint8_t* f, void* out, size_t n_pixels, int cf, int ct, int dtype,
+                                  hipStream_t st);
 hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k,
                           int s, int p, int dtype, hipStream_t st);
 hipError_t launch_add(const void* a, const void* b, void* out, size_t n, int relu, int dtype,

@@ -31,6 +31,25 @@ __global__ __launch_bounds__(kThreads) void shifted_copy_kernel(const RectDev* _
     }
 }
 
+// The same for the rectangles of every conv layer of a frame in one launch: the copies only depend
+// on the previous frame's maps, so they can all run before the first layer.
+__global__ __launch_bounds__(kThreads) void shifted_copy_all_kernel(const RectDev* __restrict__ rects,
+                                                                    const CopyLayerDev* __restrict__ layers) {
+    const RectDev r = rects[blockIdx.y];
+    const CopyLayerDev L = layers[r.pad];
+    const uint4* __restrict__ prev = static_cast<const uint4*>(L.prev);
+    uint4* __restrict__ out = static_cast<uint4*>(L.out);
+    const int row_v = r.w * L.pv;
+    const int total = r.h * row_v;
+    const size_t map = (size_t)r.stream * L.Hout * L.Wout;
+    for (int i = blockIdx.x * kThreads + threadIdx.x; i < total; i += gridDim.x * kThreads) {
+        int row = i / row_v, col = i - row * row_v;
+        size_t dst = (map + (size_t)(r.y + row) * L.Wout + r.x) * L.pv + col;
+        size_t src = (map + (size_t)(r.y + r.dy + row) * L.Wout + (r.x + r.dx)) * L.pv + col;
+        out[dst] = prev[src];
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ T from_float(float v);
 template <>
@@ -40,12 +59,17 @@ __device__ __forceinline__ __hip_bfloat16 from_float<__hip_bfloat16>(float v) { 
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(__hip_bfloat16 v) { return __bfloat162float(v); }
 
+// out[pixel][c] = (frame[pixel][c] - 128) / 128 for c < cf, 0 for the padding channels cf <= c < ct
 template <typename T>
 __global__ __launch_bounds__(kThreads) void frame_to_tensor_kernel(const uint8_t* __restrict__ f,
-                                                                   T* __restrict__ out, size_t n) {
+                                                                   T* __restrict__ out, size_t n_out, int cf, int ct) {
     size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * kThreads;
-    for (; i < n; i += stride) out[i] = from_float<T>((float)((int)f[i] - 128) * (1.0f / 128.0f));
+    for (; i < n_out; i += stride) {
+        const size_t px = i / ct;
+        const int c = (int)(i - px * ct);
+        out[i] = from_float<T>(c < cf ? (float)((int)f[px * cf + c] - 128) * (1.0f / 128.0f) : 0.f);
+    }
 }
 
 // One thread per (output pixel, channel); consecutive threads walk the channels.
@@ -129,14 +153,28 @@ hipError_t launch_shifted_copy(const RectDev* rects_dev, int n_rects, int max_re
     return hipSuccess;
 }
 
-hipError_t launch_frame_to_tensor(const uint8_t* f, void* out, size_t n, int dtype, hipStream_t st) {
+hipError_t launch_shifted_copy_all(const RectDev* rects_dev, int n_rects, const CopyLayerDev* layers_dev,
+                                   size_t max_vec_per_rect, hipStream_t st) {
+    for (int r0 = 0; r0 < n_rects; r0 += 65535) {
+        const int nr = n_rects - r0 < 65535 ? n_rects - r0 : 65535;
+        dim3 grid(grid_for((max_vec_per_rect + 3) / 4, 1024), nr);
+        hipLaunchKernelGGL(shifted_copy_all_kernel, grid, dim3(kThreads), 0, st, rects_dev + r0, layers_dev);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_frame_to_tensor(const uint8_t* f, void* out, size_t n_pixels, int cf, int ct, int dtype,
+                                  hipStream_t st) {
+    const size_t n = n_pixels * ct;
     if (n == 0) return hipSuccess;
     if (dtype == DC_BF16)
         hipLaunchKernelGGL(frame_to_tensor_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st, f,
-                           (__hip_bfloat16*)out, n);
+                           (__hip_bfloat16*)out, n, cf, ct);
     else
         hipLaunchKernelGGL(frame_to_tensor_kernel<float>, dim3(grid_for(n)), dim3(kThreads), 0, st, f,
-                           (float*)out, n);
+                           (float*)out, n, cf, ct);
     return hipGetLastError();
 }
 

@@ -14,7 +14,7 @@ namespace dc {
 
 namespace {
 
-constexpr int kSearchThreads = 256;
+constexpr int kSearchThreads = 512;
 
 __device__ __forceinline__ uint32_t udot4(uint32_t a, uint32_t b, uint32_t c) {
     return __builtin_amdgcn_udot4(a, b, c, false);
@@ -34,7 +34,9 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 //         [a0, a0+ws) of frame row y0-R+r, a0 = 4-byte-aligned start at or below the
 //         window's first byte; bytes outside the frame are zero
 //   blk : B rows of `cs` bytes (cs = B*C rounded up to 4), zero padded
-template <bool ALIGNED>
+// CDW > 0: the block row is CDW dwords (compile-time, inner loop fully unrolled so that the LDS reads of a
+// row are issued together); CDW == 0: any row length.
+template <bool ALIGNED, int CDW>
 __global__ __launch_bounds__(kSearchThreads) void match_search_kernel(
     const uint8_t* __restrict__ cur, const uint8_t* __restrict__ prev, int H, int W, int C, int B,
     int R, int gw, int gh, int ws, int cs, int16_t* __restrict__ mv, uint32_t* __restrict__ best_ssd) {
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(kSearchThreads) void match_search_kernel(
         reinterpret_cast<uint32_t*>(win)[i] = v;
     }
     // ---- stage the current block, zero padded to whole dwords ----
-    const int cdw = cs / 4;
+    const int cdw = CDW > 0 ? CDW : cs / 4;
     const int blk_bytes = B * C;
     for (int i = tid; i < B * cdw; i += kSearchThreads) {
         int r = i / cdw, j = i - r * cdw;
@@ -113,15 +115,30 @@ __global__ __launch_bounds__(kSearchThreads) void match_search_kernel(
         for (int r = 0; r < B; ++r) {
             const uint32_t* wrow = reinterpret_cast<const uint32_t*>(win + (size_t)(r + dy + R) * ws) + (boff >> 2);
             const uint32_t* arow = reinterpret_cast<const uint32_t*>(blk + (size_t)r * cs);
-            uint32_t lo = wrow[0];
-            for (int j = 0; j < cdw; ++j) {
-                uint32_t hi = wrow[j + 1];
-                uint32_t b = __builtin_amdgcn_alignbyte(hi, lo, sh);
-                if (j == cdw - 1) b &= tail_mask;
-                uint32_t a = arow[j];
-                sab = udot4(a, b, sab);
-                sbb = udot4(b, b, sbb);
-                lo = hi;
+            if (CDW > 0) {
+                uint32_t wv[CDW + 1], av[CDW > 0 ? CDW : 1];
+#pragma unroll
+                for (int j = 0; j <= CDW; ++j) wv[j] = wrow[j];
+#pragma unroll
+                for (int j = 0; j < CDW; ++j) av[j] = arow[j];
+#pragma unroll
+                for (int j = 0; j < CDW; ++j) {
+                    uint32_t b = __builtin_amdgcn_alignbyte(wv[j + 1], wv[j], sh);
+                    if (j == CDW - 1) b &= tail_mask;
+                    sab = udot4(av[j], b, sab);
+                    sbb = udot4(b, b, sbb);
+                }
+            } else {
+                uint32_t lo = wrow[0];
+                for (int j = 0; j < cdw; ++j) {
+                    uint32_t hi = wrow[j + 1];
+                    uint32_t b = __builtin_amdgcn_alignbyte(hi, lo, sh);
+                    if (j == cdw - 1) b &= tail_mask;
+                    uint32_t a = arow[j];
+                    sab = udot4(a, b, sab);
+                    sbb = udot4(b, b, sbb);
+                    lo = hi;
+                }
             }
         }
         uint32_t ssd = saa + sbb - 2u * sab;
@@ -219,12 +236,23 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
     const size_t lds = (size_t)rows * ws + (size_t)B * cs;
     const bool aligned = ((reinterpret_cast<uintptr_t>(prev) & 3) == 0) && ((W * C) % 4 == 0);
     dim3 grid(gh * gw, n_streams);
-    if (aligned)
-        hipLaunchKernelGGL(match_search_kernel<true>, grid, dim3(kSearchThreads), lds, st, cur, prev, H,
-                           W, C, B, R, gw, gh, ws, cs, mv, best_ssd);
-    else
-        hipLaunchKernelGGL(match_search_kernel<false>, grid, dim3(kSearchThreads), lds, st, cur, prev, H,
-                           W, C, B, R, gw, gh, ws, cs, mv, best_ssd);
+#define DC_MATCH_LAUNCH(AL, CD)                                                                                      \
+    hipLaunchKernelGGL((match_search_kernel<AL, CD>), grid, dim3(kSearchThreads), lds, st, cur, prev, H, W, C, B, R, \
+                       gw, gh, ws, cs, mv, best_ssd)
+#define DC_MATCH_ALIGN(CD)             \
+    do {                               \
+        if (aligned) DC_MATCH_LAUNCH(true, CD); \
+        else DC_MATCH_LAUNCH(false, CD);        \
+    } while (0)
+    switch (cs / 4) {
+        case 6: DC_MATCH_ALIGN(6); break;     // 8x8x3
+        case 8: DC_MATCH_ALIGN(8); break;     // 10x10x3, 8x8x4
+        case 12: DC_MATCH_ALIGN(12); break;   // 16x16x3
+        case 16: DC_MATCH_ALIGN(16); break;   // 16x16x4
+        default: DC_MATCH_ALIGN(0); break;
+    }
+#undef DC_MATCH_ALIGN
+#undef DC_MATCH_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(motion_retest_kernel, grid, dim3(64), 0, st, cur, prev, H, W, C, B, gw, gh,

@@ -121,3 +121,5 @@ def test_uncached_layers(oracle, bf16):
     dt = binding.DC_BF16 if bf16 else binding.DC_F32
     got = _to_np(binding.dc_frame_to_tensor(torch.from_numpy(f).to(DEV), dt))
     assert np.array_equal(got, oracle.frame_to_tensor(f))
+    got = _to_np(binding.dc_frame_to_tensor(torch.from_numpy(f).to(DEV), dt, c_tensor=8))
+    assert np.array_equal(got[..., :3], oracle.frame_to_tensor(f)) and not got[..., 3:].any()

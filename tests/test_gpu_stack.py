@@ -55,7 +55,11 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
                     assert list(regs[ti]["dxy"]) == want["dxy"][ti].tolist()
                 reuse.append(float(m["mask"].mean()))
             for ti in (check_tensors or range(len(layers) + 1)):
-                e = _rel_err(got[ti][s], want["tensors"][ti])
+                g = got[ti][s]
+                if ti == 0:          # tensor 0 may carry zero padding channels
+                    assert not g[..., C:].any()
+                    g = g[..., :C]
+                e = _rel_err(g, want["tensors"][ti])
                 worst = max(worst, e)
                 assert e <= tol, (t, s, ti, e)
     print(f"[stack] worst rel err {worst:.3e}, mean block reuse {np.mean(reuse) if reuse else 0:.3f}", flush=True)
