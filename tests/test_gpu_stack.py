@@ -121,3 +121,97 @@ def test_darknet_head_small(oracle):
     layers = synth.darknet19()[:12]
     v = synth.reuse_sweep_video(4001, 0.75, n_frames=3, H=128, W=128, cut_at=2)[None]
     _run_both(oracle, layers, v, 16, 16, True, bias_scale=0.0, resets=(2,))
+
+
+# ---- full-size configurations -------------------------------------------------------------------
+
+def _sampled_conv_check(oracle, layers, ws, bs, tensors, li, stream, bf16, n_samples, rng, tol):
+    """Recompute sampled output pixels of conv layer li from the GPU's own input tensor with the oracle's
+    direct loop (valid for pixels that were computed, i.e. on a full frame)."""
+    L = layers[li]
+    x = tensors[L["in0"]][stream].float().cpu().numpy()
+    y = tensors[li + 1][stream].float().cpu().numpy()
+    w = oracle.round_bf16(ws[li]) if bf16 else ws[li]
+    if w.shape[-1] < x.shape[-1]:     # input channels padded by the runner
+        wp = np.zeros(w.shape[:3] + (x.shape[-1],), np.float32)
+        wp[..., :w.shape[-1]] = w
+        w = wp
+    k, s, p = L["k"], L["s"], L["p"]
+    Ho, Wo, _ = y.shape
+    scale = float(np.abs(y).max()) + 1e-30
+    for _ in range(n_samples):
+        oy, ox = int(rng.integers(0, Ho)), int(rng.integers(0, Wo))
+        # window of the input around the sampled pixel, zero padded
+        win = np.zeros((k, k, x.shape[-1]), np.float32)
+        for ky in range(k):
+            for kx in range(k):
+                iy, ix = oy * s - p + ky, ox * s - p + kx
+                if 0 <= iy < x.shape[0] and 0 <= ix < x.shape[1]:
+                    win[ky, kx] = x[iy, ix]
+        want = oracle.conv_cached(win, w, bs[li], k, 1, 0, L["relu"], bf16=bf16)[0, 0]
+        assert np.abs(y[oy, ox] - want).max() / scale <= tol, (li, oy, ox)
+
+
+def test_resnet50_trunk_224_bf16_full_size(oracle):
+    """configs[2] at full size: two frames through the GPU path; frame 0 against the oracle's whole stack
+    (full compute), frame 1 (cached) for rectangles bit-exact and features within tolerance."""
+    layers = synth.resnet50_trunk()
+    video = synth.panning_video(2000, n_frames=2)[None]
+    _run_both(oracle, layers, video, 16, 16, True, bias_scale=0.0, residual_scale=0.5)
+
+
+def test_darknet19_416_bf16_sampled(oracle):
+    """configs[3] geometry at full size (416x416, 19 conv layers, bf16): match results and all rectangles
+    bit-exact on a cached frame; conv outputs checked on sampled pixels of the full frame."""
+    layers = synth.darknet19()
+    ws, bs = synth.he_weights(layers, 1)
+    video = synth.reuse_sweep_video(4002, 0.5, n_frames=2)
+    r = binding.StackRunner(layers, ws, bs, 1, 416, 416, 3, block=16, radius=16, dtype=binding.DC_BF16, want_regions=True)
+    dv = torch.from_numpy(video[:, None]).to(DEV)
+    t0 = r.step(dv[0])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    for li, L in enumerate(layers):
+        if L["type"] == synth.CONV:
+            _sampled_conv_check(oracle, layers, ws, bs, t0, li, 0, True, 6, rng, 2e-2)
+    r.step(dv[1])
+    torch.cuda.synchronize()
+    m = oracle.match_blocks(video[1], video[0], 16, 16, synth.max_block_ssd(16))
+    assert np.array_equal(r.mask[0].cpu().numpy(), m["mask"]) and r.gmv[0].cpu().numpy().tolist() == m["gmv"].tolist()
+    want = oracle.propagate(layers, 416, 416, oracle.merge_blocks(m["mask"], 16), int(m["gmv"][0]), int(m["gmv"][1]))
+    for t, g in enumerate(r.regions(0)):
+        assert g["rects"].tolist() == want["rects"][t].tolist(), t
+    assert 0.3 < m["mask"].mean() < 0.7
+
+
+def test_throughput_mode_64_streams_bf16_sampled(oracle):
+    """configs[4] launch configuration: 64 streams in one batch, VGG-16-style, bf16.  Three streams are
+    followed by the oracle over three time steps (everything compared); the others are checked for
+    bit-exact match results on the cached steps."""
+    layers = synth.vgg16()
+    n, T = 64, 3
+    videos = np.stack([synth.panning_video(5000 + s, n_frames=T) for s in range(n)])
+    ws, bs = synth.he_weights(layers, 1)
+    r = binding.StackRunner(layers, ws, bs, n, 224, 224, 3, block=16, radius=16, dtype=binding.DC_BF16, want_regions=True)
+    followed = [0, 31, 63]
+    refs = {s: oracle.Stream(layers, ws, bs, 224, 224, 3, block=16, radius=16, bf16=True) for s in followed}
+    dv = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
+    for t in range(T):
+        print(f"[batch64] step {t}", flush=True)
+        tensors = r.step(dv[t])
+        torch.cuda.synchronize()
+        for s in followed:
+            want = refs[s].step(videos[s, t])
+            for ti in range(1, len(layers) + 1):
+                g = tensors[ti][s].float().cpu().numpy()
+                assert _rel_err(g, want["tensors"][ti]) <= 2e-2, (t, s, ti)
+            if t > 0:
+                regs = r.regions(s)
+                for ti in range(len(layers) + 1):
+                    assert regs[ti]["rects"].tolist() == want["rects"][ti].tolist()
+        if t > 0:
+            masks = r.mask.cpu().numpy()
+            gmv = r.gmv.cpu().numpy()
+            for s in range(0, n, 7):
+                m = oracle.match_blocks(videos[s, t], videos[s, t - 1], 16, 16, synth.max_block_ssd(16))
+                assert np.array_equal(masks[s], m["mask"]) and gmv[s].tolist() == m["gmv"].tolist()
