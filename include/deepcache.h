@@ -108,6 +108,16 @@ int32_t dc_profile_destroy(void* profile);
 int32_t dc_profile_reset(void* profile);
 int32_t dc_profile_elapsed_ms(void* profile, int32_t slot, float* ms);
 
+/*
+ * Overlap handle (Section 7.6: matching and inference can run asynchronously): a second
+ * HIP stream and two events owned by the library object.  Passed to dc_run_stack, the
+ * matching of a frame runs on that stream, next to whatever the main stream still holds of
+ * the previous frame, and only the matching is waited for; without it the call waits for the
+ * main stream.  For callers that may not create streams the handle is simply left out.
+ */
+int32_t dc_overlap_create(void** overlap);
+int32_t dc_overlap_destroy(void* overlap);
+
 /* Name of a GEMM kernel instantiation (as a profiler prints it, without namespace and
  * argument list) for an id reported in dc_stack_stats.layer_kernel_id. */
 int32_t dc_conv_kernel_name(int32_t kernel_id, char* buf, size_t n);
@@ -222,8 +232,11 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
  *                   receives every tensor's regions (for inspection); may be NULL
  *   ws_dev, ws_host workspaces of at least dc_stack_workspace_bytes; ws_host should be pinned
  *   stats           optional host
- * The call synchronises the stream once after matching (the region logic runs on the
- * host); everything after that is asynchronous.
+ *   overlap         optional dc_overlap handle; with it the frames must be visible to any stream
+ *                   when the call is made (the matching does not wait for the main stream)
+ * The call waits once for the matching (the region logic runs on the host): for the main
+ * stream without an overlap handle, for the handle's stream with one; everything after that
+ * is asynchronous.
  */
 int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers,
                      const void* const* weights, const float* const* bias,
@@ -234,7 +247,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers,
                      int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
                      uint8_t* block_mask, int32_t max_rects, dc_regions* regions_out,
                      void* ws_dev, size_t ws_dev_bytes, void* ws_host, size_t ws_host_bytes,
-                     dc_stack_stats* stats, void* stream);
+                     dc_stack_stats* stats, void* overlap, void* stream);
 
 #ifdef __cplusplus
 }

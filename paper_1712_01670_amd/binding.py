@@ -22,7 +22,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
           -4: "DC_ERR_UNSUPPORTED", -5: "DC_ERR_WORKSPACE", -6: "DC_ERR_CAPACITY", -7: "DC_ERR_HIP"}
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
-           "dc_profile_elapsed_ms", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
+           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
            "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
@@ -71,6 +71,8 @@ def lib():
         L.dc_profile_destroy.argtypes = [vp]
         L.dc_profile_reset.argtypes = [vp]
         L.dc_profile_elapsed_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
+        L.dc_overlap_create.argtypes = [C.POINTER(vp)]
+        L.dc_overlap_destroy.argtypes = [vp]
         L.dc_conv_kernel_name.argtypes = [i32, C.c_char_p, sz]
         L.dc_conv_tile_shape.argtypes = [vp, i32, i32, i32, i32] + [C.POINTER(i32)] * 4
         L.dc_match_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
@@ -82,7 +84,7 @@ def lib():
         L.dc_add_layer.argtypes = [vp, vp, vp, sz, i32, i32, vp]
         L.dc_stack_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
         L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, i32,
-                                   vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp]
+                                   vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp, vp]
         for name in EXPORTS:
             if name != "dc_status_string":
                 getattr(L, name).restype = i32
@@ -272,7 +274,7 @@ class StackRunner:
 
     def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
-                 want_regions=False, pad_input=True):
+                 want_regions=False, pad_input=True, overlap=True):
         self.Ch_tensor = Ch
         if pad_input:
             layers, weights, self.Ch_tensor = pad_input_channels(layers, weights, Ch, dtype)
@@ -321,9 +323,23 @@ class StackRunner:
         self.stats.layer_issued_macs = C.cast(self._issued, C.POINTER(C.c_int64))
         self._kid = (C.c_int32 * nl)()
         self.stats.layer_kernel_id = C.cast(self._kid, C.POINTER(C.c_int32))
+        self.overlap = None
+        if overlap:
+            h = C.c_void_p()
+            _check("dc_overlap_create", lib().dc_overlap_create(C.byref(h)))
+            self.overlap = h
         self.regs = None
         if want_regions:
             self.regs, self._regs_store = _alloc_regions(n_streams * (nl + 1), max_rects)
+
+    def __del__(self):
+        try:
+            if self.overlap:
+                torch.cuda.synchronize()
+                lib().dc_overlap_destroy(self.overlap)
+                self.overlap = None
+        except Exception:
+            pass
 
     def reset(self):
         """Drop the cache (scene cut): the next frame is computed in full."""
@@ -344,7 +360,7 @@ class StackRunner:
             self._tp[c], self._tp[p], self.n, self.H, self.W, self.Ch, self.dtype, self.block, self.radius,
             self.max_block_ssd, int(full), _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
             _ptr(self.mask), self.max_rects, self.regs, _ptr(self.ws_dev), self.ws_dev.numel(),
-            C.c_void_p(self.ws_host.data_ptr()), self.ws_host.numel(), C.byref(self.stats), _stream()))
+            C.c_void_p(self.ws_host.data_ptr()), self.ws_host.numel(), C.byref(self.stats), self.overlap, _stream()))
         self.age = 1 if full else self.age + 1
         self.have_prev = True
         self.prev_frames = frames

@@ -187,6 +187,32 @@ int32_t dc_profile_elapsed_ms(void* profile, int32_t slot, float* ms) {
     return DC_OK;
 }
 
+int32_t dc_overlap_create(void** overlap) {
+    if (!overlap) return DC_ERR_NULL_PTR;
+    Overlap* o = new (std::nothrow) Overlap();
+    if (!o) return DC_ERR_WORKSPACE;
+    bool ok = hipStreamCreateWithFlags(&o->aux, hipStreamNonBlocking) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&o->upload_done[i], hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+        for (int i = 0; i < 2; ++i) if (o->upload_done[i]) (void)hipEventDestroy(o->upload_done[i]);
+        if (o->aux) (void)hipStreamDestroy(o->aux);
+        delete o;
+        return DC_ERR_HIP;
+    }
+    *overlap = o;
+    return DC_OK;
+}
+
+int32_t dc_overlap_destroy(void* overlap) {
+    if (!overlap) return DC_ERR_NULL_PTR;
+    Overlap* o = static_cast<Overlap*>(overlap);
+    (void)hipStreamSynchronize(o->aux);
+    for (int i = 0; i < 2; ++i) (void)hipEventDestroy(o->upload_done[i]);
+    (void)hipStreamDestroy(o->aux);
+    delete o;
+    return DC_OK;
+}
+
 int32_t dc_conv_kernel_name(int32_t kernel_id, char* buf, size_t n) {
     if (!buf) return DC_ERR_NULL_PTR;
     if (n < 2 || kernel_id < 0 || kernel_id >= 24) return DC_ERR_INVALID_ARG;
@@ -365,7 +391,7 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
     const size_t nb = (size_t)n_streams * (H / block) * (W / block);
     size_t match_host = align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
     *dev_bytes = total;
-    *host_bytes = total + match_host;
+    *host_bytes = 2 * total + match_host;   // two staging halves (used alternately with an overlap handle)
     return DC_OK;
 }
 
@@ -375,7 +401,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                      int32_t dtype, int32_t block, int32_t radius, uint32_t max_block_ssd, int32_t force_full,
                      int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask,
                      int32_t max_rects, dc_regions* regions_out, void* ws_dev, size_t ws_dev_bytes, void* ws_host,
-                     size_t ws_host_bytes, dc_stack_stats* stats, void* stream) {
+                     size_t ws_host_bytes, dc_stack_stats* stats, void* overlap, void* stream) {
     if (!layers || !weights || !frames_cur || !tensors_cur) return DC_ERR_NULL_PTR;
     if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
     if (n_layers < 1 || n_streams < 1 || n_streams > 65535 || block < 1 || radius < 0 || max_rects < 1) return DC_ERR_INVALID_ARG;
@@ -401,6 +427,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         if (rc) return rc;
         if (ws_dev_bytes < need_dev || ws_host_bytes < need_host) return DC_ERR_WORKSPACE;
     }
+    Overlap* ov = static_cast<Overlap*>(overlap);
     hipStream_t st = as_stream(stream);
     const int gh = H / block, gw = W / block;
     const size_t nb = (size_t)n_streams * gh * gw;
@@ -419,16 +446,19 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     std::vector<std::vector<TensorRegions>> regs;  // [stream][tensor]
     unsigned char* hbase = static_cast<unsigned char*>(ws_host);
     if (cached) {
+        // With an overlap handle the matching runs on its own stream, next to whatever the main stream
+        // still holds of the previous frame; only that stream is waited for.
+        hipStream_t mst = ov ? ov->aux : st;
         rc = dc_match_blocks(frames_cur, frames_prev, n_streams, H, W, C, block, radius, max_block_ssd, mv, best_ssd,
-                             global_mv, n_pass, block_mask, stream);
+                             global_mv, n_pass, block_mask, mst);
         if (rc) return rc;
-        // the network input does not depend on the match: overlap its conversion with the readback
-        DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
         uint8_t* h_mask = hbase;
         int32_t* h_gmv = reinterpret_cast<int32_t*>(hbase + align_up(nb, 256));
-        DC_TRY_HIP(hipMemcpyAsync(h_mask, block_mask, nb, hipMemcpyDeviceToHost, st));
-        DC_TRY_HIP(hipMemcpyAsync(h_gmv, global_mv, (size_t)n_streams * 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-        DC_TRY_HIP(hipStreamSynchronize(st));
+        DC_TRY_HIP(hipMemcpyAsync(h_mask, block_mask, nb, hipMemcpyDeviceToHost, mst));
+        DC_TRY_HIP(hipMemcpyAsync(h_gmv, global_mv, (size_t)n_streams * 2 * sizeof(int32_t), hipMemcpyDeviceToHost, mst));
+        // the network input does not depend on the match: its conversion overlaps the readback
+        DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
+        DC_TRY_HIP(hipStreamSynchronize(mst));
         try {
             regs.resize(n_streams);
             std::vector<dc_rect> rects0;
@@ -445,6 +475,15 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             return DC_ERR_WORKSPACE;
         }
         hbase += align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
+        if (ov) {
+            // two staging halves: the upload of the frame before last must have left the half reused now
+            const size_t half = (ws_host_bytes - (size_t)(hbase - static_cast<unsigned char*>(ws_host))) / 2 / 256 * 256;
+            hbase += (size_t)ov->parity * half;
+            if (ov->pending[ov->parity]) {
+                DC_TRY_HIP(hipEventSynchronize(ov->upload_done[ov->parity]));
+                ov->pending[ov->parity] = false;
+            }
+        }
     } else {
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
     }
@@ -542,7 +581,14 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             return DC_ERR_WORKSPACE;
         }
     }
-    if (cached && off) DC_TRY_HIP(hipMemcpyAsync(ws_dev, hbase, off, hipMemcpyHostToDevice, st));
+    if (cached && off) {
+        DC_TRY_HIP(hipMemcpyAsync(ws_dev, hbase, off, hipMemcpyHostToDevice, st));
+        if (ov) {
+            DC_TRY_HIP(hipEventRecord(ov->upload_done[ov->parity], st));
+            ov->pending[ov->parity] = true;
+            ov->parity ^= 1;
+        }
+    }
     if (n_all_rects) {
         unsigned char* d = static_cast<unsigned char*>(ws_dev);
         Bracket b(stats ? static_cast<Profile*>(stats->profile) : nullptr, n_layers, st);   // first copy slot

@@ -75,10 +75,14 @@ struct ConvParams {
     int n_tapgroups, n_chunks;
     int R;                  // number of NT-wide channel tiles
     int pv, wv;             // load slots per thread (staged) or per wavefront (direct) per stage
+    int p_instr, w_instr;   // direct kernel: 1 KiB load instructions per stage for the patches / the weights
     int patch_bytes;        // LDS bytes of one patch buffer (whole slots)
     int weight_bytes;       // LDS bytes of one weight buffer (whole slots)
     int dump_off;           // staged kernel: byte offset (after the header) of the per-thread dump slots
     uint32_t in_bytes, w_bytes;
+    int g_rt;               // units per workgroup actually used (<= G)
+    int chan_tail;          // 1: Cin is not a multiple of the channel chunk (per-slot channel check needed)
+    int tap_tail;           // 1: k*k is not a multiple of TG (per-slot tap check needed)
     int out_vec;            // 1: four consecutive output channels can be stored (and the bias read) as one vector
 };
 
@@ -95,6 +99,10 @@ struct Frag<float> {
         c = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[2], xv[2], c, 0, 0, 0);
         c = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[3], xv[3], c, 0, 0, 0);
     }
+    static constexpr int NE = 4;   // MFMAs per fragment pair
+    static __device__ __forceinline__ void mma1(const vec& wv, const vec& xv, floatx4& c, int e) {
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[e], xv[e], c, 0, 0, 0);
+    }
     static __device__ __forceinline__ void store4(float* p, const floatx4& v) { *reinterpret_cast<floatx4*>(p) = v; }
     static __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
     static __device__ __forceinline__ float elem(__amdgpu_buffer_rsrc_t r, uint32_t off) {
@@ -106,6 +114,10 @@ struct Frag<__hip_bfloat16> {
     typedef bf16x8 vec;
     static constexpr int VE = 8;
     static __device__ __forceinline__ void mma(const vec& wv, const vec& xv, floatx4& c) {
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, xv, c, 0, 0, 0);
+    }
+    static constexpr int NE = 1;
+    static __device__ __forceinline__ void mma1(const vec& wv, const vec& xv, floatx4& c, int) {
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, xv, c, 0, 0, 0);
     }
     static __device__ __forceinline__ unsigned short bits(float v) {
@@ -122,6 +134,15 @@ struct Frag<__hip_bfloat16> {
         return __builtin_bit_cast(__bf16, (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0));
     }
 };
+
+// Makes a wavefront-uniform value opaque to the optimiser, so that it is kept in scalar registers
+// instead of being re-loaded from the kernel arguments inside the main loop (a scalar load there
+// costs a full lgkmcnt(0) wait, which also drains the LDS reads in flight).
+template <typename V>
+__device__ __forceinline__ V keep_scalar(V v) {
+    asm volatile("" : "+s"(v));
+    return v;
+}
 
 __device__ __forceinline__ int fast_div(int n, uint32_t magic) { return (int)__umulhi((uint32_t)n, magic); }
 
@@ -156,8 +177,8 @@ __device__ __forceinline__ void decode_workgroup(int R, int& ug, int& ntile) {
 template <int G, int NTHREADS>
 __device__ __forceinline__ void decode_units(const ConvParams& P, const Header<G>& H, int ug, int tid) {
     if (tid < G) {
-        const int u = ug * G + tid;
-        int valid = u < P.n_units, stream = 0, uy = 0, ux = 0, mixed = 0;
+        const int u = ug * P.g_rt + tid;
+        int valid = tid < P.g_rt && u < P.n_units, stream = 0, uy = 0, ux = 0, mixed = 0;
         if (valid) {
             if (P.units) {
                 const TileDev t = P.units[u];
@@ -229,15 +250,16 @@ __device__ __forceinline__ bool reduce_k_split(floatx4 (&acc)[UPW][NBW], unsigne
 }
 
 // lane (l16, q): pixel l16 of the unit, channels 4q..4q+3 of each 16-channel block
+// wavefront-local unit u is unit u * unit_stride + unit0 of the workgroup
 template <typename T, int G, int UPW, int NBW>
 __device__ __forceinline__ void epilogue(const ConvParams& P, const Header<G>& H, const floatx4 (&acc)[UPW][NBW],
-                                         int unit0, int chan0, int l16, int q) {
+                                         int unit0, int unit_stride, int chan0, int l16, int q) {
     typedef Frag<T> F;
     T* out = reinterpret_cast<T*>(P.out);
     const bool vec_ok = P.out_vec != 0;
 #pragma unroll
     for (int u = 0; u < UPW; ++u) {
-        const int g = unit0 + u;
+        const int g = unit0 + u * unit_stride;
         if (!H.uinfo[4 * g]) continue;
         const int y = H.uinfo[4 * g + 2] + (l16 >> 2), x = H.uinfo[4 * g + 3] + (l16 & 3);
         if (y >= P.Hout || x >= P.Wout || H.tmask[g * 16 + l16]) continue;
@@ -285,6 +307,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
     constexpr int RB = KC * ES;                // row bytes
     constexpr int RPC = 256 / RB;              // rows per pass over the banks
     constexpr int RPI = 64 / NVEC;             // rows filled by one load instruction (1 KiB)
+    constexpr int UC = UPW >= 2 ? 2 : 1;       // units per compute group
     static_assert(G % WM == 0 && NT % (WN * 16) == 0 && KC % KG == 0 && RB <= 256, "tile shape");
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -303,8 +326,10 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
     const int n0 = ntile * NT;
     decode_units<G, NTHREADS>(P, H, ug, tid);
 
-    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.in), 0, P.in_bytes, kBufferFlags);
-    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.w), 0, P.w_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.in))), 0, keep_scalar(P.in_bytes), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.w))), 0, keep_scalar(P.w_bytes), kBufferFlags);
 
     // ---- load slots: instruction j of a buffer fills LDS bytes [1024 j, 1024 j + 1024); this
     // wavefront issues instructions wave, wave + NWAVES, ...; lane fills chunk position lane % NVEC
@@ -329,28 +354,39 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
         wgo[i] = (tl < P.tg && n0 + n < P.Cout) ? ((uint32_t)(((n0 + n) * kk + tl) * P.Cin) * ES + c * 16) | (uint32_t)c : kOob;
     }
 
+    // loop-invariant scalars, pinned in SGPRs
+    const int Cin = keep_scalar(P.Cin), kdim = keep_scalar(P.k), pwid = keep_scalar(P.pw), tgs = keep_scalar(P.tg);
+    const int n_tapgroups = keep_scalar(P.n_tapgroups), patch_bytes = keep_scalar(P.patch_bytes);
+    const int weight_bytes = keep_scalar(P.weight_bytes);
+    const int np_slots = keep_scalar((P.p_instr - wave + NWAVES - 1) / NWAVES);   // load instructions of this wavefront
+    const int nw_slots = keep_scalar((P.w_instr - wave + NWAVES - 1) / NWAVES);
+    const int tails = keep_scalar(P.chan_tail | P.tap_tail);
+
     auto issue_stage = [&](int chunk, int tgi, int pbuf, int wbuf) {
         const int c0 = chunk * KC;
         if (tgi == 0) {
-            unsigned char* dst = stage0 + pbuf * P.patch_bytes + wave * 1024;
+            unsigned char* dst = stage0 + pbuf * patch_bytes + wave * 1024;
 #pragma unroll
             for (int i = 0; i < DPMAX; ++i) {
-                if (i < P.pv) {
-                    const bool ok = pgo[i] != kOob && c0 + (int)(pgo[i] & 15) * VE < P.Cin;
-                    const uint32_t off = ok ? (pgo[i] & ~15u) + (uint32_t)c0 * ES : kOob;
+                if (i < np_slots) {
+                    uint32_t off = pgo[i] + (uint32_t)c0 * ES;   // kOob stays out of range; the low 4 bits are ignored below
+                    if (tails) off = (pgo[i] != kOob && c0 + (int)(pgo[i] & 15) * VE < Cin) ? off : kOob;
+                    off &= ~15u;
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(in_rsrc, (__attribute__((address_space(3))) void*)(dst + i * (NWAVES * 1024)),
                                                              16, off, 0, 0, 0);
                 }
             }
         }
-        const int tap0 = tgi * P.tg;
-        unsigned char* dst = stage0 + 2 * P.patch_bytes + wbuf * P.weight_bytes + wave * 1024;
-        const uint32_t stage_off = (uint32_t)(tap0 * P.Cin + c0) * ES;
+        const int tap0 = tgi * tgs;
+        unsigned char* dst = stage0 + 2 * patch_bytes + wbuf * weight_bytes + wave * 1024;
+        const uint32_t stage_off = (uint32_t)(tap0 * Cin + c0) * ES;
 #pragma unroll
         for (int i = 0; i < DWMAX; ++i) {
-            if (i < P.wv) {
-                const bool ok = wgo[i] != kOob && tap0 + wtl[i] < kk && c0 + (int)(wgo[i] & 15) * VE < P.Cin;
-                const uint32_t off = ok ? (wgo[i] & ~15u) + stage_off : kOob;
+            if (i < nw_slots) {
+                uint32_t off = wgo[i] + stage_off;
+                if (tails)
+                    off = (wgo[i] != kOob && tap0 + wtl[i] < kk && c0 + (int)(wgo[i] & 15) * VE < Cin) ? off : kOob;
+                off &= ~15u;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (__attribute__((address_space(3))) void*)(dst + i * (NWAVES * 1024)),
                                                          16, off, 0, 0, 0);
             }
@@ -360,7 +396,8 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
     // ---- per-lane fragment rows ----
     int xrow[UPW];   // patch row of this lane's pixel at tap (0,0)
 #pragma unroll
-    for (int u = 0; u < UPW; ++u) xrow[u] = (wave_m * UPW + u) * npix + ((l16 >> 2) * P.s) * P.pw + (l16 & 3) * P.s;
+    for (int u = 0; u < UPW; ++u) xrow[u] = (u * WM + wave_m) * npix + ((l16 >> 2) * P.s) * P.pw + (l16 & 3) * P.s;
+    const int n_u = keep_scalar((P.g_rt - wave_m + WM - 1) / WM);   // units of this wavefront: wave_m, wave_m + WM, ...
     int wbase[NBW];  // byte offset of this lane's weight row at tap 0 of the stage
 #pragma unroll
     for (int j = 0; j < NBW; ++j) wbase[j] = ((wave_n * NBW + j) * 16 + l16) * RB;
@@ -372,32 +409,37 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
 #pragma unroll
         for (int j = 0; j < NBW; ++j) acc[u][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const int n_stages = P.n_chunks * P.n_tapgroups;
+    const int n_stages = keep_scalar(P.n_chunks * P.n_tapgroups);
     issue_stage(0, 0, 0, 0);
     int chunk = 0, tgi = 0;
     for (int st = 0; st < n_stages; ++st) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's loads of stage st are in LDS
         __syncthreads();                                   // ... and everybody's; stage st-1 is fully consumed
         int nchunk = chunk, ntgi = tgi + 1;
-        if (ntgi == P.n_tapgroups) { ntgi = 0; ++nchunk; }
+        if (ntgi == n_tapgroups) { ntgi = 0; ++nchunk; }
         if (st + 1 < n_stages) issue_stage(nchunk, ntgi, nchunk & 1, (st + 1) & 1);   // fills the other buffers
 
-        const unsigned char* patch = stage0 + (chunk & 1) * P.patch_bytes;
-        const unsigned char* wt = stage0 + 2 * P.patch_bytes + (st & 1) * P.weight_bytes;
-        const int tap0 = tgi * P.tg;
-        const int ntap = (kk - tap0) < P.tg ? (kk - tap0) : P.tg;
+        const unsigned char* patch = stage0 + (chunk & 1) * patch_bytes;
+        const unsigned char* wt = stage0 + 2 * patch_bytes + (st & 1) * weight_bytes;
+        const int tap0 = tgi * tgs;
+        const int ntap = (kk - tap0) < tgs ? (kk - tap0) : tgs;
         const int steps = ntap * GPC;
         int sidx = wave_k;
         if (sidx < steps) {
             int tl = sidx / GPC, g = sidx - tl * GPC;
-            int ky = (tap0 + tl) / P.k, kx = (tap0 + tl) - ky * P.k;
+            int ky = (tap0 + tl) / kdim, kx = (tap0 + tl) - ky * kdim;
             vec x0[UPW], w0[NBW], x1[UPW], w1[NBW];
             auto frag = [&](vec (&xv)[UPW], vec (&wv)[NBW]) {
-                const int trow = ky * P.pw + kx, c = g * 4 + q;
+                const int trow = ky * pwid + kx, c = g * 4 + q;
 #pragma unroll
-                for (int u = 0; u < UPW; ++u) {
-                    const uint32_t row = (uint32_t)(xrow[u] + trow);
-                    xv[u] = *reinterpret_cast<const vec*>(patch + row * RB + (((uint32_t)c ^ ((row / RPC) % NVEC)) << 4));
+                for (int u0 = 0; u0 < UPW; u0 += UC) {
+                    if (u0 < n_u) {     // units are handled in groups of UC: one uniform branch per group
+#pragma unroll
+                        for (int u = u0; u < u0 + UC; ++u) {
+                            const uint32_t row = (uint32_t)(xrow[u] + trow);
+                            xv[u] = *reinterpret_cast<const vec*>(patch + row * RB + (((uint32_t)c ^ ((row / RPC) % NVEC)) << 4));
+                        }
+                    }
                 }
                 const int woff = tl * (NT * RB) + ((c ^ wswz) << 4);
 #pragma unroll
@@ -407,14 +449,21 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
                 g += WK;
                 while (g >= GPC) {
                     g -= GPC; ++tl; ++kx;
-                    if (kx == P.k) { kx = 0; ++ky; }
+                    if (kx == kdim) { kx = 0; ++ky; }
                 }
             };
             auto mma = [&](const vec (&xv)[UPW], const vec (&wv)[NBW]) {
 #pragma unroll
-                for (int u = 0; u < UPW; ++u)
+                for (int u0 = 0; u0 < UPW; u0 += UC) {
+                    if (u0 < n_u) {     // UC * NBW independent accumulator chains are interleaved
 #pragma unroll
-                    for (int j = 0; j < NBW; ++j) F::mma(wv[j], xv[u], acc[u][j]);
+                        for (int e = 0; e < F::NE; ++e)
+#pragma unroll
+                            for (int u = u0; u < u0 + UC; ++u)
+#pragma unroll
+                                for (int j = 0; j < NBW; ++j) F::mma1(wv[j], xv[u], acc[u][j], e);
+                    }
+                }
             };
             frag(x0, w0);
             for (;;) {
@@ -432,7 +481,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
     }
 
     if (!reduce_k_split<WM, WN, WK, UPW, NBW>(acc, stage0, wave, lane)) return;
-    epilogue<T, G, UPW, NBW>(P, H, acc, wave_m * UPW, n0 + wave_n * NBW * 16, l16, q);
+    epilogue<T, G, UPW, NBW>(P, H, acc, wave_m, WM, n0 + wave_n * NBW * 16, l16, q);
 }
 
 // ---- register-staged kernel (any channel count) -----------------------------------------
@@ -468,8 +517,10 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_staged_kernel(ConvParams
     const int n0 = ntile * NT;
     decode_units<G, NTHREADS>(P, H, ug, tid);
 
-    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.in), 0, P.in_bytes, kBufferFlags);
-    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.w), 0, P.w_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.in))), 0, keep_scalar(P.in_bytes), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.w))), 0, keep_scalar(P.w_bytes), kBufferFlags);
 
     // slot i of a thread covers LDS row (tid / NVEC) + i * RS, vector tid % NVEC
     const int row0 = tid / NVEC, chv = (tid % NVEC) * VE;
@@ -573,17 +624,19 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_staged_kernel(ConvParams
     }
 
     if (!reduce_k_split<WM, WN, WK, UPW, NBW>(acc, smem + kHeaderBytes, wave, lane)) return;
-    epilogue<T, G, UPW, NBW>(P, H, acc, wave_m * UPW, n0 + wave_n * NBW * 16, l16, q);
+    epilogue<T, G, UPW, NBW>(P, H, acc, wave_m * UPW, 1, n0 + wave_n * NBW * 16, l16, q);
 }
 
 // ---- kernel table ---------------------------------------------------------------
 struct Shape { int g, nt, wm, wn, wk; };
 // Eight wavefronts per workgroup: two per SIMD, so that one issues MFMAs while the other computes
 // addresses and waits for LDS.
-constexpr Shape kShapes[3] = {
+constexpr int kNumShapes = 4;
+constexpr Shape kShapes[kNumShapes] = {
     {4, 64, 2, 2, 2},   // 0: plenty of units
     {2, 32, 1, 2, 4},   // 1: medium
     {1, 32, 1, 1, 8},   // 2: few units, deep K (small maps)
+    {16, 64, 2, 4, 1},  // 3: up to 16 units per workgroup (the count is a launch parameter): large maps
 };
 
 typedef void (*KernelFn)(ConvParams);
@@ -595,9 +648,9 @@ struct KernelEntry { KernelFn fn[2][4]; };
 #define DC_ENTRY(S)                                                                       \
     {{{DC_D(float, S, 16), DC_D(float, S, 32), DC_D(float, S, 64), DC_S(float, S, 16)},   \
       {DC_D(__hip_bfloat16, S, 32), DC_D(__hip_bfloat16, S, 64), DC_D(__hip_bfloat16, S, 128), DC_S(__hip_bfloat16, S, 32)}}}
-const KernelEntry kTable[3] = {DC_ENTRY(0), DC_ENTRY(1), DC_ENTRY(2)};
+const KernelEntry kTable[kNumShapes] = {DC_ENTRY(0), DC_ENTRY(1), DC_ENTRY(2), DC_ENTRY(3)};
 
-struct Choice { int shape, kci, kc, tg, pv, wv, patch_bytes, weight_bytes, dump_off; size_t lds; bool ok; };
+struct Choice { int shape, kci, kc, tg, pv, wv, patch_bytes, weight_bytes, dump_off; size_t lds; bool ok; int p_instr, w_instr; };
 bool tune_override(int& kci, int& tg);
 
 size_t reduce_bytes(const Shape& S) {
@@ -612,7 +665,7 @@ Choice choose_direct(int shape, const ConvLaunch& c, int ph, int pw) {
     const size_t esz = dtype_size(c.dtype);
     const int ve = (int)(16 / esz), kg = 4 * ve;
     const int kk = c.k * c.k;
-    Choice best{shape, 0, 0, 0, 0, 0, 0, 0, 0, 0, false};
+    Choice best{shape, 0, 0, 0, 0, 0, 0, 0, 0, 0, false, 0, 0};
     long best_score = -1;
     int f_kci = -1, f_tg = 0;
     const bool forced = tune_override(f_kci, f_tg);
@@ -624,22 +677,27 @@ Choice choose_direct(int shape, const ConvLaunch& c, int ph, int pw) {
         const int p_instr = (S.g * ph * pw + rpi - 1) / rpi;
         const int pv = (p_instr + nwaves - 1) / nwaves;
         if (pv > DPMAX) continue;
-        const size_t patch_bytes = (size_t)pv * nwaves * 1024;
-        for (int tg = (forced && f_tg >= 1 && f_tg < kk) ? f_tg : kk; tg >= 1; --tg) {
+        const size_t patch_bytes = (size_t)p_instr * 1024;
+        // taps per stage: balanced splits of the k*k taps only (ceil(kk/m)), so that no stage is much shorter
+        // than the loads it has to hide
+        for (int m = 1; m <= kk; ++m) {
+            int tg = (kk + m - 1) / m;
+            if (m > 1 && tg == (kk + m - 2) / (m - 1)) continue;
+            if (forced && f_tg >= 1 && f_tg <= kk) { if (m > 1) break; tg = f_tg; }
             const int w_instr = (tg * S.nt + rpi - 1) / rpi;
             const int wv = (w_instr + nwaves - 1) / nwaves;
             if (wv > DWMAX) continue;
-            const size_t weight_bytes = (size_t)wv * nwaves * 1024;
+            const size_t weight_bytes = (size_t)w_instr * 1024;
             size_t body = 2 * patch_bytes + 2 * weight_bytes;
             if (body < reduce_bytes(S)) body = reduce_bytes(S);
             const size_t lds = kHeaderBytes + body;
-            if (lds > 150 * 1024) continue;
+            if (lds > 160 * 1024) continue;
             // useful K per stage; prefer stages that keep two workgroups per CU when the gain is small
             long score = (long)tg * (kc < c.Cin ? kc : c.Cin);
             if (lds > 80 * 1024) score = score * 3 / 4;
             if (score > best_score) {
                 best_score = score;
-                best = Choice{shape, kci, kc, tg, pv, wv, (int)patch_bytes, (int)weight_bytes, 0, lds, true};
+                best = Choice{shape, kci, kc, tg, pv, wv, (int)patch_bytes, (int)weight_bytes, 0, lds, true, p_instr, w_instr};
             }
             break;   // smaller tg only lowers the score for this kc (unless LDS-limited: handled by continue)
         }
@@ -654,7 +712,7 @@ Choice choose_staged(int shape, const ConvLaunch& c, int ph, int pw) {
     const int ve = (int)(16 / esz), kc = 4 * ve;
     const int kk = c.k * c.k;
     const int nvec = kc / ve, rs = nth / nvec, kcp = kc + ve;
-    Choice ch{shape, 3, kc, 0, 0, 0, 0, 0, 0, 0, false};
+    Choice ch{shape, 3, kc, 0, 0, 0, 0, 0, 0, 0, false, 0, 0};
     const int pv = (S.g * ph * pw + rs - 1) / rs;
     if (pv > PVMAX) return ch;
     int tg = (WVMAX * rs) / S.nt;
@@ -694,8 +752,8 @@ ConvTiling pick_tiling(const dc_layer&, int, int, int, int) { return ConvTiling{
 
 // Name of a kernel instantiation as a profiler prints it (without namespaces and arguments).
 void conv_kernel_name(int id, char* buf, size_t n) {
-    if (id < 0 || id >= 24) { snprintf(buf, n, "?"); return; }
-    const int kci = id & 3, shape = (id >> 2) % 3, bf16 = (id >> 2) / 3;
+    if (id < 0 || id >= 8 * kNumShapes) { snprintf(buf, n, "?"); return; }
+    const int kci = id & 3, shape = (id >> 2) % kNumShapes, bf16 = (id >> 2) / kNumShapes;
     const Shape& S = kShapes[shape];
     const int kg = bf16 ? 32 : 16;
     const int kc = kci == 3 ? kg : (kg << kci);
@@ -712,29 +770,35 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     if ((double)c.n_streams * c.Hin * c.Win * c.Cin * dtype_size(c.dtype) >= 2147483648.0 ||
         (double)c.Cout * c.k * c.k * c.Cin * dtype_size(c.dtype) >= 2147483648.0)
         return hipErrorInvalidValue;
-    // shape by the amount of work: largest tile that still fills the chip
-    int shape;
+    // Shape by the amount of work.  With enough units a workgroup takes g of them (up to 16) and 64
+    // channels, g chosen so that the launch fills the 256 CUs in whole rounds; with few units the
+    // smaller shapes split K among the wavefronts instead.
+    int shape, g_rt;
     {
-        static int t0 = -1, t1 = -1;
-        if (t0 < 0) {
-            const char* e0 = getenv("DC_CONV_T0");
+        static int t1 = -1, xl_min = -1;
+        if (t1 < 0) {
             const char* e1 = getenv("DC_CONV_T1");
-            t0 = e0 ? atoi(e0) : 160;
+            const char* e2 = getenv("DC_CONV_XLMIN");
             t1 = e1 ? atoi(e1) : 160;
+            xl_min = e2 ? atoi(e2) : 8;
         }
         const long r64 = (c.Cout + 63) / 64, r32 = (c.Cout + 31) / 32;
-        if (c.Cout > 32 && ((n_units + 3) / 4) * r64 >= t0) shape = 0;
-        else if (((n_units + 1) / 2) * r32 >= t1) shape = 1;
-        else shape = 2;
+        const long rounds = (n_units * r64 + 256 * 16 - 1) / (256 * 16);
+        const long g = (n_units * r64 + 256 * rounds - 1) / (256 * rounds);
+        if (c.Cout > 32 && g >= xl_min) { shape = 3; g_rt = (int)(g > 16 ? 16 : g); }
+        else if (c.Cout > 32 && ((n_units + 3) / 4) * r64 >= 160) { shape = 0; g_rt = 4; }
+        else if (((n_units + 1) / 2) * r32 >= t1) { shape = 1; g_rt = 2; }
+        else { shape = 2; g_rt = 1; }
     }
     const int ph = 3 * c.s + c.k, pw = ph;
     const size_t esz = dtype_size(c.dtype);
     const bool vec_ok = (c.Cin % (16 / esz)) == 0 && reinterpret_cast<uintptr_t>(c.in) % 16 == 0 &&
                         reinterpret_cast<uintptr_t>(c.w) % 16 == 0;
     Choice ch{};
-    for (int s2 = shape; s2 < 3; ++s2) {
+    for (int s2 = shape; s2 < 4; s2 = (s2 == 3 ? 0 : (s2 == 2 ? 4 : s2 + 1))) {   // 3 -> 0 -> 1 -> 2
         ch = vec_ok ? choose_direct(s2, c, ph, pw) : Choice{};
-        if (!ch.ok) ch = choose_staged(s2, c, ph, pw);
+        if (!ch.ok) { ch = choose_staged(s2, c, ph, pw); if (ch.ok) g_rt = kShapes[s2].g; }
+        else if (s2 != shape) g_rt = kShapes[s2].g;
         if (ch.ok) break;
     }
     if (!ch.ok) return hipErrorInvalidValue;
@@ -747,7 +811,8 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     P.units = c.tiles; P.n_units = (int)n_units; P.rects = c.rects; P.ranges = c.ranges;
     P.units_x = units_x; P.units_y = units_y;
     P.ph = ph; P.pw = pw; P.npix_magic = magic_of(ph * pw); P.pw_magic = magic_of(pw);
-    P.tg = ch.tg; P.pv = ch.pv; P.wv = ch.wv;
+    P.tg = ch.tg; P.pv = ch.pv; P.wv = ch.wv; P.g_rt = g_rt; P.p_instr = ch.p_instr; P.w_instr = ch.w_instr;
+    P.chan_tail = (c.Cin % ch.kc) != 0; P.tap_tail = ((c.k * c.k) % ch.tg) != 0;
     P.patch_bytes = ch.patch_bytes; P.weight_bytes = ch.weight_bytes; P.dump_off = ch.dump_off;
     P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * c.Cin * esz);
     P.w_bytes = (uint32_t)((size_t)c.Cout * c.k * c.k * c.Cin * esz);
@@ -757,13 +822,13 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     P.n_chunks = (c.Cin + ch.kc - 1) / ch.kc;
     P.R = (c.Cout + S.nt - 1) / S.nt;
     KernelFn fn = kTable[ch.shape].fn[c.dtype == DC_BF16 ? 1 : 0][ch.kci];
-    if (c.kernel_id) *c.kernel_id = ((c.dtype == DC_BF16 ? 1 : 0) * 3 + ch.shape) * 4 + ch.kci;
+    if (c.kernel_id) *c.kernel_id = ((c.dtype == DC_BF16 ? 1 : 0) * kNumShapes + ch.shape) * 4 + ch.kci;
     if (ch.lds > 64 * 1024) {
         hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)ch.lds);
         if (a != hipSuccess) return a;
     }
-    const long groups = (n_units + S.g - 1) / S.g;
+    const long groups = (n_units + g_rt - 1) / g_rt;
     const long wgs = groups * P.R;
     if (wgs > 2147483647L) return hipErrorInvalidValue;
     hipLaunchKernelGGL(fn, dim3((unsigned)wgs), dim3(S.wm * S.wn * S.wk * 64), ch.lds, st, P);

@@ -99,6 +99,15 @@ struct Profile {
     std::vector<uint8_t> used;
 };
 
+// Second stream and events for running a frame's matching while the previous frame's layers are
+// still executing (Section 7.6: the two stages can be carried out asynchronously).
+struct Overlap {
+    hipStream_t aux = nullptr;
+    hipEvent_t upload_done[2] = {nullptr, nullptr};   // plan upload from staging half 0 / 1 has completed
+    bool pending[2] = {false, false};
+    int parity = 0;
+};
+
 inline size_t dtype_size(int dtype) { return dtype == DC_BF16 ? 2 : 4; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
