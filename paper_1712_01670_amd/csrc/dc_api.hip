@@ -99,7 +99,7 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
                      const void* cache_prev, void* out, int n_streams, int Hin, int Win, int dtype,
                      const ConvTiling& tiling, const LayerPlan* plan, const PlanAddr* addr, hipStream_t st,
                      Profile* prof = nullptr, int gemm_slot = -1, int copy_slot = -1, int* kernel_id = nullptr,
-                     bool copy_done = false) {
+                     bool copy_done = false, void* scratch = nullptr, size_t scratch_bytes = 0) {
     const int Hout = (Hin + 2 * l.p - l.k) / l.s + 1, Wout = (Win + 2 * l.p - l.k) / l.s + 1;
     ConvLaunch c;
     c.kernel_id = kernel_id;
@@ -108,6 +108,7 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
     c.n_streams = n_streams; c.Hin = Hin; c.Win = Win; c.Cin = l.cin;
     c.Hout = Hout; c.Wout = Wout; c.Cout = l.cout; c.k = l.k; c.s = l.s; c.p = l.p; c.relu = l.relu;
     c.dtype = dtype; c.tiling = tiling;
+    c.scratch = scratch; c.scratch_bytes = scratch_bytes;
     if (!plan) {
         c.tiles = nullptr; c.n_tiles = 0; c.rects = nullptr; c.ranges = nullptr;
         Bracket b(prof, gemm_slot, st);
@@ -215,7 +216,7 @@ int32_t dc_overlap_destroy(void* overlap) {
 
 int32_t dc_conv_kernel_name(int32_t kernel_id, char* buf, size_t n) {
     if (!buf) return DC_ERR_NULL_PTR;
-    if (n < 2 || kernel_id < 0 || kernel_id >= 24) return DC_ERR_INVALID_ARG;
+    if (n < 2 || kernel_id < 0 || kernel_id >= 96) return DC_ERR_INVALID_ARG;
     conv_kernel_name(kernel_id, buf, n);
     return DC_OK;
 }
@@ -294,7 +295,7 @@ int32_t dc_conv_workspace_bytes(const dc_layer* layer, int32_t n_streams, int32_
         size_t b = plan_bytes(n_streams, Hout, Wout, pick_tiling(*layer, Hout, Wout, n_streams, dtype), max_rects);
         worst = b > worst ? b : worst;
     }
-    *dev_bytes = worst;
+    *dev_bytes = align_up(worst, 256) + kConvScratchBytes;   // plan + room for partial sums of a split K
     *host_bytes = worst;
     return DC_OK;
 }
@@ -314,7 +315,7 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
     hipStream_t st = as_stream(stream);
     if (!regions || !cache_prev)
         return run_conv_planned(*layer, in, weights, bias, nullptr, out, n_streams, Hin, Win, dtype, tiling, nullptr,
-                                nullptr, st);
+                                nullptr, st, nullptr, -1, -1, nullptr, false, ws_dev, ws_dev ? ws_dev_bytes : 0);
     if (out == cache_prev) return DC_ERR_INVALID_ARG;
     int max_rects = 0;
     for (int s = 0; s < n_streams; ++s) {
@@ -336,8 +337,11 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
     }
     PlanAddr addr = pack_plan(plan, static_cast<unsigned char*>(ws_host), static_cast<unsigned char*>(ws_dev));
     DC_TRY_HIP(hipMemcpyAsync(ws_dev, ws_host, addr.bytes, hipMemcpyHostToDevice, st));
+    // whatever the workspace holds beyond the plan serves as scratch for partial sums
+    const size_t plan_end = align_up(addr.bytes, 256);
+    unsigned char* scratch = plan_end < ws_dev_bytes ? static_cast<unsigned char*>(ws_dev) + plan_end : nullptr;
     return run_conv_planned(*layer, in, weights, bias, cache_prev, out, n_streams, Hin, Win, dtype, tiling, &plan,
-                            &addr, st);
+                            &addr, st, nullptr, -1, -1, nullptr, false, scratch, scratch ? ws_dev_bytes - plan_end : 0);
 }
 
 int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n_pixels, int32_t c_frame, int32_t c_tensor,
@@ -390,7 +394,7 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
     total += align_up((size_t)n_layers * sizeof(CopyLayerDev), 256);
     const size_t nb = (size_t)n_streams * (H / block) * (W / block);
     size_t match_host = align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
-    *dev_bytes = total;
+    *dev_bytes = total + kConvScratchBytes;   // plans, then room for partial sums of a split K
     *host_bytes = 2 * total + match_host;   // two staging halves (used alternately with an overlap handle)
     return DC_OK;
 }
@@ -597,6 +601,10 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     }
 
     // ---- layers ----
+    // the tail of the device workspace (beyond every plan) holds the partial sums of a split K
+    unsigned char* conv_scratch = nullptr;
+    if (ws_dev && ws_dev_bytes >= kConvScratchBytes)
+        conv_scratch = static_cast<unsigned char*>(ws_dev) + (ws_dev_bytes - kConvScratchBytes) / 256 * 256;
     for (int i = 0; i < n_layers; ++i) {
         const dc_layer& l = layers[i];
         const int a = l.in0, t = i + 1;
@@ -606,7 +614,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                                       cached ? tensors_prev[t] : nullptr, tensors_cur[t], n_streams, hs[a], ws[a], dtype,
                                       tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st,
                                       stats ? static_cast<Profile*>(stats->profile) : nullptr, i, n_layers + i,
-                                      local.layer_kernel_id ? &local.layer_kernel_id[i] : nullptr, copy_fused[i] != 0);
+                                      local.layer_kernel_id ? &local.layer_kernel_id[i] : nullptr, copy_fused[i] != 0,
+                                      conv_scratch, conv_scratch ? kConvScratchBytes : 0);
                 if (rc) return rc;
                 break;
             case DC_MAXPOOL:

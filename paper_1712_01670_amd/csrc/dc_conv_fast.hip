@@ -1,0 +1,456 @@
+// Cache-aware convolution (Section 5 "Reuse", steps 2-3), the kernel for the common layer
+// shape: 3x3 taps, stride 1, channel counts that are whole 64-byte rows, 64 output channels
+// per workgroup.  Same implicit GEMM over 4x4-pixel units as the general kernels, with
+// everything that shapes the inner loop fixed at compile time, so that the loop is straight-line
+// code: LDS reads at register + immediate addresses, no address arithmetic between MFMAs, and
+// exact wait counts between the reads of one K step and the MFMAs of the previous one.
+//
+//   workgroup  = g units (g <= WM*UPW, a launch parameter) x 64 channels x a range of channel chunks
+//   wavefront  = UPW units (slots wave_m, wave_m + WM, ...) x NBW 16-channel blocks
+//   stage      = one kernel row (3 taps) x one channel chunk (KC channels)
+//
+// LDS: the patch of a unit is 6 lines of 8 row slots (6 used), one row = KC channels = RB bytes.
+// Chunk c (16 bytes) of the row at (line py, slot px) sits at chunk position c ^ sw(py, px) with
+// sw = (py % 4) * (4 / RPC) + (px % 4) / RPC, RPC = 256 / RB: the 16 pixels of a unit at any tap
+// then fall into 16 different 16-byte bank groups.  Weight rows use (row / RPC) % NVEC as in the
+// general kernel.  Both buffers are filled by buffer_load ... lds, double-buffered; the patch of
+// the next chunk arrives in three parts, one per stage.
+//
+// Few units and a deep K (the small maps at the end of a stack): the launch splits the channel
+// chunks among ks workgroups per tile, which store fp32 partial sums to scratch memory; a second
+// kernel adds them in a fixed order and applies the epilogue.  Every workgroup then loads only its
+// share of the weights, which is what bounds these layers.
+#include <cstdio>
+#include <cstdlib>
+
+#include "dc_conv_common.h"
+
+namespace dc {
+
+namespace {
+
+template <typename T, int KSZ, int KC, int UPW, int WM, int WN, int NBW>
+__global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
+    typedef Frag<T> F;
+    typedef typename F::vec vec;
+    constexpr int VE = F::VE;
+    constexpr int ES = (int)sizeof(T);
+    constexpr int KG = 4 * VE;                  // K elements per MFMA group
+    constexpr int NW = WM * WN;
+    constexpr int NTHREADS = NW * 64;
+    constexpr int G = WM * UPW;
+    constexpr int NT = WN * NBW * 16;
+    constexpr int GPC = KC / KG;                // K groups per chunk
+    constexpr int NVEC = KC / VE;               // 16-byte chunks per row
+    constexpr int RB = KC * ES;                 // row bytes
+    constexpr int RPC = 256 / RB;               // rows per pass over the banks
+    constexpr int RPI = 64 / NVEC;              // rows per load instruction (1 KiB)
+    constexpr int PWP = 8;                      // row slots per patch line
+    constexpr int PH = 3 + KSZ;                 // patch lines and used slots per line
+    constexpr int PR = PH * PWP;                // LDS rows per unit
+    constexpr int P_INSTR = G * PR / RPI;       // patch load instructions per chunk
+    constexpr int W_INSTR = KSZ * NT / RPI;     // weight load instructions per stage
+    constexpr int NPI = (P_INSTR + NW - 1) / NW;
+    constexpr int NWI = (W_INSTR + NW - 1) / NW;
+    constexpr int PBYTES = P_INSTR * 1024;
+    constexpr int WBYTES = W_INSTR * 1024;
+    constexpr int NS = KSZ * GPC;               // K steps per stage
+    static_assert(KSZ == 3 && RB >= 64 && RB <= 256 && (G * PR) % RPI == 0 && (KSZ * NT) % RPI == 0, "shape");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const Header<G> H(smem);
+    unsigned char* const patch0 = smem + kHeaderBytes;
+    unsigned char* const wts0 = patch0 + 2 * PBYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_n = wave % WN, wave_m = wave / WN;
+    const int l16 = lane & 15, q = lane >> 4;
+
+    int ug, ntile;
+    decode_workgroup(P.R, ug, ntile);
+    const int n0 = ntile * NT;
+    decode_units<G, NTHREADS>(P, H, ug, tid);
+    __syncthreads();
+
+    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.in))), 0, keep_scalar(P.in_bytes), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.w))), 0, keep_scalar(P.w_bytes), kBufferFlags);
+    const int Cin = keep_scalar(P.Cin);
+
+    // ---- load side: instruction j of a buffer fills LDS bytes [1024 j, 1024 j + 1024); this wavefront
+    // issues instructions wave, wave + NW, ...; the lane fills chunk position lane % NVEC of row
+    // j * RPI + lane / NVEC and fetches the logical chunk that belongs there.
+    const int lrow = lane / NVEC, lpos = lane % NVEC;
+    uint32_t pgo[NPI];
+#pragma unroll
+    for (int i = 0; i < NPI; ++i) {
+        const int row = (wave + i * NW) * RPI + lrow;
+        const int g = row / PR, r = row - g * PR;
+        const int py = r / PWP, px = r % PWP;
+        uint32_t off = kOob;
+        if (g < G && px < PH && H.uinfo[4 * g]) {
+            const int iy = H.uinfo[4 * g + 2] - P.p + py, ix = H.uinfo[4 * g + 3] - P.p + px;
+            if (iy >= 0 && iy < P.Hin && ix >= 0 && ix < P.Win) {
+                const int sw = (py % 4) * (4 / RPC) + (px % 4) / RPC;
+                off = (uint32_t)(((H.uinfo[4 * g + 1] * P.Hin + iy) * P.Win + ix) * Cin) * ES + (uint32_t)((lpos ^ sw) << 4);
+            }
+        }
+        pgo[i] = off;
+    }
+    uint32_t wgo[NWI];
+#pragma unroll
+    for (int i = 0; i < NWI; ++i) {
+        const int row = (wave + i * NW) * RPI + lrow;   // tl * NT + n
+        const int tl = row / NT, n = row - tl * NT;
+        const int c = lpos ^ ((row / RPC) % NVEC);
+        wgo[i] = tl < KSZ ? (uint32_t)(((n0 + n) * (KSZ * KSZ) + tl) * Cin) * ES + (uint32_t)(c << 4) : kOob;
+    }
+
+    auto issue_w = [&](int chunk, int ky, int wbuf) {
+        unsigned char* dst = wts0 + wbuf * WBYTES + wave * 1024;
+        const uint32_t so = (uint32_t)(ky * KSZ * Cin + chunk * KC) * ES;
+#pragma unroll
+        for (int i = 0; i < NWI; ++i) {
+            const uint32_t off = wgo[i] + so;   // (a named value: an expression in the builtin's argument list loses the host stub)
+            if ((i + 1) * NW <= W_INSTR || wave + i * NW < W_INSTR)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (__attribute__((address_space(3))) void*)(dst + i * (NW * 1024)),
+                                                         16, off, 0, 0, 0);
+        }
+    };
+    // part < 0: the whole patch; otherwise the instructions with index % KSZ == part
+    auto issue_p = [&](int chunk, int part, int pbuf) {
+        unsigned char* dst = patch0 + pbuf * PBYTES + wave * 1024;
+        const uint32_t so = (uint32_t)(chunk * KC) * ES;
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) {
+            if (part >= 0 && i % KSZ != part) continue;
+            const uint32_t off = pgo[i] + so;
+            if ((i + 1) * NW <= P_INSTR || wave + i * NW < P_INSTR)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(in_rsrc, (__attribute__((address_space(3))) void*)(dst + i * (NW * 1024)),
+                                                         16, off, 0, 0, 0);
+        }
+    };
+
+    // ---- read side: byte address of this lane's row and chunk for every tap and K group
+    int paddr[KSZ * KSZ][GPC];
+    {
+        const int oy = l16 >> 2, ox = l16 & 3;
+#pragma unroll
+        for (int t = 0; t < KSZ * KSZ; ++t) {
+            const int py = oy + t / KSZ, px = ox + t % KSZ;
+            const int sw = (py % 4) * (4 / RPC) + (px % 4) / RPC;
+#pragma unroll
+            for (int g = 0; g < GPC; ++g)
+                paddr[t][g] = (wave_m * PR + py * PWP + px) * RB + (((g * 4 + q) ^ sw) << 4);
+        }
+    }
+    int waddr[GPC];
+#pragma unroll
+    for (int g = 0; g < GPC; ++g)
+        waddr[g] = (wave_n * NBW * 16 + l16) * RB + (((g * 4 + q) ^ ((l16 / RPC) % NVEC)) << 4);
+
+    floatx4 acc[UPW][NBW];
+#pragma unroll
+    for (int u = 0; u < UPW; ++u)
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) acc[u][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int cb = keep_scalar((int)blockIdx.y * P.chunks_per_split);
+    const int ce0 = cb + P.chunks_per_split;
+    const int ce = keep_scalar(ce0 < P.n_chunks ? ce0 : P.n_chunks);
+
+    // Loads of stage s = 3 c + ky (c counts this workgroup's chunks): the weights of kernel row ky and a
+    // third of a patch: stage 3c+1, 3c+2 and 3c+3 bring parts 0, 1 and 2 of chunk c+1.  They are issued
+    // two stages ahead, right after the barrier that ends the reads of the buffers they overwrite.
+    const int n_ch = ce - cb;
+    auto issue_stage = [&](int c, int ky, int s) {     // ky is a compile-time constant at every call
+        if (c >= n_ch) return;
+        issue_w(cb + c, ky, s & 1);
+        if (ky == 0) { if (c > 0) issue_p(cb + c, KSZ - 1, c & 1); }
+        else if (c + 1 < n_ch) issue_p(cb + c + 1, ky - 1, (c + 1) & 1);
+    };
+    vec x[2][UPW], w[2][NBW];
+    auto frag = [&](int pbuf, int wbuf, int ky, int st, int b) {
+        const int kx = st / GPC, g = st % GPC;
+        const unsigned char* xp = patch0 + pbuf * PBYTES + paddr[ky * KSZ + kx][g];
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) x[b][u] = *reinterpret_cast<const vec*>(xp + u * (WM * PR * RB));
+        const unsigned char* wp = wts0 + wbuf * WBYTES + waddr[g] + kx * (NT * RB);
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) w[b][j] = *reinterpret_cast<const vec*>(wp + j * (16 * RB));
+    };
+    auto mma = [&](int b) {
+#pragma unroll
+        for (int e = 0; e < F::NE; ++e)
+#pragma unroll
+            for (int u = 0; u < UPW; ++u)
+#pragma unroll
+                for (int j = 0; j < NBW; ++j) F::mma1(w[b][j], x[b][u], acc[u][j], e);
+    };
+
+    issue_p(cb, -1, 0);
+    issue_w(cb, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    issue_stage(0, 1, 1);
+    frag(0, 0, 0, 0, 0);
+    int sidx = 0;
+    for (int c = 0; c < n_ch; ++c) {
+        const int pbuf = c & 1;
+#pragma unroll
+        for (int ky = 0; ky < KSZ; ++ky, ++sidx) {
+            // fragments of step 0 of this stage are on their way (buffer (ky * NS) & 1)
+#pragma unroll
+            for (int st = 0; st + 1 < NS; ++st) {
+                frag(pbuf, sidx & 1, ky, st + 1, (ky * NS + st + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mma((ky * NS + st) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // Last step: first end the stage for the memory system.  After the barrier every wavefront has
+            // its last fragments of this stage in registers and the loads of the next stage are in LDS.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (ky == 0) issue_stage(c, 2, sidx + 2);
+            else issue_stage(c + 1, ky - 1, sidx + 2);
+            if (ky + 1 < KSZ) frag(pbuf, (sidx + 1) & 1, ky + 1, 0, ((ky + 1) * NS) & 1);
+            else if (c + 1 < n_ch) frag(pbuf ^ 1, (sidx + 1) & 1, 0, 0, (KSZ * NS) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma((ky * NS + NS - 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if ((KSZ * NS) & 1) {   // the next chunk expects its first fragments in buffer 0
+#pragma unroll
+            for (int u = 0; u < UPW; ++u) x[0][u] = x[1][u];
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) w[0][j] = w[1][j];
+        }
+    }
+
+    if (P.ks == 1) {
+        epilogue<T, G, UPW, NBW>(P, H, acc, wave_m, WM, n0 + wave_n * NBW * 16, l16, q);
+        return;
+    }
+    // partial sums: [split][unit][pixel][channel]
+    float* part = P.partial + (size_t)blockIdx.y * P.n_units * 16 * P.Cout;
+#pragma unroll
+    for (int u = 0; u < UPW; ++u) {
+        const int g = wave_m + u * WM;
+        if (!H.uinfo[4 * g]) continue;
+        float* px = part + ((size_t)(ug * P.g_rt + g) * 16 + l16) * P.Cout + n0 + wave_n * NBW * 16 + 4 * q;
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) *reinterpret_cast<floatx4*>(px + j * 16) = acc[u][j];
+    }
+}
+
+// Adds the partial sums of the ks workgroups of every tile in a fixed order and applies the epilogue.
+// One thread per (unit, pixel, four channels).
+template <typename T>
+__global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
+    typedef Frag<T> F;
+    const int c4n = P.Cout >> 2;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t total = (size_t)P.n_units * 16 * c4n;
+    if (idx >= total) return;
+    const int co = (int)(idx % c4n) * 4;
+    const size_t pix = idx / c4n;
+    const int l16 = (int)(pix & 15), u = (int)(pix >> 4);
+    int stream, uy, ux, mixed = 0;
+    if (P.units) {
+        const TileDev t = P.units[u];
+        stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.mixed;
+    } else {
+        const int per = P.units_x * P.units_y;
+        stream = u / per;
+        const int r = u - stream * per;
+        uy = r / P.units_x; ux = r - uy * P.units_x;
+    }
+    const int y = uy * 4 + (l16 >> 2), x = ux * 4 + (l16 & 3);
+    if (y >= P.Hout || x >= P.Wout) return;
+    if (mixed) {
+        const RangeDev rg = P.ranges[stream];
+        for (int i = 0; i < rg.count; ++i) {
+            const RectDev r = P.rects[rg.begin + i];
+            if (x >= r.x && x < r.x + r.w && y >= r.y && y < r.y + r.h) return;   // keeps the copied value
+        }
+    }
+    const size_t split_stride = (size_t)P.n_units * 16 * P.Cout;
+    const float* p = P.partial + pix * P.Cout + co;
+    floatx4 v = *reinterpret_cast<const floatx4*>(p);
+    for (int s = 1; s < P.ks; ++s) v += *reinterpret_cast<const floatx4*>(p + s * split_stride);
+    if (P.bias) v += *reinterpret_cast<const floatx4*>(P.bias + co);
+    if (P.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+    T* out = reinterpret_cast<T*>(P.out) + (((size_t)stream * P.Hout + y) * P.Wout + x) * P.Cout + co;
+    F::store4(out, v);
+}
+
+// ---- kernel table -----------------------------------------------------------------------
+constexpr int kWM = 2, kWN = 4, kNBW = 1, kNT = kWN * kNBW * 16, kMaxUPW = 8;
+typedef void (*KernelFn)(ConvParams);
+
+#define DC_F(T, KC, U) conv_fast_kernel<T, 3, KC, U, kWM, kWN, kNBW>
+template <typename T, int KC, int U>
+hipError_t fast_launch_one(dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+    auto fn = DC_F(T, KC, U);
+    if (lds > 64 * 1024) {
+        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (a != hipSuccess) return a;
+    }
+    hipLaunchKernelGGL((DC_F(T, KC, U)), grid, dim3(kWM * kWN * 64), lds, st, P);
+    return hipGetLastError();
+}
+template <typename T, int KC>
+hipError_t fast_launch_upw(int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+    switch (upw) {
+        case 1: return fast_launch_one<T, KC, 1>(grid, lds, st, P);
+        case 2: return fast_launch_one<T, KC, 2>(grid, lds, st, P);
+        case 3: return fast_launch_one<T, KC, 3>(grid, lds, st, P);
+        case 4: return fast_launch_one<T, KC, 4>(grid, lds, st, P);
+        case 5: return fast_launch_one<T, KC, 5>(grid, lds, st, P);
+        case 6: return fast_launch_one<T, KC, 6>(grid, lds, st, P);
+        case 7: return fast_launch_one<T, KC, 7>(grid, lds, st, P);
+        default: return fast_launch_one<T, KC, 8>(grid, lds, st, P);
+    }
+}
+// chunk index: KC = KG, 2 KG
+hipError_t fast_launch(bool bf16, int kci, int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+    if (bf16) return kci ? fast_launch_upw<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_upw<__hip_bfloat16, 32>(upw, grid, lds, st, P);
+    return kci ? fast_launch_upw<float, 32>(upw, grid, lds, st, P) : fast_launch_upw<float, 16>(upw, grid, lds, st, P);
+}
+
+size_t fast_lds_bytes(int kci, int upw) {
+    const int rpi = 16 >> kci;            // rows per load instruction: RB = 64 << kci
+    return kHeaderBytes + 2 * (size_t)(kWM * upw * 48 / rpi) * 1024 + 2 * (size_t)(3 * kNT / rpi) * 1024;
+}
+
+struct FastChoice { int g, ks, kci; double cost; };
+
+// Cycle model of one launch: per stage the longer of the MFMA time and the time to bring the
+// stage's bytes into LDS, plus a fixed cost per stage and per workgroup; workgroups run in rounds of
+// one per CU.  ks > 1 adds the reduction kernel.
+FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) {
+    static double bw = -1, stage_fix = 0, wg_fix = 0, red_fix = 0;
+    if (bw < 0) {
+        const char* e = getenv("DC_CONV_MODEL");   // "bytes/clk/CU,stage,wg,reduce" (experiments)
+        bw = 24; stage_fix = 400; wg_fix = 6000; red_fix = 9000;
+        if (e) sscanf(e, "%lf,%lf,%lf,%lf", &bw, &stage_fix, &wg_fix, &red_fix);
+    }
+    const bool bf16 = c.dtype == DC_BF16;
+    const int esz = bf16 ? 2 : 4, kg = bf16 ? 32 : 16;
+    const int R = c.Cout / kNT;
+    FastChoice best{0, 0, 0, 1e300};
+    for (int kci = 0; kci < 2; ++kci) {
+        const int kc = kg << kci;
+        if (c.Cin % kc) continue;
+        const int n_chunks = c.Cin / kc, gpc = 1 << kci, rb = kc * esz;
+        for (int g = 1; g <= kWM * kMaxUPW; ++g) {
+            const int upw = (g + kWM - 1) / kWM;
+            if (fast_lds_bytes(kci, upw) > 160 * 1024) continue;
+            const long groups = (n_units + g - 1) / g;
+            int last_cps = 0;
+            for (int ks = 1; ks <= n_chunks && ks <= 64; ++ks) {
+                const int cps = (n_chunks + ks - 1) / ks;
+                if (cps == last_cps) continue;        // same split as a smaller ks
+                last_cps = cps;
+                const int ks_eff = (n_chunks + cps - 1) / cps;
+                if (ks_eff > 1 && (size_t)ks_eff * n_units * 16 * c.Cout * 4 > scratch_bytes) continue;
+                const double mfma = (bf16 ? 16.0 : 128.0) * upw * kNBW * 3 * gpc * 2;
+                const double load = ((double)g * 36 * rb / 3 + 3.0 * kNT * rb) / bw;
+                const double stage = (mfma > load ? mfma : load) + stage_fix;
+                const double wg = wg_fix + cps * 3 * stage;
+                const long wgs = groups * R * ks_eff;
+                double cost = (double)((wgs + 255) / 256) * wg;
+                if (ks_eff > 1) cost += red_fix + (double)(ks_eff + 1) * n_units * 16 * c.Cout * 4 / 1200.0;
+                if (cost < best.cost) best = FastChoice{g, ks_eff, kci, cost};
+            }
+        }
+    }
+    return best;
+}
+
+}  // namespace
+
+// Ids 64.. name the instantiations of this file: 64 + ((bf16 * 2 + kci) * 8 + UPW - 1).
+void conv_fast_kernel_name(int id, char* buf, size_t n) {
+    const int v = id - 64, upw = v % 8 + 1, kci = (v / 8) % 2, bf16 = v / 16;
+    snprintf(buf, n, "conv_fast_kernel<%s, 3, %d, %d, %d, %d, %d>", bf16 ? "__hip_bfloat16" : "float",
+             (bf16 ? 32 : 16) << kci, upw, kWM, kWN, kNBW);
+}
+
+// Launches the layer with the kernel of this file if its shape qualifies; returns false otherwise.
+bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err) {
+    static int enabled = -1;
+    if (enabled < 0) { const char* e = getenv("DC_CONV_FAST"); enabled = e ? atoi(e) : 1; }
+    const size_t esz = dtype_size(c.dtype);
+    if (!enabled || c.k != 3 || c.s != 1 || c.Cout % kNT != 0 || c.Cin % (64 / esz) != 0) return false;
+    if (reinterpret_cast<uintptr_t>(c.in) % 16 || reinterpret_cast<uintptr_t>(c.w) % 16) return false;
+    size_t scratch = c.scratch && reinterpret_cast<uintptr_t>(c.scratch) % 16 == 0 ? c.scratch_bytes : 0;
+    if (scratch > kConvScratchBytes) scratch = kConvScratchBytes;
+    FastChoice ch = choose_fast(c, n_units, scratch);
+    {
+        static int f_g = -1, f_ks = 0, f_kci = 0, f_live = 0;
+        if (f_g < 0 || f_live) {
+            const char* e = getenv("DC_CONV_FORCE");   // "g,ks,kci[,1: read again at every launch]" (experiments)
+            f_g = 0;
+            if (e) sscanf(e, "%d,%d,%d,%d", &f_g, &f_ks, &f_kci, &f_live);
+        }
+        if (f_g > 0) {
+            const int kc = (c.dtype == DC_BF16 ? 32 : 16) << f_kci;
+            const int upw = (f_g + kWM - 1) / kWM;
+            if (f_g <= kWM * kMaxUPW && f_kci >= 0 && f_kci < 2 && c.Cin % kc == 0 && fast_lds_bytes(f_kci, upw) <= 160 * 1024) {
+                const int n_chunks = c.Cin / kc;
+                int ks = f_ks < 1 ? 1 : (f_ks > n_chunks ? n_chunks : f_ks);
+                const int cps = (n_chunks + ks - 1) / ks;
+                ks = (n_chunks + cps - 1) / cps;
+                if (ks == 1 || (size_t)ks * n_units * 16 * c.Cout * 4 <= scratch) ch = FastChoice{f_g, ks, f_kci, 0};
+            }
+        }
+    }
+    if (ch.g < 1) return false;
+    {
+        static int debug = -1;
+        if (debug < 0) { const char* e = getenv("DC_CONV_DEBUG"); debug = e ? atoi(e) : 0; }
+        if (debug)
+            fprintf(stderr, "[conv_fast] units=%ld %dx%d cin=%d cout=%d -> g=%d ks=%d kci=%d model=%.0f cycles\n", n_units, c.Hout,
+                    c.Wout, c.Cin, c.Cout, ch.g, ch.ks, ch.kci, ch.cost);
+    }
+    const int upw = (ch.g + kWM - 1) / kWM;
+    const int kc = (c.dtype == DC_BF16 ? 32 : 16) << ch.kci;
+    const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
+
+    ConvParams P{};
+    P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
+    P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
+    P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
+    P.units = c.tiles; P.n_units = (int)n_units; P.rects = c.rects; P.ranges = c.ranges;
+    P.units_x = units_x; P.units_y = units_y;
+    P.ph = 6; P.pw = 6;
+    P.g_rt = ch.g;
+    P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * c.Cin * esz);
+    P.w_bytes = (uint32_t)((size_t)c.Cout * 9 * c.Cin * esz);
+    P.out_vec = reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0);
+    P.n_chunks = c.Cin / kc;
+    P.R = c.Cout / kNT;
+    P.ks = ch.ks;
+    P.chunks_per_split = (P.n_chunks + ch.ks - 1) / ch.ks;
+    P.partial = ch.ks > 1 ? static_cast<float*>(c.scratch) : nullptr;
+    if (ch.ks > 1 && !P.out_vec) return false;
+
+    if (c.kernel_id) *c.kernel_id = 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
+    const long groups = (n_units + ch.g - 1) / ch.g;
+    const long wgx = groups * P.R;
+    if (wgx > 2147483647L || ch.ks > 65535) { *err = hipErrorInvalidValue; return true; }
+    *err = fast_launch(c.dtype == DC_BF16, ch.kci, upw, dim3((unsigned)wgx, (unsigned)ch.ks), fast_lds_bytes(ch.kci, upw), st, P);
+    if (*err != hipSuccess || ch.ks == 1) return true;
+    const size_t total = (size_t)n_units * 16 * (c.Cout / 4);
+    if (c.dtype == DC_BF16)
+        hipLaunchKernelGGL(conv_split_reduce_kernel<__hip_bfloat16>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, P);
+    else
+        hipLaunchKernelGGL(conv_split_reduce_kernel<float>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, P);
+    *err = hipGetLastError();
+    return true;
+}
+
+}  // namespace dc

@@ -68,8 +68,14 @@ struct ConvLaunch {
     const RectDev* rects;  // device
     const RangeDev* ranges;
     int* kernel_id = nullptr;  // out (host): which instantiation ran
+    void* scratch = nullptr;   // device memory for partial sums when K is split among workgroups (optional)
+    size_t scratch_bytes = 0;
 };
+// Upper bound of the scratch a convolution launch can make use of.
+constexpr size_t kConvScratchBytes = (size_t)32 << 20;
+bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err);
 void conv_kernel_name(int id, char* buf, size_t n);
+void conv_fast_kernel_name(int id, char* buf, size_t n);
 hipError_t launch_conv(const ConvLaunch& c, hipStream_t st);
 
 hipError_t launch_shifted_copy(const RectDev* rects_dev, int n_rects, int max_rect_w, int max_rect_h,
