@@ -29,6 +29,65 @@ namespace dc {
 
 namespace {
 
+// LDS header of this kernel.  uq[g] = {byte offset in the input of the patch origin of unit g (the
+// pixel at (-p, -p) of the unit; may lie outside the tensor), row and column of that origin, element
+// offset in the output of the unit's first pixel}; skip[16 g + i] = 1: pixel i of unit g is not stored
+// (missing unit, outside the map, or inside a reusable rectangle).
+template <int G>
+struct FastHeader {
+    int4* uq;
+    int* ustream;
+    unsigned char* ukind;   // 0: no unit, 1: unit, 2: unit with reusable pixels
+    unsigned char* skip;
+    __device__ __forceinline__ explicit FastHeader(unsigned char* smem)
+        : uq(reinterpret_cast<int4*>(smem)), ustream(reinterpret_cast<int*>(smem + 16 * G)),
+          ukind(smem + 20 * G), skip(smem + 21 * G) {}   // 37 G <= 592 bytes
+};
+
+template <int G, int NTHREADS, int ES>
+__device__ __forceinline__ void decode_units_fast(const ConvParams& P, const FastHeader<G>& H, int ug, int tid) {
+    static_assert(G * 16 <= NTHREADS, "one thread per pixel of the unit table");
+    if (tid < G) {
+        const int u = ug * P.g_rt + tid;
+        const bool valid = tid < P.g_rt && u < P.n_units;
+        int stream = 0, uy = 0, ux = 0, mixed = 0;
+        if (valid) {
+            if (P.units) {
+                const TileDev t = P.units[u];
+                stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.mixed;
+            } else {   // raster order; exact for u * (units per map) < 2^32 (checked by the launcher)
+                stream = fast_div(u, P.npix_magic);
+                const int r = u - stream * (P.units_x * P.units_y);
+                uy = fast_div(r, P.pw_magic); ux = r - uy * P.units_x;
+            }
+        }
+        const int oy = uy * 4 - P.p, ox = ux * 4 - P.p;
+        int4 v;
+        v.x = ((stream * P.Hin + oy) * P.Win + ox) * P.Cin * ES;
+        v.y = valid ? oy : -(1 << 24);      // every pixel of a missing unit fails the range test
+        v.z = ox;
+        v.w = ((stream * P.Hout + uy * 4) * P.Wout + ux * 4) * P.Cout;
+        H.uq[tid] = v;
+        H.ustream[tid] = stream;
+        H.ukind[tid] = (unsigned char)(valid ? (mixed ? 2 : 1) : 0);
+    }
+    __syncthreads();
+    if (tid < G * 16) {
+        const int g = tid >> 4, kind = H.ukind[g];
+        const int y = H.uq[g].y + P.p + ((tid >> 2) & 3), x = H.uq[g].z + P.p + (tid & 3);
+        unsigned char hit = (kind == 0 || y >= P.Hout || x >= P.Wout) ? 1 : 0;
+        if (!hit && kind == 2) {
+            const RangeDev rg = P.ranges[H.ustream[g]];
+            for (int i = 0; i < rg.count; ++i) {
+                const RectDev r = P.rects[rg.begin + i];
+                hit |= (x >= r.x && x < r.x + r.w && y >= r.y && y < r.y + r.h) ? 1 : 0;
+            }
+        }
+        H.skip[tid] = hit;
+    }
+    __syncthreads();
+}
+
 template <typename T, int KSZ, int KC, int UPW, int WM, int WN, int NBW>
 __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     typedef Frag<T> F;
@@ -55,10 +114,10 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     constexpr int PBYTES = P_INSTR * 1024;
     constexpr int WBYTES = W_INSTR * 1024;
     constexpr int NS = KSZ * GPC;               // K steps per stage
-    static_assert(KSZ == 3 && RB >= 64 && RB <= 256 && (G * PR) % RPI == 0 && (KSZ * NT) % RPI == 0, "shape");
+    static_assert(KSZ == 3 && RB >= 64 && RB <= 128 && (G * PR) % RPI == 0 && (KSZ * NT) % RPI == 0, "shape");
 
     extern __shared__ __align__(16) unsigned char smem[];
-    const Header<G> H(smem);
+    const FastHeader<G> H(smem);
     unsigned char* const patch0 = smem + kHeaderBytes;
     unsigned char* const wts0 = patch0 + 2 * PBYTES;
 
@@ -70,8 +129,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     int ug, ntile;
     decode_workgroup(P.R, ug, ntile);
     const int n0 = ntile * NT;
-    decode_units<G, NTHREADS>(P, H, ug, tid);
-    __syncthreads();
+    decode_units_fast<G, NTHREADS, ES>(P, H, ug, tid);
 
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.in))), 0, keep_scalar(P.in_bytes), kBufferFlags);
@@ -83,21 +141,26 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     // issues instructions wave, wave + NW, ...; the lane fills chunk position lane % NVEC of row
     // j * RPI + lane / NVEC and fetches the logical chunk that belongs there.
     const int lrow = lane / NVEC, lpos = lane % NVEC;
+    // patch: IPU instructions per unit; instruction j covers lines [(j % IPU) * RPI / 8, ...) of unit j / IPU,
+    // so the slot column and the line within the instruction are fixed per lane
+    constexpr int IPU = PR / RPI;
     uint32_t pgo[NPI];
+    {
+        const int px = lrow % PWP, pyl = lrow / PWP;
+        const int CinES = Cin * ES;
+        const int pxoff = px * CinES;
 #pragma unroll
-    for (int i = 0; i < NPI; ++i) {
-        const int row = (wave + i * NW) * RPI + lrow;
-        const int g = row / PR, r = row - g * PR;
-        const int py = r / PWP, px = r % PWP;
-        uint32_t off = kOob;
-        if (g < G && px < PH && H.uinfo[4 * g]) {
-            const int iy = H.uinfo[4 * g + 2] - P.p + py, ix = H.uinfo[4 * g + 3] - P.p + px;
-            if (iy >= 0 && iy < P.Hin && ix >= 0 && ix < P.Win) {
-                const int sw = (py % 4) * (4 / RPC) + (px % 4) / RPC;
-                off = (uint32_t)(((H.uinfo[4 * g + 1] * P.Hin + iy) * P.Win + ix) * Cin) * ES + (uint32_t)((lpos ^ sw) << 4);
-            }
+        for (int i = 0; i < NPI; ++i) {
+            const int j = wave + i * NW;
+            int unit = j / IPU;
+            const int part = j - unit * IPU;
+            unit = unit < G ? unit : G - 1;
+            const int4 uq = H.uq[unit];
+            const int py = part * (RPI / PWP) + pyl;
+            const int sw = (py % 4) * (4 / RPC) + (px % 4) / RPC;
+            const bool ok = px < PH && (unsigned)(uq.y + py) < (unsigned)P.Hin && (unsigned)(uq.z + px) < (unsigned)P.Win;
+            pgo[i] = ok ? (uint32_t)(uq.x + py * (P.Win * CinES) + pxoff + ((lpos ^ sw) << 4)) : kOob;
         }
-        pgo[i] = off;
     }
     uint32_t wgo[NWI];
 #pragma unroll
@@ -156,6 +219,13 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     for (int u = 0; u < UPW; ++u)
 #pragma unroll
         for (int j = 0; j < NBW; ++j) acc[u][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // epilogue operands that do not depend on the accumulators
+    const int chan = n0 + wave_n * NBW * 16 + 4 * q;
+    floatx4 bias[NBW];
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+        bias[j] = (P.bias && P.ks == 1) ? *reinterpret_cast<const floatx4*>(P.bias + chan + j * 16) : floatx4{0.f, 0.f, 0.f, 0.f};
 
     const int cb = keep_scalar((int)blockIdx.y * P.chunks_per_split);
     const int ce0 = cb + P.chunks_per_split;
@@ -230,16 +300,29 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     }
 
     if (P.ks == 1) {
-        epilogue<T, G, UPW, NBW>(P, H, acc, wave_m, WM, n0 + wave_n * NBW * 16, l16, q);
+        T* const out = reinterpret_cast<T*>(P.out) + ((l16 >> 2) * P.Wout + (l16 & 3)) * P.Cout + chan;
+        const bool relu = P.relu != 0;
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            const int g = wave_m + u * WM;
+            if (H.skip[g * 16 + l16]) continue;
+            T* px = out + H.uq[g].w;
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) {
+                floatx4 v = acc[u][j] + bias[j];
+                if (relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+                F::store4(px + j * 16, v);
+            }
+        }
         return;
     }
     // partial sums: [split][unit][pixel][channel]
-    float* part = P.partial + (size_t)blockIdx.y * P.n_units * 16 * P.Cout;
+    float* part = P.partial + (size_t)blockIdx.y * P.n_units * 16 * P.Cout + (size_t)l16 * P.Cout + chan;
 #pragma unroll
     for (int u = 0; u < UPW; ++u) {
         const int g = wave_m + u * WM;
-        if (!H.uinfo[4 * g]) continue;
-        float* px = part + ((size_t)(ug * P.g_rt + g) * 16 + l16) * P.Cout + n0 + wave_n * NBW * 16 + 4 * q;
+        if (!H.ukind[g]) continue;
+        float* px = part + (size_t)(ug * P.g_rt + g) * 16 * P.Cout;
 #pragma unroll
         for (int j = 0; j < NBW; ++j) *reinterpret_cast<floatx4*>(px + j * 16) = acc[u][j];
     }
@@ -327,14 +410,16 @@ size_t fast_lds_bytes(int kci, int upw) {
 
 struct FastChoice { int g, ks, kci; double cost; };
 
-// Cycle model of one launch: per stage the longer of the MFMA time and the time to bring the
-// stage's bytes into LDS, plus a fixed cost per stage and per workgroup; workgroups run in rounds of
-// one per CU.  ks > 1 adds the reduction kernel.
+// Cycle model of one launch.  A workgroup spends its stages (the longer of the MFMA time and the time to
+// bring the stage's bytes into LDS) plus fixed costs per stage and per workgroup (decode, address set-up,
+// first loads, epilogue).  A CU runs ceil(workgroups / 256) of them; as many as LDS and registers allow
+// are resident together, and only the stage work of resident workgroups adds up, the fixed costs overlap.
+// ks > 1 adds the reduction kernel.
 FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) {
     static double bw = -1, stage_fix = 0, wg_fix = 0, red_fix = 0;
     if (bw < 0) {
         const char* e = getenv("DC_CONV_MODEL");   // "bytes/clk/CU,stage,wg,reduce" (experiments)
-        bw = 24; stage_fix = 400; wg_fix = 6000; red_fix = 9000;
+        bw = 24; stage_fix = 250; wg_fix = 4500; red_fix = 7000;
         if (e) sscanf(e, "%lf,%lf,%lf,%lf", &bw, &stage_fix, &wg_fix, &red_fix);
     }
     const bool bf16 = c.dtype == DC_BF16;
@@ -358,10 +443,16 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
                 if (ks_eff > 1 && (size_t)ks_eff * n_units * 16 * c.Cout * 4 > scratch_bytes) continue;
                 const double mfma = (bf16 ? 16.0 : 128.0) * upw * kNBW * 3 * gpc * 2;
                 const double load = ((double)g * 36 * rb / 3 + 3.0 * kNT * rb) / bw;
-                const double stage = (mfma > load ? mfma : load) + stage_fix;
-                const double wg = wg_fix + cps * 3 * stage;
+                const double work = cps * 3 * (1.12 * mfma > load ? 1.12 * mfma : load);
+                const double fixed = wg_fix + 400.0 * upw + cps * 3 * stage_fix;
                 const long wgs = groups * R * ks_eff;
-                double cost = (double)((wgs + 255) / 256) * wg;
+                const long per_cu = (wgs + 255) / 256;
+                const int vgprs = kci ? 64 + 18 * upw : 44 + 16 * upw;
+                long occ = (long)(160 * 1024 / fast_lds_bytes(kci, upw));
+                if (occ > 512 / vgprs / 2) occ = 512 / vgprs / 2;
+                if (occ > 4) occ = 4;
+                if (occ < 1) occ = 1;
+                double cost = (double)per_cu * work + (double)((per_cu + occ - 1) / occ) * fixed;
                 if (ks_eff > 1) cost += red_fix + (double)(ks_eff + 1) * n_units * 16 * c.Cout * 4 / 1200.0;
                 if (cost < best.cost) best = FastChoice{g, ks_eff, kci, cost};
             }
@@ -386,6 +477,12 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     const size_t esz = dtype_size(c.dtype);
     if (!enabled || c.k != 3 || c.s != 1 || c.Cout % kNT != 0 || c.Cin % (64 / esz) != 0) return false;
     if (reinterpret_cast<uintptr_t>(c.in) % 16 || reinterpret_cast<uintptr_t>(c.w) % 16) return false;
+    if (reinterpret_cast<uintptr_t>(c.out) % 16 || (c.bias && reinterpret_cast<uintptr_t>(c.bias) % 16)) return false;
+    {   // 32-bit output offsets, exact magic-number division of the unit index
+        const double units_map = (double)((c.Hout + 3) / 4) * ((c.Wout + 3) / 4);
+        if ((double)c.n_streams * c.Hout * c.Wout * c.Cout >= 2147483648.0 || (double)n_units * units_map >= 4294967296.0)
+            return false;
+    }
     size_t scratch = c.scratch && reinterpret_cast<uintptr_t>(c.scratch) % 16 == 0 ? c.scratch_bytes : 0;
     if (scratch > kConvScratchBytes) scratch = kConvScratchBytes;
     FastChoice ch = choose_fast(c, n_units, scratch);
@@ -427,16 +524,17 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     P.units = c.tiles; P.n_units = (int)n_units; P.rects = c.rects; P.ranges = c.ranges;
     P.units_x = units_x; P.units_y = units_y;
     P.ph = 6; P.pw = 6;
+    P.npix_magic = (uint32_t)((0x100000000ull + (uint64_t)(units_x * units_y) - 1) / (uint64_t)(units_x * units_y));
+    P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)units_x - 1) / (uint64_t)units_x);
     P.g_rt = ch.g;
     P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * c.Cin * esz);
     P.w_bytes = (uint32_t)((size_t)c.Cout * 9 * c.Cin * esz);
-    P.out_vec = reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0);
+    P.out_vec = 1;
     P.n_chunks = c.Cin / kc;
     P.R = c.Cout / kNT;
     P.ks = ch.ks;
     P.chunks_per_split = (P.n_chunks + ch.ks - 1) / ch.ks;
     P.partial = ch.ks > 1 ? static_cast<float*>(c.scratch) : nullptr;
-    if (ch.ks > 1 && !P.out_vec) return false;
 
     if (c.kernel_id) *c.kernel_id = 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
     const long groups = (n_units + ch.g - 1) / ch.g;
