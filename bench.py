@@ -26,6 +26,16 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense matrix peaks
 PEAK_HBM_GBS = 8000.0
 
+# HBM traffic per launch of the conv kernels on this workload, from two rocprofv3 --pmc runs of this file
+# (profiles/vgg16_224_f32_hbm_traffic.txt): kernel -> (FETCH_SIZE, WRITE_SIZE) counter averages.  A plain
+# 256 MiB device copy reads 131087 / 262144 on the same counters, hence the scale factors.
+PMC_TRAFFIC = {
+    "conv_fast_kernel<float, 3, 32, 1, 2, 4, 1>": (6716.0, 2013.9),
+    "conv_fast_kernel<float, 3, 32, 3, 2, 4, 1>": (7835.8, 5014.2),
+    "conv_fast_kernel<float, 3, 16, 5, 2, 4, 1>": (8801.4, 9407.4),
+}
+PMC_SCALE = (2.0, 1.0)      # KiB of HBM traffic per counter unit (fetch, write)
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -131,7 +141,9 @@ def main():
         "frac": dflops / (dms * 1e-3) / 1e12 / peak,
         "avg_launch_us": dms / dlaunch * 1e3, "launches": dlaunch,
         "issued_tflops": dissued / (dms * 1e-3) / 1e12,
-        "traffic": None,
+        "traffic": (sum(c * f for c, f in zip(PMC_TRAFFIC[dname], PMC_SCALE)) * 1024.0
+                    if (args.dtype == "f32" and n == 1 and dname in PMC_TRAFFIC) else None),
+        "traffic_unit": "bytes of HBM traffic per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
         "all_conv": {"achieved": all_flops / (all_ms * 1e-3) / 1e12, "frac": all_flops / (all_ms * 1e-3) / 1e12 / peak,
                      "ms_per_step": all_ms / args.steps},
         "copy": {"bound": "hbm", "achieved": (copy_bytes / (copy_ms * 1e-3) / 1e9) if copy_ms else None,

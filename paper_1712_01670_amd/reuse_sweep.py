@@ -1,0 +1,97 @@
+#!/usr/bin/env python3
+"""Frame time of the cache-aware path against the input reuse ratio (Section 7.2 reports the
+saving per scenario; here the scenario is synthetic and the reuse ratio is the knob).
+
+For every target reuse ratio a 60-frame video is generated (panning background, a band of fresh
+noise sized to the non-reusable fraction, scene cut at frame 30), resident in HBM, and run three
+ways on one GPU:
+  cached   every frame but the first of a scene goes through matching + cached convolution
+           (no expiry), which isolates the cost of a cached frame;
+  expiry   as deployed: a full frame every N frames (Section 5, N = 10);
+  full     every frame computed in full (no cache).
+One JSON line per ratio: measured reuse ratio, fraction of MACs needed and issued, frames/s of
+the three modes and the saving 1 - t_mode / t_full.
+
+    python paper_1712_01670_amd/reuse_sweep.py [--net darknet19|vgg16] [--size 416] [--dtype bf16|f32]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--net", choices=["darknet19", "vgg16"], default="darknet19")
+    ap.add_argument("--size", type=int, default=416)
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16")
+    ap.add_argument("--ratios", default="0,0.25,0.5,0.75,0.95")
+    ap.add_argument("--frames", type=int, default=60)
+    ap.add_argument("--repeats", type=int, default=3)
+    ap.add_argument("--expiry", type=int, default=10)
+    args = ap.parse_args()
+
+    import numpy as np
+    import torch
+    from paper_1712_01670_amd import binding, synth
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    H = W = args.size
+    layers = synth.darknet19() if args.net == "darknet19" else synth.vgg16()
+    ws, bs = synth.he_weights(layers, 1)
+    dt = binding.DC_BF16 if args.dtype == "bf16" else binding.DC_F32
+    cut = args.frames // 2
+
+    def timed(runner, video, mode):
+        def one_pass(collect):
+            macs = [0, 0, 0]
+            reuse = []
+            for f in range(args.frames):
+                scene_start = f == 0 or f == cut
+                if scene_start:
+                    runner.reset()
+                runner.step(video[f:f + 1], force_full=(mode == "full"))
+                if collect:
+                    torch.cuda.synchronize()
+                    st = runner.stats
+                    macs[0] += st.macs_full; macs[1] += st.macs_needed; macs[2] += st.macs_issued
+                    if not st.full:
+                        reuse.append(st.n_reusable_blocks / st.n_blocks)
+            return macs, reuse
+        macs, reuse = one_pass(True)          # warm-up and statistics
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.repeats):
+            one_pass(False)
+        torch.cuda.synchronize()
+        dt_s = (time.perf_counter() - t0) / (args.repeats * args.frames)
+        return dt_s, macs, reuse
+
+    for i, r in enumerate(float(x) for x in args.ratios.split(",")):
+        video = torch.from_numpy(synth.reuse_sweep_video(4000 + i, r, n_frames=args.frames, H=H, W=W, cut_at=cut)).to(dev)
+        out = {"target_reuse": r, "net": args.net, "size": args.size, "dtype": args.dtype, "frames": args.frames}
+        for mode, expiry in (("cached", 1 << 30), ("expiry", args.expiry), ("full", 1 << 30)):
+            runner = binding.StackRunner(layers, ws, bs, 1, H, W, 3, block=16, radius=16, dtype=dt, expiry=expiry)
+            t, macs, reuse = timed(runner, video, mode)
+            out[mode] = {"frames_per_s": 1.0 / t, "ms_per_frame": t * 1e3}
+            if mode != "full":
+                out[mode]["mac_fraction_needed"] = macs[1] / max(macs[0], 1)
+                out[mode]["mac_fraction_issued"] = macs[2] / max(macs[0], 1)
+            if mode == "cached":
+                out["measured_reuse"] = float(np.mean(reuse)) if reuse else 0.0
+            del runner
+        for mode in ("cached", "expiry"):
+            out[mode]["saving"] = 1.0 - out[mode]["ms_per_frame"] / out["full"]["ms_per_frame"]
+        print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -2,7 +2,7 @@
 counters: run it under the same --pmc command as bench.py and divide the counter it shows for the
 copy kernel by the bytes printed here.
 
-    rocprofv3 --pmc FETCH_SIZE -d out -o calib -- python3 -m paper_1712_01670_amd.traffic_calib
+    rocprofv3 --pmc FETCH_SIZE -d out -o calib -- python3 paper_1712_01670_amd/traffic_calib.py
 """
 import torch
 
