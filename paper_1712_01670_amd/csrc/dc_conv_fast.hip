@@ -369,6 +369,94 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     F::store4(out, v);
 }
 
+// ---- first layer -------------------------------------------------------------------------
+// A pixel of the network input is one 16-byte vector (4 fp32 or 8 bf16 channels, the frame's three
+// plus zero padding).  The three taps of a kernel row are then consecutive pixels: 48 bytes of
+// input against 48 bytes of weights, which is one K group of the MFMA with the fourth quarter
+// zeroed.  K is 3 groups in total, so there is nothing to stage: every wavefront takes one unit
+// (16 pixels x NB 16-channel blocks), loads its fragments from memory directly and keeps the
+// weights in registers while it walks over the unit list.
+template <typename T, int NB>
+__global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
+    typedef Frag<T> F;
+    typedef typename F::vec vec;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, q = lane >> 4;
+    const int n0 = blockIdx.y * (NB * 16);
+    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.in), 0, P.in_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.w), 0, P.w_bytes, kBufferFlags);
+
+    vec wv[3][NB];
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const uint32_t off = q < 3 ? (uint32_t)(((n0 + j * 16 + l16) * 9 + ky * 3 + q) * 16) : kOob;
+            wv[ky][j] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, off, 0, 0));
+        }
+    const int chan = n0 + 4 * q;
+    floatx4 bias[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+        bias[j] = P.bias ? *reinterpret_cast<const floatx4*>(P.bias + chan + j * 16) : floatx4{0.f, 0.f, 0.f, 0.f};
+    const bool relu = P.relu != 0;
+    const int per = P.units_x * P.units_y;
+
+    for (int u = blockIdx.x * 4 + wave; u < P.n_units; u += gridDim.x * 4) {
+        int stream, uy, ux, mixed = 0;
+        if (P.units) {
+            const TileDev t = P.units[u];
+            stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.mixed;
+        } else {
+            stream = fast_div(u, P.npix_magic);
+            const int r = u - stream * per;
+            uy = fast_div(r, P.pw_magic); ux = r - uy * P.units_x;
+        }
+        const int y = uy * 4 + (l16 >> 2), x = ux * 4 + (l16 & 3);
+        vec xv[3];
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) {
+            const int iy = y - P.p + ky, ix = x - P.p + q;
+            const bool ok = q < 3 && (unsigned)iy < (unsigned)P.Hin && (unsigned)ix < (unsigned)P.Win;
+            const uint32_t off = ok ? (uint32_t)(((stream * P.Hin + iy) * P.Win + ix) * 16) : kOob;
+            xv[ky] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0));
+        }
+        floatx4 acc[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+            for (int e = 0; e < F::NE; ++e)
+#pragma unroll
+                for (int j = 0; j < NB; ++j) F::mma1(wv[ky][j], xv[ky], acc[j], e);
+        bool keep = y < P.Hout && x < P.Wout;
+        if (keep && mixed) {
+            const RangeDev rg = P.ranges[stream];
+            for (int i = 0; i < rg.count; ++i) {
+                const RectDev r = P.rects[rg.begin + i];
+                if (x >= r.x && x < r.x + r.w && y >= r.y && y < r.y + r.h) keep = false;   // holds the copied value
+            }
+        }
+        if (!keep) continue;
+        T* px = reinterpret_cast<T*>(P.out) + ((stream * P.Hout + y) * P.Wout + x) * P.Cout + chan;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            floatx4 v = acc[j] + bias[j];
+            if (relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+            F::store4(px + j * 16, v);
+        }
+    }
+}
+
+template <typename T>
+hipError_t first_launch(int nb, dim3 grid, hipStream_t st, const ConvParams& P) {
+    if (nb == 4) hipLaunchKernelGGL((conv_first_kernel<T, 4>), grid, dim3(256), 0, st, P);
+    else if (nb == 2) hipLaunchKernelGGL((conv_first_kernel<T, 2>), grid, dim3(256), 0, st, P);
+    else hipLaunchKernelGGL((conv_first_kernel<T, 1>), grid, dim3(256), 0, st, P);
+    return hipGetLastError();
+}
+
 // ---- kernel table -----------------------------------------------------------------------
 constexpr int kWM = 2, kWN = 4, kNBW = 1, kNT = kWN * kNBW * 16, kMaxUPW = 8;
 typedef void (*KernelFn)(ConvParams);
@@ -463,8 +551,12 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
 
 }  // namespace
 
-// Ids 64.. name the instantiations of this file: 64 + ((bf16 * 2 + kci) * 8 + UPW - 1).
+// Ids 64.. name the instantiations of this file: 64 + ((bf16 * 2 + kci) * 8 + UPW - 1), 96.. the first-layer kernel.
 void conv_fast_kernel_name(int id, char* buf, size_t n) {
+    if (id >= 96) {   // 96 + bf16 * 3 + {0, 1, 2}: conv_first_kernel with 1, 2, 4 channel blocks
+        snprintf(buf, n, "conv_first_kernel<%s, %d>", (id - 96) / 3 ? "__hip_bfloat16" : "float", 1 << ((id - 96) % 3));
+        return;
+    }
     const int v = id - 64, upw = v % 8 + 1, kci = (v / 8) % 2, bf16 = v / 16;
     snprintf(buf, n, "conv_fast_kernel<%s, 3, %d, %d, %d, %d, %d>", bf16 ? "__hip_bfloat16" : "float",
              (bf16 ? 32 : 16) << kci, upw, kWM, kWN, kNBW);
@@ -475,6 +567,29 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     static int enabled = -1;
     if (enabled < 0) { const char* e = getenv("DC_CONV_FAST"); enabled = e ? atoi(e) : 1; }
     const size_t esz = dtype_size(c.dtype);
+    if (enabled && c.k == 3 && c.s == 1 && c.Cin * esz == 16 && c.Cout % 16 == 0 &&
+        reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
+        reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
+        const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
+        if ((double)c.n_streams * c.Hout * c.Wout * c.Cout < 2147483648.0 && (double)n_units * units_x * units_y < 4294967296.0) {
+            ConvParams P{};
+            P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
+            P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
+            P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
+            P.units = c.tiles; P.n_units = (int)n_units; P.rects = c.rects; P.ranges = c.ranges;
+            P.units_x = units_x; P.units_y = units_y;
+            P.npix_magic = (uint32_t)((0x100000000ull + (uint64_t)(units_x * units_y) - 1) / (uint64_t)(units_x * units_y));
+            P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)units_x - 1) / (uint64_t)units_x);
+            P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * 16);
+            P.w_bytes = (uint32_t)((size_t)c.Cout * 9 * 16);
+            const int nb = c.Cout % 64 == 0 ? 4 : (c.Cout % 32 == 0 ? 2 : 1);
+            const long wgx = (n_units + 3) / 4 < 2048 ? (n_units + 3) / 4 : 2048;   // four units at a time, at most 8 workgroups per CU
+            if (c.kernel_id) *c.kernel_id = 96 + (c.dtype == DC_BF16 ? 3 : 0) + (nb == 4 ? 2 : (nb == 2 ? 1 : 0));
+            const dim3 grid((unsigned)wgx, (unsigned)(c.Cout / (16 * nb)));
+            *err = c.dtype == DC_BF16 ? first_launch<__hip_bfloat16>(nb, grid, st, P) : first_launch<float>(nb, grid, st, P);
+            return true;
+        }
+    }
     if (!enabled || c.k != 3 || c.s != 1 || c.Cout % kNT != 0 || c.Cin % (64 / esz) != 0) return false;
     if (reinterpret_cast<uintptr_t>(c.in) % 16 || reinterpret_cast<uintptr_t>(c.w) % 16) return false;
     if (reinterpret_cast<uintptr_t>(c.out) % 16 || (c.bias && reinterpret_cast<uintptr_t>(c.bias) % 16)) return false;
