@@ -433,6 +433,10 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     }
     Overlap* ov = static_cast<Overlap*>(overlap);
     hipStream_t st = as_stream(stream);
+    // the tail of the device workspace (beyond every plan) holds the partial sums of a split K
+    unsigned char* conv_scratch = nullptr;
+    if (ws_dev && ws_dev_bytes >= kConvScratchBytes)
+        conv_scratch = static_cast<unsigned char*>(ws_dev) + (ws_dev_bytes - kConvScratchBytes) / 256 * 256;
     const int gh = H / block, gw = W / block;
     const size_t nb = (size_t)n_streams * gh * gw;
 
@@ -601,10 +605,6 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     }
 
     // ---- layers ----
-    // the tail of the device workspace (beyond every plan) holds the partial sums of a split K
-    unsigned char* conv_scratch = nullptr;
-    if (ws_dev && ws_dev_bytes >= kConvScratchBytes)
-        conv_scratch = static_cast<unsigned char*>(ws_dev) + (ws_dev_bytes - kConvScratchBytes) / 256 * 256;
     for (int i = 0; i < n_layers; ++i) {
         const dc_layer& l = layers[i];
         const int a = l.in0, t = i + 1;

@@ -115,16 +115,16 @@ __device__ __forceinline__ int fast_div(int n, uint32_t magic) { return (int)__u
 
 // ---- pieces shared by both kernels ------------------------------------------------
 
-// LDS header: uinfo[G][4] = {valid, stream, oy0, ox0}, tmask[G*16], umixed[G]
+// LDS header: uinfo[G][4] = {valid, stream, oy0, ox0}, tmask[G*16], umask[G] (reusable pixels of the unit)
 template <int G>
 struct Header {
     int* uinfo;
     unsigned char* tmask;
-    unsigned char* umixed;
+    unsigned short* umask;
     __device__ __forceinline__ explicit Header(unsigned char* smem)
         : uinfo(reinterpret_cast<int*>(smem)),
           tmask(reinterpret_cast<unsigned char*>(smem) + 16 * G),
-          umixed(reinterpret_cast<unsigned char*>(smem) + 32 * G) {}
+          umask(reinterpret_cast<unsigned short*>(smem + 32 * G)) {}
 };
 
 // workgroup -> (unit group, channel tile); channel tiles spread over the 8 XCDs so that each
@@ -149,7 +149,7 @@ __device__ __forceinline__ void decode_units(const ConvParams& P, const Header<G
         if (valid) {
             if (P.units) {
                 const TileDev t = P.units[u];
-                stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.mixed;
+                stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.reuse_mask;
             } else {
                 const int per = P.units_x * P.units_y;
                 stream = u / per;
@@ -159,20 +159,11 @@ __device__ __forceinline__ void decode_units(const ConvParams& P, const Header<G
         }
         H.uinfo[4 * tid + 0] = valid; H.uinfo[4 * tid + 1] = stream;
         H.uinfo[4 * tid + 2] = uy * 4; H.uinfo[4 * tid + 3] = ux * 4;
-        H.umixed[tid] = (unsigned char)mixed;
+        H.umask[tid] = (unsigned short)mixed;
     }
     __syncthreads();
-    for (int m = tid; m < G * 16; m += NTHREADS) {   // per-pixel reuse mask of mixed units
-        const int g = m >> 4;
-        unsigned char hit = 0;
-        if (H.umixed[g]) {
-            const int y = H.uinfo[4 * g + 2] + ((m >> 2) & 3), x = H.uinfo[4 * g + 3] + (m & 3);
-            const RangeDev rg = P.ranges[H.uinfo[4 * g + 1]];
-            for (int i = 0; i < rg.count; ++i) {
-                const RectDev r = P.rects[rg.begin + i];
-                hit |= (x >= r.x && x < r.x + r.w && y >= r.y && y < r.y + r.h) ? 1 : 0;
-            }
-        }
+    for (int m = tid; m < G * 16; m += NTHREADS) {   // per-pixel reuse flags
+        const unsigned char hit = (unsigned char)((H.umask[m >> 4] >> (m & 15)) & 1);
         H.tmask[m] = hit;
     }
 }

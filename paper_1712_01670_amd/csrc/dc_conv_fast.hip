@@ -37,11 +37,11 @@ template <int G>
 struct FastHeader {
     int4* uq;
     int* ustream;
-    unsigned char* ukind;   // 0: no unit, 1: unit, 2: unit with reusable pixels
+    int* ukind;             // -1: no unit, otherwise the 16-bit mask of the unit's reusable pixels
     unsigned char* skip;
     __device__ __forceinline__ explicit FastHeader(unsigned char* smem)
         : uq(reinterpret_cast<int4*>(smem)), ustream(reinterpret_cast<int*>(smem + 16 * G)),
-          ukind(smem + 20 * G), skip(smem + 21 * G) {}   // 37 G <= 592 bytes
+          ukind(reinterpret_cast<int*>(smem + 20 * G)), skip(smem + 24 * G) {}   // 40 G <= 640 bytes
 };
 
 template <int G, int NTHREADS, int ES>
@@ -54,7 +54,7 @@ __device__ __forceinline__ void decode_units_fast(const ConvParams& P, const Fas
         if (valid) {
             if (P.units) {
                 const TileDev t = P.units[u];
-                stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.mixed;
+                stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.reuse_mask;
             } else {   // raster order; exact for u * (units per map) < 2^32 (checked by the launcher)
                 stream = fast_div(u, P.npix_magic);
                 const int r = u - stream * (P.units_x * P.units_y);
@@ -69,20 +69,13 @@ __device__ __forceinline__ void decode_units_fast(const ConvParams& P, const Fas
         v.w = ((stream * P.Hout + uy * 4) * P.Wout + ux * 4) * P.Cout;
         H.uq[tid] = v;
         H.ustream[tid] = stream;
-        H.ukind[tid] = (unsigned char)(valid ? (mixed ? 2 : 1) : 0);
+        H.ukind[tid] = valid ? mixed : -1;
     }
     __syncthreads();
     if (tid < G * 16) {
         const int g = tid >> 4, kind = H.ukind[g];
         const int y = H.uq[g].y + P.p + ((tid >> 2) & 3), x = H.uq[g].z + P.p + (tid & 3);
-        unsigned char hit = (kind == 0 || y >= P.Hout || x >= P.Wout) ? 1 : 0;
-        if (!hit && kind == 2) {
-            const RangeDev rg = P.ranges[H.ustream[g]];
-            for (int i = 0; i < rg.count; ++i) {
-                const RectDev r = P.rects[rg.begin + i];
-                hit |= (x >= r.x && x < r.x + r.w && y >= r.y && y < r.y + r.h) ? 1 : 0;
-            }
-        }
+        const unsigned char hit = (kind < 0 || y >= P.Hout || x >= P.Wout || ((kind >> (tid & 15)) & 1)) ? 1 : 0;
         H.skip[tid] = hit;
     }
     __syncthreads();
@@ -225,7 +218,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     floatx4 bias[NBW];
 #pragma unroll
     for (int j = 0; j < NBW; ++j)
-        bias[j] = (P.bias && P.ks == 1) ? *reinterpret_cast<const floatx4*>(P.bias + chan + j * 16) : floatx4{0.f, 0.f, 0.f, 0.f};
+        bias[j] = P.bias ? *reinterpret_cast<const floatx4*>(P.bias + chan + j * 16) : floatx4{0.f, 0.f, 0.f, 0.f};
 
     const int cb = keep_scalar((int)blockIdx.y * P.chunks_per_split);
     const int ce0 = cb + P.chunks_per_split;
@@ -321,7 +314,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
 #pragma unroll
     for (int u = 0; u < UPW; ++u) {
         const int g = wave_m + u * WM;
-        if (!H.ukind[g]) continue;
+        if (H.ukind[g] < 0) continue;
         float* px = part + (size_t)(ug * P.g_rt + g) * 16 * P.Cout;
 #pragma unroll
         for (int j = 0; j < NBW; ++j) *reinterpret_cast<floatx4*>(px + j * 16) = acc[u][j];
@@ -343,7 +336,7 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     int stream, uy, ux, mixed = 0;
     if (P.units) {
         const TileDev t = P.units[u];
-        stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.mixed;
+        stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.reuse_mask;
     } else {
         const int per = P.units_x * P.units_y;
         stream = u / per;
@@ -352,13 +345,7 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     }
     const int y = uy * 4 + (l16 >> 2), x = ux * 4 + (l16 & 3);
     if (y >= P.Hout || x >= P.Wout) return;
-    if (mixed) {
-        const RangeDev rg = P.ranges[stream];
-        for (int i = 0; i < rg.count; ++i) {
-            const RectDev r = P.rects[rg.begin + i];
-            if (x >= r.x && x < r.x + r.w && y >= r.y && y < r.y + r.h) return;   // keeps the copied value
-        }
-    }
+    if ((mixed >> l16) & 1) return;   // keeps the copied value
     const size_t split_stride = (size_t)P.n_units * 16 * P.Cout;
     const float* p = P.partial + pix * P.Cout + co;
     floatx4 v = *reinterpret_cast<const floatx4*>(p);
@@ -406,7 +393,7 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
         int stream, uy, ux, mixed = 0;
         if (P.units) {
             const TileDev t = P.units[u];
-            stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.mixed;
+            stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.reuse_mask;
         } else {
             stream = fast_div(u, P.npix_magic);
             const int r = u - stream * per;
@@ -430,14 +417,7 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
             for (int e = 0; e < F::NE; ++e)
 #pragma unroll
                 for (int j = 0; j < NB; ++j) F::mma1(wv[ky][j], xv[ky], acc[j], e);
-        bool keep = y < P.Hout && x < P.Wout;
-        if (keep && mixed) {
-            const RangeDev rg = P.ranges[stream];
-            for (int i = 0; i < rg.count; ++i) {
-                const RectDev r = P.rects[rg.begin + i];
-                if (x >= r.x && x < r.x + r.w && y >= r.y && y < r.y + r.h) keep = false;   // holds the copied value
-            }
-        }
+        const bool keep = y < P.Hout && x < P.Wout && !((mixed >> l16) & 1);   // a reusable pixel holds the copied value
         if (!keep) continue;
         T* px = reinterpret_cast<T*>(P.out) + ((stream * P.Hout + y) * P.Wout + x) * P.Cout + chan;
 #pragma unroll

@@ -19,7 +19,7 @@ struct RectDev {
 // One output tile (ty, tx in tile units) that holds at least one non-reusable pixel.
 struct TileDev {
     int32_t stream, ty, tx;
-    int32_t mixed;  // 1: some pixels of the tile are reusable (per-pixel test needed)
+    int32_t reuse_mask;  // bit 4*row + column: that pixel of the 4x4 tile is reusable and keeps the copied value
 };
 // Per-stream slice of the rectangle table.
 struct RangeDev {
@@ -71,6 +71,7 @@ struct ConvLaunch {
     void* scratch = nullptr;   // device memory for partial sums when K is split among workgroups (optional)
     size_t scratch_bytes = 0;
 };
+
 // Upper bound of the scratch a convolution launch can make use of.
 constexpr size_t kConvScratchBytes = (size_t)32 << 20;
 bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err);

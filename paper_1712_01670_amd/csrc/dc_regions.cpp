@@ -147,8 +147,10 @@ int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<d
 
 void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Hout, int Wout, int th,
                  int tw, LayerPlan& plan) {
-    const int tiles_y = (Hout + th - 1) / th, tiles_x = (Wout + tw - 1) / tw;
-    std::vector<int> covered((size_t)tiles_y * tiles_x, 0);
+    // tiles are 4x4 pixels: the reusable pixels of a tile are one 16-bit mask
+    (void)th; (void)tw;
+    const int tiles_y = (Hout + 3) / 4, tiles_x = (Wout + 3) / 4;
+    std::vector<uint16_t> reuse((size_t)tiles_y * tiles_x, 0);
     RangeDev range{(int)plan.rects.size(), 0};
     for (int i = 0; i < n; ++i) {
         const dc_rect& r = rects[i];
@@ -156,21 +158,26 @@ void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Ho
         plan.rects.push_back(RectDev{r.x, r.y, r.w, r.h, stream, dx, dy, 0});
         ++range.count;
         plan.reused_px += (int64_t)r.w * r.h;
-        for (int ty = r.y / th; ty <= (r.y + r.h - 1) / th; ++ty) {
-            int oy = std::min(r.y + r.h, (ty + 1) * th) - std::max(r.y, ty * th);
-            for (int tx = r.x / tw; tx <= (r.x + r.w - 1) / tw; ++tx) {
-                int ox = std::min(r.x + r.w, (tx + 1) * tw) - std::max(r.x, tx * tw);
-                covered[(size_t)ty * tiles_x + tx] += oy * ox;
+        for (int ty = r.y / 4; ty <= (r.y + r.h - 1) / 4; ++ty) {
+            const int ya = std::max(r.y, ty * 4) - ty * 4, yb = std::min(r.y + r.h, ty * 4 + 4) - ty * 4;
+            unsigned rows = 0;                                   // bit 4*y set for the covered rows
+            for (int y = ya; y < yb; ++y) rows |= 1u << (4 * y);
+            for (int tx = r.x / 4; tx <= (r.x + r.w - 1) / 4; ++tx) {
+                const int xa = std::max(r.x, tx * 4) - tx * 4, xb = std::min(r.x + r.w, tx * 4 + 4) - tx * 4;
+                const unsigned cols = ((1u << xb) - 1u) & ~((1u << xa) - 1u);
+                reuse[(size_t)ty * tiles_x + tx] |= (uint16_t)(rows * cols);
             }
         }
     }
     plan.ranges.push_back(range);
     for (int ty = 0; ty < tiles_y; ++ty)
         for (int tx = 0; tx < tiles_x; ++tx) {
-            int area = std::min(th, Hout - ty * th) * std::min(tw, Wout - tx * tw);
-            int cov = covered[(size_t)ty * tiles_x + tx];
-            if (cov >= area) continue;  // every pixel is served by the copy
-            plan.tiles.push_back(TileDev{stream, ty, tx, cov > 0 ? 1 : 0});
+            unsigned inside = 0;                                 // pixels of the tile that lie in the map
+            const int hh = std::min(4, Hout - ty * 4), ww = std::min(4, Wout - tx * 4);
+            for (int y = 0; y < hh; ++y) inside |= ((1u << ww) - 1u) << (4 * y);
+            const unsigned m = reuse[(size_t)ty * tiles_x + tx];
+            if ((m & inside) == inside) continue;  // every pixel is served by the copy
+            plan.tiles.push_back(TileDev{stream, ty, tx, (int32_t)m});
         }
 }
 
