@@ -8,6 +8,8 @@
 // (ssd, |dx|+|dy|, dy, dx) is packed in 64 bits and reduced with wavefront shuffles.
 // Kernel 2 (motion + re-test): every workgroup recomputes the stream's mean motion
 // from the per-block results (a few hundred values) and re-tests its own block.
+#include <cstdlib>
+
 #include "dc_internal.h"
 
 namespace dc {
@@ -26,6 +28,12 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
         unsigned long long o = __shfl_xor(v, off, 64);
         v = o < v ? o : v;
     }
+    return v;
+}
+
+__device__ __forceinline__ int wave_sum_i32(int v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
     return v;
 }
 
@@ -160,10 +168,223 @@ __global__ __launch_bounds__(kSearchThreads) void match_search_kernel(
     }
 }
 
-__device__ __forceinline__ int wave_sum_i32(int v) {
+// ---- search on the matrix cores ----------------------------------------------------------
+// SSD = sum a'^2 + sum b'^2 - 2 sum a'b' with a' = a - 128, b' = b - 128 (signed bytes; the offset
+// cancels in a - b).  The cross term of all candidates of a block is one integer GEMM per window row
+// wr:  X[dx][dy] += A_wr[dx][k] * B_wr[k][dy],  k = byte within the block row,
+//   A_wr[dx][k] = window row wr, byte C*dx + k          (the block-wide run that candidate dx sees)
+//   B_wr[k][dy] = block row wr - dy, byte k              (zero if that is not a row of the block)
+// (dx, dy count from -R), so that the sum over the window rows is the cross term of candidate
+// (dx, dy).  v_mfma_i32_16x16x64_i8 covers 16 dx x 16 dy x 64 bytes; NT x NT tiles cover the
+// (2R+1)^2 candidates, KS K-steps the block row.  sum b'^2 per candidate is a box sum of per-pixel
+// sums.  The wavefronts split the window rows and add their tiles into one copy in LDS (integer
+// atomics: the order does not matter).  The arg-min key is the same as in the scalar kernel, so both give
+// identical results.
+typedef int intx4 __attribute__((ext_vector_type(4)));
+constexpr int kMfmaWaves = 4;           // wavefronts per block: they split the window rows and the summing loops
+constexpr int kMfmaThreads = 64 * kMfmaWaves;
+
+// BT, CT: block edge and channel count when known at compile time (the summing loops are then unrolled and
+// their LDS reads issued together), 0: taken from the arguments.
+template <bool ALIGNED, int NT, int KS, int BT, int CT>
+__global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
+    const uint8_t* __restrict__ cur, const uint8_t* __restrict__ prev, int H, int W, int C_rt, int B_rt,
+    int R, int gw, int gh, int ws, int16_t* __restrict__ mv, uint32_t* __restrict__ best_ssd) {
+    const int B = BT ? BT : B_rt, C = CT ? CT : C_rt;
+    extern __shared__ __align__(16) uint8_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int blk_id = blockIdx.x, stream = blockIdx.y;
+    const int bx = blk_id % gw, by = blk_id / gw;
+    const int x0 = bx * B, y0 = by * B;
+    const int rows = B + 2 * R, cols = rows, nd = 2 * R + 1;
+    const int row_bytes = W * C;
+    const size_t frame_bytes = (size_t)H * row_bytes;
+    const uint8_t* pf = prev + (size_t)stream * frame_bytes;
+    const uint8_t* cf = cur + (size_t)stream * frame_bytes;
+    constexpr int BS = 64 * KS;                       // bytes of a staged block row
+    // LDS: [win rows*ws][blk B*BS][p2 rows*cols ints][h2 rows*nd ints][tiles NT*NT*256 ints][misc][v2 nd*nd ints]
+    uint8_t* win = lds;
+    uint8_t* blk = win + (size_t)rows * ws;
+    int* p2 = reinterpret_cast<int*>(blk + (size_t)B * BS);
+    int* h2 = p2 + rows * cols;
+    int* tiles = h2 + rows * nd + (4 - (rows * cols + rows * nd) % 4) % 4;   // 16-byte aligned
+    int* misc = tiles + NT * NT * 256;
+    unsigned long long* red = reinterpret_cast<unsigned long long*>(misc + kMfmaWaves);   // partial sums a'^2, then the arg-min keys
+    int* v2 = misc + 3 * kMfmaWaves;
+    for (int i = tid; i < NT * NT * 256; i += kMfmaThreads) tiles[i] = 0;
+
+    const int gx0 = (x0 - R) * C;
+    const int a0 = gx0 & ~3;
+    const int skew = gx0 - a0;
+
+    // ---- stage the window (signed bytes; out-of-frame bytes are never part of a valid candidate).  Only the
+    // dwords that hold window bytes are fetched (the rest of a row is only read for candidates beyond the
+    // search range); the loads of a thread are issued eight at a time before any of them is used ----
+    const int wdw = ws / 4;
+    const int ldw = (skew + cols * C + 3) / 4;        // dwords per row that hold window bytes
+    for (int base = 0; base < rows * ldw; base += 8 * kMfmaThreads) {
+        uint32_t v[8];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+        for (int u = 0; u < 8; ++u) {
+            const int i = base + u * kMfmaThreads + tid;
+            const int r = i / ldw, j = i - r * ldw;
+            const int y = y0 - R + r;
+            const int fb = a0 + 4 * j;
+            v[u] = 0x80808080u;
+            if (i < rows * ldw && y >= 0 && y < H) {
+                const uint8_t* src = pf + (size_t)y * row_bytes;
+                if (ALIGNED && fb >= 0 && fb + 3 < row_bytes) {
+                    v[u] = *reinterpret_cast<const uint32_t*>(src + fb);
+                } else {
+                    uint32_t t = 0;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int f = fb + b;
+                        t |= (uint32_t)((f >= 0 && f < row_bytes) ? src[f] : 128) << (8 * b);
+                    }
+                    v[u] = t;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = base + u * kMfmaThreads + tid;
+            const int r = i / ldw, j = i - r * ldw;
+            if (i < rows * ldw) reinterpret_cast<uint32_t*>(win)[r * wdw + j] = v[u] ^ 0x80808080u;
+        }
+    }
+    for (int i = tid; i < rows * (wdw - ldw); i += kMfmaThreads) {   // the tail of every row: any defined value
+        const int r = i / (wdw - ldw), j = ldw + (i - r * (wdw - ldw));
+        reinterpret_cast<uint32_t*>(win)[r * wdw + j] = 0;
+    }
+    // ---- stage the block: signed bytes, true zeros behind the row so that the padding adds nothing ----
+    const int blk_bytes = B * C;
+    int saa = 0;
+    for (int i = tid; i < B * (BS / 4); i += kMfmaThreads) {
+        const int r = i / (BS / 4), j = i - r * (BS / 4);
+        const uint8_t* src = cf + (size_t)(y0 + r) * row_bytes + (size_t)x0 * C;
+        uint32_t v = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int f = 4 * j + b;
+            if (f < blk_bytes) {
+                const int a = (int)src[f] - 128;
+                saa += a * a;
+                v |= (uint32_t)(a & 0xff) << (8 * b);
+            }
+        }
+        reinterpret_cast<uint32_t*>(blk)[i] = v;
+    }
+    saa = wave_sum_i32(saa);
+    __syncthreads();
+    if (lane == 0) misc[wave] = saa;
+
+    // ---- per-pixel sum of squares, then box sums over the block: B columns, then B rows ----
+    const int8_t* swin = reinterpret_cast<const int8_t*>(win);
+    for (int i = tid; i < rows * cols; i += kMfmaThreads) {
+        const int r = i / cols, x = i - r * cols;
+        const int8_t* px = swin + (size_t)r * ws + skew + x * C;
+        int s = 0;
+#pragma unroll
+        for (int c = 0; c < C; ++c) s += (int)px[c] * (int)px[c];
+        p2[i] = s;
+    }
+    __syncthreads();
+    for (int i = tid; i < rows * nd; i += kMfmaThreads) {
+        const int r = i / nd, d = i - r * nd;
+        int s = 0;
+#pragma unroll
+        for (int x = 0; x < B; ++x) s += p2[r * cols + d + x];
+        h2[i] = s;
+    }
+    __syncthreads();
+    for (int i = tid; i < nd * nd; i += kMfmaThreads) {
+        const int dyi = i / nd, dxi = i - dyi * nd;
+        int s = 0;
+#pragma unroll
+        for (int r = 0; r < B; ++r) s += h2[(dyi + r) * nd + dxi];
+        v2[i] = s;
+    }
+
+    // ---- cross terms: this wavefront's share of the window rows ----
+    const int n = lane & 15, kq = lane >> 4;
+    intx4 acc[NT][NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = intx4{0, 0, 0, 0};
+    const int rpw = (rows + kMfmaWaves - 1) / kMfmaWaves;
+    const int wr_end = (wave + 1) * rpw < rows ? (wave + 1) * rpw : rows;
+    for (int wr = wave * rpw; wr < wr_end; ++wr) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            intx4 af[NT], bf[NT];
+#pragma unroll
+            for (int i = 0; i < NT; ++i) {      // lane: candidate dx = 16 i + n, bytes [16 kq, 16 kq + 16) of its run
+                const int o = skew + C * (16 * i + n) + 16 * kq + 64 * ks;
+                const uint32_t* w32 = reinterpret_cast<const uint32_t*>(win + (size_t)wr * ws) + (o >> 2);
+                const int sh = o & 3;
+                uint32_t wv[5];
+#pragma unroll
+                for (int e = 0; e < 5; ++e) wv[e] = w32[e];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) af[i][e] = (int)__builtin_amdgcn_alignbyte(wv[e + 1], wv[e], sh);
+            }
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {      // lane: candidate dy = 16 j + n, block row wr - dy
+                const int r = wr - (16 * j + n);
+                const bool ok = r >= 0 && r < B;
+                const intx4 v = *reinterpret_cast<const intx4*>(blk + (size_t)(ok ? r : 0) * BS + 64 * ks + 16 * kq);
+                bf[j] = ok ? v : intx4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) atomicAdd(&tiles[((i * NT + j) * 64 + lane) * 4 + e], acc[i][j][e]);
+    __syncthreads();
+
+    // ---- SSD and arg-min: tile t is evaluated by wavefront t % kMfmaWaves; lane (n, kq) holds rows
+    // dx = 16 i + 4 kq + e of column dy = 16 j + n ----
+    int saa_all = 0;
+#pragma unroll
+    for (int w = 0; w < kMfmaWaves; ++w) saa_all += misc[w];
+    unsigned long long best = ~0ull;
+    for (int t = wave; t < NT * NT; t += kMfmaWaves) {
+        const int i = t / NT, j = t - i * NT;
+        const intx4 c = *reinterpret_cast<const intx4*>(tiles + (t * 64 + lane) * 4);
+        const int dyi = 16 * j + n;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int dxi = 16 * i + 4 * kq + e;
+            const int dx = dxi - R, dy = dyi - R;
+            if (dxi >= nd || dyi >= nd || x0 + dx < 0 || y0 + dy < 0 || x0 + dx + B > W || y0 + dy + B > H) continue;
+            const uint32_t ssd = (uint32_t)(saa_all + v2[dyi * nd + dxi] - 2 * c[e]);
+            const int ad = (dx < 0 ? -dx : dx) + (dy < 0 ? -dy : dy);
+            const unsigned long long key = ((unsigned long long)ssd << 32) | ((unsigned long long)ad << 16) |
+                                           ((unsigned long long)dyi << 8) | (unsigned long long)dxi;
+            best = key < best ? key : best;
+        }
+    }
+    best = wave_min_u64(best);
+    if (lane == 0) red[wave] = best;
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < kMfmaWaves; ++w) best = red[w] < best ? red[w] : best;
+        const size_t o = (size_t)stream * gh * gw + blk_id;
+        mv[2 * o + 0] = (int16_t)((int)(best & 0xff) - R);
+        mv[2 * o + 1] = (int16_t)((int)((best >> 8) & 0xff) - R);
+        best_ssd[o] = (uint32_t)(best >> 32);
+    }
 }
 
 __device__ __forceinline__ int round_half_away(int num, int den) {
@@ -184,11 +405,23 @@ __global__ __launch_bounds__(64) void motion_retest_kernel(
     const int16_t* smv = mv + (size_t)stream * nb * 2;
     const uint32_t* sbest = best_ssd + (size_t)stream * nb;
     int sx = 0, sy = 0, K = 0;
-    for (int i = lane; i < nb; i += 64) {
-        if (sbest[i] <= max_ssd) {
-            sx += smv[2 * i];
-            sy += smv[2 * i + 1];
-            ++K;
+    for (int base = 0; base < nb; base += 4 * 64) {     // four independent loads per lane at a time
+        uint32_t bs[4];
+        int vx[4], vy[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = base + u * 64 + lane;
+            const bool in = i < nb;
+            bs[u] = in ? sbest[i] : 0xffffffffu;
+            vx[u] = in ? smv[2 * i] : 0;
+            vy[u] = in ? smv[2 * i + 1] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool pass = base + u * 64 + lane < nb && bs[u] <= max_ssd;
+            sx += pass ? vx[u] : 0;
+            sy += pass ? vy[u] : 0;
+            K += pass ? 1 : 0;
         }
     }
     sx = wave_sum_i32(sx);
@@ -213,11 +446,18 @@ __global__ __launch_bounds__(64) void motion_retest_kernel(
         const uint8_t* cf = cur + stream * frame_bytes;
         const uint8_t* pf = prev + stream * frame_bytes;
         const int rb = B * C;
-        for (int i = lane; i < B * rb; i += 64) {
-            int r = i / rb, j = i - r * rb;
-            int a = cf[((size_t)(y0 + r) * W + x0) * C + j];
-            int b = pf[((size_t)(y0 + my + r) * W + x0 + mx) * C + j];
-            ssd += (uint32_t)((a - b) * (a - b));
+        for (int base = 0; base < B * rb; base += 8 * 64) {   // eight independent byte pairs per lane at a time
+            int a[8], b[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = base + u * 64 + lane;
+                const int r = i / rb, j = i - r * rb;
+                const bool in = i < B * rb;
+                a[u] = in ? cf[((size_t)(y0 + r) * W + x0) * C + j] : 0;
+                b[u] = in ? pf[((size_t)(y0 + my + r) * W + x0 + mx) * C + j] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) ssd += (uint32_t)((a[u] - b[u]) * (a[u] - b[u]));
         }
         ssd = (uint32_t)wave_sum_i32((int)ssd);
     }
@@ -231,11 +471,46 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
                         int32_t* gmv, int32_t* n_pass, uint8_t* mask, hipStream_t st) {
     const int gh = H / B, gw = W / B;
     const int rows = B + 2 * R;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(prev) & 3) == 0) && ((W * C) % 4 == 0);
+    dim3 grid(gh * gw, n_streams);
+    static int use_mfma = -1;
+    if (use_mfma < 0) { const char* e = getenv("DC_MATCH_MFMA"); use_mfma = e ? atoi(e) : 1; }
+    const int nt = (2 * R + 1 + 15) / 16, ksteps = (B * C + 63) / 64;
+    bool done = false;
+    if (use_mfma && nt <= 3 && ksteps <= 2 && B + 2 * R <= 255) {
+        const int nd = 2 * R + 1;
+        const int need = 3 + C * (16 * nt - 1) + 64 * ksteps + 4, real = 3 + rows * C + 4;
+        const int wsm = (int)align_up((size_t)(need > real ? need : real), 16);
+        const size_t ldsm = (size_t)rows * wsm + (size_t)B * 64 * ksteps + (size_t)(rows * rows + rows * nd) * 4 +
+                            (size_t)nt * nt * 1024 + 16 + (size_t)(3 * kMfmaWaves + nd * nd) * 4;
+        if (ldsm <= 64 * 1024) {
+#define DC_MFMA_LAUNCH(AL, NTT, KSS, BT, CT)                                                                          \
+    hipLaunchKernelGGL((match_mfma_kernel<AL, NTT, KSS, BT, CT>), grid, dim3(kMfmaThreads), ldsm, st, cur, prev, H, W, C, \
+                       B, R, gw, gh, wsm, mv, best_ssd)
+#define DC_MFMA_KS(AL, NTT)                            \
+    do {                                               \
+        if (ksteps == 1) DC_MFMA_LAUNCH(AL, NTT, 1, 0, 0); \
+        else DC_MFMA_LAUNCH(AL, NTT, 2, 0, 0);             \
+    } while (0)
+#define DC_MFMA_NT(AL)                                                     \
+    do {                                                                   \
+        if (nt == 3 && B == 16 && C == 3) DC_MFMA_LAUNCH(AL, 3, 1, 16, 3); \
+        else if (nt == 2 && B == 8 && C == 3) DC_MFMA_LAUNCH(AL, 2, 1, 8, 3); \
+        else if (nt == 1) DC_MFMA_KS(AL, 1);                               \
+        else if (nt == 2) DC_MFMA_KS(AL, 2);                               \
+        else DC_MFMA_KS(AL, 3);                                            \
+    } while (0)
+            if (aligned) DC_MFMA_NT(true);
+            else DC_MFMA_NT(false);
+#undef DC_MFMA_NT
+#undef DC_MFMA_KS
+#undef DC_MFMA_LAUNCH
+            done = true;
+        }
+    }
     const int ws = (int)align_up((size_t)rows * C + 3, 4) + 8;  // skew (<=3) + window + over-read of the last dword pair
     const int cs = (int)align_up((size_t)B * C, 4);
     const size_t lds = (size_t)rows * ws + (size_t)B * cs;
-    const bool aligned = ((reinterpret_cast<uintptr_t>(prev) & 3) == 0) && ((W * C) % 4 == 0);
-    dim3 grid(gh * gw, n_streams);
 #define DC_MATCH_LAUNCH(AL, CD)                                                                                      \
     hipLaunchKernelGGL((match_search_kernel<AL, CD>), grid, dim3(kSearchThreads), lds, st, cur, prev, H, W, C, B, R, \
                        gw, gh, ws, cs, mv, best_ssd)
@@ -244,7 +519,7 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
         if (aligned) DC_MATCH_LAUNCH(true, CD); \
         else DC_MATCH_LAUNCH(false, CD);        \
     } while (0)
-    switch (cs / 4) {
+    if (!done) switch (cs / 4) {
         case 6: DC_MATCH_ALIGN(6); break;     // 8x8x3
         case 8: DC_MATCH_ALIGN(8); break;     // 10x10x3, 8x8x4
         case 12: DC_MATCH_ALIGN(12); break;   // 16x16x3
