@@ -122,8 +122,6 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     int ug, ntile;
     decode_workgroup(P.R, ug, ntile);
     const int n0 = ntile * NT;
-    decode_units_fast<G, NTHREADS, ES>(P, H, ug, tid);
-
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.in))), 0, keep_scalar(P.in_bytes), kBufferFlags);
     const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -134,6 +132,34 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     // issues instructions wave, wave + NW, ...; the lane fills chunk position lane % NVEC of row
     // j * RPI + lane / NVEC and fetches the logical chunk that belongs there.
     const int lrow = lane / NVEC, lpos = lane % NVEC;
+    uint32_t wgo[NWI];
+#pragma unroll
+    for (int i = 0; i < NWI; ++i) {
+        const int row = (wave + i * NW) * RPI + lrow;   // tl * NT + n
+        const int tl = row / NT, n = row - tl * NT;
+        const int c = lpos ^ ((row / RPC) % NVEC);
+        wgo[i] = tl < KSZ ? (uint32_t)(((n0 + n) * (KSZ * KSZ) + tl) * Cin) * ES + (uint32_t)(c << 4) : kOob;
+    }
+
+    auto issue_w = [&](int chunk, int ky, int wbuf) {
+        unsigned char* dst = wts0 + wbuf * WBYTES + wave * 1024;
+        const uint32_t so = (uint32_t)(ky * KSZ * Cin + chunk * KC) * ES;
+#pragma unroll
+        for (int i = 0; i < NWI; ++i) {
+            const uint32_t off = wgo[i] + so;   // (a named value: an expression in the builtin's argument list loses the host stub)
+            if ((i + 1) * NW <= W_INSTR || wave + i * NW < W_INSTR)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (__attribute__((address_space(3))) void*)(dst + i * (NW * 1024)),
+                                                         16, off, 0, 0, 0);
+        }
+    };
+    const int cb = keep_scalar((int)blockIdx.y * P.chunks_per_split);
+    const int ce0 = cb + P.chunks_per_split;
+    const int ce = keep_scalar(ce0 < P.n_chunks ? ce0 : P.n_chunks);
+
+    issue_w(cb, 0, 0);   // the first weights do not depend on the units: they travel while the unit table is decoded
+
+    decode_units_fast<G, NTHREADS, ES>(P, H, ug, tid);
+
     // patch: IPU instructions per unit; instruction j covers lines [(j % IPU) * RPI / 8, ...) of unit j / IPU,
     // so the slot column and the line within the instruction are fixed per lane
     constexpr int IPU = PR / RPI;
@@ -155,26 +181,6 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
             pgo[i] = ok ? (uint32_t)(uq.x + py * (P.Win * CinES) + pxoff + ((lpos ^ sw) << 4)) : kOob;
         }
     }
-    uint32_t wgo[NWI];
-#pragma unroll
-    for (int i = 0; i < NWI; ++i) {
-        const int row = (wave + i * NW) * RPI + lrow;   // tl * NT + n
-        const int tl = row / NT, n = row - tl * NT;
-        const int c = lpos ^ ((row / RPC) % NVEC);
-        wgo[i] = tl < KSZ ? (uint32_t)(((n0 + n) * (KSZ * KSZ) + tl) * Cin) * ES + (uint32_t)(c << 4) : kOob;
-    }
-
-    auto issue_w = [&](int chunk, int ky, int wbuf) {
-        unsigned char* dst = wts0 + wbuf * WBYTES + wave * 1024;
-        const uint32_t so = (uint32_t)(ky * KSZ * Cin + chunk * KC) * ES;
-#pragma unroll
-        for (int i = 0; i < NWI; ++i) {
-            const uint32_t off = wgo[i] + so;   // (a named value: an expression in the builtin's argument list loses the host stub)
-            if ((i + 1) * NW <= W_INSTR || wave + i * NW < W_INSTR)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (__attribute__((address_space(3))) void*)(dst + i * (NW * 1024)),
-                                                         16, off, 0, 0, 0);
-        }
-    };
     // part < 0: the whole patch; otherwise the instructions with index % KSZ == part
     auto issue_p = [&](int chunk, int part, int pbuf) {
         unsigned char* dst = patch0 + pbuf * PBYTES + wave * 1024;
@@ -220,10 +226,6 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     for (int j = 0; j < NBW; ++j)
         bias[j] = P.bias ? *reinterpret_cast<const floatx4*>(P.bias + chan + j * 16) : floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const int cb = keep_scalar((int)blockIdx.y * P.chunks_per_split);
-    const int ce0 = cb + P.chunks_per_split;
-    const int ce = keep_scalar(ce0 < P.n_chunks ? ce0 : P.n_chunks);
-
     // Loads of stage s = 3 c + ky (c counts this workgroup's chunks): the weights of kernel row ky and a
     // third of a patch: stage 3c+1, 3c+2 and 3c+3 bring parts 0, 1 and 2 of chunk c+1.  They are issued
     // two stages ahead, right after the barrier that ends the reads of the buffers they overwrite.
@@ -254,7 +256,6 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     };
 
     issue_p(cb, -1, 0);
-    issue_w(cb, 0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     issue_stage(0, 1, 1);
@@ -438,45 +439,62 @@ hipError_t first_launch(int nb, dim3 grid, hipStream_t st, const ConvParams& P) 
 }
 
 // ---- kernel table -----------------------------------------------------------------------
-constexpr int kWM = 2, kWN = 4, kNBW = 1, kNT = kWN * kNBW * 16, kMaxUPW = 8;
-typedef void (*KernelFn)(ConvParams);
+// Two wavefront arrangements (8 wavefronts each):
+//   narrow: 2 x 4 wavefronts, a wavefront = up to 8 units x 16 channels, 64 channels per workgroup.  One LDS
+//           read feeds four fp32 MFMAs, so fp32 is far from the LDS limit and the finest unit granularity wins.
+//   wide:   4 x 2 wavefronts, a wavefront = up to 4 units x 64 channels, 128 channels per workgroup.  bf16 needs
+//           one LDS read per operand per MFMA of 16 cycles: u + 4 reads for 4u MFMAs keep LDS at about half
+//           of its bandwidth, where the narrow shape (u + 1 reads for u MFMAs) is bound by it.
+struct Geom { int wm, wn, nbw, max_upw; };
+constexpr Geom kGeom[2] = {{2, 4, 1, 8}, {4, 2, 4, 4}};
+inline int geom_nt(int geom) { return kGeom[geom].wn * kGeom[geom].nbw * 16; }
 
-#define DC_F(T, KC, U) conv_fast_kernel<T, 3, KC, U, kWM, kWN, kNBW>
-template <typename T, int KC, int U>
+template <typename T, int KC, int U, int WM, int WN, int NBW>
 hipError_t fast_launch_one(dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
-    auto fn = DC_F(T, KC, U);
+    auto fn = conv_fast_kernel<T, 3, KC, U, WM, WN, NBW>;
     if (lds > 64 * 1024) {
         hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (a != hipSuccess) return a;
     }
-    hipLaunchKernelGGL((DC_F(T, KC, U)), grid, dim3(kWM * kWN * 64), lds, st, P);
+    hipLaunchKernelGGL((conv_fast_kernel<T, 3, KC, U, WM, WN, NBW>), grid, dim3(WM * WN * 64), lds, st, P);
     return hipGetLastError();
 }
 template <typename T, int KC>
-hipError_t fast_launch_upw(int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+hipError_t fast_launch_narrow(int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
     switch (upw) {
-        case 1: return fast_launch_one<T, KC, 1>(grid, lds, st, P);
-        case 2: return fast_launch_one<T, KC, 2>(grid, lds, st, P);
-        case 3: return fast_launch_one<T, KC, 3>(grid, lds, st, P);
-        case 4: return fast_launch_one<T, KC, 4>(grid, lds, st, P);
-        case 5: return fast_launch_one<T, KC, 5>(grid, lds, st, P);
-        case 6: return fast_launch_one<T, KC, 6>(grid, lds, st, P);
-        case 7: return fast_launch_one<T, KC, 7>(grid, lds, st, P);
-        default: return fast_launch_one<T, KC, 8>(grid, lds, st, P);
+        case 1: return fast_launch_one<T, KC, 1, 2, 4, 1>(grid, lds, st, P);
+        case 2: return fast_launch_one<T, KC, 2, 2, 4, 1>(grid, lds, st, P);
+        case 3: return fast_launch_one<T, KC, 3, 2, 4, 1>(grid, lds, st, P);
+        case 4: return fast_launch_one<T, KC, 4, 2, 4, 1>(grid, lds, st, P);
+        case 5: return fast_launch_one<T, KC, 5, 2, 4, 1>(grid, lds, st, P);
+        case 6: return fast_launch_one<T, KC, 6, 2, 4, 1>(grid, lds, st, P);
+        case 7: return fast_launch_one<T, KC, 7, 2, 4, 1>(grid, lds, st, P);
+        default: return fast_launch_one<T, KC, 8, 2, 4, 1>(grid, lds, st, P);
     }
 }
-// chunk index: KC = KG, 2 KG
-hipError_t fast_launch(bool bf16, int kci, int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
-    if (bf16) return kci ? fast_launch_upw<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_upw<__hip_bfloat16, 32>(upw, grid, lds, st, P);
-    return kci ? fast_launch_upw<float, 32>(upw, grid, lds, st, P) : fast_launch_upw<float, 16>(upw, grid, lds, st, P);
+template <typename T, int KC>
+hipError_t fast_launch_wide(int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+    switch (upw) {
+        case 1: return fast_launch_one<T, KC, 1, 4, 2, 4>(grid, lds, st, P);
+        case 2: return fast_launch_one<T, KC, 2, 4, 2, 4>(grid, lds, st, P);
+        case 3: return fast_launch_one<T, KC, 3, 4, 2, 4>(grid, lds, st, P);
+        default: return fast_launch_one<T, KC, 4, 4, 2, 4>(grid, lds, st, P);
+    }
+}
+// chunk index: KC = KG, 2 KG.  The wide arrangement is instantiated for bf16 only.
+hipError_t fast_launch(bool bf16, int geom, int kci, int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+    if (bf16 && geom == 1)
+        return kci ? fast_launch_wide<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_wide<__hip_bfloat16, 32>(upw, grid, lds, st, P);
+    if (bf16) return kci ? fast_launch_narrow<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_narrow<__hip_bfloat16, 32>(upw, grid, lds, st, P);
+    return kci ? fast_launch_narrow<float, 32>(upw, grid, lds, st, P) : fast_launch_narrow<float, 16>(upw, grid, lds, st, P);
 }
 
-size_t fast_lds_bytes(int kci, int upw) {
+size_t fast_lds_bytes(int geom, int kci, int upw) {
     const int rpi = 16 >> kci;            // rows per load instruction: RB = 64 << kci
-    return kHeaderBytes + 2 * (size_t)(kWM * upw * 48 / rpi) * 1024 + 2 * (size_t)(3 * kNT / rpi) * 1024;
+    return kHeaderBytes + 2 * (size_t)(kGeom[geom].wm * upw * 48 / rpi) * 1024 + 2 * (size_t)(3 * geom_nt(geom) / rpi) * 1024;
 }
 
-struct FastChoice { int g, ks, kci; double cost; };
+struct FastChoice { int g, ks, kci; double cost; int geom; };
 
 // Cycle model of one launch.  A workgroup spends its stages (the longer of the MFMA time and the time to
 // bring the stage's bytes into LDS) plus fixed costs per stage and per workgroup (decode, address set-up,
@@ -492,37 +510,53 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
     }
     const bool bf16 = c.dtype == DC_BF16;
     const int esz = bf16 ? 2 : 4, kg = bf16 ? 32 : 16;
-    const int R = c.Cout / kNT;
-    FastChoice best{0, 0, 0, 1e300};
-    for (int kci = 0; kci < 2; ++kci) {
-        const int kc = kg << kci;
-        if (c.Cin % kc) continue;
-        const int n_chunks = c.Cin / kc, gpc = 1 << kci, rb = kc * esz;
-        for (int g = 1; g <= kWM * kMaxUPW; ++g) {
-            const int upw = (g + kWM - 1) / kWM;
-            if (fast_lds_bytes(kci, upw) > 160 * 1024) continue;
-            const long groups = (n_units + g - 1) / g;
-            int last_cps = 0;
-            for (int ks = 1; ks <= n_chunks && ks <= 64; ++ks) {
-                const int cps = (n_chunks + ks - 1) / ks;
-                if (cps == last_cps) continue;        // same split as a smaller ks
-                last_cps = cps;
-                const int ks_eff = (n_chunks + cps - 1) / cps;
-                if (ks_eff > 1 && (size_t)ks_eff * n_units * 16 * c.Cout * 4 > scratch_bytes) continue;
-                const double mfma = (bf16 ? 16.0 : 128.0) * upw * kNBW * 3 * gpc * 2;
-                const double load = ((double)g * 36 * rb / 3 + 3.0 * kNT * rb) / bw;
-                const double work = cps * 3 * (1.12 * mfma > load ? 1.12 * mfma : load);
-                const double fixed = wg_fix + 400.0 * upw + cps * 3 * stage_fix;
-                const long wgs = groups * R * ks_eff;
-                const long per_cu = (wgs + 255) / 256;
-                const int vgprs = kci ? 64 + 18 * upw : 44 + 16 * upw;
-                long occ = (long)(160 * 1024 / fast_lds_bytes(kci, upw));
-                if (occ > 512 / vgprs / 2) occ = 512 / vgprs / 2;
-                if (occ > 4) occ = 4;
-                if (occ < 1) occ = 1;
-                double cost = (double)per_cu * work + (double)((per_cu + occ - 1) / occ) * fixed;
-                if (ks_eff > 1) cost += red_fix + (double)(ks_eff + 1) * n_units * 16 * c.Cout * 4 / 1200.0;
-                if (cost < best.cost) best = FastChoice{g, ks_eff, kci, cost};
+    FastChoice best{0, 0, 0, 1e300, 0};
+    static int force_geom = -2;
+    if (force_geom == -2) { const char* e = getenv("DC_CONV_GEOM"); force_geom = e ? atoi(e) : -1; }   // experiments
+    for (int geom = 0; geom < 2; ++geom) {
+        const Geom& G = kGeom[geom];
+        const int nt = geom_nt(geom);
+        if (c.Cout % nt) continue;
+        if (geom == 1 && !bf16) continue;                       // not instantiated
+        if (force_geom >= 0 && force_geom != geom && c.Cout % geom_nt(force_geom) == 0 && (force_geom == 0 || bf16)) continue;
+        const int R = c.Cout / nt;
+        for (int kci = 0; kci < 2; ++kci) {
+            const int kc = kg << kci;
+            if (c.Cin % kc) continue;
+            const int n_chunks = c.Cin / kc, gpc = 1 << kci, rb = kc * esz;
+            for (int g = 1; g <= G.wm * G.max_upw; ++g) {
+                const int upw = (g + G.wm - 1) / G.wm;
+                if (fast_lds_bytes(geom, kci, upw) > 160 * 1024) continue;
+                const long groups = (n_units + g - 1) / g;
+                int last_cps = 0;
+                for (int ks = 1; ks <= n_chunks && ks <= 64; ++ks) {
+                    const int cps = (n_chunks + ks - 1) / ks;
+                    if (cps == last_cps) continue;        // same split as a smaller ks
+                    last_cps = cps;
+                    const int ks_eff = (n_chunks + cps - 1) / cps;
+                    if (ks_eff > 1 && (size_t)ks_eff * n_units * 16 * c.Cout * 4 > scratch_bytes) continue;
+                    // per stage: MFMA cycles of a SIMD (two wavefronts), LDS cycles of the CU (a 16-byte read of
+                    // a wavefront takes 4), cycles to load the stage
+                    const double mfma = 1.12 * (bf16 ? 16.0 : 128.0) * upw * G.nbw * 3 * gpc * 2;
+                    const double ldsr = 8.0 * (upw + G.nbw) * 3 * gpc * 4 * 1.3;
+                    const double load = ((double)g * 36 * rb / 3 + 3.0 * nt * rb) / bw;
+                    double stage = mfma > load ? mfma : load;
+                    if (ldsr > stage) stage = ldsr;
+                    const double work = cps * 3 * stage;
+                    const double fixed = wg_fix + 400.0 * upw * G.nbw + cps * 3 * stage_fix;
+                    const long wgs = groups * R * ks_eff;
+                    const long per_cu = (wgs + 255) / 256;
+                    // many rounds: the dispatcher balances the CUs, the last round is not a whole one
+                    const double rounds = wgs <= 512 ? (double)per_cu : wgs / 256.0 + 0.5;
+                    const int vgprs = (kci ? 64 : 44) + (geom ? 40 * upw + 24 : (kci ? 18 : 16) * upw);
+                    long occ = (long)(160 * 1024 / fast_lds_bytes(geom, kci, upw));
+                    if (occ > 512 / vgprs / 2) occ = 512 / vgprs / 2;
+                    if (occ > 4) occ = 4;
+                    if (occ < 1) occ = 1;
+                    double cost = rounds * work + (double)((per_cu + occ - 1) / occ) * fixed;
+                    if (ks_eff > 1) cost += red_fix + (double)(ks_eff + 1) * n_units * 16 * c.Cout * 4 / 1200.0;
+                    if (cost < best.cost) best = FastChoice{g, ks_eff, kci, cost, geom};
+                }
             }
         }
     }
@@ -531,15 +565,20 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
 
 }  // namespace
 
-// Ids 64.. name the instantiations of this file: 64 + ((bf16 * 2 + kci) * 8 + UPW - 1), 96.. the first-layer kernel.
+// Ids 64.. name the instantiations of this file: 64 + ((bf16 * 2 + kci) * 8 + UPW - 1), 96.. the first-layer kernel,
+// 110.. the wide arrangement.
 void conv_fast_kernel_name(int id, char* buf, size_t n) {
     if (id >= 96) {   // 96 + bf16 * 3 + {0, 1, 2}: conv_first_kernel with 1, 2, 4 channel blocks
         snprintf(buf, n, "conv_first_kernel<%s, %d>", (id - 96) / 3 ? "__hip_bfloat16" : "float", 1 << ((id - 96) % 3));
         return;
     }
+    if (id >= 110) {  // 110 + kci * 4 + UPW - 1: the wide bf16 arrangement
+        const int v = id - 110;
+        snprintf(buf, n, "conv_fast_kernel<__hip_bfloat16, 3, %d, %d, 4, 2, 4>", 32 << (v / 4), v % 4 + 1);
+        return;
+    }
     const int v = id - 64, upw = v % 8 + 1, kci = (v / 8) % 2, bf16 = v / 16;
-    snprintf(buf, n, "conv_fast_kernel<%s, 3, %d, %d, %d, %d, %d>", bf16 ? "__hip_bfloat16" : "float",
-             (bf16 ? 32 : 16) << kci, upw, kWM, kWN, kNBW);
+    snprintf(buf, n, "conv_fast_kernel<%s, 3, %d, %d, 2, 4, 1>", bf16 ? "__hip_bfloat16" : "float", (bf16 ? 32 : 16) << kci, upw);
 }
 
 // Launches the layer with the kernel of this file if its shape qualifies; returns false otherwise.
@@ -570,7 +609,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
             return true;
         }
     }
-    if (!enabled || c.k != 3 || c.s != 1 || c.Cout % kNT != 0 || c.Cin % (64 / esz) != 0) return false;
+    if (!enabled || c.k != 3 || c.s != 1 || c.Cout % geom_nt(0) != 0 || c.Cin % (64 / esz) != 0) return false;
     if (reinterpret_cast<uintptr_t>(c.in) % 16 || reinterpret_cast<uintptr_t>(c.w) % 16) return false;
     if (reinterpret_cast<uintptr_t>(c.out) % 16 || (c.bias && reinterpret_cast<uintptr_t>(c.bias) % 16)) return false;
     {   // 32-bit output offsets, exact magic-number division of the unit index
@@ -588,15 +627,16 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
             f_g = 0;
             if (e) sscanf(e, "%d,%d,%d,%d", &f_g, &f_ks, &f_kci, &f_live);
         }
-        if (f_g > 0) {
+        if (f_g > 0 && ch.g > 0) {    // keeps the arrangement the model picked
+            const Geom& G = kGeom[ch.geom];
             const int kc = (c.dtype == DC_BF16 ? 32 : 16) << f_kci;
-            const int upw = (f_g + kWM - 1) / kWM;
-            if (f_g <= kWM * kMaxUPW && f_kci >= 0 && f_kci < 2 && c.Cin % kc == 0 && fast_lds_bytes(f_kci, upw) <= 160 * 1024) {
+            const int upw = (f_g + G.wm - 1) / G.wm;
+            if (f_g <= G.wm * G.max_upw && f_kci >= 0 && f_kci < 2 && c.Cin % kc == 0 && fast_lds_bytes(ch.geom, f_kci, upw) <= 160 * 1024) {
                 const int n_chunks = c.Cin / kc;
                 int ks = f_ks < 1 ? 1 : (f_ks > n_chunks ? n_chunks : f_ks);
                 const int cps = (n_chunks + ks - 1) / ks;
                 ks = (n_chunks + cps - 1) / cps;
-                if (ks == 1 || (size_t)ks * n_units * 16 * c.Cout * 4 <= scratch) ch = FastChoice{f_g, ks, f_kci, 0};
+                if (ks == 1 || (size_t)ks * n_units * 16 * c.Cout * 4 <= scratch) ch = FastChoice{f_g, ks, f_kci, 0, ch.geom};
             }
         }
     }
@@ -605,10 +645,10 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         static int debug = -1;
         if (debug < 0) { const char* e = getenv("DC_CONV_DEBUG"); debug = e ? atoi(e) : 0; }
         if (debug)
-            fprintf(stderr, "[conv_fast] units=%ld %dx%d cin=%d cout=%d -> g=%d ks=%d kci=%d model=%.0f cycles\n", n_units, c.Hout,
-                    c.Wout, c.Cin, c.Cout, ch.g, ch.ks, ch.kci, ch.cost);
+            fprintf(stderr, "[conv_fast] units=%ld %dx%d cin=%d cout=%d -> %s g=%d ks=%d kci=%d model=%.0f cycles\n", n_units,
+                    c.Hout, c.Wout, c.Cin, c.Cout, ch.geom ? "wide" : "narrow", ch.g, ch.ks, ch.kci, ch.cost);
     }
-    const int upw = (ch.g + kWM - 1) / kWM;
+    const int upw = (ch.g + kGeom[ch.geom].wm - 1) / kGeom[ch.geom].wm;
     const int kc = (c.dtype == DC_BF16 ? 32 : 16) << ch.kci;
     const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
 
@@ -626,16 +666,17 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     P.w_bytes = (uint32_t)((size_t)c.Cout * 9 * c.Cin * esz);
     P.out_vec = 1;
     P.n_chunks = c.Cin / kc;
-    P.R = c.Cout / kNT;
+    P.R = c.Cout / geom_nt(ch.geom);
     P.ks = ch.ks;
     P.chunks_per_split = (P.n_chunks + ch.ks - 1) / ch.ks;
     P.partial = ch.ks > 1 ? static_cast<float*>(c.scratch) : nullptr;
 
-    if (c.kernel_id) *c.kernel_id = 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
+    if (c.kernel_id) *c.kernel_id = ch.geom ? 110 + ch.kci * 4 + upw - 1 : 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
     const long groups = (n_units + ch.g - 1) / ch.g;
     const long wgx = groups * P.R;
     if (wgx > 2147483647L || ch.ks > 65535) { *err = hipErrorInvalidValue; return true; }
-    *err = fast_launch(c.dtype == DC_BF16, ch.kci, upw, dim3((unsigned)wgx, (unsigned)ch.ks), fast_lds_bytes(ch.kci, upw), st, P);
+    *err = fast_launch(c.dtype == DC_BF16, ch.geom, ch.kci, upw, dim3((unsigned)wgx, (unsigned)ch.ks),
+                       fast_lds_bytes(ch.geom, ch.kci, upw), st, P);
     if (*err != hipSuccess || ch.ks == 1) return true;
     const size_t total = (size_t)n_units * 16 * (c.Cout / 4);
     if (c.dtype == DC_BF16)
