@@ -118,6 +118,15 @@ int32_t dc_profile_elapsed_ms(void* profile, int32_t slot, float* ms);
 int32_t dc_overlap_create(void** overlap);
 int32_t dc_overlap_destroy(void* overlap);
 
+/*
+ * Overrides the launch heuristics of the 3x3 stride-1 GEMM kernel for the whole process (tests and
+ * experiments; results do not depend on it beyond fp32 summation order): wavefront arrangement
+ * (0: 64 channels per workgroup, 1: 128, bf16 only), units per workgroup (1..16), number of
+ * workgroups that split K, channel chunk index (0, 1).  A negative value leaves that choice to the
+ * library; values a layer cannot use are ignored for that layer.
+ */
+int32_t dc_conv_tuning(int32_t arrangement, int32_t units_per_workgroup, int32_t k_split, int32_t chunk_index);
+
 /* Name of a GEMM kernel instantiation (as a profiler prints it, without namespace and
  * argument list) for an id reported in dc_stack_stats.layer_kernel_id. */
 int32_t dc_conv_kernel_name(int32_t kernel_id, char* buf, size_t n);

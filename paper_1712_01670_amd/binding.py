@@ -22,7 +22,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
           -4: "DC_ERR_UNSUPPORTED", -5: "DC_ERR_WORKSPACE", -6: "DC_ERR_CAPACITY", -7: "DC_ERR_HIP"}
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
-           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
+           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
            "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
@@ -73,6 +73,7 @@ def lib():
         L.dc_profile_elapsed_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
         L.dc_overlap_create.argtypes = [C.POINTER(vp)]
         L.dc_overlap_destroy.argtypes = [vp]
+        L.dc_conv_tuning.argtypes = [i32, i32, i32, i32]
         L.dc_conv_kernel_name.argtypes = [i32, C.c_char_p, sz]
         L.dc_conv_tile_shape.argtypes = [vp, i32, i32, i32, i32] + [C.POINTER(i32)] * 4
         L.dc_match_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
@@ -411,6 +412,11 @@ class StackRunner:
         nl = len(self.layers)
         return dict(reused_px=[self._reused[i] for i in range(nl)], issued_macs=[self._issued[i] for i in range(nl)],
                     kernel_id=[self._kid[i] for i in range(nl)])
+
+
+def dc_conv_tuning(arrangement=-1, units_per_workgroup=-1, k_split=-1, chunk_index=-1):
+    """Process-wide override of the conv launch heuristics (tests, experiments); -1 = automatic."""
+    _check("dc_conv_tuning", lib().dc_conv_tuning(arrangement, units_per_workgroup, k_split, chunk_index))
 
 
 def conv_kernel_name(kernel_id):

@@ -496,6 +496,18 @@ size_t fast_lds_bytes(int geom, int kci, int upw) {
 
 struct FastChoice { int g, ks, kci; double cost; int geom; };
 
+// Overrides of the launch model (tests and experiments): arrangement, units per workgroup, K split,
+// channel chunk index; -1 = chosen by the model.  Initialised from DC_CONV_GEOM / DC_CONV_FORCE="g,ks,kci".
+int g_tune[4] = {-2, -1, -1, -1};
+void init_tuning() {
+    if (g_tune[0] != -2) return;
+    int geom = -1, g = -1, ks = -1, kci = -1;
+    if (const char* e = getenv("DC_CONV_GEOM")) geom = atoi(e);
+    if (const char* e = getenv("DC_CONV_FORCE")) sscanf(e, "%d,%d,%d", &g, &ks, &kci);
+    g_tune[1] = g > 0 ? g : -1; g_tune[2] = ks > 0 ? ks : -1; g_tune[3] = kci >= 0 ? kci : -1;
+    g_tune[0] = geom >= 0 ? geom : -1;
+}
+
 // Cycle model of one launch.  A workgroup spends its stages (the longer of the MFMA time and the time to
 // bring the stage's bytes into LDS) plus fixed costs per stage and per workgroup (decode, address set-up,
 // first loads, epilogue).  A CU runs ceil(workgroups / 256) of them; as many as LDS and registers allow
@@ -511,8 +523,8 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
     const bool bf16 = c.dtype == DC_BF16;
     const int esz = bf16 ? 2 : 4, kg = bf16 ? 32 : 16;
     FastChoice best{0, 0, 0, 1e300, 0};
-    static int force_geom = -2;
-    if (force_geom == -2) { const char* e = getenv("DC_CONV_GEOM"); force_geom = e ? atoi(e) : -1; }   // experiments
+    init_tuning();
+    const int force_geom = g_tune[0];
     for (int geom = 0; geom < 2; ++geom) {
         const Geom& G = kGeom[geom];
         const int nt = geom_nt(geom);
@@ -581,6 +593,11 @@ void conv_fast_kernel_name(int id, char* buf, size_t n) {
     snprintf(buf, n, "conv_fast_kernel<%s, 3, %d, %d, 2, 4, 1>", bf16 ? "__hip_bfloat16" : "float", (bf16 ? 32 : 16) << kci, upw);
 }
 
+void conv_set_tuning(int geom, int g, int ks, int kci) {
+    init_tuning();
+    g_tune[0] = geom >= 0 ? geom : -1; g_tune[1] = g > 0 ? g : -1; g_tune[2] = ks > 0 ? ks : -1; g_tune[3] = kci >= 0 ? kci : -1;
+}
+
 // Launches the layer with the kernel of this file if its shape qualifies; returns false otherwise.
 bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err) {
     static int enabled = -1;
@@ -620,24 +637,17 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     size_t scratch = c.scratch && reinterpret_cast<uintptr_t>(c.scratch) % 16 == 0 ? c.scratch_bytes : 0;
     if (scratch > kConvScratchBytes) scratch = kConvScratchBytes;
     FastChoice ch = choose_fast(c, n_units, scratch);
-    {
-        static int f_g = -1, f_ks = 0, f_kci = 0, f_live = 0;
-        if (f_g < 0 || f_live) {
-            const char* e = getenv("DC_CONV_FORCE");   // "g,ks,kci[,1: read again at every launch]" (experiments)
-            f_g = 0;
-            if (e) sscanf(e, "%d,%d,%d,%d", &f_g, &f_ks, &f_kci, &f_live);
-        }
-        if (f_g > 0 && ch.g > 0) {    // keeps the arrangement the model picked
-            const Geom& G = kGeom[ch.geom];
-            const int kc = (c.dtype == DC_BF16 ? 32 : 16) << f_kci;
-            const int upw = (f_g + G.wm - 1) / G.wm;
-            if (f_g <= G.wm * G.max_upw && f_kci >= 0 && f_kci < 2 && c.Cin % kc == 0 && fast_lds_bytes(ch.geom, f_kci, upw) <= 160 * 1024) {
-                const int n_chunks = c.Cin / kc;
-                int ks = f_ks < 1 ? 1 : (f_ks > n_chunks ? n_chunks : f_ks);
-                const int cps = (n_chunks + ks - 1) / ks;
-                ks = (n_chunks + cps - 1) / cps;
-                if (ks == 1 || (size_t)ks * n_units * 16 * c.Cout * 4 <= scratch) ch = FastChoice{f_g, ks, f_kci, 0, ch.geom};
-            }
+    if (g_tune[1] > 0 && ch.g > 0) {    // forced shape within the arrangement the model picked
+        const int f_g = g_tune[1], f_ks = g_tune[2], f_kci = g_tune[3] < 0 ? ch.kci : g_tune[3];
+        const Geom& G = kGeom[ch.geom];
+        const int kc = (c.dtype == DC_BF16 ? 32 : 16) << f_kci;
+        const int upw = (f_g + G.wm - 1) / G.wm;
+        if (f_g <= G.wm * G.max_upw && f_kci < 2 && c.Cin % kc == 0 && fast_lds_bytes(ch.geom, f_kci, upw) <= 160 * 1024) {
+            const int n_chunks = c.Cin / kc;
+            int ks = f_ks < 1 ? 1 : (f_ks > n_chunks ? n_chunks : f_ks);
+            const int cps = (n_chunks + ks - 1) / ks;
+            ks = (n_chunks + cps - 1) / cps;
+            if (ks == 1 || (size_t)ks * n_units * 16 * c.Cout * 4 <= scratch) ch = FastChoice{f_g, ks, f_kci, 0, ch.geom};
         }
     }
     if (ch.g < 1) return false;

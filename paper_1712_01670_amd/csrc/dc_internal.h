@@ -77,6 +77,7 @@ constexpr size_t kConvScratchBytes = (size_t)32 << 20;
 bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err);
 void conv_kernel_name(int id, char* buf, size_t n);
 void conv_fast_kernel_name(int id, char* buf, size_t n);
+void conv_set_tuning(int geom, int g, int ks, int kci);
 hipError_t launch_conv(const ConvLaunch& c, hipStream_t st);
 
 hipError_t launch_shifted_copy(const RectDev* rects_dev, int n_rects, int max_rect_w, int max_rect_h,

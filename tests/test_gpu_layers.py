@@ -92,6 +92,91 @@ def test_cached_conv_matches_oracle(oracle, case, bf16):
         assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
 
 
+# 3x3 stride-1 layers with whole 64-byte channel rows take the compile-time-shaped GEMM kernel; the launch
+# heuristics are overridden so that every shape of that kernel is exercised at a size the oracle handles:
+# (arrangement, units per workgroup, K split, chunk index); arrangement 1 exists for bf16 only.
+FAST_CASES = [
+    # H, W, cin, cout, tuning
+    (22, 30, 32, 64, (0, 1, -1, 0)),     # one unit per workgroup
+    (22, 30, 64, 64, (0, 5, -1, 1)),     # odd unit count, longer channel chunk
+    (22, 30, 64, 128, (0, 16, 1, 0)),    # full workgroup tile, more units in the tile than in the map's last group
+    (14, 14, 128, 64, (0, 3, 4, 0)),     # K split among 4 workgroups + reduction kernel
+    (13, 17, 256, 128, (0, 2, 8, 1)),    # K split, ragged map
+    (22, 30, 64, 128, (1, 7, 1, 0)),     # 128 channels per workgroup
+    (22, 30, 64, 256, (1, 16, 2, 0)),    # ... with a K split
+    (19, 23, 128, 128, (-1, -1, -1, -1)),  # the library's own choice
+]
+
+
+@pytest.mark.parametrize("cached", [False, True])
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("case", FAST_CASES)
+def test_fast_conv_kernel_shapes(oracle, case, bf16, cached):
+    H, W, cin, cout, tuning = case
+    print(f"[fast conv] case={case} bf16={bf16} cached={cached}", flush=True)
+    rng = np.random.default_rng(H * 1000 + W * 10 + cin + cout)
+    n = 2
+    x = rng.standard_normal((n, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, 3, 3, cin)) * np.sqrt(2.0 / (cin * 9))).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    cache = rng.standard_normal((n, H, W, cout)).astype(np.float32)
+    if bf16:
+        x, w, cache = oracle.round_bf16(x), oracle.round_bf16(w), oracle.round_bf16(cache)
+    regions = None
+    if cached:
+        regions = [(np.array([[1, 2, W - 7, H - 6], [W - 5, 1, 3, 4]], np.int32), (2, -1)),
+                   (np.array([[0, 0, W - 1, H - 3]], np.int32), (1, 2))]
+    binding.dc_conv_tuning(*tuning)
+    try:
+        got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, 3, 1, 1, True), _to_dev(x, bf16), _to_dev(w, bf16),
+                                                  torch.from_numpy(b).to(DEV),
+                                                  cache_prev=_to_dev(cache, bf16) if cached else None, regions=regions))
+    finally:
+        binding.dc_conv_tuning()
+    for i in range(n):
+        if cached:
+            mask = oracle.rasterize(regions[i][0], H, W)
+            want = oracle.conv_cached(x[i], w, b, 3, 1, 1, True, cache_prev=cache[i], mask=mask, dxy=regions[i][1], bf16=bf16)
+            m = mask.astype(bool)
+            assert np.array_equal(got[i][m], want[m]), "copied pixels must be bit-identical"
+        else:
+            want = oracle.conv_cached(x[i], w, b, 3, 1, 1, True, bf16=bf16)
+        assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
+
+
+@pytest.mark.parametrize("cached", [False, True])
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("cout", [16, 32, 64, 128])
+def test_first_layer_kernel(oracle, cout, bf16, cached):
+    """Input pixels of one 16-byte vector (4 fp32 / 8 bf16 channels): the kernel without LDS staging."""
+    H, W = 21, 26
+    cin = 8 if bf16 else 4
+    print(f"[first layer] cout={cout} bf16={bf16} cached={cached}", flush=True)
+    rng = np.random.default_rng(cout + 7)
+    n = 2
+    x = rng.standard_normal((n, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, 3, 3, cin)) * np.sqrt(2.0 / (cin * 9))).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    cache = rng.standard_normal((n, H, W, cout)).astype(np.float32)
+    if bf16:
+        x, w, cache = oracle.round_bf16(x), oracle.round_bf16(w), oracle.round_bf16(cache)
+    regions = None
+    if cached:
+        regions = [(np.array([[3, 1, W - 8, H - 5]], np.int32), (-2, 1)), (np.zeros((0, 4), np.int32), (0, 0))]
+    got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, 3, 1, 1, True), _to_dev(x, bf16), _to_dev(w, bf16),
+                                              torch.from_numpy(b).to(DEV),
+                                              cache_prev=_to_dev(cache, bf16) if cached else None, regions=regions))
+    for i in range(n):
+        if cached:
+            mask = oracle.rasterize(regions[i][0], H, W)
+            want = oracle.conv_cached(x[i], w, b, 3, 1, 1, True, cache_prev=cache[i], mask=mask, dxy=regions[i][1], bf16=bf16)
+            m = mask.astype(bool)
+            assert np.array_equal(got[i][m], want[m])
+        else:
+            want = oracle.conv_cached(x[i], w, b, 3, 1, 1, True, bf16=bf16)
+        assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (cout, i)
+
+
 def test_cached_conv_everything_reusable_launches_no_gemm(oracle):
     rng = np.random.default_rng(1)
     x = rng.standard_normal((1, 16, 16, 16)).astype(np.float32)
