@@ -121,7 +121,7 @@ int32_t dc_overlap_destroy(void* overlap);
 /*
  * Overrides the launch heuristics of the 3x3 stride-1 GEMM kernel for the whole process (tests and
  * experiments; results do not depend on it beyond fp32 summation order): wavefront arrangement
- * (0: 64 channels per workgroup, 1: 128, bf16 only), units per workgroup (1..16), number of
+ * (0: 64 channels per workgroup; bf16 only: 1: 128 channels, 2: 64 channels in two blocks per wavefront), units per workgroup (1..16), number of
  * workgroups that split K, channel chunk index (0, 1).  A negative value leaves that choice to the
  * library; values a layer cannot use are ignored for that layer.
  */

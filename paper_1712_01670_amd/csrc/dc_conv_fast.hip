@@ -445,8 +445,11 @@ hipError_t first_launch(int nb, dim3 grid, hipStream_t st, const ConvParams& P) 
 //   wide:   4 x 2 wavefronts, a wavefront = up to 4 units x 64 channels, 128 channels per workgroup.  bf16 needs
 //           one LDS read per operand per MFMA of 16 cycles: u + 4 reads for 4u MFMAs keep LDS at about half
 //           of its bandwidth, where the narrow shape (u + 1 reads for u MFMAs) is bound by it.
+//   wide64: 4 x 2 wavefronts, a wavefront = up to 4 units x 32 channels, 64 channels per workgroup: the bf16
+//           shape for layers whose channel count is not a multiple of 128 (u + 2 reads for 2u MFMAs).
 struct Geom { int wm, wn, nbw, max_upw; };
-constexpr Geom kGeom[2] = {{2, 4, 1, 8}, {4, 2, 4, 4}};
+constexpr int kNumGeom = 3;
+constexpr Geom kGeom[kNumGeom] = {{2, 4, 1, 8}, {4, 2, 4, 4}, {4, 2, 2, 4}};
 inline int geom_nt(int geom) { return kGeom[geom].wn * kGeom[geom].nbw * 16; }
 
 template <typename T, int KC, int U, int WM, int WN, int NBW>
@@ -481,10 +484,21 @@ hipError_t fast_launch_wide(int upw, dim3 grid, size_t lds, hipStream_t st, cons
         default: return fast_launch_one<T, KC, 4, 4, 2, 4>(grid, lds, st, P);
     }
 }
-// chunk index: KC = KG, 2 KG.  The wide arrangement is instantiated for bf16 only.
+template <typename T, int KC>
+hipError_t fast_launch_wide64(int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+    switch (upw) {
+        case 1: return fast_launch_one<T, KC, 1, 4, 2, 2>(grid, lds, st, P);
+        case 2: return fast_launch_one<T, KC, 2, 4, 2, 2>(grid, lds, st, P);
+        case 3: return fast_launch_one<T, KC, 3, 4, 2, 2>(grid, lds, st, P);
+        default: return fast_launch_one<T, KC, 4, 4, 2, 2>(grid, lds, st, P);
+    }
+}
+// chunk index: KC = KG, 2 KG.  The wide arrangements are instantiated for bf16 only.
 hipError_t fast_launch(bool bf16, int geom, int kci, int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
     if (bf16 && geom == 1)
         return kci ? fast_launch_wide<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_wide<__hip_bfloat16, 32>(upw, grid, lds, st, P);
+    if (bf16 && geom == 2)
+        return kci ? fast_launch_wide64<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_wide64<__hip_bfloat16, 32>(upw, grid, lds, st, P);
     if (bf16) return kci ? fast_launch_narrow<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_narrow<__hip_bfloat16, 32>(upw, grid, lds, st, P);
     return kci ? fast_launch_narrow<float, 32>(upw, grid, lds, st, P) : fast_launch_narrow<float, 16>(upw, grid, lds, st, P);
 }
@@ -525,12 +539,12 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
     FastChoice best{0, 0, 0, 1e300, 0};
     init_tuning();
     const int force_geom = g_tune[0];
-    for (int geom = 0; geom < 2; ++geom) {
+    for (int geom = 0; geom < kNumGeom; ++geom) {
         const Geom& G = kGeom[geom];
         const int nt = geom_nt(geom);
         if (c.Cout % nt) continue;
-        if (geom == 1 && !bf16) continue;                       // not instantiated
-        if (force_geom >= 0 && force_geom != geom && c.Cout % geom_nt(force_geom) == 0 && (force_geom == 0 || bf16)) continue;
+        if (geom != 0 && !bf16) continue;                       // not instantiated
+        if (force_geom >= 0 && force_geom < kNumGeom && force_geom != geom && c.Cout % geom_nt(force_geom) == 0 && (force_geom == 0 || bf16)) continue;
         const int R = c.Cout / nt;
         for (int kci = 0; kci < 2; ++kci) {
             const int kc = kg << kci;
@@ -560,7 +574,7 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
                     const long per_cu = (wgs + 255) / 256;
                     // many rounds: the dispatcher balances the CUs, the last round is not a whole one
                     const double rounds = wgs <= 512 ? (double)per_cu : wgs / 256.0 + 0.5;
-                    const int vgprs = (kci ? 64 : 44) + (geom ? 40 * upw + 24 : (kci ? 18 : 16) * upw);
+                    const int vgprs = (kci ? 64 : 44) + (geom ? 10 * G.nbw * upw + 6 * G.nbw : (kci ? 18 : 16) * upw);
                     long occ = (long)(160 * 1024 / fast_lds_bytes(geom, kci, upw));
                     if (occ > 512 / vgprs / 2) occ = 512 / vgprs / 2;
                     if (occ > 4) occ = 4;
@@ -580,13 +594,13 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
 // Ids 64.. name the instantiations of this file: 64 + ((bf16 * 2 + kci) * 8 + UPW - 1), 96.. the first-layer kernel,
 // 110.. the wide arrangement.
 void conv_fast_kernel_name(int id, char* buf, size_t n) {
-    if (id >= 96) {   // 96 + bf16 * 3 + {0, 1, 2}: conv_first_kernel with 1, 2, 4 channel blocks
-        snprintf(buf, n, "conv_first_kernel<%s, %d>", (id - 96) / 3 ? "__hip_bfloat16" : "float", 1 << ((id - 96) % 3));
+    if (id >= 110) {  // 110 + (arrangement - 1) * 8 + kci * 4 + UPW - 1: the wide bf16 arrangements
+        const int v = (id - 110) % 8, wide64 = (id - 110) / 8;
+        snprintf(buf, n, "conv_fast_kernel<__hip_bfloat16, 3, %d, %d, 4, 2, %d>", 32 << (v / 4), v % 4 + 1, wide64 ? 2 : 4);
         return;
     }
-    if (id >= 110) {  // 110 + kci * 4 + UPW - 1: the wide bf16 arrangement
-        const int v = id - 110;
-        snprintf(buf, n, "conv_fast_kernel<__hip_bfloat16, 3, %d, %d, 4, 2, 4>", 32 << (v / 4), v % 4 + 1);
+    if (id >= 96) {   // 96 + bf16 * 3 + {0, 1, 2}: conv_first_kernel with 1, 2, 4 channel blocks
+        snprintf(buf, n, "conv_first_kernel<%s, %d>", (id - 96) / 3 ? "__hip_bfloat16" : "float", 1 << ((id - 96) % 3));
         return;
     }
     const int v = id - 64, upw = v % 8 + 1, kci = (v / 8) % 2, bf16 = v / 16;
@@ -656,7 +670,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         if (debug < 0) { const char* e = getenv("DC_CONV_DEBUG"); debug = e ? atoi(e) : 0; }
         if (debug)
             fprintf(stderr, "[conv_fast] units=%ld %dx%d cin=%d cout=%d -> %s g=%d ks=%d kci=%d model=%.0f cycles\n", n_units,
-                    c.Hout, c.Wout, c.Cin, c.Cout, ch.geom ? "wide" : "narrow", ch.g, ch.ks, ch.kci, ch.cost);
+                    c.Hout, c.Wout, c.Cin, c.Cout, ch.geom == 0 ? "narrow" : (ch.geom == 1 ? "wide" : "wide64"), ch.g, ch.ks, ch.kci, ch.cost);
     }
     const int upw = (ch.g + kGeom[ch.geom].wm - 1) / kGeom[ch.geom].wm;
     const int kc = (c.dtype == DC_BF16 ? 32 : 16) << ch.kci;
@@ -681,7 +695,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     P.chunks_per_split = (P.n_chunks + ch.ks - 1) / ch.ks;
     P.partial = ch.ks > 1 ? static_cast<float*>(c.scratch) : nullptr;
 
-    if (c.kernel_id) *c.kernel_id = ch.geom ? 110 + ch.kci * 4 + upw - 1 : 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
+    if (c.kernel_id) *c.kernel_id = ch.geom ? 110 + (ch.geom - 1) * 8 + ch.kci * 4 + upw - 1 : 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
     const long groups = (n_units + ch.g - 1) / ch.g;
     const long wgx = groups * P.R;
     if (wgx > 2147483647L || ch.ks > 65535) { *err = hipErrorInvalidValue; return true; }

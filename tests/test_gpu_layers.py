@@ -104,6 +104,8 @@ FAST_CASES = [
     (13, 17, 256, 128, (0, 2, 8, 1)),    # K split, ragged map
     (22, 30, 64, 128, (1, 7, 1, 0)),     # 128 channels per workgroup
     (22, 30, 64, 256, (1, 16, 2, 0)),    # ... with a K split
+    (22, 30, 64, 64, (2, 11, 1, 0)),     # 64 channels per workgroup in two blocks per wavefront (bf16)
+    (14, 14, 128, 192, (2, 4, 2, 1)),
     (19, 23, 128, 128, (-1, -1, -1, -1)),  # the library's own choice
 ]
 
