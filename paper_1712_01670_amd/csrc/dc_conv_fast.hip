@@ -22,6 +22,7 @@
 // share of the weights, which is what bounds these layers.
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "dc_conv_common.h"
 
@@ -236,62 +237,70 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
         if (ky == 0) { if (c > 0) issue_p(cb + c, KSZ - 1, c & 1); }
         else if (c + 1 < n_ch) issue_p(cb + c + 1, ky - 1, (c + 1) & 1);
     };
-    vec x[2][UPW], w[2][NBW];
-    auto frag = [&](int pbuf, int wbuf, int ky, int st, int b) {
-        const int kx = st / GPC, g = st % GPC;
-        const unsigned char* xp = patch0 + pbuf * PBYTES + paddr[ky * KSZ + kx][g];
+    // The main loop for a wavefront with NU units.  The units of a workgroup are dealt to the wave_m groups
+    // round-robin, so a group holds UPW or UPW - 1 of them; both variants run the same stages and barriers.
+    auto main_loop = [&](auto nu_tag) {
+        constexpr int NU = decltype(nu_tag)::value;
+        vec x[2][NU > 0 ? NU : 1], w[2][NBW];
+        auto frag = [&](int pbuf, int wbuf, int ky, int st, int b) {
+            const int kx = st / GPC, g = st % GPC;
+            const unsigned char* xp = patch0 + pbuf * PBYTES + paddr[ky * KSZ + kx][g];
 #pragma unroll
-        for (int u = 0; u < UPW; ++u) x[b][u] = *reinterpret_cast<const vec*>(xp + u * (WM * PR * RB));
-        const unsigned char* wp = wts0 + wbuf * WBYTES + waddr[g] + kx * (NT * RB);
+            for (int u = 0; u < NU; ++u) x[b][u] = *reinterpret_cast<const vec*>(xp + u * (WM * PR * RB));
+            const unsigned char* wp = wts0 + wbuf * WBYTES + waddr[g] + kx * (NT * RB);
 #pragma unroll
-        for (int j = 0; j < NBW; ++j) w[b][j] = *reinterpret_cast<const vec*>(wp + j * (16 * RB));
-    };
-    auto mma = [&](int b) {
+            for (int j = 0; j < NBW; ++j) w[b][j] = *reinterpret_cast<const vec*>(wp + j * (16 * RB));
+        };
+        auto mma = [&](int b) {
 #pragma unroll
-        for (int e = 0; e < F::NE; ++e)
+            for (int e = 0; e < F::NE; ++e)
 #pragma unroll
-            for (int u = 0; u < UPW; ++u)
+                for (int u = 0; u < NU; ++u)
 #pragma unroll
-                for (int j = 0; j < NBW; ++j) F::mma1(w[b][j], x[b][u], acc[u][j], e);
-    };
+                    for (int j = 0; j < NBW; ++j) F::mma1(w[b][j], x[b][u], acc[u][j], e);
+        };
 
-    issue_p(cb, -1, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    issue_stage(0, 1, 1);
-    frag(0, 0, 0, 0, 0);
-    int sidx = 0;
-    for (int c = 0; c < n_ch; ++c) {
-        const int pbuf = c & 1;
+        issue_p(cb, -1, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        issue_stage(0, 1, 1);
+        frag(0, 0, 0, 0, 0);
+        int sidx = 0;
+        for (int c = 0; c < n_ch; ++c) {
+            const int pbuf = c & 1;
 #pragma unroll
-        for (int ky = 0; ky < KSZ; ++ky, ++sidx) {
-            // fragments of step 0 of this stage are on their way (buffer (ky * NS) & 1)
+            for (int ky = 0; ky < KSZ; ++ky, ++sidx) {
+                // fragments of step 0 of this stage are on their way (buffer (ky * NS) & 1)
 #pragma unroll
-            for (int st = 0; st + 1 < NS; ++st) {
-                frag(pbuf, sidx & 1, ky, st + 1, (ky * NS + st + 1) & 1);
+                for (int st = 0; st + 1 < NS; ++st) {
+                    frag(pbuf, sidx & 1, ky, st + 1, (ky * NS + st + 1) & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma((ky * NS + st) & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // Last step: first end the stage for the memory system.  After the barrier every wavefront has
+                // its last fragments of this stage in registers and the loads of the next stage are in LDS.
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (ky == 0) issue_stage(c, 2, sidx + 2);
+                else issue_stage(c + 1, ky - 1, sidx + 2);
+                if (ky + 1 < KSZ) frag(pbuf, (sidx + 1) & 1, ky + 1, 0, ((ky + 1) * NS) & 1);
+                else if (c + 1 < n_ch) frag(pbuf ^ 1, (sidx + 1) & 1, 0, 0, (KSZ * NS) & 1);
                 __builtin_amdgcn_sched_barrier(0);
-                mma((ky * NS + st) & 1);
+                mma((ky * NS + NS - 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // Last step: first end the stage for the memory system.  After the barrier every wavefront has
-            // its last fragments of this stage in registers and the loads of the next stage are in LDS.
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (ky == 0) issue_stage(c, 2, sidx + 2);
-            else issue_stage(c + 1, ky - 1, sidx + 2);
-            if (ky + 1 < KSZ) frag(pbuf, (sidx + 1) & 1, ky + 1, 0, ((ky + 1) * NS) & 1);
-            else if (c + 1 < n_ch) frag(pbuf ^ 1, (sidx + 1) & 1, 0, 0, (KSZ * NS) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mma((ky * NS + NS - 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if ((KSZ * NS) & 1) {   // the next chunk expects its first fragments in buffer 0
+            if ((KSZ * NS) & 1) {   // the next chunk expects its first fragments in buffer 0
 #pragma unroll
-            for (int u = 0; u < UPW; ++u) x[0][u] = x[1][u];
+                for (int u = 0; u < NU; ++u) x[0][u] = x[1][u];
 #pragma unroll
-            for (int j = 0; j < NBW; ++j) w[0][j] = w[1][j];
+                for (int j = 0; j < NBW; ++j) w[0][j] = w[1][j];
+            }
         }
-    }
+    };
+    const int n_u = keep_scalar((P.g_rt - wave_m + WM - 1) / WM);
+    if (n_u == UPW) main_loop(std::integral_constant<int, UPW>());
+    else main_loop(std::integral_constant<int, UPW - 1>());
 
     if (P.ks == 1) {
         T* const out = reinterpret_cast<T*>(P.out) + ((l16 >> 2) * P.Wout + (l16 & 3)) * P.Cout + chan;
@@ -563,7 +572,10 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
                     if (ks_eff > 1 && (size_t)ks_eff * n_units * 16 * c.Cout * 4 > scratch_bytes) continue;
                     // per stage: MFMA cycles of a SIMD (two wavefronts), LDS cycles of the CU (a 16-byte read of
                     // a wavefront takes 4), cycles to load the stage
-                    const double mfma = 1.12 * (bf16 ? 16.0 : 128.0) * upw * G.nbw * 3 * gpc * 2;
+                    // units per SIMD: the two wavefronts of a SIMD belong to wave_m groups 0/1 (narrow) or 0/2, 1/3
+                    auto nu = [&](int m) { return (g - m + G.wm - 1) / G.wm; };
+                    const int su = G.wm == 2 ? nu(0) + nu(1) : (nu(0) + nu(2) > nu(1) + nu(3) ? nu(0) + nu(2) : nu(1) + nu(3));
+                    const double mfma = 1.12 * (bf16 ? 16.0 : 128.0) * su * G.nbw * 3 * gpc;
                     const double ldsr = 8.0 * (upw + G.nbw) * 3 * gpc * 4 * 1.3;
                     const double load = ((double)g * 36 * rb / 3 + 3.0 * nt * rb) / bw;
                     double stage = mfma > load ? mfma : load;
