@@ -109,14 +109,23 @@ int32_t dc_profile_reset(void* profile);
 int32_t dc_profile_elapsed_ms(void* profile, int32_t slot, float* ms);
 
 /*
- * Overlap handle (Section 7.6: matching and inference can run asynchronously): a second
- * HIP stream and two events owned by the library object.  Passed to dc_run_stack, the
- * matching of a frame runs on that stream, next to whatever the main stream still holds of
- * the previous frame, and only the matching is waited for; without it the call waits for the
- * main stream.  For callers that may not create streams the handle is simply left out.
+ * Overlap handle (Section 7.6: matching and inference can run asynchronously): streams and
+ * events owned by the library object.  Passed to dc_run_stack,
+ *  - the matching of a frame runs on a stream of its own, next to whatever is still queued of
+ *    the previous frame, and only the matching is waited for (without a handle the call waits
+ *    for the caller's stream);
+ *  - with dc_overlap_pipeline(handle, 2) two frames are in flight: consecutive calls enqueue
+ *    their layers on two alternating internal streams, layer i of a frame waiting for layer i of
+ *    the previous frame (its cache) and for the previous frame's readers of any tensor it
+ *    overwrites.  The caller's stream is made to wait for the end of the frame, so synchronising
+ *    it still yields the frame's results.  In this mode the inputs (frames, weights) must be
+ *    complete in memory when the call is made, and the caller's own streams must be done with the
+ *    tensors handed over; the device workspace holds two sets of plans and scratch.
+ * Callers that may not create streams simply pass no handle.
  */
 int32_t dc_overlap_create(void** overlap);
 int32_t dc_overlap_destroy(void* overlap);
+int32_t dc_overlap_pipeline(void* overlap, int32_t frames_in_flight /* 1 or 2 */);
 
 /*
  * Overrides the launch heuristics of the 3x3 stride-1 GEMM kernel for the whole process (tests and

@@ -22,7 +22,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
           -4: "DC_ERR_UNSUPPORTED", -5: "DC_ERR_WORKSPACE", -6: "DC_ERR_CAPACITY", -7: "DC_ERR_HIP"}
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
-           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
+           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
            "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
@@ -73,6 +73,7 @@ def lib():
         L.dc_profile_elapsed_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
         L.dc_overlap_create.argtypes = [C.POINTER(vp)]
         L.dc_overlap_destroy.argtypes = [vp]
+        L.dc_overlap_pipeline.argtypes = [vp, i32]
         L.dc_conv_tuning.argtypes = [i32, i32, i32, i32]
         L.dc_conv_kernel_name.argtypes = [i32, C.c_char_p, sz]
         L.dc_conv_tile_shape.argtypes = [vp, i32, i32, i32, i32] + [C.POINTER(i32)] * 4
@@ -275,7 +276,7 @@ class StackRunner:
 
     def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
-                 want_regions=False, pad_input=True, overlap=True):
+                 want_regions=False, pad_input=True, overlap=True, pipeline=True):
         self.Ch_tensor = Ch
         if pad_input:
             layers, weights, self.Ch_tensor = pad_input_channels(layers, weights, Ch, dtype)
@@ -329,6 +330,9 @@ class StackRunner:
             h = C.c_void_p()
             _check("dc_overlap_create", lib().dc_overlap_create(C.byref(h)))
             self.overlap = h
+            if pipeline:
+                _check("dc_overlap_pipeline", lib().dc_overlap_pipeline(h, 2))
+        torch.cuda.synchronize(dev)   # weights and buffers are complete before any internal stream reads them
         self.regs = None
         if want_regions:
             self.regs, self._regs_store = _alloc_regions(n_streams * (nl + 1), max_rects)
@@ -349,9 +353,10 @@ class StackRunner:
         self.age = 0
 
     def step(self, frames, force_full=False):
-        """frames: uint8 cuda tensor [n][H][W][C], resident and contiguous; it is kept by reference as
-        the next step's previous frame, so the caller must not overwrite it before that step has run.
-        Returns the list of this frame's tensors."""
+        """frames: uint8 cuda tensor [n][H][W][C], resident (its producer has completed: the library reads it on
+        streams of its own) and contiguous; it is kept by reference as the next step's previous frame, so the
+        caller must not overwrite it before that step has run.  Returns the list of this frame's tensors, valid
+        once the current stream is synchronised."""
         assert frames.is_cuda and frames.dtype == torch.uint8 and frames.is_contiguous()
         assert tuple(frames.shape) == (self.n, self.H, self.W, self.Ch)
         c, p = self.cur, 1 - self.cur

@@ -83,6 +83,15 @@ int check_conv_layer(const dc_layer* l) {
     return DC_OK;
 }
 
+// Waits for an event by polling: the host thread is needed again within tens of microseconds, which a
+// blocking wait's wake-up latency would double.
+hipError_t spin_wait(hipEvent_t e) {
+    for (;;) {
+        const hipError_t q = hipEventQuery(e);
+        if (q != hipErrorNotReady) return q;
+    }
+}
+
 // Copy + conv launches of one layer given its packed plan on the device.
 struct Bracket {   // records a profile slot around a launch when a profile is attached
     Profile* p; int slot; hipStream_t st;
@@ -194,10 +203,11 @@ int32_t dc_overlap_create(void** overlap) {
     if (!o) return DC_ERR_WORKSPACE;
     bool ok = hipStreamCreateWithFlags(&o->aux, hipStreamNonBlocking) == hipSuccess;
     for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&o->upload_done[i], hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i) ok = hipStreamCreateWithFlags(&o->work[i], hipStreamNonBlocking) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&o->frame_done[i], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&o->match_done, hipEventDisableTiming) == hipSuccess;
     if (!ok) {
-        for (int i = 0; i < 2; ++i) if (o->upload_done[i]) (void)hipEventDestroy(o->upload_done[i]);
-        if (o->aux) (void)hipStreamDestroy(o->aux);
-        delete o;
+        (void)dc_overlap_destroy(o);
         return DC_ERR_HIP;
     }
     *overlap = o;
@@ -207,10 +217,26 @@ int32_t dc_overlap_create(void** overlap) {
 int32_t dc_overlap_destroy(void* overlap) {
     if (!overlap) return DC_ERR_NULL_PTR;
     Overlap* o = static_cast<Overlap*>(overlap);
-    (void)hipStreamSynchronize(o->aux);
-    for (int i = 0; i < 2; ++i) (void)hipEventDestroy(o->upload_done[i]);
-    (void)hipStreamDestroy(o->aux);
+    if (o->aux) (void)hipStreamSynchronize(o->aux);
+    for (int i = 0; i < 2; ++i) {
+        if (o->work[i]) (void)hipStreamSynchronize(o->work[i]);
+        if (o->upload_done[i]) (void)hipEventDestroy(o->upload_done[i]);
+        if (o->frame_done[i]) (void)hipEventDestroy(o->frame_done[i]);
+        for (hipEvent_t e : o->layer_done[i]) (void)hipEventDestroy(e);
+        if (o->work[i]) (void)hipStreamDestroy(o->work[i]);
+    }
+    if (o->match_done) (void)hipEventDestroy(o->match_done);
+    if (o->aux) (void)hipStreamDestroy(o->aux);
     delete o;
+    return DC_OK;
+}
+
+int32_t dc_overlap_pipeline(void* overlap, int32_t frames_in_flight) {
+    if (!overlap) return DC_ERR_NULL_PTR;
+    if (frames_in_flight < 1 || frames_in_flight > 2) return DC_ERR_INVALID_ARG;
+    Overlap* o = static_cast<Overlap*>(overlap);
+    for (int i = 0; i < 2; ++i) DC_TRY_HIP(hipStreamSynchronize(o->work[i]));
+    o->pipeline = frames_in_flight == 2;
     return DC_OK;
 }
 
@@ -400,7 +426,7 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
     total += align_up((size_t)n_layers * sizeof(CopyLayerDev), 256);
     const size_t nb = (size_t)n_streams * (H / block) * (W / block);
     size_t match_host = align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
-    *dev_bytes = total + kConvScratchBytes;   // plans, then room for partial sums of a split K
+    *dev_bytes = 2 * align_up(total, 256) + 2 * kConvScratchBytes;   // two frames in flight: plans and K-split scratch for each
     *host_bytes = 2 * total + match_host;   // two staging halves (used alternately with an overlap handle)
     return DC_OK;
 }
@@ -438,11 +464,43 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         if (ws_dev_bytes < need_dev || ws_host_bytes < need_host) return DC_ERR_WORKSPACE;
     }
     Overlap* ov = static_cast<Overlap*>(overlap);
-    hipStream_t st = as_stream(stream);
-    // the tail of the device workspace (beyond every plan) holds the partial sums of a split K
+    hipStream_t caller_st = as_stream(stream);
+    // Pipelined: this frame's work goes to one of the handle's two streams, the previous frame's is on the other.
+    const bool pipe = ov && ov->pipeline;
+    const int fp = pipe ? ov->frame_parity : 0;
+    hipStream_t st = pipe ? ov->work[fp] : caller_st;
+    if (pipe) {
+        try {
+            for (int p = 0; p < 2; ++p)
+                while ((int)ov->layer_done[p].size() < n_layers) {
+                    hipEvent_t e;
+                    DC_TRY_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+                    ov->layer_done[p].push_back(e);
+                }
+        } catch (const std::bad_alloc&) {
+            return DC_ERR_WORKSPACE;
+        }
+    }
+    // last layer that reads each tensor: a layer that overwrites a single-buffered tensor waits for it
+    std::vector<int> last_reader(n_layers + 1, -1);
+    for (int i = 0; i < n_layers; ++i) {
+        last_reader[layers[i].in0] = i;
+        if (layers[i].type == DC_ADD) last_reader[layers[i].in1] = i;
+    }
+    int waited = -1;
+    auto wait_prev = [&](int w) -> hipError_t {     // the previous frame has finished its layers 0..w
+        if (!pipe || w <= waited) return hipSuccess;
+        waited = w;
+        return hipStreamWaitEvent(st, ov->layer_done[1 - fp][w], 0);
+    };
+    // Device workspace: [plans, frame parity 0][plans, parity 1][K-split scratch 0][scratch 1]
+    unsigned char* plan_dev = nullptr;
     unsigned char* conv_scratch = nullptr;
-    if (ws_dev && ws_dev_bytes >= kConvScratchBytes)
-        conv_scratch = static_cast<unsigned char*>(ws_dev) + (ws_dev_bytes - kConvScratchBytes) / 256 * 256;
+    if (ws_dev && ws_dev_bytes >= 2 * kConvScratchBytes) {
+        const size_t plan_half = (ws_dev_bytes - 2 * kConvScratchBytes) / 2 / 256 * 256;
+        plan_dev = static_cast<unsigned char*>(ws_dev) + (size_t)fp * plan_half;
+        conv_scratch = static_cast<unsigned char*>(ws_dev) + 2 * plan_half + (size_t)fp * kConvScratchBytes;
+    }
     const int gh = H / block, gw = W / block;
     const size_t nb = (size_t)n_streams * gh * gw;
 
@@ -471,8 +529,14 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         DC_TRY_HIP(hipMemcpyAsync(h_mask, block_mask, nb, hipMemcpyDeviceToHost, mst));
         DC_TRY_HIP(hipMemcpyAsync(h_gmv, global_mv, (size_t)n_streams * 2 * sizeof(int32_t), hipMemcpyDeviceToHost, mst));
         // the network input does not depend on the match: its conversion overlaps the readback
+        DC_TRY_HIP(wait_prev(last_reader[0]));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
-        DC_TRY_HIP(hipStreamSynchronize(mst));
+        if (ov) {
+            DC_TRY_HIP(hipEventRecord(ov->match_done, mst));
+            DC_TRY_HIP(spin_wait(ov->match_done));
+        } else {
+            DC_TRY_HIP(hipStreamSynchronize(mst));
+        }
         try {
             regs.resize(n_streams);
             std::vector<dc_rect> rects0;
@@ -494,11 +558,12 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             const size_t half = (ws_host_bytes - (size_t)(hbase - static_cast<unsigned char*>(ws_host))) / 2 / 256 * 256;
             hbase += (size_t)ov->parity * half;
             if (ov->pending[ov->parity]) {
-                DC_TRY_HIP(hipEventSynchronize(ov->upload_done[ov->parity]));
+                DC_TRY_HIP(spin_wait(ov->upload_done[ov->parity]));
                 ov->pending[ov->parity] = false;
             }
         }
     } else {
+        DC_TRY_HIP(wait_prev(last_reader[0]));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
     }
     if (regions_out) {
@@ -548,7 +613,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 plan_stream(g.rects.data(), (int)g.rects.size(), g.dx, g.dy, s, hs[i + 1], ws[i + 1], tilings[i].th,
                             tilings[i].tw, plan);
             }
-            addrs[i] = pack_plan(plan, hbase + off, static_cast<unsigned char*>(ws_dev) + off);
+            addrs[i] = pack_plan(plan, hbase + off, plan_dev + off);
             off += addrs[i].bytes;
             int64_t issued = (int64_t)plan.tiles.size() * tilings[i].th * tilings[i].tw * mac_px;
             local.macs_needed += (px - plan.reused_px) * mac_px;
@@ -560,9 +625,12 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     } catch (const std::bad_alloc&) {
         return DC_ERR_WORKSPACE;
     }
-    // ---- the shifted copies of all layers in one launch (16-byte vector path only) ----
+    // ---- the shifted copies of all layers in one launch (16-byte vector path only); pipelined: one launch per
+    // run of consecutive conv layers, issued when the previous frame has finished that run ----
     std::vector<char> copy_fused(n_layers, 0);
-    size_t all_rects_off = 0, copy_layers_off = 0, n_all_rects = 0, max_vec = 0;
+    struct CopyGroup { int first_layer, last_layer; size_t rect_begin, rect_end, max_vec; };
+    std::vector<CopyGroup> groups;
+    size_t all_rects_off = 0, copy_layers_off = 0, n_all_rects = 0;
     if (cached) {
         try {
             std::vector<RectDev> all_rects;
@@ -575,11 +643,19 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                     continue;
                 copy_fused[i] = 1;
                 const int pv = (int)(px_bytes / 16);
+                // a new group starts at the first layer and, when pipelined, after every layer that is not a conv
+                bool fresh = groups.empty();
+                if (!fresh && pipe)
+                    for (int j = groups.back().last_layer + 1; j < i; ++j) fresh |= layers[j].type != DC_CONV;
+                if (fresh) groups.push_back(CopyGroup{i, i, all_rects.size(), all_rects.size(), 0});
+                CopyGroup& g = groups.back();
+                g.last_layer = i;
                 for (RectDev r : plans[i].rects) {
                     r.pad = (int)copy_layers.size();
                     all_rects.push_back(r);
-                    max_vec = std::max(max_vec, (size_t)r.w * r.h * pv);
+                    g.max_vec = std::max(g.max_vec, (size_t)r.w * r.h * pv);
                 }
+                g.rect_end = all_rects.size();
                 copy_layers.push_back(CopyLayerDev{tensors_prev[i + 1], tensors_cur[i + 1], hs[i + 1], ws[i + 1], pv, 0});
             }
             n_all_rects = all_rects.size();
@@ -596,19 +672,24 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         }
     }
     if (cached && off) {
-        DC_TRY_HIP(hipMemcpyAsync(ws_dev, hbase, off, hipMemcpyHostToDevice, st));
+        DC_TRY_HIP(hipMemcpyAsync(plan_dev, hbase, off, hipMemcpyHostToDevice, st));
         if (ov) {
             DC_TRY_HIP(hipEventRecord(ov->upload_done[ov->parity], st));
             ov->pending[ov->parity] = true;
             ov->parity ^= 1;
         }
     }
-    if (n_all_rects) {
-        unsigned char* d = static_cast<unsigned char*>(ws_dev);
-        Bracket b(stats ? static_cast<Profile*>(stats->profile) : nullptr, n_layers, st);   // first copy slot
-        DC_TRY_HIP(launch_shifted_copy_all(reinterpret_cast<const RectDev*>(d + all_rects_off), (int)n_all_rects,
-                                           reinterpret_cast<const CopyLayerDev*>(d + copy_layers_off), max_vec, st));
-    }
+    size_t next_group = 0;
+    auto launch_copy_group = [&](int layer) -> int {     // the group that starts at `layer`, if any
+        if (next_group >= groups.size() || groups[next_group].first_layer != layer) return DC_OK;
+        const CopyGroup& g = groups[next_group++];
+        DC_TRY_HIP(wait_prev(g.last_layer));
+        Bracket b(stats ? static_cast<Profile*>(stats->profile) : nullptr, n_layers + g.first_layer, st);
+        DC_TRY_HIP(launch_shifted_copy_all(reinterpret_cast<const RectDev*>(plan_dev + all_rects_off) + g.rect_begin,
+                                           (int)(g.rect_end - g.rect_begin),
+                                           reinterpret_cast<const CopyLayerDev*>(plan_dev + copy_layers_off), g.max_vec, st));
+        return DC_OK;
+    };
 
     // ---- layers ----
     for (int i = 0; i < n_layers; ++i) {
@@ -616,6 +697,9 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         const int a = l.in0, t = i + 1;
         switch (l.type) {
             case DC_CONV:
+                rc = launch_copy_group(i);
+                if (rc) return rc;
+                DC_TRY_HIP(wait_prev(i));       // its cache: the previous frame's output of this layer
                 rc = run_conv_planned(l, tensors_cur[a], weights[i], bias ? bias[i] : nullptr,
                                       cached ? tensors_prev[t] : nullptr, tensors_cur[t], n_streams, hs[a], ws[a], dtype,
                                       tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st,
@@ -625,18 +709,28 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 if (rc) return rc;
                 break;
             case DC_MAXPOOL:
+                DC_TRY_HIP(wait_prev(last_reader[t]));
                 DC_TRY_HIP(launch_maxpool(tensors_cur[a], tensors_cur[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
                                           dtype, st));
                 break;
             case DC_ADD:
+                DC_TRY_HIP(wait_prev(last_reader[t]));
                 DC_TRY_HIP(launch_add(tensors_cur[a], tensors_cur[l.in1], tensors_cur[t],
                                       (size_t)n_streams * hs[t] * ws[t] * cs[t], l.relu, dtype, st));
                 break;
             default:
+                DC_TRY_HIP(wait_prev(last_reader[t]));
                 DC_TRY_HIP(launch_add(tensors_cur[a], nullptr, tensors_cur[t], (size_t)n_streams * hs[t] * ws[t] * cs[t],
                                       1, dtype, st));
                 break;
         }
+        if (pipe) DC_TRY_HIP(hipEventRecord(ov->layer_done[fp][i], st));
+    }
+    if (pipe) {
+        // the caller's stream sees the frame complete; the next frame goes to the other work stream
+        DC_TRY_HIP(hipEventRecord(ov->frame_done[fp], st));
+        DC_TRY_HIP(hipStreamWaitEvent(caller_st, ov->frame_done[fp], 0));
+        ov->frame_parity ^= 1;
     }
     if (stats) *stats = local;
     return DC_OK;

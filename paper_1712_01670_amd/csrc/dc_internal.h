@@ -107,13 +107,22 @@ struct Profile {
     std::vector<uint8_t> used;
 };
 
-// Second stream and events for running a frame's matching while the previous frame's layers are
-// still executing (Section 7.6: the two stages can be carried out asynchronously).
+// Streams and events of an overlap handle (Section 7.6: the stages can be carried out asynchronously).
+//  - aux: the matching of a frame and the read-back of its mask run here, next to the previous frame's layers;
+//  - pipeline: consecutive frames alternate between two work streams; layer i of a frame waits for layer i of
+//    the previous frame (its cache) and for the previous frame's readers of every single-buffered tensor it
+//    overwrites, so two frames are in flight and the second fills the CUs the first leaves idle.
 struct Overlap {
     hipStream_t aux = nullptr;
+    hipEvent_t match_done = nullptr;                  // mask and motion of the current frame are in host memory
     hipEvent_t upload_done[2] = {nullptr, nullptr};   // plan upload from staging half 0 / 1 has completed
     bool pending[2] = {false, false};
     int parity = 0;
+    bool pipeline = false;
+    hipStream_t work[2] = {nullptr, nullptr};
+    hipEvent_t frame_done[2] = {nullptr, nullptr};
+    std::vector<hipEvent_t> layer_done[2];            // [frame parity][layer]
+    int frame_parity = 0;
 };
 
 inline size_t dtype_size(int dtype) { return dtype == DC_BF16 ? 2 : 4; }

@@ -215,3 +215,40 @@ def test_throughput_mode_64_streams_bf16_sampled(oracle):
             for s in range(0, n, 7):
                 m = oracle.match_blocks(videos[s, t], videos[s, t - 1], 16, 16, synth.max_block_ssd(16))
                 assert np.array_equal(masks[s], m["mask"]) and gmv[s].tolist() == m["gmv"].tolist()
+
+
+@pytest.mark.parametrize("net,size,bf16", [("vgg16", 96, False), ("resnet", 64, True)])
+def test_overlap_modes_give_identical_tensors(net, size, bf16):
+    """Two frames in flight, matching on a second stream only, and everything on the caller's stream run the
+    same kernels with the same plans: every tensor of every frame must be bit-identical, also when the frames
+    are issued back to back without any synchronisation in between (Section 7.6: asynchronous stages)."""
+    H = W = size
+    if net == "vgg16":
+        layers = synth.vgg16()
+        ws, bs = synth.he_weights(layers, 3, bias_scale=0.05)
+    else:
+        layers = synth.resnet50_trunk()[:24]       # stem, pool, the first two bottleneck blocks
+        ws, bs = synth.he_weights(layers, 3, bias_scale=0.05, residual_scale=0.5)
+    T = 14
+    video = torch.from_numpy(synth.panning_video(77, n_frames=T, H=H, W=W, fg=((24, 24), (16, 32)))).to(DEV)
+    frames = [video[t:t + 1].contiguous() for t in range(T)]
+    torch.cuda.synchronize()
+    dt = binding.DC_BF16 if bf16 else binding.DC_F32
+    results = {}
+    for mode, kw in (("pipeline", dict(overlap=True, pipeline=True)), ("overlap", dict(overlap=True, pipeline=False)),
+                     ("plain", dict(overlap=False))):
+        print(f"[overlap modes] {net} {mode}", flush=True)
+        runner = binding.StackRunner(layers, ws, bs, 1, H, W, 3, block=16, radius=16, dtype=dt, expiry=5, **kw)
+        kept = []
+        for stop in (3, 8, T):                        # the tensors are read when a run of frames has drained
+            runner.reset()
+            for t in range(stop):
+                tensors = runner.step(frames[t])      # no synchronisation between the frames of a run
+            torch.cuda.synchronize()
+            kept.append([x.clone() for x in tensors])
+        results[mode] = kept
+        del runner
+    for mode in ("overlap", "plain"):
+        for f, (a, b) in enumerate(zip(results["pipeline"], results[mode])):
+            for i, (x, y) in enumerate(zip(a, b)):
+                assert torch.equal(x, y), (net, mode, f, i)
