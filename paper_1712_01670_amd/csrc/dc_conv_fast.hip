@@ -537,11 +537,11 @@ void init_tuning() {
 // are resident together, and only the stage work of resident workgroups adds up, the fixed costs overlap.
 // ks > 1 adds the reduction kernel.
 FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) {
-    static double bw = -1, stage_fix = 0, wg_fix = 0, red_fix = 0;
+    static double bw = -1, stage_fix = 0, wg_fix = 0, red_fix = 0, occ1_penalty = 1.08, lds_cap_kb = 160;
     if (bw < 0) {
-        const char* e = getenv("DC_CONV_MODEL");   // "bytes/clk/CU,stage,wg,reduce" (experiments)
+        const char* e = getenv("DC_CONV_MODEL");   // "bytes/clk/CU,stage,wg,reduce,penalty" (experiments)
         bw = 24; stage_fix = 250; wg_fix = 4500; red_fix = 13000;
-        if (e) sscanf(e, "%lf,%lf,%lf,%lf", &bw, &stage_fix, &wg_fix, &red_fix);
+        if (e) sscanf(e, "%lf,%lf,%lf,%lf,%lf,%lf", &bw, &stage_fix, &wg_fix, &red_fix, &occ1_penalty, &lds_cap_kb);
     }
     const bool bf16 = c.dtype == DC_BF16;
     const int esz = bf16 ? 2 : 4, kg = bf16 ? 32 : 16;
@@ -562,6 +562,7 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
             for (int g = 1; g <= G.wm * G.max_upw; ++g) {
                 const int upw = (g + G.wm - 1) / G.wm;
                 if (fast_lds_bytes(geom, kci, upw) > 160 * 1024) continue;
+                if (geom == 0 && !bf16 && fast_lds_bytes(geom, kci, upw) > (size_t)(lds_cap_kb * 1024)) continue;
                 const long groups = (n_units + g - 1) / g;
                 int last_cps = 0;
                 for (int ks = 1; ks <= n_chunks && ks <= 64; ++ks) {
@@ -592,6 +593,9 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
                     if (occ > 4) occ = 4;
                     if (occ < 1) occ = 1;
                     double cost = rounds * work + (double)((per_cu + occ - 1) / occ) * fixed;
+                    // a lone workgroup per CU leaves the matrix cores idle during its barriers, prologue and epilogue,
+                    // and leaves no room for the workgroups of the other frame in flight (measured: 5 % per frame)
+                    if (occ < 2) cost *= occ1_penalty;
                     if (ks_eff > 1) cost += red_fix + (double)(ks_eff + 1) * n_units * 16 * c.Cout * 4 / 1200.0;
                     if (cost < best.cost) best = FastChoice{g, ks_eff, kci, cost, geom};
                 }
