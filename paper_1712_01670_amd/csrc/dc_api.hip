@@ -487,6 +487,21 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         last_reader[layers[i].in0] = i;
         if (layers[i].type == DC_ADD) last_reader[layers[i].in1] = i;
     }
+    // conv layers wait per run of consecutive conv layers (for the last one of the run): fewer cross-stream
+    // dependencies, and the copies of a run go out in one launch
+    std::vector<int> run_end(n_layers, -1);
+    for (int i = n_layers - 1; i >= 0; --i)
+        if (layers[i].type == DC_CONV)
+            run_end[i] = (i + 1 < n_layers && layers[i + 1].type == DC_CONV) ? run_end[i + 1] : i;
+    // only the layers that the next frame can wait for get an event
+    std::vector<char> is_target(n_layers, 0);
+    if (pipe) {
+        if (last_reader[0] >= 0) is_target[last_reader[0]] = 1;
+        for (int i = 0; i < n_layers; ++i) {
+            if (layers[i].type == DC_CONV) is_target[run_end[i]] = 1;
+            else if (last_reader[i + 1] >= 0) is_target[last_reader[i + 1]] = 1;
+        }
+    }
     int waited = -1;
     auto wait_prev = [&](int w) -> hipError_t {     // the previous frame has finished its layers 0..w
         if (!pipe || w <= waited) return hipSuccess;
@@ -683,7 +698,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     auto launch_copy_group = [&](int layer) -> int {     // the group that starts at `layer`, if any
         if (next_group >= groups.size() || groups[next_group].first_layer != layer) return DC_OK;
         const CopyGroup& g = groups[next_group++];
-        DC_TRY_HIP(wait_prev(g.last_layer));
+        DC_TRY_HIP(wait_prev(run_end[g.last_layer]));
         Bracket b(stats ? static_cast<Profile*>(stats->profile) : nullptr, n_layers + g.first_layer, st);
         DC_TRY_HIP(launch_shifted_copy_all(reinterpret_cast<const RectDev*>(plan_dev + all_rects_off) + g.rect_begin,
                                            (int)(g.rect_end - g.rect_begin),
@@ -699,7 +714,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             case DC_CONV:
                 rc = launch_copy_group(i);
                 if (rc) return rc;
-                DC_TRY_HIP(wait_prev(i));       // its cache: the previous frame's output of this layer
+                DC_TRY_HIP(wait_prev(run_end[i]));   // its cache: the previous frame's output of this layer (whole run)
                 rc = run_conv_planned(l, tensors_cur[a], weights[i], bias ? bias[i] : nullptr,
                                       cached ? tensors_prev[t] : nullptr, tensors_cur[t], n_streams, hs[a], ws[a], dtype,
                                       tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st,
@@ -724,7 +739,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                                       1, dtype, st));
                 break;
         }
-        if (pipe) DC_TRY_HIP(hipEventRecord(ov->layer_done[fp][i], st));
+        if (pipe && is_target[i]) DC_TRY_HIP(hipEventRecord(ov->layer_done[fp][i], st));
     }
     if (pipe) {
         // the caller's stream sees the frame complete; the next frame goes to the other work stream
