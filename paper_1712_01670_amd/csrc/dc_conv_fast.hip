@@ -10,10 +10,11 @@
 //   stage      = one kernel row (3 taps) x one channel chunk (KC channels)
 //
 // LDS: the patch of a unit is 6 lines of 8 row slots (6 used), one row = KC channels = RB bytes.
-// Chunk c (16 bytes) of the row at (line py, slot px) sits at chunk position c ^ sw(py, px) with
-// sw = (py % 4) * (4 / RPC) + (px % 4) / RPC, RPC = 256 / RB: the 16 pixels of a unit at any tap
-// then fall into 16 different 16-byte bank groups.  Weight rows use (row / RPC) % NVEC as in the
-// general kernel.  Both buffers are filled by buffer_load ... lds, double-buffered; the patch of
+// Chunk c (16 bytes) of the row at (line py, slot px) sits at chunk position c ^ sw(py, px), of weight row
+// r at c ^ (r / 2) % NVEC.  sw = (2 py + px / 4) % 4 for 64-byte rows, (py % 4) * 2 + (px % 4) / 2 for
+// 128-byte rows: these are the swizzles for which SQ_LDS_BANK_CONFLICT stays at zero for every tap (a
+// 16-byte read of a wavefront is not served 16 consecutive lanes at a time, so "16 different bank groups
+// per quarter wavefront" is not the rule; the candidates were measured).  Both buffers are filled by buffer_load ... lds, double-buffered; the patch of
 // the next chunk arrives in three parts, one per stage.
 //
 // Few units and a deep K (the small maps at the end of a stack): the launch splits the channel
@@ -82,6 +83,12 @@ __device__ __forceinline__ void decode_units_fast(const ConvParams& P, const Fas
     __syncthreads();
 }
 
+// Chunk swizzle of the patch row at (line py, slot px) for rows of RB bytes.
+template <int RB>
+__device__ __forceinline__ int patch_swizzle(int py, int px) {
+    return RB == 64 ? (2 * py + px / 4) % 4 : (py % 4) * 2 + (px % 4) / 2;
+}
+
 template <typename T, int KSZ, int KC, int UPW, int WM, int WN, int NBW>
 __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     typedef Frag<T> F;
@@ -96,7 +103,6 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     constexpr int GPC = KC / KG;                // K groups per chunk
     constexpr int NVEC = KC / VE;               // 16-byte chunks per row
     constexpr int RB = KC * ES;                 // row bytes
-    constexpr int RPC = 256 / RB;               // rows per pass over the banks
     constexpr int RPI = 64 / NVEC;              // rows per load instruction (1 KiB)
     constexpr int PWP = 8;                      // row slots per patch line
     constexpr int PH = 3 + KSZ;                 // patch lines and used slots per line
@@ -138,7 +144,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     for (int i = 0; i < NWI; ++i) {
         const int row = (wave + i * NW) * RPI + lrow;   // tl * NT + n
         const int tl = row / NT, n = row - tl * NT;
-        const int c = lpos ^ ((row / RPC) % NVEC);
+        const int c = lpos ^ ((row / 2) % NVEC);
         wgo[i] = tl < KSZ ? (uint32_t)(((n0 + n) * (KSZ * KSZ) + tl) * Cin) * ES + (uint32_t)(c << 4) : kOob;
     }
 
@@ -177,7 +183,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
             unit = unit < G ? unit : G - 1;
             const int4 uq = H.uq[unit];
             const int py = part * (RPI / PWP) + pyl;
-            const int sw = (py % 4) * (4 / RPC) + (px % 4) / RPC;
+            const int sw = patch_swizzle<RB>(py, px);
             const bool ok = px < PH && (unsigned)(uq.y + py) < (unsigned)P.Hin && (unsigned)(uq.z + px) < (unsigned)P.Win;
             pgo[i] = ok ? (uint32_t)(uq.x + py * (P.Win * CinES) + pxoff + ((lpos ^ sw) << 4)) : kOob;
         }
@@ -203,7 +209,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
 #pragma unroll
         for (int t = 0; t < KSZ * KSZ; ++t) {
             const int py = oy + t / KSZ, px = ox + t % KSZ;
-            const int sw = (py % 4) * (4 / RPC) + (px % 4) / RPC;
+            const int sw = patch_swizzle<RB>(py, px);
 #pragma unroll
             for (int g = 0; g < GPC; ++g)
                 paddr[t][g] = (wave_m * PR + py * PWP + px) * RB + (((g * 4 + q) ^ sw) << 4);
@@ -212,7 +218,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     int waddr[GPC];
 #pragma unroll
     for (int g = 0; g < GPC; ++g)
-        waddr[g] = (wave_n * NBW * 16 + l16) * RB + (((g * 4 + q) ^ ((l16 / RPC) % NVEC)) << 4);
+        waddr[g] = (wave_n * NBW * 16 + l16) * RB + (((g * 4 + q) ^ ((l16 / 2) % NVEC)) << 4);
 
     floatx4 acc[UPW][NBW];
 #pragma unroll
