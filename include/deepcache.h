@@ -189,6 +189,23 @@ int32_t dc_propagate_regions(const dc_layer* layers, int32_t n_layers, int32_t H
                              int32_t block, const uint8_t* block_mask, int32_t gh, int32_t gw,
                              int32_t mx, int32_t my, dc_regions* regions);
 
+/*
+ * Packed weights (a layout choice of this library, not part of the method): the weights of a
+ * 3x3 stride-1 layer with cout % 64 == 0 and cin * element size % 64 == 0, re-laid as
+ * [cout/16][cin*es/64][3*3][16][64 bytes], so that the 64-byte channel runs the GEMM kernel
+ * stages per load instruction are contiguous in memory and whole cache lines are used (the
+ * strided runs of [cout][k][k][cin] use half of every line they touch).  The weights are constant
+ * over a video, so they are packed once.
+ *   dc_packed_weights_bytes  size of the packed copy; 0: the layer has no packed form
+ *   dc_pack_conv_weights     weights dev [cout][3][3][cin] -> packed dev, both 16-byte aligned, distinct;
+ *                            DC_ERR_BAD_SHAPE for a layer without a packed form
+ * A packed copy passed to dc_cached_conv_layer / dc_run_stack next to the plain weights is used
+ * where the kernel chosen for the layer reads it; results are identical bit for bit.
+ */
+int32_t dc_packed_weights_bytes(const dc_layer* layer, int32_t dtype, size_t* bytes);
+int32_t dc_pack_conv_weights(const dc_layer* layer, const void* weights, int32_t dtype,
+                             void* packed, void* stream);
+
 /* Bytes of device / host workspace dc_cached_conv_layer needs for the given shape. */
 int32_t dc_conv_workspace_bytes(const dc_layer* layer, int32_t n_streams, int32_t Hin,
                                 int32_t Win, int32_t max_rects_per_stream,
@@ -199,6 +216,7 @@ int32_t dc_conv_workspace_bytes(const dc_layer* layer, int32_t n_streams, int32_
  * c_forward(top, bottom, c_blob, c_regions)).
  *   in          dev [n_streams][Hin][Win][cin]       current input map (complete)
  *   weights     dev [cout][k][k][cin], bias dev fp32 [cout] or NULL
+ *   packed_weights  dev, optional (NULL): the result of dc_pack_conv_weights for `weights`
  *   cache_prev  dev [n_streams][Hout][Wout][cout]    this layer's output for the previous frame
  *   out         dev [n_streams][Hout][Wout][cout]    written completely; must not alias cache_prev
  *   regions     host [n_streams]: reusable rectangles of the OUTPUT tensor and their source
@@ -210,7 +228,7 @@ int32_t dc_conv_workspace_bytes(const dc_layer* layer, int32_t n_streams, int32_
  *               staging must stay untouched until the stream has passed this call
  */
 int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* weights,
-                             const float* bias, const void* cache_prev, void* out,
+                             const void* packed_weights, const float* bias, const void* cache_prev, void* out,
                              int32_t n_streams, int32_t Hin, int32_t Win,
                              const dc_regions* regions, int32_t dtype,
                              void* ws_dev, size_t ws_dev_bytes,
@@ -236,6 +254,8 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
  * merge, propagate, then per layer shifted copy + convolution of dirty tiles, with
  * pooling / add / ReLU layers computed in full.
  *   weights, bias   host arrays [n_layers] of dev pointers (NULL for non-conv layers)
+ *   packed_weights  optional (NULL) host array [n_layers] of dev pointers: packed copies of the
+ *                   weights (NULL entries for layers without one)
  *   frames_cur      dev u8 [n_streams][H][W][C]
  *   frames_prev     dev u8, previous frames (cache keys); ignored when force_full
  *   tensors_cur     host array [n_layers+1] of dev pointers, every tensor of this frame
@@ -257,7 +277,8 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
  * is asynchronous.
  */
 int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers,
-                     const void* const* weights, const float* const* bias,
+                     const void* const* weights, const void* const* packed_weights,
+                     const float* const* bias,
                      const uint8_t* frames_cur, const uint8_t* frames_prev,
                      void* const* tensors_cur, const void* const* tensors_prev,
                      int32_t n_streams, int32_t H, int32_t W, int32_t C, int32_t dtype,

@@ -23,7 +23,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
            "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
-           "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
+           "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
 
@@ -80,12 +80,14 @@ def lib():
         L.dc_match_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
         L.dc_propagate_regions.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, vp]
         L.dc_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
-        L.dc_cached_conv_layer.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp, sz, vp, sz, vp]
+        L.dc_packed_weights_bytes.argtypes = [vp, i32, C.POINTER(sz)]
+        L.dc_pack_conv_weights.argtypes = [vp, vp, i32, vp, vp]
+        L.dc_cached_conv_layer.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp, sz, vp, sz, vp]
         L.dc_frame_to_tensor.argtypes = [vp, vp, sz, i32, i32, i32, vp]
         L.dc_maxpool_layer.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
         L.dc_add_layer.argtypes = [vp, vp, vp, sz, i32, i32, vp]
         L.dc_stack_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
-        L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, i32,
+        L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, i32,
                                    vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp, vp]
         for name in EXPORTS:
             if name != "dc_status_string":
@@ -189,9 +191,26 @@ class _Workspace:
 _conv_ws = _Workspace()
 
 
-def dc_cached_conv_layer(layer, x, weights, bias, cache_prev=None, regions=None, out=None):
+def dc_pack_conv_weights(layer, weights):
+    """Packed copy of the weights [cout][3][3][cin] (cuda, fp32 or bf16) of a layer, or None if the layer has
+    no packed form."""
+    assert weights.is_cuda and weights.is_contiguous()
+    dtype = DC_BF16 if weights.dtype == torch.bfloat16 else DC_F32
+    Lc = layers_to_c([layer])
+    nb = C.c_size_t()
+    _check("dc_packed_weights_bytes", lib().dc_packed_weights_bytes(Lc, dtype, C.byref(nb)))
+    if nb.value == 0:
+        return None
+    assert nb.value == weights.numel() * weights.element_size()
+    packed = torch.empty_like(weights)
+    _check("dc_pack_conv_weights", lib().dc_pack_conv_weights(Lc, _ptr(weights), dtype, _ptr(packed), _stream()))
+    return packed
+
+
+def dc_cached_conv_layer(layer, x, weights, bias, cache_prev=None, regions=None, out=None, packed=None):
     """x [n][Hin][Win][cin] cuda (fp32 or bf16); weights [cout][k][k][cin] same dtype; bias fp32 or None.
-    regions: list (per stream) of (rects int32 [m][4], (dx, dy)) for the output tensor, or None."""
+    regions: list (per stream) of (rects int32 [m][4], (dx, dy)) for the output tensor, or None.
+    packed: the result of dc_pack_conv_weights for `weights`, or None."""
     assert x.is_cuda and x.is_contiguous() and x.dim() == 4
     dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
     assert weights.dtype == x.dtype and weights.is_contiguous()
@@ -217,7 +236,7 @@ def dc_cached_conv_layer(layer, x, weights, bias, cache_prev=None, regions=None,
     _check("dc_conv_workspace_bytes", lib().dc_conv_workspace_bytes(Lc, n, Hin, Win, max_rects, C.byref(db), C.byref(hb)))
     wd, wh = _conv_ws.get(db.value, hb.value, x.device)
     _check("dc_cached_conv_layer", lib().dc_cached_conv_layer(
-        Lc, _ptr(x), _ptr(weights), _ptr(bias), _ptr(cache_prev), _ptr(out), n, Hin, Win, regs, dtype,
+        Lc, _ptr(x), _ptr(weights), _ptr(packed), _ptr(bias), _ptr(cache_prev), _ptr(out), n, Hin, Win, regs, dtype,
         _ptr(wd), wd.numel(), C.c_void_p(wh.data_ptr()), wh.numel(), _stream()))
     _conv_ws.busy = torch.cuda.Event()
     _conv_ws.busy.record()
@@ -276,7 +295,7 @@ class StackRunner:
 
     def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
-                 want_regions=False, pad_input=True, overlap=True, pipeline=True):
+                 want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True):
         self.Ch_tensor = Ch
         if pad_input:
             layers, weights, self.Ch_tensor = pad_input_channels(layers, weights, Ch, dtype)
@@ -291,6 +310,9 @@ class StackRunner:
         self.w = [None if w is None else torch.from_numpy(w).to(self.device).to(td).contiguous() for w in weights]
         self.b = [None if b is None else torch.from_numpy(b).to(self.device).float().contiguous() for b in biases]
         self._wp = (C.c_void_p * nl)(*[None if w is None else w.data_ptr() for w in self.w])
+        torch.cuda.set_device(self.device)
+        self.w_packed = [None if (w is None or not pack_weights) else dc_pack_conv_weights(L, w) for L, w in zip(layers, self.w)]
+        self._wpp = (C.c_void_p * nl)(*[None if w is None else w.data_ptr() for w in self.w_packed])
         self._bp = (C.c_void_p * nl)(*[None if b is None else b.data_ptr() for b in self.b])
         self.shapes = synth.tensor_shapes(layers, H, W, self.Ch_tensor)
         # conv outputs are cache values: two copies (previous / current frame); the rest is shared
@@ -362,7 +384,7 @@ class StackRunner:
         c, p = self.cur, 1 - self.cur
         full = force_full or not self.have_prev or (self.expiry > 0 and self.age >= self.expiry)
         _check("dc_run_stack", lib().dc_run_stack(
-            self.Lc, len(self.layers), self._wp, self._bp, _ptr(frames), _ptr(self.prev_frames),
+            self.Lc, len(self.layers), self._wp, self._wpp, self._bp, _ptr(frames), _ptr(self.prev_frames),
             self._tp[c], self._tp[p], self.n, self.H, self.W, self.Ch, self.dtype, self.block, self.radius,
             self.max_block_ssd, int(full), _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
             _ptr(self.mask), self.max_rects, self.regs, _ptr(self.ws_dev), self.ws_dev.numel(),

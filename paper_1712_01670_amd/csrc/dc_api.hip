@@ -108,12 +108,13 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
                      const void* cache_prev, void* out, int n_streams, int Hin, int Win, int dtype,
                      const ConvTiling& tiling, const LayerPlan* plan, const PlanAddr* addr, hipStream_t st,
                      Profile* prof = nullptr, int gemm_slot = -1, int copy_slot = -1, int* kernel_id = nullptr,
-                     bool copy_done = false, void* scratch = nullptr, size_t scratch_bytes = 0) {
+                     bool copy_done = false, void* scratch = nullptr, size_t scratch_bytes = 0,
+                     const void* w_packed = nullptr) {
     const int Hout = (Hin + 2 * l.p - l.k) / l.s + 1, Wout = (Win + 2 * l.p - l.k) / l.s + 1;
     ConvLaunch c;
     c.kernel_id = kernel_id;
     if (kernel_id) *kernel_id = -1;
-    c.in = in; c.w = w; c.bias = bias; c.out = out;
+    c.in = in; c.w = w; c.w_packed = w_packed; c.bias = bias; c.out = out;
     c.n_streams = n_streams; c.Hin = Hin; c.Win = Win; c.Cin = l.cin;
     c.Hout = Hout; c.Wout = Wout; c.Cout = l.cout; c.k = l.k; c.s = l.s; c.p = l.p; c.relu = l.relu;
     c.dtype = dtype; c.tiling = tiling;
@@ -332,8 +333,29 @@ int32_t dc_conv_workspace_bytes(const dc_layer* layer, int32_t n_streams, int32_
     return DC_OK;
 }
 
-int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* weights, const float* bias,
-                             const void* cache_prev, void* out, int32_t n_streams, int32_t Hin, int32_t Win,
+int32_t dc_packed_weights_bytes(const dc_layer* layer, int32_t dtype, size_t* bytes) {
+    if (!layer || !bytes) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    int rc = check_conv_layer(layer);
+    if (rc) return rc;
+    *bytes = packed_weights_bytes(layer->k, layer->s, layer->cin, layer->cout, dtype);
+    return DC_OK;
+}
+
+int32_t dc_pack_conv_weights(const dc_layer* layer, const void* weights, int32_t dtype, void* packed, void* stream) {
+    if (!layer || !weights || !packed) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    int rc = check_conv_layer(layer);
+    if (rc) return rc;
+    if (!packed_weights_bytes(layer->k, layer->s, layer->cin, layer->cout, dtype)) return DC_ERR_BAD_SHAPE;
+    if (reinterpret_cast<uintptr_t>(weights) % 16 || reinterpret_cast<uintptr_t>(packed) % 16 || weights == packed)
+        return DC_ERR_INVALID_ARG;
+    DC_TRY_HIP(launch_pack_weights(weights, packed, layer->cin, layer->cout, dtype, as_stream(stream)));
+    return DC_OK;
+}
+
+int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* weights, const void* packed_weights,
+                             const float* bias, const void* cache_prev, void* out, int32_t n_streams, int32_t Hin, int32_t Win,
                              const dc_regions* regions, int32_t dtype, void* ws_dev, size_t ws_dev_bytes,
                              void* ws_host, size_t ws_host_bytes, void* stream) {
     if (!layer || !in || !weights || !out) return DC_ERR_NULL_PTR;
@@ -347,7 +369,7 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
     hipStream_t st = as_stream(stream);
     if (!regions || !cache_prev)
         return run_conv_planned(*layer, in, weights, bias, nullptr, out, n_streams, Hin, Win, dtype, tiling, nullptr,
-                                nullptr, st, nullptr, -1, -1, nullptr, false, ws_dev, ws_dev ? ws_dev_bytes : 0);
+                                nullptr, st, nullptr, -1, -1, nullptr, false, ws_dev, ws_dev ? ws_dev_bytes : 0, packed_weights);
     if (out == cache_prev) return DC_ERR_INVALID_ARG;
     int max_rects = 0;
     for (int s = 0; s < n_streams; ++s) {
@@ -373,7 +395,8 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
     const size_t plan_end = align_up(addr.bytes, 256);
     unsigned char* scratch = plan_end < ws_dev_bytes ? static_cast<unsigned char*>(ws_dev) + plan_end : nullptr;
     return run_conv_planned(*layer, in, weights, bias, cache_prev, out, n_streams, Hin, Win, dtype, tiling, &plan,
-                            &addr, st, nullptr, -1, -1, nullptr, false, scratch, scratch ? ws_dev_bytes - plan_end : 0);
+                            &addr, st, nullptr, -1, -1, nullptr, false, scratch, scratch ? ws_dev_bytes - plan_end : 0,
+                            packed_weights);
 }
 
 int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n_pixels, int32_t c_frame, int32_t c_tensor,
@@ -431,7 +454,8 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
     return DC_OK;
 }
 
-int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const* weights, const float* const* bias,
+int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const* weights,
+                     const void* const* packed_weights, const float* const* bias,
                      const uint8_t* frames_cur, const uint8_t* frames_prev, void* const* tensors_cur,
                      const void* const* tensors_prev, int32_t n_streams, int32_t H, int32_t W, int32_t C,
                      int32_t dtype, int32_t block, int32_t radius, uint32_t max_block_ssd, int32_t force_full,
@@ -720,7 +744,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                                       tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st,
                                       stats ? static_cast<Profile*>(stats->profile) : nullptr, i, n_layers + i,
                                       local.layer_kernel_id ? &local.layer_kernel_id[i] : nullptr, copy_fused[i] != 0,
-                                      conv_scratch, conv_scratch ? kConvScratchBytes : 0);
+                                      conv_scratch, conv_scratch ? kConvScratchBytes : 0,
+                                      packed_weights ? packed_weights[i] : nullptr);
                 if (rc) return rc;
                 break;
             case DC_MAXPOOL:

@@ -51,6 +51,7 @@ struct ConvParams {
     int ks;                 // workgroups that share one output tile, each with its own range of channel chunks
     int chunks_per_split;
     float* partial;         // ks > 1: [ks][n_units][16 pixels][Cout] partial sums
+    int w_packed;           // 1: w is the packed layout [Cout/16][Cin*es/64][k*k][16][64 bytes]
 };
 
 template <typename T>

@@ -134,6 +134,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
     const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.w))), 0, keep_scalar(P.w_bytes), kBufferFlags);
     const int Cin = keep_scalar(P.Cin);
+    const bool packed = keep_scalar(P.w_packed) != 0;
 
     // ---- load side: instruction j of a buffer fills LDS bytes [1024 j, 1024 j + 1024); this wavefront
     // issues instructions wave, wave + NW, ...; the lane fills chunk position lane % NVEC of row
@@ -145,12 +146,17 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
         const int row = (wave + i * NW) * RPI + lrow;   // tl * NT + n
         const int tl = row / NT, n = row - tl * NT;
         const int c = lpos ^ ((row / 2) % NVEC);
-        wgo[i] = tl < KSZ ? (uint32_t)(((n0 + n) * (KSZ * KSZ) + tl) * Cin) * ES + (uint32_t)(c << 4) : kOob;
+        uint32_t off;
+        if (packed)   // [channel / 16][64-byte chunk of the row][tap][channel % 16][64 bytes]
+            off = (uint32_t)((((n0 + n) / 16 * (Cin * ES / 64) * (KSZ * KSZ) + tl) * 16 + n % 16) * 64 + (c / 4) * (KSZ * KSZ * 1024) + ((c % 4) << 4));
+        else
+            off = (uint32_t)(((n0 + n) * (KSZ * KSZ) + tl) * Cin) * ES + (uint32_t)(c << 4);
+        wgo[i] = tl < KSZ ? off : kOob;
     }
 
     auto issue_w = [&](int chunk, int ky, int wbuf) {
         unsigned char* dst = wts0 + wbuf * WBYTES + wave * 1024;
-        const uint32_t so = (uint32_t)(ky * KSZ * Cin + chunk * KC) * ES;
+        const uint32_t so = packed ? (uint32_t)((chunk * (RB / 64) * KSZ + ky) * (KSZ * 1024)) : (uint32_t)(ky * KSZ * Cin + chunk * KC) * ES;
 #pragma unroll
         for (int i = 0; i < NWI; ++i) {
             const uint32_t off = wgo[i] + so;   // (a named value: an expression in the builtin's argument list loses the host stub)
@@ -370,6 +376,17 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     if (P.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
     T* out = reinterpret_cast<T*>(P.out) + (((size_t)stream * P.Hout + y) * P.Wout + x) * P.Cout + co;
     F::store4(out, v);
+}
+
+// dst vector idx = (((blk * nc64 + c64) * 9 + tap) * 16 + n16) * 4 + v  <-  src row (blk * 16 + n16, tap), 64-byte chunk c64
+__global__ __launch_bounds__(256) void pack_weights_kernel(const uintx4* src, uintx4* dst, int nc64, size_t n_vec) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n_vec) return;
+    const int v = (int)(idx % 4), n16 = (int)((idx / 4) % 16), tap = (int)((idx / 64) % 9);
+    const size_t rest = idx / 576;
+    const int c64 = (int)(rest % nc64);
+    const size_t blk = rest / nc64;
+    dst[idx] = src[((blk * 16 + n16) * 9 + tap) * ((size_t)nc64 * 4) + (size_t)c64 * 4 + v];
 }
 
 // ---- first layer -------------------------------------------------------------------------
@@ -634,6 +651,20 @@ void conv_set_tuning(int geom, int g, int ks, int kci) {
     g_tune[0] = geom >= 0 ? geom : -1; g_tune[1] = g > 0 ? g : -1; g_tune[2] = ks > 0 ? ks : -1; g_tune[3] = kci >= 0 ? kci : -1;
 }
 
+size_t packed_weights_bytes(int k, int s, int cin, int cout, int dtype) {
+    const size_t esz = dtype_size(dtype);
+    if (k != 3 || s != 1 || cout % geom_nt(0) != 0 || (cin * esz) % 64 != 0 || cin * esz == 16) return 0;
+    return (size_t)cout * 9 * cin * esz;
+}
+
+hipError_t launch_pack_weights(const void* w, void* packed, int cin, int cout, int dtype, hipStream_t st) {
+    const size_t esz = dtype_size(dtype);
+    const size_t n_vec = (size_t)cout * 9 * cin * esz / 16;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((n_vec + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const uintx4*>(w), static_cast<uintx4*>(packed), (int)(cin * esz / 64), n_vec);
+    return hipGetLastError();
+}
+
 // Launches the layer with the kernel of this file if its shape qualifies; returns false otherwise.
 bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err) {
     static int enabled = -1;
@@ -716,6 +747,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     P.ks = ch.ks;
     P.chunks_per_split = (P.n_chunks + ch.ks - 1) / ch.ks;
     P.partial = ch.ks > 1 ? static_cast<float*>(c.scratch) : nullptr;
+    if (c.w_packed && reinterpret_cast<uintptr_t>(c.w_packed) % 16 == 0) { P.w = c.w_packed; P.w_packed = 1; }
 
     if (c.kernel_id) *c.kernel_id = ch.geom ? 110 + (ch.geom - 1) * 8 + ch.kci * 4 + upw - 1 : 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
     const long groups = (n_units + ch.g - 1) / ch.g;

@@ -59,6 +59,7 @@ void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Ho
 struct ConvLaunch {
     const void* in;
     const void* w;
+    const void* w_packed = nullptr;   // optional: the same weights in the layout of launch_pack_weights
     const float* bias;
     void* out;
     int n_streams, Hin, Win, Cin, Hout, Wout, Cout, k, s, p, relu, dtype;
@@ -75,6 +76,10 @@ struct ConvLaunch {
 // Upper bound of the scratch a convolution launch can make use of.
 constexpr size_t kConvScratchBytes = (size_t)32 << 20;
 bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err);
+// Packed weights of a layer the 3x3 stride-1 GEMM kernel runs: [cout/16][cin*es/64][9][16][64 bytes], i.e. the
+// 64-byte channel runs that one load instruction brings into LDS are contiguous.  0 bytes: no packed form.
+size_t packed_weights_bytes(int k, int s, int cin, int cout, int dtype);
+hipError_t launch_pack_weights(const void* w, void* packed, int cin, int cout, int dtype, hipStream_t st);
 void conv_kernel_name(int id, char* buf, size_t n);
 void conv_fast_kernel_name(int id, char* buf, size_t n);
 void conv_set_tuning(int geom, int g, int ks, int kci);

@@ -130,11 +130,23 @@ def test_fast_conv_kernel_shapes(oracle, case, bf16, cached):
                    (np.array([[0, 0, W - 1, H - 3]], np.int32), (1, 2))]
     binding.dc_conv_tuning(*tuning)
     try:
-        got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, 3, 1, 1, True), _to_dev(x, bf16), _to_dev(w, bf16),
-                                                  torch.from_numpy(b).to(DEV),
+        layer, wd = _layer(cin, cout, 3, 1, 1, True), _to_dev(w, bf16)
+        got = _to_np(binding.dc_cached_conv_layer(layer, _to_dev(x, bf16), wd, torch.from_numpy(b).to(DEV),
                                                   cache_prev=_to_dev(cache, bf16) if cached else None, regions=regions))
+        # the same layer reading the packed copy of the weights: same products in the same order
+        wp = binding.dc_pack_conv_weights(layer, wd)
+        assert wp is not None
+        es = 2 if bf16 else 4
+        raw = wd.view(torch.uint8).cpu().numpy().reshape(cout // 16, 16, 9, cin * es // 64, 64)
+        assert np.array_equal(wp.view(torch.uint8).cpu().numpy().reshape(cout // 16, cin * es // 64, 9, 16, 64),
+                              raw.transpose(0, 3, 2, 1, 4)), "layout [cout/16][64-byte chunk][tap][16][64 bytes]"
+        # plain weights zeroed: the result shows that the kernel reads the packed copy
+        got_p = _to_np(binding.dc_cached_conv_layer(layer, _to_dev(x, bf16), torch.zeros_like(wd), torch.from_numpy(b).to(DEV),
+                                                    cache_prev=_to_dev(cache, bf16) if cached else None, regions=regions,
+                                                    packed=wp))
     finally:
         binding.dc_conv_tuning()
+    assert np.array_equal(got, got_p), "packed weights must not change a bit"
     for i in range(n):
         if cached:
             mask = oracle.rasterize(regions[i][0], H, W)

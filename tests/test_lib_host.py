@@ -40,16 +40,28 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.dc_match_blocks(one, one, 1, 64, 64, 3, 128, 8, 0, one, one, one, one, one, None) == -3
     assert L.dc_match_blocks(one, one, 1, 64, 64, 3, 8, 200, 0, one, one, one, one, one, None) == -4
     bad = binding.layers_to_c([dict(type=0, k=3, s=0, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
-    assert L.dc_cached_conv_layer(bad, one, one, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -1
+    assert L.dc_cached_conv_layer(bad, one, one, None, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -1
     ok = binding.layers_to_c([dict(type=0, k=3, s=1, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
-    assert L.dc_cached_conv_layer(ok, one, one, None, None, one, 1, 8, 8, None, 7, None, 0, None, 0, None) == -1
-    assert L.dc_cached_conv_layer(ok, None, one, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -2
+    assert L.dc_cached_conv_layer(ok, one, one, None, None, None, one, 1, 8, 8, None, 7, None, 0, None, 0, None) == -1
+    assert L.dc_cached_conv_layer(ok, None, one, None, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -2
+    # packed weights exist for the layers the 3x3 stride-1 GEMM kernel takes, and are a permutation of the plain ones
+    nb = C.c_size_t(1)
+    assert L.dc_packed_weights_bytes(ok, 0, C.byref(nb)) == 0 and nb.value == 0
+    big = binding.layers_to_c([dict(type=0, k=3, s=1, p=1, cin=32, cout=128, relu=1, in0=0, in1=-1)])
+    assert L.dc_packed_weights_bytes(big, 0, C.byref(nb)) == 0 and nb.value == 128 * 9 * 32 * 4
+    assert L.dc_packed_weights_bytes(big, 1, C.byref(nb)) == 0 and nb.value == 128 * 9 * 32 * 2
+    odd = binding.layers_to_c([dict(type=0, k=3, s=1, p=1, cin=24, cout=128, relu=1, in0=0, in1=-1)])
+    assert L.dc_packed_weights_bytes(odd, 1, C.byref(nb)) == 0 and nb.value == 0      # 48-byte channel runs
+    assert L.dc_packed_weights_bytes(big, 5, C.byref(nb)) == -1
+    assert L.dc_pack_conv_weights(ok, one, 0, C.c_void_p(32), None) == -3
+    assert L.dc_pack_conv_weights(big, one, 0, None, None) == -2
+    assert L.dc_pack_conv_weights(big, one, 0, one, None) == -1                         # in place
     # overlapping rectangles are rejected
     regs, keep = binding._alloc_regions(1, 2)
     keep[0][0] = binding.Rect(0, 0, 4, 4)
     keep[0][1] = binding.Rect(2, 2, 4, 4)
     regs[0].n = 2
-    assert L.dc_cached_conv_layer(ok, one, one, None, one, C.c_void_p(32), 1, 8, 8, regs, 0, one, 1 << 20, one,
+    assert L.dc_cached_conv_layer(ok, one, one, None, None, one, C.c_void_p(32), 1, 8, 8, regs, 0, one, 1 << 20, one,
                                   1 << 20, None) == -3
     # a layer table whose channel counts do not chain
     layers = synth.tiny_net()
