@@ -26,6 +26,12 @@
  * closed-form matching results on constructed frame pairs, scipy's correlate
  * for the convolution, and the three invariants (zero reuse == full forward,
  * identical frames -> full reuse, exact shifted copy == full forward).
+ * The diamond-search matcher (Step 2 as the paper runs it, plus k-skip) is
+ * pinned by walks worked out by hand on small cost tables (moves, ties, range
+ * and frame limits, a trap that separates it from the exhaustive search), by
+ * the fixed-point property of the published algorithm checked against an
+ * independent numpy cost table, by the closed form for content moved by a
+ * point of the large pattern, and by the k-skip bookkeeping.
  * Unpinned by the paper (pinned only by hand cases of the stated reading):
  * the merge decomposition, the rounding of fractional motion, and the source
  * offset when the motion is not a multiple of the cumulative stride.
@@ -135,6 +141,146 @@ void oc_match_blocks(const uint8_t* cur, const uint8_t* prev, int H, int W, int 
     gmv[0] = mx; gmv[1] = my;
     /* Step 4 */
     for (int by = 0; by < gh; ++by)
+        for (int bx = 0; bx < gw; ++bx) {
+            int x = bx * B, y = by * B;
+            int ok = !(x + mx < 0 || y + my < 0 || x + mx + B > W || y + my + B > H);
+            if (ok) ok = block_ssd(cur, prev, W, C, B, x, y, mx, my) <= max_ssd;
+            mask[by * gw + bx] = (uint8_t)ok;
+        }
+}
+
+/* ------------------------------------------------------------------ */
+/* Section 4, Step 2 with diamond search, k-skip (Section 4, last part) */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Diamond search (the block-matching algorithm Section 4 names for Step 2; the
+ * paper cites it and does not restate it, so this is the published algorithm):
+ *   large pattern: the centre and the eight points at (0,+-2), (+-2,0), (+-1,+-1);
+ *   small pattern: the centre and the four points at (0,+-1), (+-1,0).
+ *   1. centre = (0,0);
+ *   2. evaluate the large pattern around the centre; if the best point is the
+ *      centre go to 3, otherwise the best point becomes the centre, repeat 2;
+ *   3. evaluate the small pattern around the centre; its best point is the result.
+ * Readings: a candidate is valid iff |dx|,|dy| <= R and its window lies inside
+ * the previous frame (as for the exhaustive search); the best point of a pattern
+ * is the valid one with the smallest (cost, position in the pattern), the centre
+ * being position 0 and the others following in raster order (dy, then dx), so
+ * the centre only moves to a strictly smaller cost and the walk ends.
+ * `cost` returns the block cost of a vector, `valid` whether it may be used.
+ * rounds = number of times step 2 ran.
+ */
+typedef uint32_t (*ds_cost_fn)(void* ctx, int dx, int dy);
+typedef int (*ds_valid_fn)(void* ctx, int dx, int dy);
+
+static const int kLarge[9][2] = {{0, 0}, {0, -2}, {-1, -1}, {1, -1}, {-2, 0}, {2, 0}, {-1, 1}, {1, 1}, {0, 2}};
+static const int kSmall[5][2] = {{0, 0}, {0, -1}, {-1, 0}, {1, 0}, {0, 1}};
+
+static void diamond_search(ds_cost_fn cost, ds_valid_fn valid, void* ctx,
+                           int* out_dx, int* out_dy, uint32_t* out_cost, int* out_rounds)
+{
+    int cx = 0, cy = 0, rounds = 0;
+    uint32_t ccost = cost(ctx, 0, 0);          /* (0,0) is always valid: the block lies in both frames */
+    for (;;) {
+        int best = 0;
+        uint32_t bcost = ccost;
+        ++rounds;
+        for (int i = 1; i < 9; ++i) {
+            int dx = cx + kLarge[i][0], dy = cy + kLarge[i][1];
+            if (!valid(ctx, dx, dy)) continue;
+            uint32_t c = cost(ctx, dx, dy);
+            if (c < bcost) { bcost = c; best = i; }
+        }
+        if (best == 0) break;
+        cx += kLarge[best][0]; cy += kLarge[best][1]; ccost = bcost;
+    }
+    int best = 0;
+    uint32_t bcost = ccost;
+    for (int i = 1; i < 5; ++i) {
+        int dx = cx + kSmall[i][0], dy = cy + kSmall[i][1];
+        if (!valid(ctx, dx, dy)) continue;
+        uint32_t c = cost(ctx, dx, dy);
+        if (c < bcost) { bcost = c; best = i; }
+    }
+    *out_dx = cx + kSmall[best][0]; *out_dy = cy + kSmall[best][1];
+    *out_cost = bcost; *out_rounds = rounds;
+}
+
+/* Diamond search over a given cost table: table[(dy+R)*(2R+1) + dx+R], entries
+ * equal to UINT32_MAX are invalid vectors.  For tests of the search itself. */
+typedef struct { const uint32_t* table; int R; } table_ctx;
+static uint32_t table_cost(void* p, int dx, int dy)
+{
+    table_ctx* t = (table_ctx*)p;
+    return t->table[(dy + t->R) * (2 * t->R + 1) + dx + t->R];
+}
+static int table_valid(void* p, int dx, int dy)
+{
+    table_ctx* t = (table_ctx*)p;
+    if (iabs(dx) > t->R || iabs(dy) > t->R) return 0;
+    return table_cost(p, dx, dy) != UINT32_MAX;
+}
+void oc_diamond_search_table(const uint32_t* table, int R, int32_t* best_dxdy, uint32_t* best, int32_t* rounds)
+{
+    table_ctx t = {table, R};
+    int dx, dy, n;
+    diamond_search(table_cost, table_valid, &t, &dx, &dy, best, &n);
+    best_dxdy[0] = dx; best_dxdy[1] = dy; *rounds = n;
+}
+
+typedef struct { const uint8_t* cur; const uint8_t* prev; int H, W, C, B, R, x, y; } block_ctx;
+static uint32_t block_cost(void* p, int dx, int dy)
+{
+    block_ctx* b = (block_ctx*)p;
+    return block_ssd(b->cur, b->prev, b->W, b->C, b->B, b->x, b->y, dx, dy);
+}
+static int block_valid(void* p, int dx, int dy)
+{
+    block_ctx* b = (block_ctx*)p;
+    if (iabs(dx) > b->R || iabs(dy) > b->R) return 0;
+    return !(b->x + dx < 0 || b->y + dy < 0 || b->x + dx + b->B > b->W || b->y + dy + b->B > b->H);
+}
+
+/*
+ * Steps 1-4 with the diamond search in Step 2 and k-skip: only the blocks whose
+ * grid row and grid column are both multiples of k are searched (k = 1: all);
+ * Step 3 averages over the searched blocks that pass; Step 4 tests every block.
+ * Blocks that were not searched get mv = (0,0), best_ssd = UINT32_MAX, rounds = 0.
+ * (Re-using Step 2's costs in Step 4 changes no result and is not modelled.)
+ */
+void oc_match_blocks_ds(const uint8_t* cur, const uint8_t* prev, int H, int W, int C,
+                        int B, int R, int k, uint32_t max_ssd,
+                        int16_t* mv, uint32_t* best_ssd, int32_t* gmv, int32_t* n_pass,
+                        uint8_t* mask, int32_t* rounds)
+{
+    int gh = H / B, gw = W / B;
+    int64_t sx = 0, sy = 0;
+    int K = 0;
+    for (int by = 0; by < gh; ++by)
+        for (int bx = 0; bx < gw; ++bx) {
+            int i = by * gw + bx;
+            mv[2 * i] = mv[2 * i + 1] = 0;
+            best_ssd[i] = UINT32_MAX;
+            if (rounds) rounds[i] = 0;
+            if (by % k != 0 || bx % k != 0) continue;
+            block_ctx b = {cur, prev, H, W, C, B, R, bx * B, by * B};
+            int dx, dy, n;
+            uint32_t s;
+            diamond_search(block_cost, block_valid, &b, &dx, &dy, &s, &n);
+            mv[2 * i] = (int16_t)dx; mv[2 * i + 1] = (int16_t)dy;
+            best_ssd[i] = s;
+            if (rounds) rounds[i] = n;
+            if (s <= max_ssd) { sx += dx; sy += dy; ++K; }      /* Step 3 */
+        }
+    *n_pass = K;
+    if (K == 0) {
+        gmv[0] = gmv[1] = 0;
+        memset(mask, 0, (size_t)gh * gw);
+        return;
+    }
+    int mx = round_div(sx, K), my = round_div(sy, K);
+    gmv[0] = mx; gmv[1] = my;
+    for (int by = 0; by < gh; ++by)                              /* Step 4 */
         for (int bx = 0; bx < gw; ++bx) {
             int x = bx * B, y = by * B;
             int ok = !(x + mx < 0 || y + my < 0 || x + mx + B > W || y + my + B > H);

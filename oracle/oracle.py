@@ -87,6 +87,37 @@ def match_blocks(cur, prev, block, radius, max_ssd):
     return dict(mv=mv, best_ssd=best, gmv=gmv, n_pass=int(npass[0]), mask=mask)
 
 
+def match_blocks_ds(cur, prev, block, radius, max_ssd, k_skip=1):
+    """Section 4, Steps 1-4 with diamond search in Step 2 and k-skip.  Returns dict(mv, best_ssd, gmv,
+    n_pass, mask, rounds); rounds = large-pattern rounds per searched block."""
+    H, W, Ch = cur.shape
+    gh, gw = H // block, W // block
+    mv = np.zeros((gh, gw, 2), np.int16)
+    best = np.zeros((gh, gw), np.uint32)
+    gmv = np.zeros(2, np.int32)
+    npass = np.zeros(1, np.int32)
+    mask = np.zeros((gh, gw), np.uint8)
+    rounds = np.zeros((gh, gw), np.int32)
+    cur = np.ascontiguousarray(cur, np.uint8)
+    prev = np.ascontiguousarray(prev, np.uint8)
+    lib().oc_match_blocks_ds(_p(cur), _p(prev), H, W, Ch, block, radius, int(k_skip), C.c_uint32(max_ssd),
+                             _p(mv), _p(best), _p(gmv), _p(npass), _p(mask), _p(rounds))
+    return dict(mv=mv, best_ssd=best, gmv=gmv, n_pass=int(npass[0]), mask=mask, rounds=rounds)
+
+
+def diamond_search_table(table):
+    """Diamond search over a cost table [(2R+1)][(2R+1)] indexed [dy+R][dx+R]; 0xFFFFFFFF = invalid vector.
+    Returns ((dx, dy), cost, rounds)."""
+    table = np.ascontiguousarray(table, np.uint32)
+    R = (table.shape[0] - 1) // 2
+    assert table.shape == (2 * R + 1, 2 * R + 1)
+    d = np.zeros(2, np.int32)
+    best = np.zeros(1, np.uint32)
+    rounds = np.zeros(1, np.int32)
+    lib().oc_diamond_search_table(_p(table), R, _p(d), _p(best), _p(rounds))
+    return (int(d[0]), int(d[1])), int(best[0]), int(rounds[0])
+
+
 def merge_blocks(mask, block, cap=4096):
     """Section 4, Step 5.  Returns int32 [n][4] rectangles (x,y,w,h) in pixels."""
     mask = np.ascontiguousarray(mask, np.uint8)
