@@ -77,6 +77,13 @@ typedef struct {
     int32_t h, w;          /* out: spatial size of this tensor */
 } dc_regions;
 
+/* Which search dc_run_stack uses in Step 2 of the matching (Section 4; Section 7.6 compares them). */
+enum { DC_MATCH_EXHAUSTIVE = 0, DC_MATCH_DIAMOND = 1 };
+typedef struct {
+    int32_t method;        /* DC_MATCH_EXHAUSTIVE (dc_match_blocks) or DC_MATCH_DIAMOND (dc_match_blocks_ds) */
+    int32_t k_skip;        /* >= 1; must be 1 for the exhaustive search */
+} dc_match_options;
+
 /* Work counters of one dc_run_stack call, summed over streams. */
 typedef struct {
     int32_t full;               /* 1: every pixel was computed (no cache used) */
@@ -171,6 +178,29 @@ int32_t dc_match_blocks(const uint8_t* cur, const uint8_t* prev, int32_t n_strea
                         void* stream);
 
 /*
+ * Section 4, Steps 1-4 with the search the paper runs in Step 2, the diamond search it cites,
+ * and the k-skip acceleration of the same section.  Arguments as dc_match_blocks, plus
+ *   k_skip   k >= 1: Step 2 runs only for the blocks whose grid row and grid column are both
+ *            multiples of k; Step 3 averages over those; Step 4 still tests every block.
+ *            A block that is not searched gets mv = (0,0) and best_ssd = 2^32 - 1.
+ * The search: centre (0,0); evaluate the centre and the eight points at (0,+-2), (+-2,0),
+ * (+-1,+-1) around it; if the centre is best evaluate the four points at (0,+-1), (+-1,0)
+ * and take the best of the five, otherwise move the centre to the best point and repeat.
+ * A point is usable iff |dx|,|dy| <= radius and its window lies inside the previous frame;
+ * the best point is the one with the smallest (ssd, position in the pattern), the centre first
+ * and the others in raster order (dy, then dx), so the centre moves only to a strictly smaller
+ * sum.  The result is a local minimum and may differ from dc_match_blocks (Section 7.6 compares
+ * the two).  Re-using Step 2's sums in Step 4 (same section) changes no result; Step 4 reads
+ * 6 bytes per pixel here and is not worth a table.
+ * Limits: radius <= 16383, block*block*C*255^2 < 2^32, block*W*C < 2^31.
+ */
+int32_t dc_match_blocks_ds(const uint8_t* cur, const uint8_t* prev, int32_t n_streams,
+                           int32_t H, int32_t W, int32_t C, int32_t block, int32_t radius,
+                           int32_t k_skip, uint32_t max_block_ssd, int16_t* mv,
+                           uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
+                           uint8_t* block_mask, void* stream);
+
+/*
  * Section 4 Step 5 and Section 5 "Propagation" for one stream; pure host integer code.
  *   block_mask     host u8 [gh][gw] (Step 4 result)
  *   mx, my         global motion of the stream
@@ -262,6 +292,7 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
  *                   (written).  Conv outputs are the cache values of the next frame.
  *   tensors_prev    host array [n_layers+1] of dev pointers: the previous frame's tensors;
  *                   only conv-layer outputs are read.  Must not alias tensors_cur for them.
+ *   match_options   optional (NULL: exhaustive search over every block)
  *   force_full      nonzero: first frame, cache expiry (Section 5) or reset: skip matching
  *                   and compute everything
  *   mv .. block_mask  dev buffers as in dc_match_blocks (written unless force_full)
@@ -282,7 +313,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers,
                      const uint8_t* frames_cur, const uint8_t* frames_prev,
                      void* const* tensors_cur, const void* const* tensors_prev,
                      int32_t n_streams, int32_t H, int32_t W, int32_t C, int32_t dtype,
-                     int32_t block, int32_t radius, uint32_t max_block_ssd, int32_t force_full,
+                     int32_t block, int32_t radius, uint32_t max_block_ssd,
+                     const dc_match_options* match_options, int32_t force_full,
                      int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
                      uint8_t* block_mask, int32_t max_rects, dc_regions* regions_out,
                      void* ws_dev, size_t ws_dev_bytes, void* ws_host, size_t ws_host_bytes,

@@ -220,7 +220,8 @@ class Stream:
     the previous feature maps (cache values), Section 3."""
 
     def __init__(self, layers, weights, biases, H, W, Ch=3, block=16, radius=16, max_ssd=None,
-                 bf16=False, expiry=0, cap=1024):
+                 bf16=False, expiry=0, cap=1024, diamond=False, k_skip=1):
+        self.diamond, self.k_skip = diamond, k_skip
         self.layers, self.H, self.W, self.Ch = layers, H, W, Ch
         self.block, self.radius, self.bf16, self.expiry, self.cap = block, radius, bf16, expiry, cap
         self.max_ssd = max_ssd if max_ssd is not None else 20 * block * block * Ch
@@ -262,7 +263,10 @@ class Stream:
             n0, mx, my = -1, 0, 0
             self.age = 1
         else:
-            m = match_blocks(frame, self.prev_frame, self.block, self.radius, self.max_ssd)
+            if self.diamond:
+                m = match_blocks_ds(frame, self.prev_frame, self.block, self.radius, self.max_ssd, self.k_skip)
+            else:
+                m = match_blocks(frame, self.prev_frame, self.block, self.radius, self.max_ssd)
             r0 = merge_blocks(m["mask"], self.block)
             n0, mx, my = len(r0), int(m["gmv"][0]), int(m["gmv"][1])
             self.age += 1

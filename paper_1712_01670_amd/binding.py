@@ -22,7 +22,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
           -4: "DC_ERR_UNSUPPORTED", -5: "DC_ERR_WORKSPACE", -6: "DC_ERR_CAPACITY", -7: "DC_ERR_HIP"}
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
-           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_propagate_regions", "dc_conv_workspace_bytes",
+           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_propagate_regions", "dc_conv_workspace_bytes",
            "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
@@ -45,6 +45,13 @@ class Regions(C.Structure):
     _fields_ = [("rects", C.POINTER(Rect)), ("capacity", C.c_int32), ("n", C.c_int32),
                 ("dx", C.c_int32), ("dy", C.c_int32), ("cum_stride", C.c_int32),
                 ("h", C.c_int32), ("w", C.c_int32)]
+
+
+class MatchOptions(C.Structure):
+    _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32)]
+
+
+DC_MATCH_EXHAUSTIVE, DC_MATCH_DIAMOND = 0, 1
 
 
 class StackStats(C.Structure):
@@ -78,6 +85,7 @@ def lib():
         L.dc_conv_kernel_name.argtypes = [i32, C.c_char_p, sz]
         L.dc_conv_tile_shape.argtypes = [vp, i32, i32, i32, i32] + [C.POINTER(i32)] * 4
         L.dc_match_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
+        L.dc_match_blocks_ds.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
         L.dc_propagate_regions.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, vp]
         L.dc_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
         L.dc_packed_weights_bytes.argtypes = [vp, i32, C.POINTER(sz)]
@@ -87,7 +95,7 @@ def lib():
         L.dc_maxpool_layer.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
         L.dc_add_layer.argtypes = [vp, vp, vp, sz, i32, i32, vp]
         L.dc_stack_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
-        L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, i32,
+        L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, vp, i32,
                                    vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp, vp]
         for name in EXPORTS:
             if name != "dc_status_string":
@@ -138,6 +146,24 @@ def dc_match_blocks(cur, prev, block, radius, max_block_ssd):
                mask=torch.empty((n, gh, gw), dtype=torch.uint8, device=dev))
     _check("dc_match_blocks", lib().dc_match_blocks(
         _ptr(cur), _ptr(prev), n, H, W, Ch, block, radius, max_block_ssd, _ptr(out["mv"]),
+        _ptr(out["best_ssd"]), _ptr(out["gmv"]), _ptr(out["n_pass"]), _ptr(out["mask"]), _stream()))
+    return out
+
+
+def dc_match_blocks_ds(cur, prev, block, radius, max_block_ssd, k_skip=1):
+    """Diamond search with k-skip; arguments and result as dc_match_blocks."""
+    assert cur.is_cuda and cur.dtype == torch.uint8 and cur.is_contiguous() and cur.dim() == 4
+    assert prev.shape == cur.shape and prev.is_cuda and prev.dtype == torch.uint8 and prev.is_contiguous()
+    n, H, W, Ch = cur.shape
+    gh, gw = H // block, W // block
+    dev = cur.device
+    out = dict(mv=torch.empty((n, gh, gw, 2), dtype=torch.int16, device=dev),
+               best_ssd=torch.empty((n, gh, gw), dtype=torch.int32, device=dev),
+               gmv=torch.empty((n, 2), dtype=torch.int32, device=dev),
+               n_pass=torch.empty((n,), dtype=torch.int32, device=dev),
+               mask=torch.empty((n, gh, gw), dtype=torch.uint8, device=dev))
+    _check("dc_match_blocks_ds", lib().dc_match_blocks_ds(
+        _ptr(cur), _ptr(prev), n, H, W, Ch, block, radius, int(k_skip), max_block_ssd, _ptr(out["mv"]),
         _ptr(out["best_ssd"]), _ptr(out["gmv"]), _ptr(out["n_pass"]), _ptr(out["mask"]), _stream()))
     return out
 
@@ -295,7 +321,8 @@ class StackRunner:
 
     def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
-                 want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True):
+                 want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True,
+                 match_method=DC_MATCH_EXHAUSTIVE, k_skip=1):
         self.Ch_tensor = Ch
         if pad_input:
             layers, weights, self.Ch_tensor = pad_input_channels(layers, weights, Ch, dtype)
@@ -303,6 +330,7 @@ class StackRunner:
         self.block, self.radius, self.dtype, self.expiry = block, radius, dtype, expiry
         self.max_block_ssd = int(max_block_ssd if max_block_ssd is not None else synth.max_block_ssd(block, Ch))
         self.max_rects = max_rects
+        self.match_options = MatchOptions(int(match_method), int(k_skip))
         self.device = torch.device(device)
         td = torch_dtype(dtype)
         self.Lc = layers_to_c(layers)
@@ -386,7 +414,7 @@ class StackRunner:
         _check("dc_run_stack", lib().dc_run_stack(
             self.Lc, len(self.layers), self._wp, self._wpp, self._bp, _ptr(frames), _ptr(self.prev_frames),
             self._tp[c], self._tp[p], self.n, self.H, self.W, self.Ch, self.dtype, self.block, self.radius,
-            self.max_block_ssd, int(full), _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
+            self.max_block_ssd, C.byref(self.match_options), int(full), _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
             _ptr(self.mask), self.max_rects, self.regs, _ptr(self.ws_dev), self.ws_dev.numel(),
             C.c_void_p(self.ws_host.data_ptr()), self.ws_host.numel(), C.byref(self.stats), self.overlap, _stream()))
         self.age = 1 if full else self.age + 1

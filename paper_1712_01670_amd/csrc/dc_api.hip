@@ -284,6 +284,22 @@ int32_t dc_match_blocks(const uint8_t* cur, const uint8_t* prev, int32_t n_strea
     return DC_OK;
 }
 
+int32_t dc_match_blocks_ds(const uint8_t* cur, const uint8_t* prev, int32_t n_streams, int32_t H, int32_t W,
+                           int32_t C, int32_t block, int32_t radius, int32_t k_skip, uint32_t max_block_ssd,
+                           int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask,
+                           void* stream) {
+    if (!cur || !prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask) return DC_ERR_NULL_PTR;
+    if (n_streams < 1 || n_streams > 65535 || H < 1 || W < 1 || C < 1 || block < 1 || radius < 0 || k_skip < 1)
+        return DC_ERR_INVALID_ARG;
+    if (block > H || block > W) return DC_ERR_BAD_SHAPE;
+    if (radius > 16383) return DC_ERR_UNSUPPORTED;                                   // vectors are int16
+    if ((double)block * block * C * 65025.0 * 2.0 > 4.0e9) return DC_ERR_UNSUPPORTED;   // 32-bit sums
+    if ((double)block * W * C >= 2147483648.0) return DC_ERR_UNSUPPORTED;             // 32-bit offsets inside a block
+    DC_TRY_HIP(launch_match_diamond(cur, prev, n_streams, H, W, C, block, radius, k_skip, max_block_ssd, mv, best_ssd,
+                                    global_mv, n_pass, block_mask, as_stream(stream)));
+    return DC_OK;
+}
+
 int32_t dc_propagate_regions(const dc_layer* layers, int32_t n_layers, int32_t H, int32_t W, int32_t block,
                              const uint8_t* block_mask, int32_t gh, int32_t gw, int32_t mx, int32_t my,
                              dc_regions* regions) {
@@ -458,7 +474,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                      const void* const* packed_weights, const float* const* bias,
                      const uint8_t* frames_cur, const uint8_t* frames_prev, void* const* tensors_cur,
                      const void* const* tensors_prev, int32_t n_streams, int32_t H, int32_t W, int32_t C,
-                     int32_t dtype, int32_t block, int32_t radius, uint32_t max_block_ssd, int32_t force_full,
+                     int32_t dtype, int32_t block, int32_t radius, uint32_t max_block_ssd,
+                     const dc_match_options* match_options, int32_t force_full,
                      int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask,
                      int32_t max_rects, dc_regions* regions_out, void* ws_dev, size_t ws_dev_bytes, void* ws_host,
                      size_t ws_host_bytes, dc_stack_stats* stats, void* overlap, void* stream) {
@@ -475,6 +492,11 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     for (int i = 0; i < n_layers; ++i)
         if (layers[i].type == DC_CONV && !weights[i]) return DC_ERR_NULL_PTR;
     const bool cached = !force_full;
+    if (match_options) {
+        if (match_options->method != DC_MATCH_EXHAUSTIVE && match_options->method != DC_MATCH_DIAMOND) return DC_ERR_INVALID_ARG;
+        if (match_options->k_skip < 1) return DC_ERR_INVALID_ARG;
+        if (match_options->method == DC_MATCH_EXHAUSTIVE && match_options->k_skip != 1) return DC_ERR_UNSUPPORTED;
+    }
     if (cached) {
         if (!frames_prev || !tensors_prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask || !ws_dev || !ws_host)
             return DC_ERR_NULL_PTR;
@@ -560,8 +582,12 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         // With an overlap handle the matching runs on its own stream, next to whatever the main stream
         // still holds of the previous frame; only that stream is waited for.
         hipStream_t mst = ov ? ov->aux : st;
-        rc = dc_match_blocks(frames_cur, frames_prev, n_streams, H, W, C, block, radius, max_block_ssd, mv, best_ssd,
-                             global_mv, n_pass, block_mask, mst);
+        if (match_options && match_options->method == DC_MATCH_DIAMOND)
+            rc = dc_match_blocks_ds(frames_cur, frames_prev, n_streams, H, W, C, block, radius, match_options->k_skip,
+                                    max_block_ssd, mv, best_ssd, global_mv, n_pass, block_mask, mst);
+        else
+            rc = dc_match_blocks(frames_cur, frames_prev, n_streams, H, W, C, block, radius, max_block_ssd, mv, best_ssd,
+                                 global_mv, n_pass, block_mask, mst);
         if (rc) return rc;
         uint8_t* h_mask = hbase;
         int32_t* h_gmv = reinterpret_cast<int32_t*>(hbase + align_up(nb, 256));

@@ -398,7 +398,7 @@ __global__ __launch_bounds__(64) void motion_retest_kernel(
     const uint8_t* __restrict__ cur, const uint8_t* __restrict__ prev, int H, int W, int C, int B,
     int gw, int gh, uint32_t max_ssd, const int16_t* __restrict__ mv,
     const uint32_t* __restrict__ best_ssd, int32_t* __restrict__ gmv, int32_t* __restrict__ n_pass,
-    uint8_t* __restrict__ mask) {
+    uint8_t* __restrict__ mask, int k_skip) {
     const int lane = threadIdx.x;
     const int blk_id = blockIdx.x, stream = blockIdx.y;
     const int nb = gh * gw;
@@ -418,7 +418,10 @@ __global__ __launch_bounds__(64) void motion_retest_kernel(
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const bool pass = base + u * 64 + lane < nb && bs[u] <= max_ssd;
+            const int i = base + u * 64 + lane;
+            // with k-skip only the blocks on every k-th grid row and column carry a vector
+            const bool searched = k_skip == 1 || ((i / gw) % k_skip == 0 && (i % gw) % k_skip == 0);
+            const bool pass = i < nb && searched && bs[u] <= max_ssd;
             sx += pass ? vx[u] : 0;
             sy += pass ? vy[u] : 0;
             K += pass ? 1 : 0;
@@ -462,6 +465,115 @@ __global__ __launch_bounds__(64) void motion_retest_kernel(
         ssd = (uint32_t)wave_sum_i32((int)ssd);
     }
     if (lane == 0) mask[(size_t)stream * nb + blk_id] = (inside && ssd <= max_ssd) ? 1 : 0;
+}
+
+
+// ---- diamond search (Section 4, Step 2 as the paper runs it) with k-skip ----------------------
+// One wavefront per block of the grid.  The walk is sequential, so a round costs one memory latency:
+// the lanes hold the block's samples (element i of the block goes to lane i % 64), the eight new points of
+// the large pattern are evaluated together (eight independent loads in flight per sample, eight wavefront
+// sums), and every decision is taken on wavefront-uniform values.
+//   large pattern: centre, (0,-2), (-1,-1), (1,-1), (-2,0), (2,0), (-1,1), (1,1), (0,2)
+//   small pattern: centre, (0,-1), (-1,0), (1,0), (0,1)
+// The best point of a pattern is the valid one with the smallest (cost, position in the list above); the
+// centre is position 0, so it moves only to a strictly smaller cost and the walk ends; max_rounds (the
+// number of vectors in the search range) bounds it independently of the data.
+// Blocks off the k-skip lattice get mv = (0,0) and best_ssd = 2^32 - 1.
+constexpr int kDiamondWaves = 4;
+__constant__ const signed char kLargeDx[8] = {0, -1, 1, -2, 2, -1, 1, 0};
+__constant__ const signed char kLargeDy[8] = {-2, -1, -1, 0, 0, 1, 1, 2};
+__constant__ const signed char kSmallDx[4] = {0, -1, 1, 0};
+__constant__ const signed char kSmallDy[4] = {-1, 0, 0, 1};
+
+// Costs of NP points around (cx, cy): cost[p] = SSD of the block against the previous frame at
+// (cx + pdx[p], cy + pdy[p]), or 2^32 - 1 for a point outside the range or the frame.
+template <int NP>
+__device__ __forceinline__ void diamond_costs(const uint8_t* __restrict__ cblk, const uint8_t* __restrict__ pf, int H,
+                                              int W, int C, int B, int R, int x0, int y0, int cx, int cy,
+                                              const signed char* pdx, const signed char* pdy, int lane,
+                                              uint32_t (&cost)[NP]) {
+    const int rb = B * C, n_elem = B * rb;
+    const size_t pitch = (size_t)W * C;
+    const uint8_t* src[NP];
+    bool ok[NP];
+    uint32_t s[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int dx = cx + pdx[p], dy = cy + pdy[p];
+        ok[p] = dx >= -R && dx <= R && dy >= -R && dy <= R && x0 + dx >= 0 && y0 + dy >= 0 && x0 + dx + B <= W &&
+                y0 + dy + B <= H;
+        src[p] = pf + ((size_t)(y0 + (ok[p] ? dy : 0)) * W + x0 + (ok[p] ? dx : 0)) * C;   // always inside the frame
+        s[p] = 0;
+    }
+    for (int base = 0; base < n_elem; base += 2 * 64) {       // two samples per lane at a time
+        int a[2], off[2];
+        bool in[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int i = base + u * 64 + lane;
+            in[u] = i < n_elem;
+            const int r = i / rb, j = i - r * rb;
+            off[u] = in[u] ? (int)(r * pitch) + j : 0;
+            a[u] = in[u] ? cblk[off[u]] : 0;
+        }
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            if (!ok[p]) continue;                                // uniform
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int b = in[u] ? src[p][off[u]] : 0;
+                s[p] += (uint32_t)((a[u] - b) * (a[u] - b));
+            }
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < NP; ++p) cost[p] = ok[p] ? (uint32_t)wave_sum_i32((int)s[p]) : 0xffffffffu;
+}
+
+__global__ __launch_bounds__(kDiamondWaves * 64) void match_diamond_kernel(
+    const uint8_t* __restrict__ cur, const uint8_t* __restrict__ prev, int H, int W, int C, int B, int R, int gw,
+    int gh, int k_skip, int max_rounds, int16_t* __restrict__ mv, uint32_t* __restrict__ best_ssd) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nb = gh * gw;
+    const int blk_id = blockIdx.x * kDiamondWaves + wave, stream = blockIdx.y;
+    if (blk_id >= nb) return;
+    const int bx = blk_id % gw, by = blk_id / gw;
+    int16_t* out_mv = mv + ((size_t)stream * nb + blk_id) * 2;
+    uint32_t* out_ssd = best_ssd + (size_t)stream * nb + blk_id;
+    if (bx % k_skip != 0 || by % k_skip != 0) {
+        if (lane == 0) { out_mv[0] = 0; out_mv[1] = 0; *out_ssd = 0xffffffffu; }
+        return;
+    }
+    const size_t frame_bytes = (size_t)H * W * C;
+    const uint8_t* pf = prev + stream * frame_bytes;
+    const int x0 = bx * B, y0 = by * B;
+    const uint8_t* cblk = cur + stream * frame_bytes + ((size_t)y0 * W + x0) * C;
+
+    const signed char zero = 0;
+    uint32_t c0[1];
+    diamond_costs<1>(cblk, pf, H, W, C, B, R, x0, y0, 0, 0, &zero, &zero, lane, c0);
+    int cx = 0, cy = 0;
+    uint32_t ccost = c0[0];
+    for (int round = 0; round < max_rounds; ++round) {
+        uint32_t c[8];
+        diamond_costs<8>(cblk, pf, H, W, C, B, R, x0, y0, cx, cy, kLargeDx, kLargeDy, lane, c);
+        int best = -1;
+        uint32_t bcost = ccost;
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            if (c[p] < bcost) { bcost = c[p]; best = p; }
+        if (best < 0) break;
+        cx += kLargeDx[best]; cy += kLargeDy[best]; ccost = bcost;
+    }
+    uint32_t c[4];
+    diamond_costs<4>(cblk, pf, H, W, C, B, R, x0, y0, cx, cy, kSmallDx, kSmallDy, lane, c);
+    int best = -1;
+    uint32_t bcost = ccost;
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+        if (c[p] < bcost) { bcost = c[p]; best = p; }
+    if (best >= 0) { cx += kSmallDx[best]; cy += kSmallDy[best]; }
+    if (lane == 0) { out_mv[0] = (int16_t)cx; out_mv[1] = (int16_t)cy; *out_ssd = bcost; }
 }
 
 }  // namespace
@@ -531,7 +643,22 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(motion_retest_kernel, grid, dim3(64), 0, st, cur, prev, H, W, C, B, gw, gh,
-                       max_ssd, mv, best_ssd, gmv, n_pass, mask);
+                       max_ssd, mv, best_ssd, gmv, n_pass, mask, 1);
+    return hipGetLastError();
+}
+
+hipError_t launch_match_diamond(const uint8_t* cur, const uint8_t* prev, int n_streams, int H, int W, int C, int B,
+                                int R, int k_skip, uint32_t max_ssd, int16_t* mv, uint32_t* best_ssd, int32_t* gmv,
+                                int32_t* n_pass, uint8_t* mask, hipStream_t st) {
+    const int gh = H / B, gw = W / B;
+    const unsigned long long side = 2ull * R + 1;
+    const unsigned long long cap = side * side < 0x7fffffffull ? side * side : 0x7fffffffull;
+    hipLaunchKernelGGL(match_diamond_kernel, dim3((gh * gw + kDiamondWaves - 1) / kDiamondWaves, n_streams),
+                       dim3(kDiamondWaves * 64), 0, st, cur, prev, H, W, C, B, R, gw, gh, k_skip, (int)cap, mv, best_ssd);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(motion_retest_kernel, dim3(gh * gw, n_streams), dim3(64), 0, st, cur, prev, H, W, C, B, gw, gh,
+                       max_ssd, mv, best_ssd, gmv, n_pass, mask, k_skip);
     return hipGetLastError();
 }
 

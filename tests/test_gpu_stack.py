@@ -17,15 +17,17 @@ def _rel_err(got, want):
 
 
 def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
-              residual_scale=1.0, check_tensors=None, resets=()):
+              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1):
     """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
     n, T, H, W, C = videos.shape
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale)
     tol = 2e-2 if bf16 else 1e-4
     dt = binding.DC_BF16 if bf16 else binding.DC_F32
     runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
-                                 want_regions=True)
-    streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry)
+                                 want_regions=True, k_skip=k_skip,
+                                 match_method=binding.DC_MATCH_DIAMOND if diamond else binding.DC_MATCH_EXHAUSTIVE)
+    streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry,
+                             diamond=diamond, k_skip=k_skip)
                for _ in range(n)]
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
     worst = 0.0
@@ -96,6 +98,29 @@ def test_tiny_exact_shift_equals_full_forward_on_gpu(oracle):
 def test_vgg16_224_first_frames(oracle):
     video = synth.panning_video(2000, n_frames=3)[None]
     _run_both(oracle, synth.vgg16(), video, 16, 16, False, bias_scale=0.0)
+
+
+@pytest.mark.parametrize("k_skip", [1, 2])
+def test_diamond_search_in_the_whole_path(oracle, k_skip):
+    # the paper's matcher (diamond search, k-skip) feeding the same region logic and cached convolutions
+    f1, f2 = synth.tiny_pair(0)
+    runner, reuse = _run_both(oracle, synth.tiny_net(), np.stack([f1, f2, f2, f1])[None], 8, 8, False,
+                              diamond=True, k_skip=k_skip)
+    assert reuse[1] == 1.0
+    v = np.stack([synth.panning_video(5100 + s, n_frames=4, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
+    runner, reuse = _run_both(oracle, synth.vgg16(), v, 16, 16, False, bias_scale=0.0, diamond=True, k_skip=k_skip,
+                              check_tensors=(0, 1, 2, 5, 10, 17))
+    assert max(reuse) > 0.3
+
+
+def test_exhaustive_search_rejects_k_skip():
+    layers = synth.tiny_net()
+    ws, bs = synth.he_weights(layers, 1)
+    f1, f2 = synth.tiny_pair(0)
+    r = binding.StackRunner(layers, ws, bs, 1, 64, 64, 3, block=8, radius=8, k_skip=2)
+    with pytest.raises(binding.DcError) as e:
+        r.step(torch.from_numpy(f1[None]).to(DEV))
+    assert e.value.status == -4
 
 
 def test_vgg16_two_streams_bf16_small(oracle):
