@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
     ap.add_argument("--streams", type=int, default=1)
     ap.add_argument("--expiry", type=int, default=10, help="full recompute every N frames (Section 5 default 10)")
+    ap.add_argument("--matcher", choices=["es", "ds"], default="es",
+                    help="Step 2 of the matching: exhaustive search, or the diamond search of Section 4")
+    ap.add_argument("--k-skip", type=int, default=1, help="search every k-th block row/column only (diamond search)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=10)
     args = ap.parse_args()
@@ -69,7 +72,9 @@ def main():
     videos = np.stack([synth.panning_video(2000 + s, n_frames=n_frames, H=H, W=W) for s in range(n)])  # [n][T][H][W][3]
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(dev)
     dt = binding.DC_BF16 if args.dtype == "bf16" else binding.DC_F32
-    runner = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry)
+    runner = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
+                                 match_method=binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE,
+                                 k_skip=args.k_skip)
 
     def run_steps(k, start, collect=None):
         """Run k steps through the cyclic video starting at global step `start`."""
@@ -167,7 +172,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import oracle as oc
-        ref = oc.Stream(layers, ws, bs, H, W, 3, block=16, radius=16, bf16=(args.dtype == "bf16"), expiry=args.expiry)
+        ref = oc.Stream(layers, ws, bs, H, W, 3, block=16, radius=16, bf16=(args.dtype == "bf16"), expiry=args.expiry,
+                        diamond=(args.matcher == "ds"), k_skip=args.k_skip)
         k_cpu = min(args.cpu_frames, n_frames)
         t0 = time.perf_counter()
         for f in range(k_cpu):
@@ -185,7 +191,8 @@ def main():
         "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": "configs[1]: 30-frame 224x224x3 synthetic panning video, VGG-16-style 13-conv stack, "
                                "16x16 blocks, search +/-16, tau=20",
-                   "streams": n, "cache_expiry_frames": args.expiry, "frames_per_video": n_frames,
+                   "streams": n, "matcher": "exhaustive search" if args.matcher == "es" else f"diamond search, k-skip {args.k_skip}",
+                   "cache_expiry_frames": args.expiry, "frames_per_video": n_frames,
                    "mean_block_reuse": float(np.mean(agg["reuse"])) if agg["reuse"] else 0.0,
                    "full_frame_fraction": agg["full_frames"] / max(steps_all, 1),
                    "mac_fraction_needed": agg["macs_needed"] / max(agg["macs_full"], 1),

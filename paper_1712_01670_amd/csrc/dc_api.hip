@@ -295,6 +295,7 @@ int32_t dc_match_blocks_ds(const uint8_t* cur, const uint8_t* prev, int32_t n_st
     if (radius > 16383) return DC_ERR_UNSUPPORTED;                                   // vectors are int16
     if ((double)block * block * C * 65025.0 * 2.0 > 4.0e9) return DC_ERR_UNSUPPORTED;   // 32-bit sums
     if ((double)block * W * C >= 2147483648.0) return DC_ERR_UNSUPPORTED;             // 32-bit offsets inside a block
+    if ((double)block * block * block * C * C >= 4294967296.0) return DC_ERR_UNSUPPORTED;   // row index by multiplication
     DC_TRY_HIP(launch_match_diamond(cur, prev, n_streams, H, W, C, block, radius, k_skip, max_block_ssd, mv, best_ssd,
                                     global_mv, n_pass, block_mask, as_stream(stream)));
     return DC_OK;

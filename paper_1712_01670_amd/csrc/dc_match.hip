@@ -31,10 +31,22 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
     return v;
 }
 
+// Sum over the 64 lanes, returned to every lane.  Data-parallel-primitive moves instead of LDS permutes (a
+// dependent chain of six permutes costs more than a round of the diamond search should): within quads by
+// quad permutation, within a row of 16 by row shifts, across rows by broadcasting lane 15 / lane 31 into
+// the following rows; lanes without a source add zero.  The total ends up in lane 63.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_add(int v) {
+    return v + __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
 __device__ __forceinline__ int wave_sum_i32(int v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v = dpp_add<0xb1, 0xf>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4e, 0xf>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x114, 0xf>(v);   // row_shr:4
+    v = dpp_add<0x118, 0xf>(v);   // row_shr:8
+    v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+    return __builtin_amdgcn_readlane(v, 63);
 }
 
 // LDS layout (bytes):
@@ -469,60 +481,73 @@ __global__ __launch_bounds__(64) void motion_retest_kernel(
 
 
 // ---- diamond search (Section 4, Step 2 as the paper runs it) with k-skip ----------------------
-// One wavefront per block of the grid.  The walk is sequential, so a round costs one memory latency:
-// the lanes hold the block's samples (element i of the block goes to lane i % 64), the eight new points of
-// the large pattern are evaluated together (eight independent loads in flight per sample, eight wavefront
-// sums), and every decision is taken on wavefront-uniform values.
+// One wavefront per block of the grid.  The walk is sequential, so what counts is the latency of a round:
+// the wavefront first copies its search window of the previous frame ((B+2R)^2 pixels) and its block into
+// LDS (one pass of independent loads), then every round reads LDS only.  The lanes share the block's
+// samples (sample i goes to lane i % 64), the eight new points of the large pattern are evaluated
+// together, and every decision is taken on wavefront-uniform values.  Windows too large for LDS are read
+// from memory instead (WIN = false).
 //   large pattern: centre, (0,-2), (-1,-1), (1,-1), (-2,0), (2,0), (-1,1), (1,1), (0,2)
 //   small pattern: centre, (0,-1), (-1,0), (1,0), (0,1)
 // The best point of a pattern is the valid one with the smallest (cost, position in the list above); the
 // centre is position 0, so it moves only to a strictly smaller cost and the walk ends; max_rounds (the
 // number of vectors in the search range) bounds it independently of the data.
 // Blocks off the k-skip lattice get mv = (0,0) and best_ssd = 2^32 - 1.
-constexpr int kDiamondWaves = 4;
 __constant__ const signed char kLargeDx[8] = {0, -1, 1, -2, 2, -1, 1, 0};
 __constant__ const signed char kLargeDy[8] = {-2, -1, -1, 0, 0, 1, 1, 2};
 __constant__ const signed char kSmallDx[4] = {0, -1, 1, 0};
 __constant__ const signed char kSmallDy[4] = {-1, 0, 0, 1};
 
+struct DiamondBlock {
+    const uint8_t* cblk;   // the block: memory (pitch W*C) or LDS (pitch B*C)
+    const uint8_t* pwin;   // WIN: LDS window whose origin is the frame position (x0-R, y0-R); else the previous frame
+    int H, W, C, B, R, x0, y0;
+    uint32_t rb_magic;     // ceil(2^32 / (B*C)): sample index -> block row by one multiplication (exact for B^3 C^2 < 2^32)
+};
+
 // Costs of NP points around (cx, cy): cost[p] = SSD of the block against the previous frame at
 // (cx + pdx[p], cy + pdy[p]), or 2^32 - 1 for a point outside the range or the frame.
-template <int NP>
-__device__ __forceinline__ void diamond_costs(const uint8_t* __restrict__ cblk, const uint8_t* __restrict__ pf, int H,
-                                              int W, int C, int B, int R, int x0, int y0, int cx, int cy,
-                                              const signed char* pdx, const signed char* pdy, int lane,
-                                              uint32_t (&cost)[NP]) {
-    const int rb = B * C, n_elem = B * rb;
-    const size_t pitch = (size_t)W * C;
+template <int NP, bool WIN>
+__device__ __forceinline__ void diamond_costs(const DiamondBlock& k, int cx, int cy, const signed char* pdx,
+                                              const signed char* pdy, int lane, uint32_t (&cost)[NP]) {
+    const int rb = k.B * k.C, n_elem = k.B * rb;
+    const int cpitch = WIN ? rb : k.W * k.C;                    // block rows
+    const int ppitch = WIN ? (k.B + 2 * k.R) * k.C : k.W * k.C; // previous-frame rows
     const uint8_t* src[NP];
     bool ok[NP];
     uint32_t s[NP];
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         const int dx = cx + pdx[p], dy = cy + pdy[p];
-        ok[p] = dx >= -R && dx <= R && dy >= -R && dy <= R && x0 + dx >= 0 && y0 + dy >= 0 && x0 + dx + B <= W &&
-                y0 + dy + B <= H;
-        src[p] = pf + ((size_t)(y0 + (ok[p] ? dy : 0)) * W + x0 + (ok[p] ? dx : 0)) * C;   // always inside the frame
+        ok[p] = dx >= -k.R && dx <= k.R && dy >= -k.R && dy <= k.R && k.x0 + dx >= 0 && k.y0 + dy >= 0 &&
+                k.x0 + dx + k.B <= k.W && k.y0 + dy + k.B <= k.H;
+        const int ex = ok[p] ? dx : 0, ey = ok[p] ? dy : 0;       // a point that is not usable is never read
+        src[p] = WIN ? k.pwin + (size_t)(k.R + ey) * ppitch + (k.R + ex) * k.C
+                     : k.pwin + ((size_t)(k.y0 + ey) * k.W + k.x0 + ex) * k.C;
         s[p] = 0;
     }
-    for (int base = 0; base < n_elem; base += 2 * 64) {       // two samples per lane at a time
-        int a[2], off[2];
-        bool in[2];
+    // Straight-line code: every read is unconditional, so that the reads of a batch are issued together instead
+    // of one latency after the other.  A sample beyond the block reads the block's first byte on both sides
+    // (difference zero); a point that is not usable reads the centre's samples and is discarded below.
+    for (int base = 0; base < n_elem; base += 4 * 64) {       // four samples per lane at a time
+        int a[4], off[4];
+        bool in[4];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < 4; ++u) {
             const int i = base + u * 64 + lane;
             in[u] = i < n_elem;
-            const int r = i / rb, j = i - r * rb;
-            off[u] = in[u] ? (int)(r * pitch) + j : 0;
-            a[u] = in[u] ? cblk[off[u]] : 0;
+            const int r = rb == 1 ? i : (int)__umulhi((uint32_t)i, k.rb_magic), j = i - r * rb;
+            off[u] = r * ppitch + j;
+            const uint8_t* pa = in[u] ? k.cblk + (r * cpitch + j) : k.cblk;
+            a[u] = *pa;
         }
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
-            if (!ok[p]) continue;                                // uniform
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int b = in[u] ? src[p][off[u]] : 0;
-                s[p] += (uint32_t)((a[u] - b) * (a[u] - b));
+            for (int u = 0; u < 4; ++u) {
+                const uint8_t* pb = in[u] ? src[p] + off[u] : k.cblk;
+                const int d = a[u] - (int)*pb;
+                s[p] += (uint32_t)(d * d);
             }
         }
     }
@@ -530,33 +555,77 @@ __device__ __forceinline__ void diamond_costs(const uint8_t* __restrict__ cblk, 
     for (int p = 0; p < NP; ++p) cost[p] = ok[p] ? (uint32_t)wave_sum_i32((int)s[p]) : 0xffffffffu;
 }
 
-__global__ __launch_bounds__(kDiamondWaves * 64) void match_diamond_kernel(
+template <bool WIN>
+__global__ __launch_bounds__(256) void match_diamond_kernel(
     const uint8_t* __restrict__ cur, const uint8_t* __restrict__ prev, int H, int W, int C, int B, int R, int gw,
-    int gh, int k_skip, int max_rounds, int16_t* __restrict__ mv, uint32_t* __restrict__ best_ssd) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int gh, int k_skip, int max_rounds, int region_bytes, uint32_t rb_magic, int16_t* __restrict__ mv,
+    uint32_t* __restrict__ best_ssd) {
+    extern __shared__ __align__(16) unsigned char dsm[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
     const int nb = gh * gw;
-    const int blk_id = blockIdx.x * kDiamondWaves + wave, stream = blockIdx.y;
-    if (blk_id >= nb) return;
+    const int blk_id = blockIdx.x * waves + wave, stream = blockIdx.y;
     const int bx = blk_id % gw, by = blk_id / gw;
-    int16_t* out_mv = mv + ((size_t)stream * nb + blk_id) * 2;
-    uint32_t* out_ssd = best_ssd + (size_t)stream * nb + blk_id;
-    if (bx % k_skip != 0 || by % k_skip != 0) {
-        if (lane == 0) { out_mv[0] = 0; out_mv[1] = 0; *out_ssd = 0xffffffffu; }
-        return;
-    }
+    const bool searched = blk_id < nb && bx % k_skip == 0 && by % k_skip == 0;
     const size_t frame_bytes = (size_t)H * W * C;
     const uint8_t* pf = prev + stream * frame_bytes;
     const int x0 = bx * B, y0 = by * B;
-    const uint8_t* cblk = cur + stream * frame_bytes + ((size_t)y0 * W + x0) * C;
-
+    const int rb = B * C, side = B + 2 * R;
+    DiamondBlock k{cur + stream * frame_bytes + ((size_t)y0 * W + x0) * C, pf, H, W, C, B, R, x0, y0, rb_magic};
+    if (WIN) {
+        unsigned char* win = dsm + (size_t)wave * region_bytes;   // side rows of side*C bytes, then the block
+        unsigned char* lblk = win + (size_t)side * side * C;
+        if (searched) {
+            // Row by row, the lanes across a row's bytes; four rows at a time, so that a pass issues 4 * ceil(wb/64)
+            // independent loads per lane and the copy costs a few memory latencies, not one per byte.
+            const int wb = side * C, per_row = (wb + 63) / 64;
+            const int fb0 = (x0 - R) * C;
+            for (int r0 = 0; r0 < side; r0 += 4) {
+                for (int q = 0; q < per_row; ++q) {
+                    const int j = q * 64 + lane, fb = fb0 + j;
+                    unsigned char v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {             // bytes outside the frame are never used: zero
+                        const int r = r0 + u, fy = y0 - R + r;
+                        const bool in = r < side && j < wb && fy >= 0 && fy < H && fb >= 0 && fb < W * C;
+                        const unsigned char g = pf[in ? (size_t)fy * W * C + fb : 0];   // unconditional: the loads overlap
+                        v[u] = in ? g : 0;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (r0 + u < side && j < wb) win[(r0 + u) * wb + j] = v[u];
+                }
+            }
+            for (int r0 = 0; r0 < B; r0 += 8) {
+                for (int q = 0; q < (rb + 63) / 64; ++q) {
+                    const int j = q * 64 + lane;
+                    unsigned char v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = k.cblk[(r0 + u < B && j < rb) ? (size_t)(r0 + u) * W * C + j : 0];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (r0 + u < B && j < rb) lblk[(r0 + u) * rb + j] = v[u];
+                }
+            }
+        }
+        __syncthreads();     // every wavefront of the workgroup arrives here, searched block or not
+        k.cblk = lblk;
+        k.pwin = win;
+    }
+    if (blk_id >= nb) return;
+    int16_t* out_mv = mv + ((size_t)stream * nb + blk_id) * 2;
+    uint32_t* out_ssd = best_ssd + (size_t)stream * nb + blk_id;
+    if (!searched) {
+        if (lane == 0) { out_mv[0] = 0; out_mv[1] = 0; *out_ssd = 0xffffffffu; }
+        return;
+    }
     const signed char zero = 0;
     uint32_t c0[1];
-    diamond_costs<1>(cblk, pf, H, W, C, B, R, x0, y0, 0, 0, &zero, &zero, lane, c0);
+    diamond_costs<1, WIN>(k, 0, 0, &zero, &zero, lane, c0);
     int cx = 0, cy = 0;
     uint32_t ccost = c0[0];
     for (int round = 0; round < max_rounds; ++round) {
         uint32_t c[8];
-        diamond_costs<8>(cblk, pf, H, W, C, B, R, x0, y0, cx, cy, kLargeDx, kLargeDy, lane, c);
+        diamond_costs<8, WIN>(k, cx, cy, kLargeDx, kLargeDy, lane, c);
         int best = -1;
         uint32_t bcost = ccost;
 #pragma unroll
@@ -566,7 +635,7 @@ __global__ __launch_bounds__(kDiamondWaves * 64) void match_diamond_kernel(
         cx += kLargeDx[best]; cy += kLargeDy[best]; ccost = bcost;
     }
     uint32_t c[4];
-    diamond_costs<4>(cblk, pf, H, W, C, B, R, x0, y0, cx, cy, kSmallDx, kSmallDy, lane, c);
+    diamond_costs<4, WIN>(k, cx, cy, kSmallDx, kSmallDy, lane, c);
     int best = -1;
     uint32_t bcost = ccost;
 #pragma unroll
@@ -651,10 +720,19 @@ hipError_t launch_match_diamond(const uint8_t* cur, const uint8_t* prev, int n_s
                                 int R, int k_skip, uint32_t max_ssd, int16_t* mv, uint32_t* best_ssd, int32_t* gmv,
                                 int32_t* n_pass, uint8_t* mask, hipStream_t st) {
     const int gh = H / B, gw = W / B;
-    const unsigned long long side = 2ull * R + 1;
-    const unsigned long long cap = side * side < 0x7fffffffull ? side * side : 0x7fffffffull;
-    hipLaunchKernelGGL(match_diamond_kernel, dim3((gh * gw + kDiamondWaves - 1) / kDiamondWaves, n_streams),
-                       dim3(kDiamondWaves * 64), 0, st, cur, prev, H, W, C, B, R, gw, gh, k_skip, (int)cap, mv, best_ssd);
+    const unsigned long long nvec = (2ull * R + 1) * (2ull * R + 1);
+    const int cap = (int)(nvec < 0x7fffffffull ? nvec : 0x7fffffffull);
+    const uint32_t rb_magic = (uint32_t)((0x100000000ull + (uint64_t)(B * C) - 1) / (uint64_t)(B * C));
+    // LDS per wavefront: the search window and the block; as many wavefronts per workgroup as fit into 64 KiB
+    const size_t side = (size_t)B + 2 * (size_t)R;
+    const size_t region = align_up(side * side * C + (size_t)B * B * C, 16);
+    const int waves = region <= 16 * 1024 ? 4 : (region <= 32 * 1024 ? 2 : 1);
+    if (region <= 64 * 1024)
+        hipLaunchKernelGGL(match_diamond_kernel<true>, dim3((gh * gw + waves - 1) / waves, n_streams), dim3(waves * 64),
+                           region * waves, st, cur, prev, H, W, C, B, R, gw, gh, k_skip, cap, (int)region, rb_magic, mv, best_ssd);
+    else
+        hipLaunchKernelGGL(match_diamond_kernel<false>, dim3((gh * gw + 3) / 4, n_streams), dim3(256), 0, st, cur, prev,
+                           H, W, C, B, R, gw, gh, k_skip, cap, 0, rb_magic, mv, best_ssd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(motion_retest_kernel, dim3(gh * gw, n_streams), dim3(64), 0, st, cur, prev, H, W, C, B, gw, gh,

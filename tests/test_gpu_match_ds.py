@@ -68,7 +68,8 @@ def test_panning_video_vgg_geometry(oracle):
 
 @pytest.mark.parametrize("H,W,C,B,R", [(50, 70, 3, 10, 7), (45, 53, 1, 5, 3), (40, 44, 4, 8, 8),
                                        (227, 227, 3, 10, 8), (33, 35, 3, 16, 16), (64, 64, 2, 7, 5),
-                                       (96, 128, 3, 32, 40), (64, 64, 3, 8, 0), (64, 64, 3, 8, 1)])
+                                       (96, 128, 3, 32, 40), (64, 64, 3, 8, 0), (64, 64, 3, 8, 1),
+                                       (120, 136, 3, 16, 70), (20, 24, 1, 1, 3)])   # the last one: window too large for LDS
 def test_ragged_shapes_long_walks_and_small_ranges(oracle, H, W, C, B, R):
     rng = np.random.default_rng(H * W + R)
     prev = synth._box_blur5(synth._box_blur5(rng.integers(0, 256, (H, W, C)).astype(np.uint8)))
