@@ -1,5 +1,8 @@
 // C ABI entry points: argument validation, host-side planning, kernel sequencing.
 #include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -471,6 +474,32 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
     return DC_OK;
 }
 
+namespace {
+// DC_HOST_TIMING=1: host time of a cached dc_run_stack call by phase, printed every 200 calls (experiments).
+struct HostTiming {
+    bool on = false;
+    double acc[6] = {0, 0, 0, 0, 0, 0};
+    long calls = 0;
+    std::chrono::steady_clock::time_point last;
+    HostTiming() { const char* e = getenv("DC_HOST_TIMING"); on = e && atoi(e) != 0; }
+    void start() { if (on) last = std::chrono::steady_clock::now(); }
+    void mark(int phase) {
+        if (!on) return;
+        const auto now = std::chrono::steady_clock::now();
+        acc[phase] += std::chrono::duration<double, std::micro>(now - last).count();
+        last = now;
+    }
+    void end_call() {
+        if (!on || ++calls % 200) return;
+        fprintf(stderr, "[dc_run_stack host us/call] launch match %.1f | wait match %.1f | merge+propagate %.1f | plans %.1f | "
+                        "copy tables+upload %.1f | layer launches %.1f\n",
+                acc[0] / 200, acc[1] / 200, acc[2] / 200, acc[3] / 200, acc[4] / 200, acc[5] / 200);
+        for (double& a : acc) a = 0;
+    }
+};
+HostTiming g_host_timing;
+}  // namespace
+
 int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const* weights,
                      const void* const* packed_weights, const float* const* bias,
                      const uint8_t* frames_cur, const uint8_t* frames_prev, void* const* tensors_cur,
@@ -580,6 +609,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     std::vector<std::vector<TensorRegions>> regs;  // [stream][tensor]
     unsigned char* hbase = static_cast<unsigned char*>(ws_host);
     if (cached) {
+        g_host_timing.start();
         // With an overlap handle the matching runs on its own stream, next to whatever the main stream
         // still holds of the previous frame; only that stream is waited for.
         hipStream_t mst = ov ? ov->aux : st;
@@ -597,12 +627,14 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         // the network input does not depend on the match: its conversion overlaps the readback
         DC_TRY_HIP(wait_prev(last_reader[0]));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
+        g_host_timing.mark(0);
         if (ov) {
             DC_TRY_HIP(hipEventRecord(ov->match_done, mst));
             DC_TRY_HIP(spin_wait(ov->match_done));
         } else {
             DC_TRY_HIP(hipStreamSynchronize(mst));
         }
+        g_host_timing.mark(1);
         try {
             regs.resize(n_streams);
             std::vector<dc_rect> rects0;
@@ -618,6 +650,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         } catch (const std::bad_alloc&) {
             return DC_ERR_WORKSPACE;
         }
+        g_host_timing.mark(2);
         hbase += align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
         if (ov) {
             // two staging halves: the upload of the frame before last must have left the half reused now
@@ -691,6 +724,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     } catch (const std::bad_alloc&) {
         return DC_ERR_WORKSPACE;
     }
+    if (cached) g_host_timing.mark(3);
     // ---- the shifted copies of all layers in one launch (16-byte vector path only); pipelined: one launch per
     // run of consecutive conv layers, issued when the previous frame has finished that run ----
     std::vector<char> copy_fused(n_layers, 0);
@@ -757,6 +791,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         return DC_OK;
     };
 
+    if (cached) g_host_timing.mark(4);
     // ---- layers ----
     for (int i = 0; i < n_layers; ++i) {
         const dc_layer& l = layers[i];
@@ -799,6 +834,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         DC_TRY_HIP(hipStreamWaitEvent(caller_st, ov->frame_done[fp], 0));
         ov->frame_parity ^= 1;
     }
+    if (cached) { g_host_timing.mark(5); g_host_timing.end_call(); }
     if (stats) *stats = local;
     return DC_OK;
 }

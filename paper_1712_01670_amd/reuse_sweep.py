@@ -13,6 +13,7 @@ One JSON line per ratio: measured reuse ratio, fraction of MACs needed and issue
 the three modes and the saving 1 - t_mode / t_full.
 
     python paper_1712_01670_amd/reuse_sweep.py [--net darknet19|vgg16] [--size 416] [--dtype bf16|f32]
+                                               [--streams n] [--matcher es|ds] [--k-skip k]
 """
 from __future__ import annotations
 
@@ -36,6 +37,9 @@ def main():
     ap.add_argument("--frames", type=int, default=60)
     ap.add_argument("--repeats", type=int, default=3)
     ap.add_argument("--expiry", type=int, default=10)
+    ap.add_argument("--streams", type=int, default=1, help="independent videos processed as one batch per step")
+    ap.add_argument("--matcher", choices=["es", "ds"], default="es")
+    ap.add_argument("--k-skip", type=int, default=1)
     args = ap.parse_args()
 
     import numpy as np
@@ -58,7 +62,7 @@ def main():
                 scene_start = f == 0 or f == cut
                 if scene_start:
                     runner.reset()
-                runner.step(video[f:f + 1], force_full=(mode == "full"))
+                runner.step(video[f], force_full=(mode == "full"))
                 if collect:
                     torch.cuda.synchronize()
                     st = runner.stats
@@ -76,12 +80,17 @@ def main():
         return dt_s, macs, reuse
 
     for i, r in enumerate(float(x) for x in args.ratios.split(",")):
-        video = torch.from_numpy(synth.reuse_sweep_video(4000 + i, r, n_frames=args.frames, H=H, W=W, cut_at=cut)).to(dev)
-        out = {"target_reuse": r, "net": args.net, "size": args.size, "dtype": args.dtype, "frames": args.frames}
+        vids = np.stack([synth.reuse_sweep_video(4000 + i + 100 * s, r, n_frames=args.frames, H=H, W=W, cut_at=cut)
+                         for s in range(args.streams)])                       # [streams][T][H][W][3]
+        video = torch.from_numpy(np.ascontiguousarray(vids.transpose(1, 0, 2, 3, 4))).to(dev)
+        out = {"target_reuse": r, "net": args.net, "size": args.size, "dtype": args.dtype, "frames": args.frames,
+               "streams": args.streams, "matcher": args.matcher, "k_skip": args.k_skip}
         for mode, expiry in (("cached", 1 << 30), ("expiry", args.expiry), ("full", 1 << 30)):
-            runner = binding.StackRunner(layers, ws, bs, 1, H, W, 3, block=16, radius=16, dtype=dt, expiry=expiry)
+            runner = binding.StackRunner(layers, ws, bs, args.streams, H, W, 3, block=16, radius=16, dtype=dt, expiry=expiry,
+                                         match_method=binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE,
+                                         k_skip=args.k_skip)
             t, macs, reuse = timed(runner, video, mode)
-            out[mode] = {"frames_per_s": 1.0 / t, "ms_per_frame": t * 1e3}
+            out[mode] = {"frames_per_s": args.streams / t, "ms_per_frame": t * 1e3 / args.streams}
             if mode != "full":
                 out[mode]["mac_fraction_needed"] = macs[1] / max(macs[0], 1)
                 out[mode]["mac_fraction_issued"] = macs[2] / max(macs[0], 1)
