@@ -608,13 +608,15 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
                     const double fixed = wg_fix + 400.0 * upw * G.nbw + cps * 3 * stage_fix;
                     const long wgs = groups * R * ks_eff;
                     const long per_cu = (wgs + 255) / 256;
-                    // many rounds: the dispatcher balances the CUs, the last round is not a whole one
-                    const double rounds = wgs <= 512 ? (double)per_cu : wgs / 256.0 + 0.5;
                     const int vgprs = (kci ? 64 : 44) + (geom ? 10 * G.nbw * upw + 6 * G.nbw : (kci ? 18 : 16) * upw);
                     long occ = (long)(160 * 1024 / fast_lds_bytes(geom, kci, upw));
                     if (occ > 512 / vgprs / 2) occ = 512 / vgprs / 2;
                     if (occ > 4) occ = 4;
                     if (occ < 1) occ = 1;
+                    // Workgroups that are all resident from the start share their CU to the end: the fullest CU
+                    // sets the time.  With more rounds than that the dispatcher balances the CUs and only the last
+                    // round is not a whole one.
+                    const double rounds = (wgs <= 512 || wgs <= 256 * occ) ? (double)per_cu : wgs / 256.0 + 0.5;
                     double cost = rounds * work + (double)((per_cu + occ - 1) / occ) * fixed;
                     // a lone workgroup per CU leaves the matrix cores idle during its barriers, prologue and epilogue,
                     // and leaves no room for the workgroups of the other frame in flight (measured: 5 % per frame)
