@@ -563,7 +563,7 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
     static double bw = -1, stage_fix = 0, wg_fix = 0, red_fix = 0, occ1_penalty = 1.08, lds_cap_kb = 160;
     if (bw < 0) {
         const char* e = getenv("DC_CONV_MODEL");   // "bytes/clk/CU,stage,wg,reduce,penalty" (experiments)
-        bw = 24; stage_fix = 250; wg_fix = 4500; red_fix = 13000;
+        bw = 32; stage_fix = 250; wg_fix = 4500; red_fix = 13000;
         if (e) sscanf(e, "%lf,%lf,%lf,%lf,%lf,%lf", &bw, &stage_fix, &wg_fix, &red_fix, &occ1_penalty, &lds_cap_kb);
     }
     const bool bf16 = c.dtype == DC_BF16;
