@@ -378,6 +378,224 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     F::store4(out, v);
 }
 
+// ---- 3x3, 64 input channels, bf16: the weights live in registers -----------------------------
+// K is only 576, so a workgroup of the kernel above spends more time on its prologue and epilogue than on its
+// six stages.  Here a wavefront keeps the weights of its 32 output channels for the whole K in registers
+// (9 taps x 2 K groups x 2 channel blocks = 36 fragments, 144 registers), the workgroups are persistent
+// (one per CU and channel tile) and walk over the unit list; per step only the patches of the next G units
+// travel (buffer_load ... lds into the other half of a double buffer) while the current ones are multiplied.
+// There is no unit table in LDS: the two wavefronts that share a row of units (they differ in the channel
+// half) also load exactly those units' patches, half each, so everything a wavefront needs to know about a
+// unit is wavefront-uniform and lives in registers; the unit list entries are fetched two steps ahead.
+//   workgroup = 8 wavefronts = 4 unit rows x 2 channel halves; step = G = 4 * UPW units x 64 channels
+//   LDS       = 2 x G patches of 6 lines x 8 slots x 128 bytes (layout and swizzle of the kernel above)
+struct UnitRegs {
+    int in_base;    // byte offset in the input of the patch origin
+    int oy, ox;     // row / column of that origin (may be negative); oy = -2^24 for a missing unit
+    int out_base;   // element offset in the output of the unit's first pixel
+    int kind;       // -1: missing unit, else the 16-bit mask of reusable pixels
+};
+
+// The unit list entry of unit u (or its raster position), not yet turned into offsets: fetched two steps ahead.
+__device__ __forceinline__ TileDev regw_fetch(const ConvParams& P, long u) {
+    TileDev t{0, 0, 0, -1};                 // reuse_mask -1: no such unit
+    if (u >= P.n_units) return t;
+    if (P.units) return P.units[u];
+    t.stream = fast_div((int)u, P.npix_magic);
+    const int rem = (int)u - t.stream * (P.units_x * P.units_y);
+    t.ty = fast_div(rem, P.pw_magic); t.tx = rem - t.ty * P.units_x;
+    t.reuse_mask = 0;
+    return t;
+}
+__device__ __forceinline__ UnitRegs regw_unit(const ConvParams& P, const TileDev& t) {
+    UnitRegs r;
+    const bool valid = t.reuse_mask != -1;
+    const int oy = t.ty * 4 - P.p, ox = t.tx * 4 - P.p;
+    r.in_base = ((t.stream * P.Hin + oy) * P.Win + ox) * P.Cin * 2;
+    r.oy = valid ? oy : -(1 << 24);
+    r.ox = ox;
+    r.out_base = ((t.stream * P.Hout + t.ty * 4) * P.Wout + t.tx * 4) * P.Cout;
+    r.kind = valid ? (t.reuse_mask & 0xffff) : -1;
+    return r;
+}
+
+template <int WM, int UPW>
+__global__ __launch_bounds__(WM * 128) void conv_regw_kernel(ConvParams P) {
+    typedef Frag<__hip_bfloat16> F;
+    typedef F::vec vec;
+    constexpr int WN = 2, NBW = 2, G = WM * UPW;
+    constexpr int RB = 128, PWP = 8, PR = 48;
+    constexpr int PBYTES = G * PR * RB;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_n = wave % WN, wave_m = wave / WN;
+    const int l16 = lane & 15, q = lane >> 4;
+    const int n0 = (int)blockIdx.y * 64 + wave_n * 32;          // first output channel of this wavefront
+    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.in))), 0, keep_scalar(P.in_bytes), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.w))), 0, keep_scalar(P.w_bytes), kBufferFlags);
+
+    // weights [cout][3][3][64]: fragment (tap, K group g, block j) of lane (l16, q) = 8 channels from g*32 + q*8
+    vec wreg[9][2][NBW];
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) {
+                const uint32_t off = (uint32_t)((((n0 + j * 16 + l16) * 9 + t) * 64 + g * 32 + q * 8) * 2);
+                wreg[t][g][j] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, off, 0, 0));
+            }
+    const int chan = n0 + 4 * q;
+    floatx4 bias[NBW];
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+        bias[j] = P.bias ? *reinterpret_cast<const floatx4*>(P.bias + chan + j * 16) : floatx4{0.f, 0.f, 0.f, 0.f};
+    // ReLU on the bit pattern: a float with the sign bit set is a negative integer, so max(bits, 0) as integers
+    // clears exactly the negative values; without ReLU the floor is the smallest integer and changes nothing
+    const int relu_floor = P.relu ? 0 : (int)0x80000000;
+
+    // load side: of each of its units this wavefront brings lines 3 * wave_n .. 3 * wave_n + 2 (one instruction per
+    // line: 8 slots x 128 bytes); the lane fills chunk position lane % 8 of slot lane / 8.  Everything that does
+    // not depend on the unit is computed once: the step's address work is one add and one select per instruction.
+    const int px_l = lane >> 3, lpos = lane & 7;
+    const int CinES = 128;
+    const int line_bytes = P.Win * CinES;
+    int lane_off[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const int py = wave_n * 3 + i;
+        lane_off[i] = py * line_bytes + px_l * CinES + ((lpos ^ patch_swizzle<RB>(py, px_l)) << 4);
+    }
+    const int Hin = keep_scalar(P.Hin), Win = keep_scalar(P.Win);
+    auto issue_p = [&](const UnitRegs (&info)[UPW], int buf) {
+#pragma unroll
+        for (int uu = 0; uu < UPW; ++uu) {
+            // columns: slot px_l is inside the map iff 0 <= ox + px_l < Win (slots 6 and 7 are never used)
+            const bool col_ok = px_l < 6 && (unsigned)(info[uu].ox + px_l) < (unsigned)Win;
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const int py = wave_n * 3 + i;
+                const bool row_ok = (unsigned)(info[uu].oy + py) < (unsigned)Hin;       // wavefront-uniform
+                const uint32_t off = (col_ok && row_ok) ? (uint32_t)(info[uu].in_base + lane_off[i]) : kOob;
+                unsigned char* dst = smem + buf * PBYTES + ((wave_m + uu * WM) * PR + py * PWP) * RB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(in_rsrc, (__attribute__((address_space(3))) void*)dst, 16, off, 0, 0, 0);
+            }
+        }
+    };
+    // read side: byte address of this lane's row and chunk for every tap and K group
+    int paddr[9][2];
+    {
+        const int oy = l16 >> 2, ox = l16 & 3;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int py = oy + t / 3, px = ox + t % 3;
+            const int sw = patch_swizzle<RB>(py, px);
+#pragma unroll
+            for (int g = 0; g < 2; ++g) paddr[t][g] = (wave_m * PR + py * PWP + px) * RB + (((g * 4 + q) ^ sw) << 4);
+        }
+    }
+
+    const long n_groups = ((long)P.n_units + G - 1) / G;
+    const long stride = gridDim.x;
+    // Workgroup b runs on XCD b % 8.  In every pass over the list the workgroups of one XCD take consecutive
+    // groups, so that the units above and below (a row of units further in the list) are in the same L2 at about
+    // the same time and the halo rows are fetched from HBM once.
+    const long first = (gridDim.x % 8 == 0) ? (long)(blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8 : (long)blockIdx.x;
+    auto fetch = [&](long ug, TileDev (&raw)[UPW]) {
+#pragma unroll
+        for (int uu = 0; uu < UPW; ++uu) raw[uu] = regw_fetch(P, ug < n_groups ? ug * G + wave_m + uu * WM : (long)P.n_units);
+    };
+    auto decode = [&](const TileDev (&raw)[UPW], UnitRegs (&info)[UPW]) {
+#pragma unroll
+        for (int uu = 0; uu < UPW; ++uu) info[uu] = regw_unit(P, raw[uu]);
+    };
+    UnitRegs cur[UPW], nxt[UPW];
+    TileDev raw[UPW];
+    long ug = first;
+    fetch(ug, raw); decode(raw, cur);
+    fetch(ug + stride, raw); decode(raw, nxt);
+    fetch(ug + 2 * stride, raw);             // decoded at the end of the first step
+    issue_p(cur, 0);
+    // results of the previous step, stored one step late: the wait for this step's patches at the top of the
+    // loop would otherwise also wait for the stores just issued
+    uintx2 pend[UPW][NBW];
+    __hip_bfloat16* pend_px[UPW];
+    bool pend_on[UPW];
+#pragma unroll
+    for (int uu = 0; uu < UPW; ++uu) pend_on[uu] = false;
+    auto flush = [&]() {
+#pragma unroll
+        for (int uu = 0; uu < UPW; ++uu) {
+            if (!pend_on[uu]) continue;
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) *reinterpret_cast<uintx2*>(pend_px[uu] + j * 16) = pend[uu][j];
+        }
+    };
+    for (int it = 0; ug < n_groups; ug += stride, ++it) {
+        const int buf = it & 1;
+        // the patches of this step have arrived; after the barrier every wavefront is done with the other buffer,
+        // which the next step's patches may overwrite
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (ug + stride < n_groups) issue_p(nxt, buf ^ 1);
+        flush();
+
+        floatx4 acc[UPW][NBW];                     // start from the bias
+#pragma unroll
+        for (int uu = 0; uu < UPW; ++uu)
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) acc[uu][j] = bias[j];
+        const unsigned char* pbase = smem + buf * PBYTES;
+        // 18 steps (tap, K group); the fragments of step s + 2 are read before the MFMAs of step s
+        vec x[3][UPW];
+        auto frag = [&](int st, int b) {
+#pragma unroll
+            for (int uu = 0; uu < UPW; ++uu)
+                x[b][uu] = *reinterpret_cast<const vec*>(pbase + paddr[st / 2][st % 2] + uu * (WM * PR * RB));
+        };
+        frag(0, 0);
+        frag(1, 1);
+#pragma unroll
+        for (int st = 0; st < 18; ++st) {
+            if (st + 2 < 18) frag(st + 2, (st + 2) % 3);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int uu = 0; uu < UPW; ++uu)
+#pragma unroll
+                for (int j = 0; j < NBW; ++j) F::mma1(wreg[st / 2][st % 2][j], x[st % 3][uu], acc[uu][j], 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // epilogue: pixel l16 of the unit, channels chan + 16 j .. + 3
+#pragma unroll
+        for (int uu = 0; uu < UPW; ++uu) {
+            const int y = cur[uu].oy + P.p + (l16 >> 2), x = cur[uu].ox + P.p + (l16 & 3);
+            pend_on[uu] = !(cur[uu].kind < 0 || y >= P.Hout || x >= P.Wout || ((cur[uu].kind >> l16) & 1));
+            pend_px[uu] = reinterpret_cast<__hip_bfloat16*>(P.out) + cur[uu].out_base +
+                          ((l16 >> 2) * P.Wout + (l16 & 3)) * P.Cout + chan;
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) {
+                floatx4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {      // negative values (sign bit set) are negative integers
+                    const int b = __float_as_int(acc[uu][j][e]);
+                    v[e] = __int_as_float(b > relu_floor ? b : relu_floor);
+                }
+                pend[uu][j][0] = (uint32_t)F::bits(v[0]) | ((uint32_t)F::bits(v[1]) << 16);
+                pend[uu][j][1] = (uint32_t)F::bits(v[2]) | ((uint32_t)F::bits(v[3]) << 16);
+            }
+        }
+#pragma unroll
+        for (int uu = 0; uu < UPW; ++uu) cur[uu] = nxt[uu];
+        decode(raw, nxt);                        // the entries fetched a step ago
+        fetch(ug + 3 * stride, raw);             // for the step after next
+    }
+    flush();
+}
+
 // dst vector idx = (((blk * nc64 + c64) * 9 + tap) * 16 + n16) * 4 + v  <-  src row (blk * 16 + n16, tap), 64-byte chunk c64
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uintx4* src, uintx4* dst, int nc64, size_t n_vec) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -635,6 +853,7 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
 // Ids 64.. name the instantiations of this file: 64 + ((bf16 * 2 + kci) * 8 + UPW - 1), 96.. the first-layer kernel,
 // 110.. the wide arrangement.
 void conv_fast_kernel_name(int id, char* buf, size_t n) {
+    if (id == 126) { snprintf(buf, n, "conv_regw_kernel<2, 2>"); return; }
     if (id >= 110) {  // 110 + (arrangement - 1) * 8 + kci * 4 + UPW - 1: the wide bf16 arrangements
         const int v = (id - 110) % 8, wide64 = (id - 110) / 8;
         snprintf(buf, n, "conv_fast_kernel<__hip_bfloat16, 3, %d, %d, 4, 2, %d>", 32 << (v / 4), v % 4 + 1, wide64 ? 2 : 4);
@@ -664,6 +883,18 @@ hipError_t launch_pack_weights(const void* w, void* packed, int cin, int cout, i
     const size_t n_vec = (size_t)cout * 9 * cin * esz / 16;
     hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((n_vec + 255) / 256)), dim3(256), 0, st,
                        static_cast<const uintx4*>(w), static_cast<uintx4*>(packed), (int)(cin * esz / 64), n_vec);
+    return hipGetLastError();
+}
+
+template <int WM, int UPW>
+hipError_t regw_launch(dim3 grid, hipStream_t st, const ConvParams& P) {
+    const size_t lds = 2 * (size_t)(WM * UPW) * 48 * 128;
+    if (lds > 64 * 1024) {
+        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_regw_kernel<WM, UPW>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (a != hipSuccess) return a;
+    }
+    hipLaunchKernelGGL((conv_regw_kernel<WM, UPW>), grid, dim3(WM * 128), lds, st, P);
     return hipGetLastError();
 }
 
@@ -702,6 +933,29 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         const double units_map = (double)((c.Hout + 3) / 4) * ((c.Wout + 3) / 4);
         if ((double)c.n_streams * c.Hout * c.Wout * c.Cout >= 2147483648.0 || (double)n_units * units_map >= 4294967296.0)
             return false;
+    }
+    init_tuning();
+    // 64 input channels in bf16 and enough units to keep persistent workgroups busy: the weights go to registers
+    if (c.dtype == DC_BF16 && c.Cin == 64 && (g_tune[0] == 3 || (g_tune[0] < 0 && g_tune[1] < 0 && n_units >= 4096))) {
+        ConvParams P{};
+        P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
+        P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
+        P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
+        P.units = c.tiles; P.n_units = (int)n_units;
+        P.units_x = (c.Wout + 3) / 4; P.units_y = (c.Hout + 3) / 4;
+        P.npix_magic = (uint32_t)((0x100000000ull + (uint64_t)(P.units_x * P.units_y) - 1) / (uint64_t)(P.units_x * P.units_y));
+        P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)P.units_x - 1) / (uint64_t)P.units_x);
+        P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * c.Cin * esz);
+        P.w_bytes = (uint32_t)((size_t)c.Cout * 9 * c.Cin * esz);
+        // Two persistent workgroups of four wavefronts per CU (the registers allow two wavefronts per SIMD): they
+        // drift apart, so that one's address work and epilogue overlap the other's MFMAs.
+        const int R = c.Cout / 64;
+        const long groups = (n_units + 3) / 4;
+        long gx = 512 / R > 0 ? 512 / R : 1;
+        if (gx > groups) gx = groups;
+        if (c.kernel_id) *c.kernel_id = 126;
+        *err = regw_launch<2, 2>(dim3((unsigned)gx, (unsigned)R), st, P);
+        return true;
     }
     size_t scratch = c.scratch && reinterpret_cast<uintptr_t>(c.scratch) % 16 == 0 ? c.scratch_bytes : 0;
     if (scratch > kConvScratchBytes) scratch = kConvScratchBytes;

@@ -107,6 +107,8 @@ FAST_CASES = [
     (22, 30, 64, 64, (2, 11, 1, 0)),     # 64 channels per workgroup in two blocks per wavefront (bf16)
     (14, 14, 128, 192, (2, 4, 2, 1)),
     (19, 23, 128, 128, (-1, -1, -1, -1)),  # the library's own choice
+    (22, 30, 64, 64, (3, -1, -1, -1)),    # bf16: persistent kernel with the weights in registers (plain weights)
+    (37, 41, 64, 128, (3, -1, -1, -1)),   # ... two channel tiles, more unit groups than one step, ragged map
 ]
 
 
@@ -141,7 +143,8 @@ def test_fast_conv_kernel_shapes(oracle, case, bf16, cached):
         assert np.array_equal(wp.view(torch.uint8).cpu().numpy().reshape(cout // 16, cin * es // 64, 9, 16, 64),
                               raw.transpose(0, 3, 2, 1, 4)), "layout [cout/16][64-byte chunk][tap][16][64 bytes]"
         # plain weights zeroed: the result shows that the kernel reads the packed copy
-        got_p = _to_np(binding.dc_cached_conv_layer(layer, _to_dev(x, bf16), torch.zeros_like(wd), torch.from_numpy(b).to(DEV),
+        plain = wd if tuning[0] == 3 else torch.zeros_like(wd)     # arrangement 3 reads the plain layout
+        got_p = _to_np(binding.dc_cached_conv_layer(layer, _to_dev(x, bf16), plain, torch.from_numpy(b).to(DEV),
                                                     cache_prev=_to_dev(cache, bf16) if cached else None, regions=regions,
                                                     packed=wp))
     finally:
