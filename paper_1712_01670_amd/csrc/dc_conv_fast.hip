@@ -618,6 +618,7 @@ template <typename T, int NB>
 __global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
     typedef Frag<T> F;
     typedef typename F::vec vec;
+    constexpr bool kWide = sizeof(T) == 2 && NB >= 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.y * (NB * 16);
@@ -629,54 +630,96 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
     for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            const uint32_t off = q < 3 ? (uint32_t)(((n0 + j * 16 + l16) * 9 + ky * 3 + q) * 16) : kOob;
+            // bf16: row l16 of block j carries output channel (l16 / 4) * 4 NB + 4 j + l16 % 4, so that the accumulators
+            // of a lane (rows 4q .. 4q+3 of every block) are 4 NB consecutive channels and leave in 16-byte stores.
+            // fp32 keeps channel 16 j + l16: there a store instruction already writes 64 contiguous bytes per pixel.
+            const int co = kWide ? (l16 >> 2) * (4 * NB) + j * 4 + (l16 & 3) : j * 16 + l16;
+            const uint32_t off = q < 3 ? (uint32_t)(((n0 + co) * 9 + ky * 3 + q) * 16) : kOob;
             wv[ky][j] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, off, 0, 0));
         }
-    const int chan = n0 + 4 * q;
+    constexpr int kBlockStep = kWide ? 4 : 16;               // channel distance between a lane's blocks
+    const int chan = n0 + (kWide ? 4 * NB : 4) * q;
     floatx4 bias[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j)
-        bias[j] = P.bias ? *reinterpret_cast<const floatx4*>(P.bias + chan + j * 16) : floatx4{0.f, 0.f, 0.f, 0.f};
+        bias[j] = P.bias ? *reinterpret_cast<const floatx4*>(P.bias + chan + j * kBlockStep) : floatx4{0.f, 0.f, 0.f, 0.f};
     const bool relu = P.relu != 0;
     const int per = P.units_x * P.units_y;
 
-    for (int u = blockIdx.x * 4 + wave; u < P.n_units; u += gridDim.x * 4) {
-        int stream, uy, ux, mixed = 0;
+    // The loop is pipelined by hand: the input vectors of the next unit are requested before the current one is
+    // multiplied and stored, so that a wavefront does not sit out a memory latency per unit.
+    struct UnitPos { int stream, uy, ux, mixed; };
+    auto locate = [&](int u) {
+        UnitPos r{0, 0, 0, 0};
         if (P.units) {
             const TileDev t = P.units[u];
-            stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.reuse_mask;
+            r.stream = t.stream; r.uy = t.ty; r.ux = t.tx; r.mixed = t.reuse_mask;
         } else {
-            stream = fast_div(u, P.npix_magic);
-            const int r = u - stream * per;
-            uy = fast_div(r, P.pw_magic); ux = r - uy * P.units_x;
+            r.stream = fast_div(u, P.npix_magic);
+            const int rem = u - r.stream * per;
+            r.uy = fast_div(rem, P.pw_magic); r.ux = rem - r.uy * P.units_x;
         }
-        const int y = uy * 4 + (l16 >> 2), x = ux * 4 + (l16 & 3);
-        vec xv[3];
+        return r;
+    };
+    auto load_x = [&](const UnitPos& pos, vec (&xv)[3]) {
+        const int y = pos.uy * 4 + (l16 >> 2), x = pos.ux * 4 + (l16 & 3);
 #pragma unroll
         for (int ky = 0; ky < 3; ++ky) {
             const int iy = y - P.p + ky, ix = x - P.p + q;
             const bool ok = q < 3 && (unsigned)iy < (unsigned)P.Hin && (unsigned)ix < (unsigned)P.Win;
-            const uint32_t off = ok ? (uint32_t)(((stream * P.Hin + iy) * P.Win + ix) * 16) : kOob;
+            const uint32_t off = ok ? (uint32_t)(((pos.stream * P.Hin + iy) * P.Win + ix) * 16) : kOob;
             xv[ky] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0));
+        }
+    };
+    const int step = gridDim.x * 4;
+    int u = blockIdx.x * 4 + wave;
+    if (u >= P.n_units) return;
+    UnitPos pos = locate(u), pos_next = pos;
+    vec xv[3], xv_next[3];
+    load_x(pos, xv);
+    for (; u < P.n_units; u += step) {
+        const bool more = u + step < P.n_units;          // wavefront-uniform
+        if (more) {
+            pos_next = locate(u + step);
+            load_x(pos_next, xv_next);
         }
         floatx4 acc[NB];
 #pragma unroll
-        for (int j = 0; j < NB; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < NB; ++j) acc[j] = bias[j];
 #pragma unroll
         for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
             for (int e = 0; e < F::NE; ++e)
 #pragma unroll
                 for (int j = 0; j < NB; ++j) F::mma1(wv[ky][j], xv[ky], acc[j], e);
-        const bool keep = y < P.Hout && x < P.Wout && !((mixed >> l16) & 1);   // a reusable pixel holds the copied value
-        if (!keep) continue;
-        T* px = reinterpret_cast<T*>(P.out) + ((stream * P.Hout + y) * P.Wout + x) * P.Cout + chan;
+        const int y = pos.uy * 4 + (l16 >> 2), x = pos.ux * 4 + (l16 & 3);
+        const bool keep = y < P.Hout && x < P.Wout && !((pos.mixed >> l16) & 1);   // a reusable pixel holds the copied value
+        if (keep) {
+            T* px = reinterpret_cast<T*>(P.out) + ((pos.stream * P.Hout + y) * P.Wout + x) * P.Cout + chan;
+            floatx4 v[NB];
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            floatx4 v = acc[j] + bias[j];
-            if (relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
-            F::store4(px + j * 16, v);
+            for (int j = 0; j < NB; ++j) {
+                v[j] = acc[j];
+                if (relu) { v[j][0] = fmaxf(v[j][0], 0.f); v[j][1] = fmaxf(v[j][1], 0.f); v[j][2] = fmaxf(v[j][2], 0.f); v[j][3] = fmaxf(v[j][3], 0.f); }
+            }
+            if constexpr (kWide) {                          // eight bf16 channels per 16-byte store
+#pragma unroll
+                for (int j = 0; j < NB; j += 2) {
+                    uintx4 w4;
+                    w4[0] = (uint32_t)F::bits(v[j][0]) | ((uint32_t)F::bits(v[j][1]) << 16);
+                    w4[1] = (uint32_t)F::bits(v[j][2]) | ((uint32_t)F::bits(v[j][3]) << 16);
+                    w4[2] = (uint32_t)F::bits(v[j + 1][0]) | ((uint32_t)F::bits(v[j + 1][1]) << 16);
+                    w4[3] = (uint32_t)F::bits(v[j + 1][2]) | ((uint32_t)F::bits(v[j + 1][3]) << 16);
+                    *reinterpret_cast<uintx4*>(px + j * 4) = w4;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < NB; ++j) F::store4(px + j * kBlockStep, v[j]);
+            }
         }
+        pos = pos_next;
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) xv[ky] = xv_next[ky];
     }
 }
 
