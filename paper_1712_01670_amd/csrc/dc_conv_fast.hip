@@ -1,21 +1,27 @@
-// Cache-aware convolution (Section 5 "Reuse", steps 2-3), the kernel for the common layer
-// shape: 3x3 taps, stride 1, channel counts that are whole 64-byte rows, 64 output channels
-// per workgroup.  Same implicit GEMM over 4x4-pixel units as the general kernels, with
-// everything that shapes the inner loop fixed at compile time, so that the loop is straight-line
-// code: LDS reads at register + immediate addresses, no address arithmetic between MFMAs, and
-// exact wait counts between the reads of one K step and the MFMAs of the previous one.
+// Cache-aware convolution (Section 5 "Reuse", steps 2-3), the kernels for the common layer shape: 3x3 taps,
+// stride 1.  Three kernels share this file:
+//   conv_fast_kernel   channel counts that are whole 64-byte rows, 64 or 128 output channels per workgroup;
+//   conv_regw_kernel   64 input channels in bf16 and many units: persistent, weights in registers (see there);
+//   conv_first_kernel  input pixels of one 16-byte vector (the padded first layer), nothing staged (see there).
 //
-//   workgroup  = g units (g <= WM*UPW, a launch parameter) x 64 channels x a range of channel chunks
+// conv_fast_kernel is the same implicit GEMM over 4x4-pixel units as the general kernels, with everything that
+// shapes the inner loop fixed at compile time, so that the loop is straight-line code: LDS reads at register +
+// immediate addresses, no address arithmetic between MFMAs, and exact wait counts between the reads of one
+// K step and the MFMAs of the previous one.
+//
+//   workgroup  = g units (g <= WM*UPW, a launch parameter) x NT channels x a range of channel chunks
 //   wavefront  = UPW units (slots wave_m, wave_m + WM, ...) x NBW 16-channel blocks
 //   stage      = one kernel row (3 taps) x one channel chunk (KC channels)
 //
-// LDS: the patch of a unit is 6 lines of 8 row slots (6 used), one row = KC channels = RB bytes.
-// Chunk c (16 bytes) of the row at (line py, slot px) sits at chunk position c ^ sw(py, px), of weight row
-// r at c ^ (r / 2) % NVEC.  sw = (2 py + px / 4) % 4 for 64-byte rows, (py % 4) * 2 + (px % 4) / 2 for
-// 128-byte rows: these are the swizzles for which SQ_LDS_BANK_CONFLICT stays at zero for every tap (a
-// 16-byte read of a wavefront is not served 16 consecutive lanes at a time, so "16 different bank groups
-// per quarter wavefront" is not the rule; the candidates were measured).  Both buffers are filled by buffer_load ... lds, double-buffered; the patch of
-// the next chunk arrives in three parts, one per stage.
+// LDS: the patch of a unit is 6 lines of 8 row slots (6 used), one row = KC channels = RB bytes.  Chunk c
+// (16 bytes) of the row at (line py, slot px) sits at chunk position c ^ sw(py, px), of weight row r at
+// c ^ (r / 2) % NVEC.  sw = (2 py + px / 4) % 4 for 64-byte rows, (py % 4) * 2 + (px % 4) / 2 for 128-byte rows:
+// these are the swizzles for which SQ_LDS_BANK_CONFLICT stays at zero for every tap (a 16-byte read of a
+// wavefront is not served 16 consecutive lanes at a time, so "16 different bank groups per quarter wavefront"
+// is not the rule; the candidates were measured).  Both buffers are filled by buffer_load ... lds,
+// double-buffered; the patch of the next chunk arrives in three parts, one per stage.  The weights come from
+// the plain [cout][3][3][cin] layout or, when the caller has one, from the packed copy whose 1 KiB load units
+// are contiguous (launch_pack_weights).
 //
 // Few units and a deep K (the small maps at the end of a stack): the launch splits the channel
 // chunks among ks workgroups per tile, which store fp32 partial sums to scratch memory; a second

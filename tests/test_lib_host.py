@@ -61,6 +61,15 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.dc_pack_conv_weights(ok, one, 0, C.c_void_p(32), None) == -3
     assert L.dc_pack_conv_weights(big, one, 0, None, None) == -2
     assert L.dc_pack_conv_weights(big, one, 0, one, None) == -1                         # in place
+    # kernel ids of dc_stack_stats.layer_kernel_id name the instantiation a profiler shows
+    assert binding.conv_kernel_name(64) == "conv_fast_kernel<float, 3, 16, 1, 2, 4, 1>"
+    assert binding.conv_kernel_name(64 + 3 * 8 + 4) == "conv_fast_kernel<__hip_bfloat16, 3, 64, 5, 2, 4, 1>"
+    assert binding.conv_kernel_name(96 + 2) == "conv_first_kernel<float, 4>"
+    assert binding.conv_kernel_name(110 + 3) == "conv_fast_kernel<__hip_bfloat16, 3, 32, 4, 4, 2, 4>"
+    assert binding.conv_kernel_name(110 + 8 + 4) == "conv_fast_kernel<__hip_bfloat16, 3, 64, 1, 4, 2, 2>"
+    assert binding.conv_kernel_name(126) == "conv_regw_kernel<2, 2>"
+    with pytest.raises(binding.DcError):
+        binding.conv_kernel_name(127)
     # overlapping rectangles are rejected
     regs, keep = binding._alloc_regions(1, 2)
     keep[0][0] = binding.Rect(0, 0, 4, 4)
