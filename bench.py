@@ -50,7 +50,7 @@ def main():
     ap.add_argument("--expiry", type=int, default=10, help="full recompute every N frames (Section 5 default 10)")
     ap.add_argument("--matcher", choices=["es", "ds"], default="es",
                     help="Step 2 of the matching: exhaustive search, or the diamond search of Section 4")
-    ap.add_argument("--k-skip", type=int, default=1, help="search every k-th block row/column only (diamond search)")
+    ap.add_argument("--k-skip", type=int, default=1, help="search every k-th block row and column only (Section 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=10)
     args = ap.parse_args()
@@ -192,7 +192,7 @@ def main():
         "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": "configs[1]: 30-frame 224x224x3 synthetic panning video, VGG-16-style 13-conv stack, "
                                "16x16 blocks, search +/-16, tau=20",
-                   "streams": n, "matcher": "exhaustive search" if args.matcher == "es" else f"diamond search, k-skip {args.k_skip}",
+                   "streams": n, "matcher": ("exhaustive search" if args.matcher == "es" else "diamond search") + f", k-skip {args.k_skip}",
                    "cache_expiry_frames": args.expiry, "frames_per_video": n_frames,
                    "mean_block_reuse": float(np.mean(agg["reuse"])) if agg["reuse"] else 0.0,
                    "full_frame_fraction": agg["full_frames"] / max(steps_all, 1),

@@ -81,7 +81,7 @@ typedef struct {
 enum { DC_MATCH_EXHAUSTIVE = 0, DC_MATCH_DIAMOND = 1 };
 typedef struct {
     int32_t method;        /* DC_MATCH_EXHAUSTIVE (dc_match_blocks) or DC_MATCH_DIAMOND (dc_match_blocks_ds) */
-    int32_t k_skip;        /* >= 1; must be 1 for the exhaustive search */
+    int32_t k_skip;        /* >= 1: Step 2 runs only for blocks whose grid row and column are multiples of k */
 } dc_match_options;
 
 /* Work counters of one dc_run_stack call, summed over streams. */
@@ -200,6 +200,18 @@ int32_t dc_match_blocks_ds(const uint8_t* cur, const uint8_t* prev, int32_t n_st
                            int32_t k_skip, uint32_t max_block_ssd, int16_t* mv,
                            uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
                            uint8_t* block_mask, void* stream);
+
+/*
+ * Steps 1-4 with the search and the k-skip of `options` (NULL: exhaustive search, every block):
+ * dc_match_blocks and dc_match_blocks_ds in one call, plus k-skip for the exhaustive search (the
+ * acceleration of Section 4 does not depend on the search in Step 2; skipped blocks report
+ * mv = (0,0), best_ssd = 2^32 - 1 as in dc_match_blocks_ds).  Limits as for the chosen search.
+ */
+int32_t dc_match_blocks_opt(const uint8_t* cur, const uint8_t* prev, int32_t n_streams,
+                            int32_t H, int32_t W, int32_t C, int32_t block, int32_t radius,
+                            const dc_match_options* options, uint32_t max_block_ssd, int16_t* mv,
+                            uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
+                            uint8_t* block_mask, void* stream);
 
 /*
  * Section 4 Step 5 and Section 5 "Propagation" for one stream; pure host integer code.

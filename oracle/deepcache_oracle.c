@@ -149,6 +149,64 @@ void oc_match_blocks(const uint8_t* cur, const uint8_t* prev, int H, int W, int 
         }
 }
 
+/*
+ * Steps 1-4 with the exhaustive search and k-skip (Section 4, last part: the
+ * acceleration skips blocks in Step 2 whatever the search is): as
+ * oc_match_blocks, but only the blocks whose grid row and column are multiples
+ * of k are searched; Step 3 averages over those that pass; Step 4 tests every
+ * block.  Blocks that were not searched get mv = (0,0), best_ssd = UINT32_MAX.
+ */
+void oc_match_blocks_k(const uint8_t* cur, const uint8_t* prev, int H, int W, int C,
+                       int B, int R, int k, uint32_t max_ssd,
+                       int16_t* mv, uint32_t* best_ssd, int32_t* gmv, int32_t* n_pass,
+                       uint8_t* mask)
+{
+    int gh = H / B, gw = W / B;
+    int64_t sx = 0, sy = 0;
+    int K = 0;
+    for (int by = 0; by < gh; ++by)
+        for (int bx = 0; bx < gw; ++bx) {
+            int i = by * gw + bx;
+            mv[2 * i] = mv[2 * i + 1] = 0;
+            best_ssd[i] = UINT32_MAX;
+            if (by % k != 0 || bx % k != 0) continue;
+            int x = bx * B, y = by * B;
+            int have = 0, bdx = 0, bdy = 0;
+            uint32_t bs = 0;
+            for (int dy = -R; dy <= R; ++dy)
+                for (int dx = -R; dx <= R; ++dx) {
+                    if (x + dx < 0 || y + dy < 0 || x + dx + B > W || y + dy + B > H) continue;
+                    uint32_t s = block_ssd(cur, prev, W, C, B, x, y, dx, dy);
+                    int better;
+                    if (!have) better = 1;
+                    else if (s != bs) better = s < bs;
+                    else if (iabs(dx) + iabs(dy) != iabs(bdx) + iabs(bdy))
+                        better = iabs(dx) + iabs(dy) < iabs(bdx) + iabs(bdy);
+                    else if (dy != bdy) better = dy < bdy;
+                    else better = dx < bdx;
+                    if (better) { have = 1; bs = s; bdx = dx; bdy = dy; }
+                }
+            mv[2 * i] = (int16_t)bdx; mv[2 * i + 1] = (int16_t)bdy;
+            best_ssd[i] = bs;
+            if (bs <= max_ssd) { sx += bdx; sy += bdy; ++K; }
+        }
+    *n_pass = K;
+    if (K == 0) {
+        gmv[0] = gmv[1] = 0;
+        memset(mask, 0, (size_t)gh * gw);
+        return;
+    }
+    int mx = round_div(sx, K), my = round_div(sy, K);
+    gmv[0] = mx; gmv[1] = my;
+    for (int by = 0; by < gh; ++by)
+        for (int bx = 0; bx < gw; ++bx) {
+            int x = bx * B, y = by * B;
+            int ok = !(x + mx < 0 || y + my < 0 || x + mx + B > W || y + my + B > H);
+            if (ok) ok = block_ssd(cur, prev, W, C, B, x, y, mx, my) <= max_ssd;
+            mask[by * gw + bx] = (uint8_t)ok;
+        }
+}
+
 /* ------------------------------------------------------------------ */
 /* Section 4, Step 2 with diamond search, k-skip (Section 4, last part) */
 /* ------------------------------------------------------------------ */

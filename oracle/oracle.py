@@ -71,8 +71,9 @@ def rects_to_np(rects):
     return np.ascontiguousarray(np.array(rects, dtype=np.int32).reshape(-1, 4))
 
 
-def match_blocks(cur, prev, block, radius, max_ssd):
-    """Section 4, Steps 1-4.  Returns dict(mv, best_ssd, gmv, n_pass, mask)."""
+def match_blocks(cur, prev, block, radius, max_ssd, k_skip=1):
+    """Section 4, Steps 1-4 (exhaustive search; k_skip > 1: only every k-th block row and column is searched).
+    Returns dict(mv, best_ssd, gmv, n_pass, mask)."""
     H, W, Ch = cur.shape
     gh, gw = H // block, W // block
     mv = np.zeros((gh, gw, 2), np.int16)
@@ -82,8 +83,12 @@ def match_blocks(cur, prev, block, radius, max_ssd):
     mask = np.zeros((gh, gw), np.uint8)
     cur = np.ascontiguousarray(cur, np.uint8)
     prev = np.ascontiguousarray(prev, np.uint8)
-    lib().oc_match_blocks(_p(cur), _p(prev), H, W, Ch, block, radius, C.c_uint32(max_ssd),
-                          _p(mv), _p(best), _p(gmv), _p(npass), _p(mask))
+    if k_skip == 1:
+        lib().oc_match_blocks(_p(cur), _p(prev), H, W, Ch, block, radius, C.c_uint32(max_ssd),
+                              _p(mv), _p(best), _p(gmv), _p(npass), _p(mask))
+    else:
+        lib().oc_match_blocks_k(_p(cur), _p(prev), H, W, Ch, block, radius, int(k_skip), C.c_uint32(max_ssd),
+                                _p(mv), _p(best), _p(gmv), _p(npass), _p(mask))
     return dict(mv=mv, best_ssd=best, gmv=gmv, n_pass=int(npass[0]), mask=mask)
 
 
@@ -266,7 +271,7 @@ class Stream:
             if self.diamond:
                 m = match_blocks_ds(frame, self.prev_frame, self.block, self.radius, self.max_ssd, self.k_skip)
             else:
-                m = match_blocks(frame, self.prev_frame, self.block, self.radius, self.max_ssd)
+                m = match_blocks(frame, self.prev_frame, self.block, self.radius, self.max_ssd, self.k_skip)
             r0 = merge_blocks(m["mask"], self.block)
             n0, mx, my = len(r0), int(m["gmv"][0]), int(m["gmv"][1])
             self.age += 1

@@ -22,7 +22,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
           -4: "DC_ERR_UNSUPPORTED", -5: "DC_ERR_WORKSPACE", -6: "DC_ERR_CAPACITY", -7: "DC_ERR_HIP"}
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
-           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_propagate_regions", "dc_conv_workspace_bytes",
+           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_conv_workspace_bytes",
            "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
@@ -86,6 +86,7 @@ def lib():
         L.dc_conv_tile_shape.argtypes = [vp, i32, i32, i32, i32] + [C.POINTER(i32)] * 4
         L.dc_match_blocks.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
         L.dc_match_blocks_ds.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
+        L.dc_match_blocks_opt.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, u32, vp, vp, vp, vp, vp, vp]
         L.dc_propagate_regions.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, vp]
         L.dc_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
         L.dc_packed_weights_bytes.argtypes = [vp, i32, C.POINTER(sz)]
@@ -146,6 +147,25 @@ def dc_match_blocks(cur, prev, block, radius, max_block_ssd):
                mask=torch.empty((n, gh, gw), dtype=torch.uint8, device=dev))
     _check("dc_match_blocks", lib().dc_match_blocks(
         _ptr(cur), _ptr(prev), n, H, W, Ch, block, radius, max_block_ssd, _ptr(out["mv"]),
+        _ptr(out["best_ssd"]), _ptr(out["gmv"]), _ptr(out["n_pass"]), _ptr(out["mask"]), _stream()))
+    return out
+
+
+def dc_match_blocks_opt(cur, prev, block, radius, max_block_ssd, method=0, k_skip=1):
+    """Either search (method DC_MATCH_EXHAUSTIVE / DC_MATCH_DIAMOND) with k-skip; result as dc_match_blocks."""
+    assert cur.is_cuda and cur.dtype == torch.uint8 and cur.is_contiguous() and cur.dim() == 4
+    assert prev.shape == cur.shape and prev.is_cuda and prev.dtype == torch.uint8 and prev.is_contiguous()
+    n, H, W, Ch = cur.shape
+    gh, gw = H // block, W // block
+    dev = cur.device
+    out = dict(mv=torch.empty((n, gh, gw, 2), dtype=torch.int16, device=dev),
+               best_ssd=torch.empty((n, gh, gw), dtype=torch.int32, device=dev),
+               gmv=torch.empty((n, 2), dtype=torch.int32, device=dev),
+               n_pass=torch.empty((n,), dtype=torch.int32, device=dev),
+               mask=torch.empty((n, gh, gw), dtype=torch.uint8, device=dev))
+    opt = MatchOptions(int(method), int(k_skip))
+    _check("dc_match_blocks_opt", lib().dc_match_blocks_opt(
+        _ptr(cur), _ptr(prev), n, H, W, Ch, block, radius, C.byref(opt), max_block_ssd, _ptr(out["mv"]),
         _ptr(out["best_ssd"]), _ptr(out["gmv"]), _ptr(out["n_pass"]), _ptr(out["mask"]), _stream()))
     return out
 

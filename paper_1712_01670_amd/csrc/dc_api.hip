@@ -270,21 +270,42 @@ int32_t dc_conv_tile_shape(const dc_layer* layer, int32_t n_streams, int32_t Hin
     return DC_OK;
 }
 
-int32_t dc_match_blocks(const uint8_t* cur, const uint8_t* prev, int32_t n_streams, int32_t H, int32_t W,
-                        int32_t C, int32_t block, int32_t radius, uint32_t max_block_ssd, int16_t* mv,
-                        uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask,
-                        void* stream) {
+static int match_exhaustive(const uint8_t* cur, const uint8_t* prev, int32_t n_streams, int32_t H, int32_t W, int32_t C,
+                     int32_t block, int32_t radius, int32_t k_skip, uint32_t max_block_ssd, int16_t* mv,
+                     uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask, void* stream) {
     if (!cur || !prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask) return DC_ERR_NULL_PTR;
-    if (n_streams < 1 || n_streams > 65535 || H < 1 || W < 1 || C < 1 || block < 1 || radius < 0) return DC_ERR_INVALID_ARG;
+    if (n_streams < 1 || n_streams > 65535 || H < 1 || W < 1 || C < 1 || block < 1 || radius < 0 || k_skip < 1)
+        return DC_ERR_INVALID_ARG;
     if (block > H || block > W) return DC_ERR_BAD_SHAPE;
     if (radius > 127 || block * C > 256) return DC_ERR_UNSUPPORTED;
     const long rows = block + 2 * radius;
     if (rows * (rows * C + 16) > 60 * 1024) return DC_ERR_UNSUPPORTED;
     // 32-bit sums: B*B*C*255^2 must fit
     if ((double)block * block * C * 65025.0 * 2.0 > 4.0e9) return DC_ERR_UNSUPPORTED;
-    DC_TRY_HIP(launch_match(cur, prev, n_streams, H, W, C, block, radius, max_block_ssd, mv, best_ssd, global_mv,
+    DC_TRY_HIP(launch_match(cur, prev, n_streams, H, W, C, block, radius, k_skip, max_block_ssd, mv, best_ssd, global_mv,
                             n_pass, block_mask, as_stream(stream)));
     return DC_OK;
+}
+
+int32_t dc_match_blocks(const uint8_t* cur, const uint8_t* prev, int32_t n_streams, int32_t H, int32_t W,
+                        int32_t C, int32_t block, int32_t radius, uint32_t max_block_ssd, int16_t* mv,
+                        uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask,
+                        void* stream) {
+    return match_exhaustive(cur, prev, n_streams, H, W, C, block, radius, 1, max_block_ssd, mv, best_ssd, global_mv,
+                            n_pass, block_mask, stream);
+}
+
+int32_t dc_match_blocks_opt(const uint8_t* cur, const uint8_t* prev, int32_t n_streams, int32_t H, int32_t W,
+                            int32_t C, int32_t block, int32_t radius, const dc_match_options* options,
+                            uint32_t max_block_ssd, int16_t* mv, uint32_t* best_ssd, int32_t* global_mv,
+                            int32_t* n_pass, uint8_t* block_mask, void* stream) {
+    const int method = options ? options->method : DC_MATCH_EXHAUSTIVE, k = options ? options->k_skip : 1;
+    if (method == DC_MATCH_DIAMOND)
+        return dc_match_blocks_ds(cur, prev, n_streams, H, W, C, block, radius, k, max_block_ssd, mv, best_ssd, global_mv,
+                                  n_pass, block_mask, stream);
+    if (method != DC_MATCH_EXHAUSTIVE) return DC_ERR_INVALID_ARG;
+    return match_exhaustive(cur, prev, n_streams, H, W, C, block, radius, k, max_block_ssd, mv, best_ssd, global_mv,
+                            n_pass, block_mask, stream);
 }
 
 int32_t dc_match_blocks_ds(const uint8_t* cur, const uint8_t* prev, int32_t n_streams, int32_t H, int32_t W,
@@ -525,7 +546,6 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     if (match_options) {
         if (match_options->method != DC_MATCH_EXHAUSTIVE && match_options->method != DC_MATCH_DIAMOND) return DC_ERR_INVALID_ARG;
         if (match_options->k_skip < 1) return DC_ERR_INVALID_ARG;
-        if (match_options->method == DC_MATCH_EXHAUSTIVE && match_options->k_skip != 1) return DC_ERR_UNSUPPORTED;
     }
     if (cached) {
         if (!frames_prev || !tensors_prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask || !ws_dev || !ws_host)
@@ -613,12 +633,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         // With an overlap handle the matching runs on its own stream, next to whatever the main stream
         // still holds of the previous frame; only that stream is waited for.
         hipStream_t mst = ov ? ov->aux : st;
-        if (match_options && match_options->method == DC_MATCH_DIAMOND)
-            rc = dc_match_blocks_ds(frames_cur, frames_prev, n_streams, H, W, C, block, radius, match_options->k_skip,
-                                    max_block_ssd, mv, best_ssd, global_mv, n_pass, block_mask, mst);
-        else
-            rc = dc_match_blocks(frames_cur, frames_prev, n_streams, H, W, C, block, radius, max_block_ssd, mv, best_ssd,
-                                 global_mv, n_pass, block_mask, mst);
+        rc = dc_match_blocks_opt(frames_cur, frames_prev, n_streams, H, W, C, block, radius, match_options, max_block_ssd,
+                                 mv, best_ssd, global_mv, n_pass, block_mask, mst);
         if (rc) return rc;
         uint8_t* h_mask = hbase;
         int32_t* h_gmv = reinterpret_cast<int32_t*>(hbase + align_up(nb, 256));

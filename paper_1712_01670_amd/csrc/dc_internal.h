@@ -97,7 +97,7 @@ struct CopyLayerDev {
 hipError_t launch_shifted_copy_all(const RectDev* rects_dev, int n_rects, const CopyLayerDev* layers_dev,
                                    size_t max_vec_per_rect, hipStream_t st);
 hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, int H, int W, int C,
-                        int B, int R, uint32_t max_ssd, int16_t* mv, uint32_t* best_ssd,
+                        int B, int R, int k_skip, uint32_t max_ssd, int16_t* mv, uint32_t* best_ssd,
                         int32_t* gmv, int32_t* n_pass, uint8_t* mask, hipStream_t st);
 // Steps 1-4 with the diamond search in Step 2; only the blocks on every k-th grid row and column are searched.
 hipError_t launch_match_diamond(const uint8_t* cur, const uint8_t* prev, int n_streams, int H, int W, int C, int B,

@@ -59,11 +59,13 @@ __device__ __forceinline__ int wave_sum_i32(int v) {
 template <bool ALIGNED, int CDW>
 __global__ __launch_bounds__(kSearchThreads) void match_search_kernel(
     const uint8_t* __restrict__ cur, const uint8_t* __restrict__ prev, int H, int W, int C, int B,
-    int R, int gw, int gh, int ws, int cs, int16_t* __restrict__ mv, uint32_t* __restrict__ best_ssd) {
+    int R, int gw, int gh, int ws, int cs, int k_skip, int16_t* __restrict__ mv, uint32_t* __restrict__ best_ssd) {
     extern __shared__ __align__(16) uint8_t lds[];
     const int tid = threadIdx.x;
-    const int blk_id = blockIdx.x, stream = blockIdx.y;
-    const int bx = blk_id % gw, by = blk_id / gw;
+    // k-skip: the grid covers only the blocks on every k-th grid row and column
+    const int lgw = (gw + k_skip - 1) / k_skip;
+    const int bx = ((int)blockIdx.x % lgw) * k_skip, by = ((int)blockIdx.x / lgw) * k_skip;
+    const int blk_id = by * gw + bx, stream = blockIdx.y;
     const int x0 = bx * B, y0 = by * B;
     const int rows = B + 2 * R;
     const int row_bytes = W * C;
@@ -201,12 +203,14 @@ constexpr int kMfmaThreads = 64 * kMfmaWaves;
 template <bool ALIGNED, int NT, int KS, int BT, int CT>
 __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
     const uint8_t* __restrict__ cur, const uint8_t* __restrict__ prev, int H, int W, int C_rt, int B_rt,
-    int R, int gw, int gh, int ws, int16_t* __restrict__ mv, uint32_t* __restrict__ best_ssd) {
+    int R, int gw, int gh, int ws, int k_skip, int16_t* __restrict__ mv, uint32_t* __restrict__ best_ssd) {
     const int B = BT ? BT : B_rt, C = CT ? CT : C_rt;
     extern __shared__ __align__(16) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int blk_id = blockIdx.x, stream = blockIdx.y;
-    const int bx = blk_id % gw, by = blk_id / gw;
+    // k-skip: the grid covers only the blocks on every k-th grid row and column
+    const int lgw = (gw + k_skip - 1) / k_skip;
+    const int bx = ((int)blockIdx.x % lgw) * k_skip, by = ((int)blockIdx.x / lgw) * k_skip;
+    const int blk_id = by * gw + bx, stream = blockIdx.y;
     const int x0 = bx * B, y0 = by * B;
     const int rows = B + 2 * R, cols = rows, nd = 2 * R + 1;
     const int row_bytes = W * C;
@@ -408,14 +412,13 @@ __device__ __forceinline__ int round_half_away(int num, int den) {
 // One wavefront per block: Step 3 (redundantly per workgroup) then Step 4 for this block.
 __global__ __launch_bounds__(64) void motion_retest_kernel(
     const uint8_t* __restrict__ cur, const uint8_t* __restrict__ prev, int H, int W, int C, int B,
-    int gw, int gh, uint32_t max_ssd, const int16_t* __restrict__ mv,
-    const uint32_t* __restrict__ best_ssd, int32_t* __restrict__ gmv, int32_t* __restrict__ n_pass,
-    uint8_t* __restrict__ mask, int k_skip) {
+    int gw, int gh, uint32_t max_ssd, int16_t* mv, uint32_t* best_ssd, int32_t* __restrict__ gmv,
+    int32_t* __restrict__ n_pass, uint8_t* __restrict__ mask, int k_skip) {
     const int lane = threadIdx.x;
     const int blk_id = blockIdx.x, stream = blockIdx.y;
     const int nb = gh * gw;
-    const int16_t* smv = mv + (size_t)stream * nb * 2;
-    const uint32_t* sbest = best_ssd + (size_t)stream * nb;
+    int16_t* smv = mv + (size_t)stream * nb * 2;
+    uint32_t* sbest = best_ssd + (size_t)stream * nb;
     int sx = 0, sy = 0, K = 0;
     for (int base = 0; base < nb; base += 4 * 64) {     // four independent loads per lane at a time
         uint32_t bs[4];
@@ -453,6 +456,11 @@ __global__ __launch_bounds__(64) void motion_retest_kernel(
         n_pass[stream] = K;
     }
     const int bx = blk_id % gw, by = blk_id / gw;
+    if (k_skip > 1 && (bx % k_skip != 0 || by % k_skip != 0) && lane == 0) {
+        // not searched: no vector (nobody reads these entries, the mean above skips them)
+        smv[2 * blk_id] = 0; smv[2 * blk_id + 1] = 0;
+        sbest[blk_id] = 0xffffffffu;
+    }
     const int x0 = bx * B, y0 = by * B;
     bool inside = K > 0 && x0 + mx >= 0 && y0 + my >= 0 && x0 + mx + B <= W && y0 + my + B <= H;
     uint32_t ssd = 0;
@@ -648,12 +656,12 @@ __global__ __launch_bounds__(256) void match_diamond_kernel(
 }  // namespace
 
 hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, int H, int W, int C,
-                        int B, int R, uint32_t max_ssd, int16_t* mv, uint32_t* best_ssd,
+                        int B, int R, int k_skip, uint32_t max_ssd, int16_t* mv, uint32_t* best_ssd,
                         int32_t* gmv, int32_t* n_pass, uint8_t* mask, hipStream_t st) {
     const int gh = H / B, gw = W / B;
     const int rows = B + 2 * R;
     const bool aligned = ((reinterpret_cast<uintptr_t>(prev) & 3) == 0) && ((W * C) % 4 == 0);
-    dim3 grid(gh * gw, n_streams);
+    dim3 grid(((gw + k_skip - 1) / k_skip) * ((gh + k_skip - 1) / k_skip), n_streams);   // the searched blocks
     static int use_mfma = -1;
     if (use_mfma < 0) { const char* e = getenv("DC_MATCH_MFMA"); use_mfma = e ? atoi(e) : 1; }
     const int nt = (2 * R + 1 + 15) / 16, ksteps = (B * C + 63) / 64;
@@ -667,7 +675,7 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
         if (ldsm <= 64 * 1024) {
 #define DC_MFMA_LAUNCH(AL, NTT, KSS, BT, CT)                                                                          \
     hipLaunchKernelGGL((match_mfma_kernel<AL, NTT, KSS, BT, CT>), grid, dim3(kMfmaThreads), ldsm, st, cur, prev, H, W, C, \
-                       B, R, gw, gh, wsm, mv, best_ssd)
+                       B, R, gw, gh, wsm, k_skip, mv, best_ssd)
 #define DC_MFMA_KS(AL, NTT)                            \
     do {                                               \
         if (ksteps == 1) DC_MFMA_LAUNCH(AL, NTT, 1, 0, 0); \
@@ -694,7 +702,7 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
     const size_t lds = (size_t)rows * ws + (size_t)B * cs;
 #define DC_MATCH_LAUNCH(AL, CD)                                                                                      \
     hipLaunchKernelGGL((match_search_kernel<AL, CD>), grid, dim3(kSearchThreads), lds, st, cur, prev, H, W, C, B, R, \
-                       gw, gh, ws, cs, mv, best_ssd)
+                       gw, gh, ws, cs, k_skip, mv, best_ssd)
 #define DC_MATCH_ALIGN(CD)             \
     do {                               \
         if (aligned) DC_MATCH_LAUNCH(true, CD); \
@@ -711,8 +719,8 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
 #undef DC_MATCH_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(motion_retest_kernel, grid, dim3(64), 0, st, cur, prev, H, W, C, B, gw, gh,
-                       max_ssd, mv, best_ssd, gmv, n_pass, mask, 1);
+    hipLaunchKernelGGL(motion_retest_kernel, dim3(gh * gw, n_streams), dim3(64), 0, st, cur, prev, H, W, C, B, gw, gh,
+                       max_ssd, mv, best_ssd, gmv, n_pass, mask, k_skip);
     return hipGetLastError();
 }
 

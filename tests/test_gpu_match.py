@@ -82,3 +82,30 @@ def test_darknet_geometry_sampled(oracle):
     # full-size 416x416 frame pair; the oracle checks everything (676 blocks, a few seconds)
     fr = synth.reuse_sweep_video(4002, 0.5, n_frames=2)
     _compare(oracle, fr[1:2], fr[0:1], 16, 16, synth.max_block_ssd(16), "sweep 416")
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_k_skip(oracle, k):
+    """Exhaustive search on every k-th block row and column only (the acceleration at the end of Section 4)."""
+    dev = torch.device("cuda:0")
+    fr = synth.panning_video(2000, n_frames=4)
+    cases = [(fr[1:4], fr[0:3], 16, 16, synth.max_block_ssd(16))]
+    rng = np.random.default_rng(k)
+    prev = synth._box_blur5(rng.integers(0, 256, (1, 50, 70, 3)).astype(np.uint8).reshape(50, 70, 3))[None]
+    cur = np.roll(prev, (2, -3), axis=(1, 2))
+    cases.append((cur, prev, 10, 7, 30 * 300))
+    cases.append((cur, prev, 10, 7, 2 ** 32 - 1))          # the bound does not make skipped blocks count
+    for cur, prev, B, R, thr in cases:
+        print(f"[match k-skip] k={k} shape={cur.shape} B={B} R={R} thr={thr}", flush=True)
+        out = binding.dc_match_blocks_opt(torch.from_numpy(np.ascontiguousarray(cur)).to(dev),
+                                          torch.from_numpy(np.ascontiguousarray(prev)).to(dev), B, R, thr,
+                                          method=binding.DC_MATCH_EXHAUSTIVE, k_skip=k)
+        torch.cuda.synchronize()
+        got = {key: v.cpu().numpy() for key, v in out.items()}
+        for s in range(cur.shape[0]):
+            want = oracle.match_blocks(cur[s], prev[s], B, R, thr, k_skip=k)
+            assert np.array_equal(got["best_ssd"][s].view(np.uint32), want["best_ssd"])
+            assert np.array_equal(got["mv"][s], want["mv"])
+            assert got["gmv"][s].tolist() == want["gmv"].tolist()
+            assert int(got["n_pass"][s]) == want["n_pass"]
+            assert np.array_equal(got["mask"][s], want["mask"])

@@ -113,14 +113,9 @@ def test_diamond_search_in_the_whole_path(oracle, k_skip):
     assert max(reuse) > 0.3
 
 
-def test_exhaustive_search_rejects_k_skip():
-    layers = synth.tiny_net()
-    ws, bs = synth.he_weights(layers, 1)
+def test_exhaustive_search_with_k_skip_in_the_whole_path(oracle):
     f1, f2 = synth.tiny_pair(0)
-    r = binding.StackRunner(layers, ws, bs, 1, 64, 64, 3, block=8, radius=8, k_skip=2)
-    with pytest.raises(binding.DcError) as e:
-        r.step(torch.from_numpy(f1[None]).to(DEV))
-    assert e.value.status == -4
+    _run_both(oracle, synth.tiny_net(), np.stack([f1, f2, f2, f1])[None], 8, 8, False, k_skip=2)
 
 
 def test_vgg16_two_streams_bf16_small(oracle):

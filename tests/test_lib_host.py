@@ -44,6 +44,11 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.dc_match_blocks_ds(one, one, 1, 64, 64, 3, 128, 8, 1, 0, one, one, one, one, one, None) == -3  # block > frame
     assert L.dc_match_blocks_ds(one, one, 1, 64, 64, 3, 8, 20000, 1, 0, one, one, one, one, one, None) == -4
     assert L.dc_match_blocks_ds(one, one, 1, 4096, 4096, 4, 200, 8, 1, 0, one, one, one, one, one, None) == -4  # 32-bit sums
+    opt = binding.MatchOptions(7, 1)
+    assert L.dc_match_blocks_opt(one, one, 1, 64, 64, 3, 8, 8, C.byref(opt), 0, one, one, one, one, one, None) == -1    # method
+    opt = binding.MatchOptions(0, 0)
+    assert L.dc_match_blocks_opt(one, one, 1, 64, 64, 3, 8, 8, C.byref(opt), 0, one, one, one, one, one, None) == -1    # k_skip
+    assert L.dc_match_blocks_opt(None, one, 1, 64, 64, 3, 8, 8, None, 0, one, one, one, one, one, None) == -2
     bad = binding.layers_to_c([dict(type=0, k=3, s=0, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
     assert L.dc_cached_conv_layer(bad, one, one, None, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -1
     ok = binding.layers_to_c([dict(type=0, k=3, s=1, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])

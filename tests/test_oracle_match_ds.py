@@ -166,3 +166,29 @@ def test_k_skip(oracle):
     # a bound of 2^32-1 does not make the skipped blocks count
     m = oracle.match_blocks_ds(f2, f1, 8, 8, INVALID, k_skip=2)
     assert m["n_pass"] == 5 * 6
+
+
+def test_k_skip_with_exhaustive_search(oracle):
+    # the same bookkeeping with the exhaustive search in Step 2 (the acceleration does not depend on the search)
+    rng = np.random.default_rng(9)
+    f1, f2 = _moved(8, 72, 88, (-2, 3))
+    f2 = f2.copy()
+    f2[40:56, 16:40] = rng.integers(0, 256, (16, 24, 3))
+    full = oracle.match_blocks(f2, f1, 8, 6, 300)
+    assert np.array_equal(oracle.match_blocks(f2, f1, 8, 6, 300, k_skip=1)["mv"], full["mv"])
+    for k in (2, 4):
+        m = oracle.match_blocks(f2, f1, 8, 6, 300, k_skip=k)
+        searched = np.zeros((9, 11), bool)
+        searched[::k, ::k] = True
+        assert np.array_equal(m["mv"][searched], full["mv"][searched])
+        assert np.array_equal(m["best_ssd"][searched], full["best_ssd"][searched])
+        assert not m["mv"][~searched].any() and (m["best_ssd"][~searched] == INVALID).all()
+        ok = searched & (m["best_ssd"] <= 300)
+        assert m["n_pass"] == int(ok.sum()) > 0
+        mx = _round_half_away(Fraction(int(m["mv"][..., 0][ok].sum()), int(ok.sum())))
+        my = _round_half_away(Fraction(int(m["mv"][..., 1][ok].sum()), int(ok.sum())))
+        assert m["gmv"].tolist() == [mx, my] == [2, -3]
+        for by in range(9):
+            for bx in range(11):
+                tab = _np_ssd_table(f2, f1, 8, 6, bx, by)
+                assert m["mask"][by, bx] == int((mx, my) in tab and tab[(mx, my)] <= 300)
