@@ -161,6 +161,24 @@ def test_fast_conv_kernel_shapes(oracle, case, bf16, cached):
         assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
 
 
+def test_register_weight_kernel_without_relu_and_bias(oracle):
+    """The persistent bf16 kernel for 64 input channels: negative outputs survive when the layer has no ReLU,
+    and a missing bias is zero."""
+    H, W, cin, cout = 26, 34, 64, 64
+    rng = np.random.default_rng(5)
+    x = oracle.round_bf16(rng.standard_normal((3, H, W, cin)).astype(np.float32))
+    w = oracle.round_bf16((rng.standard_normal((cout, 3, 3, cin)) * np.sqrt(2.0 / (cin * 9))).astype(np.float32))
+    binding.dc_conv_tuning(3, -1, -1, -1)
+    try:
+        got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, 3, 1, 1, False), _to_dev(x, True), _to_dev(w, True), None))
+    finally:
+        binding.dc_conv_tuning()
+    assert (got < 0).mean() > 0.3
+    for i in range(3):
+        want = oracle.conv_cached(x[i], w, None, 3, 1, 1, False, bf16=True)
+        assert _rel_err(got[i], want) <= 2e-2
+
+
 @pytest.mark.parametrize("cached", [False, True])
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("cout", [16, 32, 64, 128])
