@@ -754,9 +754,11 @@ inline int geom_nt(int geom) { return kGeom[geom].wn * kGeom[geom].nbw * 16; }
 template <typename T, int KC, int U, int WM, int WN, int NBW>
 hipError_t fast_launch_one(dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
     auto fn = conv_fast_kernel<T, 3, KC, U, WM, WN, NBW>;
-    if (lds > 64 * 1024) {
+    static size_t allowed = 64 * 1024;      // per instantiation: the attribute is raised once, not per launch
+    if (lds > allowed) {
         hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (a != hipSuccess) return a;
+        allowed = lds;
     }
     hipLaunchKernelGGL((conv_fast_kernel<T, 3, KC, U, WM, WN, NBW>), grid, dim3(WM * WN * 64), lds, st, P);
     return hipGetLastError();
@@ -938,10 +940,12 @@ hipError_t launch_pack_weights(const void* w, void* packed, int cin, int cout, i
 template <int WM, int UPW>
 hipError_t regw_launch(dim3 grid, hipStream_t st, const ConvParams& P) {
     const size_t lds = 2 * (size_t)(WM * UPW) * 48 * 128;
-    if (lds > 64 * 1024) {
+    static size_t allowed = 64 * 1024;
+    if (lds > allowed) {
         hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_regw_kernel<WM, UPW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (a != hipSuccess) return a;
+        allowed = lds;
     }
     hipLaunchKernelGGL((conv_regw_kernel<WM, UPW>), grid, dim3(WM * 128), lds, st, P);
     return hipGetLastError();
@@ -1008,7 +1012,20 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     }
     size_t scratch = c.scratch && reinterpret_cast<uintptr_t>(c.scratch) % 16 == 0 ? c.scratch_bytes : 0;
     if (scratch > kConvScratchBytes) scratch = kConvScratchBytes;
-    FastChoice ch = choose_fast(c, n_units, scratch);
+    // The model costs about 2 us per call on the host; the same layers come back every frame with the same or a
+    // recently seen unit count, so its answers are kept in a small direct-mapped table.
+    struct Memo { int dtype, cin, cout, tune[4]; long n_units; size_t scratch; FastChoice ch; bool used; };
+    static Memo memo[256];
+    Memo& slot = memo[((unsigned long)n_units * 2654435761ul + (unsigned)c.Cin * 40503u + (unsigned)c.Cout * 97u + (unsigned)c.dtype) % 256];
+    FastChoice ch;
+    if (slot.used && slot.dtype == c.dtype && slot.cin == c.Cin && slot.cout == c.Cout && slot.n_units == n_units &&
+        slot.scratch == scratch && slot.tune[0] == g_tune[0] && slot.tune[1] == g_tune[1] && slot.tune[2] == g_tune[2] &&
+        slot.tune[3] == g_tune[3]) {
+        ch = slot.ch;
+    } else {
+        ch = choose_fast(c, n_units, scratch);
+        slot = Memo{c.dtype, c.Cin, c.Cout, {g_tune[0], g_tune[1], g_tune[2], g_tune[3]}, n_units, scratch, ch, true};
+    }
     if (g_tune[1] > 0 && ch.g > 0) {    // forced shape within the arrangement the model picked
         const int f_g = g_tune[1], f_ks = g_tune[2], f_kci = g_tune[3] < 0 ? ch.kci : g_tune[3];
         const Geom& G = kGeom[ch.geom];

@@ -150,7 +150,8 @@ void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Ho
     // tiles are 4x4 pixels: the reusable pixels of a tile are one 16-bit mask
     (void)th; (void)tw;
     const int tiles_y = (Hout + 3) / 4, tiles_x = (Wout + 3) / 4;
-    std::vector<uint16_t> reuse((size_t)tiles_y * tiles_x, 0);
+    static thread_local std::vector<uint16_t> reuse;          // kept between calls: no allocation per layer and frame
+    reuse.assign((size_t)tiles_y * tiles_x, 0);
     RangeDev range{(int)plan.rects.size(), 0};
     for (int i = 0; i < n; ++i) {
         const dc_rect& r = rects[i];
@@ -170,6 +171,7 @@ void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Ho
         }
     }
     plan.ranges.push_back(range);
+    plan.tiles.reserve(plan.tiles.size() + (size_t)tiles_y * tiles_x);
     for (int ty = 0; ty < tiles_y; ++ty)
         for (int tx = 0; tx < tiles_x; ++tx) {
             unsigned inside = 0;                                 // pixels of the tile that lie in the map
