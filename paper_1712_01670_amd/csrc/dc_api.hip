@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "dc_internal.h"
@@ -56,7 +57,7 @@ PlanAddr pack_plan(const LayerPlan& plan, unsigned char* host, unsigned char* de
     PlanAddr a;
     a.tiles = reinterpret_cast<const TileDev*>(dev + off);
     if (!plan.tiles.empty()) std::memcpy(host + off, plan.tiles.data(), plan.tiles.size() * sizeof(TileDev));
-    off += align_up(plan.tiles.size() * sizeof(TileDev), 256);
+    off += align_up(plan.n_tiles * sizeof(TileDev), 256);       // the caller may fill the tile list itself
     a.rects = reinterpret_cast<const RectDev*>(dev + off);
     if (!plan.rects.empty()) std::memcpy(host + off, plan.rects.data(), plan.rects.size() * sizeof(RectDev));
     off += align_up(plan.rects.size() * sizeof(RectDev), 256);
@@ -135,9 +136,9 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
         DC_TRY_HIP(launch_shifted_copy(addr->rects, (int)plan->rects.size(), mw, mh, cache_prev, out, Hout, Wout,
                                        l.cout, dtype, st));
     }
-    if (!plan->tiles.empty()) {
+    if (plan->n_tiles) {
         Bracket b(prof, gemm_slot, st);
-        c.tiles = addr->tiles; c.n_tiles = (int)plan->tiles.size(); c.rects = addr->rects; c.ranges = addr->ranges;
+        c.tiles = addr->tiles; c.n_tiles = (int)plan->n_tiles; c.rects = addr->rects; c.ranges = addr->ranges;
         DC_TRY_HIP(launch_conv(c, st));
     }
     return DC_OK;
@@ -430,6 +431,7 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
     } catch (const std::bad_alloc&) {
         return DC_ERR_WORKSPACE;
     }
+    plan.n_tiles = plan.tiles.size();
     PlanAddr addr = pack_plan(plan, static_cast<unsigned char*>(ws_host), static_cast<unsigned char*>(ws_dev));
     DC_TRY_HIP(hipMemcpyAsync(ws_dev, ws_host, addr.bytes, hipMemcpyHostToDevice, st));
     // whatever the workspace holds beyond the plan serves as scratch for partial sums
@@ -496,10 +498,86 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
 }
 
 namespace {
+// Planning of one frame for dc_run_stack: per (stream, conv layer) lists built in parallel, merged by offset.
+struct FramePlan {
+    std::vector<int> conv_layers;          // layer indices
+    std::vector<LayerPlan> part;           // [stream][conv layer], storage kept between frames
+    std::vector<size_t> tile_off;          // [stream][conv layer]: first tile of the part in the layer's list
+    std::vector<unsigned char*> tile_dst;  // [conv layer]: the layer's tile list in the staging buffer
+    int n_streams = 0;
+
+    int classify(const dc_layer* layers, int n_layers, int streams, const std::vector<std::vector<TensorRegions>>& regs,
+                 const std::vector<int>& hs, const std::vector<int>& ws) {
+        n_streams = streams;
+        conv_layers.clear();
+        for (int i = 0; i < n_layers; ++i)
+            if (layers[i].type == DC_CONV) conv_layers.push_back(i);
+        const int nc = (int)conv_layers.size();
+        std::vector<int> ok(streams, 1);
+        try {
+            if (part.size() < (size_t)streams * nc) part.resize((size_t)streams * nc);
+            tile_off.assign((size_t)streams * nc, 0);
+            tile_dst.assign(nc, nullptr);
+        } catch (const std::bad_alloc&) {
+            return DC_ERR_WORKSPACE;
+        }
+        parallel_for(streams, [&](int s) {
+            try {
+                for (int c = 0; c < nc; ++c) {
+                    const int i = conv_layers[c];
+                    LayerPlan& lp = part[(size_t)s * nc + c];
+                    lp.rects.clear(); lp.ranges.clear(); lp.tiles.clear(); lp.reused_px = 0;
+                    const TensorRegions& g = regs[s][i + 1];
+                    plan_stream(g.rects.data(), (int)g.rects.size(), g.dx, g.dy, s, hs[i + 1], ws[i + 1], 4, 4, lp);
+                }
+            } catch (const std::bad_alloc&) {
+                ok[s] = 0;
+            }
+        });
+        for (int s = 0; s < streams; ++s)
+            if (!ok[s]) return DC_ERR_WORKSPACE;
+        return DC_OK;
+    }
+    // Lays layer i out in the staging buffer ([tiles][rects][ranges], as pack_plan), fills the small tables and
+    // notes where each stream's tiles go.
+    PlanAddr finish_layer(int layer, LayerPlan& plan, unsigned char* host, unsigned char* dev) {
+        const int nc = (int)conv_layers.size();
+        int c = 0;
+        while (conv_layers[c] != layer) ++c;
+        size_t n_tiles = 0;
+        for (int s = 0; s < n_streams; ++s) {
+            LayerPlan& lp = part[(size_t)s * nc + c];
+            tile_off[(size_t)s * nc + c] = n_tiles;
+            n_tiles += lp.tiles.size();
+            RangeDev r{(int)plan.rects.size(), (int)lp.rects.size()};
+            plan.rects.insert(plan.rects.end(), lp.rects.begin(), lp.rects.end());
+            plan.ranges.push_back(r);
+            plan.reused_px += lp.reused_px;
+        }
+        plan.n_tiles = n_tiles;
+        tile_dst[c] = host;
+        PlanAddr a = pack_plan(plan, host, dev);        // plan.tiles is empty: copies rects and ranges, sizes from n_tiles
+        return a;
+    }
+    void copy_tiles() {
+        const int nc = (int)conv_layers.size();
+        parallel_for(n_streams, [&](int s) {
+            for (int c = 0; c < nc; ++c) {
+                const LayerPlan& lp = part[(size_t)s * nc + c];
+                if (!lp.tiles.empty())
+                    std::memcpy(tile_dst[c] + tile_off[(size_t)s * nc + c] * sizeof(TileDev), lp.tiles.data(),
+                                lp.tiles.size() * sizeof(TileDev));
+            }
+        });
+    }
+};
+FramePlan g_frame_plan;
+std::mutex g_frame_plan_mutex;
+
 // DC_HOST_TIMING=1: host time of a cached dc_run_stack call by phase, printed every 200 calls (experiments).
 struct HostTiming {
     bool on = false;
-    double acc[6] = {0, 0, 0, 0, 0, 0};
+    double acc[7] = {0, 0, 0, 0, 0, 0, 0};
     long calls = 0;
     std::chrono::steady_clock::time_point last;
     HostTiming() { const char* e = getenv("DC_HOST_TIMING"); on = e && atoi(e) != 0; }
@@ -512,9 +590,10 @@ struct HostTiming {
     }
     void end_call() {
         if (!on || ++calls % 200) return;
-        fprintf(stderr, "[dc_run_stack host us/call] launch match %.1f | wait match %.1f | merge+propagate %.1f | plans %.1f | "
-                        "copy tables+upload %.1f | layer launches %.1f\n",
-                acc[0] / 200, acc[1] / 200, acc[2] / 200, acc[3] / 200, acc[4] / 200, acc[5] / 200);
+        fprintf(stderr, "[dc_run_stack host us/call] launch match %.1f | wait match %.1f | merge+propagate %.1f | "
+                        "wait for the staging half (GPU two frames back) %.1f | plans %.1f | copy tables+upload %.1f | "
+                        "layer launches %.1f\n",
+                acc[0] / 200, acc[1] / 200, acc[2] / 200, acc[6] / 200, acc[3] / 200, acc[4] / 200, acc[5] / 200);
         for (double& a : acc) a = 0;
     }
 };
@@ -653,18 +732,31 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         g_host_timing.mark(1);
         try {
             regs.resize(n_streams);
-            std::vector<dc_rect> rects0;
-            for (int s = 0; s < n_streams; ++s) {
-                const uint8_t* m = h_mask + (size_t)s * gh * gw;
-                for (int i = 0; i < gh * gw; ++i) local.n_reusable_blocks += m[i] ? 1 : 0;
-                merge_blocks(m, gh, gw, block, rects0);
-                rc = propagate(layers, n_layers, H, W, rects0, h_gmv[2 * s], h_gmv[2 * s + 1], regs[s]);
-                if (rc) return rc;
-                for (int t = 0; t <= n_layers; ++t)
-                    if ((int)regs[s][t].rects.size() > max_rects) return DC_ERR_CAPACITY;
-            }
         } catch (const std::bad_alloc&) {
             return DC_ERR_WORKSPACE;
+        }
+        {   // per stream: count, merge (Step 5), propagate (Section 5); streams are independent
+            std::vector<int> stream_rc(n_streams, DC_OK), stream_reusable(n_streams, 0);
+            parallel_for(n_streams, [&](int s) {
+                try {
+                    std::vector<dc_rect> rects0;
+                    const uint8_t* m = h_mask + (size_t)s * gh * gw;
+                    int cnt = 0;
+                    for (int i = 0; i < gh * gw; ++i) cnt += m[i] ? 1 : 0;
+                    stream_reusable[s] = cnt;
+                    merge_blocks(m, gh, gw, block, rects0);
+                    int r = propagate(layers, n_layers, H, W, rects0, h_gmv[2 * s], h_gmv[2 * s + 1], regs[s]);
+                    for (int t = 0; r == DC_OK && t <= n_layers; ++t)
+                        if ((int)regs[s][t].rects.size() > max_rects) r = DC_ERR_CAPACITY;
+                    stream_rc[s] = r;
+                } catch (const std::bad_alloc&) {
+                    stream_rc[s] = DC_ERR_WORKSPACE;
+                }
+            });
+            for (int s = 0; s < n_streams; ++s) {
+                if (stream_rc[s]) return stream_rc[s];
+                local.n_reusable_blocks += stream_reusable[s];
+            }
         }
         g_host_timing.mark(2);
         hbase += align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
@@ -677,6 +769,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 ov->pending[ov->parity] = false;
             }
         }
+        g_host_timing.mark(6);
     } else {
         DC_TRY_HIP(wait_prev(last_reader[0]));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
@@ -704,6 +797,16 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     std::vector<PlanAddr> addrs(n_layers);
     std::vector<ConvTiling> tilings(n_layers);
     size_t off = 0;
+    // The tiles of every (stream, conv layer) are classified in parallel over the streams into per-stream lists,
+    // the per-layer offsets follow from their sizes, and the lists are then copied straight into the pinned
+    // staging buffer, again in parallel (64 streams: 550 k tiles per frame).
+    std::lock_guard<std::mutex> plan_guard(g_frame_plan_mutex);
+    FramePlan& frame_plan = g_frame_plan;
+    if (cached) {
+        int rc_plan = frame_plan.classify(layers, n_layers, n_streams, regs, hs, ws);
+        if (rc_plan) return rc_plan;
+    }
+
     try {
         for (int i = 0; i < n_layers; ++i) {
             const dc_layer& l = layers[i];
@@ -723,14 +826,9 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 continue;
             }
             LayerPlan& plan = plans[i];
-            for (int s = 0; s < n_streams; ++s) {
-                const TensorRegions& g = regs[s][i + 1];
-                plan_stream(g.rects.data(), (int)g.rects.size(), g.dx, g.dy, s, hs[i + 1], ws[i + 1], tilings[i].th,
-                            tilings[i].tw, plan);
-            }
-            addrs[i] = pack_plan(plan, hbase + off, plan_dev + off);
+            addrs[i] = frame_plan.finish_layer(i, plan, hbase + off, plan_dev + off);
             off += addrs[i].bytes;
-            int64_t issued = (int64_t)plan.tiles.size() * tilings[i].th * tilings[i].tw * mac_px;
+            int64_t issued = (int64_t)plan.n_tiles * tilings[i].th * tilings[i].tw * mac_px;
             local.macs_needed += (px - plan.reused_px) * mac_px;
             local.macs_issued += issued;
             local.copy_bytes += 2 * plan.reused_px * l.cout * (int64_t)dtype_size(dtype);
@@ -740,6 +838,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     } catch (const std::bad_alloc&) {
         return DC_ERR_WORKSPACE;
     }
+    if (cached) frame_plan.copy_tiles();
     if (cached) g_host_timing.mark(3);
     // ---- the shifted copies of all layers in one launch (16-byte vector path only); pipelined: one launch per
     // run of consecutive conv layers, issued when the previous frame has finished that run ----

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <functional>
 #include <vector>
 
 #include "deepcache.h"
@@ -48,9 +49,13 @@ int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C,
 struct LayerPlan {
     std::vector<RectDev> rects;    // all streams
     std::vector<RangeDev> ranges;  // [n_streams]
-    std::vector<TileDev> tiles;    // dirty tiles, all streams
+    std::vector<TileDev> tiles;    // dirty tiles, all streams (empty when they were written to the staging buffer directly)
+    size_t n_tiles = 0;            // number of dirty tiles, all streams
     int64_t reused_px = 0;
 };
+// Runs fn(0) .. fn(n-1) on the calling thread and a small pool of host threads (created on first use, at most
+// 16 in all); returns when all are done.  Calls from several threads are serialised.  n < 4 runs inline.
+void parallel_for(int n, const std::function<void(int)>& fn);
 // Classify the tiles of one stream's output map against its rectangles and append.
 void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Hout, int Wout,
                  int th, int tw, LayerPlan& plan);

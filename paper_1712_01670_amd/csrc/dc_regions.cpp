@@ -2,6 +2,10 @@
 // propagating rectangles through the layer table (Section 5, Table 2) and sorting the
 // output tiles of a conv layer into clean / mixed / dirty for the GEMM tile list.
 #include <algorithm>
+#include <atomic>
+#include <condition_variable>
+#include <mutex>
+#include <thread>
 
 #include "dc_internal.h"
 
@@ -171,7 +175,6 @@ void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Ho
         }
     }
     plan.ranges.push_back(range);
-    plan.tiles.reserve(plan.tiles.size() + (size_t)tiles_y * tiles_x);
     for (int ty = 0; ty < tiles_y; ++ty)
         for (int tx = 0; tx < tiles_x; ++tx) {
             unsigned inside = 0;                                 // pixels of the tile that lie in the map
@@ -181,6 +184,93 @@ void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Ho
             if ((m & inside) == inside) continue;  // every pixel is served by the copy
             plan.tiles.push_back(TileDev{stream, ty, tx, (int32_t)m});
         }
+}
+
+
+// ---- host thread pool for the per-stream planning of many streams ----------------------------
+namespace {
+class Pool {
+public:
+    void run(int n, const std::function<void(int)>& fn) {
+        std::lock_guard<std::mutex> serial(callers_);
+        start_workers();
+        unsigned long gen;
+        {
+            std::lock_guard<std::mutex> g(m_);
+            gen = ++generation_;
+            fn_ = &fn; n_ = n;
+            pending_.store(n);
+            ticket_.store((unsigned long long)gen << 32);      // (generation, next index): published last
+        }
+        work_.notify_all();
+        drain(gen, &fn, n);                                    // the caller works too
+        std::unique_lock<std::mutex> g(m_);
+        done_.wait(g, [&] { return pending_.load() == 0; });
+    }
+    ~Pool() {
+        {
+            std::lock_guard<std::mutex> g(m_);
+            stop_ = true;
+        }
+        work_.notify_all();
+        for (std::thread& t : threads_) t.join();
+    }
+
+private:
+    void start_workers() {
+        if (!threads_.empty()) return;
+        unsigned hw = std::thread::hardware_concurrency();
+        int want = (int)(hw ? hw : 4);
+        if (want > 16) want = 16;
+        for (int i = 1; i < want; ++i) threads_.emplace_back([this] { worker(); });
+    }
+    // Takes indices of generation `gen` until none is left.  The ticket carries the generation, so a thread that
+    // wakes up late (its generation is over, another one may have started) takes nothing and calls nothing.
+    void drain(unsigned long gen, const std::function<void(int)>* fn, int n) {
+        for (;;) {
+            unsigned long long t = ticket_.load();
+            if ((unsigned long)(t >> 32) != (gen & 0xfffffffful) || (int)(t & 0xffffffffull) >= n) return;
+            if (!ticket_.compare_exchange_weak(t, t + 1)) continue;
+            (*fn)((int)(t & 0xffffffffull));
+            if (pending_.fetch_sub(1) == 1) {
+                std::lock_guard<std::mutex> g(m_);
+                done_.notify_all();
+            }
+        }
+    }
+    void worker() {
+        unsigned long seen = 0;
+        for (;;) {
+            const std::function<void(int)>* fn;
+            int n;
+            {
+                std::unique_lock<std::mutex> g(m_);
+                work_.wait(g, [&] { return stop_ || generation_ != seen; });
+                if (stop_) return;
+                seen = generation_; fn = fn_; n = n_;
+            }
+            drain(seen, fn, n);
+        }
+    }
+    std::mutex callers_, m_;
+    std::condition_variable work_, done_;
+    std::vector<std::thread> threads_;
+    const std::function<void(int)>* fn_ = nullptr;
+    int n_ = 0;
+    std::atomic<unsigned long long> ticket_{0};
+    std::atomic<int> pending_{0};
+    unsigned long generation_ = 0;
+    bool stop_ = false;
+};
+Pool g_pool;
+}  // namespace
+
+void parallel_for(int n, const std::function<void(int)>& fn) {
+    if (n < 4) {
+        for (int i = 0; i < n; ++i) fn(i);
+        return;
+    }
+    g_pool.run(n, fn);
 }
 
 }  // namespace dc
