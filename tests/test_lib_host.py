@@ -124,3 +124,51 @@ def test_host_regions_equal_oracle(oracle, net, H, W, B):
         _compare(oracle, layers, H, W, B, mask, mx, my)
     _compare(oracle, layers, H, W, B, np.ones((gh, gw), np.uint8), 0, 0)
     _compare(oracle, layers, H, W, B, np.zeros((gh, gw), np.uint8), 3, -2)
+
+
+def _random_layers(rng, H, W):
+    """A random layer table: convs and pools with assorted kernels / strides / paddings, ReLUs, and adds of
+    same-shaped tensors, kept valid (every map stays at least as large as the next kernel)."""
+    layers, shapes = [], [(H, W, 8)]
+    for _ in range(int(rng.integers(3, 9))):
+        a = len(shapes) - 1
+        h, w, c = shapes[a]
+        kind = rng.choice(["conv", "conv", "conv", "pool", "relu", "add"])
+        if kind == "add":
+            same = [t for t in range(len(shapes) - 1) if shapes[t] == shapes[a]]
+            if not same:
+                kind = "relu"
+            else:
+                layers.append(dict(type=synth.ADD, k=1, s=1, p=0, cin=c, cout=c, relu=int(rng.integers(0, 2)), in0=a,
+                                   in1=int(rng.choice(same))))
+                shapes.append((h, w, c))
+                continue
+        if kind == "relu":
+            layers.append(dict(type=synth.RELU, k=1, s=1, p=0, cin=c, cout=c, relu=1, in0=a, in1=-1))
+            shapes.append((h, w, c))
+            continue
+        k = int(rng.choice([1, 2, 3, 3, 5, 7]))
+        s_ = int(rng.choice([1, 1, 2, 3]))
+        p_ = int(rng.integers(0, k))
+        if h + 2 * p_ < k or w + 2 * p_ < k:
+            k, s_, p_ = 1, 1, 0
+        ho, wo = (h + 2 * p_ - k) // s_ + 1, (w + 2 * p_ - k) // s_ + 1
+        if kind == "pool":
+            layers.append(dict(type=synth.MAXPOOL, k=k, s=s_, p=p_, cin=c, cout=c, relu=0, in0=a, in1=-1))
+            shapes.append((ho, wo, c))
+        else:
+            co = int(rng.choice([8, 16]))
+            layers.append(dict(type=synth.CONV, k=k, s=s_, p=p_, cin=c, cout=co, relu=1, in0=a, in1=-1))
+            shapes.append((ho, wo, co))
+    return layers
+
+
+def test_host_regions_equal_oracle_on_random_layer_tables(oracle):
+    rng = np.random.default_rng(2024)
+    for trial in range(60):
+        H, W, B = int(rng.integers(20, 90)), int(rng.integers(20, 90)), int(rng.choice([4, 5, 8]))
+        layers = _random_layers(rng, H, W)
+        gh, gw = H // B, W // B
+        mask = (rng.random((gh, gw)) < rng.choice([0.5, 0.8, 0.95, 1.0])).astype(np.uint8)
+        mx, my = int(rng.integers(-2 * B, 2 * B + 1)), int(rng.integers(-2 * B, 2 * B + 1))
+        _compare(oracle, layers, H, W, B, mask, mx, my)
