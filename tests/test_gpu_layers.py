@@ -92,6 +92,52 @@ def test_cached_conv_matches_oracle(oracle, case, bf16):
         assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
 
 
+def _random_regions(rng, oracle, Ho, Wo):
+    """Disjoint rectangles (merged from a random grid mask) whose sources stay inside the map."""
+    cell = int(rng.choice([2, 3, 5]))
+    mask = (rng.random((Ho // cell, Wo // cell)) < rng.choice([0.3, 0.6, 0.9])).astype(np.uint8)
+    rects = oracle.merge_blocks(mask, cell)
+    dx, dy = int(rng.integers(-4, 5)), int(rng.integers(-4, 5))
+    out = []
+    for x, y, w, h in rects.tolist():
+        x0, y0 = max(x, -dx, 0), max(y, -dy, 0)
+        x1, y1 = min(x + w, Wo - dx, Wo), min(y + h, Ho - dy, Ho)
+        if x1 > x0 and y1 > y0:
+            out.append([x0, y0, x1 - x0, y1 - y0])
+    return np.array(out, np.int32).reshape(-1, 4), (dx, dy)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("seed", range(6))
+def test_cached_conv_random_regions(oracle, seed, bf16):
+    """Random layer shapes of both kernel families with random disjoint reusable rectangles per stream:
+    copied pixels bit-identical, recomputed ones within tolerance, nothing else touched."""
+    rng = np.random.default_rng(100 + seed)
+    k, s, p = [(3, 1, 1), (3, 1, 1), (1, 1, 0), (3, 2, 1), (5, 1, 2), (3, 1, 0)][seed]
+    cin = int(rng.choice([16, 32, 64])) if seed < 2 else int(rng.choice([8, 16, 24]))
+    cout = int(rng.choice([64, 128])) if seed < 2 else int(rng.choice([16, 40, 64]))
+    H, W = int(rng.integers(18, 40)), int(rng.integers(18, 44))
+    print(f"[cached conv random] seed={seed} bf16={bf16} {H}x{W} cin={cin} cout={cout} k={k} s={s} p={p}", flush=True)
+    n = 3
+    x = rng.standard_normal((n, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, k, k, cin)) * np.sqrt(2.0 / (cin * k * k))).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    Ho, Wo = (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1
+    cache = rng.standard_normal((n, Ho, Wo, cout)).astype(np.float32)
+    if bf16:
+        x, w, cache = oracle.round_bf16(x), oracle.round_bf16(w), oracle.round_bf16(cache)
+    regions = [_random_regions(rng, oracle, Ho, Wo) for _ in range(n)]
+    got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, k, s, p, True), _to_dev(x, bf16), _to_dev(w, bf16),
+                                              torch.from_numpy(b).to(DEV), cache_prev=_to_dev(cache, bf16),
+                                              regions=regions))
+    for i in range(n):
+        mask = oracle.rasterize(regions[i][0], Ho, Wo)
+        want = oracle.conv_cached(x[i], w, b, k, s, p, True, cache_prev=cache[i], mask=mask, dxy=regions[i][1], bf16=bf16)
+        m = mask.astype(bool)
+        assert np.array_equal(got[i][m], want[m]), "copied pixels must be bit-identical"
+        assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (seed, i)
+
+
 # 3x3 stride-1 layers with whole 64-byte channel rows take the compile-time-shaped GEMM kernel; the launch
 # heuristics are overridden so that every shape of that kernel is exercised at a size the oracle handles:
 # (arrangement, units per workgroup, K split, chunk index); arrangement 1 exists for bf16 only.
