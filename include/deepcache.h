@@ -318,7 +318,9 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
  *                   when the call is made (the matching does not wait for the main stream)
  * The call waits once for the matching (the region logic runs on the host): for the main
  * stream without an overlap handle, for the handle's stream with one; everything after that
- * is asynchronous.
+ * is asynchronous.  With four or more streams the per-stream host work (merge, propagation,
+ * tile classification) is spread over a pool of at most 16 host threads that the library
+ * creates on first use and keeps; concurrent calls from several threads are serialised.
  */
 int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers,
                      const void* const* weights, const void* const* packed_weights,
