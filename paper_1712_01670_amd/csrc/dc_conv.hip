@@ -556,13 +556,17 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     const size_t esz = dtype_size(c.dtype);
     const bool vec_ok = (c.Cin % (16 / esz)) == 0 && reinterpret_cast<uintptr_t>(c.in) % 16 == 0 &&
                         reinterpret_cast<uintptr_t>(c.w) % 16 == 0;
+    // A smaller shape of the direct kernel (loads straight into LDS) beats any shape of the staged one (element
+    // loads through registers): the staged kernel is only for channel counts that are not whole vectors, or for
+    // patches that fit no direct shape (large strided kernels).
     Choice ch{};
-    for (int s2 = shape; s2 < 4; s2 = (s2 == 3 ? 0 : (s2 == 2 ? 4 : s2 + 1))) {   // 3 -> 0 -> 1 -> 2
-        ch = vec_ok ? choose_direct(s2, c, ph, pw) : Choice{};
-        if (!ch.ok) { ch = choose_staged(s2, c, ph, pw); if (ch.ok) g_rt = kShapes[s2].g; }
-        else if (s2 != shape) g_rt = kShapes[s2].g;
-        if (ch.ok) break;
-    }
+    for (int pass = 0; pass < 2 && !ch.ok; ++pass)
+        for (int s2 = shape; s2 < 4; s2 = (s2 == 3 ? 0 : (s2 == 2 ? 4 : s2 + 1))) {   // 3 -> 0 -> 1 -> 2
+            if (pass == 0 && !vec_ok) break;
+            ch = pass == 0 ? choose_direct(s2, c, ph, pw) : choose_staged(s2, c, ph, pw);
+            if (ch.ok && (s2 != shape || pass == 1)) g_rt = kShapes[s2].g;
+            if (ch.ok) break;
+        }
     if (!ch.ok) return hipErrorInvalidValue;
     const Shape& S = kShapes[ch.shape];
 
