@@ -615,13 +615,14 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uintx4* src, ui
 
 // ---- first layer -------------------------------------------------------------------------
 // A pixel of the network input is one 16-byte vector (4 fp32 or 8 bf16 channels, the frame's three
-// plus zero padding).  The three taps of a kernel row are then consecutive pixels: 48 bytes of
-// input against 48 bytes of weights, which is one K group of the MFMA with the fourth quarter
-// zeroed.  K is 3 groups in total, so there is nothing to stage: every wavefront takes one unit
-// (16 pixels x NB 16-channel blocks), loads its fragments from memory directly and keeps the
-// weights in registers while it walks over the unit list.
-template <typename T, int NB>
-__global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
+// plus zero padding).  Four taps of a kernel row are then consecutive pixels, 64 bytes of input
+// against 64 bytes of weights, which is one K group of the MFMA: a 3x3 kernel is 3 groups with
+// the fourth quarter zeroed, a 7x7 kernel 14 groups with one quarter in eight zeroed.  There is
+// nothing to stage: every wavefront takes one unit (16 pixels x NB 16-channel blocks), loads its
+// fragments from memory directly and keeps the weights in registers while it walks over the unit
+// list.  S is the stride: output pixel (y, x) reads input rows y S - p .. y S - p + K - 1.
+template <typename T, int NB, int K, int S>
+__device__ __forceinline__ void conv_first_body(const ConvParams& P) {
     typedef Frag<T> F;
     typedef typename F::vec vec;
     constexpr bool kWide = sizeof(T) == 2 && NB >= 2;
@@ -631,17 +632,20 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.in), 0, P.in_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.w), 0, P.w_bytes, kBufferFlags);
 
-    vec wv[3][NB];
+    constexpr int TG = (K + 3) / 4;                          // groups of four taps per kernel row
+    vec wv[K][TG][NB];
 #pragma unroll
-    for (int ky = 0; ky < 3; ++ky)
+    for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+      for (int g = 0; g < TG; ++g)
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             // bf16: row l16 of block j carries output channel (l16 / 4) * 4 NB + 4 j + l16 % 4, so that the accumulators
             // of a lane (rows 4q .. 4q+3 of every block) are 4 NB consecutive channels and leave in 16-byte stores.
             // fp32 keeps channel 16 j + l16: there a store instruction already writes 64 contiguous bytes per pixel.
             const int co = kWide ? (l16 >> 2) * (4 * NB) + j * 4 + (l16 & 3) : j * 16 + l16;
-            const uint32_t off = q < 3 ? (uint32_t)(((n0 + co) * 9 + ky * 3 + q) * 16) : kOob;
-            wv[ky][j] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, off, 0, 0));
+            const uint32_t off = g * 4 + q < K ? (uint32_t)(((n0 + co) * (K * K) + ky * K + g * 4 + q) * 16) : kOob;
+            wv[ky][g][j] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, off, 0, 0));
         }
     constexpr int kBlockStep = kWide ? 4 : 16;               // channel distance between a lane's blocks
     const int chan = n0 + (kWide ? 4 * NB : 4) * q;
@@ -667,21 +671,23 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
         }
         return r;
     };
-    auto load_x = [&](const UnitPos& pos, vec (&xv)[3]) {
+    auto load_x = [&](const UnitPos& pos, vec (&xv)[K][TG]) {
         const int y = pos.uy * 4 + (l16 >> 2), x = pos.ux * 4 + (l16 & 3);
 #pragma unroll
-        for (int ky = 0; ky < 3; ++ky) {
-            const int iy = y - P.p + ky, ix = x - P.p + q;
-            const bool ok = q < 3 && (unsigned)iy < (unsigned)P.Hin && (unsigned)ix < (unsigned)P.Win;
-            const uint32_t off = ok ? (uint32_t)(((pos.stream * P.Hin + iy) * P.Win + ix) * 16) : kOob;
-            xv[ky] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0));
-        }
+        for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+            for (int g = 0; g < TG; ++g) {
+                const int iy = y * S - P.p + ky, ix = x * S - P.p + g * 4 + q;
+                const bool ok = g * 4 + q < K && (unsigned)iy < (unsigned)P.Hin && (unsigned)ix < (unsigned)P.Win;
+                const uint32_t off = ok ? (uint32_t)(((pos.stream * P.Hin + iy) * P.Win + ix) * 16) : kOob;
+                xv[ky][g] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0));
+            }
     };
     const int step = gridDim.x * 4;
     int u = blockIdx.x * 4 + wave;
     if (u >= P.n_units) return;
     UnitPos pos = locate(u), pos_next = pos;
-    vec xv[3], xv_next[3];
+    vec xv[K][TG], xv_next[K][TG];
     load_x(pos, xv);
     for (; u < P.n_units; u += step) {
         const bool more = u + step < P.n_units;          // wavefront-uniform
@@ -693,11 +699,13 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
 #pragma unroll
         for (int j = 0; j < NB; ++j) acc[j] = bias[j];
 #pragma unroll
-        for (int ky = 0; ky < 3; ++ky)
+        for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+          for (int g = 0; g < TG; ++g)
 #pragma unroll
             for (int e = 0; e < F::NE; ++e)
 #pragma unroll
-                for (int j = 0; j < NB; ++j) F::mma1(wv[ky][j], xv[ky], acc[j], e);
+                for (int j = 0; j < NB; ++j) F::mma1(wv[ky][g][j], xv[ky][g], acc[j], e);
         const int y = pos.uy * 4 + (l16 >> 2), x = pos.ux * 4 + (l16 & 3);
         const bool keep = y < P.Hout && x < P.Wout && !((pos.mixed >> l16) & 1);   // a reusable pixel holds the copied value
         if (keep) {
@@ -725,13 +733,25 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) {
         }
         pos = pos_next;
 #pragma unroll
-        for (int ky = 0; ky < 3; ++ky) xv[ky] = xv_next[ky];
+        for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+            for (int g = 0; g < TG; ++g) xv[ky][g] = xv_next[ky][g];
     }
 }
 
+// 3x3 stride 1 (the first layer of the VGG-like stacks) and 7x7 stride 2 (the stem of the residual networks).
+template <typename T, int NB>
+__global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) { conv_first_body<T, NB, 3, 1>(P); }
+template <typename T, int NB>
+__global__ __launch_bounds__(256) void conv_stem_kernel(ConvParams P) { conv_first_body<T, NB, 7, 2>(P); }
+
 template <typename T>
-hipError_t first_launch(int nb, dim3 grid, hipStream_t st, const ConvParams& P) {
-    if (nb == 4) hipLaunchKernelGGL((conv_first_kernel<T, 4>), grid, dim3(256), 0, st, P);
+hipError_t first_launch(int k, int nb, dim3 grid, hipStream_t st, const ConvParams& P) {
+    if (k == 7) {
+        if (nb == 2) hipLaunchKernelGGL((conv_stem_kernel<T, 2>), grid, dim3(256), 0, st, P);
+        else hipLaunchKernelGGL((conv_stem_kernel<T, 1>), grid, dim3(256), 0, st, P);
+    }
+    else if (nb == 4) hipLaunchKernelGGL((conv_first_kernel<T, 4>), grid, dim3(256), 0, st, P);
     else if (nb == 2) hipLaunchKernelGGL((conv_first_kernel<T, 2>), grid, dim3(256), 0, st, P);
     else hipLaunchKernelGGL((conv_first_kernel<T, 1>), grid, dim3(256), 0, st, P);
     return hipGetLastError();
@@ -910,6 +930,10 @@ void conv_fast_kernel_name(int id, char* buf, size_t n) {
         snprintf(buf, n, "conv_fast_kernel<__hip_bfloat16, 3, %d, %d, 4, 2, %d>", 32 << (v / 4), v % 4 + 1, wide64 ? 2 : 4);
         return;
     }
+    if (id >= 102 && id < 106) {   // 102 + bf16 * 2 + {0, 1}: conv_stem_kernel (7x7 stride 2) with 1, 2 channel blocks
+        snprintf(buf, n, "conv_stem_kernel<%s, %d>", (id - 102) / 2 ? "__hip_bfloat16" : "float", 1 << ((id - 102) % 2));
+        return;
+    }
     if (id >= 96) {   // 96 + bf16 * 3 + {0, 1, 2}: conv_first_kernel with 1, 2, 4 channel blocks
         snprintf(buf, n, "conv_first_kernel<%s, %d>", (id - 96) / 3 ? "__hip_bfloat16" : "float", 1 << ((id - 96) % 3));
         return;
@@ -956,7 +980,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     static int enabled = -1;
     if (enabled < 0) { const char* e = getenv("DC_CONV_FAST"); enabled = e ? atoi(e) : 1; }
     const size_t esz = dtype_size(c.dtype);
-    if (enabled && c.k == 3 && c.s == 1 && c.Cin * esz == 16 && c.Cout % 16 == 0 &&
+    if (enabled && ((c.k == 3 && c.s == 1) || (c.k == 7 && c.s == 2)) && c.Cin * esz == 16 && c.Cout % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
         const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
@@ -970,12 +994,15 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
             P.npix_magic = (uint32_t)((0x100000000ull + (uint64_t)(units_x * units_y) - 1) / (uint64_t)(units_x * units_y));
             P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)units_x - 1) / (uint64_t)units_x);
             P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * 16);
-            P.w_bytes = (uint32_t)((size_t)c.Cout * 9 * 16);
-            const int nb = c.Cout % 64 == 0 ? 4 : (c.Cout % 32 == 0 ? 2 : 1);
+            P.w_bytes = (uint32_t)((size_t)c.Cout * c.k * c.k * 16);
+            // the 7x7 kernel keeps 14 weight vectors per channel block in registers: two blocks at most
+            const int nb = c.Cout % 64 == 0 && c.k == 3 ? 4 : (c.Cout % 32 == 0 ? 2 : 1);
             const long wgx = (n_units + 3) / 4 < 2048 ? (n_units + 3) / 4 : 2048;   // four units at a time, at most 8 workgroups per CU
-            if (c.kernel_id) *c.kernel_id = 96 + (c.dtype == DC_BF16 ? 3 : 0) + (nb == 4 ? 2 : (nb == 2 ? 1 : 0));
+            if (c.kernel_id)
+                *c.kernel_id = c.k == 7 ? 102 + (c.dtype == DC_BF16 ? 2 : 0) + (nb == 2 ? 1 : 0)
+                                        : 96 + (c.dtype == DC_BF16 ? 3 : 0) + (nb == 4 ? 2 : (nb == 2 ? 1 : 0));
             const dim3 grid((unsigned)wgx, (unsigned)(c.Cout / (16 * nb)));
-            *err = c.dtype == DC_BF16 ? first_launch<__hip_bfloat16>(nb, grid, st, P) : first_launch<float>(nb, grid, st, P);
+            *err = c.dtype == DC_BF16 ? first_launch<__hip_bfloat16>(c.k, nb, grid, st, P) : first_launch<float>(c.k, nb, grid, st, P);
             return true;
         }
     }

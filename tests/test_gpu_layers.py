@@ -258,6 +258,43 @@ def test_first_layer_kernel(oracle, cout, bf16, cached):
         assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (cout, i)
 
 
+@pytest.mark.parametrize("cached", [False, True])
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("cout", [16, 64, 96])
+def test_stem_kernel(oracle, cout, bf16, cached):
+    """7x7 stride-2 convolution over 16-byte input pixels (the stem of the residual networks); odd and even sizes,
+    so that the last output row reads past the input on one side only."""
+    H, W = 45, 54
+    k, s, p = 7, 2, 3
+    Ho, Wo = (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1
+    cin = 8 if bf16 else 4
+    print(f"[stem] cout={cout} bf16={bf16} cached={cached}", flush=True)
+    rng = np.random.default_rng(cout + 11)
+    n = 2
+    x = rng.standard_normal((n, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, k, k, cin)) * np.sqrt(2.0 / (cin * k * k))).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    cache = rng.standard_normal((n, Ho, Wo, cout)).astype(np.float32)
+    if bf16:
+        x, w, cache = oracle.round_bf16(x), oracle.round_bf16(w), oracle.round_bf16(cache)
+    regions = None
+    if cached:
+        regions = [(np.zeros((0, 4), np.int32), (0, 0)), (np.array([[2, 3, Wo - 9, Ho - 6], [Wo - 6, 4, 3, 6]], np.int32), (1, -2))]
+    got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, k, s, p, True), _to_dev(x, bf16), _to_dev(w, bf16),
+                                              torch.from_numpy(b).to(DEV),
+                                              cache_prev=_to_dev(cache, bf16) if cached else None, regions=regions))
+    assert got.shape == (n, Ho, Wo, cout)
+    for i in range(n):
+        if cached:
+            mask = oracle.rasterize(regions[i][0], Ho, Wo)
+            want = oracle.conv_cached(x[i], w, b, k, s, p, True, cache_prev=cache[i], mask=mask, dxy=regions[i][1], bf16=bf16)
+            m = mask.astype(bool)
+            assert np.array_equal(got[i][m], want[m])
+        else:
+            want = oracle.conv_cached(x[i], w, b, k, s, p, True, bf16=bf16)
+        assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (cout, i)
+
+
 def test_cached_conv_everything_reusable_launches_no_gemm(oracle):
     rng = np.random.default_rng(1)
     x = rng.standard_normal((1, 16, 16, 16)).astype(np.float32)
