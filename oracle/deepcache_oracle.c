@@ -32,6 +32,10 @@
  * the fixed-point property of the published algorithm checked against an
  * independent numpy cost table, by the closed form for content moved by a
  * point of the large pattern, and by the k-skip bookkeeping.
+ * The remaining layer types (LRN, concat, fully-connected, softmax, average
+ * pooling) are pinned by hand-computed values, the printed LRN row of Table 2
+ * and brute-force window containment, pixel-wise AND for the concat row, and
+ * the torch / scipy / numpy routines for the cases those implement.
  * Unpinned by the paper (pinned only by hand cases of the stated reading):
  * the merge decomposition, the rounding of fractional motion, and the source
  * offset when the motion is not a multiple of the cumulative stride.
@@ -43,15 +47,31 @@
 
 typedef struct { int32_t x, y, w, h; } oc_rect;
 
-enum { OC_CONV = 0, OC_MAXPOOL = 1, OC_RELU = 2, OC_ADD = 3 };
+enum { OC_CONV = 0, OC_MAXPOOL = 1, OC_RELU = 2, OC_ADD = 3, OC_LRN = 4, OC_CONCAT = 5, OC_FC = 6, OC_SOFTMAX = 7,
+       OC_AVGPOOL = 8 };
 
 typedef struct {
     int32_t type;          /* OC_* */
-    int32_t k, s, p;       /* kernel, stride, padding (conv, pool) */
+    int32_t k, s, p;       /* kernel, stride, padding (conv, pool); k = window size of an LRN (odd) */
     int32_t cin, cout;
-    int32_t relu;          /* fused ReLU after conv / add */
+    int32_t relu;          /* fused ReLU after conv / add / fc */
     int32_t in0, in1;      /* producer tensor ids; tensor 0 = network input, tensor i+1 = layer i output */
+    int32_t in2, in3;      /* further producers of a concat, -1: none */
+    int32_t within;        /* LRN: 0 = window over channels at one pixel, 1 = k x k pixels of one channel */
+    float alpha, beta, kappa;   /* LRN constants */
 } oc_layer;
+
+#define OC_MAX_CONCAT 4
+/* producers of a concat layer, in channel order; returns their number */
+static int concat_inputs(const oc_layer* l, int* ids)
+{
+    int n = 0;
+    ids[n++] = l->in0;
+    ids[n++] = l->in1;
+    if (l->in2 >= 0) ids[n++] = l->in2;
+    if (l->in2 >= 0 && l->in3 >= 0) ids[n++] = l->in3;
+    return n;
+}
 
 /* ------------------------------------------------------------------ */
 /* Section 4, Steps 1-4: block matching                               */
@@ -415,6 +435,15 @@ int oc_dt_overlap(oc_rect a, oc_rect b, oc_rect* out)
     return 1;
 }
 
+/* LRN row of Table 2 for a window of radius r pixels: (x+r, y+r, w-2r, h-2r).  A window over channels only has
+ * no spatial extent: its radius in the pixel grid is 0 and the row leaves the rectangle as it is (reading). */
+int oc_dt_lrn(oc_rect in, int r, oc_rect* out)
+{
+    if (in.w - 2 * r <= 0 || in.h - 2 * r <= 0) return 0;
+    out->x = in.x + r; out->y = in.y + r; out->w = in.w - 2 * r; out->h = in.h - 2 * r;
+    return 1;
+}
+
 /* Keep the part of r whose source r+(dx,dy) lies inside a WxH map. */
 static int clip_to_source(oc_rect r, int dx, int dy, int W, int H, oc_rect* out)
 {
@@ -466,16 +495,45 @@ int oc_propagate(const oc_layer* L, int n_layers, int H, int W,
         const oc_rect* ra = rects + (size_t)a * cap;
         oc_rect* ro = rects + (size_t)t * cap;
         int ho = ha, wo = wa, S = cum_stride[a];
-        if (l->type == OC_CONV || l->type == OC_MAXPOOL) {
+        int windowed = l->type == OC_CONV || l->type == OC_MAXPOOL || l->type == OC_AVGPOOL;
+        if (windowed) {
             ho = (ha + 2 * l->p - l->k) / l->s + 1;
             wo = (wa + 2 * l->p - l->k) / l->s + 1;
             S *= l->s;
         }
+        if (l->type == OC_FC) { ho = 1; wo = 1; }
         hw[2 * t] = ho; hw[2 * t + 1] = wo; cum_stride[t] = S;
         int dx = round_div(mx, S), dy = round_div(my, S);
         dxy[2 * t] = dx; dxy[2 * t + 1] = dy;
         n = 0;
-        if (l->type == OC_CONV || l->type == OC_MAXPOOL) {
+        if (l->type == OC_FC || l->type == OC_SOFTMAX) {
+            /* fully-connected / softmax row: (0,0,0,0), nothing is reusable from here on */
+        } else if (l->type == OC_LRN && l->within) {
+            for (int i = 0; i < na; ++i) {
+                oc_rect r, c;
+                if (!oc_dt_lrn(ra[i], (l->k - 1) / 2, &r)) continue;
+                if (!clip_to_source(r, dx, dy, wo, ho, &c)) continue;
+                if (n < cap) ro[n] = c; else overflow = 1;
+                ++n;
+            }
+        } else if (l->type == OC_CONCAT) {
+            /* overlapped region of the N inputs: every N-tuple of rectangles, one from each list */
+            int ids[OC_MAX_CONCAT], m = concat_inputs(l, ids);
+            int idx[OC_MAX_CONCAT] = {0, 0, 0, 0}, cnt[OC_MAX_CONCAT], empty = 0;
+            for (int j = 0; j < m; ++j) { cnt[j] = n_rects[ids[j]] < cap ? n_rects[ids[j]] : cap; if (cnt[j] == 0) empty = 1; }
+            while (!empty) {
+                oc_rect r = rects[(size_t)ids[0] * cap + idx[0]], c;
+                int ok = 1;
+                for (int j = 1; j < m && ok; ++j) ok = oc_dt_overlap(r, rects[(size_t)ids[j] * cap + idx[j]], &r);
+                if (ok && clip_to_source(r, dx, dy, wo, ho, &c)) {
+                    if (n < cap) ro[n] = c; else overflow = 1;
+                    ++n;
+                }
+                int j = m - 1;                 /* next tuple, last index fastest */
+                while (j >= 0 && ++idx[j] == cnt[j]) idx[j--] = 0;
+                if (j < 0) break;
+            }
+        } else if (windowed) {
             for (int i = 0; i < na; ++i) {
                 oc_rect r, c;
                 if (!oc_dt_window(ra[i], l->k, l->s, l->p, &r)) continue;
@@ -637,6 +695,107 @@ void oc_relu(const float* a, size_t n, float* out)
     for (size_t i = 0; i < n; ++i) out[i] = a[i] > 0.0f ? a[i] : 0.0f;
 }
 
+/* Average pooling over the in-bounds part of each window (reading: the divisor counts the elements inside the
+ * map; the models of Table 3 only average without padding, where every convention agrees). */
+void oc_avgpool(const float* in, int Hin, int Win, int C, int k, int s, int p, int bf16, float* out)
+{
+    int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
+#pragma omp parallel for schedule(static)
+    for (int y = 0; y < Hout; ++y)
+        for (int x = 0; x < Wout; ++x)
+            for (int c = 0; c < C; ++c) {
+                double sum = 0.0;
+                int cnt = 0;
+                for (int ky = 0; ky < k; ++ky) {
+                    int iy = y * s - p + ky;
+                    if (iy < 0 || iy >= Hin) continue;
+                    for (int kx = 0; kx < k; ++kx) {
+                        int ix = x * s - p + kx;
+                        if (ix < 0 || ix >= Win) continue;
+                        sum += (double)in[((size_t)iy * Win + ix) * C + c];
+                        ++cnt;
+                    }
+                }
+                out[((size_t)y * Wout + x) * C + c] = store_val(cnt ? sum / cnt : 0.0, bf16);
+            }
+}
+
+/*
+ * Local response normalisation (the layer of Table 2's LRN row; the paper gives no arithmetic, the reading is the
+ * published definition of Krizhevsky et al. 2012 with the window average used by Caffe-style engines):
+ *   out = in / (kappa + alpha / n * S)^beta
+ * S = sum of squares over the window, zeros outside the tensor; window = `size` channels centred on the element's
+ * channel at the same pixel (n = size), or size x size pixels centred on the element in its channel (n = size^2).
+ */
+void oc_lrn(const float* in, int H, int W, int C, int size, int within, double alpha, double beta, double kappa,
+            int bf16, float* out)
+{
+    int r = (size - 1) / 2;
+#pragma omp parallel for schedule(static)
+    for (int y = 0; y < H; ++y)
+        for (int x = 0; x < W; ++x)
+            for (int c = 0; c < C; ++c) {
+                double S = 0.0;
+                if (within) {
+                    for (int yy = y - r; yy <= y + r; ++yy)
+                        for (int xx = x - r; xx <= x + r; ++xx) {
+                            if (yy < 0 || yy >= H || xx < 0 || xx >= W) continue;
+                            double v = in[((size_t)yy * W + xx) * C + c];
+                            S += v * v;
+                        }
+                } else {
+                    for (int cc = c - r; cc <= c + r; ++cc) {
+                        if (cc < 0 || cc >= C) continue;
+                        double v = in[((size_t)y * W + x) * C + cc];
+                        S += v * v;
+                    }
+                }
+                double n = within ? (double)size * size : (double)size;
+                double v = (double)in[((size_t)y * W + x) * C + c] / pow(kappa + alpha / n * S, beta);
+                out[((size_t)y * W + x) * C + c] = store_val(v, bf16);
+            }
+}
+
+/* Concatenation along the channel axis: pixel by pixel, the channels of input 0, then of input 1, ... */
+void oc_concat(const float* const* ins, const int32_t* cs, int n_in, size_t n_pixels, float* out)
+{
+    int ctot = 0;
+    for (int j = 0; j < n_in; ++j) ctot += cs[j];
+    for (size_t px = 0; px < n_pixels; ++px) {
+        int off = 0;
+        for (int j = 0; j < n_in; ++j) {
+            for (int c = 0; c < cs[j]; ++c) out[px * ctot + off + c] = ins[j][px * cs[j] + c];
+            off += cs[j];
+        }
+    }
+}
+
+/* Fully-connected layer over the whole input tensor, flattened in storage order (row, column, channel):
+ * out[o] = bias[o] + sum_i w[o][i] in[i]. */
+void oc_fc(const float* in, size_t K, const float* w, const float* bias, int cout, int relu, int bf16, float* out)
+{
+#pragma omp parallel for schedule(static)
+    for (int o = 0; o < cout; ++o) {
+        double acc = bias ? (double)bias[o] : 0.0;
+        for (size_t i = 0; i < K; ++i) acc += (double)w[(size_t)o * K + i] * (double)in[i];
+        if (relu && acc < 0.0) acc = 0.0;
+        out[o] = store_val(acc, bf16);
+    }
+}
+
+/* Softmax over the channels of each pixel: exp(v_c) / sum_j exp(v_j), evaluated after subtracting the largest
+ * element (which leaves the quotient unchanged). */
+void oc_softmax(const float* in, size_t n_pixels, int C, int bf16, float* out)
+{
+    for (size_t px = 0; px < n_pixels; ++px) {
+        const float* v = in + px * C;
+        double m = v[0], sum = 0.0;
+        for (int c = 1; c < C; ++c) if (v[c] > m) m = v[c];
+        for (int c = 0; c < C; ++c) sum += exp((double)v[c] - m);
+        for (int c = 0; c < C; ++c) out[px * C + c] = store_val(exp((double)v[c] - m) / sum, bf16);
+    }
+}
+
 /* ------------------------------------------------------------------ */
 /* whole frame through the stack (Section 3 workflow)                 */
 /* ------------------------------------------------------------------ */
@@ -684,6 +843,20 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
             oc_maxpool(cur[a], ha, wa, l->cin, l->k, l->s, l->p, cur[t]);
         } else if (l->type == OC_ADD) {
             oc_add(cur[a], cur[l->in1], (size_t)ho * wo * l->cout, l->relu, bf16, cur[t]);
+        } else if (l->type == OC_AVGPOOL) {
+            oc_avgpool(cur[a], ha, wa, l->cin, l->k, l->s, l->p, bf16, cur[t]);
+        } else if (l->type == OC_LRN) {
+            oc_lrn(cur[a], ha, wa, l->cin, l->k, l->within, l->alpha, l->beta, l->kappa, bf16, cur[t]);
+        } else if (l->type == OC_CONCAT) {
+            int ids[OC_MAX_CONCAT], m = concat_inputs(l, ids);
+            const float* ins[OC_MAX_CONCAT];
+            int32_t cs[OC_MAX_CONCAT];
+            for (int j = 0; j < m; ++j) { ins[j] = cur[ids[j]]; cs[j] = ids[j] == 0 ? C : L[ids[j] - 1].cout; }
+            oc_concat(ins, cs, m, (size_t)ho * wo, cur[t]);
+        } else if (l->type == OC_FC) {
+            oc_fc(cur[a], (size_t)ha * wa * l->cin, weights[li], bias ? bias[li] : NULL, l->cout, l->relu, bf16, cur[t]);
+        } else if (l->type == OC_SOFTMAX) {
+            oc_softmax(cur[a], (size_t)ho * wo, l->cout, bf16, cur[t]);
         } else {
             oc_relu(cur[a], (size_t)ho * wo * l->cout, cur[t]);
         }

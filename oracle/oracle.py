@@ -29,7 +29,12 @@ class Rect(C.Structure):
 
 
 class Layer(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("type", "k", "s", "p", "cin", "cout", "relu", "in0", "in1")]
+    _fields_ = [(n, C.c_int32) for n in ("type", "k", "s", "p", "cin", "cout", "relu", "in0", "in1", "in2", "in3",
+                                         "within")] + [(n, C.c_float) for n in ("alpha", "beta", "kappa")]
+
+
+# value of a field that a layer's dict leaves out
+_LAYER_DEFAULTS = dict(k=1, s=1, p=0, relu=0, in1=-1, in2=-1, in3=-1, within=0, alpha=0.0, beta=0.0, kappa=1.0)
 
 
 _lib = None
@@ -43,6 +48,8 @@ def lib():
         _lib.oc_round_bf16.argtypes = [C.c_float]
         _lib.oc_round_bf16_array.argtypes = [C.c_void_p, C.c_size_t]
         _lib.oc_conv_cached.restype = None
+        for f in ("oc_avgpool", "oc_lrn", "oc_concat", "oc_fc", "oc_softmax"):
+            getattr(_lib, f).restype = None
         _lib.oc_maxpool.restype = None
         _lib.oc_add.restype = None
         _lib.oc_add.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]
@@ -61,8 +68,9 @@ def num_threads():
 def layers_to_c(layers):
     arr = (Layer * len(layers))()
     for i, L in enumerate(layers):
-        for f, _ in Layer._fields_:
-            setattr(arr[i], f, int(L[f]))
+        for f, ct in Layer._fields_:
+            v = L[f] if f in L else _LAYER_DEFAULTS[f]
+            setattr(arr[i], f, float(v) if ct is C.c_float else int(v))
     return arr
 
 
@@ -146,6 +154,13 @@ def dt_overlap(a, b):
     return (out.x, out.y, out.w, out.h) if ok else None
 
 
+def dt_lrn(rect, r):
+    """Table 2 LRN row for a window of radius r pixels.  Returns (x,y,w,h) or None."""
+    out = Rect()
+    ok = lib().oc_dt_lrn(Rect(*[int(v) for v in rect]), int(r), C.byref(out))
+    return (out.x, out.y, out.w, out.h) if ok else None
+
+
 def propagate(layers, H, W, rects0, mx, my, cap=1024):
     """Section 5 propagation.  Returns dict(rects=[per tensor int32 [n][4]], dxy, cum_stride, hw)."""
     n = len(layers)
@@ -212,6 +227,52 @@ def maxpool(x, k, s, p):
     return out
 
 
+def avgpool(x, k, s, p, bf16=False):
+    x = np.ascontiguousarray(x, np.float32)
+    H, W, Cc = x.shape
+    out = np.zeros(((H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1, Cc), np.float32)
+    lib().oc_avgpool(_p(x), H, W, Cc, int(k), int(s), int(p), int(bf16), _p(out))
+    return out
+
+
+def lrn(x, size, alpha, beta, kappa, within=False, bf16=False):
+    x = np.ascontiguousarray(x, np.float32)
+    H, W, Cc = x.shape
+    out = np.zeros_like(x)
+    lib().oc_lrn(_p(x), H, W, Cc, int(size), int(within), C.c_double(alpha), C.c_double(beta), C.c_double(kappa),
+                 int(bf16), _p(out))
+    return out
+
+
+def concat(xs):
+    xs = [np.ascontiguousarray(x, np.float32) for x in xs]
+    H, W = xs[0].shape[:2]
+    cs = np.array([x.shape[2] for x in xs], np.int32)
+    out = np.zeros((H, W, int(cs.sum())), np.float32)
+    ptrs = (C.c_void_p * len(xs))(*[x.ctypes.data for x in xs])
+    lib().oc_concat(ptrs, _p(cs), len(xs), C.c_size_t(H * W), _p(out))
+    return out
+
+
+def fc(x, w, bias, relu, bf16=False):
+    x = np.ascontiguousarray(x, np.float32)
+    w = np.ascontiguousarray(w, np.float32)
+    cout = w.shape[0]
+    assert w.size == cout * x.size
+    b = None if bias is None else np.ascontiguousarray(bias, np.float32)
+    out = np.zeros((1, 1, cout), np.float32)
+    lib().oc_fc(_p(x), C.c_size_t(x.size), _p(w), _p(b), cout, int(relu), int(bf16), _p(out))
+    return out
+
+
+def softmax(x, bf16=False):
+    x = np.ascontiguousarray(x, np.float32)
+    H, W, Cc = x.shape
+    out = np.zeros_like(x)
+    lib().oc_softmax(_p(x), C.c_size_t(H * W), Cc, int(bf16), _p(out))
+    return out
+
+
 def add(a, b, relu, bf16=False):
     a = np.ascontiguousarray(a, np.float32)
     b = np.ascontiguousarray(b, np.float32)
@@ -241,9 +302,11 @@ class Stream:
         shapes = [(H, W, Ch)]
         for L in layers:
             h, w_, _ = shapes[L["in0"]]
-            if L["type"] in (0, 1):
+            if L["type"] in (0, 1, 8):
                 shapes.append(((h + 2 * L["p"] - L["k"]) // L["s"] + 1,
                                (w_ + 2 * L["p"] - L["k"]) // L["s"] + 1, L["cout"]))
+            elif L["type"] == 6:
+                shapes.append((1, 1, L["cout"]))
             else:
                 shapes.append((h, w_, L["cout"]))
         self.shapes = shapes
