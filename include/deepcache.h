@@ -47,7 +47,9 @@ enum {
 };
 
 enum { DC_F32 = 0, DC_BF16 = 1 };
-enum { DC_CONV = 0, DC_MAXPOOL = 1, DC_RELU = 2, DC_ADD = 3 };
+/* Layer types: the rows of Table 2.  Only DC_CONV is cached (Section 5); the others are computed in full. */
+enum { DC_CONV = 0, DC_MAXPOOL = 1, DC_RELU = 2, DC_ADD = 3, DC_LRN = 4, DC_CONCAT = 5, DC_FC = 6, DC_SOFTMAX = 7,
+       DC_AVGPOOL = 8 };
 
 /* Rectangle in the pixel grid of one tensor, left-top origin (Section 3). */
 typedef struct { int32_t x, y, w, h; } dc_rect;
@@ -56,14 +58,26 @@ typedef struct { int32_t x, y, w, h; } dc_rect;
  * (u8-128)/128; it has the cin of the layers that read it, which may exceed the frame's
  * channel count: the extra channels are zero, so that a 3-channel frame can feed a first
  * layer whose weights are laid out with a 16-byte channel run); tensor i+1 is the output
- * of layer i.  in0 (and in1 for DC_ADD)
- * name producer tensors, so the table describes a DAG in topological order. */
+ * of layer i.  in0 (and in1 for DC_ADD, in1..in3 for DC_CONCAT)
+ * name producer tensors, so the table describes a DAG in topological order.
+ *   DC_LRN      out = in / (kappa + alpha / n * S)^beta, S = sum of squares over a window centred on the element,
+ *               zeros outside the tensor: k channels at the same pixel (within = 0, n = k) or k x k pixels of the
+ *               same channel (within = 1, n = k * k); k odd, cin == cout.
+ *   DC_CONCAT   channels of in0, then in1, then in2, in3 (each -1: absent; in3 needs in2) at every pixel;
+ *               cout = sum of the producers' channels (cin repeats cout), equal spatial sizes.
+ *   DC_FC       out[o] = bias[o] + sum_i w[o][i] in[i] over the whole producer tensor flattened in storage order
+ *               (row, column, channel); weights [cout][H*W*cin], output tensor 1 x 1 x cout, optional fused ReLU.
+ *   DC_SOFTMAX  over the channels of every pixel; cin == cout.
+ *   DC_AVGPOOL  mean over the in-bounds part of each k x k window (stride s, padding p); cin == cout. */
 typedef struct {
-    int32_t type;          /* DC_CONV, DC_MAXPOOL, DC_RELU, DC_ADD */
-    int32_t k, s, p;       /* kernel size, stride, zero padding (conv, pool) */
+    int32_t type;          /* DC_CONV ... DC_AVGPOOL */
+    int32_t k, s, p;       /* kernel size, stride, zero padding (conv, pool); k: window size of an LRN */
     int32_t cin, cout;
-    int32_t relu;          /* fused ReLU after a conv or an add */
+    int32_t relu;          /* fused ReLU after a conv, an add or a fully-connected layer */
     int32_t in0, in1;
+    int32_t in2, in3;      /* DC_CONCAT: third and fourth producer, -1: none (other types ignore them) */
+    int32_t within;        /* DC_LRN: 0 = window over channels, 1 = window over pixels */
+    float alpha, beta, kappa;   /* DC_LRN */
 } dc_layer;
 
 /* Reusable regions of one tensor of one stream (Section 5 "Propagation"):
@@ -223,7 +237,11 @@ int32_t dc_match_blocks_opt(const uint8_t* cur, const uint8_t* prev, int32_t n_s
  * blocks, then down while the whole run is set and unclaimed.  Conv and pool map a
  * rectangle to the largest output rectangle whose k x k windows lie inside it
  * (Table 2; x' = ceil((x+p)/s), last column floor((x+w-k+p)/s)); DC_ADD takes pairwise
- * overlaps (Table 2, concat row); DC_RELU leaves rectangles unchanged.  Every tensor has
+ * overlaps (Table 2, concat row) and DC_CONCAT the overlap of one rectangle from each of its
+ * inputs; DC_LRN over pixels shrinks a rectangle by its radius on every side (Table 2, LRN row:
+ * x+r, y+r, w-2r, h-2r), over channels it has no extent in the pixel grid and changes nothing;
+ * DC_AVGPOOL follows the pooling row; after DC_FC or DC_SOFTMAX nothing is reusable (their row
+ * is the empty rectangle); DC_RELU leaves rectangles unchanged.  Every tensor has
  * one source offset round(M / cum_stride) (halves away from zero) and rectangles are
  * clipped so that their source stays inside the map.
  * Returns DC_ERR_CAPACITY if a list overflowed (n is exact, stored rects are truncated).
@@ -285,6 +303,22 @@ int32_t dc_maxpool_layer(const void* in, void* out, int32_t n_streams, int32_t H
                          int32_t C, int32_t k, int32_t s, int32_t p, int32_t dtype, void* stream);
 int32_t dc_add_layer(const void* a, const void* b, void* out, size_t n, int32_t relu,
                      int32_t dtype, void* stream);
+/* The layer types of Table 2 besides convolution and pooling, and average pooling (arithmetic: see dc_layer).
+ * All pointers dev; tensors [n_streams][H][W][C] in `dtype`; results are rounded once when stored.
+ *   dc_lrn_layer      size odd >= 1
+ *   dc_concat_layer   ins: host array of n_in (2..4) dev pointers, channels: host array of their channel counts;
+ *                     out [n_pixels][sum of channels]; out must not alias an input
+ *   dc_fc_layer       in [n_streams][K], weights [cout][K], bias fp32 [cout] or NULL, out [n_streams][cout]
+ *   dc_softmax_layer  in, out [n_pixels][C] */
+int32_t dc_avgpool_layer(const void* in, void* out, int32_t n_streams, int32_t Hin, int32_t Win,
+                         int32_t C, int32_t k, int32_t s, int32_t p, int32_t dtype, void* stream);
+int32_t dc_lrn_layer(const void* in, void* out, int32_t n_streams, int32_t H, int32_t W, int32_t C, int32_t size,
+                     int32_t within, float alpha, float beta, float kappa, int32_t dtype, void* stream);
+int32_t dc_concat_layer(const void* const* ins, const int32_t* channels, int32_t n_in, void* out, size_t n_pixels,
+                        int32_t dtype, void* stream);
+int32_t dc_fc_layer(const void* in, const void* weights, const float* bias, void* out, int32_t n_streams, size_t K,
+                    int32_t cout, int32_t relu, int32_t dtype, void* stream);
+int32_t dc_softmax_layer(const void* in, void* out, size_t n_pixels, int32_t C, int32_t dtype, void* stream);
 
 /* Workspace sizes for dc_run_stack. */
 int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32_t n_streams,

@@ -23,7 +23,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
            "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_conv_workspace_bytes",
-           "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer",
+           "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer", "dc_avgpool_layer", "dc_lrn_layer", "dc_concat_layer", "dc_fc_layer", "dc_softmax_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
 
@@ -38,7 +38,8 @@ class Rect(C.Structure):
 
 
 class Layer(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("type", "k", "s", "p", "cin", "cout", "relu", "in0", "in1")]
+    _fields_ = [(n, C.c_int32) for n in ("type", "k", "s", "p", "cin", "cout", "relu", "in0", "in1", "in2", "in3",
+                                         "within")] + [(n, C.c_float) for n in ("alpha", "beta", "kappa")]
 
 
 class Regions(C.Structure):
@@ -95,6 +96,12 @@ def lib():
         L.dc_frame_to_tensor.argtypes = [vp, vp, sz, i32, i32, i32, vp]
         L.dc_maxpool_layer.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
         L.dc_add_layer.argtypes = [vp, vp, vp, sz, i32, i32, vp]
+        f32 = C.c_float
+        L.dc_avgpool_layer.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+        L.dc_lrn_layer.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, f32, f32, f32, i32, vp]
+        L.dc_concat_layer.argtypes = [vp, vp, i32, vp, sz, i32, vp]
+        L.dc_fc_layer.argtypes = [vp, vp, vp, vp, i32, sz, i32, i32, i32, vp]
+        L.dc_softmax_layer.argtypes = [vp, vp, sz, i32, i32, vp]
         L.dc_stack_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
         L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, vp, i32,
                                    vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp, vp]
@@ -121,8 +128,9 @@ def _ptr(t):
 def layers_to_c(layers):
     arr = (Layer * len(layers))()
     for i, L in enumerate(layers):
-        for f, _ in Layer._fields_:
-            setattr(arr[i], f, int(L[f]))
+        for f, ct in Layer._fields_:
+            v = L[f] if f in L else synth.LAYER_DEFAULTS[f]
+            setattr(arr[i], f, float(v) if ct is C.c_float else int(v))
     return arr
 
 
@@ -310,11 +318,11 @@ def pad_input_channels(layers, weights, Ch, dtype):
     weights = list(weights)
     for i, L in enumerate(layers):
         if L["in0"] == 0 and L["type"] == synth.CONV:
-            w = np.zeros(weights[i].shape[:3] + (cp,), np.float32)
+            w = np.zeros(tuple(weights[i].shape[:3]) + (cp,), np.float32)
             w[..., :Ch] = weights[i]
             weights[i] = w
             L["cin"] = cp
-        elif L["in0"] == 0 or L["in1"] == 0:
+        elif 0 in (L["in0"], L.get("in1", -1), L.get("in2", -1), L.get("in3", -1)):
             return [dict(L) for L in layers], weights, Ch   # a non-conv layer reads the input: leave it alone
     return layers, weights, cp
 
@@ -324,6 +332,54 @@ def dc_maxpool_layer(x, k, s, p):
     dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
     out = torch.empty((n, (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1, Ch), dtype=x.dtype, device=x.device)
     _check("dc_maxpool_layer", lib().dc_maxpool_layer(_ptr(x), _ptr(out), n, H, W, Ch, k, s, p, dtype, _stream()))
+    return out
+
+
+def dc_avgpool_layer(x, k, s, p):
+    n, H, W, Ch = x.shape
+    dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
+    out = torch.empty((n, (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1, Ch), dtype=x.dtype, device=x.device)
+    _check("dc_avgpool_layer", lib().dc_avgpool_layer(_ptr(x), _ptr(out), n, H, W, Ch, k, s, p, dtype, _stream()))
+    return out
+
+
+def dc_lrn_layer(x, size, alpha, beta, kappa, within=False):
+    n, H, W, Ch = x.shape
+    dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
+    out = torch.empty_like(x)
+    _check("dc_lrn_layer", lib().dc_lrn_layer(_ptr(x), _ptr(out), n, H, W, Ch, int(size), int(within), C.c_float(alpha),
+                                              C.c_float(beta), C.c_float(kappa), dtype, _stream()))
+    return out
+
+
+def dc_concat_layer(xs):
+    n, H, W = xs[0].shape[:3]
+    dtype = DC_BF16 if xs[0].dtype == torch.bfloat16 else DC_F32
+    cs = [int(x.shape[3]) for x in xs]
+    out = torch.empty((n, H, W, sum(cs)), dtype=xs[0].dtype, device=xs[0].device)
+    ins = (C.c_void_p * len(xs))(*[x.data_ptr() for x in xs])
+    chans = (C.c_int32 * len(xs))(*cs)
+    _check("dc_concat_layer", lib().dc_concat_layer(ins, chans, len(xs), _ptr(out), C.c_size_t(n * H * W), dtype, _stream()))
+    return out
+
+
+def dc_fc_layer(x, w, bias, relu):
+    n = x.shape[0]
+    K = x[0].numel()
+    cout = w.shape[0]
+    assert w.numel() == cout * K and x.is_contiguous() and w.is_contiguous()
+    dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
+    out = torch.empty((n, 1, 1, cout), dtype=x.dtype, device=x.device)
+    _check("dc_fc_layer", lib().dc_fc_layer(_ptr(x), _ptr(w), _ptr(bias) if bias is not None else None, _ptr(out), n,
+                                            C.c_size_t(K), cout, int(relu), dtype, _stream()))
+    return out
+
+
+def dc_softmax_layer(x):
+    dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
+    out = torch.empty_like(x)
+    Ch = x.shape[-1]
+    _check("dc_softmax_layer", lib().dc_softmax_layer(_ptr(x), _ptr(out), C.c_size_t(x.numel() // Ch), Ch, dtype, _stream()))
     return out
 
 
@@ -359,7 +415,8 @@ class StackRunner:
         self.b = [None if b is None else torch.from_numpy(b).to(self.device).float().contiguous() for b in biases]
         self._wp = (C.c_void_p * nl)(*[None if w is None else w.data_ptr() for w in self.w])
         torch.cuda.set_device(self.device)
-        self.w_packed = [None if (w is None or not pack_weights) else dc_pack_conv_weights(L, w) for L, w in zip(layers, self.w)]
+        self.w_packed = [None if (w is None or not pack_weights or L["type"] != synth.CONV) else dc_pack_conv_weights(L, w)
+                         for L, w in zip(layers, self.w)]
         self._wpp = (C.c_void_p * nl)(*[None if w is None else w.data_ptr() for w in self.w_packed])
         self._bp = (C.c_void_p * nl)(*[None if b is None else b.data_ptr() for b in self.b])
         self.shapes = synth.tensor_shapes(layers, H, W, self.Ch_tensor)

@@ -73,6 +73,13 @@ PlanAddr pack_plan(const LayerPlan& plan, unsigned char* host, unsigned char* de
 int input_channels(const dc_layer* L, int n_layers, int c_frame) {
     int c = -1;
     for (int i = 0; i < n_layers; ++i) {
+        if (L[i].type == DC_CONCAT) {             // its cin is the sum of its producers' channels
+            int ids[4];
+            const int m = concat_inputs(L[i], ids);
+            for (int j = 0; j < m; ++j)
+                if (ids[j] == 0) return -1;       // a concat reads layer outputs only
+            continue;
+        }
         if (L[i].in0 == 0 || (L[i].type == DC_ADD && L[i].in1 == 0)) {
             if (c >= 0 && L[i].cin != c) return -1;
             c = L[i].cin;
@@ -468,6 +475,58 @@ int32_t dc_add_layer(const void* a, const void* b, void* out, size_t n, int32_t 
     return DC_OK;
 }
 
+int32_t dc_avgpool_layer(const void* in, void* out, int32_t n_streams, int32_t Hin, int32_t Win, int32_t C,
+                         int32_t k, int32_t s, int32_t p, int32_t dtype, void* stream) {
+    if (!in || !out) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (n_streams < 1 || Hin < 1 || Win < 1 || C < 1 || k < 1 || s < 1 || p < 0 || p >= k) return DC_ERR_INVALID_ARG;
+    if (Hin + 2 * p < k || Win + 2 * p < k) return DC_ERR_BAD_SHAPE;
+    DC_TRY_HIP(launch_avgpool(in, out, n_streams, Hin, Win, C, k, s, p, dtype, as_stream(stream)));
+    return DC_OK;
+}
+
+int32_t dc_lrn_layer(const void* in, void* out, int32_t n_streams, int32_t H, int32_t W, int32_t C, int32_t size,
+                     int32_t within, float alpha, float beta, float kappa, int32_t dtype, void* stream) {
+    if (!in || !out) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (n_streams < 1 || H < 1 || W < 1 || C < 1 || size < 1 || size % 2 == 0) return DC_ERR_INVALID_ARG;
+    DC_TRY_HIP(launch_lrn(in, out, n_streams, H, W, C, size, within != 0, alpha, beta, kappa, dtype, as_stream(stream)));
+    return DC_OK;
+}
+
+int32_t dc_concat_layer(const void* const* ins, const int32_t* channels, int32_t n_in, void* out, size_t n_pixels,
+                        int32_t dtype, void* stream) {
+    if (!ins || !channels || !out) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (n_in < 2 || n_in > 4) return DC_ERR_INVALID_ARG;
+    int chans[4];
+    for (int j = 0; j < n_in; ++j) {
+        if (!ins[j]) return DC_ERR_NULL_PTR;
+        if (channels[j] < 1) return DC_ERR_INVALID_ARG;
+        if (ins[j] == out) return DC_ERR_INVALID_ARG;
+        chans[j] = channels[j];
+    }
+    DC_TRY_HIP(launch_concat(ins, chans, n_in, out, n_pixels, dtype, as_stream(stream)));
+    return DC_OK;
+}
+
+int32_t dc_fc_layer(const void* in, const void* weights, const float* bias, void* out, int32_t n_streams, size_t K,
+                    int32_t cout, int32_t relu, int32_t dtype, void* stream) {
+    if (!in || !weights || !out) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (n_streams < 1 || K < 1 || cout < 1) return DC_ERR_INVALID_ARG;
+    DC_TRY_HIP(launch_fc(in, weights, bias, out, n_streams, K, cout, relu, dtype, as_stream(stream)));
+    return DC_OK;
+}
+
+int32_t dc_softmax_layer(const void* in, void* out, size_t n_pixels, int32_t C, int32_t dtype, void* stream) {
+    if (!in || !out) return DC_ERR_NULL_PTR;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (C < 1) return DC_ERR_INVALID_ARG;
+    DC_TRY_HIP(launch_softmax(in, out, n_pixels, C, dtype, as_stream(stream)));
+    return DC_OK;
+}
+
 int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32_t n_streams, int32_t H, int32_t W,
                                  int32_t C, int32_t block, int32_t max_rects, size_t* dev_bytes, size_t* host_bytes) {
     if (!layers || !dev_bytes || !host_bytes) return DC_ERR_NULL_PTR;
@@ -620,7 +679,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     for (int t = 0; t <= n_layers; ++t)
         if (!tensors_cur[t]) return DC_ERR_NULL_PTR;
     for (int i = 0; i < n_layers; ++i)
-        if (layers[i].type == DC_CONV && !weights[i]) return DC_ERR_NULL_PTR;
+        if ((layers[i].type == DC_CONV || layers[i].type == DC_FC) && !weights[i]) return DC_ERR_NULL_PTR;
     const bool cached = !force_full;
     if (match_options) {
         if (match_options->method != DC_MATCH_EXHAUSTIVE && match_options->method != DC_MATCH_DIAMOND) return DC_ERR_INVALID_ARG;
@@ -661,6 +720,11 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     for (int i = 0; i < n_layers; ++i) {
         last_reader[layers[i].in0] = i;
         if (layers[i].type == DC_ADD) last_reader[layers[i].in1] = i;
+        if (layers[i].type == DC_CONCAT) {
+            int ids[4];
+            const int m = concat_inputs(layers[i], ids);
+            for (int j = 0; j < m; ++j) last_reader[ids[j]] = i;
+        }
     }
     // conv layers wait per run of consecutive conv layers (for the last one of the run): fewer cross-stream
     // dependencies, and the copies of a run go out in one launch
@@ -934,6 +998,34 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 DC_TRY_HIP(wait_prev(last_reader[t]));
                 DC_TRY_HIP(launch_add(tensors_cur[a], tensors_cur[l.in1], tensors_cur[t],
                                       (size_t)n_streams * hs[t] * ws[t] * cs[t], l.relu, dtype, st));
+                break;
+            case DC_AVGPOOL:
+                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(launch_avgpool(tensors_cur[a], tensors_cur[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
+                                          dtype, st));
+                break;
+            case DC_LRN:
+                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(launch_lrn(tensors_cur[a], tensors_cur[t], n_streams, hs[a], ws[a], cs[a], l.k, l.within,
+                                      l.alpha, l.beta, l.kappa, dtype, st));
+                break;
+            case DC_CONCAT: {
+                int ids[4], chans[4];
+                const void* ins[4];
+                const int m = concat_inputs(l, ids);
+                for (int j = 0; j < m; ++j) { ins[j] = tensors_cur[ids[j]]; chans[j] = cs[ids[j]]; }
+                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(launch_concat(ins, chans, m, tensors_cur[t], (size_t)n_streams * hs[t] * ws[t], dtype, st));
+                break;
+            }
+            case DC_FC:
+                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(launch_fc(tensors_cur[a], weights[i], bias ? bias[i] : nullptr, tensors_cur[t], n_streams,
+                                     (size_t)hs[a] * ws[a] * cs[a], l.cout, l.relu, dtype, st));
+                break;
+            case DC_SOFTMAX:
+                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(launch_softmax(tensors_cur[a], tensors_cur[t], (size_t)n_streams * hs[t] * ws[t], cs[t], dtype, st));
                 break;
             default:
                 DC_TRY_HIP(wait_prev(last_reader[t]));

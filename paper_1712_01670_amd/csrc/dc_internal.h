@@ -114,6 +114,19 @@ hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int
                           int s, int p, int dtype, hipStream_t st);
 hipError_t launch_add(const void* a, const void* b, void* out, size_t n, int relu, int dtype,
                       hipStream_t st);
+hipError_t launch_avgpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k,
+                          int s, int p, int dtype, hipStream_t st);
+hipError_t launch_lrn(const void* in, void* out, int n_streams, int H, int W, int C, int size, int within,
+                      float alpha, float beta, float kappa, int dtype, hipStream_t st);
+// ins/cs: host arrays of n_in device pointers and channel counts
+hipError_t launch_concat(const void* const* ins, const int* cs, int n_in, void* out, size_t n_pixels, int dtype,
+                         hipStream_t st);
+hipError_t launch_softmax(const void* in, void* out, size_t n_pixels, int C, int dtype, hipStream_t st);
+// x: [n_streams][K], w: [cout][K], out: [n_streams][cout]
+hipError_t launch_fc(const void* x, const void* w, const float* bias, void* out, int n_streams, size_t K, int cout,
+                     int relu, int dtype, hipStream_t st);
+// Producer tensors of a DC_CONCAT layer in channel order; returns their number (2..4).
+int concat_inputs(const dc_layer& l, int* ids);
 
 // Event pairs for kernel timing (measurement aid).
 struct Profile {

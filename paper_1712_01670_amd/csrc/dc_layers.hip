@@ -1,6 +1,7 @@
 // HBM-bound kernels: the shifted copy that serves reusable pixels from the previous
 // frame's cached feature map (Section 5 "Reuse", step 1) and the layers that are never
-// cached (Section 5: pooling, add, the input conversion).  All channels-last, 16-byte
+// cached (Section 5: pooling, add, the input conversion; the layer types of Table 2 other
+// than convolution: LRN, concat, fully-connected, softmax).  All channels-last, 16-byte
 // vector accesses whenever the channel run allows it.
 #include <hip/hip_bf16.h>
 
@@ -114,6 +115,175 @@ __global__ __launch_bounds__(kThreads) void add_kernel(const T* __restrict__ a, 
     }
 }
 
+// Mean over the in-bounds part of each window; one thread per (output pixel, channel).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void avgpool_kernel(const T* __restrict__ in, T* __restrict__ out,
+                                                           int n_streams, int Hin, int Win, int C, int Hout,
+                                                           int Wout, int k, int s, int p) {
+    const size_t total = (size_t)n_streams * Hout * Wout * C;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (; i < total; i += stride) {
+        int c = (int)(i % C);
+        size_t pix = i / C;
+        int x = (int)(pix % Wout);
+        size_t t = pix / Wout;
+        int y = (int)(t % Hout);
+        int st = (int)(t / Hout);
+        float sum = 0.f;
+        int cnt = 0;
+        for (int ky = 0; ky < k; ++ky) {
+            int iy = y * s - p + ky;
+            if (iy < 0 || iy >= Hin) continue;
+            for (int kx = 0; kx < k; ++kx) {
+                int ix = x * s - p + kx;
+                if (ix < 0 || ix >= Win) continue;
+                sum += to_float(in[(((size_t)st * Hin + iy) * Win + ix) * C + c]);
+                ++cnt;
+            }
+        }
+        out[i] = from_float<T>(cnt ? sum / (float)cnt : 0.f);
+    }
+}
+
+// Local response normalisation, out = in / (kappa + alpha_n * S)^beta with S the sum of squares over the window
+// (zeros outside the tensor) and alpha_n = alpha / window elements: `size` channels around the element's channel
+// at the same pixel, or size x size pixels around the element in its channel.  One thread per element; the
+// neighbours are re-read through the vector cache.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void lrn_kernel(const T* __restrict__ in, T* __restrict__ out, int n_streams,
+                                                       int H, int W, int C, int r, int within, float alpha_n,
+                                                       float beta, float kappa) {
+    const size_t total = (size_t)n_streams * H * W * C;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (; i < total; i += stride) {
+        const int c = (int)(i % C);
+        float S = 0.f;
+        if (within) {
+            const size_t pix = i / C;
+            const int x = (int)(pix % W);
+            const size_t t = pix / W;
+            const int y = (int)(t % H);
+            const size_t map = (t / H) * H;
+            for (int yy = y - r; yy <= y + r; ++yy) {
+                if (yy < 0 || yy >= H) continue;
+                for (int xx = x - r; xx <= x + r; ++xx) {
+                    if (xx < 0 || xx >= W) continue;
+                    const float v = to_float(in[((map + yy) * W + xx) * C + c]);
+                    S += v * v;
+                }
+            }
+        } else {
+            const size_t base = i - c;
+            const int c0 = c - r < 0 ? 0 : c - r, c1 = c + r >= C ? C - 1 : c + r;
+            for (int cc = c0; cc <= c1; ++cc) {
+                const float v = to_float(in[base + cc]);
+                S += v * v;
+            }
+        }
+        out[i] = from_float<T>(to_float(in[i]) * powf(kappa + alpha_n * S, -beta));
+    }
+}
+
+// out[pixel][off + c] = in[pixel][c], c < cj: one input of a concatenation along the channel axis.  V is the unit
+// moved per thread (16 bytes when every channel count involved is a whole number of them, else one element).
+template <typename V>
+__global__ __launch_bounds__(kThreads) void concat_kernel(const V* __restrict__ in, V* __restrict__ out, size_t n_pixels,
+                                                          int cj, int off, int ctot) {
+    const size_t total = n_pixels * cj;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (; i < total; i += stride) {
+        const size_t px = i / cj;
+        out[px * ctot + off + (i - px * cj)] = in[i];
+    }
+}
+
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+
+// Softmax over the channels of a pixel; one wavefront per pixel, the largest element subtracted first.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void softmax_kernel(const T* __restrict__ in, T* __restrict__ out, size_t n_pixels,
+                                                           int C) {
+    const int lane = threadIdx.x & 63;
+    const size_t px = (size_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (px >= n_pixels) return;                   // whole wavefronts leave
+    const T* v = in + px * C;
+    float m = -INFINITY;
+    for (int c = lane; c < C; c += 64) m = fmaxf(m, to_float(v[c]));
+    m = wave_max_f32(m);
+    float sum = 0.f;
+    for (int c = lane; c < C; c += 64) sum += expf(to_float(v[c]) - m);
+    sum = wave_sum_f32(sum);
+    const float inv = 1.0f / sum;
+    for (int c = lane; c < C; c += 64) out[px * C + c] = from_float<T>(expf(to_float(v[c]) - m) * inv);
+}
+
+// Fully-connected layer: out[s][o] = bias[o] + sum_i w[o][i] x[s][i].  The weights are the large operand (each is
+// used once per stream), so a wavefront takes one output neuron, streams its weight row once and multiplies it with
+// the inputs of NS streams, which come from the caches; per-lane partial sums are added across the wavefront at the
+// end.  VE elements per load: a 16-byte vector, or 1 when K or an address is not a multiple of that.
+template <typename T, int VE>
+__device__ __forceinline__ void fc_load(const T* p, float (&f)[VE]) {
+    if constexpr (VE == 1) {
+        f[0] = to_float(*p);
+    } else if constexpr (sizeof(T) == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    } else {                                      // eight bf16: the value is the upper half of the fp32 pattern
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f[2 * e] = __uint_as_float(u[e] << 16);
+            f[2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
+        }
+    }
+}
+template <typename T, int NS, int VE>
+__global__ __launch_bounds__(kThreads) void fc_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                      const float* __restrict__ bias, T* __restrict__ out, int n_streams,
+                                                      size_t K, int cout, int relu) {
+    const int lane = threadIdx.x & 63;
+    const int o = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    const int s0 = blockIdx.y * NS;
+    if (o >= cout) return;                        // whole wavefronts leave
+    float acc[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) acc[s] = 0.f;
+    const T* wrow = w + (size_t)o * K;
+    for (size_t k = (size_t)lane * VE; k < K; k += 64 * VE) {
+        float wf[VE];
+        fc_load<T, VE>(wrow + k, wf);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (s0 + s < n_streams) {             // uniform over the wavefront
+                float xf[VE];
+                fc_load<T, VE>(x + (size_t)(s0 + s) * K + k, xf);
+#pragma unroll
+                for (int e = 0; e < VE; ++e) acc[s] = fmaf(wf[e], xf[e], acc[s]);
+            }
+        }
+    }
+    const float b = bias ? bias[o] : 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        float v = wave_sum_f32(acc[s]) + b;
+        if (relu) v = v > 0.f ? v : 0.f;
+        if (lane == 0 && s0 + s < n_streams) out[(size_t)(s0 + s) * cout + o] = from_float<T>(v);
+    }
+}
+
 inline int grid_for(size_t n, int cap = 256 * 16) {
     size_t g = (n + kThreads - 1) / kThreads;
     return (int)(g < 1 ? 1 : (g > (size_t)cap ? cap : g));
@@ -191,6 +361,114 @@ hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int
         hipLaunchKernelGGL(maxpool_kernel<float>, dim3(grid_for(n)), dim3(kThreads), 0, st, (const float*)in,
                            (float*)out, n_streams, Hin, Win, C, Hout, Wout, k, s, p);
     return hipGetLastError();
+}
+
+hipError_t launch_avgpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k, int s,
+                          int p, int dtype, hipStream_t st) {
+    const int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
+    const size_t n = (size_t)n_streams * Hout * Wout * C;
+    if (n == 0) return hipSuccess;
+    if (dtype == DC_BF16)
+        hipLaunchKernelGGL(avgpool_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st,
+                           (const __hip_bfloat16*)in, (__hip_bfloat16*)out, n_streams, Hin, Win, C, Hout, Wout,
+                           k, s, p);
+    else
+        hipLaunchKernelGGL(avgpool_kernel<float>, dim3(grid_for(n)), dim3(kThreads), 0, st, (const float*)in,
+                           (float*)out, n_streams, Hin, Win, C, Hout, Wout, k, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_lrn(const void* in, void* out, int n_streams, int H, int W, int C, int size, int within,
+                      float alpha, float beta, float kappa, int dtype, hipStream_t st) {
+    const size_t n = (size_t)n_streams * H * W * C;
+    if (n == 0) return hipSuccess;
+    const int r = (size - 1) / 2;
+    const float alpha_n = alpha / (within ? (float)size * (float)size : (float)size);
+    if (dtype == DC_BF16)
+        hipLaunchKernelGGL(lrn_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st,
+                           (const __hip_bfloat16*)in, (__hip_bfloat16*)out, n_streams, H, W, C, r, within, alpha_n, beta,
+                           kappa);
+    else
+        hipLaunchKernelGGL(lrn_kernel<float>, dim3(grid_for(n)), dim3(kThreads), 0, st, (const float*)in, (float*)out,
+                           n_streams, H, W, C, r, within, alpha_n, beta, kappa);
+    return hipGetLastError();
+}
+
+hipError_t launch_concat(const void* const* ins, const int* cs, int n_in, void* out, size_t n_pixels, int dtype,
+                         hipStream_t st) {
+    const size_t es = dtype_size(dtype);
+    int ctot = 0;
+    bool vec = reinterpret_cast<uintptr_t>(out) % 16 == 0;
+    for (int j = 0; j < n_in; ++j) {
+        ctot += cs[j];
+        vec = vec && (cs[j] * es) % 16 == 0 && reinterpret_cast<uintptr_t>(ins[j]) % 16 == 0;
+    }
+    if (n_pixels == 0) return hipSuccess;
+    int off = 0;
+    for (int j = 0; j < n_in; ++j) {
+        const size_t n = n_pixels * cs[j];
+        if (vec) {
+            const int ve = (int)(16 / es);
+            hipLaunchKernelGGL(concat_kernel<uint4>, dim3(grid_for(n / ve)), dim3(kThreads), 0, st, (const uint4*)ins[j],
+                               (uint4*)out, n_pixels, cs[j] / ve, off / ve, ctot / ve);
+        } else if (dtype == DC_BF16) {
+            hipLaunchKernelGGL(concat_kernel<uint16_t>, dim3(grid_for(n)), dim3(kThreads), 0, st, (const uint16_t*)ins[j],
+                               (uint16_t*)out, n_pixels, cs[j], off, ctot);
+        } else {
+            hipLaunchKernelGGL(concat_kernel<uint32_t>, dim3(grid_for(n)), dim3(kThreads), 0, st, (const uint32_t*)ins[j],
+                               (uint32_t*)out, n_pixels, cs[j], off, ctot);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        off += cs[j];
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_softmax(const void* in, void* out, size_t n_pixels, int C, int dtype, hipStream_t st) {
+    if (n_pixels == 0 || C == 0) return hipSuccess;
+    const size_t wgs = (n_pixels + kThreads / 64 - 1) / (kThreads / 64);
+    if (wgs > 2147483647u) return hipErrorInvalidValue;
+    if (dtype == DC_BF16)
+        hipLaunchKernelGGL(softmax_kernel<__hip_bfloat16>, dim3((unsigned)wgs), dim3(kThreads), 0, st,
+                           (const __hip_bfloat16*)in, (__hip_bfloat16*)out, n_pixels, C);
+    else
+        hipLaunchKernelGGL(softmax_kernel<float>, dim3((unsigned)wgs), dim3(kThreads), 0, st, (const float*)in,
+                           (float*)out, n_pixels, C);
+    return hipGetLastError();
+}
+
+namespace {
+template <typename T, int VE>
+hipError_t fc_launch(const void* x, const void* w, const float* bias, void* out, int n_streams, size_t K, int cout,
+                     int relu, hipStream_t st) {
+    const unsigned gx = (unsigned)((cout + kThreads / 64 - 1) / (kThreads / 64));
+    const T* xp = (const T*)x;
+    const T* wp = (const T*)w;
+    T* op = (T*)out;
+    // streams per pass over the weights: the partial sums of a pass live in registers
+    if (n_streams == 1)
+        hipLaunchKernelGGL((fc_kernel<T, 1, VE>), dim3(gx, 1), dim3(kThreads), 0, st, xp, wp, bias, op, n_streams, K, cout, relu);
+    else if (n_streams <= 4)
+        hipLaunchKernelGGL((fc_kernel<T, 4, VE>), dim3(gx, 1), dim3(kThreads), 0, st, xp, wp, bias, op, n_streams, K, cout, relu);
+    else
+        hipLaunchKernelGGL((fc_kernel<T, 16, VE>), dim3(gx, (unsigned)((n_streams + 15) / 16)), dim3(kThreads), 0, st, xp, wp,
+                           bias, op, n_streams, K, cout, relu);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_fc(const void* x, const void* w, const float* bias, void* out, int n_streams, size_t K, int cout,
+                     int relu, int dtype, hipStream_t st) {
+    if (n_streams == 0 || cout == 0) return hipSuccess;
+    if ((n_streams + 15) / 16 > 65535) return hipErrorInvalidValue;
+    const size_t es = dtype_size(dtype);
+    const bool vec = (K * es) % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0;
+    if (dtype == DC_BF16)
+        return vec ? fc_launch<__hip_bfloat16, 8>(x, w, bias, out, n_streams, K, cout, relu, st)
+                   : fc_launch<__hip_bfloat16, 1>(x, w, bias, out, n_streams, K, cout, relu, st);
+    return vec ? fc_launch<float, 4>(x, w, bias, out, n_streams, K, cout, relu, st)
+               : fc_launch<float, 1>(x, w, bias, out, n_streams, K, cout, relu, st);
 }
 
 hipError_t launch_add(const void* a, const void* b, void* out, size_t n, int relu, int dtype, hipStream_t st) {

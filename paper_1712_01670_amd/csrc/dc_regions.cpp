@@ -69,6 +69,15 @@ void merge_blocks(const uint8_t* mask, int gh, int gw, int B, std::vector<dc_rec
     }
 }
 
+int concat_inputs(const dc_layer& l, int* ids) {
+    int n = 0;
+    ids[n++] = l.in0;
+    ids[n++] = l.in1;
+    if (l.in2 >= 0) ids[n++] = l.in2;
+    if (l.in2 >= 0 && l.in3 >= 0) ids[n++] = l.in3;
+    return n;
+}
+
 int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C, std::vector<int>* hs,
                     std::vector<int>* ws, std::vector<int>* cs) {
     std::vector<int> h(n_layers + 1), w(n_layers + 1), c(n_layers + 1);
@@ -80,9 +89,10 @@ int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C, std::v
         switch (l.type) {
             case DC_CONV:
             case DC_MAXPOOL:
+            case DC_AVGPOOL:
                 if (l.k < 1 || l.s < 1 || l.p < 0 || l.p >= l.k) return DC_ERR_INVALID_ARG;
                 if (l.cin != c[a] || l.cout < 1) return DC_ERR_BAD_SHAPE;
-                if (l.type == DC_MAXPOOL && l.cout != l.cin) return DC_ERR_BAD_SHAPE;
+                if (l.type != DC_CONV && l.cout != l.cin) return DC_ERR_BAD_SHAPE;
                 if (h[a] + 2 * l.p < l.k || w[a] + 2 * l.p < l.k) return DC_ERR_BAD_SHAPE;
                 h[i + 1] = (h[a] + 2 * l.p - l.k) / l.s + 1;
                 w[i + 1] = (w[a] + 2 * l.p - l.k) / l.s + 1;
@@ -95,9 +105,30 @@ int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C, std::v
                     return DC_ERR_BAD_SHAPE;
                 h[i + 1] = h[a]; w[i + 1] = w[a]; c[i + 1] = c[a];
                 break;
+            case DC_LRN:
+                if (l.k < 1 || l.k % 2 == 0) return DC_ERR_INVALID_ARG;
+                // fall through
+            case DC_SOFTMAX:
             case DC_RELU:
                 if (l.cin != c[a] || l.cout != c[a]) return DC_ERR_BAD_SHAPE;
                 h[i + 1] = h[a]; w[i + 1] = w[a]; c[i + 1] = c[a];
+                break;
+            case DC_CONCAT: {
+                if (l.in1 < 0 || (l.in2 < 0 && l.in3 >= 0)) return DC_ERR_BAD_SHAPE;
+                int ids[4];
+                const int m = concat_inputs(l, ids);
+                int sum = 0;
+                for (int j = 0; j < m; ++j) {
+                    if (ids[j] < 0 || ids[j] > i || h[ids[j]] != h[a] || w[ids[j]] != w[a]) return DC_ERR_BAD_SHAPE;
+                    sum += c[ids[j]];
+                }
+                if (l.cout != sum || l.cin != sum) return DC_ERR_BAD_SHAPE;
+                h[i + 1] = h[a]; w[i + 1] = w[a]; c[i + 1] = sum;
+                break;
+            }
+            case DC_FC:
+                if (l.cin != c[a] || l.cout < 1) return DC_ERR_BAD_SHAPE;
+                h[i + 1] = 1; w[i + 1] = 1; c[i + 1] = l.cout;
                 break;
             default:
                 return DC_ERR_INVALID_ARG;
@@ -119,13 +150,42 @@ int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<d
         const dc_layer& l = L[i];
         const TensorRegions& a = out[l.in0];
         TensorRegions& t = out[i + 1];
-        const bool windowed = (l.type == DC_CONV || l.type == DC_MAXPOOL);
-        t.h = windowed ? (a.h + 2 * l.p - l.k) / l.s + 1 : a.h;
-        t.w = windowed ? (a.w + 2 * l.p - l.k) / l.s + 1 : a.w;
+        const bool windowed = (l.type == DC_CONV || l.type == DC_MAXPOOL || l.type == DC_AVGPOOL);
+        t.h = windowed ? (a.h + 2 * l.p - l.k) / l.s + 1 : (l.type == DC_FC ? 1 : a.h);
+        t.w = windowed ? (a.w + 2 * l.p - l.k) / l.s + 1 : (l.type == DC_FC ? 1 : a.w);
         t.cum_stride = windowed ? a.cum_stride * l.s : a.cum_stride;
         t.dx = round_half_away(mx, t.cum_stride);
         t.dy = round_half_away(my, t.cum_stride);
-        if (windowed) {
+        if (l.type == DC_FC || l.type == DC_SOFTMAX) {
+            // every output depends on every input: nothing is reusable from here on
+        } else if (l.type == DC_LRN && l.within) {
+            const int r = (l.k - 1) / 2;
+            for (const dc_rect& rc : a.rects) {
+                if (rc.w - 2 * r <= 0 || rc.h - 2 * r <= 0) continue;
+                push_clipped(t.rects, Span{rc.x + r, rc.x + rc.w - r}, Span{rc.y + r, rc.y + rc.h - r}, t);
+            }
+        } else if (l.type == DC_CONCAT) {
+            int ids[4];
+            const int m = concat_inputs(l, ids);
+            // overlaps of the first two lists, then of that with the third, ...: in the order of the tuples
+            // (i0, i1, ..) with the last index fastest, which is the order a direct enumeration gives
+            std::vector<std::pair<Span, Span>> acc, next;
+            for (const dc_rect& r : a.rects) acc.push_back({Span{r.x, r.x + r.w}, Span{r.y, r.y + r.h}});
+            for (int j = 1; j < m; ++j) {
+                const TensorRegions& b = out[ids[j]];
+                if (b.cum_stride != a.cum_stride) return DC_ERR_BAD_SHAPE;
+                next.clear();
+                for (const auto& ra : acc)
+                    for (const dc_rect& rb : b.rects) {
+                        Span xs = intersect(ra.first, Span{rb.x, rb.x + rb.w});
+                        Span ys = intersect(ra.second, Span{rb.y, rb.y + rb.h});
+                        if (xs.empty() || ys.empty()) continue;
+                        next.push_back({xs, ys});
+                    }
+                acc.swap(next);
+            }
+            for (const auto& r : acc) push_clipped(t.rects, r.first, r.second, t);
+        } else if (windowed) {
             for (const dc_rect& r : a.rects) {
                 Span xs = window_span(Span{r.x, r.x + r.w}, l.k, l.s, l.p);
                 Span ys = window_span(Span{r.y, r.y + r.h}, l.k, l.s, l.p);

@@ -15,7 +15,10 @@ from __future__ import annotations
 import numpy as np
 
 # layer types (plain data; each side maps them to its own C enum)
-CONV, MAXPOOL, RELU, ADD = 0, 1, 2, 3
+CONV, MAXPOOL, RELU, ADD, LRN, CONCAT, FC, SOFTMAX, AVGPOOL = 0, 1, 2, 3, 4, 5, 6, 7, 8
+
+# fields a layer's dict may leave out
+LAYER_DEFAULTS = dict(k=1, s=1, p=0, relu=0, in1=-1, in2=-1, in3=-1, within=0, alpha=0.0, beta=0.0, kappa=1.0)
 
 
 # --------------------------------------------------------------------------- #
@@ -31,6 +34,29 @@ def _pool(c, k, s, p, in0):
 
 def _add(c, in0, in1, relu):
     return dict(type=ADD, k=1, s=1, p=0, cin=c, cout=c, relu=int(relu), in0=in0, in1=in1)
+
+
+def _avgpool(c, k, s, p, in0):
+    return dict(type=AVGPOOL, k=k, s=s, p=p, cin=c, cout=c, relu=0, in0=in0, in1=-1)
+
+
+def _lrn(c, size, in0, within=0, alpha=1e-4, beta=0.75, kappa=1.0):
+    return dict(type=LRN, k=size, s=1, p=0, cin=c, cout=c, relu=0, in0=in0, in1=-1, within=int(within),
+                alpha=alpha, beta=beta, kappa=kappa)
+
+
+def _concat(cs, ins):
+    ins = list(ins) + [-1] * (4 - len(ins))
+    return dict(type=CONCAT, k=1, s=1, p=0, cin=sum(cs), cout=sum(cs), relu=0, in0=ins[0], in1=ins[1], in2=ins[2],
+                in3=ins[3])
+
+
+def _fc(cin, cout, relu, in0):
+    return dict(type=FC, k=1, s=1, p=0, cin=cin, cout=cout, relu=int(relu), in0=in0, in1=-1)
+
+
+def _softmax(c, in0):
+    return dict(type=SOFTMAX, k=1, s=1, p=0, cin=c, cout=c, relu=0, in0=in0, in1=-1)
 
 
 def _chain(spec, cin):
@@ -109,22 +135,107 @@ def resnet50_trunk():
     return layers
 
 
+def alexnet(n_classes=1000, width=1.0):
+    """AlexNet-style stack in one tower (Table 3, REC_1): 5 convolutions (11x11 s4, 5x5, three 3x3), LRN over 5
+    channels after the first two, three 3x3 s2 max-poolings, three fully-connected layers and a softmax.
+    `width` scales every channel count (tests use a narrow copy)."""
+    c = lambda v: max(8, int(v * width) // 8 * 8)
+    L = []
+    L.append(_conv(3, c(96), 11, 4, 0, True, 0))
+    L.append(_lrn(c(96), 5, len(L), alpha=1e-4, beta=0.75, kappa=2.0))
+    L.append(_pool(c(96), 3, 2, 0, len(L)))
+    L.append(_conv(c(96), c(256), 5, 1, 2, True, len(L)))
+    L.append(_lrn(c(256), 5, len(L), alpha=1e-4, beta=0.75, kappa=2.0))
+    L.append(_pool(c(256), 3, 2, 0, len(L)))
+    L.append(_conv(c(256), c(384), 3, 1, 1, True, len(L)))
+    L.append(_conv(c(384), c(384), 3, 1, 1, True, len(L)))
+    L.append(_conv(c(384), c(256), 3, 1, 1, True, len(L)))
+    L.append(_pool(c(256), 3, 2, 0, len(L)))
+    L.append(_fc(c(256), c(4096), True, len(L)))
+    L.append(_fc(c(4096), c(4096), True, len(L)))
+    L.append(_fc(c(4096), n_classes, False, len(L)))
+    L.append(_softmax(n_classes, len(L)))
+    return L
+
+
+def googlenet(n_classes=1000, width=1.0):
+    """GoogLeNet-style stack (Table 3, REC_2): stem, nine inception modules (four branches joined by a concat),
+    global average pooling, one fully-connected layer and a softmax: 57 convolutions.  Poolings use zero padding
+    where the published network rounds the output size up."""
+    c = lambda v: max(8, int(v * width) // 8 * 8)
+    L = []
+    L.append(_conv(3, c(64), 7, 2, 3, True, 0))
+    L.append(_pool(c(64), 3, 2, 1, len(L)))
+    L.append(_lrn(c(64), 5, len(L)))
+    L.append(_conv(c(64), c(64), 1, 1, 0, True, len(L)))
+    L.append(_conv(c(64), c(192), 3, 1, 1, True, len(L)))
+    L.append(_lrn(c(192), 5, len(L)))
+    L.append(_pool(c(192), 3, 2, 1, len(L)))
+    x, cin = len(L), c(192)
+
+    def inception(x, cin, n1, n3r, n3, n5r, n5, npj):
+        L.append(_conv(cin, c(n1), 1, 1, 0, True, x)); b1 = len(L)
+        L.append(_conv(cin, c(n3r), 1, 1, 0, True, x))
+        L.append(_conv(c(n3r), c(n3), 3, 1, 1, True, len(L))); b2 = len(L)
+        L.append(_conv(cin, c(n5r), 1, 1, 0, True, x))
+        L.append(_conv(c(n5r), c(n5), 5, 1, 2, True, len(L))); b3 = len(L)
+        L.append(_pool(cin, 3, 1, 1, x))
+        L.append(_conv(cin, c(npj), 1, 1, 0, True, len(L))); b4 = len(L)
+        cs = [c(n1), c(n3), c(n5), c(npj)]
+        L.append(_concat(cs, [b1, b2, b3, b4]))
+        return len(L), sum(cs)
+
+    x, cin = inception(x, cin, 64, 96, 128, 16, 32, 32)
+    x, cin = inception(x, cin, 128, 128, 192, 32, 96, 64)
+    L.append(_pool(cin, 3, 2, 1, x)); x = len(L)
+    x, cin = inception(x, cin, 192, 96, 208, 16, 48, 64)
+    x, cin = inception(x, cin, 160, 112, 224, 24, 64, 64)
+    x, cin = inception(x, cin, 128, 128, 256, 24, 64, 64)
+    x, cin = inception(x, cin, 112, 144, 288, 32, 64, 64)
+    x, cin = inception(x, cin, 256, 160, 320, 32, 128, 128)
+    L.append(_pool(cin, 3, 2, 1, x)); x = len(L)
+    x, cin = inception(x, cin, 256, 160, 320, 32, 128, 128)
+    x, cin = inception(x, cin, 384, 192, 384, 48, 128, 128)
+    L.append(dict(_avgpool(cin, 7, 1, 0, x), k=-1)); x = len(L)     # k = -1: replaced by the map size (global pooling)
+    L.append(_fc(cin, n_classes, False, x))
+    L.append(_softmax(n_classes, len(L)))
+    return L
+
+
+def resolve_global_pooling(layers, H, W, C):
+    """Layer tables may mark a pooling as global with k = -1: returns a copy with the map size filled in."""
+    out = []
+    shapes = [(H, W, C)]
+    for L in layers:
+        L = dict(L)
+        h, w, _ = shapes[L["in0"]]
+        if L["type"] in (MAXPOOL, AVGPOOL) and L["k"] < 0:
+            assert h == w, "global pooling of a square map"
+            L["k"], L["s"], L["p"] = h, 1, 0
+        out.append(L)
+        shapes.append(tensor_shapes([dict(L, in0=0)], h, w, shapes[L["in0"]][2])[1])
+    return out
+
+
 def tensor_shapes(layers, H, W, C):
     """(H, W, C) of every tensor; tensor 0 is the input, tensor i+1 is layer i's output."""
     shapes = [(H, W, C)]
     for L in layers:
         h, w, _ = shapes[L["in0"]]
-        if L["type"] in (CONV, MAXPOOL):
+        if L["type"] in (CONV, MAXPOOL, AVGPOOL):
             ho = (h + 2 * L["p"] - L["k"]) // L["s"] + 1
             wo = (w + 2 * L["p"] - L["k"]) // L["s"] + 1
             shapes.append((ho, wo, L["cout"]))
+        elif L["type"] == FC:
+            shapes.append((1, 1, L["cout"]))
         else:
             shapes.append((h, w, L["cout"]))
     return shapes
 
 
-def he_weights(layers, seed, bias_scale=0.0, residual_scale=1.0):
-    """He-normal weights N(0, 2/(cin*k*k)) in [cout][k][k][cin] order and biases.
+def he_weights(layers, seed, bias_scale=0.0, residual_scale=1.0, input_shape=None):
+    """He-normal weights N(0, 2/(cin*k*k)) in [cout][k][k][cin] order and biases; a fully-connected layer gets
+    [cout][h*w*cin] with variance 2/(h*w*cin), for which `input_shape` = (H, W, C) of tensor 0 is needed.
 
     `residual_scale` multiplies the conv that feeds in0 of every ADD layer (keeps
     activations of deep residual stacks in a tame range without normalisation layers).
@@ -132,7 +243,13 @@ def he_weights(layers, seed, bias_scale=0.0, residual_scale=1.0):
     rng = np.random.default_rng(seed)
     feeds_add = {L["in0"] - 1 for L in layers if L["type"] == ADD}
     ws, bs = [], []
+    shapes = tensor_shapes(layers, *input_shape) if input_shape is not None else None
     for i, L in enumerate(layers):
+        if L["type"] == FC:
+            K = int(np.prod(shapes[L["in0"]]))
+            ws.append(np.ascontiguousarray(rng.standard_normal((L["cout"], K)) * np.sqrt(2.0 / K), dtype=np.float32))
+            bs.append(np.ascontiguousarray(rng.standard_normal(L["cout"]) * bias_scale, dtype=np.float32))
+            continue
         if L["type"] != CONV:
             ws.append(None)
             bs.append(None)

@@ -326,3 +326,57 @@ def test_uncached_layers(oracle, bf16):
     assert np.array_equal(got, oracle.frame_to_tensor(f))
     got = _to_np(binding.dc_frame_to_tensor(torch.from_numpy(f).to(DEV), dt, c_tensor=8))
     assert np.array_equal(got[..., :3], oracle.frame_to_tensor(f)) and not got[..., 3:].any()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_lrn_avgpool_concat_softmax_layers(oracle, bf16):
+    """The un-cached layer types of Table 2 besides pooling and add, each against the oracle."""
+    print(f"[more layers] bf16={bf16}", flush=True)
+    rng = np.random.default_rng(9)
+    tol = 2e-2 if bf16 else 1e-4
+    n = 2
+    x = (rng.standard_normal((n, 13, 17, 24)) * 2).astype(np.float32)
+    if bf16:
+        x = oracle.round_bf16(x)
+    xd = _to_dev(x, bf16)
+    for size, within in [(5, False), (3, False), (1, False), (3, True), (5, True)]:
+        got = _to_np(binding.dc_lrn_layer(xd, size, 0.5, 0.75, 2.0, within))
+        for i in range(n):
+            assert _rel_err(got[i], oracle.lrn(x[i], size, 0.5, 0.75, 2.0, within, bf16=bf16)) <= tol, (size, within)
+    for k, s, p in [(3, 2, 1), (2, 2, 0), (13, 1, 0), (5, 3, 2)]:
+        got = _to_np(binding.dc_avgpool_layer(xd, k, s, p))
+        for i in range(n):
+            assert _rel_err(got[i], oracle.avgpool(x[i], k, s, p, bf16=bf16)) <= tol, (k, s, p)
+    for cs in [(24, 8, 16), (24, 3), (5, 7, 24, 1), (8, 8)]:       # whole 16-byte vectors and odd channel counts
+        parts = [np.ascontiguousarray(rng.standard_normal((n, 13, 17, c)).astype(np.float32)) for c in cs]
+        if bf16:
+            parts = [oracle.round_bf16(q) for q in parts]
+        got = _to_np(binding.dc_concat_layer([_to_dev(q, bf16) for q in parts]))
+        for i in range(n):
+            assert np.array_equal(got[i], oracle.concat([q[i] for q in parts])), cs
+    for c in (10, 64, 1000):
+        v = (rng.standard_normal((n, 2, 3, c)) * 4).astype(np.float32)
+        if bf16:
+            v = oracle.round_bf16(v)
+        got = _to_np(binding.dc_softmax_layer(_to_dev(v, bf16)))
+        for i in range(n):
+            want = oracle.softmax(v[i], bf16=bf16)
+            assert np.abs(got[i] - want).max() <= tol * max(float(want.max()), 1e-30), c
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("n,shape,cout", [(1, (6, 6, 32), 100), (3, (5, 5, 7), 33), (20, (1, 1, 256), 64), (5, (2, 3, 24), 1)])
+def test_fully_connected_layer(oracle, n, shape, cout, bf16):
+    print(f"[fc] n={n} shape={shape} cout={cout} bf16={bf16}", flush=True)
+    rng = np.random.default_rng(n * 100 + cout)
+    K = int(np.prod(shape))
+    x = rng.standard_normal((n,) + shape).astype(np.float32)
+    w = (rng.standard_normal((cout, K)) * np.sqrt(2.0 / K)).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    if bf16:
+        x, w = oracle.round_bf16(x), oracle.round_bf16(w)
+    for relu, bias in [(True, b), (False, None)]:
+        got = _to_np(binding.dc_fc_layer(_to_dev(x, bf16), _to_dev(w, bf16), None if bias is None else torch.from_numpy(bias).to(DEV), relu))
+        assert got.shape == (n, 1, 1, cout)
+        want = np.stack([oracle.fc(x[i], w, bias, relu, bf16=bf16) for i in range(n)])
+        assert _rel_err(got, want) <= (2e-2 if bf16 else 1e-4)

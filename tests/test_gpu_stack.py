@@ -20,7 +20,7 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
               residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1):
     """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
     n, T, H, W, C = videos.shape
-    ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale)
+    ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale, input_shape=(H, W, C))
     tol = 2e-2 if bf16 else 1e-4
     dt = binding.DC_BF16 if bf16 else binding.DC_F32
     runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
@@ -116,6 +116,24 @@ def test_diamond_search_in_the_whole_path(oracle, k_skip):
 def test_exhaustive_search_with_k_skip_in_the_whole_path(oracle):
     f1, f2 = synth.tiny_pair(0)
     _run_both(oracle, synth.tiny_net(), np.stack([f1, f2, f2, f1])[None], 8, 8, False, k_skip=2)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_alexnet_style_stack_small(oracle, bf16):
+    """Every layer type of Table 2 in one stack: 11x11 stride-4 first layer, LRN, pooling, fully-connected, softmax
+    (a narrow AlexNet at its 227x227 input size; the paper's 10-pixel blocks)."""
+    layers = synth.alexnet(n_classes=40, width=0.25)
+    video = np.stack([synth.panning_video(300 + s, n_frames=3, H=227, W=227) for s in range(2)])
+    runner, reuse = _run_both(oracle, layers, video, 10, 8, bf16)
+    assert len(reuse) == 4 and min(reuse) > 0.2
+
+
+def test_googlenet_style_stack_small(oracle):
+    """Inception modules: four branches of different depth joined by a concat; global average pooling at the end."""
+    layers = synth.resolve_global_pooling(synth.googlenet(n_classes=24, width=0.25), 224, 224, 3)
+    assert sum(L["type"] == synth.CONV for L in layers) == 57
+    video = np.stack([synth.panning_video(400 + s, n_frames=3, H=224, W=224) for s in range(1)])
+    _run_both(oracle, layers, video, 16, 8, True)
 
 
 def test_vgg16_two_streams_bf16_small(oracle):

@@ -173,3 +173,93 @@ def test_host_regions_equal_oracle_on_random_layer_tables(oracle):
         mask = (rng.random((gh, gw)) < rng.choice([0.5, 0.8, 0.95, 1.0])).astype(np.uint8)
         mx, my = int(rng.integers(-2 * B, 2 * B + 1)), int(rng.integers(-2 * B, 2 * B + 1))
         _compare(oracle, layers, H, W, B, mask, mx, my)
+
+
+def _random_layers_all_types(rng, H, W):
+    """As _random_layers, with LRN (both windows), average pooling, concats of 2-4 earlier tensors of the current
+    spatial size, and sometimes a fully-connected / softmax tail."""
+    layers, shapes = [], [(H, W, 8)]
+    for _ in range(int(rng.integers(4, 11))):
+        a = len(shapes) - 1
+        h, w, c = shapes[a]
+        kind = rng.choice(["conv", "conv", "pool", "avg", "lrn", "lrnw", "concat", "concat", "relu"])
+        if kind == "concat":
+            same = [t for t in range(1, len(shapes)) if shapes[t][:2] == (h, w)]
+            if len(same) < 2:
+                kind = "conv"
+            else:
+                m = int(rng.integers(2, min(4, len(same)) + 1))
+                ins = [int(t) for t in rng.choice(same, size=m, replace=False)]
+                cs = [shapes[t][2] for t in ins]
+                layers.append(synth._concat(cs, ins))
+                shapes.append((h, w, sum(cs)))
+                continue
+        if kind in ("lrn", "lrnw"):
+            size = int(rng.choice([1, 3, 5]))
+            layers.append(synth._lrn(c, size, a, within=(kind == "lrnw")))
+            shapes.append((h, w, c))
+            continue
+        if kind == "relu":
+            layers.append(dict(type=synth.RELU, k=1, s=1, p=0, cin=c, cout=c, relu=1, in0=a, in1=-1))
+            shapes.append((h, w, c))
+            continue
+        k = int(rng.choice([1, 2, 3, 3, 5]))
+        s_ = int(rng.choice([1, 1, 2]))
+        p_ = int(rng.integers(0, k))
+        if h + 2 * p_ < k or w + 2 * p_ < k:
+            k, s_, p_ = 1, 1, 0
+        ho, wo = (h + 2 * p_ - k) // s_ + 1, (w + 2 * p_ - k) // s_ + 1
+        if kind in ("pool", "avg"):
+            layers.append((synth._pool if kind == "pool" else synth._avgpool)(c, k, s_, p_, a))
+            shapes.append((ho, wo, c))
+        else:
+            co = int(rng.choice([8, 16]))
+            layers.append(synth._conv(c, co, k, s_, p_, True, a))
+            shapes.append((ho, wo, co))
+    if rng.random() < 0.5:
+        c = shapes[-1][2]
+        layers.append(synth._fc(c, 12, True, len(layers)))
+        layers.append(dict(type=synth.RELU, k=1, s=1, p=0, cin=12, cout=12, relu=1, in0=len(layers), in1=-1))
+        layers.append(synth._softmax(12, len(layers)))
+    return layers
+
+
+def test_host_regions_equal_oracle_with_every_layer_type(oracle):
+    rng = np.random.default_rng(77)
+    seen = set()
+    for trial in range(80):
+        H, W, B = int(rng.integers(24, 90)), int(rng.integers(24, 90)), int(rng.choice([4, 5, 8]))
+        layers = _random_layers_all_types(rng, H, W)
+        seen |= {L["type"] for L in layers}
+        gh, gw = H // B, W // B
+        mask = (rng.random((gh, gw)) < rng.choice([0.6, 0.9, 1.0])).astype(np.uint8)
+        mx, my = int(rng.integers(-B, B + 1)), int(rng.integers(-B, B + 1))
+        _compare(oracle, layers, H, W, B, mask, mx, my)
+    assert seen >= {synth.CONV, synth.MAXPOOL, synth.AVGPOOL, synth.LRN, synth.CONCAT, synth.FC, synth.SOFTMAX}
+    for net, H in ((synth.alexnet(), 227), (synth.resolve_global_pooling(synth.googlenet(), 224, 224, 3), 224)):
+        gh = H // 16
+        mask = np.ones((gh, gh), np.uint8)
+        mask[3:5, 2:9] = 0
+        _compare(oracle, net, H, H, 16, mask, 5, -3)
+
+
+def test_layer_table_validation_of_the_new_types():
+    L = binding.lib()
+    one = C.c_void_p(16)
+    regs, keep = binding._alloc_regions(4, 8)
+    mask = np.ones((4, 4), np.uint8)
+
+    def status(layers):
+        return L.dc_propagate_regions(binding.layers_to_c(layers), len(layers), 32, 32, 8, mask.ctypes.data_as(C.c_void_p),
+                                      4, 4, 0, 0, regs)
+    conv = synth._conv(3, 8, 3, 1, 1, True, 0)
+    assert status([conv, synth._lrn(8, 5, 1)]) == 0
+    assert status([conv, synth._lrn(8, 4, 1)]) == -1                                    # even window
+    assert status([conv, synth._lrn(16, 5, 1)]) == -3                                   # channel mismatch
+    assert status([conv, conv, synth._concat([8, 8], [1, 2])]) == 0
+    assert status([conv, conv, synth._concat([8, 4], [1, 2])]) == -3                    # wrong channel sum
+    assert status([conv, conv, dict(synth._concat([8, 8], [1, 2]), in2=-1, in3=1)]) == -3   # in3 without in2
+    assert status([conv, synth._pool(8, 2, 2, 0, 1), synth._concat([8, 8], [1, 2])]) == -3   # sizes differ
+    assert status([conv, synth._fc(8, 10, False, 1), synth._softmax(10, 2)]) == 0
+    assert status([conv, synth._fc(4, 10, False, 1)]) == -3
+    assert status([conv, synth._avgpool(8, 3, 2, 3, 1)]) == -1                          # padding >= kernel
