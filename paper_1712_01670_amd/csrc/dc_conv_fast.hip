@@ -744,10 +744,14 @@ template <typename T, int NB>
 __global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) { conv_first_body<T, NB, 3, 1>(P); }
 template <typename T, int NB>
 __global__ __launch_bounds__(256) void conv_stem_kernel(ConvParams P) { conv_first_body<T, NB, 7, 2>(P); }
+// 11x11 stride 4 (the first layer of AlexNet-style stacks): 33 weight vectors per channel block stay in registers
+template <typename T>
+__global__ __launch_bounds__(256) void conv_stem11_kernel(ConvParams P) { conv_first_body<T, 1, 11, 4>(P); }
 
 template <typename T>
 hipError_t first_launch(int k, int nb, dim3 grid, hipStream_t st, const ConvParams& P) {
-    if (k == 7) {
+    if (k == 11) hipLaunchKernelGGL((conv_stem11_kernel<T>), grid, dim3(256), 0, st, P);
+    else if (k == 7) {
         if (nb == 2) hipLaunchKernelGGL((conv_stem_kernel<T, 2>), grid, dim3(256), 0, st, P);
         else hipLaunchKernelGGL((conv_stem_kernel<T, 1>), grid, dim3(256), 0, st, P);
     }
@@ -930,6 +934,10 @@ void conv_fast_kernel_name(int id, char* buf, size_t n) {
         snprintf(buf, n, "conv_fast_kernel<__hip_bfloat16, 3, %d, %d, 4, 2, %d>", 32 << (v / 4), v % 4 + 1, wide64 ? 2 : 4);
         return;
     }
+    if (id == 106 || id == 107) {     // 106 + bf16: conv_stem11_kernel (11x11 stride 4)
+        snprintf(buf, n, "conv_stem11_kernel<%s>", id == 107 ? "__hip_bfloat16" : "float");
+        return;
+    }
     if (id >= 102 && id < 106) {   // 102 + bf16 * 2 + {0, 1}: conv_stem_kernel (7x7 stride 2) with 1, 2 channel blocks
         snprintf(buf, n, "conv_stem_kernel<%s, %d>", (id - 102) / 2 ? "__hip_bfloat16" : "float", 1 << ((id - 102) % 2));
         return;
@@ -980,7 +988,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     static int enabled = -1;
     if (enabled < 0) { const char* e = getenv("DC_CONV_FAST"); enabled = e ? atoi(e) : 1; }
     const size_t esz = dtype_size(c.dtype);
-    if (enabled && ((c.k == 3 && c.s == 1) || (c.k == 7 && c.s == 2)) && c.Cin * esz == 16 && c.Cout % 16 == 0 &&
+    if (enabled && ((c.k == 3 && c.s == 1) || (c.k == 7 && c.s == 2) || (c.k == 11 && c.s == 4)) && c.Cin * esz == 16 && c.Cout % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
         const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
@@ -996,10 +1004,11 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
             P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * 16);
             P.w_bytes = (uint32_t)((size_t)c.Cout * c.k * c.k * 16);
             // the 7x7 kernel keeps 14 weight vectors per channel block in registers: two blocks at most
-            const int nb = c.Cout % 64 == 0 && c.k == 3 ? 4 : (c.Cout % 32 == 0 ? 2 : 1);
+            const int nb = c.k == 11 ? 1 : (c.Cout % 64 == 0 && c.k == 3 ? 4 : (c.Cout % 32 == 0 ? 2 : 1));
             const long wgx = (n_units + 3) / 4 < 2048 ? (n_units + 3) / 4 : 2048;   // four units at a time, at most 8 workgroups per CU
             if (c.kernel_id)
-                *c.kernel_id = c.k == 7 ? 102 + (c.dtype == DC_BF16 ? 2 : 0) + (nb == 2 ? 1 : 0)
+                *c.kernel_id = c.k == 11 ? 106 + (c.dtype == DC_BF16 ? 1 : 0)
+                             : c.k == 7 ? 102 + (c.dtype == DC_BF16 ? 2 : 0) + (nb == 2 ? 1 : 0)
                                         : 96 + (c.dtype == DC_BF16 ? 3 : 0) + (nb == 4 ? 2 : (nb == 2 ? 1 : 0));
             const dim3 grid((unsigned)wgx, (unsigned)(c.Cout / (16 * nb)));
             *err = c.dtype == DC_BF16 ? first_launch<__hip_bfloat16>(c.k, nb, grid, st, P) : first_launch<float>(c.k, nb, grid, st, P);

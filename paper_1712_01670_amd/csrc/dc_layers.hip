@@ -186,20 +186,6 @@ __global__ __launch_bounds__(kThreads) void lrn_kernel(const T* __restrict__ in,
     }
 }
 
-// out[pixel][off + c] = in[pixel][c], c < cj: one input of a concatenation along the channel axis.  V is the unit
-// moved per thread (16 bytes when every channel count involved is a whole number of them, else one element).
-template <typename V>
-__global__ __launch_bounds__(kThreads) void concat_kernel(const V* __restrict__ in, V* __restrict__ out, size_t n_pixels,
-                                                          int cj, int off, int ctot) {
-    const size_t total = n_pixels * cj;
-    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    for (; i < total; i += stride) {
-        const size_t px = i / cj;
-        out[px * ctot + off + (i - px * cj)] = in[i];
-    }
-}
-
 __device__ __forceinline__ float wave_sum_f32(float v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
@@ -284,6 +270,133 @@ __global__ __launch_bounds__(kThreads) void fc_kernel(const T* __restrict__ x, c
     }
 }
 
+// ---- 16-byte vector forms: one thread per (pixel, vector of 4 fp32 / 8 bf16 channels) --------------------------
+template <typename T>
+struct Vec16 {
+    static constexpr int VE = 16 / sizeof(T);
+    static __device__ __forceinline__ void load(const uint4* p, float (&f)[VE]) {
+        const uint4 v = *p;
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(u[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                f[2 * e] = __uint_as_float(u[e] << 16);
+                f[2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
+            }
+        }
+    }
+    static __device__ __forceinline__ void store(uint4* p, const float (&f)[VE]) {
+        uint32_t u[4];
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) u[e] = __float_as_uint(f[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const __hip_bfloat16 lo = __float2bfloat16(f[2 * e]), hi = __float2bfloat16(f[2 * e + 1]);
+                u[e] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+            }
+        }
+        *p = uint4{u[0], u[1], u[2], u[3]};
+    }
+};
+
+// Max or average pooling, CV vectors per pixel.
+template <typename T, bool AVG>
+__global__ __launch_bounds__(kThreads) void pool_vec_kernel(const uint4* __restrict__ in, uint4* __restrict__ out,
+                                                            int n_streams, int Hin, int Win, int CV, int Hout, int Wout,
+                                                            int k, int s, int p) {
+    constexpr int VE = Vec16<T>::VE;
+    const size_t total = (size_t)n_streams * Hout * Wout * CV;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (; i < total; i += stride) {
+        const int cv = (int)(i % CV);
+        const size_t pix = i / CV;
+        const int x = (int)(pix % Wout);
+        const size_t t = pix / Wout;
+        const int y = (int)(t % Hout);
+        const size_t map = (t / Hout) * Hin;
+        float acc[VE];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) acc[e] = AVG ? 0.f : -INFINITY;
+        const int y0 = max(y * s - p, 0), y1 = min(y * s - p + k, Hin), x0 = max(x * s - p, 0), x1 = min(x * s - p + k, Win);
+        for (int iy = y0; iy < y1; ++iy)
+            for (int ix = x0; ix < x1; ++ix) {
+                float f[VE];
+                Vec16<T>::load(in + ((map + iy) * Win + ix) * CV + cv, f);
+#pragma unroll
+                for (int e = 0; e < VE; ++e) acc[e] = AVG ? acc[e] + f[e] : fmaxf(acc[e], f[e]);
+            }
+        if (AVG) {
+            const int cnt = (y1 - y0) * (x1 - x0);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) acc[e] = cnt > 0 ? acc[e] / (float)cnt : 0.f;
+        }
+        Vec16<T>::store(out + i, acc);
+    }
+}
+
+// LRN over channels with radius R <= VE: the thread's vector and its two neighbours hold every channel of the window.
+template <typename T, int R>
+__global__ __launch_bounds__(kThreads) void lrn_vec_kernel(const uint4* __restrict__ in, uint4* __restrict__ out,
+                                                           size_t n_pixels, int CV, float alpha_n, float beta, float kappa) {
+    constexpr int VE = Vec16<T>::VE;
+    static_assert(R <= VE, "window inside the neighbouring vectors");
+    const size_t total = n_pixels * CV;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (; i < total; i += stride) {
+        const int cv = (int)(i % CV);
+        float f[3][VE];
+        Vec16<T>::load(in + i, f[1]);
+        if (cv > 0) Vec16<T>::load(in + i - 1, f[0]);
+        if (cv + 1 < CV) Vec16<T>::load(in + i + 1, f[2]);
+        float sq[3 * VE];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) {
+            sq[e] = cv > 0 ? f[0][e] * f[0][e] : 0.f;
+            sq[VE + e] = f[1][e] * f[1][e];
+            sq[2 * VE + e] = cv + 1 < CV ? f[2][e] * f[2][e] : 0.f;
+        }
+        float o[VE];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) {
+            float S = 0.f;
+#pragma unroll
+            for (int d = -R; d <= R; ++d) S += sq[VE + e + d];
+            o[e] = f[1][e] * __powf(kappa + alpha_n * S, -beta);
+        }
+        Vec16<T>::store(out + i, o);
+    }
+}
+
+// All inputs of a concatenation in one launch: a thread moves one unit of V of the output and finds the input it
+// comes from by its channel offset.
+struct ConcatArgs {
+    const void* in[4];
+    int c[4], off[4];     // channel count and first output channel of each input, in units of V
+    int n, ctot;
+};
+template <typename V>
+__global__ __launch_bounds__(kThreads) void concat_all_kernel(ConcatArgs a, V* __restrict__ out, size_t n_pixels) {
+    const size_t total = n_pixels * a.ctot;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (; i < total; i += stride) {
+        const size_t px = i / a.ctot;
+        const int c = (int)(i - px * a.ctot);
+        int j = 0;
+        if (a.n > 1 && c >= a.off[1]) j = 1;
+        if (a.n > 2 && c >= a.off[2]) j = 2;
+        if (a.n > 3 && c >= a.off[3]) j = 3;
+        out[i] = static_cast<const V*>(a.in[j])[px * a.c[j] + (c - a.off[j])];
+    }
+}
+
 inline int grid_for(size_t n, int cap = 256 * 16) {
     size_t g = (n + kThreads - 1) / kThreads;
     return (int)(g < 1 ? 1 : (g > (size_t)cap ? cap : g));
@@ -353,6 +466,17 @@ hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int
     const int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
     const size_t n = (size_t)n_streams * Hout * Wout * C;
     if (n == 0) return hipSuccess;
+    if ((C * dtype_size(dtype)) % 16 == 0 && reinterpret_cast<uintptr_t>(in) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0) {
+        const int cv = (int)(C * dtype_size(dtype) / 16);
+        const size_t nv = (size_t)n_streams * Hout * Wout * cv;
+        if (dtype == DC_BF16)
+            hipLaunchKernelGGL((pool_vec_kernel<__hip_bfloat16, false>), dim3(grid_for(nv)), dim3(kThreads), 0, st,
+                               (const uint4*)in, (uint4*)out, n_streams, Hin, Win, cv, Hout, Wout, k, s, p);
+        else
+            hipLaunchKernelGGL((pool_vec_kernel<float, false>), dim3(grid_for(nv)), dim3(kThreads), 0, st, (const uint4*)in,
+                               (uint4*)out, n_streams, Hin, Win, cv, Hout, Wout, k, s, p);
+        return hipGetLastError();
+    }
     if (dtype == DC_BF16)
         hipLaunchKernelGGL(maxpool_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st,
                            (const __hip_bfloat16*)in, (__hip_bfloat16*)out, n_streams, Hin, Win, C, Hout, Wout,
@@ -368,6 +492,17 @@ hipError_t launch_avgpool(const void* in, void* out, int n_streams, int Hin, int
     const int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
     const size_t n = (size_t)n_streams * Hout * Wout * C;
     if (n == 0) return hipSuccess;
+    if ((C * dtype_size(dtype)) % 16 == 0 && reinterpret_cast<uintptr_t>(in) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0) {
+        const int cv = (int)(C * dtype_size(dtype) / 16);
+        const size_t nv = (size_t)n_streams * Hout * Wout * cv;
+        if (dtype == DC_BF16)
+            hipLaunchKernelGGL((pool_vec_kernel<__hip_bfloat16, true>), dim3(grid_for(nv)), dim3(kThreads), 0, st,
+                               (const uint4*)in, (uint4*)out, n_streams, Hin, Win, cv, Hout, Wout, k, s, p);
+        else
+            hipLaunchKernelGGL((pool_vec_kernel<float, true>), dim3(grid_for(nv)), dim3(kThreads), 0, st, (const uint4*)in,
+                               (uint4*)out, n_streams, Hin, Win, cv, Hout, Wout, k, s, p);
+        return hipGetLastError();
+    }
     if (dtype == DC_BF16)
         hipLaunchKernelGGL(avgpool_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st,
                            (const __hip_bfloat16*)in, (__hip_bfloat16*)out, n_streams, Hin, Win, C, Hout, Wout,
@@ -384,6 +519,18 @@ hipError_t launch_lrn(const void* in, void* out, int n_streams, int H, int W, in
     if (n == 0) return hipSuccess;
     const int r = (size - 1) / 2;
     const float alpha_n = alpha / (within ? (float)size * (float)size : (float)size);
+    if (!within && (r == 1 || r == 2) && (C * dtype_size(dtype)) % 16 == 0 && reinterpret_cast<uintptr_t>(in) % 16 == 0 &&
+        reinterpret_cast<uintptr_t>(out) % 16 == 0) {
+        const int cv = (int)(C * dtype_size(dtype) / 16);
+        const size_t px = (size_t)n_streams * H * W;
+        const dim3 grid(grid_for(px * cv));
+#define DC_LRN_VEC(T, R) hipLaunchKernelGGL((lrn_vec_kernel<T, R>), grid, dim3(kThreads), 0, st, (const uint4*)in, \
+                                            (uint4*)out, px, cv, alpha_n, beta, kappa)
+        if (dtype == DC_BF16) { if (r == 1) DC_LRN_VEC(__hip_bfloat16, 1); else DC_LRN_VEC(__hip_bfloat16, 2); }
+        else { if (r == 1) DC_LRN_VEC(float, 1); else DC_LRN_VEC(float, 2); }
+#undef DC_LRN_VEC
+        return hipGetLastError();
+    }
     if (dtype == DC_BF16)
         hipLaunchKernelGGL(lrn_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st,
                            (const __hip_bfloat16*)in, (__hip_bfloat16*)out, n_streams, H, W, C, r, within, alpha_n, beta,
@@ -404,25 +551,19 @@ hipError_t launch_concat(const void* const* ins, const int* cs, int n_in, void* 
         vec = vec && (cs[j] * es) % 16 == 0 && reinterpret_cast<uintptr_t>(ins[j]) % 16 == 0;
     }
     if (n_pixels == 0) return hipSuccess;
+    const int unit = vec ? (int)(16 / es) : 1;        // elements per moved unit
+    ConcatArgs a{};
+    a.n = n_in; a.ctot = ctot / unit;
     int off = 0;
     for (int j = 0; j < n_in; ++j) {
-        const size_t n = n_pixels * cs[j];
-        if (vec) {
-            const int ve = (int)(16 / es);
-            hipLaunchKernelGGL(concat_kernel<uint4>, dim3(grid_for(n / ve)), dim3(kThreads), 0, st, (const uint4*)ins[j],
-                               (uint4*)out, n_pixels, cs[j] / ve, off / ve, ctot / ve);
-        } else if (dtype == DC_BF16) {
-            hipLaunchKernelGGL(concat_kernel<uint16_t>, dim3(grid_for(n)), dim3(kThreads), 0, st, (const uint16_t*)ins[j],
-                               (uint16_t*)out, n_pixels, cs[j], off, ctot);
-        } else {
-            hipLaunchKernelGGL(concat_kernel<uint32_t>, dim3(grid_for(n)), dim3(kThreads), 0, st, (const uint32_t*)ins[j],
-                               (uint32_t*)out, n_pixels, cs[j], off, ctot);
-        }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+        a.in[j] = ins[j]; a.c[j] = cs[j] / unit; a.off[j] = off / unit;
         off += cs[j];
     }
-    return hipSuccess;
+    const dim3 grid(grid_for(n_pixels * a.ctot));
+    if (vec) hipLaunchKernelGGL(concat_all_kernel<uint4>, grid, dim3(kThreads), 0, st, a, (uint4*)out, n_pixels);
+    else if (dtype == DC_BF16) hipLaunchKernelGGL(concat_all_kernel<uint16_t>, grid, dim3(kThreads), 0, st, a, (uint16_t*)out, n_pixels);
+    else hipLaunchKernelGGL(concat_all_kernel<uint32_t>, grid, dim3(kThreads), 0, st, a, (uint32_t*)out, n_pixels);
+    return hipGetLastError();
 }
 
 hipError_t launch_softmax(const void* in, void* out, size_t n_pixels, int C, int dtype, hipStream_t st) {

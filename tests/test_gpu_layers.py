@@ -261,14 +261,16 @@ def test_first_layer_kernel(oracle, cout, bf16, cached):
 @pytest.mark.parametrize("cached", [False, True])
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("cout", [16, 64, 96])
-def test_stem_kernel(oracle, cout, bf16, cached):
-    """7x7 stride-2 convolution over 16-byte input pixels (the stem of the residual networks); odd and even sizes,
-    so that the last output row reads past the input on one side only."""
-    H, W = 45, 54
-    k, s, p = 7, 2, 3
+@pytest.mark.parametrize("geom", [(7, 2, 3), (11, 4, 0), (11, 4, 2)])
+def test_stem_kernel(oracle, geom, cout, bf16, cached):
+    """7x7 stride-2 and 11x11 stride-4 convolutions over 16-byte input pixels (the first layers of the residual and
+    the AlexNet-style networks); odd and even sizes, so that the last output row reads past the input on one side
+    only."""
+    H, W = (45, 54) if geom[0] == 7 else (75, 91)
+    k, s, p = geom
     Ho, Wo = (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1
     cin = 8 if bf16 else 4
-    print(f"[stem] cout={cout} bf16={bf16} cached={cached}", flush=True)
+    print(f"[stem] geom={geom} cout={cout} bf16={bf16} cached={cached}", flush=True)
     rng = np.random.default_rng(cout + 11)
     n = 2
     x = rng.standard_normal((n, H, W, cin)).astype(np.float32)
@@ -335,18 +337,22 @@ def test_lrn_avgpool_concat_softmax_layers(oracle, bf16):
     rng = np.random.default_rng(9)
     tol = 2e-2 if bf16 else 1e-4
     n = 2
-    x = (rng.standard_normal((n, 13, 17, 24)) * 2).astype(np.float32)
-    if bf16:
-        x = oracle.round_bf16(x)
-    xd = _to_dev(x, bf16)
-    for size, within in [(5, False), (3, False), (1, False), (3, True), (5, True)]:
-        got = _to_np(binding.dc_lrn_layer(xd, size, 0.5, 0.75, 2.0, within))
-        for i in range(n):
-            assert _rel_err(got[i], oracle.lrn(x[i], size, 0.5, 0.75, 2.0, within, bf16=bf16)) <= tol, (size, within)
-    for k, s, p in [(3, 2, 1), (2, 2, 0), (13, 1, 0), (5, 3, 2)]:
-        got = _to_np(binding.dc_avgpool_layer(xd, k, s, p))
-        for i in range(n):
-            assert _rel_err(got[i], oracle.avgpool(x[i], k, s, p, bf16=bf16)) <= tol, (k, s, p)
+    for ch in (24, 7, 8):          # whole 16-byte vectors per pixel (several, one) and an odd channel count
+        x = (rng.standard_normal((n, 13, 17, ch)) * 2).astype(np.float32)
+        if bf16:
+            x = oracle.round_bf16(x)
+        xd = _to_dev(x, bf16)
+        for size, within in [(5, False), (3, False), (1, False), (7, False), (3, True), (5, True)]:
+            got = _to_np(binding.dc_lrn_layer(xd, size, 0.5, 0.75, 2.0, within))
+            for i in range(n):
+                assert _rel_err(got[i], oracle.lrn(x[i], size, 0.5, 0.75, 2.0, within, bf16=bf16)) <= tol, (ch, size, within)
+        for k, s, p in [(3, 2, 1), (2, 2, 0), (13, 1, 0), (5, 3, 2)]:
+            got = _to_np(binding.dc_avgpool_layer(xd, k, s, p))
+            for i in range(n):
+                assert _rel_err(got[i], oracle.avgpool(x[i], k, s, p, bf16=bf16)) <= tol, (ch, k, s, p)
+            got = _to_np(binding.dc_maxpool_layer(xd, k, s, p))
+            for i in range(n):
+                assert np.array_equal(got[i], oracle.maxpool(x[i], k, s, p)), (ch, k, s, p)
     for cs in [(24, 8, 16), (24, 3), (5, 7, 24, 1), (8, 8)]:       # whole 16-byte vectors and odd channel counts
         parts = [np.ascontiguousarray(rng.standard_normal((n, 13, 17, c)).astype(np.float32)) for c in cs]
         if bf16:
