@@ -260,7 +260,7 @@ int32_t dc_conv_tuning(int32_t arrangement, int32_t units_per_workgroup, int32_t
 
 int32_t dc_conv_kernel_name(int32_t kernel_id, char* buf, size_t n) {
     if (!buf) return DC_ERR_NULL_PTR;
-    if (n < 2 || kernel_id < 0 || kernel_id >= 127) return DC_ERR_INVALID_ARG;
+    if (n < 2 || kernel_id < 0 || kernel_id >= 129) return DC_ERR_INVALID_ARG;
     conv_kernel_name(kernel_id, buf, n);
     return DC_OK;
 }

@@ -52,6 +52,7 @@ struct ConvParams {
     int chunks_per_split;
     float* partial;         // ks > 1: [ks][n_units][16 pixels][Cout] partial sums
     int w_packed;           // 1: w is the packed layout [Cout/16][Cin*es/64][k*k][16][64 bytes]
+    int n_wg_tiles, tiles_per_xcd;   // 1x1 kernel: (unit group, channel tile) pairs in all, and per XCD
 };
 
 template <typename T>

@@ -613,6 +613,202 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uintx4* src, ui
     dst[idx] = src[((blk * 16 + n16) * 9 + tap) * ((size_t)nc64 * 4) + (size_t)c64 * 4 + v];
 }
 
+// ---- 1x1 convolutions ----------------------------------------------------------------------------
+// A 1x1 layer is a plain GEMM [pixels][Cin] x [Cin][Cout] with nothing to reuse between taps, so it is bound by
+// memory (large maps, small K) or by the latency of its K loop (small maps, deep K: a stage is 16 KiB of loads
+// for 8 MFMAs per wavefront).  A workgroup of four wavefronts takes 4 units (64 pixels) x 64 channels and walks K
+// in chunks of 128 bytes per row through a ring of up to NSTG LDS stages that are filled NSTG - 1 chunks ahead
+// (buffer_load ... lds, one barrier per chunk); with 16 KiB per stage several workgroups share a CU and cover
+// each other's waits.  Rows of 128 bytes, chunk c of row r at position c ^ (r / 2) % 8: the 16 rows a fragment
+// read touches spread over all banks.  Stride 1 or 2 (a strided 1x1 projection reads every second pixel).
+// Weight row l16 of block j of a wavefront carries channel (l16 / 4) * 8 + 4 j + l16 % 4 of its 32, so that a lane
+// ends up with eight consecutive channels of one pixel and stores 16 (bf16) or 32 (fp32) contiguous bytes.
+// Cin only has to be a whole number of 16-byte vectors (the last chunk is filled with zeros), Cout a multiple of 8.
+// Workgroups are numbered so that the channel tiles of one unit group run on the same XCD at about the same time:
+// the second to last of them find the input pixels in that XCD's L2.
+template <typename T, int NSTG>
+__global__ __launch_bounds__(256) void conv_pw_kernel(ConvParams P) {
+    typedef Frag<T> F;
+    typedef typename F::vec vec;
+    constexpr int ES = (int)sizeof(T), VE = F::VE;
+    constexpr int RB = 128, KC = RB / ES, GPC = 2;
+    constexpr int G = 4, NT = 64, UPW = 2, NBW = 2, WN = 2, NW = 4;
+    constexpr int PBYTES = G * 16 * RB;             // patch rows of a stage, then the weight rows
+    constexpr int STAGE = PBYTES + NT * RB;
+    constexpr int D = NSTG - 1;                     // chunks in flight ahead of the one being multiplied
+    static_assert(NSTG == 2 || NSTG == 4 || NSTG == 8, "ring size");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const FastHeader<G> H(smem);
+    unsigned char* const ring = smem + kHeaderBytes;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_n = wave % WN, wave_m = wave / WN;
+    const int l16 = lane & 15, q = lane >> 4;
+
+    const int t = (int)(blockIdx.x & 7) * P.tiles_per_xcd + (int)(blockIdx.x >> 3);
+    if (t >= P.n_wg_tiles) return;                  // the whole workgroup, before any barrier
+    const int ug = t / P.R, ntile = t - ug * P.R;
+    const int n0 = ntile * NT;
+    const int CinES = P.Cin * ES;
+    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.in), 0, P.in_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.w), 0, P.w_bytes, kBufferFlags);
+
+    // unit table: uq = {byte offset of the input pixel under the unit's first output pixel, row and column of
+    // that output pixel, element offset of it in the output}
+    if (tid < G) {
+        const int u = ug * G + tid;
+        const bool valid = u < P.n_units;
+        int stream = 0, uy = 0, ux = 0, mixed = 0;
+        if (valid) {
+            if (P.units) {
+                const TileDev td = P.units[u];
+                stream = td.stream; uy = td.ty; ux = td.tx; mixed = td.reuse_mask;
+            } else {
+                stream = fast_div(u, P.npix_magic);
+                const int r = u - stream * (P.units_x * P.units_y);
+                uy = fast_div(r, P.pw_magic); ux = r - uy * P.units_x;
+            }
+        }
+        int4 v;
+        v.x = ((stream * P.Hin + uy * 4 * P.s) * P.Win + ux * 4 * P.s) * CinES;
+        v.y = valid ? uy * 4 : (1 << 24);           // every pixel of a missing unit fails the range test
+        v.z = ux * 4;
+        v.w = ((stream * P.Hout + uy * 4) * P.Wout + ux * 4) * P.Cout;
+        H.uq[tid] = v;
+        H.ukind[tid] = valid ? mixed : -1;
+    }
+    __syncthreads();
+    if (tid < G * 16) {
+        const int g = tid >> 4, kind = H.ukind[g];
+        const int y = H.uq[g].y + ((tid >> 2) & 3), x = H.uq[g].z + (tid & 3);
+        H.skip[tid] = (kind < 0 || y >= P.Hout || x >= P.Wout || ((kind >> (tid & 15)) & 1)) ? 1 : 0;
+    }
+    __syncthreads();
+
+    // load side: instruction j of a stage fills its LDS bytes [1024 j, 1024 j + 1024) = rows 8 j .. 8 j + 7; this
+    // wavefront issues j = wave and wave + 4 of the patch rows and of the weight rows
+    const int lrow = lane >> 3, lpos = lane & 7;
+    uint32_t pgo[2], wgo[2];
+    int lch[2];                                     // first channel (within a chunk) of the vector the lane fetches
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = (wave + i * NW) * 8 + lrow;
+        const int c = lpos ^ ((row >> 1) & 7);
+        lch[i] = c * VE;
+        const int g = row >> 4, oy = (row >> 2) & 3, ox = row & 3;
+        const int4 uq = H.uq[g];
+        const bool ok = uq.y + oy < P.Hout && uq.z + ox < P.Wout;
+        pgo[i] = ok ? (uint32_t)(uq.x + (oy * P.Win + ox) * P.s * CinES + (c << 4)) : kOob;
+        const int ch = n0 + (row >> 5) * 32 + ((row & 15) >> 2) * 8 + ((row >> 4) & 1) * 4 + (row & 3);
+        wgo[i] = ch < P.Cout ? (uint32_t)(ch * CinES + (c << 4)) : kOob;
+    }
+    auto issue = [&](int chunk, int slot) {
+        unsigned char* dst = ring + slot * STAGE + wave * 1024;
+        const int c0 = chunk * KC;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const bool in_k = c0 + lch[i] < P.Cin;
+            const uint32_t off = in_k ? pgo[i] + (uint32_t)(chunk * RB) : kOob;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(in_rsrc, (__attribute__((address_space(3))) void*)(dst + i * (NW * 1024)),
+                                                     16, off, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const bool in_k = c0 + lch[i] < P.Cin;
+            const uint32_t off = in_k ? wgo[i] + (uint32_t)(chunk * RB) : kOob;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (__attribute__((address_space(3))) void*)(dst + PBYTES + i * (NW * 1024)),
+                                                     16, off, 0, 0, 0);
+        }
+    };
+
+    // read side
+    const int sw = (l16 >> 1) & 7;
+    int xaddr[GPC], waddr[GPC];
+#pragma unroll
+    for (int g = 0; g < GPC; ++g) {
+        xaddr[g] = (wave_m * UPW * 16 + l16) * RB + (((g * 4 + q) ^ sw) << 4);
+        waddr[g] = PBYTES + (wave_n * NBW * 16 + l16) * RB + (((g * 4 + q) ^ sw) << 4);
+    }
+    floatx4 acc[UPW][NBW];
+#pragma unroll
+    for (int u = 0; u < UPW; ++u)
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) acc[u][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // Every unit group starts its walk over K at another chunk: rows are Cin * ES bytes apart, a power of two for
+    // most layers, so workgroups that all read chunk c of their rows at the same time would all hit the few memory
+    // channels those addresses map to.
+    const int n_ch = P.n_chunks;
+    const int start = ug % n_ch;
+    auto chunk_of = [&](int c) { const int cc = start + c; return cc < n_ch ? cc : cc - n_ch; };
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d < n_ch) issue(chunk_of(d), d);
+    for (int c = 0; c < n_ch; ++c) {
+        // the loads of chunk c are complete when at most the later chunks' (4 instructions each) are outstanding
+        const int ahead = n_ch - 1 - c < D - 1 ? n_ch - 1 - c : D - 1;
+        switch (ahead) {
+            case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+            case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+            case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+            case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+            case 4: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+            case 5: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
+            default: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
+        }
+        __syncthreads();                            // chunk c is in LDS; everyone is done with chunk c - 1
+        if (c + D < n_ch) issue(chunk_of(c + D), (c + D) % NSTG);
+        const unsigned char* sb = ring + (c % NSTG) * STAGE;
+#pragma unroll
+        for (int g = 0; g < GPC; ++g) {
+            vec x[UPW], w[NBW];
+#pragma unroll
+            for (int u = 0; u < UPW; ++u) x[u] = *reinterpret_cast<const vec*>(sb + xaddr[g] + u * (16 * RB));
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) w[j] = *reinterpret_cast<const vec*>(sb + waddr[g] + j * (16 * RB));
+#pragma unroll
+            for (int e = 0; e < F::NE; ++e)
+#pragma unroll
+                for (int u = 0; u < UPW; ++u)
+#pragma unroll
+                    for (int j = 0; j < NBW; ++j) F::mma1(w[j], x[u], acc[u][j], e);
+        }
+    }
+
+    const int chan0 = n0 + wave_n * 32 + q * 8;
+    if (chan0 >= P.Cout) return;
+    floatx4 b0{0.f, 0.f, 0.f, 0.f}, b1{0.f, 0.f, 0.f, 0.f};
+    if (P.bias) {
+        b0 = *reinterpret_cast<const floatx4*>(P.bias + chan0);
+        b1 = *reinterpret_cast<const floatx4*>(P.bias + chan0 + 4);
+    }
+    const bool relu = P.relu != 0;
+#pragma unroll
+    for (int u = 0; u < UPW; ++u) {
+        const int g = wave_m * UPW + u;
+        if (H.skip[g * 16 + l16]) continue;
+        T* px = reinterpret_cast<T*>(P.out) + H.uq[g].w + ((l16 >> 2) * P.Wout + (l16 & 3)) * P.Cout + chan0;
+        floatx4 v0 = acc[u][0] + b0, v1 = acc[u][1] + b1;
+        if (relu) {
+            v0[0] = fmaxf(v0[0], 0.f); v0[1] = fmaxf(v0[1], 0.f); v0[2] = fmaxf(v0[2], 0.f); v0[3] = fmaxf(v0[3], 0.f);
+            v1[0] = fmaxf(v1[0], 0.f); v1[1] = fmaxf(v1[1], 0.f); v1[2] = fmaxf(v1[2], 0.f); v1[3] = fmaxf(v1[3], 0.f);
+        }
+        if constexpr (sizeof(T) == 2) {             // eight bf16 channels in one 16-byte store
+            uintx4 w4;
+            w4[0] = (uint32_t)F::bits(v0[0]) | ((uint32_t)F::bits(v0[1]) << 16);
+            w4[1] = (uint32_t)F::bits(v0[2]) | ((uint32_t)F::bits(v0[3]) << 16);
+            w4[2] = (uint32_t)F::bits(v1[0]) | ((uint32_t)F::bits(v1[1]) << 16);
+            w4[3] = (uint32_t)F::bits(v1[2]) | ((uint32_t)F::bits(v1[3]) << 16);
+            *reinterpret_cast<uintx4*>(px) = w4;
+        } else {
+            F::store4(px, v0);
+            F::store4(px + 4, v1);
+        }
+    }
+}
+
 // ---- first layer -------------------------------------------------------------------------
 // A pixel of the network input is one 16-byte vector (4 fp32 or 8 bf16 channels, the frame's three
 // plus zero padding).  Four taps of a kernel row are then consecutive pixels, 64 bytes of input
@@ -929,6 +1125,10 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
 // 110.. the wide arrangement.
 void conv_fast_kernel_name(int id, char* buf, size_t n) {
     if (id == 126) { snprintf(buf, n, "conv_regw_kernel<2, 2>"); return; }
+    if (id == 127 || id == 128 || id == 108 || id == 109) {      // 108 + bf16 (4 ring stages), 127 + bf16 (8): conv_pw_kernel (1x1)
+        snprintf(buf, n, "conv_pw_kernel<%s, %d>", id == 109 || id == 128 ? "__hip_bfloat16" : "float", id >= 127 ? 8 : 4);
+        return;
+    }
     if (id >= 110) {  // 110 + (arrangement - 1) * 8 + kci * 4 + UPW - 1: the wide bf16 arrangements
         const int v = (id - 110) % 8, wide64 = (id - 110) / 8;
         snprintf(buf, n, "conv_fast_kernel<__hip_bfloat16, 3, %d, %d, 4, 2, %d>", 32 << (v / 4), v % 4 + 1, wide64 ? 2 : 4);
@@ -984,6 +1184,22 @@ hipError_t regw_launch(dim3 grid, hipStream_t st, const ConvParams& P) {
 }
 
 // Launches the layer with the kernel of this file if its shape qualifies; returns false otherwise.
+template <typename T, int NSTG>
+hipError_t pw_launch_n(dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+    static size_t allowed = 64 * 1024;
+    if (lds > allowed) {
+        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_pw_kernel<T, NSTG>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kHeaderBytes + NSTG * 16384));
+        if (a != hipSuccess) return a;
+        allowed = kHeaderBytes + NSTG * 16384;
+    }
+    hipLaunchKernelGGL((conv_pw_kernel<T, NSTG>), grid, dim3(256), lds, st, P);
+    return hipGetLastError();
+}
+template <typename T>
+hipError_t pw_launch(int nstg, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+    return nstg == 8 ? pw_launch_n<T, 8>(grid, lds, st, P) : pw_launch_n<T, 4>(grid, lds, st, P);
+}
 bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err) {
     static int enabled = -1;
     if (enabled < 0) { const char* e = getenv("DC_CONV_FAST"); enabled = e ? atoi(e) : 1; }
@@ -1012,6 +1228,44 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
                                         : 96 + (c.dtype == DC_BF16 ? 3 : 0) + (nb == 4 ? 2 : (nb == 2 ? 1 : 0));
             const dim3 grid((unsigned)wgx, (unsigned)(c.Cout / (16 * nb)));
             *err = c.dtype == DC_BF16 ? first_launch<__hip_bfloat16>(c.k, nb, grid, st, P) : first_launch<float>(c.k, nb, grid, st, P);
+            return true;
+        }
+    }
+    if (enabled && c.k == 1 && c.p == 0 && (c.s == 1 || c.s == 2) && (c.Cin * esz) % 16 == 0 && c.Cout % 8 == 0 &&
+        reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
+        reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
+        static int pw_enabled = -1;
+        if (pw_enabled < 0) { const char* e = getenv("DC_CONV_PW"); pw_enabled = e ? atoi(e) : 1; }
+        const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
+        const long R = (c.Cout + 63) / 64, tiles = (n_units + 3) / 4 * R;
+        if (pw_enabled && (double)c.n_streams * c.Hout * c.Wout * c.Cout < 2147483648.0 &&
+            (double)n_units * units_x * units_y < 4294967296.0 && tiles + 8 < 2147483647L) {
+            ConvParams P{};
+            P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
+            P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
+            P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
+            P.units = c.tiles; P.n_units = (int)n_units;
+            P.units_x = units_x; P.units_y = units_y;
+            P.npix_magic = (uint32_t)((0x100000000ull + (uint64_t)(units_x * units_y) - 1) / (uint64_t)(units_x * units_y));
+            P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)units_x - 1) / (uint64_t)units_x);
+            P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * c.Cin * esz);
+            P.w_bytes = (uint32_t)((size_t)c.Cout * c.Cin * esz);
+            const int kc = (int)(128 / esz);
+            P.n_chunks = (c.Cin + kc - 1) / kc;
+            P.R = (int)R;
+            P.n_wg_tiles = (int)tiles;
+            P.tiles_per_xcd = (int)((tiles + 7) / 8);
+            // Every kernel starts with cold caches, so a workgroup's walk over K is a chain of long-latency loads:
+            // what counts is the number of chunks in flight per CU.  With at most one workgroup per CU the ring
+            // takes most of the LDS (8 stages); otherwise 4 stages and two or more workgroups per CU.
+            static int f_stg = -1;
+            if (f_stg < 0) { const char* e = getenv("DC_CONV_PW_STAGES"); f_stg = e ? atoi(e) : 0; }
+            const int nstg = f_stg == 4 || f_stg == 8 ? f_stg : (tiles <= 256 && P.n_chunks > 4 ? 8 : 4);
+            const int stages = P.n_chunks < nstg ? P.n_chunks : nstg;
+            const size_t lds = kHeaderBytes + (size_t)stages * 16384;
+            if (c.kernel_id) *c.kernel_id = (nstg == 8 ? 127 : 108) + (c.dtype == DC_BF16 ? 1 : 0);
+            *err = c.dtype == DC_BF16 ? pw_launch<__hip_bfloat16>(nstg, dim3((unsigned)(8 * P.tiles_per_xcd)), lds, st, P)
+                                      : pw_launch<float>(nstg, dim3((unsigned)(8 * P.tiles_per_xcd)), lds, st, P);
             return true;
         }
     }

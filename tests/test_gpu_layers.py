@@ -386,3 +386,50 @@ def test_fully_connected_layer(oracle, n, shape, cout, bf16):
         assert got.shape == (n, 1, 1, cout)
         want = np.stack([oracle.fc(x[i], w, bias, relu, bf16=bf16) for i in range(n)])
         assert _rel_err(got, want) <= (2e-2 if bf16 else 1e-4)
+
+
+PW_CASES = [
+    # H, W, cin, cout, stride
+    (13, 18, 64, 64, 1),       # one chunk in bf16, two in fp32
+    (13, 18, 96, 24, 1),       # last chunk half empty (bf16), cout below one channel tile
+    (9, 9, 1024, 72, 1),       # more chunks than ring stages; channel tile with a tail
+    (14, 14, 256, 200, 1),
+    (8, 8, 8, 8, 1),           # a single 16-byte vector per pixel (bf16)
+    (27, 21, 128, 136, 2),     # strided projection, odd map
+    (28, 28, 64, 256, 2),
+]
+
+
+@pytest.mark.parametrize("cached", [False, True])
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("case", PW_CASES)
+def test_pointwise_kernel(oracle, case, bf16, cached):
+    """1x1 convolutions (stride 1 and 2) on the GEMM kernel with the staged K ring."""
+    H, W, cin, cout, s = case
+    print(f"[pointwise] case={case} bf16={bf16} cached={cached}", flush=True)
+    rng = np.random.default_rng(sum(case) + 3)
+    n = 3
+    Ho, Wo = (H - 1) // s + 1, (W - 1) // s + 1
+    x = rng.standard_normal((n, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, 1, 1, cin)) * np.sqrt(2.0 / cin)).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    cache = rng.standard_normal((n, Ho, Wo, cout)).astype(np.float32)
+    if bf16:
+        x, w, cache = oracle.round_bf16(x), oracle.round_bf16(w), oracle.round_bf16(cache)
+    regions = None
+    if cached:
+        regions = [(np.array([[1, 0, Wo - 3, Ho - 2]], np.int32), (1, 1)), (np.zeros((0, 4), np.int32), (0, 0)),
+                   (np.array([[0, 1, 2, Ho - 2], [3, 2, Wo - 4, 3]], np.int32), (1, 0))]
+    got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, 1, s, 0, True), _to_dev(x, bf16), _to_dev(w, bf16),
+                                              torch.from_numpy(b).to(DEV),
+                                              cache_prev=_to_dev(cache, bf16) if cached else None, regions=regions))
+    assert got.shape == (n, Ho, Wo, cout)
+    for i in range(n):
+        if cached:
+            mask = oracle.rasterize(regions[i][0], Ho, Wo)
+            want = oracle.conv_cached(x[i], w, b, 1, s, 0, True, cache_prev=cache[i], mask=mask, dxy=regions[i][1], bf16=bf16)
+            m = mask.astype(bool)
+            assert np.array_equal(got[i][m], want[m])
+        else:
+            want = oracle.conv_cached(x[i], w, b, 1, s, 0, True, bf16=bf16)
+        assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
