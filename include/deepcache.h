@@ -339,9 +339,18 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
  *                   (written).  Conv outputs are the cache values of the next frame.
  *   tensors_prev    host array [n_layers+1] of dev pointers: the previous frame's tensors;
  *                   only conv-layer outputs are read.  Must not alias tensors_cur for them.
+ *                   Written only in an in-place frame (see in_place).
  *   match_options   optional (NULL: exhaustive search over every block)
  *   force_full      nonzero: first frame, cache expiry (Section 5) or reset: skip matching
  *                   and compute everything
+ *   in_place        optional host (NULL: never).  When the global motion of every stream is (0,0)
+ *                   (a static camera), every reusable pixel of every conv output already holds its
+ *                   value in the previous frame's buffer, so the frame is computed in place: the
+ *                   conv layers write their non-reusable pixels into the buffers of tensors_prev,
+ *                   nothing is copied, and *in_place is set to 1.  The frame's conv outputs are then
+ *                   the tensors_prev buffers (the other tensors are in tensors_cur as always), and
+ *                   the caller passes the same two sets in the same roles for the next frame
+ *                   instead of swapping them.  The values are the same as without it.  Otherwise 0.
  *   mv .. block_mask  dev buffers as in dc_match_blocks (written unless force_full)
  *   max_rects       capacity of each per-tensor rectangle list
  *   regions_out     optional host [n_streams][n_layers+1] with caller-provided rect storage,
@@ -360,10 +369,10 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers,
                      const void* const* weights, const void* const* packed_weights,
                      const float* const* bias,
                      const uint8_t* frames_cur, const uint8_t* frames_prev,
-                     void* const* tensors_cur, const void* const* tensors_prev,
+                     void* const* tensors_cur, void* const* tensors_prev,
                      int32_t n_streams, int32_t H, int32_t W, int32_t C, int32_t dtype,
                      int32_t block, int32_t radius, uint32_t max_block_ssd,
-                     const dc_match_options* match_options, int32_t force_full,
+                     const dc_match_options* match_options, int32_t force_full, int32_t* in_place,
                      int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
                      uint8_t* block_mask, int32_t max_rects, dc_regions* regions_out,
                      void* ws_dev, size_t ws_dev_bytes, void* ws_host, size_t ws_host_bytes,

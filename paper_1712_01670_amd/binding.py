@@ -103,7 +103,7 @@ def lib():
         L.dc_fc_layer.argtypes = [vp, vp, vp, vp, i32, sz, i32, i32, i32, vp]
         L.dc_softmax_layer.argtypes = [vp, vp, sz, i32, i32, vp]
         L.dc_stack_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
-        L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, vp, i32,
+        L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, vp, i32, vp,
                                    vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp, vp]
         for name in EXPORTS:
             if name != "dc_status_string":
@@ -398,7 +398,10 @@ class StackRunner:
     def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
                  want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True,
-                 match_method=DC_MATCH_EXHAUSTIVE, k_skip=1):
+                 match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False):
+        self.in_place = bool(in_place)
+        self.last_in_place = False
+        self._in_place_flag = C.c_int32(0)
         self.Ch_tensor = Ch
         if pad_input:
             layers, weights, self.Ch_tensor = pad_input_channels(layers, weights, Ch, dtype)
@@ -422,6 +425,7 @@ class StackRunner:
         self.shapes = synth.tensor_shapes(layers, H, W, self.Ch_tensor)
         # conv outputs are cache values: two copies (previous / current frame); the rest is shared
         is_conv = [False] + [L["type"] == synth.CONV for L in layers]
+        self._is_conv_out = is_conv
         self.bufs = [[], []]
         for t, (h, w, c) in enumerate(self.shapes):
             a = torch.empty((n_streams, h, w, c), dtype=td, device=self.device)
@@ -491,14 +495,18 @@ class StackRunner:
         _check("dc_run_stack", lib().dc_run_stack(
             self.Lc, len(self.layers), self._wp, self._wpp, self._bp, _ptr(frames), _ptr(self.prev_frames),
             self._tp[c], self._tp[p], self.n, self.H, self.W, self.Ch, self.dtype, self.block, self.radius,
-            self.max_block_ssd, C.byref(self.match_options), int(full), _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
+            self.max_block_ssd, C.byref(self.match_options), int(full),
+            C.byref(self._in_place_flag) if self.in_place else None, _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
             _ptr(self.mask), self.max_rects, self.regs, _ptr(self.ws_dev), self.ws_dev.numel(),
             C.c_void_p(self.ws_host.data_ptr()), self.ws_host.numel(), C.byref(self.stats), self.overlap, _stream()))
         self.age = 1 if full else self.age + 1
         self.have_prev = True
         self.prev_frames = frames
-        self.cur = p
         self.last_full = full
+        self.last_in_place = self.in_place and self._in_place_flag.value != 0
+        if self.last_in_place:      # the conv outputs were updated in the previous frame's buffers: no swap
+            return [self.bufs[p][t] if self._is_conv_out[t] else self.bufs[c][t] for t in range(len(self.bufs[c]))]
+        self.cur = p
         return self.bufs[c]
 
     def enable_profile(self, on=True):

@@ -662,9 +662,9 @@ HostTiming g_host_timing;
 int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const* weights,
                      const void* const* packed_weights, const float* const* bias,
                      const uint8_t* frames_cur, const uint8_t* frames_prev, void* const* tensors_cur,
-                     const void* const* tensors_prev, int32_t n_streams, int32_t H, int32_t W, int32_t C,
+                     void* const* tensors_prev, int32_t n_streams, int32_t H, int32_t W, int32_t C,
                      int32_t dtype, int32_t block, int32_t radius, uint32_t max_block_ssd,
-                     const dc_match_options* match_options, int32_t force_full,
+                     const dc_match_options* match_options, int32_t force_full, int32_t* in_place,
                      int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass, uint8_t* block_mask,
                      int32_t max_rects, dc_regions* regions_out, void* ws_dev, size_t ws_dev_bytes, void* ws_host,
                      size_t ws_host_bytes, dc_stack_stats* stats, void* overlap, void* stream) {
@@ -738,7 +738,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         if (last_reader[0] >= 0) is_target[last_reader[0]] = 1;
         for (int i = 0; i < n_layers; ++i) {
             if (layers[i].type == DC_CONV) is_target[run_end[i]] = 1;
-            else if (last_reader[i + 1] >= 0) is_target[last_reader[i + 1]] = 1;
+            if ((layers[i].type != DC_CONV || in_place) && last_reader[i + 1] >= 0) is_target[last_reader[i + 1]] = 1;
         }
     }
     int waited = -1;
@@ -769,6 +769,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     local.full = cached ? 0 : 1;
     local.n_blocks = (int32_t)nb;
 
+    bool inplace = false;
+    if (in_place) *in_place = 0;
     std::vector<std::vector<TensorRegions>> regs;  // [stream][tensor]
     unsigned char* hbase = static_cast<unsigned char*>(ws_host);
     if (cached) {
@@ -794,6 +796,10 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             DC_TRY_HIP(hipStreamSynchronize(mst));
         }
         g_host_timing.mark(1);
+        if (in_place) {     // no stream moved: the previous frame's conv outputs can be updated where they are
+            inplace = true;
+            for (int s = 0; s < n_streams; ++s) inplace = inplace && h_gmv[2 * s] == 0 && h_gmv[2 * s + 1] == 0;
+        }
         try {
             regs.resize(n_streams);
         } catch (const std::bad_alloc&) {
@@ -895,7 +901,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             int64_t issued = (int64_t)plan.n_tiles * tilings[i].th * tilings[i].tw * mac_px;
             local.macs_needed += (px - plan.reused_px) * mac_px;
             local.macs_issued += issued;
-            local.copy_bytes += 2 * plan.reused_px * l.cout * (int64_t)dtype_size(dtype);
+            if (!inplace) local.copy_bytes += 2 * plan.reused_px * l.cout * (int64_t)dtype_size(dtype);
             if (local.layer_reused_px) local.layer_reused_px[i] = plan.reused_px;
             if (local.layer_issued_macs) local.layer_issued_macs[i] = issued;
         }
@@ -910,7 +916,9 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     struct CopyGroup { int first_layer, last_layer; size_t rect_begin, rect_end, max_vec; };
     std::vector<CopyGroup> groups;
     size_t all_rects_off = 0, copy_layers_off = 0, n_all_rects = 0;
-    if (cached) {
+    if (inplace)        // every reusable pixel already holds its value
+        for (int i = 0; i < n_layers; ++i) copy_fused[i] = 1;
+    if (cached && !inplace) {
         try {
             std::vector<RectDev> all_rects;
             std::vector<CopyLayerDev> copy_layers;
@@ -971,6 +979,11 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     };
 
     if (cached) g_host_timing.mark(4);
+    // Where each tensor of this frame lives: an in-place frame keeps the conv outputs in the previous frame's buffers.
+    std::vector<void*> eff(n_layers + 1);
+    for (int t = 0; t <= n_layers; ++t)
+        eff[t] = (inplace && t > 0 && layers[t - 1].type == DC_CONV) ? tensors_prev[t] : tensors_cur[t];
+    if (in_place) *in_place = inplace ? 1 : 0;
     // ---- layers ----
     for (int i = 0; i < n_layers; ++i) {
         const dc_layer& l = layers[i];
@@ -980,8 +993,9 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 rc = launch_copy_group(i);
                 if (rc) return rc;
                 DC_TRY_HIP(wait_prev(run_end[i]));   // its cache: the previous frame's output of this layer (whole run)
-                rc = run_conv_planned(l, tensors_cur[a], weights[i], bias ? bias[i] : nullptr,
-                                      cached ? tensors_prev[t] : nullptr, tensors_cur[t], n_streams, hs[a], ws[a], dtype,
+                if (inplace) DC_TRY_HIP(wait_prev(last_reader[t]));   // and the previous frame's readers of the buffer it updates
+                rc = run_conv_planned(l, eff[a], weights[i], bias ? bias[i] : nullptr,
+                                      cached ? tensors_prev[t] : nullptr, eff[t], n_streams, hs[a], ws[a], dtype,
                                       tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st,
                                       stats ? static_cast<Profile*>(stats->profile) : nullptr, i, n_layers + i,
                                       local.layer_kernel_id ? &local.layer_kernel_id[i] : nullptr, copy_fused[i] != 0,
@@ -991,45 +1005,45 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 break;
             case DC_MAXPOOL:
                 DC_TRY_HIP(wait_prev(last_reader[t]));
-                DC_TRY_HIP(launch_maxpool(tensors_cur[a], tensors_cur[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
+                DC_TRY_HIP(launch_maxpool(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
                                           dtype, st));
                 break;
             case DC_ADD:
                 DC_TRY_HIP(wait_prev(last_reader[t]));
-                DC_TRY_HIP(launch_add(tensors_cur[a], tensors_cur[l.in1], tensors_cur[t],
+                DC_TRY_HIP(launch_add(eff[a], eff[l.in1], eff[t],
                                       (size_t)n_streams * hs[t] * ws[t] * cs[t], l.relu, dtype, st));
                 break;
             case DC_AVGPOOL:
                 DC_TRY_HIP(wait_prev(last_reader[t]));
-                DC_TRY_HIP(launch_avgpool(tensors_cur[a], tensors_cur[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
+                DC_TRY_HIP(launch_avgpool(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
                                           dtype, st));
                 break;
             case DC_LRN:
                 DC_TRY_HIP(wait_prev(last_reader[t]));
-                DC_TRY_HIP(launch_lrn(tensors_cur[a], tensors_cur[t], n_streams, hs[a], ws[a], cs[a], l.k, l.within,
+                DC_TRY_HIP(launch_lrn(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], l.k, l.within,
                                       l.alpha, l.beta, l.kappa, dtype, st));
                 break;
             case DC_CONCAT: {
                 int ids[4], chans[4];
                 const void* ins[4];
                 const int m = concat_inputs(l, ids);
-                for (int j = 0; j < m; ++j) { ins[j] = tensors_cur[ids[j]]; chans[j] = cs[ids[j]]; }
+                for (int j = 0; j < m; ++j) { ins[j] = eff[ids[j]]; chans[j] = cs[ids[j]]; }
                 DC_TRY_HIP(wait_prev(last_reader[t]));
-                DC_TRY_HIP(launch_concat(ins, chans, m, tensors_cur[t], (size_t)n_streams * hs[t] * ws[t], dtype, st));
+                DC_TRY_HIP(launch_concat(ins, chans, m, eff[t], (size_t)n_streams * hs[t] * ws[t], dtype, st));
                 break;
             }
             case DC_FC:
                 DC_TRY_HIP(wait_prev(last_reader[t]));
-                DC_TRY_HIP(launch_fc(tensors_cur[a], weights[i], bias ? bias[i] : nullptr, tensors_cur[t], n_streams,
+                DC_TRY_HIP(launch_fc(eff[a], weights[i], bias ? bias[i] : nullptr, eff[t], n_streams,
                                      (size_t)hs[a] * ws[a] * cs[a], l.cout, l.relu, dtype, st));
                 break;
             case DC_SOFTMAX:
                 DC_TRY_HIP(wait_prev(last_reader[t]));
-                DC_TRY_HIP(launch_softmax(tensors_cur[a], tensors_cur[t], (size_t)n_streams * hs[t] * ws[t], cs[t], dtype, st));
+                DC_TRY_HIP(launch_softmax(eff[a], eff[t], (size_t)n_streams * hs[t] * ws[t], cs[t], dtype, st));
                 break;
             default:
                 DC_TRY_HIP(wait_prev(last_reader[t]));
-                DC_TRY_HIP(launch_add(tensors_cur[a], nullptr, tensors_cur[t], (size_t)n_streams * hs[t] * ws[t] * cs[t],
+                DC_TRY_HIP(launch_add(eff[a], nullptr, eff[t], (size_t)n_streams * hs[t] * ws[t] * cs[t],
                                       1, dtype, st));
                 break;
         }

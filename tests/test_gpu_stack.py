@@ -17,14 +17,14 @@ def _rel_err(got, want):
 
 
 def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
-              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1):
+              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False):
     """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
     n, T, H, W, C = videos.shape
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale, input_shape=(H, W, C))
     tol = 2e-2 if bf16 else 1e-4
     dt = binding.DC_BF16 if bf16 else binding.DC_F32
     runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
-                                 want_regions=True, k_skip=k_skip,
+                                 want_regions=True, k_skip=k_skip, in_place=in_place,
                                  match_method=binding.DC_MATCH_DIAMOND if diamond else binding.DC_MATCH_EXHAUSTIVE)
     streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry,
                              diamond=diamond, k_skip=k_skip)
@@ -32,6 +32,7 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
     worst = 0.0
     reuse = []
+    runner.in_place_frames = []
     for t in range(T):
         print(f"[stack] frame {t}/{T} n={n} {H}x{W} bf16={bf16}", flush=True)
         if t in resets:
@@ -40,6 +41,7 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
                 s.reset()
         tensors = runner.step(dev_video[t])
         torch.cuda.synchronize()
+        runner.in_place_frames.append(bool(runner.last_in_place))
         got = [x.float().cpu().numpy() for x in tensors]
         for s in range(n):
             want = streams[s].step(videos[s, t])
@@ -134,6 +136,48 @@ def test_googlenet_style_stack_small(oracle):
     assert sum(L["type"] == synth.CONV for L in layers) == 57
     video = np.stack([synth.panning_video(400 + s, n_frames=3, H=224, W=224) for s in range(1)])
     _run_both(oracle, layers, video, 16, 8, True)
+
+
+def _static_then_moving(seed, H, W, n_static, n_moving):
+    """A camera that stands still (only a small object moves), then pans, then stands still again."""
+    still = synth.panning_video(seed, n_frames=n_static, H=H, W=W, fg=((24, 24),), pan_speeds=(0,))
+    moving = synth.panning_video(seed, n_frames=n_static + n_moving, H=H, W=W, fg=((24, 24),), pan_speeds=(2,),
+                                 redraw_every=100)[n_static:]
+    return np.concatenate([still, moving, still[::-1]])
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_in_place_frames_of_a_static_camera(oracle, bf16):
+    """No stream moves: the conv outputs are updated in the previous frame's buffers and nothing is copied; the
+    values are the oracle's (which knows nothing of buffers)."""
+    layers = synth.vgg16()[:7]
+    video = np.stack([synth.panning_video(500 + s, n_frames=4, H=96, W=96, fg=((24, 24),), pan_speeds=(0,)) for s in range(2)])
+    runner, reuse = _run_both(oracle, layers, video, 16, 8, bf16, in_place=True)
+    assert runner.in_place_frames == [False, True, True, True]
+    assert runner.stats.copy_bytes == 0 and runner.stats.macs_needed < runner.stats.macs_full
+    assert min(reuse) > 0.5
+
+
+def test_in_place_and_copied_frames_mix(oracle):
+    """Static and moving stretches in one video: in-place frames where every stream's motion is zero, shifted copies
+    elsewhere, parity on every frame; and bit-identical tensors with the option off."""
+    layers = synth.resnet50_trunk()[:14]
+    video = np.stack([_static_then_moving(600 + s, 96, 96, 3, 3) for s in range(2)])
+    runner, _ = _run_both(oracle, layers, video, 16, 8, True, residual_scale=0.5, in_place=True)
+    flags = runner.in_place_frames
+    assert flags[1] and flags[2] and not any(flags[3:6]) and flags[-1], flags
+    ws, bs = synth.he_weights(layers, 1, bias_scale=0.05, residual_scale=0.5, input_shape=(96, 96, 3))
+    dev_video = torch.from_numpy(np.ascontiguousarray(video.transpose(1, 0, 2, 3, 4))).to(DEV)
+    runs = [binding.StackRunner(layers, ws, bs, 2, 96, 96, 3, block=16, radius=8, dtype=binding.DC_BF16, in_place=ip)
+            for ip in (False, True)]
+    for t in range(video.shape[1]):
+        outs = []
+        for r in runs:
+            tensors = r.step(dev_video[t])
+            torch.cuda.synchronize()
+            outs.append([x.clone() for x in tensors])
+        for a, b in zip(*outs):
+            assert torch.equal(a, b), t
 
 
 def test_vgg16_two_streams_bf16_small(oracle):
