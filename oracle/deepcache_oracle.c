@@ -424,6 +424,26 @@ int oc_dt_window(oc_rect in, int k, int s, int p, oc_rect* out)
     return 1;
 }
 
+/* The same row with the border case that Table 2 leaves out, for a stream that did not move (offset zero in
+ * every tensor): the taps of a window that fall into the zero padding read zeros in both frames, so only the
+ * taps inside the map have to lie in the rectangle.  A rectangle that touches a side of the wa x ha input map
+ * therefore extends, for this rule, beyond that side: the first output column is 0 if x == 0, the last one is
+ * the last of the map if x + w == wa; likewise for rows.  (An optional extension beyond the paper; off = the
+ * printed rule.) */
+int oc_dt_window_ext(oc_rect in, int k, int s, int p, int wa, int ha, oc_rect* out)
+{
+    int wo = (wa + 2 * p - k) / s + 1, ho = (ha + 2 * p - k) / s + 1;
+    int x0 = in.x == 0 ? 0 : ceil_div(in.x + p, s);
+    int x1 = in.x + in.w == wa ? wo - 1 : floor_div(in.x + in.w - k + p, s);
+    int y0 = in.y == 0 ? 0 : ceil_div(in.y + p, s);
+    int y1 = in.y + in.h == ha ? ho - 1 : floor_div(in.y + in.h - k + p, s);
+    if (x1 > wo - 1) x1 = wo - 1;
+    if (y1 > ho - 1) y1 = ho - 1;
+    if (x1 < x0 || y1 < y0) return 0;
+    out->x = x0; out->y = y0; out->w = x1 - x0 + 1; out->h = y1 - y0 + 1;
+    return 1;
+}
+
 /* Concat row of Table 2, used for a residual add: overlap of two rectangles. */
 int oc_dt_overlap(oc_rect a, oc_rect b, oc_rect* out)
 {
@@ -472,12 +492,13 @@ static int clip_to_source(oc_rect r, int dx, int dy, int W, int H, oc_rect* out)
  * is clipped so that its source stays inside the map.
  * Returns 0, or -1 if some list overflowed `cap` (counts are still exact).
  */
-int oc_propagate(const oc_layer* L, int n_layers, int H, int W,
-                 const oc_rect* rects0, int n0, int mx, int my,
-                 oc_rect* rects, int cap, int32_t* n_rects, int32_t* dxy,
-                 int32_t* cum_stride, int32_t* hw /* [2*(n_layers+1)] heights, widths */)
+int oc_propagate_ext(const oc_layer* L, int n_layers, int H, int W,
+                     const oc_rect* rects0, int n0, int mx, int my, int extend_borders,
+                     oc_rect* rects, int cap, int32_t* n_rects, int32_t* dxy,
+                     int32_t* cum_stride, int32_t* hw /* [2*(n_layers+1)] heights, widths */)
 {
     int overflow = 0;
+    int ext = extend_borders && mx == 0 && my == 0;    /* border case of a stream that did not move */
     hw[0] = H; hw[1] = W; cum_stride[0] = 1; dxy[0] = mx; dxy[1] = my;
     int n = 0;
     for (int i = 0; i < n0; ++i) {
@@ -511,7 +532,7 @@ int oc_propagate(const oc_layer* L, int n_layers, int H, int W,
         } else if (l->type == OC_LRN && l->within) {
             for (int i = 0; i < na; ++i) {
                 oc_rect r, c;
-                if (!oc_dt_lrn(ra[i], (l->k - 1) / 2, &r)) continue;
+                if (!(ext ? oc_dt_window_ext(ra[i], l->k, 1, (l->k - 1) / 2, wa, ha, &r) : oc_dt_lrn(ra[i], (l->k - 1) / 2, &r))) continue;
                 if (!clip_to_source(r, dx, dy, wo, ho, &c)) continue;
                 if (n < cap) ro[n] = c; else overflow = 1;
                 ++n;
@@ -536,7 +557,7 @@ int oc_propagate(const oc_layer* L, int n_layers, int H, int W,
         } else if (windowed) {
             for (int i = 0; i < na; ++i) {
                 oc_rect r, c;
-                if (!oc_dt_window(ra[i], l->k, l->s, l->p, &r)) continue;
+                if (!(ext ? oc_dt_window_ext(ra[i], l->k, l->s, l->p, wa, ha, &r) : oc_dt_window(ra[i], l->k, l->s, l->p, &r))) continue;
                 if (!clip_to_source(r, dx, dy, wo, ho, &c)) continue;
                 if (n < cap) ro[n] = c; else overflow = 1;
                 ++n;
@@ -564,6 +585,15 @@ int oc_propagate(const oc_layer* L, int n_layers, int H, int W,
         n_rects[t] = n;
     }
     return overflow ? -1 : 0;
+}
+
+/* Table 2 as printed (no border case). */
+int oc_propagate(const oc_layer* L, int n_layers, int H, int W,
+                 const oc_rect* rects0, int n0, int mx, int my,
+                 oc_rect* rects, int cap, int32_t* n_rects, int32_t* dxy,
+                 int32_t* cum_stride, int32_t* hw)
+{
+    return oc_propagate_ext(L, n_layers, H, W, rects0, n0, mx, my, 0, rects, cap, n_rects, dxy, cum_stride, hw);
 }
 
 /* Boolean map of Section 5 "Reuse", step 2: 1 where the pixel lies in a rectangle. */
@@ -811,6 +841,7 @@ void oc_softmax(const float* in, size_t n_pixels, int C, int bf16, float* out)
  *   cur[t]       tensor t of this frame (written), t = 0..n_layers
  *   prev[t]      tensor t of the previous frame (read for conv outputs only)
  *   rects,cap,n_rects,dxy,cum_stride,hw: as oc_propagate (outputs)
+ *   extend_borders  the border case of oc_dt_window_ext for a stream that did not move
  * Returns 0, -1 on rect overflow.
  */
 int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
@@ -818,11 +849,11 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
                  int bf16, const oc_rect* rects0, int n0, int mx, int my,
                  float* const* cur, const float* const* prev,
                  oc_rect* rects, int cap, int32_t* n_rects, int32_t* dxy,
-                 int32_t* cum_stride, int32_t* hw)
+                 int32_t* cum_stride, int32_t* hw, int extend_borders)
 {
     int cached = n0 >= 0;
-    int rc = oc_propagate(L, n_layers, H, W, rects0, cached ? n0 : 0, cached ? mx : 0,
-                          cached ? my : 0, rects, cap, n_rects, dxy, cum_stride, hw);
+    int rc = oc_propagate_ext(L, n_layers, H, W, rects0, cached ? n0 : 0, cached ? mx : 0,
+                              cached ? my : 0, extend_borders, rects, cap, n_rects, dxy, cum_stride, hw);
     if (rc) return rc;
     oc_frame_to_tensor(frame, (size_t)H * W * C, cur[0]);
     for (int li = 0; li < n_layers; ++li) {

@@ -161,7 +161,14 @@ def dt_lrn(rect, r):
     return (out.x, out.y, out.w, out.h) if ok else None
 
 
-def propagate(layers, H, W, rects0, mx, my, cap=1024):
+def dt_window_ext(rect, k, s, p, wa, ha):
+    """Conv/pool row with the border case (a rectangle touching a side of the wa x ha map extends beyond it)."""
+    out = Rect()
+    ok = lib().oc_dt_window_ext(Rect(*[int(v) for v in rect]), int(k), int(s), int(p), int(wa), int(ha), C.byref(out))
+    return (out.x, out.y, out.w, out.h) if ok else None
+
+
+def propagate(layers, H, W, rects0, mx, my, cap=1024, extend_borders=False):
     """Section 5 propagation.  Returns dict(rects=[per tensor int32 [n][4]], dxy, cum_stride, hw)."""
     n = len(layers)
     Lc = layers_to_c(layers)
@@ -171,7 +178,7 @@ def propagate(layers, H, W, rects0, mx, my, cap=1024):
     dxy = np.zeros((n + 1, 2), np.int32)
     cs = np.zeros(n + 1, np.int32)
     hw = np.zeros((n + 1, 2), np.int32)
-    rc = lib().oc_propagate(Lc, n, int(H), int(W), _p(r0), len(r0), int(mx), int(my), _p(rects), cap,
+    rc = lib().oc_propagate_ext(Lc, n, int(H), int(W), _p(r0), len(r0), int(mx), int(my), int(extend_borders), _p(rects), cap,
                             _p(n_rects), _p(dxy), _p(cs), _p(hw))
     assert rc == 0, "rect capacity exceeded"
     return dict(rects=[rects[t, :n_rects[t]].copy() for t in range(n + 1)], dxy=dxy,
@@ -286,8 +293,8 @@ class Stream:
     the previous feature maps (cache values), Section 3."""
 
     def __init__(self, layers, weights, biases, H, W, Ch=3, block=16, radius=16, max_ssd=None,
-                 bf16=False, expiry=0, cap=1024, diamond=False, k_skip=1):
-        self.diamond, self.k_skip = diamond, k_skip
+                 bf16=False, expiry=0, cap=1024, diamond=False, k_skip=1, extend_borders=False):
+        self.diamond, self.k_skip, self.extend_borders = diamond, k_skip, extend_borders
         self.layers, self.H, self.W, self.Ch = layers, H, W, Ch
         self.block, self.radius, self.bf16, self.expiry, self.cap = block, radius, bf16, expiry, cap
         self.max_ssd = max_ssd if max_ssd is not None else 20 * block * block * Ch
@@ -347,7 +354,7 @@ class Stream:
         prevp = (C.c_void_p * (n + 1))(*[t.ctypes.data for t in prev])
         rc = lib().oc_run_stack(self.Lc, n, self._wp, self._bp, _p(frame), self.H, self.W, self.Ch,
                                 int(self.bf16), _p(r0), n0, mx, my, curp, prevp, _p(rects),
-                                self.cap, _p(n_rects), _p(dxy), _p(cs), _p(hw))
+                                self.cap, _p(n_rects), _p(dxy), _p(cs), _p(hw), int(self.extend_borders))
         assert rc == 0
         self.bufs = [prev, cur]  # cur becomes next frame's prev
         self.prev_frame = frame.copy()

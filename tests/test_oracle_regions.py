@@ -186,3 +186,51 @@ def test_propagate_residual_intersection(oracle):
             assert out["cum_stride"][l["in0"]] == out["cum_stride"][l["in1"]]
             assert tuple(out["hw"][l["in0"]]) == tuple(out["hw"][l["in1"]])
     assert out["cum_stride"][-1] == 32
+
+
+# ---- border case for a stream that did not move (an extension beyond Table 2) ------------------------------------
+def test_border_extension_is_in_bounds_window_containment(oracle):
+    """Brute force: an output pixel is reusable iff every tap of its window that lies inside the map lies inside the
+    rectangle (the taps in the zero padding read zeros in both frames)."""
+    rng = np.random.default_rng(12)
+    for trial in range(300):
+        wa, ha = int(rng.integers(5, 20)), int(rng.integers(5, 20))
+        k = int(rng.choice([1, 2, 3, 5, 7]))
+        s = int(rng.choice([1, 2, 3]))
+        p = int(rng.integers(0, k))
+        if wa + 2 * p < k or ha + 2 * p < k:
+            continue
+        x, y = int(rng.integers(0, wa)), int(rng.integers(0, ha))
+        w, h = int(rng.integers(1, wa - x + 1)), int(rng.integers(1, ha - y + 1))
+        if trial % 3 == 0: x, w = 0, wa                     # touches both sides
+        if trial % 4 == 0: y = 0
+        if trial % 5 == 0: h = ha - y
+        wo, ho = (wa + 2 * p - k) // s + 1, (ha + 2 * p - k) // s + 1
+        want = np.zeros((ho, wo), bool)
+        for oy in range(ho):
+            for ox in range(wo):
+                taps = [(oy * s - p + ky, ox * s - p + kx) for ky in range(k) for kx in range(k)]
+                inb = [(a, b) for a, b in taps if 0 <= a < ha and 0 <= b < wa]
+                want[oy, ox] = len(inb) > 0 and all(y <= a < y + h and x <= b < x + w for a, b in inb)
+        got = oracle.dt_window_ext((x, y, w, h), k, s, p, wa, ha)
+        mask = oracle.rasterize([got] if got else [], ho, wo).astype(bool)
+        assert np.array_equal(mask, want), (wa, ha, k, s, p, (x, y, w, h), got)
+        # away from the borders it is the printed rule
+        if x > 0 and y > 0 and x + w < wa and y + h < ha:
+            assert got == oracle.dt_window((x, y, w, h), k, s, p)
+
+
+def test_border_extension_only_for_zero_motion(oracle):
+    from paper_1712_01670_amd import synth
+    layers = synth.vgg16()
+    rects0 = [(0, 0, 224, 224)]
+    plain = oracle.propagate(layers, 224, 224, rects0, 0, 0)
+    ext = oracle.propagate(layers, 224, 224, rects0, 0, 0, extend_borders=True)
+    moved = oracle.propagate(layers, 224, 224, rects0, 3, 0, extend_borders=True)
+    moved_plain = oracle.propagate(layers, 224, 224, rects0, 3, 0)
+    for t in range(len(layers) + 1):
+        h, w = ext["hw"][t]
+        assert ext["rects"][t].tolist() == [[0, 0, w, h]]                      # identical frames: everything reusable
+        assert moved["rects"][t].tolist() == moved_plain["rects"][t].tolist()   # a moving stream: the printed rule
+    # the printed rule loses a ring per layer: the last 14x14 maps keep almost nothing
+    assert plain["rects"][len(layers)].size == 0 or np.prod(plain["rects"][len(layers)][0][2:]) <= 4

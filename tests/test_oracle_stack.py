@@ -213,3 +213,32 @@ def test_resnet_block_runs_and_reuses(oracle):
     for a, b in zip(outs[0]["tensors"], outs[1]["tensors"]):
         assert np.array_equal(a, b)
     assert len(outs[1]["rects"][12]) == 1
+
+
+@pytest.mark.parametrize("extend", [False, True])
+def test_invariant_static_scene_is_exact(oracle, extend):
+    """A stream that did not move, blocks accepted only when identical (bound 0): every reused pixel has the same
+    inputs as in the previous frame, so the cached frame equals the full forward bit for bit, with the printed
+    rule and with the border case; the border case reuses more."""
+    rng = np.random.default_rng(21)
+    layers = synth.vgg16()[:7]
+    H = W = 64
+    f0 = rng.integers(0, 256, (H, W, 3)).astype(np.uint8)
+    f1 = f0.copy()
+    f1[24:40, 8:24] = rng.integers(0, 256, (16, 16, 3))            # one changed patch (2 x 2 blocks of 8)
+    ws, bs = synth.he_weights(layers, 3, bias_scale=0.1)
+    st = oracle.Stream(layers, ws, bs, H, W, 3, block=8, radius=4, max_ssd=0, extend_borders=extend)
+    st.step(f0)
+    out = st.step(f1)
+    assert out["match"]["gmv"].tolist() == [0, 0] and int(out["match"]["mask"].sum()) == 64 - 4
+    full = _full_forward(oracle, layers, ws, bs, f1)
+    for a, b in zip(out["tensors"], full):
+        assert np.array_equal(a, b)
+    reused = [int(oracle.rasterize(out["rects"][t], *out["hw"][t]).sum()) for t in range(1, len(layers) + 1)]
+    test_invariant_static_scene_is_exact.reused[extend] = reused
+    if len(test_invariant_static_scene_is_exact.reused) == 2:
+        plain, ext = (test_invariant_static_scene_is_exact.reused[e] for e in (False, True))
+        assert all(e >= p for e, p in zip(ext, plain)) and sum(ext) > sum(plain)
+
+
+test_invariant_static_scene_is_exact.reused = {}
