@@ -96,6 +96,11 @@ enum { DC_MATCH_EXHAUSTIVE = 0, DC_MATCH_DIAMOND = 1 };
 typedef struct {
     int32_t method;        /* DC_MATCH_EXHAUSTIVE (dc_match_blocks) or DC_MATCH_DIAMOND (dc_match_blocks_ds) */
     int32_t k_skip;        /* >= 1: Step 2 runs only for blocks whose grid row and column are multiples of k */
+    int32_t extend_borders;  /* dc_run_stack only; not a matching option.  0: Table 2 as printed.  1: for a stream
+                              whose global motion is (0,0), the taps of a window that fall into the zero padding
+                              need not lie in the rectangle (they read zeros in both frames), so a rectangle that
+                              touches a side of the map keeps the outputs along that side: an extension beyond
+                              the paper's table for static cameras (dc_propagate_regions_opt) */
 } dc_match_options;
 
 /* Work counters of one dc_run_stack call, summed over streams. */
@@ -249,6 +254,10 @@ int32_t dc_match_blocks_opt(const uint8_t* cur, const uint8_t* prev, int32_t n_s
 int32_t dc_propagate_regions(const dc_layer* layers, int32_t n_layers, int32_t H, int32_t W,
                              int32_t block, const uint8_t* block_mask, int32_t gh, int32_t gw,
                              int32_t mx, int32_t my, dc_regions* regions);
+/* The same with the border case of dc_match_options.extend_borders (applied only when mx == my == 0). */
+int32_t dc_propagate_regions_opt(const dc_layer* layers, int32_t n_layers, int32_t H, int32_t W,
+                                 int32_t block, const uint8_t* block_mask, int32_t gh, int32_t gw,
+                                 int32_t mx, int32_t my, int32_t extend_borders, dc_regions* regions);
 
 /*
  * Packed weights (a layout choice of this library, not part of the method): the weights of a

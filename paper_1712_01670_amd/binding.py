@@ -22,7 +22,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
           -4: "DC_ERR_UNSUPPORTED", -5: "DC_ERR_WORKSPACE", -6: "DC_ERR_CAPACITY", -7: "DC_ERR_HIP"}
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
-           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_conv_workspace_bytes",
+           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_propagate_regions_opt", "dc_conv_workspace_bytes",
            "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer", "dc_avgpool_layer", "dc_lrn_layer", "dc_concat_layer", "dc_fc_layer", "dc_softmax_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
@@ -49,7 +49,7 @@ class Regions(C.Structure):
 
 
 class MatchOptions(C.Structure):
-    _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32)]
+    _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32), ("extend_borders", C.c_int32)]
 
 
 DC_MATCH_EXHAUSTIVE, DC_MATCH_DIAMOND = 0, 1
@@ -89,6 +89,7 @@ def lib():
         L.dc_match_blocks_ds.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp]
         L.dc_match_blocks_opt.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, u32, vp, vp, vp, vp, vp, vp]
         L.dc_propagate_regions.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, vp]
+        L.dc_propagate_regions_opt.argtypes = [vp, i32, i32, i32, i32, vp, i32, i32, i32, i32, i32, vp]
         L.dc_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
         L.dc_packed_weights_bytes.argtypes = [vp, i32, C.POINTER(sz)]
         L.dc_pack_conv_weights.argtypes = [vp, vp, i32, vp, vp]
@@ -212,14 +213,14 @@ def _regions_to_py(r):
     return dict(rects=rects, n=r.n, dxy=(r.dx, r.dy), cum_stride=r.cum_stride, hw=(r.h, r.w))
 
 
-def dc_propagate_regions(layers, H, W, block, block_mask, mx, my, cap=1024):
+def dc_propagate_regions(layers, H, W, block, block_mask, mx, my, cap=1024, extend_borders=False):
     """Host call.  block_mask: numpy uint8 [gh][gw].  Returns a list (per tensor) of dicts."""
     mask = np.ascontiguousarray(block_mask, np.uint8)
     gh, gw = mask.shape
     Lc = layers_to_c(layers)
     regs, store = _alloc_regions(len(layers) + 1, cap)
-    _check("dc_propagate_regions", lib().dc_propagate_regions(
-        Lc, len(layers), H, W, block, mask.ctypes.data_as(C.c_void_p), gh, gw, int(mx), int(my), regs))
+    _check("dc_propagate_regions_opt", lib().dc_propagate_regions_opt(
+        Lc, len(layers), H, W, block, mask.ctypes.data_as(C.c_void_p), gh, gw, int(mx), int(my), int(extend_borders), regs))
     return [_regions_to_py(regs[t]) for t in range(len(layers) + 1)]
 
 
@@ -398,7 +399,7 @@ class StackRunner:
     def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
                  want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True,
-                 match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False):
+                 match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False, extend_borders=False):
         self.in_place = bool(in_place)
         self.last_in_place = False
         self._in_place_flag = C.c_int32(0)
@@ -409,7 +410,7 @@ class StackRunner:
         self.block, self.radius, self.dtype, self.expiry = block, radius, dtype, expiry
         self.max_block_ssd = int(max_block_ssd if max_block_ssd is not None else synth.max_block_ssd(block, Ch))
         self.max_rects = max_rects
-        self.match_options = MatchOptions(int(match_method), int(k_skip))
+        self.match_options = MatchOptions(int(match_method), int(k_skip), int(extend_borders))
         self.device = torch.device(device)
         td = torch_dtype(dtype)
         self.Lc = layers_to_c(layers)

@@ -336,6 +336,12 @@ int32_t dc_match_blocks_ds(const uint8_t* cur, const uint8_t* prev, int32_t n_st
 int32_t dc_propagate_regions(const dc_layer* layers, int32_t n_layers, int32_t H, int32_t W, int32_t block,
                              const uint8_t* block_mask, int32_t gh, int32_t gw, int32_t mx, int32_t my,
                              dc_regions* regions) {
+    return dc_propagate_regions_opt(layers, n_layers, H, W, block, block_mask, gh, gw, mx, my, 0, regions);
+}
+
+int32_t dc_propagate_regions_opt(const dc_layer* layers, int32_t n_layers, int32_t H, int32_t W, int32_t block,
+                                 const uint8_t* block_mask, int32_t gh, int32_t gw, int32_t mx, int32_t my,
+                                 int32_t extend_borders, dc_regions* regions) {
     if (!layers || !block_mask || !regions) return DC_ERR_NULL_PTR;
     if (n_layers < 0 || H < 1 || W < 1 || block < 1 || gh < 0 || gw < 0) return DC_ERR_INVALID_ARG;
     if (gh != H / block || gw != W / block) return DC_ERR_BAD_SHAPE;
@@ -347,7 +353,7 @@ int32_t dc_propagate_regions(const dc_layer* layers, int32_t n_layers, int32_t H
     std::vector<TensorRegions> out;
     try {
         merge_blocks(block_mask, gh, gw, block, rects0);
-        rc = propagate(layers, n_layers, H, W, rects0, mx, my, out);
+        rc = propagate(layers, n_layers, H, W, rects0, mx, my, out, extend_borders != 0);
     } catch (const std::bad_alloc&) {
         return DC_ERR_WORKSPACE;
     }
@@ -815,7 +821,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                     for (int i = 0; i < gh * gw; ++i) cnt += m[i] ? 1 : 0;
                     stream_reusable[s] = cnt;
                     merge_blocks(m, gh, gw, block, rects0);
-                    int r = propagate(layers, n_layers, H, W, rects0, h_gmv[2 * s], h_gmv[2 * s + 1], regs[s]);
+                    int r = propagate(layers, n_layers, H, W, rects0, h_gmv[2 * s], h_gmv[2 * s + 1], regs[s],
+                                      match_options && match_options->extend_borders != 0);
                     for (int t = 0; r == DC_OK && t <= n_layers; ++t)
                         if ((int)regs[s][t].rects.size() > max_rects) r = DC_ERR_CAPACITY;
                     stream_rc[s] = r;

@@ -41,8 +41,9 @@ struct TensorRegions {
     int dx = 0, dy = 0, cum_stride = 1, h = 0, w = 0;
 };
 void merge_blocks(const uint8_t* mask, int gh, int gw, int B, std::vector<dc_rect>& out);
+// extend_borders: for a stream with zero motion, windows may reach into the zero padding (see dc_match_options)
 int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<dc_rect>& rects0,
-              int mx, int my, std::vector<TensorRegions>& out);
+              int mx, int my, std::vector<TensorRegions>& out, bool extend_borders = false);
 int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C,
                     std::vector<int>* hs, std::vector<int>* ws, std::vector<int>* cs);
 

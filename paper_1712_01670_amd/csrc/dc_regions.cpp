@@ -29,6 +29,15 @@ inline Span window_span(Span in, int k, int s, int p) {
     return Span{cdiv(in.lo + p, s), fdiv(in.hi - k + p, s) + 1};
 }
 
+// The same for a stream that did not move, with the border case: taps in the zero padding read zeros in both
+// frames, so a span that touches an end of the input axis [0, size_in) reaches, for this rule, beyond that end.
+inline Span window_span_ext(Span in, int k, int s, int p, int size_in) {
+    const int size_out = (size_in + 2 * p - k) / s + 1;
+    const int lo = in.lo == 0 ? 0 : cdiv(in.lo + p, s);
+    const int hi = in.hi == size_in ? size_out : std::min(fdiv(in.hi - k + p, s) + 1, size_out);
+    return Span{lo, hi};
+}
+
 inline Span intersect(Span a, Span b) { return Span{std::max(a.lo, b.lo), std::min(a.hi, b.hi)}; }
 
 // Part of `cur` whose source cur+d lies inside [0, size).
@@ -141,7 +150,8 @@ int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C, std::v
 }
 
 int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<dc_rect>& rects0,
-              int mx, int my, std::vector<TensorRegions>& out) {
+              int mx, int my, std::vector<TensorRegions>& out, bool extend_borders) {
+    const bool ext = extend_borders && mx == 0 && my == 0;
     out.assign(n_layers + 1, TensorRegions());
     TensorRegions& t0 = out[0];
     t0.h = H; t0.w = W; t0.dx = mx; t0.dy = my; t0.cum_stride = 1;
@@ -161,8 +171,13 @@ int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<d
         } else if (l.type == DC_LRN && l.within) {
             const int r = (l.k - 1) / 2;
             for (const dc_rect& rc : a.rects) {
-                if (rc.w - 2 * r <= 0 || rc.h - 2 * r <= 0) continue;
-                push_clipped(t.rects, Span{rc.x + r, rc.x + rc.w - r}, Span{rc.y + r, rc.y + rc.h - r}, t);
+                Span xs{rc.x + r, rc.x + rc.w - r}, ys{rc.y + r, rc.y + rc.h - r};
+                if (ext) {
+                    xs = window_span_ext(Span{rc.x, rc.x + rc.w}, l.k, 1, r, a.w);
+                    ys = window_span_ext(Span{rc.y, rc.y + rc.h}, l.k, 1, r, a.h);
+                }
+                if (xs.empty() || ys.empty()) continue;
+                push_clipped(t.rects, xs, ys, t);
             }
         } else if (l.type == DC_CONCAT) {
             int ids[4];
@@ -187,8 +202,8 @@ int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<d
             for (const auto& r : acc) push_clipped(t.rects, r.first, r.second, t);
         } else if (windowed) {
             for (const dc_rect& r : a.rects) {
-                Span xs = window_span(Span{r.x, r.x + r.w}, l.k, l.s, l.p);
-                Span ys = window_span(Span{r.y, r.y + r.h}, l.k, l.s, l.p);
+                Span xs = ext ? window_span_ext(Span{r.x, r.x + r.w}, l.k, l.s, l.p, a.w) : window_span(Span{r.x, r.x + r.w}, l.k, l.s, l.p);
+                Span ys = ext ? window_span_ext(Span{r.y, r.y + r.h}, l.k, l.s, l.p, a.h) : window_span(Span{r.y, r.y + r.h}, l.k, l.s, l.p);
                 if (xs.empty() || ys.empty()) continue;
                 push_clipped(t.rects, xs, ys, t);
             }

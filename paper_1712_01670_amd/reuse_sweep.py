@@ -14,7 +14,7 @@ the three modes and the saving 1 - t_mode / t_full.
 
     python paper_1712_01670_amd/reuse_sweep.py [--net darknet19|vgg16] [--size 416] [--dtype bf16|f32]
                                                [--streams n] [--matcher es|ds] [--k-skip k]
-                                               [--pan dx,dy] [--in-place]
+                                               [--pan dx,dy] [--in-place] [--extend-borders]
 """
 from __future__ import annotations
 
@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--matcher", choices=["es", "ds"], default="es")
     ap.add_argument("--k-skip", type=int, default=1)
     ap.add_argument("--pan", default="2,0", help="background motion in pixels per frame; 0,0 is a static camera")
+    ap.add_argument("--extend-borders", action="store_true",
+                    help="border case of the region rule for streams that did not move (beyond the paper's table)")
     ap.add_argument("--in-place", action="store_true",
                     help="let frames in which no stream moved update the cached tensors in place (no copies)")
     args = ap.parse_args()
@@ -89,11 +91,11 @@ def main():
                          for s in range(args.streams)])                       # [streams][T][H][W][3]
         video = torch.from_numpy(np.ascontiguousarray(vids.transpose(1, 0, 2, 3, 4))).to(dev)
         out = {"target_reuse": r, "net": args.net, "size": args.size, "dtype": args.dtype, "frames": args.frames,
-               "streams": args.streams, "matcher": args.matcher, "k_skip": args.k_skip, "pan": list(pan), "in_place": bool(args.in_place)}
+               "streams": args.streams, "matcher": args.matcher, "k_skip": args.k_skip, "pan": list(pan), "in_place": bool(args.in_place), "extend_borders": bool(args.extend_borders)}
         for mode, expiry in (("cached", 1 << 30), ("expiry", args.expiry), ("full", 1 << 30)):
             runner = binding.StackRunner(layers, ws, bs, args.streams, H, W, 3, block=16, radius=16, dtype=dt, expiry=expiry,
                                          match_method=binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE,
-                                         k_skip=args.k_skip, in_place=args.in_place)
+                                         k_skip=args.k_skip, in_place=args.in_place, extend_borders=args.extend_borders)
             t, macs, reuse = timed(runner, video, mode)
             out[mode] = {"frames_per_s": args.streams / t, "ms_per_frame": t * 1e3 / args.streams}
             if mode != "full":

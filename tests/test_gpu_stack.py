@@ -17,17 +17,18 @@ def _rel_err(got, want):
 
 
 def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
-              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False):
+              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False,
+              extend_borders=False):
     """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
     n, T, H, W, C = videos.shape
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale, input_shape=(H, W, C))
     tol = 2e-2 if bf16 else 1e-4
     dt = binding.DC_BF16 if bf16 else binding.DC_F32
     runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
-                                 want_regions=True, k_skip=k_skip, in_place=in_place,
+                                 want_regions=True, k_skip=k_skip, in_place=in_place, extend_borders=extend_borders,
                                  match_method=binding.DC_MATCH_DIAMOND if diamond else binding.DC_MATCH_EXHAUSTIVE)
     streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry,
-                             diamond=diamond, k_skip=k_skip)
+                             diamond=diamond, k_skip=k_skip, extend_borders=extend_borders)
                for _ in range(n)]
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
     worst = 0.0
@@ -156,6 +157,19 @@ def test_in_place_frames_of_a_static_camera(oracle, bf16):
     assert runner.in_place_frames == [False, True, True, True]
     assert runner.stats.copy_bytes == 0 and runner.stats.macs_needed < runner.stats.macs_full
     assert min(reuse) > 0.5
+
+
+def test_border_case_of_a_static_camera(oracle):
+    """extend_borders: windows may reach into the zero padding when the stream did not move; regions and tensors
+    follow the oracle with the same option, and more pixels are reused than with the printed rule."""
+    layers = synth.vgg16()[:10]
+    video = np.stack([_static_then_moving(700 + s, 96, 96, 3, 2) for s in range(2)])
+    needed = {}
+    for ext in (False, True):
+        runner, _ = _run_both(oracle, layers, video, 16, 8, True, in_place=True, extend_borders=ext)
+        needed[ext] = runner.stats.macs_needed          # last frame: static again
+        assert runner.in_place_frames[-1]
+    assert needed[True] < needed[False]
 
 
 def test_in_place_and_copied_frames_mix(oracle):

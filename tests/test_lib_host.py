@@ -100,10 +100,10 @@ def test_argument_errors_are_reported_before_any_launch():
     assert e.value.status in (-2, -6)
 
 
-def _compare(oracle, layers, H, W, B, mask, mx, my):
-    got = binding.dc_propagate_regions(layers, H, W, B, mask, mx, my)
+def _compare(oracle, layers, H, W, B, mask, mx, my, extend=False):
+    got = binding.dc_propagate_regions(layers, H, W, B, mask, mx, my, extend_borders=extend)
     r0 = oracle.merge_blocks(mask, B)
-    want = oracle.propagate(layers, H, W, r0, mx, my)
+    want = oracle.propagate(layers, H, W, r0, mx, my, extend_borders=extend)
     for t in range(len(layers) + 1):
         assert got[t]["rects"].tolist() == want["rects"][t].tolist(), t
         assert list(got[t]["dxy"]) == want["dxy"][t].tolist(), t
@@ -266,3 +266,24 @@ def test_layer_table_validation_of_the_new_types():
     assert status([conv, synth._fc(8, 10, False, 1), synth._softmax(10, 2)]) == 0
     assert status([conv, synth._fc(4, 10, False, 1)]) == -3
     assert status([conv, synth._avgpool(8, 3, 2, 3, 1)]) == -1                          # padding >= kernel
+
+
+def test_host_regions_with_the_border_case_equal_oracle(oracle):
+    rng = np.random.default_rng(99)
+    grew = 0
+    for trial in range(60):
+        B = int(rng.choice([4, 8]))
+        H, W = B * int(rng.integers(4, 12)), B * int(rng.integers(4, 12)) + int(rng.integers(0, 3))
+        layers = _random_layers_all_types(rng, H, W) if trial % 2 else _random_layers(rng, H, W)
+        gh, gw = H // B, W // B
+        mask = (rng.random((gh, gw)) < rng.choice([0.8, 0.95, 1.0])).astype(np.uint8)
+        mx, my = (0, 0) if trial % 3 else (int(rng.integers(-B, B + 1)), int(rng.integers(-B, B + 1)))
+        _compare(oracle, layers, H, W, B, mask, mx, my, extend=True)
+        if (mx, my) == (0, 0):
+            r0 = oracle.merge_blocks(mask, B)
+            a = oracle.propagate(layers, H, W, r0, 0, 0)
+            b = oracle.propagate(layers, H, W, r0, 0, 0, extend_borders=True)
+            area = lambda pr: sum(int(r[2]) * int(r[3]) for t in pr["rects"] for r in t)
+            assert area(b) >= area(a)
+            grew += area(b) > area(a)
+    assert grew > 10
