@@ -617,26 +617,28 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uintx4* src, ui
 // A 1x1 layer is a plain GEMM [pixels][Cin] x [Cin][Cout] with nothing to reuse between taps, so it is bound by
 // memory (large maps, small K) or by the latency of its K loop (small maps, deep K: a stage is 16 KiB of loads
 // for 8 MFMAs per wavefront).  A workgroup of four wavefronts takes 4 units (64 pixels) x 64 channels and walks K
-// in chunks of 128 bytes per row through a ring of up to NSTG LDS stages that are filled NSTG - 1 chunks ahead
+// in chunks of 128 bytes per row through a ring of up to four LDS stages that are filled three chunks ahead
 // (buffer_load ... lds, one barrier per chunk); with 16 KiB per stage several workgroups share a CU and cover
-// each other's waits.  Rows of 128 bytes, chunk c of row r at position c ^ (r / 2) % 8: the 16 rows a fragment
+// each other's waits.  With many units the tile is 8 units x 128 channels on eight wavefronts (WM = 4): half the
+// bytes from L2 per multiply-add, which is what bounds the kernel then.  Rows of 128 bytes, chunk c of row r at position c ^ (r / 2) % 8: the 16 rows a fragment
 // read touches spread over all banks.  Stride 1 or 2 (a strided 1x1 projection reads every second pixel).
-// Weight row l16 of block j of a wavefront carries channel (l16 / 4) * 8 + 4 j + l16 % 4 of its 32, so that a lane
-// ends up with eight consecutive channels of one pixel and stores 16 (bf16) or 32 (fp32) contiguous bytes.
+// Weight row l16 of block j of a wavefront (NBW blocks) carries channel (l16 / 4) * 4 NBW + 4 j + l16 % 4 of its
+// 16 NBW, so that a lane ends up with 4 NBW consecutive channels of one pixel and stores them in 16-byte pieces.
 // Cin only has to be a whole number of 16-byte vectors (the last chunk is filled with zeros), Cout a multiple of 8.
 // Workgroups are numbered so that the channel tiles of one unit group run on the same XCD at about the same time:
 // the second to last of them find the input pixels in that XCD's L2.
-template <typename T, int NSTG>
-__global__ __launch_bounds__(256) void conv_pw_kernel(ConvParams P) {
+template <typename T, int WM>
+__global__ __launch_bounds__(WM * 128) void conv_pw_kernel(ConvParams P) {
     typedef Frag<T> F;
     typedef typename F::vec vec;
     constexpr int ES = (int)sizeof(T), VE = F::VE;
     constexpr int RB = 128, KC = RB / ES, GPC = 2;
-    constexpr int G = 4, NT = 64, UPW = 2, NBW = 2, WN = 2, NW = 4;
+    constexpr int UPW = 2, NBW = WM, WN = 2, NW = WM * WN, NSTG = 4;
+    constexpr int G = WM * UPW, NT = WN * NBW * 16;   // WM = 2: 4 units x 64 channels; WM = 4: 8 units x 128 channels
     constexpr int PBYTES = G * 16 * RB;             // patch rows of a stage, then the weight rows
     constexpr int STAGE = PBYTES + NT * RB;
     constexpr int D = NSTG - 1;                     // chunks in flight ahead of the one being multiplied
-    static_assert(NSTG == 2 || NSTG == 4 || NSTG == 8, "ring size");
+    static_assert(WM == 2 || WM == 4, "two patch and two weight load instructions per wavefront and stage");
 
     extern __shared__ __align__(16) unsigned char smem[];
     const FastHeader<G> H(smem);
@@ -688,7 +690,7 @@ __global__ __launch_bounds__(256) void conv_pw_kernel(ConvParams P) {
     __syncthreads();
 
     // load side: instruction j of a stage fills its LDS bytes [1024 j, 1024 j + 1024) = rows 8 j .. 8 j + 7; this
-    // wavefront issues j = wave and wave + 4 of the patch rows and of the weight rows
+    // wavefront issues j = wave and wave + NW of the patch rows and of the weight rows
     const int lrow = lane >> 3, lpos = lane & 7;
     uint32_t pgo[2], wgo[2];
     int lch[2];                                     // first channel (within a chunk) of the vector the lane fetches
@@ -701,7 +703,7 @@ __global__ __launch_bounds__(256) void conv_pw_kernel(ConvParams P) {
         const int4 uq = H.uq[g];
         const bool ok = uq.y + oy < P.Hout && uq.z + ox < P.Wout;
         pgo[i] = ok ? (uint32_t)(uq.x + (oy * P.Win + ox) * P.s * CinES + (c << 4)) : kOob;
-        const int ch = n0 + (row >> 5) * 32 + ((row & 15) >> 2) * 8 + ((row >> 4) & 1) * 4 + (row & 3);
+        const int ch = n0 + row / (NBW * 16) * (NBW * 16) + ((row & 15) >> 2) * (4 * NBW) + ((row >> 4) % NBW) * 4 + (row & 3);
         wgo[i] = ch < P.Cout ? (uint32_t)(ch * CinES + (c << 4)) : kOob;
     }
     auto issue = [&](int chunk, int slot) {
@@ -749,15 +751,9 @@ __global__ __launch_bounds__(256) void conv_pw_kernel(ConvParams P) {
     for (int c = 0; c < n_ch; ++c) {
         // the loads of chunk c are complete when at most the later chunks' (4 instructions each) are outstanding
         const int ahead = n_ch - 1 - c < D - 1 ? n_ch - 1 - c : D - 1;
-        switch (ahead) {
-            case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-            case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
-            case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
-            case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
-            case 4: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
-            case 5: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
-            default: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
-        }
+        if (ahead >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (ahead == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();                            // chunk c is in LDS; everyone is done with chunk c - 1
         if (c + D < n_ch) issue(chunk_of(c + D), (c + D) % NSTG);
         const unsigned char* sb = ring + (c % NSTG) * STAGE;
@@ -777,34 +773,38 @@ __global__ __launch_bounds__(256) void conv_pw_kernel(ConvParams P) {
         }
     }
 
-    const int chan0 = n0 + wave_n * 32 + q * 8;
+    // a lane holds 4 NBW consecutive channels of each of its pixels
+    const int chan0 = n0 + wave_n * (NBW * 16) + q * (4 * NBW);
     if (chan0 >= P.Cout) return;
-    floatx4 b0{0.f, 0.f, 0.f, 0.f}, b1{0.f, 0.f, 0.f, 0.f};
-    if (P.bias) {
-        b0 = *reinterpret_cast<const floatx4*>(P.bias + chan0);
-        b1 = *reinterpret_cast<const floatx4*>(P.bias + chan0 + 4);
-    }
+    floatx4 b[NBW];
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+        b[j] = (P.bias && chan0 + j * 4 < P.Cout) ? *reinterpret_cast<const floatx4*>(P.bias + chan0 + j * 4) : floatx4{0.f, 0.f, 0.f, 0.f};
     const bool relu = P.relu != 0;
 #pragma unroll
     for (int u = 0; u < UPW; ++u) {
         const int g = wave_m * UPW + u;
         if (H.skip[g * 16 + l16]) continue;
         T* px = reinterpret_cast<T*>(P.out) + H.uq[g].w + ((l16 >> 2) * P.Wout + (l16 & 3)) * P.Cout + chan0;
-        floatx4 v0 = acc[u][0] + b0, v1 = acc[u][1] + b1;
-        if (relu) {
-            v0[0] = fmaxf(v0[0], 0.f); v0[1] = fmaxf(v0[1], 0.f); v0[2] = fmaxf(v0[2], 0.f); v0[3] = fmaxf(v0[3], 0.f);
-            v1[0] = fmaxf(v1[0], 0.f); v1[1] = fmaxf(v1[1], 0.f); v1[2] = fmaxf(v1[2], 0.f); v1[3] = fmaxf(v1[3], 0.f);
-        }
-        if constexpr (sizeof(T) == 2) {             // eight bf16 channels in one 16-byte store
-            uintx4 w4;
-            w4[0] = (uint32_t)F::bits(v0[0]) | ((uint32_t)F::bits(v0[1]) << 16);
-            w4[1] = (uint32_t)F::bits(v0[2]) | ((uint32_t)F::bits(v0[3]) << 16);
-            w4[2] = (uint32_t)F::bits(v1[0]) | ((uint32_t)F::bits(v1[1]) << 16);
-            w4[3] = (uint32_t)F::bits(v1[2]) | ((uint32_t)F::bits(v1[3]) << 16);
-            *reinterpret_cast<uintx4*>(px) = w4;
-        } else {
-            F::store4(px, v0);
-            F::store4(px + 4, v1);
+#pragma unroll
+        for (int j = 0; j < NBW; j += 2) {          // eight channels at a time (Cout is a multiple of 8)
+            if (chan0 + j * 4 >= P.Cout) break;
+            floatx4 v0 = acc[u][j] + b[j], v1 = acc[u][j + 1] + b[j + 1];
+            if (relu) {
+                v0[0] = fmaxf(v0[0], 0.f); v0[1] = fmaxf(v0[1], 0.f); v0[2] = fmaxf(v0[2], 0.f); v0[3] = fmaxf(v0[3], 0.f);
+                v1[0] = fmaxf(v1[0], 0.f); v1[1] = fmaxf(v1[1], 0.f); v1[2] = fmaxf(v1[2], 0.f); v1[3] = fmaxf(v1[3], 0.f);
+            }
+            if constexpr (sizeof(T) == 2) {         // eight bf16 channels in one 16-byte store
+                uintx4 w4;
+                w4[0] = (uint32_t)F::bits(v0[0]) | ((uint32_t)F::bits(v0[1]) << 16);
+                w4[1] = (uint32_t)F::bits(v0[2]) | ((uint32_t)F::bits(v0[3]) << 16);
+                w4[2] = (uint32_t)F::bits(v1[0]) | ((uint32_t)F::bits(v1[1]) << 16);
+                w4[3] = (uint32_t)F::bits(v1[2]) | ((uint32_t)F::bits(v1[3]) << 16);
+                *reinterpret_cast<uintx4*>(px + j * 4) = w4;
+            } else {
+                F::store4(px + j * 4, v0);
+                F::store4(px + j * 4 + 4, v1);
+            }
         }
     }
 }
@@ -1125,8 +1125,8 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) 
 // 110.. the wide arrangement.
 void conv_fast_kernel_name(int id, char* buf, size_t n) {
     if (id == 126) { snprintf(buf, n, "conv_regw_kernel<2, 2>"); return; }
-    if (id == 127 || id == 128 || id == 108 || id == 109) {      // 108 + bf16 (4 ring stages), 127 + bf16 (8): conv_pw_kernel (1x1)
-        snprintf(buf, n, "conv_pw_kernel<%s, %d>", id == 109 || id == 128 ? "__hip_bfloat16" : "float", id >= 127 ? 8 : 4);
+    if (id == 127 || id == 128 || id == 108 || id == 109) {      // 108 + bf16 (64 x 64 tile), 127 + bf16 (128 x 128): conv_pw_kernel (1x1)
+        snprintf(buf, n, "conv_pw_kernel<%s, %d>", id == 109 || id == 128 ? "__hip_bfloat16" : "float", id >= 127 ? 4 : 2);
         return;
     }
     if (id >= 110) {  // 110 + (arrangement - 1) * 8 + kci * 4 + UPW - 1: the wide bf16 arrangements
@@ -1184,21 +1184,22 @@ hipError_t regw_launch(dim3 grid, hipStream_t st, const ConvParams& P) {
 }
 
 // Launches the layer with the kernel of this file if its shape qualifies; returns false otherwise.
-template <typename T, int NSTG>
+template <typename T, int WM>
 hipError_t pw_launch_n(dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
     static size_t allowed = 64 * 1024;
     if (lds > allowed) {
-        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_pw_kernel<T, NSTG>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kHeaderBytes + NSTG * 16384));
+        const size_t most = kHeaderBytes + 4 * (size_t)(WM * 8192);
+        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_pw_kernel<T, WM>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
         if (a != hipSuccess) return a;
-        allowed = kHeaderBytes + NSTG * 16384;
+        allowed = most;
     }
-    hipLaunchKernelGGL((conv_pw_kernel<T, NSTG>), grid, dim3(256), lds, st, P);
+    hipLaunchKernelGGL((conv_pw_kernel<T, WM>), grid, dim3(WM * 128), lds, st, P);
     return hipGetLastError();
 }
 template <typename T>
-hipError_t pw_launch(int nstg, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
-    return nstg == 8 ? pw_launch_n<T, 8>(grid, lds, st, P) : pw_launch_n<T, 4>(grid, lds, st, P);
+hipError_t pw_launch(int wm, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
+    return wm == 4 ? pw_launch_n<T, 4>(grid, lds, st, P) : pw_launch_n<T, 2>(grid, lds, st, P);
 }
 bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err) {
     static int enabled = -1;
@@ -1237,9 +1238,14 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         static int pw_enabled = -1;
         if (pw_enabled < 0) { const char* e = getenv("DC_CONV_PW"); pw_enabled = e ? atoi(e) : 1; }
         const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
-        const long R = (c.Cout + 63) / 64, tiles = (n_units + 3) / 4 * R;
+        // Tile: 4 units x 64 channels; with enough of those to give every CU several, 8 units x 128 channels
+        init_tuning();
+        const long small_tiles = (n_units + 3) / 4 * ((c.Cout + 63) / 64);
+        const int wm = g_tune[1] == 8 ? 4 : (g_tune[1] == 4 ? 2 : (small_tiles >= 4096 && c.Cout >= 128 ? 4 : 2));
+        const int g_units = 2 * wm, nt = 32 * wm;
+        const long R = (c.Cout + nt - 1) / nt, tiles = (n_units + g_units - 1) / g_units * R;
         if (pw_enabled && (double)c.n_streams * c.Hout * c.Wout * c.Cout < 2147483648.0 &&
-            (double)n_units * units_x * units_y < 4294967296.0 && tiles + 8 < 2147483647L) {
+            (double)n_units * units_x * units_y < 4294967296.0 && tiles + 8 < 2147483647L / (wm * 128)) {
             ConvParams P{};
             P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
             P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
@@ -1256,16 +1262,12 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
             P.n_wg_tiles = (int)tiles;
             P.tiles_per_xcd = (int)((tiles + 7) / 8);
             // Every kernel starts with cold caches, so a workgroup's walk over K is a chain of long-latency loads:
-            // what counts is the number of chunks in flight per CU.  With at most one workgroup per CU the ring
-            // takes most of the LDS (8 stages); otherwise 4 stages and two or more workgroups per CU.
-            static int f_stg = -1;
-            if (f_stg < 0) { const char* e = getenv("DC_CONV_PW_STAGES"); f_stg = e ? atoi(e) : 0; }
-            const int nstg = f_stg == 4 || f_stg == 8 ? f_stg : (tiles <= 256 && P.n_chunks > 4 ? 8 : 4);
-            const int stages = P.n_chunks < nstg ? P.n_chunks : nstg;
-            const size_t lds = kHeaderBytes + (size_t)stages * 16384;
-            if (c.kernel_id) *c.kernel_id = (nstg == 8 ? 127 : 108) + (c.dtype == DC_BF16 ? 1 : 0);
-            *err = c.dtype == DC_BF16 ? pw_launch<__hip_bfloat16>(nstg, dim3((unsigned)(8 * P.tiles_per_xcd)), lds, st, P)
-                                      : pw_launch<float>(nstg, dim3((unsigned)(8 * P.tiles_per_xcd)), lds, st, P);
+            // up to four chunks are in flight per workgroup, and several workgroups share a CU.
+            const int stages = P.n_chunks < 4 ? P.n_chunks : 4;
+            const size_t lds = kHeaderBytes + (size_t)stages * (size_t)(wm * 8192);
+            if (c.kernel_id) *c.kernel_id = (wm == 4 ? 127 : 108) + (c.dtype == DC_BF16 ? 1 : 0);
+            *err = c.dtype == DC_BF16 ? pw_launch<__hip_bfloat16>(wm, dim3((unsigned)(8 * P.tiles_per_xcd)), lds, st, P)
+                                      : pw_launch<float>(wm, dim3((unsigned)(8 * P.tiles_per_xcd)), lds, st, P);
             return true;
         }
     }

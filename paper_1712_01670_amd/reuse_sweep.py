@@ -12,7 +12,7 @@ ways on one GPU:
 One JSON line per ratio: measured reuse ratio, fraction of MACs needed and issued, frames/s of
 the three modes and the saving 1 - t_mode / t_full.
 
-    python paper_1712_01670_amd/reuse_sweep.py [--net darknet19|vgg16] [--size 416] [--dtype bf16|f32]
+    python paper_1712_01670_amd/reuse_sweep.py [--net darknet19|vgg16|resnet50|alexnet|googlenet] [--size 416] [--dtype bf16|f32]
                                                [--streams n] [--matcher es|ds] [--k-skip k]
                                                [--pan dx,dy] [--in-place] [--extend-borders]
 """
@@ -31,7 +31,7 @@ if ROOT not in sys.path:
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--net", choices=["darknet19", "vgg16"], default="darknet19")
+    ap.add_argument("--net", choices=["darknet19", "vgg16", "resnet50", "alexnet", "googlenet"], default="darknet19")
     ap.add_argument("--size", type=int, default=416)
     ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--ratios", default="0,0.25,0.5,0.75,0.95")
@@ -56,8 +56,10 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     H = W = args.size
-    layers = synth.darknet19() if args.net == "darknet19" else synth.vgg16()
-    ws, bs = synth.he_weights(layers, 1)
+    layers = {"darknet19": synth.darknet19, "vgg16": synth.vgg16, "resnet50": synth.resnet50_trunk,
+              "alexnet": synth.alexnet, "googlenet": synth.googlenet}[args.net]()
+    layers = synth.resolve_global_pooling(layers, H, W, 3)
+    ws, bs = synth.he_weights(layers, 1, residual_scale=0.5 if args.net == "resnet50" else 1.0, input_shape=(H, W, 3))
     dt = binding.DC_BF16 if args.dtype == "bf16" else binding.DC_F32
     cut = args.frames // 2
 

@@ -400,13 +400,22 @@ PW_CASES = [
 ]
 
 
+@pytest.fixture
+def pw_tile(request):
+    """Forces the 1x1 kernel's tile (units per workgroup) for one test."""
+    binding.dc_conv_tuning(units_per_workgroup=request.param)
+    yield request.param
+    binding.dc_conv_tuning()
+
+
 @pytest.mark.parametrize("cached", [False, True])
 @pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("pw_tile", [4, 8], indirect=True)
 @pytest.mark.parametrize("case", PW_CASES)
-def test_pointwise_kernel(oracle, case, bf16, cached):
-    """1x1 convolutions (stride 1 and 2) on the GEMM kernel with the staged K ring."""
+def test_pointwise_kernel(oracle, case, pw_tile, bf16, cached):
+    """1x1 convolutions (stride 1 and 2) on the GEMM kernel with the staged K ring, both tile sizes."""
     H, W, cin, cout, s = case
-    print(f"[pointwise] case={case} bf16={bf16} cached={cached}", flush=True)
+    print(f"[pointwise] case={case} tile={pw_tile} bf16={bf16} cached={cached}", flush=True)
     rng = np.random.default_rng(sum(case) + 3)
     n = 3
     Ho, Wo = (H - 1) // s + 1, (W - 1) // s + 1

@@ -72,8 +72,8 @@ def test_argument_errors_are_reported_before_any_launch():
     assert binding.conv_kernel_name(96 + 2) == "conv_first_kernel<float, 4>"
     assert binding.conv_kernel_name(102 + 2 + 1) == "conv_stem_kernel<__hip_bfloat16, 2>"
     assert binding.conv_kernel_name(107) == "conv_stem11_kernel<__hip_bfloat16>"
-    assert binding.conv_kernel_name(108) == "conv_pw_kernel<float, 4>"
-    assert binding.conv_kernel_name(128) == "conv_pw_kernel<__hip_bfloat16, 8>"
+    assert binding.conv_kernel_name(108) == "conv_pw_kernel<float, 2>"
+    assert binding.conv_kernel_name(128) == "conv_pw_kernel<__hip_bfloat16, 4>"
     assert binding.conv_kernel_name(110 + 3) == "conv_fast_kernel<__hip_bfloat16, 3, 32, 4, 4, 2, 4>"
     assert binding.conv_kernel_name(110 + 8 + 4) == "conv_fast_kernel<__hip_bfloat16, 3, 64, 1, 4, 2, 2>"
     assert binding.conv_kernel_name(126) == "conv_regw_kernel<2, 2>"
