@@ -27,6 +27,7 @@
 // chunks among ks workgroups per tile, which store fp32 partial sums to scratch memory; a second
 // kernel adds them in a fixed order and applies the epilogue.  Every workgroup then loads only its
 // share of the weights, which is what bounds these layers.
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <type_traits>
@@ -1203,6 +1204,8 @@ hipError_t pw_launch(int wm, dim3 grid, size_t lds, hipStream_t st, const ConvPa
 }
 bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err) {
     static int enabled = -1;
+    static int g_stem_wgs = -1;
+    if (g_stem_wgs < 0) { const char* e = getenv("DC_CONV_STEM_WGS"); g_stem_wgs = e && atoi(e) > 0 ? atoi(e) : 256; }
     if (enabled < 0) { const char* e = getenv("DC_CONV_FAST"); enabled = e ? atoi(e) : 1; }
     const size_t esz = dtype_size(c.dtype);
     if (enabled && ((c.k == 3 && c.s == 1) || (c.k == 7 && c.s == 2) || (c.k == 11 && c.s == 4)) && c.Cin * esz == 16 && c.Cout % 16 == 0 &&
@@ -1222,7 +1225,11 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
             P.w_bytes = (uint32_t)((size_t)c.Cout * c.k * c.k * 16);
             // the 7x7 kernel keeps 14 weight vectors per channel block in registers: two blocks at most
             const int nb = c.k == 11 ? 1 : (c.Cout % 64 == 0 && c.k == 3 ? 4 : (c.Cout % 32 == 0 ? 2 : 1));
-            const long wgx = (n_units + 3) / 4 < 2048 ? (n_units + 3) / 4 : 2048;   // four units at a time, at most 8 workgroups per CU
+            // four units at a time.  3x3: at most 8 workgroups per CU.  The large kernels hold one workgroup per CU
+            // (registers) and pay 28 / 33 weight loads per wavefront before the first unit, so the launch is one
+            // persistent workgroup per CU and channel block, each walking its share of the units.
+            const long cap = c.k == 3 ? 2048 : std::max(1L, (long)g_stem_wgs / (c.Cout / (16 * nb)));
+            const long wgx = (n_units + 3) / 4 < cap ? (n_units + 3) / 4 : cap;
             if (c.kernel_id)
                 *c.kernel_id = c.k == 11 ? 106 + (c.dtype == DC_BF16 ? 1 : 0)
                              : c.k == 7 ? 102 + (c.dtype == DC_BF16 ? 2 : 0) + (nb == 2 ? 1 : 0)
