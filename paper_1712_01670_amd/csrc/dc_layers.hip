@@ -340,6 +340,44 @@ __global__ __launch_bounds__(kThreads) void pool_vec_kernel(const uint4* __restr
     }
 }
 
+// out = a + b (b == nullptr: out = a), optional ReLU, 16 bytes per thread.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void add_vec_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b,
+                                                           uint4* __restrict__ out, size_t n_vec, int relu) {
+    constexpr int VE = Vec16<T>::VE;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (; i < n_vec; i += stride) {
+        float x[VE], y[VE];
+        Vec16<T>::load(a + i, x);
+        if (b) {
+            Vec16<T>::load(b + i, y);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) x[e] += y[e];
+        }
+        if (relu) {
+#pragma unroll
+            for (int e = 0; e < VE; ++e) x[e] = x[e] > 0.f ? x[e] : 0.f;
+        }
+        Vec16<T>::store(out + i, x);
+    }
+}
+
+// The input conversion for a tensor pixel of exactly 16 bytes (the padded first layer): one thread per pixel.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void frame_to_tensor_px_kernel(const uint8_t* __restrict__ f, uint4* __restrict__ out,
+                                                                      size_t n_pixels, int cf) {
+    constexpr int VE = Vec16<T>::VE;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (; i < n_pixels; i += stride) {
+        float v[VE];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) v[e] = e < cf ? (float)((int)f[i * cf + e] - 128) * (1.0f / 128.0f) : 0.f;
+        Vec16<T>::store(out + i, v);
+    }
+}
+
 // LRN over channels with radius R <= VE: the thread's vector and its two neighbours hold every channel of the window.
 template <typename T, int R>
 __global__ __launch_bounds__(kThreads) void lrn_vec_kernel(const uint4* __restrict__ in, uint4* __restrict__ out,
@@ -452,6 +490,15 @@ hipError_t launch_frame_to_tensor(const uint8_t* f, void* out, size_t n_pixels, 
                                   hipStream_t st) {
     const size_t n = n_pixels * ct;
     if (n == 0) return hipSuccess;
+    if (ct * dtype_size(dtype) == 16 && reinterpret_cast<uintptr_t>(out) % 16 == 0) {
+        if (dtype == DC_BF16)
+            hipLaunchKernelGGL(frame_to_tensor_px_kernel<__hip_bfloat16>, dim3(grid_for(n_pixels)), dim3(kThreads), 0, st, f,
+                               (uint4*)out, n_pixels, cf);
+        else
+            hipLaunchKernelGGL(frame_to_tensor_px_kernel<float>, dim3(grid_for(n_pixels)), dim3(kThreads), 0, st, f,
+                               (uint4*)out, n_pixels, cf);
+        return hipGetLastError();
+    }
     if (dtype == DC_BF16)
         hipLaunchKernelGGL(frame_to_tensor_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st, f,
                            (__hip_bfloat16*)out, n, cf, ct);
@@ -614,6 +661,17 @@ hipError_t launch_fc(const void* x, const void* w, const float* bias, void* out,
 
 hipError_t launch_add(const void* a, const void* b, void* out, size_t n, int relu, int dtype, hipStream_t st) {
     if (n == 0) return hipSuccess;
+    if ((n * dtype_size(dtype)) % 16 == 0 && reinterpret_cast<uintptr_t>(a) % 16 == 0 && reinterpret_cast<uintptr_t>(b) % 16 == 0 &&
+        reinterpret_cast<uintptr_t>(out) % 16 == 0) {
+        const size_t nv = n * dtype_size(dtype) / 16;
+        if (dtype == DC_BF16)
+            hipLaunchKernelGGL(add_vec_kernel<__hip_bfloat16>, dim3(grid_for(nv)), dim3(kThreads), 0, st, (const uint4*)a,
+                               (const uint4*)b, (uint4*)out, nv, relu);
+        else
+            hipLaunchKernelGGL(add_vec_kernel<float>, dim3(grid_for(nv)), dim3(kThreads), 0, st, (const uint4*)a, (const uint4*)b,
+                               (uint4*)out, nv, relu);
+        return hipGetLastError();
+    }
     if (dtype == DC_BF16)
         hipLaunchKernelGGL(add_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st,
                            (const __hip_bfloat16*)a, (const __hip_bfloat16*)b, (__hip_bfloat16*)out, n, relu);

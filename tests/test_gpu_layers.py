@@ -326,8 +326,14 @@ def test_uncached_layers(oracle, bf16):
     dt = binding.DC_BF16 if bf16 else binding.DC_F32
     got = _to_np(binding.dc_frame_to_tensor(torch.from_numpy(f).to(DEV), dt))
     assert np.array_equal(got, oracle.frame_to_tensor(f))
-    got = _to_np(binding.dc_frame_to_tensor(torch.from_numpy(f).to(DEV), dt, c_tensor=8))
-    assert np.array_equal(got[..., :3], oracle.frame_to_tensor(f)) and not got[..., 3:].any()
+    for ct in (4, 8):      # a tensor pixel of exactly 16 bytes (fp32 x 4, bf16 x 8) takes the per-pixel kernel
+        got = _to_np(binding.dc_frame_to_tensor(torch.from_numpy(f).to(DEV), dt, c_tensor=ct))
+        assert np.array_equal(got[..., :3], oracle.frame_to_tensor(f)) and not got[..., 3:].any()
+    # element counts that are not whole 16-byte vectors
+    xs, ys = x[:, :5, :7, :3].copy(), y[:, :5, :7, :3].copy()
+    for relu in (0, 1):
+        got = _to_np(binding.dc_add_layer(_to_dev(xs, bf16), _to_dev(ys, bf16), relu))
+        assert np.array_equal(got, oracle.add(xs, ys, relu, bf16=bf16))
 
 
 @pytest.mark.parametrize("bf16", [False, True])
