@@ -197,7 +197,9 @@ __device__ __forceinline__ float wave_max_f32(float v) {
     return v;
 }
 
-// Softmax over the channels of a pixel; one wavefront per pixel, the largest element subtracted first.
+// Softmax over the channels of a pixel; one wavefront per pixel, the largest element subtracted first.  Up to 1024
+// channels are read once and kept in registers (a pixel of a classifier's output is read from cold memory, and each
+// pass over it would pay that latency again).
 template <typename T>
 __global__ __launch_bounds__(kThreads) void softmax_kernel(const T* __restrict__ in, T* __restrict__ out, size_t n_pixels,
                                                            int C) {
@@ -205,6 +207,24 @@ __global__ __launch_bounds__(kThreads) void softmax_kernel(const T* __restrict__
     const size_t px = (size_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
     if (px >= n_pixels) return;                   // whole wavefronts leave
     const T* v = in + px * C;
+    if (C <= 1024) {
+        float r[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) r[i] = lane + 64 * i < C ? to_float(v[lane + 64 * i]) : -INFINITY;
+        float m = r[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) m = fmaxf(m, r[i]);
+        m = wave_max_f32(m);
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { r[i] = expf(r[i] - m); sum += r[i]; }    // exp(-inf) = 0 for the padding
+        sum = wave_sum_f32(sum);
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (lane + 64 * i < C) out[px * C + lane + 64 * i] = from_float<T>(r[i] * inv);
+        return;
+    }
     float m = -INFINITY;
     for (int c = lane; c < C; c += 64) m = fmaxf(m, to_float(v[c]));
     m = wave_max_f32(m);

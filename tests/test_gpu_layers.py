@@ -366,7 +366,7 @@ def test_lrn_avgpool_concat_softmax_layers(oracle, bf16):
         got = _to_np(binding.dc_concat_layer([_to_dev(q, bf16) for q in parts]))
         for i in range(n):
             assert np.array_equal(got[i], oracle.concat([q[i] for q in parts])), cs
-    for c in (10, 64, 1000):
+    for c in (10, 64, 1000, 1024, 1500):      # up to 1024 channels stay in registers
         v = (rng.standard_normal((n, 2, 3, c)) * 4).astype(np.float32)
         if bf16:
             v = oracle.round_bf16(v)
