@@ -9,7 +9,9 @@ HBM before the timed region starts.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--dtype f32|bf16] [--streams n]
 
-Prints one JSON line ("Measurement").
+Prints one JSON line: whole-job frames/s with the cache (`value`) and without it (`no_cache`), the roofline of
+the dominant convolution kernel measured with HIP events during the run, and the CPU oracle timed on a bounded
+sample of the same video.
 """
 from __future__ import annotations
 
