@@ -131,6 +131,21 @@ def test_alexnet_style_stack_small(oracle, bf16):
     assert len(reuse) == 4 and min(reuse) > 0.2
 
 
+def test_alexnet_full_width_fp32(oracle):
+    """The AlexNet-style stack at its real widths (96-256-384-384-256 channels, 4096-wide fully-connected layers),
+    227x227, the paper's 10-pixel blocks: every tensor of a full and a cached frame against the oracle."""
+    layers = synth.alexnet()
+    video = synth.panning_video(310, n_frames=2, H=227, W=227)[None]
+    _run_both(oracle, layers, video, 10, 8, False, bias_scale=0.02)
+
+
+def test_googlenet_full_width_bf16(oracle):
+    """The GoogLeNet-style stack at its real widths, 224x224, bf16: a full and a cached frame."""
+    layers = synth.resolve_global_pooling(synth.googlenet(), 224, 224, 3)
+    video = synth.panning_video(410, n_frames=2, H=224, W=224)[None]
+    _run_both(oracle, layers, video, 16, 8, True, bias_scale=0.02)
+
+
 def test_googlenet_style_stack_small(oracle):
     """Inception modules: four branches of different depth joined by a concat; global average pooling at the end."""
     layers = synth.resolve_global_pooling(synth.googlenet(n_classes=24, width=0.25), 224, 224, 3)
