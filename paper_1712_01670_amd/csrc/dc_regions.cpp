@@ -2,6 +2,7 @@
 // propagating rectangles through the layer table (Section 5, Table 2) and sorting the
 // output tiles of a conv layer into clean / mixed / dirty for the GEMM tile list.
 #include <algorithm>
+#include <cstring>
 #include <atomic>
 #include <condition_variable>
 #include <mutex>
@@ -226,7 +227,7 @@ int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<d
 
 void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Hout, int Wout, int th,
                  int tw, LayerPlan& plan) {
-    // tiles are 4x4 pixels: the reusable pixels of a tile are one 16-bit mask
+    // tiles are 4x4 pixels: the reusable pixels of a tile are one 16-bit mask (bit 4*row + column)
     (void)th; (void)tw;
     const int tiles_y = (Hout + 3) / 4, tiles_x = (Wout + 3) / 4;
     static thread_local std::vector<uint16_t> reuse;          // kept between calls: no allocation per layer and frame
@@ -238,27 +239,53 @@ void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Ho
         plan.rects.push_back(RectDev{r.x, r.y, r.w, r.h, stream, dx, dy, 0});
         ++range.count;
         plan.reused_px += (int64_t)r.w * r.h;
+        const int tx0 = r.x / 4, tx1 = (r.x + r.w - 1) / 4;
+        const int fx0 = (r.x + 3) / 4, fx1 = (r.x + r.w) / 4;    // tile columns [fx0, fx1) lie wholly inside the rectangle
         for (int ty = r.y / 4; ty <= (r.y + r.h - 1) / 4; ++ty) {
             const int ya = std::max(r.y, ty * 4) - ty * 4, yb = std::min(r.y + r.h, ty * 4 + 4) - ty * 4;
             unsigned rows = 0;                                   // bit 4*y set for the covered rows
             for (int y = ya; y < yb; ++y) rows |= 1u << (4 * y);
-            for (int tx = r.x / 4; tx <= (r.x + r.w - 1) / 4; ++tx) {
+            uint16_t* rowp = reuse.data() + (size_t)ty * tiles_x;
+            auto partial = [&](int tx) {
                 const int xa = std::max(r.x, tx * 4) - tx * 4, xb = std::min(r.x + r.w, tx * 4 + 4) - tx * 4;
                 const unsigned cols = ((1u << xb) - 1u) & ~((1u << xa) - 1u);
-                reuse[(size_t)ty * tiles_x + tx] |= (uint16_t)(rows * cols);
+                rowp[tx] |= (uint16_t)(rows * cols);
+            };
+            if (rows == 0x1111u && fx1 > fx0) {                  // the interior of the rectangle: whole tiles
+                for (int tx = tx0; tx < fx0; ++tx) partial(tx);
+                std::fill(rowp + fx0, rowp + fx1, (uint16_t)0xffff);
+                for (int tx = fx1; tx <= tx1; ++tx) partial(tx);
+            } else {
+                for (int tx = tx0; tx <= tx1; ++tx) partial(tx);
             }
         }
     }
     plan.ranges.push_back(range);
-    for (int ty = 0; ty < tiles_y; ++ty)
-        for (int tx = 0; tx < tiles_x; ++tx) {
-            unsigned inside = 0;                                 // pixels of the tile that lie in the map
-            const int hh = std::min(4, Hout - ty * 4), ww = std::min(4, Wout - tx * 4);
-            for (int y = 0; y < hh; ++y) inside |= ((1u << ww) - 1u) << (4 * y);
-            const unsigned m = reuse[(size_t)ty * tiles_x + tx];
-            if ((m & inside) == inside) continue;  // every pixel is served by the copy
-            plan.tiles.push_back(TileDev{stream, ty, tx, (int32_t)m});
+    // a tile is listed unless every pixel of it that lies in the map is served by the copy
+    const int full_cols = Wout / 4;                              // tile columns with all four pixel columns in the map
+    for (int ty = 0; ty < tiles_y; ++ty) {
+        const uint16_t* rowp = reuse.data() + (size_t)ty * tiles_x;
+        const int hh = std::min(4, Hout - ty * 4);
+        unsigned rows = 0;
+        for (int y = 0; y < hh; ++y) rows |= 1u << (4 * y);
+        const unsigned inside_full = rows * 0xfu;
+        int tx = 0;
+        if (inside_full == 0xffffu) {
+            for (; tx + 4 <= full_cols; tx += 4) {               // four tiles at a time: the common case is "all reusable"
+                uint64_t v;
+                std::memcpy(&v, rowp + tx, sizeof(v));
+                if (v == ~0ull) continue;
+                for (int k = 0; k < 4; ++k)
+                    if (rowp[tx + k] != 0xffffu) plan.tiles.push_back(TileDev{stream, ty, tx + k, (int32_t)rowp[tx + k]});
+            }
         }
+        for (; tx < full_cols; ++tx)
+            if ((rowp[tx] & inside_full) != inside_full) plan.tiles.push_back(TileDev{stream, ty, tx, (int32_t)rowp[tx]});
+        if (full_cols < tiles_x) {                               // the last column holds Wout % 4 pixel columns
+            const unsigned inside = rows * ((1u << (Wout - full_cols * 4)) - 1u);
+            if ((rowp[tx] & inside) != inside) plan.tiles.push_back(TileDev{stream, ty, tx, (int32_t)rowp[tx]});
+        }
+    }
 }
 
 
