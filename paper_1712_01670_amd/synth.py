@@ -158,6 +158,22 @@ def alexnet(n_classes=1000, width=1.0):
     return L
 
 
+def dave_orig():
+    """The steering network of Table 3 (DRV): five convolutions without padding (three 5x5 stride 2 with 24, 36 and
+    48 channels, two 3x3 with 64) on a 66x200 frame, then fully-connected layers of 100, 50, 10 and 1 outputs."""
+    L = []
+    L.append(_conv(3, 24, 5, 2, 0, True, 0))
+    L.append(_conv(24, 36, 5, 2, 0, True, len(L)))
+    L.append(_conv(36, 48, 5, 2, 0, True, len(L)))
+    L.append(_conv(48, 64, 3, 1, 0, True, len(L)))
+    L.append(_conv(64, 64, 3, 1, 0, True, len(L)))
+    L.append(_fc(64, 100, True, len(L)))
+    L.append(_fc(100, 50, True, len(L)))
+    L.append(_fc(50, 10, True, len(L)))
+    L.append(_fc(10, 1, False, len(L)))
+    return L
+
+
 def googlenet(n_classes=1000, width=1.0):
     """GoogLeNet-style stack (Table 3, REC_2): stem, nine inception modules (four branches joined by a concat),
     global average pooling, one fully-connected layer and a softmax: 57 convolutions.  Poolings use zero padding

@@ -139,6 +139,16 @@ def test_alexnet_full_width_fp32(oracle):
     _run_both(oracle, layers, video, 10, 8, False, bias_scale=0.02)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_dave_orig_stack(oracle, bf16):
+    """The steering network: a 66x200 frame (not square), 5x5 stride-2 convolutions without padding, channel counts
+    (24, 36, 48) that are not whole 16-byte vectors in bf16, four fully-connected layers."""
+    layers = synth.dave_orig()
+    video = np.stack([synth.panning_video(800 + s, n_frames=3, H=66, W=200, fg=((16, 24),)) for s in range(2)])
+    runner, reuse = _run_both(oracle, layers, video, 10, 8, bf16, bias_scale=0.02)
+    assert runner.shapes[5] == (1, 18, 64) and runner.shapes[-1] == (1, 1, 1)
+
+
 def test_googlenet_full_width_bf16(oracle):
     """The GoogLeNet-style stack at its real widths, 224x224, bf16: a full and a cached frame."""
     layers = synth.resolve_global_pooling(synth.googlenet(), 224, 224, 3)
