@@ -73,7 +73,8 @@ typedef struct {
     int32_t type;          /* DC_CONV ... DC_AVGPOOL */
     int32_t k, s, p;       /* kernel size, stride, zero padding (conv, pool); k: window size of an LRN */
     int32_t cin, cout;
-    int32_t relu;          /* fused ReLU after a conv, an add or a fully-connected layer */
+    int32_t relu;          /* fused ReLU after a conv, an add or a fully-connected layer; DC_CONV also takes 2:
+                              leaky ReLU, v < 0 -> 0.1 v (Darknet-style stacks) */
     int32_t in0, in1;
     int32_t in2, in3;      /* DC_CONCAT: third and fourth producer, -1: none (other types ignore them) */
     int32_t within;        /* DC_LRN: 0 = window over channels, 1 = window over pixels */

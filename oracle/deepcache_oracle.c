@@ -650,7 +650,7 @@ void oc_frame_to_tensor(const uint8_t* frame, size_t n, float* out)
 
 /*
  * out[y][x][:] = cache_prev[y+dy][x+dx][:]                 where mask[y][x] = 1   (step 1)
- *              = bias + sum_{ky,kx,ci} in * w  (+ReLU)     elsewhere              (step 3)
+ *              = bias + sum_{ky,kx,ci} in * w  (+ReLU; relu == 2: leaky, v < 0 -> 0.1 v)  elsewhere   (step 3)
  * mask == NULL (or cache_prev == NULL) means: compute every pixel.
  * in [Hin][Win][cin], out [Hout][Wout][cout], w [cout][k][k][cin].
  */
@@ -682,7 +682,8 @@ void oc_conv_cached(const float* in, int Hin, int Win, int cin,
                         for (int ci = 0; ci < cin; ++ci) acc += (double)ip[ci] * (double)wp[ci];
                     }
                 }
-                if (relu && acc < 0.0) acc = 0.0;
+                if (relu == 2) { if (acc < 0.0) acc *= 0.1; }      /* leaky ReLU, slope 0.1 (Darknet-style stacks) */
+                else if (relu && acc < 0.0) acc = 0.0;
                 o[co] = store_val(acc, bf16);
             }
         }

@@ -91,6 +91,7 @@ int input_channels(const dc_layer* L, int n_layers, int c_frame) {
 int check_conv_layer(const dc_layer* l) {
     if (l->type != DC_CONV) return DC_ERR_INVALID_ARG;
     if (l->k < 1 || l->s < 1 || l->p < 0 || l->p >= l->k || l->cin < 1 || l->cout < 1) return DC_ERR_INVALID_ARG;
+    if (l->relu < 0 || l->relu > 2) return DC_ERR_INVALID_ARG;
     return DC_OK;
 }
 

@@ -113,6 +113,14 @@ __device__ __forceinline__ V keep_scalar(V v) {
     return v;
 }
 
+// Activation fused into a convolution's epilogue: 1 = ReLU, 2 = leaky ReLU with slope 0.1 (Darknet-style stacks).
+__device__ __forceinline__ float activate(float v, int mode) {
+    return mode == 2 ? (v > 0.f ? v : 0.1f * v) : fmaxf(v, 0.f);
+}
+__device__ __forceinline__ void activate4(floatx4& v, int mode) {
+    v[0] = activate(v[0], mode); v[1] = activate(v[1], mode); v[2] = activate(v[2], mode); v[3] = activate(v[3], mode);
+}
+
 __device__ __forceinline__ int fast_div(int n, uint32_t magic) { return (int)__umulhi((uint32_t)n, magic); }
 
 // ---- pieces shared by both kernels ------------------------------------------------
@@ -231,14 +239,14 @@ __device__ __forceinline__ void epilogue(const ConvParams& P, const Header<G>& H
             floatx4 v = acc[u][j];
             if (vec_ok) {   // co + 3 < Cout because both are multiples of 4
                 if (P.bias) v += *reinterpret_cast<const floatx4*>(P.bias + co);
-                if (P.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+                if (P.relu) activate4(v, P.relu);
                 F::store4(px + co, v);
             } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     if (co + r >= P.Cout) continue;
                     float s = v[r] + (P.bias ? P.bias[co + r] : 0.f);
-                    if (P.relu) s = fmaxf(s, 0.f);
+                    if (P.relu) s = activate(s, P.relu);
                     F::store1(px + co + r, s);
                 }
             }

@@ -332,7 +332,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
 #pragma unroll
             for (int j = 0; j < NBW; ++j) {
                 floatx4 v = acc[u][j] + bias[j];
-                if (relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+                if (relu) activate4(v, P.relu);
                 F::store4(px + j * 16, v);
             }
         }
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     floatx4 v = *reinterpret_cast<const floatx4*>(p);
     for (int s = 1; s < P.ks; ++s) v += *reinterpret_cast<const floatx4*>(p + s * split_stride);
     if (P.bias) v += *reinterpret_cast<const floatx4*>(P.bias + co);
-    if (P.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+    if (P.relu) activate4(v, P.relu);
     T* out = reinterpret_cast<T*>(P.out) + (((size_t)stream * P.Hout + y) * P.Wout + x) * P.Cout + co;
     F::store4(out, v);
 }
@@ -791,10 +791,7 @@ __global__ __launch_bounds__(WM * 128) void conv_pw_kernel(ConvParams P) {
         for (int j = 0; j < NBW; j += 2) {          // eight channels at a time (Cout is a multiple of 8)
             if (chan0 + j * 4 >= P.Cout) break;
             floatx4 v0 = acc[u][j] + b[j], v1 = acc[u][j + 1] + b[j + 1];
-            if (relu) {
-                v0[0] = fmaxf(v0[0], 0.f); v0[1] = fmaxf(v0[1], 0.f); v0[2] = fmaxf(v0[2], 0.f); v0[3] = fmaxf(v0[3], 0.f);
-                v1[0] = fmaxf(v1[0], 0.f); v1[1] = fmaxf(v1[1], 0.f); v1[2] = fmaxf(v1[2], 0.f); v1[3] = fmaxf(v1[3], 0.f);
-            }
+            if (relu) { activate4(v0, P.relu); activate4(v1, P.relu); }
             if constexpr (sizeof(T) == 2) {         // eight bf16 channels in one 16-byte store
                 uintx4 w4;
                 w4[0] = (uint32_t)F::bits(v0[0]) | ((uint32_t)F::bits(v0[1]) << 16);
@@ -911,7 +908,7 @@ __device__ __forceinline__ void conv_first_body(const ConvParams& P) {
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
                 v[j] = acc[j];
-                if (relu) { v[j][0] = fmaxf(v[j][0], 0.f); v[j][1] = fmaxf(v[j][1], 0.f); v[j][2] = fmaxf(v[j][2], 0.f); v[j][3] = fmaxf(v[j][3], 0.f); }
+                if (relu) activate4(v[j], P.relu);
             }
             if constexpr (kWide) {                          // eight bf16 channels per 16-byte store
 #pragma unroll
@@ -1288,7 +1285,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     }
     init_tuning();
     // 64 input channels in bf16 and enough units to keep persistent workgroups busy: the weights go to registers
-    if (c.dtype == DC_BF16 && c.Cin == 64 && (g_tune[0] == 3 || (g_tune[0] < 0 && g_tune[1] < 0 && n_units >= 4096))) {
+    if (c.dtype == DC_BF16 && c.Cin == 64 && c.relu != 2 && (g_tune[0] == 3 || (g_tune[0] < 0 && g_tune[1] < 0 && n_units >= 4096))) {
         ConvParams P{};
         P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
         P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;

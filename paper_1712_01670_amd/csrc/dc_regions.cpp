@@ -101,6 +101,7 @@ int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C, std::v
             case DC_MAXPOOL:
             case DC_AVGPOOL:
                 if (l.k < 1 || l.s < 1 || l.p < 0 || l.p >= l.k) return DC_ERR_INVALID_ARG;
+                if (l.type == DC_CONV && (l.relu < 0 || l.relu > 2)) return DC_ERR_INVALID_ARG;
                 if (l.cin != c[a] || l.cout < 1) return DC_ERR_BAD_SHAPE;
                 if (l.type != DC_CONV && l.cout != l.cin) return DC_ERR_BAD_SHAPE;
                 if (h[a] + 2 * l.p < l.k || w[a] + 2 * l.p < l.k) return DC_ERR_BAD_SHAPE;

@@ -90,8 +90,9 @@ def vgg16():
     return _chain(spec, 3)
 
 
-def darknet19():
-    """Darknet-19-style stack: 3x3 convs with 1x1 bottlenecks, 5 maxpools, 1x1 head."""
+def darknet19(leaky=False):
+    """Darknet-19-style stack: 3x3 convs with 1x1 bottlenecks, 5 maxpools, 1x1 head.  `leaky`: the activation of
+    the published network (leaky ReLU, slope 0.1) instead of ReLU."""
     spec = [("c", 32, 3, 1, 1), ("p", 2, 2, 0), ("c", 64, 3, 1, 1), ("p", 2, 2, 0)]
     for c, n in [(128, 3), (256, 3)]:
         for i in range(n):
@@ -103,7 +104,12 @@ def darknet19():
     for i in range(5):
         spec.append(("c", 1024, 3, 1, 1) if i % 2 == 0 else ("c", 512, 1, 1, 0))
     spec.append(("c", 1024, 1, 1, 0))
-    return _chain(spec, 3)
+    layers = _chain(spec, 3)
+    if leaky:
+        for L in layers:
+            if L["type"] == CONV:
+                L["relu"] = 2
+    return layers
 
 
 def resnet50_trunk():

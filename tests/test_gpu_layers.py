@@ -448,3 +448,26 @@ def test_pointwise_kernel(oracle, case, pw_tile, bf16, cached):
         else:
             want = oracle.conv_cached(x[i], w, b, 1, s, 0, True, bf16=bf16)
         assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("case", [(20, 24, 4, 32, 3, 1, 1), (20, 24, 64, 64, 3, 1, 1), (20, 24, 64, 128, 1, 1, 0), (21, 25, 32, 48, 5, 2, 2),
+                                  (21, 25, 6, 10, 3, 1, 1), (12, 12, 512, 64, 3, 1, 1)])
+def test_leaky_relu_in_every_conv_kernel(oracle, case, bf16):
+    """relu = 2 (leaky, slope 0.1) in the epilogue of the first-layer, 3x3, 1x1, general, element-load and split-K
+    kernels."""
+    H, W, cin, cout, k, s, p = case
+    if bf16 and cin == 4:
+        cin = 8
+    print(f"[leaky] case={case} bf16={bf16}", flush=True)
+    rng = np.random.default_rng(sum(case) + 1)
+    x = rng.standard_normal((2, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, k, k, cin)) * np.sqrt(2.0 / (cin * k * k))).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    if bf16:
+        x, w = oracle.round_bf16(x), oracle.round_bf16(w)
+    got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, k, s, p, 2), _to_dev(x, bf16), _to_dev(w, bf16), torch.from_numpy(b).to(DEV)))
+    for i in range(2):
+        want = oracle.conv_cached(x[i], w, b, k, s, p, 2, bf16=bf16)
+        assert (want < 0).any()
+        assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)

@@ -238,6 +238,15 @@ def test_resnet_stage_small(oracle):
     _run_both(oracle, layers, v, 16, 16, False, bias_scale=0.0, residual_scale=0.5)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_darknet_with_leaky_relu_small(oracle, bf16):
+    """The published Darknet activation (leaky ReLU, slope 0.1) through every conv kernel family: first layer, 3x3,
+    1x1, and the register-weight kernel's fallback."""
+    layers = synth.darknet19(leaky=True)[:12]
+    video = np.stack([synth.panning_video(900 + s, n_frames=3, H=96, W=96, fg=((24, 24),)) for s in range(2)])
+    _run_both(oracle, layers, video, 16, 8, bf16)
+
+
 def test_darknet_head_small(oracle):
     layers = synth.darknet19()[:12]
     v = synth.reuse_sweep_video(4001, 0.75, n_frames=3, H=128, W=128, cut_at=2)[None]

@@ -242,3 +242,17 @@ def test_invariant_static_scene_is_exact(oracle, extend):
 
 
 test_invariant_static_scene_is_exact.reused = {}
+
+
+def test_leaky_relu_of_a_convolution(oracle):
+    """relu == 2: v < 0 -> 0.1 v, applied to the same sums as the other two settings."""
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal((9, 11, 5)).astype(np.float32)
+    w = rng.standard_normal((6, 3, 3, 5)).astype(np.float32)
+    b = rng.standard_normal(6).astype(np.float32)
+    plain = oracle.conv_cached(x, w, b, 3, 1, 1, 0).astype(np.float64)
+    assert (plain < 0).any() and (plain > 0).any()
+    assert np.allclose(oracle.conv_cached(x, w, b, 3, 1, 1, 2), np.where(plain > 0, plain, 0.1 * plain), rtol=1e-6, atol=1e-7)
+    assert np.allclose(oracle.conv_cached(x, w, b, 3, 1, 1, 1), np.maximum(plain, 0), rtol=1e-6, atol=1e-7)
+    one = np.full((1, 1, 1), -2.0, np.float32)                      # hand value: -2 * 3 = -6 -> -0.6
+    assert abs(float(oracle.conv_cached(one, np.full((1, 1, 1, 1), 3.0, np.float32), None, 1, 1, 0, 2)[0, 0, 0]) + 0.6) < 1e-7
