@@ -329,9 +329,10 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
     for (int i = 0; i < NT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j) acc[i][j] = intx4{0, 0, 0, 0};
-    const int rpw = (rows + kMfmaWaves - 1) / kMfmaWaves;
-    const int wr_end = (wave + 1) * rpw < rows ? (wave + 1) * rpw : rows;
-    for (int wr = wave * rpw; wr < wr_end; ++wr) {
+    // Window row wr meets block rows only for the candidates dy with 0 <= wr - dy < B: a tile of 16 dy whose
+    // block rows all fall outside is a product with zeros and is skipped (about half of the tiles).  The rows are
+    // dealt round-robin so that every wavefront gets its share of the rows with one and with two live tiles.
+    for (int wr = wave; wr < rows; wr += kMfmaWaves) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             intx4 af[NT], bf[NT];
@@ -348,16 +349,16 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
             }
 #pragma unroll
             for (int j = 0; j < NT; ++j) {      // lane: candidate dy = 16 j + n, block row wr - dy
+                const bool live = wr >= 16 * j && wr - 16 * j < B + 15;   // wavefront-uniform: some dy of the tile has a block row
+                if (!live) continue;
                 const int r = wr - (16 * j + n);
                 const bool ok = r >= 0 && r < B;
                 const intx4 v = *reinterpret_cast<const intx4*>(blk + (size_t)(ok ? r : 0) * BS + 64 * ks + 16 * kq);
                 bf[j] = ok ? v : intx4{0, 0, 0, 0};
-            }
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
+                for (int i = 0; i < NT; ++i)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+            }
         }
     }
 #pragma unroll
