@@ -191,9 +191,8 @@ __global__ __launch_bounds__(kSearchThreads) void match_search_kernel(
 // (dx, dy count from -R), so that the sum over the window rows is the cross term of candidate
 // (dx, dy).  v_mfma_i32_16x16x64_i8 covers 16 dx x 16 dy x 64 bytes; NT x NT tiles cover the
 // (2R+1)^2 candidates, KS K-steps the block row.  sum b'^2 per candidate is a box sum of per-pixel
-// sums.  The wavefronts split the window rows and add their tiles into one copy in LDS (integer
-// atomics: the order does not matter).  The arg-min key is the same as in the scalar kernel, so both give
-// identical results.
+// sums.  The wavefronts split the window rows and add their partial tiles pairwise through LDS.  The arg-min
+// key is the same as in the scalar kernel, so both give identical results.
 typedef int intx4 __attribute__((ext_vector_type(4)));
 constexpr int kMfmaWaves = 4;           // wavefronts per block: they split the window rows and the summing loops
 constexpr int kMfmaThreads = 64 * kMfmaWaves;
@@ -227,7 +226,6 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
     int* misc = tiles + NT * NT * 256;
     unsigned long long* red = reinterpret_cast<unsigned long long*>(misc + kMfmaWaves);   // partial sums a'^2, then the arg-min keys
     int* v2 = misc + 3 * kMfmaWaves;
-    for (int i = tid; i < NT * NT * 256; i += kMfmaThreads) tiles[i] = 0;
 
     const int gx0 = (x0 - R) * C;
     const int a0 = gx0 & ~3;
@@ -361,13 +359,35 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
             }
         }
     }
+    // The four partial copies are added pairwise through LDS with plain 16-byte accesses (integer atomics, 36 per
+    // lane, took more than a third of the kernel): wavefronts 2 and 3 store theirs, 0 and 1 add them, 1 stores its
+    // sum, 0 adds it and stores the result where the evaluation below reads it.  The second buffer is the per-pixel
+    // sums, which are no longer needed (NT * NT * 1 KiB <= rows * cols * 4 bytes is checked by the launcher).
+    {
+        intx4* bufa = reinterpret_cast<intx4*>(tiles);
+        intx4* bufb = reinterpret_cast<intx4*>(p2);
+        auto store_tiles = [&](intx4* dst) {
 #pragma unroll
-    for (int i = 0; i < NT; ++i)
+            for (int i = 0; i < NT; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+                for (int j = 0; j < NT; ++j) dst[(i * NT + j) * 64 + lane] = acc[i][j];
+        };
+        auto add_tiles = [&](const intx4* src) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) atomicAdd(&tiles[((i * NT + j) * 64 + lane) * 4 + e], acc[i][j][e]);
-    __syncthreads();
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) acc[i][j] += src[(i * NT + j) * 64 + lane];
+        };
+        __syncthreads();                       // every wavefront is done with the per-pixel sums
+        if (wave == 2) store_tiles(bufa);
+        if (wave == 3) store_tiles(bufb);
+        __syncthreads();
+        if (wave == 0) add_tiles(bufa);
+        if (wave == 1) { add_tiles(bufb); store_tiles(bufb); }
+        __syncthreads();
+        if (wave == 0) { add_tiles(bufb); store_tiles(bufa); }
+        __syncthreads();
+    }
 
     // ---- SSD and arg-min: tile t is evaluated by wavefront t % kMfmaWaves; lane (n, kq) holds rows
     // dx = 16 i + 4 kq + e of column dy = 16 j + n ----
@@ -673,7 +693,7 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
         const int wsm = (int)align_up((size_t)(need > real ? need : real), 16);
         const size_t ldsm = (size_t)rows * wsm + (size_t)B * 64 * ksteps + (size_t)(rows * rows + rows * nd) * 4 +
                             (size_t)nt * nt * 1024 + 16 + (size_t)(3 * kMfmaWaves + nd * nd) * 4;
-        if (ldsm <= 64 * 1024) {
+        if (ldsm <= 64 * 1024 && (size_t)nt * nt * 1024 <= (size_t)rows * rows * 4) {   // the tiles fit the per-pixel sums' buffer
 #define DC_MFMA_LAUNCH(AL, NTT, KSS, BT, CT)                                                                          \
     hipLaunchKernelGGL((match_mfma_kernel<AL, NTT, KSS, BT, CT>), grid, dim3(kMfmaThreads), ldsm, st, cur, prev, H, W, C, \
                        B, R, gw, gh, wsm, k_skip, mv, best_ssd)
