@@ -217,13 +217,14 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
     const uint8_t* pf = prev + (size_t)stream * frame_bytes;
     const uint8_t* cf = cur + (size_t)stream * frame_bytes;
     constexpr int BS = 64 * KS;                       // bytes of a staged block row
-    // LDS: [win rows*ws][blk B*BS][p2 rows*cols ints][h2 rows*nd ints][tiles NT*NT*256 ints][misc][v2 nd*nd ints]
+    // LDS: [win rows*ws][blk B*BS][p2 rows*cols ints][h2 rows*nd ints][misc][v2 nd*nd ints]
     uint8_t* win = lds;
     uint8_t* blk = win + (size_t)rows * ws;
     int* p2 = reinterpret_cast<int*>(blk + (size_t)B * BS);
     int* h2 = p2 + rows * cols;
-    int* tiles = h2 + rows * nd + (4 - (rows * cols + rows * nd) % 4) % 4;   // 16-byte aligned
-    int* misc = tiles + NT * NT * 256;
+    int* misc = h2 + rows * nd + (4 - (rows * cols + rows * nd) % 4) % 4;   // 16-byte aligned
+    // The summed tiles land at the start of LDS, over the window, the block and the sums, which are dead by then.
+    int* tiles = reinterpret_cast<int*>(lds);
     unsigned long long* red = reinterpret_cast<unsigned long long*>(misc + kMfmaWaves);   // partial sums a'^2, then the arg-min keys
     int* v2 = misc + 3 * kMfmaWaves;
 
@@ -360,12 +361,12 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
         }
     }
     // The four partial copies are added pairwise through LDS with plain 16-byte accesses (integer atomics, 36 per
-    // lane, took more than a third of the kernel): wavefronts 2 and 3 store theirs, 0 and 1 add them, 1 stores its
-    // sum, 0 adds it and stores the result where the evaluation below reads it.  The second buffer is the per-pixel
-    // sums, which are no longer needed (NT * NT * 1 KiB <= rows * cols * 4 bytes is checked by the launcher).
+    // lane, cost more): wavefronts 2 and 3 store theirs, 0 and 1 add them, 1 stores its sum, 0 adds it and stores
+    // the result where the evaluation below reads it.  The two buffers lie over the window, the block and the box
+    // sums' inputs, all dead after the barrier (the launcher checks that 2 NT^2 KiB fit there).
     {
         intx4* bufa = reinterpret_cast<intx4*>(tiles);
-        intx4* bufb = reinterpret_cast<intx4*>(p2);
+        intx4* bufb = bufa + NT * NT * 64;
         auto store_tiles = [&](intx4* dst) {
 #pragma unroll
             for (int i = 0; i < NT; ++i)
@@ -378,7 +379,7 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
 #pragma unroll
                 for (int j = 0; j < NT; ++j) acc[i][j] += src[(i * NT + j) * 64 + lane];
         };
-        __syncthreads();                       // every wavefront is done with the per-pixel sums
+        __syncthreads();                       // every wavefront is done with the window, the block and the sums
         if (wave == 2) store_tiles(bufa);
         if (wave == 3) store_tiles(bufb);
         __syncthreads();
@@ -692,8 +693,9 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
         const int need = 3 + C * (16 * nt - 1) + 64 * ksteps + 4, real = 3 + rows * C + 4;
         const int wsm = (int)align_up((size_t)(need > real ? need : real), 16);
         const size_t ldsm = (size_t)rows * wsm + (size_t)B * 64 * ksteps + (size_t)(rows * rows + rows * nd) * 4 +
-                            (size_t)nt * nt * 1024 + 16 + (size_t)(3 * kMfmaWaves + nd * nd) * 4;
-        if (ldsm <= 64 * 1024 && (size_t)nt * nt * 1024 <= (size_t)rows * rows * 4) {   // the tiles fit the per-pixel sums' buffer
+                            16 + (size_t)(3 * kMfmaWaves + nd * nd) * 4;
+        const size_t dead = (size_t)rows * wsm + (size_t)B * 64 * ksteps + (size_t)(rows * rows + rows * nd) * 4;
+        if (ldsm <= 64 * 1024 && (size_t)2 * nt * nt * 1024 <= dead) {   // the two tile buffers of the final sum fit over the dead part
 #define DC_MFMA_LAUNCH(AL, NTT, KSS, BT, CT)                                                                          \
     hipLaunchKernelGGL((match_mfma_kernel<AL, NTT, KSS, BT, CT>), grid, dim3(kMfmaThreads), ldsm, st, cur, prev, H, W, C, \
                        B, R, gw, gh, wsm, k_skip, mv, best_ssd)
