@@ -256,37 +256,50 @@ __device__ __forceinline__ void fc_load(const T* p, float (&f)[VE]) {
         }
     }
 }
-template <typename T, int NS, int VE>
+template <typename T, int NS, int VE, int NO>
 __global__ __launch_bounds__(kThreads) void fc_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                       const float* __restrict__ bias, T* __restrict__ out, int n_streams,
                                                       size_t K, int cout, int relu) {
+    // NO output neurons per wavefront: with many streams the inputs (read again for every neuron) are the larger
+    // traffic, and one input vector then serves NO weight rows.
     const int lane = threadIdx.x & 63;
-    const int o = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    const int o0 = (blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * NO;
     const int s0 = blockIdx.y * NS;
-    if (o >= cout) return;                        // whole wavefronts leave
-    float acc[NS];
+    if (o0 >= cout) return;                       // whole wavefronts leave
+    float acc[NO][NS];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) acc[s] = 0.f;
-    const T* wrow = w + (size_t)o * K;
+    for (int j = 0; j < NO; ++j)
+#pragma unroll
+        for (int s = 0; s < NS; ++s) acc[j][s] = 0.f;
     for (size_t k = (size_t)lane * VE; k < K; k += 64 * VE) {
-        float wf[VE];
-        fc_load<T, VE>(wrow + k, wf);
+        float wf[NO][VE];
+#pragma unroll
+        for (int j = 0; j < NO; ++j) {
+            const int o = o0 + j < cout ? o0 + j : cout - 1;      // a row past the end repeats the last one (not stored)
+            fc_load<T, VE>(w + (size_t)o * K + k, wf[j]);
+        }
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
             if (s0 + s < n_streams) {             // uniform over the wavefront
                 float xf[VE];
                 fc_load<T, VE>(x + (size_t)(s0 + s) * K + k, xf);
 #pragma unroll
-                for (int e = 0; e < VE; ++e) acc[s] = fmaf(wf[e], xf[e], acc[s]);
+                for (int j = 0; j < NO; ++j)
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) acc[j][s] = fmaf(wf[j][e], xf[e], acc[j][s]);
             }
         }
     }
-    const float b = bias ? bias[o] : 0.f;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        float v = wave_sum_f32(acc[s]) + b;
-        if (relu) v = v > 0.f ? v : 0.f;
-        if (lane == 0 && s0 + s < n_streams) out[(size_t)(s0 + s) * cout + o] = from_float<T>(v);
+    for (int j = 0; j < NO; ++j) {
+        if (o0 + j >= cout) break;                // uniform
+        const float b = bias ? bias[o0 + j] : 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            float v = wave_sum_f32(acc[j][s]) + b;
+            if (relu) v = v > 0.f ? v : 0.f;
+            if (lane == 0 && s0 + s < n_streams) out[(size_t)(s0 + s) * cout + o0 + j] = from_float<T>(v);
+        }
     }
 }
 
@@ -650,18 +663,25 @@ namespace {
 template <typename T, int VE>
 hipError_t fc_launch(const void* x, const void* w, const float* bias, void* out, int n_streams, size_t K, int cout,
                      int relu, hipStream_t st) {
-    const unsigned gx = (unsigned)((cout + kThreads / 64 - 1) / (kThreads / 64));
     const T* xp = (const T*)x;
     const T* wp = (const T*)w;
     T* op = (T*)out;
+    constexpr int WPB = kThreads / 64;
     // streams per pass over the weights: the partial sums of a pass live in registers
-    if (n_streams == 1)
-        hipLaunchKernelGGL((fc_kernel<T, 1, VE>), dim3(gx, 1), dim3(kThreads), 0, st, xp, wp, bias, op, n_streams, K, cout, relu);
-    else if (n_streams <= 4)
-        hipLaunchKernelGGL((fc_kernel<T, 4, VE>), dim3(gx, 1), dim3(kThreads), 0, st, xp, wp, bias, op, n_streams, K, cout, relu);
-    else
-        hipLaunchKernelGGL((fc_kernel<T, 16, VE>), dim3(gx, (unsigned)((n_streams + 15) / 16)), dim3(kThreads), 0, st, xp, wp,
+    if (n_streams == 1) {
+        const unsigned gx = (unsigned)((cout + WPB - 1) / WPB);
+        hipLaunchKernelGGL((fc_kernel<T, 1, VE, 1>), dim3(gx, 1), dim3(kThreads), 0, st, xp, wp, bias, op, n_streams, K, cout, relu);
+    } else if (n_streams <= 4) {
+        const unsigned gx = (unsigned)((cout + WPB - 1) / WPB);
+        hipLaunchKernelGGL((fc_kernel<T, 4, VE, 1>), dim3(gx, 1), dim3(kThreads), 0, st, xp, wp, bias, op, n_streams, K, cout, relu);
+    } else if (n_streams <= 16) {     // one pass: bound by streaming the weights, as many wavefronts as possible
+        const unsigned gx = (unsigned)((cout + WPB - 1) / WPB);
+        hipLaunchKernelGGL((fc_kernel<T, 16, VE, 1>), dim3(gx, 1), dim3(kThreads), 0, st, xp, wp, bias, op, n_streams, K, cout, relu);
+    } else {                          // several passes: four neurons per wavefront share every input vector
+        const unsigned gx = (unsigned)((cout + 4 * WPB - 1) / (4 * WPB));
+        hipLaunchKernelGGL((fc_kernel<T, 16, VE, 4>), dim3(gx, (unsigned)((n_streams + 15) / 16)), dim3(kThreads), 0, st, xp, wp,
                            bias, op, n_streams, K, cout, relu);
+    }
     return hipGetLastError();
 }
 }  // namespace

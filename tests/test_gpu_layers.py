@@ -377,7 +377,8 @@ def test_lrn_avgpool_concat_softmax_layers(oracle, bf16):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("n,shape,cout", [(1, (6, 6, 32), 100), (3, (5, 5, 7), 33), (20, (1, 1, 256), 64), (5, (2, 3, 24), 1)])
+@pytest.mark.parametrize("n,shape,cout", [(1, (6, 6, 32), 100), (3, (5, 5, 7), 33), (20, (1, 1, 256), 64), (5, (2, 3, 24), 1),
+                                          (16, (2, 2, 64), 30), (37, (3, 3, 16), 50), (18, (1, 1, 40), 3)])
 def test_fully_connected_layer(oracle, n, shape, cout, bf16):
     print(f"[fc] n={n} shape={shape} cout={cout} bf16={bf16}", flush=True)
     rng = np.random.default_rng(n * 100 + cout)
