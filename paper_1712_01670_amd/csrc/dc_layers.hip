@@ -73,11 +73,12 @@ __global__ __launch_bounds__(kThreads) void frame_to_tensor_kernel(const uint8_t
     }
 }
 
-// One thread per (output pixel, channel); consecutive threads walk the channels.
-template <typename T>
-__global__ __launch_bounds__(kThreads) void maxpool_kernel(const T* __restrict__ in, T* __restrict__ out,
-                                                           int n_streams, int Hin, int Win, int C, int Hout,
-                                                           int Wout, int k, int s, int p) {
+// Max or average pooling (mean over the in-bounds part of the window) for channel counts that are not whole 16-byte
+// vectors: one thread per (output pixel, channel); consecutive threads walk the channels.
+template <typename T, bool AVG>
+__global__ __launch_bounds__(kThreads) void pool_kernel(const T* __restrict__ in, T* __restrict__ out,
+                                                        int n_streams, int Hin, int Win, int C, int Hout,
+                                                        int Wout, int k, int s, int p) {
     const size_t total = (size_t)n_streams * Hout * Wout * C;
     size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * kThreads;
@@ -88,7 +89,8 @@ __global__ __launch_bounds__(kThreads) void maxpool_kernel(const T* __restrict__
         size_t t = pix / Wout;
         int y = (int)(t % Hout);
         int st = (int)(t / Hout);
-        float m = -INFINITY;
+        float acc = AVG ? 0.f : -INFINITY;
+        int cnt = 0;
         for (int ky = 0; ky < k; ++ky) {
             int iy = y * s - p + ky;
             if (iy < 0 || iy >= Hin) continue;
@@ -96,10 +98,11 @@ __global__ __launch_bounds__(kThreads) void maxpool_kernel(const T* __restrict__
                 int ix = x * s - p + kx;
                 if (ix < 0 || ix >= Win) continue;
                 float v = to_float(in[(((size_t)st * Hin + iy) * Win + ix) * C + c]);
-                m = v > m ? v : m;
+                acc = AVG ? acc + v : (v > acc ? v : acc);
+                ++cnt;
             }
         }
-        out[i] = from_float<T>(m);
+        out[i] = from_float<T>(AVG ? (cnt ? acc / (float)cnt : 0.f) : acc);
     }
 }
 
@@ -112,37 +115,6 @@ __global__ __launch_bounds__(kThreads) void add_kernel(const T* __restrict__ a, 
         float v = to_float(a[i]) + (b ? to_float(b[i]) : 0.f);  // b == nullptr: plain ReLU layer
         if (relu) v = v > 0.f ? v : 0.f;
         out[i] = from_float<T>(v);
-    }
-}
-
-// Mean over the in-bounds part of each window; one thread per (output pixel, channel).
-template <typename T>
-__global__ __launch_bounds__(kThreads) void avgpool_kernel(const T* __restrict__ in, T* __restrict__ out,
-                                                           int n_streams, int Hin, int Win, int C, int Hout,
-                                                           int Wout, int k, int s, int p) {
-    const size_t total = (size_t)n_streams * Hout * Wout * C;
-    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    for (; i < total; i += stride) {
-        int c = (int)(i % C);
-        size_t pix = i / C;
-        int x = (int)(pix % Wout);
-        size_t t = pix / Wout;
-        int y = (int)(t % Hout);
-        int st = (int)(t / Hout);
-        float sum = 0.f;
-        int cnt = 0;
-        for (int ky = 0; ky < k; ++ky) {
-            int iy = y * s - p + ky;
-            if (iy < 0 || iy >= Hin) continue;
-            for (int kx = 0; kx < k; ++kx) {
-                int ix = x * s - p + kx;
-                if (ix < 0 || ix >= Win) continue;
-                sum += to_float(in[(((size_t)st * Hin + iy) * Win + ix) * C + c]);
-                ++cnt;
-            }
-        }
-        out[i] = from_float<T>(cnt ? sum / (float)cnt : 0.f);
     }
 }
 
@@ -541,8 +513,10 @@ hipError_t launch_frame_to_tensor(const uint8_t* f, void* out, size_t n_pixels, 
     return hipGetLastError();
 }
 
-hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k, int s,
-                          int p, int dtype, hipStream_t st) {
+namespace {
+template <bool AVG>
+hipError_t launch_pool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k, int s, int p, int dtype,
+                       hipStream_t st) {
     const int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
     const size_t n = (size_t)n_streams * Hout * Wout * C;
     if (n == 0) return hipSuccess;
@@ -550,47 +524,31 @@ hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int
         const int cv = (int)(C * dtype_size(dtype) / 16);
         const size_t nv = (size_t)n_streams * Hout * Wout * cv;
         if (dtype == DC_BF16)
-            hipLaunchKernelGGL((pool_vec_kernel<__hip_bfloat16, false>), dim3(grid_for(nv)), dim3(kThreads), 0, st,
+            hipLaunchKernelGGL((pool_vec_kernel<__hip_bfloat16, AVG>), dim3(grid_for(nv)), dim3(kThreads), 0, st,
                                (const uint4*)in, (uint4*)out, n_streams, Hin, Win, cv, Hout, Wout, k, s, p);
         else
-            hipLaunchKernelGGL((pool_vec_kernel<float, false>), dim3(grid_for(nv)), dim3(kThreads), 0, st, (const uint4*)in,
+            hipLaunchKernelGGL((pool_vec_kernel<float, AVG>), dim3(grid_for(nv)), dim3(kThreads), 0, st, (const uint4*)in,
                                (uint4*)out, n_streams, Hin, Win, cv, Hout, Wout, k, s, p);
         return hipGetLastError();
     }
     if (dtype == DC_BF16)
-        hipLaunchKernelGGL(maxpool_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st,
-                           (const __hip_bfloat16*)in, (__hip_bfloat16*)out, n_streams, Hin, Win, C, Hout, Wout,
-                           k, s, p);
+        hipLaunchKernelGGL((pool_kernel<__hip_bfloat16, AVG>), dim3(grid_for(n)), dim3(kThreads), 0, st,
+                           (const __hip_bfloat16*)in, (__hip_bfloat16*)out, n_streams, Hin, Win, C, Hout, Wout, k, s, p);
     else
-        hipLaunchKernelGGL(maxpool_kernel<float>, dim3(grid_for(n)), dim3(kThreads), 0, st, (const float*)in,
+        hipLaunchKernelGGL((pool_kernel<float, AVG>), dim3(grid_for(n)), dim3(kThreads), 0, st, (const float*)in,
                            (float*)out, n_streams, Hin, Win, C, Hout, Wout, k, s, p);
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k, int s,
+                          int p, int dtype, hipStream_t st) {
+    return launch_pool<false>(in, out, n_streams, Hin, Win, C, k, s, p, dtype, st);
 }
 
 hipError_t launch_avgpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k, int s,
                           int p, int dtype, hipStream_t st) {
-    const int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
-    const size_t n = (size_t)n_streams * Hout * Wout * C;
-    if (n == 0) return hipSuccess;
-    if ((C * dtype_size(dtype)) % 16 == 0 && reinterpret_cast<uintptr_t>(in) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0) {
-        const int cv = (int)(C * dtype_size(dtype) / 16);
-        const size_t nv = (size_t)n_streams * Hout * Wout * cv;
-        if (dtype == DC_BF16)
-            hipLaunchKernelGGL((pool_vec_kernel<__hip_bfloat16, true>), dim3(grid_for(nv)), dim3(kThreads), 0, st,
-                               (const uint4*)in, (uint4*)out, n_streams, Hin, Win, cv, Hout, Wout, k, s, p);
-        else
-            hipLaunchKernelGGL((pool_vec_kernel<float, true>), dim3(grid_for(nv)), dim3(kThreads), 0, st, (const uint4*)in,
-                               (uint4*)out, n_streams, Hin, Win, cv, Hout, Wout, k, s, p);
-        return hipGetLastError();
-    }
-    if (dtype == DC_BF16)
-        hipLaunchKernelGGL(avgpool_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(kThreads), 0, st,
-                           (const __hip_bfloat16*)in, (__hip_bfloat16*)out, n_streams, Hin, Win, C, Hout, Wout,
-                           k, s, p);
-    else
-        hipLaunchKernelGGL(avgpool_kernel<float>, dim3(grid_for(n)), dim3(kThreads), 0, st, (const float*)in,
-                           (float*)out, n_streams, Hin, Win, C, Hout, Wout, k, s, p);
-    return hipGetLastError();
+    return launch_pool<true>(in, out, n_streams, Hin, Win, C, k, s, p, dtype, st);
 }
 
 hipError_t launch_lrn(const void* in, void* out, int n_streams, int H, int W, int C, int size, int within,
