@@ -217,12 +217,17 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
     const uint8_t* pf = prev + (size_t)stream * frame_bytes;
     const uint8_t* cf = cur + (size_t)stream * frame_bytes;
     constexpr int BS = 64 * KS;                       // bytes of a staged block row
-    // LDS: [win rows*ws][blk B*BS][p2 rows*cols ints][h2 rows*nd ints][misc][v2 nd*nd ints]
+    // With the block shape known at compile time the row sums of squares are taken straight from the window bytes
+    // and the per-pixel sums (p2) do not exist: one phase and 9 KB of LDS less (the kernel is bound by the latency of
+    // its chain of phases, i.e. by how many workgroups a CU holds).
+    constexpr bool kFused = BT > 0 && CT > 0 && CT <= 4 && (BT * CT) % 4 == 0;
+    // LDS: [win rows*ws][blk B*BS][p2 rows*cols ints, unless kFused][h2 rows*nd ints][misc][v2 nd*nd ints]
     uint8_t* win = lds;
     uint8_t* blk = win + (size_t)rows * ws;
     int* p2 = reinterpret_cast<int*>(blk + (size_t)B * BS);
-    int* h2 = p2 + rows * cols;
-    int* misc = h2 + rows * nd + (4 - (rows * cols + rows * nd) % 4) % 4;   // 16-byte aligned
+    const int n_p2 = kFused ? 0 : rows * cols;
+    int* h2 = p2 + n_p2;
+    int* misc = h2 + rows * nd + (4 - (n_p2 + rows * nd) % 4) % 4;   // 16-byte aligned
     // The summed tiles land at the start of LDS, over the window, the block and the sums, which are dead by then.
     int* tiles = reinterpret_cast<int*>(lds);
     unsigned long long* red = reinterpret_cast<unsigned long long*>(misc + kMfmaWaves);   // partial sums a'^2, then the arg-min keys
@@ -294,23 +299,57 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
     __syncthreads();
     if (lane == 0) misc[wave] = saa;
 
-    // ---- per-pixel sum of squares, then box sums over the block: B columns, then B rows ----
-    const int8_t* swin = reinterpret_cast<const int8_t*>(win);
-    for (int i = tid; i < rows * cols; i += kMfmaThreads) {
-        const int r = i / cols, x = i - r * cols;
-        const int8_t* px = swin + (size_t)r * ws + skew + x * C;
-        int s = 0;
+    // ---- box sums of squares over the block: B columns (h2), then B rows (v2) ----
+    if constexpr (kFused) {
+        // h2[r][d] = sum of squares of the BT * CT window bytes of row r that candidate d sees.  A thread takes four
+        // neighbouring d: it aligns the bytes it needs once, sums the first run with byte dot products and slides it
+        // three times by one pixel (CT bytes enter, CT leave).
+        constexpr int NB = BT * CT;                                 // bytes of a block row
+        constexpr int NA = (NB + 3 * CT + 3) / 4;                   // aligned dwords that hold NB + 3 CT bytes
+        constexpr uint32_t kPix = CT == 4 ? 0xffffffffu : (1u << (8 * CT)) - 1u;
+        const int ng = (nd + 3) / 4;
+        for (int i = tid; i < rows * ng; i += kMfmaThreads) {
+            const int r = i / ng, d0 = 4 * (i - r * ng);
+            const int o0 = skew + CT * d0;
+            const uint32_t* w32 = reinterpret_cast<const uint32_t*>(win + (size_t)r * ws) + (o0 >> 2);
+            const int sh = o0 & 3;
+            uint32_t raw[NA + 1], al[NA + 1];
 #pragma unroll
-        for (int c = 0; c < C; ++c) s += (int)px[c] * (int)px[c];
-        p2[i] = s;
-    }
-    __syncthreads();
-    for (int i = tid; i < rows * nd; i += kMfmaThreads) {
-        const int r = i / nd, d = i - r * nd;
-        int s = 0;
+            for (int k = 0; k <= NA; ++k) raw[k] = w32[k];
 #pragma unroll
-        for (int x = 0; x < B; ++x) s += p2[r * cols + d + x];
-        h2[i] = s;
+            for (int k = 0; k < NA; ++k) al[k] = __builtin_amdgcn_alignbyte(raw[k + 1], raw[k], sh);
+            al[NA] = 0;
+            int sq = 0;
+#pragma unroll
+            for (int k = 0; k < NB / 4; ++k) sq = __builtin_amdgcn_sdot4((int)al[k], (int)al[k], sq, false);
+            h2[r * nd + d0] = sq;
+#pragma unroll
+            for (int q = 1; q < 4; ++q) {
+                const int tin = NB + CT * (q - 1), tout = CT * (q - 1);       // first byte entering / leaving
+                const uint32_t vin = __builtin_amdgcn_alignbyte(al[tin / 4 + 1], al[tin / 4], tin % 4) & kPix;
+                const uint32_t vout = __builtin_amdgcn_alignbyte(al[tout / 4 + 1], al[tout / 4], tout % 4) & kPix;
+                sq += __builtin_amdgcn_sdot4((int)vin, (int)vin, 0, false) - __builtin_amdgcn_sdot4((int)vout, (int)vout, 0, false);
+                if (d0 + q < nd) h2[r * nd + d0 + q] = sq;
+            }
+        }
+    } else {
+        const int8_t* swin = reinterpret_cast<const int8_t*>(win);
+        for (int i = tid; i < rows * cols; i += kMfmaThreads) {
+            const int r = i / cols, x = i - r * cols;
+            const int8_t* px = swin + (size_t)r * ws + skew + x * C;
+            int s = 0;
+#pragma unroll
+            for (int c = 0; c < C; ++c) s += (int)px[c] * (int)px[c];
+            p2[i] = s;
+        }
+        __syncthreads();
+        for (int i = tid; i < rows * nd; i += kMfmaThreads) {
+            const int r = i / nd, d = i - r * nd;
+            int s = 0;
+#pragma unroll
+            for (int x = 0; x < B; ++x) s += p2[r * cols + d + x];
+            h2[i] = s;
+        }
     }
     __syncthreads();
     for (int i = tid; i < nd * nd; i += kMfmaThreads) {
@@ -360,34 +399,27 @@ __global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
             }
         }
     }
-    // The four partial copies are added pairwise through LDS with plain 16-byte accesses (integer atomics, 36 per
-    // lane, cost more): wavefronts 2 and 3 store theirs, 0 and 1 add them, 1 stores its sum, 0 adds it and stores
-    // the result where the evaluation below reads it.  The two buffers lie over the window, the block and the box
-    // sums' inputs, all dead after the barrier (the launcher checks that 2 NT^2 KiB fit there).
+    // The four partial copies are added through one LDS buffer with plain 16-byte accesses (integer atomics, 36 per
+    // lane, cost more): wavefront 3 stores its tiles, 2 adds them to its own and stores the sum, then 1, then 0, whose
+    // sum the evaluation below reads.  A lane only ever touches its own slots, so a wavefront's reads and writes need
+    // no barrier between them.  The buffer lies over the window, which is dead after the barrier (the launcher checks
+    // that NT^2 KiB fit into what is dead by then).
     {
-        intx4* bufa = reinterpret_cast<intx4*>(tiles);
-        intx4* bufb = bufa + NT * NT * 64;
-        auto store_tiles = [&](intx4* dst) {
-#pragma unroll
-            for (int i = 0; i < NT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j) dst[(i * NT + j) * 64 + lane] = acc[i][j];
-        };
-        auto add_tiles = [&](const intx4* src) {
-#pragma unroll
-            for (int i = 0; i < NT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j) acc[i][j] += src[(i * NT + j) * 64 + lane];
-        };
+        intx4* buf = reinterpret_cast<intx4*>(tiles);
         __syncthreads();                       // every wavefront is done with the window, the block and the sums
-        if (wave == 2) store_tiles(bufa);
-        if (wave == 3) store_tiles(bufb);
-        __syncthreads();
-        if (wave == 0) add_tiles(bufa);
-        if (wave == 1) { add_tiles(bufb); store_tiles(bufb); }
-        __syncthreads();
-        if (wave == 0) { add_tiles(bufb); store_tiles(bufa); }
-        __syncthreads();
+#pragma unroll
+        for (int w = kMfmaWaves - 1; w >= 0; --w) {
+            if (wave == w) {
+#pragma unroll
+                for (int i = 0; i < NT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) {
+                        if (w < kMfmaWaves - 1) acc[i][j] += buf[(i * NT + j) * 64 + lane];
+                        buf[(i * NT + j) * 64 + lane] = acc[i][j];
+                    }
+            }
+            __syncthreads();
+        }
     }
 
     // ---- SSD and arg-min: tile t is evaluated by wavefront t % kMfmaWaves; lane (n, kq) holds rows
@@ -692,10 +724,11 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
         const int nd = 2 * R + 1;
         const int need = 3 + C * (16 * nt - 1) + 64 * ksteps + 4, real = 3 + rows * C + 4;
         const int wsm = (int)align_up((size_t)(need > real ? need : real), 16);
-        const size_t ldsm = (size_t)rows * wsm + (size_t)B * 64 * ksteps + (size_t)(rows * rows + rows * nd) * 4 +
-                            16 + (size_t)(3 * kMfmaWaves + nd * nd) * 4;
-        const size_t dead = (size_t)rows * wsm + (size_t)B * 64 * ksteps + (size_t)(rows * rows + rows * nd) * 4;
-        if (ldsm <= 64 * 1024 && (size_t)2 * nt * nt * 1024 <= dead) {   // the two tile buffers of the final sum fit over the dead part
+        // the instantiations below that know the block shape take their row sums from the window bytes: no per-pixel sums
+        const bool fused = (nt == 3 && B == 16 && C == 3) || (nt == 2 && B == 8 && C == 3);
+        const size_t dead = (size_t)rows * wsm + (size_t)B * 64 * ksteps + (size_t)((fused ? 0 : rows * rows) + rows * nd) * 4;
+        const size_t ldsm = dead + 16 + (size_t)(3 * kMfmaWaves + nd * nd) * 4;
+        if (ldsm <= 64 * 1024 && (size_t)nt * nt * 1024 <= dead) {   // the tile buffer of the final sum fits over the dead part
 #define DC_MFMA_LAUNCH(AL, NTT, KSS, BT, CT)                                                                          \
     hipLaunchKernelGGL((match_mfma_kernel<AL, NTT, KSS, BT, CT>), grid, dim3(kMfmaThreads), ldsm, st, cur, prev, H, W, C, \
                        B, R, gw, gh, wsm, k_skip, mv, best_ssd)
