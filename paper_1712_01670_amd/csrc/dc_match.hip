@@ -200,7 +200,7 @@ constexpr int kMfmaThreads = 64 * kMfmaWaves;
 // BT, CT: block edge and channel count when known at compile time (the summing loops are then unrolled and
 // their LDS reads issued together), 0: taken from the arguments.
 template <bool ALIGNED, int NT, int KS, int BT, int CT>
-__global__ __launch_bounds__(kMfmaThreads) void match_mfma_kernel(
+__global__ __launch_bounds__(kMfmaThreads, 7) void match_mfma_kernel(
     const uint8_t* __restrict__ cur, const uint8_t* __restrict__ prev, int H, int W, int C_rt, int B_rt,
     int R, int gw, int gh, int ws, int k_skip, int16_t* __restrict__ mv, uint32_t* __restrict__ best_ssd) {
     const int B = BT ? BT : B_rt, C = CT ? CT : C_rt;
