@@ -414,9 +414,10 @@ size_t reduce_bytes(const Shape& S) {
     return (size_t)(S.wk - 1) * S.wm * S.wn * (S.g / S.wm) * (S.nt / S.wn / 16) * 64 * 16;
 }
 
-// Direct kernel: pick the channel chunk KC and taps per stage TG with the deepest stage
-// (TG*KC useful K) whose two LDS buffers fit.
-Choice choose_direct(int shape, const ConvLaunch& c, int ph, int pw) {
+// Direct kernel: pick the channel chunk KC and taps per stage TG.  With `f_tg` > 0 only that stage shape
+// (chunk index f_kci, f_tg taps) is considered; otherwise the deepest stage (TG*KC useful K) whose two LDS
+// buffers fit wins.
+Choice choose_direct_from(int shape, const ConvLaunch& c, int ph, int pw, bool forced, int f_kci, int f_tg) {
     const Shape& S = kShapes[shape];
     const int nwaves = S.wm * S.wn * S.wk;
     const size_t esz = dtype_size(c.dtype);
@@ -424,8 +425,6 @@ Choice choose_direct(int shape, const ConvLaunch& c, int ph, int pw) {
     const int kk = c.k * c.k;
     Choice best{shape, 0, 0, 0, 0, 0, 0, 0, 0, 0, false, 0, 0};
     long best_score = -1;
-    int f_kci = -1, f_tg = 0;
-    const bool forced = tune_override(f_kci, f_tg);
     for (int kci = 0; kci < 3; ++kci) {
         const int kc = kg << kci;
         if (kci > 0 && kc / 2 >= c.Cin) break;   // a deeper chunk would be mostly padding
@@ -460,6 +459,24 @@ Choice choose_direct(int shape, const ConvLaunch& c, int ph, int pw) {
         }
     }
     return best;
+}
+
+// A deep stage hides the load latency of a workgroup that has its CU to itself.  Once a launch puts
+// three workgroups on every two CUs or more, co-resident workgroups hide it for each other, and short
+// stages with the narrowest channel chunk (less LDS per workgroup, hence more of them per CU) measure
+// 15-25 % faster: one kernel row of taps per stage where at most two wavefronts share a stage's K, about a
+// dozen taps where four do.  `wgs` is the number of workgroups the launch would have with this shape.
+Choice choose_direct(int shape, const ConvLaunch& c, int ph, int pw, long wgs) {
+    int f_kci = -1, f_tg = 0;
+    if (tune_override(f_kci, f_tg)) return choose_direct_from(shape, c, ph, pw, true, f_kci, f_tg);
+    const int kk = c.k * c.k;
+    if (wgs >= 384 && c.k > 1) {
+        int tg = c.k;
+        if (kShapes[shape].wk > 2) { const int m = (kk + 12) / 13; tg = (kk + m - 1) / m; }
+        Choice ch = choose_direct_from(shape, c, ph, pw, true, 0, tg);
+        if (ch.ok) return ch;
+    }
+    return choose_direct_from(shape, c, ph, pw, false, -1, 0);
 }
 
 Choice choose_staged(int shape, const ConvLaunch& c, int ph, int pw) {
@@ -563,7 +580,9 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     for (int pass = 0; pass < 2 && !ch.ok; ++pass)
         for (int s2 = shape; s2 < 4; s2 = (s2 == 3 ? 0 : (s2 == 2 ? 4 : s2 + 1))) {   // 3 -> 0 -> 1 -> 2
             if (pass == 0 && !vec_ok) break;
-            ch = pass == 0 ? choose_direct(s2, c, ph, pw) : choose_staged(s2, c, ph, pw);
+            const long g2 = s2 == shape ? g_rt : kShapes[s2].g;
+            const long wgs2 = ((n_units + g2 - 1) / g2) * ((c.Cout + kShapes[s2].nt - 1) / kShapes[s2].nt);
+            ch = pass == 0 ? choose_direct(s2, c, ph, pw, wgs2) : choose_staged(s2, c, ph, pw);
             if (ch.ok && (s2 != shape || pass == 1)) g_rt = kShapes[s2].g;
             if (ch.ok) break;
         }
@@ -598,6 +617,13 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     const long groups = (n_units + g_rt - 1) / g_rt;
     const long wgs = groups * P.R;
     if (wgs > 2147483647L) return hipErrorInvalidValue;
+    {   // DC_CONV_TRACE=1: one line per launch on stderr with the configuration chosen
+        static int trace = -1;
+        if (trace < 0) { const char* e = getenv("DC_CONV_TRACE"); trace = (e && atoi(e) > 0) ? 1 : 0; }
+        if (trace)
+            fprintf(stderr, "dc_conv: %dx%d %d->%d k%d s%d units %ld: shape %d g %d kc %d tg %d lds %zu wgs %ld\n",
+                    c.Hin, c.Win, c.Cin, c.Cout, c.k, c.s, n_units, ch.shape, g_rt, ch.kc, ch.tg, ch.lds, wgs);
+    }
     hipLaunchKernelGGL(fn, dim3((unsigned)wgs), dim3(S.wm * S.wn * S.wk * 64), ch.lds, st, P);
     return hipGetLastError();
 }
