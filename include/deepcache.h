@@ -347,7 +347,10 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
  *   frames_cur      dev u8 [n_streams][H][W][C]
  *   frames_prev     dev u8, previous frames (cache keys); ignored when force_full
  *   tensors_cur     host array [n_layers+1] of dev pointers, every tensor of this frame
- *                   (written).  Conv outputs are the cache values of the next frame.
+ *                   (written).  Conv outputs are the cache values of the next frame.  The other
+ *                   tensors may be the same buffers for every frame; with a pipelined overlap
+ *                   handle a caller that alternates them between two sets as well saves the
+ *                   library one cross-stream wait and one event per such tensor and frame.
  *   tensors_prev    host array [n_layers+1] of dev pointers: the previous frame's tensors;
  *                   only conv-layer outputs are read.  Must not alias tensors_cur for them.
  *                   Written only in an in-place frame (see in_place).

@@ -424,16 +424,21 @@ class StackRunner:
         self._wpp = (C.c_void_p * nl)(*[None if w is None else w.data_ptr() for w in self.w_packed])
         self._bp = (C.c_void_p * nl)(*[None if b is None else b.data_ptr() for b in self.b])
         self.shapes = synth.tensor_shapes(layers, H, W, self.Ch_tensor)
-        # conv outputs are cache values: two copies (previous / current frame); the rest is shared
+        # conv outputs are cache values: two copies (previous / current frame).  The rest is shared, except with
+        # two frames in flight: alternating those tensors too spares the library its cross-stream waits for them.
         is_conv = [False] + [L["type"] == synth.CONV for L in layers]
         self._is_conv_out = is_conv
+        both = bool(overlap and pipeline)
         self.bufs = [[], []]
         for t, (h, w, c) in enumerate(self.shapes):
             a = torch.empty((n_streams, h, w, c), dtype=td, device=self.device)
-            b = torch.empty_like(a) if is_conv[t] else a
+            b = torch.empty_like(a) if (is_conv[t] or both) else a
             self.bufs[0].append(a)
             self.bufs[1].append(b)
-        self._tp = [(C.c_void_p * (nl + 1))(*[t.data_ptr() for t in self.bufs[i]]) for i in range(2)]
+        # pointer tables [set of the conv outputs][set of the other tensors]: the two only differ after in-place frames
+        self._tp = [[(C.c_void_p * (nl + 1))(*[self.bufs[cc if is_conv[t] else cn][t].data_ptr() for t in range(nl + 1)])
+                     for cn in range(2)] for cc in range(2)]
+        self.cur_other = 0    # set that receives the next frame's tensors other than conv outputs
         gh, gw = H // block, W // block
         dev = self.device
         self.mv = torch.zeros((n_streams, gh, gw, 2), dtype=torch.int16, device=dev)
@@ -492,10 +497,11 @@ class StackRunner:
         assert frames.is_cuda and frames.dtype == torch.uint8 and frames.is_contiguous()
         assert tuple(frames.shape) == (self.n, self.H, self.W, self.Ch)
         c, p = self.cur, 1 - self.cur
+        cn = self.cur_other
         full = force_full or not self.have_prev or (self.expiry > 0 and self.age >= self.expiry)
         _check("dc_run_stack", lib().dc_run_stack(
             self.Lc, len(self.layers), self._wp, self._wpp, self._bp, _ptr(frames), _ptr(self.prev_frames),
-            self._tp[c], self._tp[p], self.n, self.H, self.W, self.Ch, self.dtype, self.block, self.radius,
+            self._tp[c][cn], self._tp[p][cn], self.n, self.H, self.W, self.Ch, self.dtype, self.block, self.radius,
             self.max_block_ssd, C.byref(self.match_options), int(full),
             C.byref(self._in_place_flag) if self.in_place else None, _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
             _ptr(self.mask), self.max_rects, self.regs, _ptr(self.ws_dev), self.ws_dev.numel(),
@@ -505,10 +511,11 @@ class StackRunner:
         self.prev_frames = frames
         self.last_full = full
         self.last_in_place = self.in_place and self._in_place_flag.value != 0
-        if self.last_in_place:      # the conv outputs were updated in the previous frame's buffers: no swap
-            return [self.bufs[p][t] if self._is_conv_out[t] else self.bufs[c][t] for t in range(len(self.bufs[c]))]
+        self.cur_other = 1 - cn
+        if self.last_in_place:      # the conv outputs were updated in the previous frame's buffers: no swap of those
+            return [self.bufs[p if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]
         self.cur = p
-        return self.bufs[c]
+        return [self.bufs[c if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]
 
     def enable_profile(self, on=True):
         """Attach (or detach) HIP-event brackets around every conv GEMM and copy launch."""

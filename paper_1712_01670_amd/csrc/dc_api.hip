@@ -248,7 +248,12 @@ int32_t dc_overlap_pipeline(void* overlap, int32_t frames_in_flight) {
     if (!overlap) return DC_ERR_NULL_PTR;
     if (frames_in_flight < 1 || frames_in_flight > 2) return DC_ERR_INVALID_ARG;
     Overlap* o = static_cast<Overlap*>(overlap);
-    for (int i = 0; i < 2; ++i) DC_TRY_HIP(hipStreamSynchronize(o->work[i]));
+    for (int i = 0; i < 2; ++i) {
+        DC_TRY_HIP(hipStreamSynchronize(o->work[i]));
+        o->recorded[i].clear();
+        o->last_cur[i].clear();
+        o->frame_recorded[i] = false;
+    }
     o->pipeline = frames_in_flight == 2;
     return DC_OK;
 }
@@ -739,21 +744,49 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     for (int i = n_layers - 1; i >= 0; --i)
         if (layers[i].type == DC_CONV)
             run_end[i] = (i + 1 < n_layers && layers[i + 1].type == DC_CONV) ? run_end[i + 1] : i;
+    // A tensor that holds no cached values (anything but a conv output) may be one buffer for all frames, or the
+    // caller may alternate it like the conv outputs.  If this frame's buffer is not the previous frame's but the
+    // one this work stream used for its last frame, its last users are on this same stream: no cross-stream
+    // wait, and (expecting the caller to go on alternating) no event for the next frame.  Should the next frame
+    // then use this frame's buffer after all, it finds no event and waits for the whole frame.
+    std::vector<char> fresh(n_layers + 1, 0);
+    if (pipe && ov->last_cur[0].size() == (size_t)n_layers + 1 && ov->last_cur[1].size() == (size_t)n_layers + 1)
+        for (int t = 0; t <= n_layers; ++t)
+            fresh[t] = (t == 0 || layers[t - 1].type != DC_CONV) && ov->last_cur[1 - fp][t] != tensors_cur[t] &&
+                       ov->last_cur[fp][t] == tensors_cur[t];
     // only the layers that the next frame can wait for get an event
     std::vector<char> is_target(n_layers, 0);
     if (pipe) {
-        if (last_reader[0] >= 0) is_target[last_reader[0]] = 1;
+        if (last_reader[0] >= 0 && !fresh[0]) is_target[last_reader[0]] = 1;
         for (int i = 0; i < n_layers; ++i) {
             if (layers[i].type == DC_CONV) is_target[run_end[i]] = 1;
-            if ((layers[i].type != DC_CONV || in_place) && last_reader[i + 1] >= 0) is_target[last_reader[i + 1]] = 1;
+            if ((layers[i].type != DC_CONV || in_place) && last_reader[i + 1] >= 0 && !fresh[i + 1])
+                is_target[last_reader[i + 1]] = 1;
         }
     }
     int waited = -1;
     auto wait_prev = [&](int w) -> hipError_t {     // the previous frame has finished its layers 0..w
         if (!pipe || w <= waited) return hipSuccess;
-        waited = w;
-        return hipStreamWaitEvent(st, ov->layer_done[1 - fp][w], 0);
+        const std::vector<char>& rec = ov->recorded[1 - fp];
+        if ((size_t)w < rec.size() && rec[w]) {
+            waited = w;
+            return hipStreamWaitEvent(st, ov->layer_done[1 - fp][w], 0);
+        }
+        waited = n_layers;
+        return ov->frame_recorded[1 - fp] ? hipStreamWaitEvent(st, ov->frame_done[1 - fp], 0) : hipSuccess;
     };
+    auto wait_readers = [&](int t) -> hipError_t {  // before tensor t is overwritten
+        return fresh[t] ? hipSuccess : wait_prev(last_reader[t]);
+    };
+    if (pipe) {
+        try {
+            ov->recorded[fp].assign(n_layers, 0);
+            ov->last_cur[fp].reserve(n_layers + 1);
+        } catch (const std::bad_alloc&) {
+            return DC_ERR_WORKSPACE;
+        }
+        ov->frame_recorded[fp] = false;
+    }
     // Device workspace: [plans, frame parity 0][plans, parity 1][K-split scratch 0][scratch 1]
     unsigned char* plan_dev = nullptr;
     unsigned char* conv_scratch = nullptr;
@@ -793,7 +826,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         DC_TRY_HIP(hipMemcpyAsync(h_mask, block_mask, nb, hipMemcpyDeviceToHost, mst));
         DC_TRY_HIP(hipMemcpyAsync(h_gmv, global_mv, (size_t)n_streams * 2 * sizeof(int32_t), hipMemcpyDeviceToHost, mst));
         // the network input does not depend on the match: its conversion overlaps the readback
-        DC_TRY_HIP(wait_prev(last_reader[0]));
+        DC_TRY_HIP(wait_readers(0));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
         g_host_timing.mark(0);
         if (ov) {
@@ -849,7 +882,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         }
         g_host_timing.mark(6);
     } else {
-        DC_TRY_HIP(wait_prev(last_reader[0]));
+        DC_TRY_HIP(wait_readers(0));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
     }
     if (regions_out) {
@@ -1012,22 +1045,22 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 if (rc) return rc;
                 break;
             case DC_MAXPOOL:
-                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(wait_readers(t));
                 DC_TRY_HIP(launch_maxpool(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
                                           dtype, st));
                 break;
             case DC_ADD:
-                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(wait_readers(t));
                 DC_TRY_HIP(launch_add(eff[a], eff[l.in1], eff[t],
                                       (size_t)n_streams * hs[t] * ws[t] * cs[t], l.relu, dtype, st));
                 break;
             case DC_AVGPOOL:
-                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(wait_readers(t));
                 DC_TRY_HIP(launch_avgpool(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
                                           dtype, st));
                 break;
             case DC_LRN:
-                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(wait_readers(t));
                 DC_TRY_HIP(launch_lrn(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], l.k, l.within,
                                       l.alpha, l.beta, l.kappa, dtype, st));
                 break;
@@ -1036,30 +1069,35 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 const void* ins[4];
                 const int m = concat_inputs(l, ids);
                 for (int j = 0; j < m; ++j) { ins[j] = eff[ids[j]]; chans[j] = cs[ids[j]]; }
-                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(wait_readers(t));
                 DC_TRY_HIP(launch_concat(ins, chans, m, eff[t], (size_t)n_streams * hs[t] * ws[t], dtype, st));
                 break;
             }
             case DC_FC:
-                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(wait_readers(t));
                 DC_TRY_HIP(launch_fc(eff[a], weights[i], bias ? bias[i] : nullptr, eff[t], n_streams,
                                      (size_t)hs[a] * ws[a] * cs[a], l.cout, l.relu, dtype, st));
                 break;
             case DC_SOFTMAX:
-                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(wait_readers(t));
                 DC_TRY_HIP(launch_softmax(eff[a], eff[t], (size_t)n_streams * hs[t] * ws[t], cs[t], dtype, st));
                 break;
             default:
-                DC_TRY_HIP(wait_prev(last_reader[t]));
+                DC_TRY_HIP(wait_readers(t));
                 DC_TRY_HIP(launch_add(eff[a], nullptr, eff[t], (size_t)n_streams * hs[t] * ws[t] * cs[t],
                                       1, dtype, st));
                 break;
         }
-        if (pipe && is_target[i]) DC_TRY_HIP(hipEventRecord(ov->layer_done[fp][i], st));
+        if (pipe && is_target[i]) {
+            DC_TRY_HIP(hipEventRecord(ov->layer_done[fp][i], st));
+            ov->recorded[fp][i] = 1;
+        }
     }
     if (pipe) {
         // the caller's stream sees the frame complete; the next frame goes to the other work stream
         DC_TRY_HIP(hipEventRecord(ov->frame_done[fp], st));
+        ov->frame_recorded[fp] = true;
+        ov->last_cur[fp].assign(tensors_cur, tensors_cur + n_layers + 1);   // capacity reserved above
         DC_TRY_HIP(hipStreamWaitEvent(caller_st, ov->frame_done[fp], 0));
         ov->frame_parity ^= 1;
     }

@@ -139,7 +139,9 @@ struct Profile {
 //  - aux: the matching of a frame and the read-back of its mask run here, next to the previous frame's layers;
 //  - pipeline: consecutive frames alternate between two work streams; layer i of a frame waits for layer i of
 //    the previous frame (its cache) and for the previous frame's readers of every single-buffered tensor it
-//    overwrites, so two frames are in flight and the second fills the CUs the first leaves idle.
+//    overwrites, so two frames are in flight and the second fills the CUs the first leaves idle.  A tensor
+//    whose buffer is not the previous frame's but that of the frame before it (a caller that alternates all
+//    its tensors, not only the conv outputs) was last used on this same stream and needs neither wait nor event.
 struct Overlap {
     hipStream_t aux = nullptr;
     hipEvent_t match_done = nullptr;                  // mask and motion of the current frame are in host memory
@@ -150,6 +152,9 @@ struct Overlap {
     hipStream_t work[2] = {nullptr, nullptr};
     hipEvent_t frame_done[2] = {nullptr, nullptr};
     std::vector<hipEvent_t> layer_done[2];            // [frame parity][layer]
+    std::vector<char> recorded[2];                    // [frame parity][layer]: that frame recorded layer_done
+    bool frame_recorded[2] = {false, false};          // that frame recorded frame_done
+    std::vector<const void*> last_cur[2];             // [frame parity]: tensors_cur of that stream's last frame
     int frame_parity = 0;
 };
 
