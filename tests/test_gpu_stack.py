@@ -382,3 +382,37 @@ def test_overlap_modes_give_identical_tensors(net, size, bf16):
         for f, (a, b) in enumerate(zip(results["pipeline"], results[mode])):
             for i, (x, y) in enumerate(zip(a, b)):
                 assert torch.equal(x, y), (net, mode, f, i)
+
+
+def test_pipelined_frames_with_irregular_buffer_alternation():
+    """With two frames in flight the library skips the cross-stream wait for a tensor whose buffer is the one its
+    work stream used last and not the previous frame's, and records no event for it; a caller that then reuses the
+    previous frame's buffer after all must still get the same tensors (the library waits for the whole previous
+    frame instead).  The runner's choice of the set for the tensors that are not conv outputs is overridden
+    frame by frame with a pattern that holds every transition; frames are issued without synchronisation."""
+    H = W = 96
+    layers = synth.vgg16()
+    ws, bs = synth.he_weights(layers, 3, bias_scale=0.05)
+    T = 14
+    video = torch.from_numpy(synth.panning_video(78, n_frames=T, H=H, W=W, fg=((24, 24), (16, 32)))).to(DEV)
+    frames = [video[t:t + 1].contiguous() for t in range(T)]
+    torch.cuda.synchronize()
+    pattern = [0, 1, 0, 0, 1, 1, 1, 0, 1, 0, 0, 0, 1, 0]
+    finals = {}
+    for mode, kw in (("pipeline", dict(overlap=True, pipeline=True)), ("plain", dict(overlap=False))):
+        print(f"[irregular alternation] {mode}", flush=True)
+        runner = binding.StackRunner(layers, ws, bs, 1, H, W, 3, block=16, radius=16, dtype=binding.DC_F32, expiry=6, **kw)
+        kept = []
+        for stop in (5, 9, T):
+            runner.reset()
+            for t in range(stop):
+                if mode == "pipeline":
+                    runner.cur_other = pattern[t]
+                tensors = runner.step(frames[t])
+            torch.cuda.synchronize()
+            kept.append([x.clone() for x in tensors])
+        finals[mode] = kept
+        del runner
+    for f, (a, b) in enumerate(zip(finals["pipeline"], finals["plain"])):
+        for i, (x, y) in enumerate(zip(a, b)):
+            assert torch.equal(x, y), (f, i)
