@@ -472,3 +472,50 @@ def test_leaky_relu_in_every_conv_kernel(oracle, case, bf16):
         want = oracle.conv_cached(x[i], w, b, k, s, p, 2, bf16=bf16)
         assert (want < 0).any()
         assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
+
+
+# Launches of the general kernel with at least three workgroups on every two CUs switch to short stages of the
+# narrowest channel chunk (one kernel row of taps, or about a dozen taps where four wavefronts share a stage):
+# shapes that reach that many workgroups at a size the oracle still handles.
+SHORT_STAGE_CASES = [
+    # n, H, W, cin, cout, k, s, p
+    (12, 64, 64, 32, 128, 3, 2, 1),     # 384 workgroups of 4 units x 64 channels: 3 taps per stage
+    (6, 48, 48, 16, 128, 5, 1, 2),      # 432 workgroups: 5 taps per stage
+    (16, 28, 28, 16, 32, 5, 1, 2),      # 392 workgroups of 2 units x 32 channels: 13 + 12 taps (tap tail)
+    (12, 62, 66, 40, 72, 3, 2, 0),      # channel tail in the chunk, ragged channel tile, no padding
+]
+
+
+@pytest.mark.parametrize("cached", [False, True])
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("case", SHORT_STAGE_CASES)
+def test_general_kernel_short_stages(oracle, case, bf16, cached):
+    n, H, W, cin, cout, k, s, p = case
+    print(f"[short stages] case={case} bf16={bf16} cached={cached}", flush=True)
+    rng = np.random.default_rng(sum(case) + 7)
+    x = rng.standard_normal((n, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, k, k, cin)) * np.sqrt(2.0 / (cin * k * k))).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    Ho, Wo = (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1
+    cache = rng.standard_normal((n, Ho, Wo, cout)).astype(np.float32)
+    if bf16:
+        x, w, cache = oracle.round_bf16(x), oracle.round_bf16(w), oracle.round_bf16(cache)
+    regions = None
+    if cached:      # few reusable pixels, so that the launch keeps its many workgroups
+        regions = []
+        for i in range(n):
+            rw, rh = int(rng.integers(2, 7)), int(rng.integers(2, 7))
+            rx, ry = int(rng.integers(2, Wo - rw - 2)), int(rng.integers(2, Ho - rh - 2))
+            regions.append((np.array([[rx, ry, rw, rh]], np.int32), (int(rng.integers(-2, 3)), int(rng.integers(-2, 3)))))
+    got = _to_np(binding.dc_cached_conv_layer(_layer(cin, cout, k, s, p, True), _to_dev(x, bf16), _to_dev(w, bf16),
+                                              torch.from_numpy(b).to(DEV),
+                                              cache_prev=_to_dev(cache, bf16) if cached else None, regions=regions))
+    for i in range(n):
+        if cached:
+            mask = oracle.rasterize(regions[i][0], Ho, Wo)
+            want = oracle.conv_cached(x[i], w, b, k, s, p, True, cache_prev=cache[i], mask=mask, dxy=regions[i][1], bf16=bf16)
+            m = mask.astype(bool)
+            assert np.array_equal(got[i][m], want[m]), "copied pixels must be bit-identical"
+        else:
+            want = oracle.conv_cached(x[i], w, b, k, s, p, True, bf16=bf16)
+        assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
