@@ -30,13 +30,13 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM traffic per launch of the conv kernels on this workload, from two rocprofv3 --pmc runs of this file
 # (profiles/vgg16_224_f32_hbm_traffic.txt): kernel -> (FETCH_SIZE, WRITE_SIZE) counter averages.  A plain
-# 256 MiB device copy reads 131087 / 262144 on the same counters, hence the scale factors.
+# 256 MiB device copy reads 131085 / 262144 on the same counters, hence the scale factors.
 PMC_TRAFFIC = {
-    "conv_fast_kernel<float, 3, 16, 1, 2, 4, 1>": (7623.0, 3142.0),
-    "conv_fast_kernel<float, 3, 16, 2, 2, 4, 1>": (8939.0, 9088.0),
-    "conv_fast_kernel<float, 3, 16, 3, 2, 4, 1>": (4189.0, 3664.1),
-    "conv_fast_kernel<float, 3, 16, 4, 2, 4, 1>": (6369.9, 8362.7),
-    "conv_fast_kernel<float, 3, 32, 1, 2, 4, 1>": (7242.5, 1986.0),
+    "conv_fast_kernel<float, 3, 16, 1, 2, 4, 1>": (7625.5, 3142.0),
+    "conv_fast_kernel<float, 3, 16, 2, 2, 4, 1>": (8938.4, 9088.0),
+    "conv_fast_kernel<float, 3, 16, 3, 2, 4, 1>": (4191.0, 3664.1),
+    "conv_fast_kernel<float, 3, 16, 4, 2, 4, 1>": (6366.4, 8362.7),
+    "conv_fast_kernel<float, 3, 32, 1, 2, 4, 1>": (7245.5, 1986.0),
 }
 PMC_SCALE = (2.0, 1.0)      # KiB of HBM traffic per counter unit (fetch, write)
 
