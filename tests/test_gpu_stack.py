@@ -416,3 +416,32 @@ def test_pipelined_frames_with_irregular_buffer_alternation():
     for f, (a, b) in enumerate(zip(finals["pipeline"], finals["plain"])):
         for i, (x, y) in enumerate(zip(a, b)):
             assert torch.equal(x, y), (f, i)
+
+
+def test_pageable_host_workspace_gives_the_same_tensors():
+    """The frame's plans reach the device through a kernel that reads the pinned staging buffer, or through an
+    asynchronous copy when the host workspace is pageable memory: same tensors either way."""
+    H = W = 64
+    layers = synth.vgg16()[:7]
+    ws, bs = synth.he_weights(layers, 3, bias_scale=0.05)
+    T = 6
+    video = torch.from_numpy(synth.panning_video(79, n_frames=T, H=H, W=W, fg=((16, 16), (8, 24)))).to(DEV)
+    frames = [video[t:t + 1].contiguous() for t in range(T)]
+    torch.cuda.synchronize()
+    outs = {}
+    for pinned in (True, False):
+        print(f"[host workspace] pinned={pinned}", flush=True)
+        runner = binding.StackRunner(layers, ws, bs, 1, H, W, 3, block=16, radius=16, dtype=binding.DC_F32)
+        if not pinned:
+            runner.ws_host = torch.empty(runner.ws_host.numel(), dtype=torch.uint8)
+        kept = []
+        for t in range(T):
+            tensors = runner.step(frames[t])
+            torch.cuda.synchronize()
+            kept.append([x.clone() for x in tensors])
+        assert runner.stats.n_reusable_blocks > 0
+        outs[pinned] = kept
+        del runner
+    for a, b in zip(outs[True], outs[False]):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
