@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--matcher", choices=["es", "ds"], default="es",
                     help="Step 2 of the matching: exhaustive search, or the diamond search of Section 4")
     ap.add_argument("--k-skip", type=int, default=1, help="search every k-th block row and column only (Section 4)")
+    ap.add_argument("--lookahead", action="store_true",
+                    help="start the matching of the next frame at the end of a step (dc_prefetch_match), as a decoder "
+                         "one frame ahead would allow")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=10)
     args = ap.parse_args()
@@ -84,7 +87,8 @@ def main():
             f = i % n_frames
             if f == 0:
                 runner.reset()          # the video wraps: a scene cut
-            runner.step(dev_video[f])
+            nxt = (i + 1) % n_frames
+            runner.step(dev_video[f], next_frames=dev_video[nxt] if (args.lookahead and nxt != 0) else None)
             if collect is not None:
                 collect(i, f)
 
@@ -195,6 +199,7 @@ def main():
                                "16x16 blocks, search +/-16, tau=20",
                    "streams": n, "matcher": ("exhaustive search" if args.matcher == "es" else "diamond search") + f", k-skip {args.k_skip}",
                    "cache_expiry_frames": args.expiry, "frames_per_video": n_frames,
+                   "lookahead_frames": 1 if args.lookahead else 0,
                    "mean_block_reuse": float(np.mean(agg["reuse"])) if agg["reuse"] else 0.0,
                    "full_frame_fraction": agg["full_frames"] / max(steps_all, 1),
                    "mac_fraction_needed": agg["macs_needed"] / max(agg["macs_full"], 1),

@@ -151,6 +151,23 @@ int32_t dc_profile_elapsed_ms(void* profile, int32_t slot, float* ms);
  * Callers that may not create streams simply pass no handle.
  */
 int32_t dc_overlap_create(void** overlap);
+/*
+ * Look-ahead matching (Section 7.6): starts Steps 1-4 for the NEXT frame on the handle's matching
+ * stream and returns at once, so that the dc_run_stack call for that frame finds the mask and the
+ * motion already in host memory instead of waiting for them.  Call it after the dc_run_stack call of
+ * the current frame, with the arguments the next dc_run_stack call will pass (frames_next as its
+ * frames_cur, frames_cur as its frames_prev, the same match buffers and host workspace): the very
+ * next dc_run_stack call with the handle uses the result if every one of them is the same and
+ * otherwise matches again itself; any later call ignores it.  Both frames must be complete in memory
+ * and stay unchanged until that call; the match buffers and the head of ws_host are written from now
+ * on (the previous frame's mv / mask are overwritten early).  Not needed before a frame that is
+ * computed in full.  Errors as dc_match_blocks_opt; DC_ERR_WORKSPACE if ws_host is too small.
+ */
+int32_t dc_prefetch_match(void* overlap, const uint8_t* frames_next, const uint8_t* frames_cur,
+                          int32_t n_streams, int32_t H, int32_t W, int32_t C, int32_t block, int32_t radius,
+                          uint32_t max_block_ssd, const dc_match_options* match_options,
+                          int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
+                          uint8_t* block_mask, void* ws_host, size_t ws_host_bytes);
 int32_t dc_overlap_destroy(void* overlap);
 int32_t dc_overlap_pipeline(void* overlap, int32_t frames_in_flight /* 1 or 2 */);
 

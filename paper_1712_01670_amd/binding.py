@@ -22,7 +22,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
           -4: "DC_ERR_UNSUPPORTED", -5: "DC_ERR_WORKSPACE", -6: "DC_ERR_CAPACITY", -7: "DC_ERR_HIP"}
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
-           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_propagate_regions_opt", "dc_conv_workspace_bytes",
+           "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_prefetch_match", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_propagate_regions_opt", "dc_conv_workspace_bytes",
            "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer", "dc_avgpool_layer", "dc_lrn_layer", "dc_concat_layer", "dc_fc_layer", "dc_softmax_layer",
            "dc_stack_workspace_bytes", "dc_run_stack"]
 
@@ -82,6 +82,7 @@ def lib():
         L.dc_overlap_create.argtypes = [C.POINTER(vp)]
         L.dc_overlap_destroy.argtypes = [vp]
         L.dc_overlap_pipeline.argtypes = [vp, i32]
+        L.dc_prefetch_match.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, u32, vp, vp, vp, vp, vp, vp, vp, sz]
         L.dc_conv_tuning.argtypes = [i32, i32, i32, i32]
         L.dc_conv_kernel_name.argtypes = [i32, C.c_char_p, sz]
         L.dc_conv_tile_shape.argtypes = [vp, i32, i32, i32, i32] + [C.POINTER(i32)] * 4
@@ -489,11 +490,13 @@ class StackRunner:
         self.prev_frames = None
         self.age = 0
 
-    def step(self, frames, force_full=False):
+    def step(self, frames, force_full=False, next_frames=None):
         """frames: uint8 cuda tensor [n][H][W][C], resident (its producer has completed: the library reads it on
         streams of its own) and contiguous; it is kept by reference as the next step's previous frame, so the
         caller must not overwrite it before that step has run.  Returns the list of this frame's tensors, valid
-        once the current stream is synchronised."""
+        once the current stream is synchronised.  next_frames: the tensor the next step will be called with, if
+        the caller has it already (a decoder one frame ahead): its matching is started at the end of this step
+        (dc_prefetch_match), so the next step does not wait for it; mv / mask then belong to that frame."""
         assert frames.is_cuda and frames.dtype == torch.uint8 and frames.is_contiguous()
         assert tuple(frames.shape) == (self.n, self.H, self.W, self.Ch)
         c, p = self.cur, 1 - self.cur
@@ -511,6 +514,13 @@ class StackRunner:
         self.prev_frames = frames
         self.last_full = full
         self.last_in_place = self.in_place and self._in_place_flag.value != 0
+        if next_frames is not None and self.overlap and not (self.expiry > 0 and self.age >= self.expiry):
+            assert next_frames.is_cuda and next_frames.dtype == torch.uint8 and next_frames.is_contiguous()
+            assert tuple(next_frames.shape) == (self.n, self.H, self.W, self.Ch)
+            _check("dc_prefetch_match", lib().dc_prefetch_match(
+                self.overlap, _ptr(next_frames), _ptr(frames), self.n, self.H, self.W, self.Ch, self.block, self.radius,
+                self.max_block_ssd, C.byref(self.match_options), _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv),
+                _ptr(self.n_pass), _ptr(self.mask), C.c_void_p(self.ws_host.data_ptr()), self.ws_host.numel()))
         self.cur_other = 1 - cn
         if self.last_in_place:      # the conv outputs were updated in the previous frame's buffers: no swap of those
             return [self.bufs[p if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]

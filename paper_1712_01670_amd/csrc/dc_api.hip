@@ -276,6 +276,38 @@ int32_t dc_overlap_destroy(void* overlap) {
     return DC_OK;
 }
 
+int32_t dc_prefetch_match(void* overlap, const uint8_t* frames_next, const uint8_t* frames_cur,
+                          int32_t n_streams, int32_t H, int32_t W, int32_t C, int32_t block, int32_t radius,
+                          uint32_t max_block_ssd, const dc_match_options* match_options,
+                          int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
+                          uint8_t* block_mask, void* ws_host, size_t ws_host_bytes) {
+    if (!overlap || !frames_next || !frames_cur || !global_mv || !block_mask || !ws_host) return DC_ERR_NULL_PTR;
+    if (n_streams < 1 || H < 1 || W < 1 || C < 1 || block < 1 || H % block || W % block) return DC_ERR_INVALID_ARG;
+    Overlap* ov = static_cast<Overlap*>(overlap);
+    const size_t nb = (size_t)n_streams * (H / block) * (W / block);
+    if (ws_host_bytes < align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256)) return DC_ERR_WORKSPACE;
+    if (ov->prefetch.valid) {     // an unused look-ahead is dropped once its kernels are out of the way
+        DC_TRY_HIP(hipStreamSynchronize(ov->aux));
+        ov->prefetch.valid = false;
+    }
+    int rc = dc_match_blocks_opt(frames_next, frames_cur, n_streams, H, W, C, block, radius, match_options, max_block_ssd,
+                                 mv, best_ssd, global_mv, n_pass, block_mask, ov->aux);
+    if (rc) return rc;
+    unsigned char* hbase = static_cast<unsigned char*>(ws_host);
+    DC_TRY_HIP(hipMemcpyAsync(hbase, block_mask, nb, hipMemcpyDeviceToHost, ov->aux));
+    DC_TRY_HIP(hipMemcpyAsync(hbase + align_up(nb, 256), global_mv, (size_t)n_streams * 2 * sizeof(int32_t),
+                              hipMemcpyDeviceToHost, ov->aux));
+    DC_TRY_HIP(hipEventRecord(ov->match_done, ov->aux));
+    Overlap::Prefetch& pf = ov->prefetch;
+    pf.cur = frames_next; pf.prev = frames_cur; pf.mv = mv; pf.best_ssd = best_ssd; pf.gmv = global_mv; pf.n_pass = n_pass;
+    pf.mask = block_mask; pf.ws_host = ws_host; pf.n_streams = n_streams; pf.H = H; pf.W = W; pf.C = C; pf.block = block;
+    pf.radius = radius; pf.max_block_ssd = max_block_ssd;
+    pf.method = match_options ? match_options->method : DC_MATCH_EXHAUSTIVE;
+    pf.k_skip = match_options ? match_options->k_skip : 1;
+    pf.valid = true;
+    return DC_OK;
+}
+
 int32_t dc_overlap_pipeline(void* overlap, int32_t frames_in_flight) {
     if (!overlap) return DC_ERR_NULL_PTR;
     if (frames_in_flight < 1 || frames_in_flight > 2) return DC_ERR_INVALID_ARG;
@@ -743,6 +775,9 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     }
     Overlap* ov = static_cast<Overlap*>(overlap);
     hipStream_t caller_st = as_stream(stream);
+    // a look-ahead match is for the very next call only (the caller may reuse its frame buffers after that)
+    Overlap::Prefetch pf;
+    if (ov) { pf = ov->prefetch; ov->prefetch.valid = false; }
     // Pipelined: this frame's work goes to one of the handle's two streams, the previous frame's is on the other.
     const bool pipe = ov && ov->pipeline;
     const int fp = pipe ? ov->frame_parity : 0;
@@ -850,19 +885,32 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         // With an overlap handle the matching runs on its own stream, next to whatever the main stream
         // still holds of the previous frame; only that stream is waited for.
         hipStream_t mst = ov ? ov->aux : st;
-        rc = dc_match_blocks_opt(frames_cur, frames_prev, n_streams, H, W, C, block, radius, match_options, max_block_ssd,
-                                 mv, best_ssd, global_mv, n_pass, block_mask, mst);
-        if (rc) return rc;
         uint8_t* h_mask = hbase;
         int32_t* h_gmv = reinterpret_cast<int32_t*>(hbase + align_up(nb, 256));
-        DC_TRY_HIP(hipMemcpyAsync(h_mask, block_mask, nb, hipMemcpyDeviceToHost, mst));
-        DC_TRY_HIP(hipMemcpyAsync(h_gmv, global_mv, (size_t)n_streams * 2 * sizeof(int32_t), hipMemcpyDeviceToHost, mst));
+        // a match started ahead of time with exactly these arguments is on its way or done already
+        bool prefetched = false;
+        if (ov) {
+            prefetched = pf.valid && pf.cur == frames_cur && pf.prev == frames_prev && pf.mv == mv &&
+                         pf.best_ssd == best_ssd && pf.gmv == global_mv && pf.n_pass == n_pass && pf.mask == block_mask &&
+                         pf.ws_host == ws_host && pf.n_streams == n_streams && pf.H == H && pf.W == W && pf.C == C &&
+                         pf.block == block && pf.radius == radius && pf.max_block_ssd == max_block_ssd &&
+                         pf.method == (match_options ? match_options->method : DC_MATCH_EXHAUSTIVE) &&
+                         pf.k_skip == (match_options ? match_options->k_skip : 1);
+            if (pf.valid && !prefetched) DC_TRY_HIP(hipStreamSynchronize(mst));   // let the stale match finish first
+        }
+        if (!prefetched) {
+            rc = dc_match_blocks_opt(frames_cur, frames_prev, n_streams, H, W, C, block, radius, match_options,
+                                     max_block_ssd, mv, best_ssd, global_mv, n_pass, block_mask, mst);
+            if (rc) return rc;
+            DC_TRY_HIP(hipMemcpyAsync(h_mask, block_mask, nb, hipMemcpyDeviceToHost, mst));
+            DC_TRY_HIP(hipMemcpyAsync(h_gmv, global_mv, (size_t)n_streams * 2 * sizeof(int32_t), hipMemcpyDeviceToHost, mst));
+        }
         // the network input does not depend on the match: its conversion overlaps the readback
         DC_TRY_HIP(wait_readers(0));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
         g_host_timing.mark(0);
         if (ov) {
-            DC_TRY_HIP(hipEventRecord(ov->match_done, mst));
+            if (!prefetched) DC_TRY_HIP(hipEventRecord(ov->match_done, mst));
             DC_TRY_HIP(spin_wait(ov->match_done));
         } else {
             DC_TRY_HIP(hipStreamSynchronize(mst));

@@ -156,6 +156,14 @@ struct Overlap {
     bool frame_recorded[2] = {false, false};          // that frame recorded frame_done
     std::vector<const void*> last_cur[2];             // [frame parity]: tensors_cur of that stream's last frame
     int frame_parity = 0;
+    // look-ahead matching: the arguments of a match already started for the next frame
+    struct Prefetch {
+        bool valid = false;
+        const void *cur = nullptr, *prev = nullptr, *mv = nullptr, *best_ssd = nullptr, *gmv = nullptr, *n_pass = nullptr,
+                   *mask = nullptr, *ws_host = nullptr;
+        int n_streams = 0, H = 0, W = 0, C = 0, block = 0, radius = 0, method = 0, k_skip = 1;
+        uint32_t max_block_ssd = 0;
+    } prefetch;
 };
 
 inline size_t dtype_size(int dtype) { return dtype == DC_BF16 ? 2 : 4; }

@@ -445,3 +445,66 @@ def test_pageable_host_workspace_gives_the_same_tensors():
     for a, b in zip(outs[True], outs[False]):
         for x, y in zip(a, b):
             assert torch.equal(x, y)
+
+
+def test_lookahead_matching_gives_the_same_tensors():
+    """Section 7.6: the matching of the next frame started one step early (dc_prefetch_match) must change
+    nothing but the time at which it runs: same tensors and the same masks as without it, across cache expiry,
+    a scene cut, and a look-ahead that names a frame other than the one that follows (it must be ignored)."""
+    H = W = 96
+    layers = synth.vgg16()[:10]
+    ws, bs = synth.he_weights(layers, 3, bias_scale=0.05)
+    T = 12
+    video = torch.from_numpy(synth.panning_video(80, n_frames=T, H=H, W=W, fg=((24, 24), (16, 32)))).to(DEV)
+    frames = [video[t:t + 1].contiguous() for t in range(T)]
+    torch.cuda.synchronize()
+    order = list(range(T)) + [3, 4, 5]              # a jump back: a scene cut handled by reset()
+    results = {}
+    for look in (False, True):
+        print(f"[lookahead] {look}", flush=True)
+        runner = binding.StackRunner(layers, ws, bs, 1, H, W, 3, block=16, radius=16, dtype=binding.DC_F32, expiry=5)
+        kept = []
+        for j, t in enumerate(order):
+            if j == T:
+                runner.reset()
+            nxt = None
+            if look and j + 1 < len(order):
+                nxt = frames[order[j + 1]]
+                if j == 6:
+                    nxt = frames[0]                 # wrong guess: the next call must match again itself
+            tensors = runner.step(frames[t], next_frames=nxt)
+            torch.cuda.synchronize()
+            kept.append(([x.clone() for x in tensors], runner.stats.n_reusable_blocks, runner.stats.full))
+        results[look] = kept
+        del runner
+    assert any(not full and reusable > 0 for _, reusable, full in results[True])
+    for j, ((a, ra, fa), (b, rb, fb)) in enumerate(zip(results[False], results[True])):
+        assert (ra, fa) == (rb, fb), j
+        for i, (x, y) in enumerate(zip(a, b)):
+            assert torch.equal(x, y), (j, i)
+
+
+def test_lookahead_matching_without_synchronisation():
+    """The same with two frames in flight and no synchronisation between the steps."""
+    H = W = 96
+    layers = synth.vgg16()
+    ws, bs = synth.he_weights(layers, 3, bias_scale=0.05)
+    T = 14
+    video = torch.from_numpy(synth.panning_video(81, n_frames=T, H=H, W=W, fg=((24, 24), (16, 32)))).to(DEV)
+    frames = [video[t:t + 1].contiguous() for t in range(T)]
+    torch.cuda.synchronize()
+    finals = {}
+    for look in (False, True):
+        runner = binding.StackRunner(layers, ws, bs, 1, H, W, 3, block=16, radius=16, dtype=binding.DC_F32, expiry=6)
+        kept = []
+        for stop in (4, 9, T):
+            runner.reset()
+            for t in range(stop):
+                tensors = runner.step(frames[t], next_frames=frames[t + 1] if (look and t + 1 < stop) else None)
+            torch.cuda.synchronize()
+            kept.append([x.clone() for x in tensors])
+        finals[look] = kept
+        del runner
+    for a, b in zip(finals[False], finals[True]):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
