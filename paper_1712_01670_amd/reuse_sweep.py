@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--matcher", choices=["es", "ds"], default="es")
     ap.add_argument("--k-skip", type=int, default=1)
     ap.add_argument("--pan", default="2,0", help="background motion in pixels per frame; 0,0 is a static camera")
+    ap.add_argument("--lookahead", action="store_true",
+                    help="hand the next frame over one step early, so that its matching starts then (dc_prefetch_match)")
     ap.add_argument("--extend-borders", action="store_true",
                     help="border case of the region rule for streams that did not move (beyond the paper's table)")
     ap.add_argument("--in-place", action="store_true",
@@ -71,7 +73,9 @@ def main():
                 scene_start = f == 0 or f == cut
                 if scene_start:
                     runner.reset()
-                runner.step(video[f], force_full=(mode == "full"))
+                nxt = f + 1
+                ahead = args.lookahead and mode != "full" and nxt < args.frames and nxt != cut
+                runner.step(video[f], force_full=(mode == "full"), next_frames=video[nxt] if ahead else None)
                 if collect:
                     torch.cuda.synchronize()
                     st = runner.stats
@@ -93,7 +97,8 @@ def main():
                          for s in range(args.streams)])                       # [streams][T][H][W][3]
         video = torch.from_numpy(np.ascontiguousarray(vids.transpose(1, 0, 2, 3, 4))).to(dev)
         out = {"target_reuse": r, "net": args.net, "size": args.size, "dtype": args.dtype, "frames": args.frames,
-               "streams": args.streams, "matcher": args.matcher, "k_skip": args.k_skip, "pan": list(pan), "in_place": bool(args.in_place), "extend_borders": bool(args.extend_borders)}
+               "streams": args.streams, "matcher": args.matcher, "k_skip": args.k_skip, "pan": list(pan), "in_place": bool(args.in_place), "extend_borders": bool(args.extend_borders),
+               "lookahead": bool(args.lookahead)}
         for mode, expiry in (("cached", 1 << 30), ("expiry", args.expiry), ("full", 1 << 30)):
             runner = binding.StackRunner(layers, ws, bs, args.streams, H, W, 3, block=16, radius=16, dtype=dt, expiry=expiry,
                                          match_method=binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE,
