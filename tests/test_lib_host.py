@@ -49,6 +49,12 @@ def test_argument_errors_are_reported_before_any_launch():
     opt = binding.MatchOptions(0, 0)
     assert L.dc_match_blocks_opt(one, one, 1, 64, 64, 3, 8, 8, C.byref(opt), 0, one, one, one, one, one, None) == -1    # k_skip
     assert L.dc_match_blocks_opt(None, one, 1, 64, 64, 3, 8, 8, None, 0, one, one, one, one, one, None) == -2
+    # look-ahead matching: handle and buffers are checked before anything is touched
+    assert L.dc_prefetch_match(None, one, one, 1, 64, 64, 3, 8, 8, 0, None, one, one, one, one, one, one, 4096) == -2
+    assert L.dc_prefetch_match(one, one, one, 1, 64, 64, 3, 8, 8, 0, None, one, one, one, one, None, one, 4096) == -2
+    assert L.dc_prefetch_match(one, one, one, 0, 64, 64, 3, 8, 8, 0, None, one, one, one, one, one, one, 4096) == -1
+    assert L.dc_prefetch_match(one, one, one, 1, 64, 60, 3, 8, 8, 0, None, one, one, one, one, one, one, 4096) == -1
+    assert L.dc_prefetch_match(one, one, one, 1, 64, 64, 3, 8, 8, 0, None, one, one, one, one, one, one, 16) == -5
     bad = binding.layers_to_c([dict(type=0, k=3, s=0, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
     assert L.dc_cached_conv_layer(bad, one, one, None, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -1
     ok = binding.layers_to_c([dict(type=0, k=3, s=1, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
