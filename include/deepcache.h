@@ -13,10 +13,14 @@
  *    throws or aborts across this boundary.  Argument errors are detected before
  *    any kernel is launched.
  *  - "dev" pointers are device (HBM) addresses, "host" pointers are host memory.
- *    The caller owns all memory.  The library keeps no state between calls and
- *    allocates no device memory; scratch comes in as caller-provided workspaces.
+ *    The caller owns all memory.  Apart from the handles it hands out (dc_profile_*,
+ *    dc_overlap_*) and a pool of host threads, the library keeps no state between
+ *    calls and allocates no device memory; scratch comes in as caller-provided
+ *    workspaces.
  *  - All GPU work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
- *    the default stream) and is asynchronous unless stated otherwise.
+ *    the default stream) and is asynchronous unless stated otherwise; with an overlap
+ *    handle dc_run_stack also uses the handle's own streams and makes `stream` wait
+ *    for them.
  *  - Frames are uint8 [n_streams][H][W][C] with interleaved channels, left-top
  *    origin.  Feature maps are [n_streams][H][W][C] channels-last in the storage
  *    type `dtype` (DC_F32 or DC_BF16; bf16 sums are accumulated in fp32 and rounded
