@@ -56,7 +56,7 @@ def main():
                     help="start the matching of the next frame at the end of a step (dc_prefetch_match), as a decoder "
                          "one frame ahead would allow")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-frames", type=int, default=10)
+    ap.add_argument("--cpu-frames", type=int, default=30)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (streams are independent and would shard "
@@ -217,8 +217,9 @@ def main():
         for f in range(k_cpu):
             ref.step(videos[0, f])
         cpu_s = time.perf_counter() - t0
+        n_cpu_full = len(range(0, k_cpu, args.expiry)) if args.expiry > 0 else 1
         cpu = {"value": k_cpu / cpu_s, "unit": "frames/s", "cores": oc.num_threads(), "kind": "oracle",
-               "sample": f"first {k_cpu} frames of stream 0 of the same video (1 full + {k_cpu - 1} cached), "
+               "sample": f"first {k_cpu} frames of stream 0 of the same video ({n_cpu_full} full + {k_cpu - n_cpu_full} cached), "
                          f"{cpu_s:.1f} s"}
 
     steps_all = agg["cached_frames"] + agg["full_frames"]
