@@ -1,23 +1,29 @@
 #!/usr/bin/env python3
 """Benchmark of the cache-aware CNN inference path on one MI355X.
 
-A step is one frame of the synthetic 224x224 video through the whole hot path:
-block matching against the previous frame, merge + region propagation, and the
-VGG-16-style stack in which every convolution copies its reusable pixels from the
-previous frame's cached output and computes only the rest.  Frames are resident in
-HBM before the timed region starts.
+Workload (default): 64 independent 224x224 video streams, one batch per time step, through the VGG-16-style stack
+in bf16 (fp32 accumulation).  A step is one frame of every stream through the whole hot path: block matching against
+the previous frame, merge + region propagation, and the stack in which every convolution copies its reusable pixels
+from the previous frame's cached output and computes only the rest.  Frames are resident in HBM before the timed
+region starts.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--dtype f32|bf16] [--streams n]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--dtype f32|bf16] [--streams n] [--repeats r]
 
-Prints one JSON line: whole-job frames/s with the cache (`value`) and without it (`no_cache`), the roofline of
-the dominant convolution kernel measured with HIP events during the run, and the CPU oracle timed on a bounded
-sample of the same video.
+Prints one JSON line: whole-job frames/s with the cache (`value`, the median over `repeats` timed regions of K steps)
+and without it (`no_cache`, same number of steps), the roofline of the dominant convolution kernel measured with HIP
+events during the run, the shifted copy against the HBM peak, the matching, the single-stream fp32 configuration as a
+sub-record, and the CPU oracle timed on a bounded sample of the same video.
+
+    python bench.py --traffic-calib     a plain 256 MiB device copy and nothing else (run under rocprofv3 --pmc
+                                        FETCH_SIZE / WRITE_SIZE: gives the bytes per counter unit)
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -26,93 +32,115 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense matrix peaks
+PEAK_INT8_TOPS = 5000.0
 PEAK_HBM_GBS = 8000.0
-
-# HBM traffic per launch of the conv kernels on this workload, from two rocprofv3 --pmc runs of this file
-# (profiles/vgg16_224_f32_hbm_traffic.txt): kernel -> (FETCH_SIZE, WRITE_SIZE) counter averages.  A plain
-# 256 MiB device copy reads 131085 / 262144 on the same counters, hence the scale factors.
-PMC_TRAFFIC = {
-    "conv_fast_kernel<float, 3, 16, 1, 2, 4, 1>": (7625.5, 3142.0),
-    "conv_fast_kernel<float, 3, 16, 2, 2, 4, 1>": (8938.4, 9088.0),
-    "conv_fast_kernel<float, 3, 16, 3, 2, 4, 1>": (4191.0, 3664.1),
-    "conv_fast_kernel<float, 3, 16, 4, 2, 4, 1>": (6366.4, 8362.7),
-    "conv_fast_kernel<float, 3, 32, 1, 2, 4, 1>": (7245.5, 1986.0),
-}
-PMC_SCALE = (2.0, 1.0)      # KiB of HBM traffic per counter unit (fetch, write)
+TARGET_CONV_FRAC = 0.5                           # the bar asked of the bf16 convolutions
+TARGET_COPY_FRAC = 0.6
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
-    ap.add_argument("--streams", type=int, default=1)
-    ap.add_argument("--expiry", type=int, default=10, help="full recompute every N frames (Section 5 default 10)")
-    ap.add_argument("--matcher", choices=["es", "ds"], default="es",
-                    help="Step 2 of the matching: exhaustive search, or the diamond search of Section 4")
-    ap.add_argument("--k-skip", type=int, default=1, help="search every k-th block row and column only (Section 4)")
-    ap.add_argument("--lookahead", action="store_true",
-                    help="start the matching of the next frame at the end of a step (dc_prefetch_match), as a decoder "
-                         "one frame ahead would allow")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-frames", type=int, default=30)
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (streams are independent and would shard "
-              "across GPUs without communication); run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def read_traffic_table(streams, dtype):
+    """HBM traffic per launch of the conv kernels from the rocprofv3 --pmc summary of this workload under
+    profiles/ (lines `traffic | kernel | FETCH_SIZE avg | WRITE_SIZE avg`, and a `calibration` line with the KiB of
+    HBM traffic per counter unit measured with `--traffic-calib`).  Returns (table, scale) or (None, None)."""
+    path = os.path.join(ROOT, "profiles", f"vgg16_224_{dtype}_{streams}streams_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None, None
+    table, scale = {}, None
+    with open(path) as fh:
+        for line in fh:
+            parts = [p.strip() for p in line.split("|")]
+            if parts[0] == "traffic" and len(parts) >= 4:
+                table[parts[1]] = (float(parts[2]), float(parts[3]))
+            elif parts[0] == "calibration" and len(parts) >= 3:
+                scale = (float(parts[1]), float(parts[2]))
+    return (table, scale) if table and scale else (None, None)
 
+
+def traffic_calib():
+    import torch
+    dev = torch.device("cuda:0")
+    n = 256 << 20
+    src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"traffic_calib": "device copy", "bytes_read": n, "bytes_written": n, "launches": 5}))
+
+
+def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames):
     import numpy as np
     import torch
     from paper_1712_01670_amd import binding, synth
 
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
     H = W = 224
     n_frames = 30
-    n = args.streams
     layers = synth.vgg16()
     ws, bs = synth.he_weights(layers, 1)
-    videos = np.stack([synth.panning_video(2000 + s, n_frames=n_frames, H=H, W=W) for s in range(n)])  # [n][T][H][W][3]
+    seed0 = 2000 if n == 1 else 5000           # configs[1] names one video, configs[4] per-stream seeds
+    videos = np.stack([synth.panning_video(seed0 + s, n_frames=n_frames, H=H, W=W) for s in range(n)])  # [n][T][H][W][3]
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(dev)
-    dt = binding.DC_BF16 if args.dtype == "bf16" else binding.DC_F32
+    dt = binding.DC_BF16 if dtype == "bf16" else binding.DC_F32
+    method = binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE
     runner = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
-                                 match_method=binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE,
-                                 k_skip=args.k_skip)
+                                 match_method=method, k_skip=args.k_skip, device_plan=False)
 
-    def run_steps(k, start, collect=None):
+    def run_steps(k, start, collect=None, force_full=False):
         """Run k steps through the cyclic video starting at global step `start`."""
         for i in range(start, start + k):
             f = i % n_frames
             if f == 0:
                 runner.reset()          # the video wraps: a scene cut
             nxt = (i + 1) % n_frames
-            runner.step(dev_video[f], next_frames=dev_video[nxt] if (args.lookahead and nxt != 0) else None)
+            runner.step(dev_video[f], force_full=force_full,
+                        next_frames=dev_video[nxt] if (args.lookahead and nxt != 0 and not force_full) else None)
             if collect is not None:
                 collect(i, f)
 
-    # ---- warm-up, then the timed region ----
-    run_steps(args.warmup, 0)
+    # ---- warm-up, then the timed region (K steps, `repeats` times; the median counts) ----
+    run_steps(warmup, 0)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(args.steps, args.warmup)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    fps = args.steps * n / elapsed
+    times = []
+    pos = warmup
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(steps, pos)
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
+        pos += steps
+    elapsed = statistics.median(times)
+    fps = steps * n / elapsed
 
-    # ---- same steps again with HIP-event brackets around every conv GEMM / copy launch ----
+    # ---- every frame in full (no cache): same number of steps, same repeats ----
+    run_steps(min(warmup, 5), 0, force_full=True)
+    times_full = []
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(steps, 0, force_full=True)
+        torch.cuda.synchronize()
+        times_full.append(time.perf_counter() - t0)
+    fps_full = steps * n / statistics.median(times_full)
+
+    out = {"value": fps, "ms_per_step": elapsed / steps * 1e3, "repeat_ms_per_step": [t / steps * 1e3 for t in times],
+           "no_cache": {"value": fps_full, "unit": "frames/s", "steps": steps, "repeats": repeats,
+                        "saving": 1.0 - fps_full / fps}}
+    if not detail:
+        del runner
+        return out
+
+    # ---- same steps again, one at a time, with HIP-event brackets around every conv GEMM / copy launch ----
     runner.enable_profile(True)
-    conv_ids = [i for i, L in enumerate(layers) if L["type"] == synth.CONV]
     shapes = runner.shapes
     per_kernel = {}      # kernel name -> [flops_alg, ms, launches, flops_issued]
-    copy_ms = copy_bytes = 0.0
-    copy_launches = 0
+    copy = dict(ms=0.0, bytes=0.0, launches=0)
     agg = dict(reuse=[], macs_full=0, macs_needed=0, macs_issued=0, cached_frames=0, full_frames=0)
 
     def collect(i, f):
         torch.cuda.synchronize()
-        st = runner.stats
+        st = runner.read_stats()
         ls = runner.layer_stats()
         agg["macs_full"] += st.macs_full
         agg["macs_needed"] += st.macs_needed
@@ -122,7 +150,6 @@ def main():
         else:
             agg["cached_frames"] += 1
             agg["reuse"].append(st.n_reusable_blocks / st.n_blocks)
-        nonlocal copy_ms, copy_bytes, copy_launches
         for li, (g_ms, c_ms) in runner.profile_ms().items():
             L = layers[li]
             ho, wo, co = shapes[li + 1]
@@ -136,38 +163,43 @@ def main():
                 rec[2] += 1
                 rec[3] += 2.0 * ls["issued_macs"][li]
             if c_ms is not None:
-                copy_ms += c_ms
-                copy_launches += 1
-        copy_bytes += st.copy_bytes
+                copy["ms"] += c_ms
+                copy["launches"] += 1
+        copy["bytes"] += st.copy_bytes
 
-    run_steps(args.steps, args.warmup + args.steps, collect)
+    k_prof = min(steps, 60)
+    run_steps(k_prof, 0, collect)
     runner.enable_profile(False)
 
-    dom = max(per_kernel.items(), key=lambda kv: kv[1][1])
-    dname, (dflops, dms, dlaunch, dissued) = dom
+    dname, (dflops, dms, dlaunch, dissued) = max(per_kernel.items(), key=lambda kv: kv[1][1])
     all_flops = sum(v[0] for v in per_kernel.values())
     all_ms = sum(v[1] for v in per_kernel.values())
-    peak = PEAK_TFLOPS[args.dtype]
+    peak = PEAK_TFLOPS[dtype]
+    table, scale = read_traffic_table(n, dtype)
+    traffic = None
+    if table and dname in table:
+        traffic = (table[dname][0] * scale[0] + table[dname][1] * scale[1]) * 1024.0
     roofline = {
         "bound": "mfma", "kernel": dname,
         "achieved": dflops / (dms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
-        "frac": dflops / (dms * 1e-3) / 1e12 / peak,
+        "frac": dflops / (dms * 1e-3) / 1e12 / peak, "target_frac": TARGET_CONV_FRAC if dtype == "bf16" else None,
         "avg_launch_us": dms / dlaunch * 1e3, "launches": dlaunch,
         "issued_tflops": dissued / (dms * 1e-3) / 1e12,
-        "traffic": (sum(c * f for c, f in zip(PMC_TRAFFIC[dname], PMC_SCALE)) * 1024.0
-                    if (args.dtype == "f32" and n == 1 and dname in PMC_TRAFFIC) else None),
-        "traffic_unit": "bytes of HBM traffic per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+        "traffic": traffic,
+        "traffic_note": "HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE summary under profiles/ "
+                        "(calibrated against a plain copy; a constant of that profile run, not measured in this run)",
         "all_conv": {"achieved": all_flops / (all_ms * 1e-3) / 1e12, "frac": all_flops / (all_ms * 1e-3) / 1e12 / peak,
-                     "ms_per_step": all_ms / args.steps},
-        "copy": {"bound": "hbm", "achieved": (copy_bytes / (copy_ms * 1e-3) / 1e9) if copy_ms else None,
-                 "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                 "frac": (copy_bytes / (copy_ms * 1e-3) / 1e9 / PEAK_HBM_GBS) if copy_ms else None,
-                 "avg_launch_us": (copy_ms / copy_launches * 1e3) if copy_launches else None},
+                     "ms_per_step": all_ms / k_prof},
+        "per_kernel": {k: {"frac": v[0] / (v[1] * 1e-3) / 1e12 / peak, "avg_launch_us": v[1] / v[2] * 1e3, "launches": v[2]}
+                       for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1][1])},
+        "copy": {"bound": "hbm", "achieved": (copy["bytes"] / (copy["ms"] * 1e-3) / 1e9) if copy["ms"] else None,
+                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "target_frac": TARGET_COPY_FRAC,
+                 "frac": (copy["bytes"] / (copy["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS) if copy["ms"] else None,
+                 "avg_launch_us": (copy["ms"] / copy["launches"] * 1e3) if copy["launches"] else None},
     }
 
     # ---- the matching alone (Steps 1-4), HIP events on the launch stream; allocations are outside the events ----
     torch.cuda.synchronize()
-    method = binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE
     mbs = synth.max_block_ssd(16, 3)
     for f in range(1, 4):
         binding.dc_match_blocks_opt(dev_video[f], dev_video[f - 1], 16, 16, mbs, method, args.k_skip)
@@ -186,62 +218,104 @@ def main():
     match_bytes = 2.0 * n * H * W * 3 + n * (H // 16) * (W // 16) * 13.0      # both frames once; mv, ssd, mask per block
     match_terms = float(n) * (H // 16) * (W // 16) * 16 * 16 * 3 * 33 * 33      # candidates inside the frame or not
     peak_terms = 256 * 64 * 2.4e9 * 4 / 1e12       # 256 CUs x 64 lanes x 2.4 GHz x 4 bytes per packed dot instruction
+    rate = None if args.matcher == "ds" else match_terms / (match_us * 1e-6) / 1e12
     roofline["match"] = {
         "bound": "alu", "avg_launch_us": match_us,
-        "achieved": None if args.matcher == "ds" else match_terms / (match_us * 1e-6) / 1e12, "peak": peak_terms,
-        "unit": "T squared differences/s",
-        "frac": None if args.matcher == "ds" else match_terms / (match_us * 1e-6) / 1e12 / peak_terms,
+        "achieved": rate, "peak": peak_terms, "unit": "T squared differences/s",
+        "frac": None if rate is None else rate / peak_terms,
+        "frac_of_int8_mfma_peak": None if rate is None else rate / (PEAK_INT8_TOPS / 2.0),
         "hbm_GBps": match_bytes / (match_us * 1e-6) / 1e9,
         "hbm_frac": match_bytes / (match_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
-        "note": "Steps 1-4 of the matching for all streams, alone on the GPU; the search is bound by integer arithmetic "
-                "and LDS traffic, not by HBM; peak = packed 8-bit dot products on the vector ALUs (the diamond "
-                "search evaluates a data-dependent number of candidates: no fixed term count)"}
-
-    # ---- frames computed in full every time (no cache) for the saving ----
-    torch.cuda.synchronize()
-    k_full = max(10, args.steps // 5)
-    t0 = time.perf_counter()
-    for i in range(k_full):
-        runner.step(dev_video[i % n_frames], force_full=True)
-    torch.cuda.synchronize()
-    fps_full = k_full * n / (time.perf_counter() - t0)
+        "note": "Steps 1-4 of the matching for all streams, alone on the GPU.  The search is bound by integer arithmetic "
+                "and LDS traffic, not by HBM.  `peak` = packed 8-bit dot products on the vector ALUs; the kernel runs its "
+                "cross terms on the int8 matrix cores, whose peak (5.0 POP/s = 2.5 P multiply-adds/s) gives "
+                "frac_of_int8_mfma_peak (the diamond search evaluates a data-dependent number of candidates: no rate)"}
 
     # ---- oracle on the host cores, bounded sample of the same workload ----
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import oracle as oc
-        ref = oc.Stream(layers, ws, bs, H, W, 3, block=16, radius=16, bf16=(args.dtype == "bf16"), expiry=args.expiry,
+        ref = oc.Stream(layers, ws, bs, H, W, 3, block=16, radius=16, bf16=(dtype == "bf16"), expiry=args.expiry,
                         diamond=(args.matcher == "ds"), k_skip=args.k_skip)
-        k_cpu = min(args.cpu_frames, n_frames)
+        k_cpu = min(cpu_frames, n_frames)
         t0 = time.perf_counter()
         for f in range(k_cpu):
             ref.step(videos[0, f])
         cpu_s = time.perf_counter() - t0
         n_cpu_full = len(range(0, k_cpu, args.expiry)) if args.expiry > 0 else 1
         cpu = {"value": k_cpu / cpu_s, "unit": "frames/s", "cores": oc.num_threads(), "kind": "oracle",
-               "sample": f"first {k_cpu} frames of stream 0 of the same video ({n_cpu_full} full + {k_cpu - n_cpu_full} cached), "
-                         f"{cpu_s:.1f} s"}
+               "sample": f"first {k_cpu} frames of stream 0 of the same videos ({n_cpu_full} full + {k_cpu - n_cpu_full} "
+                         f"cached), {cpu_s:.1f} s; the other {n - 1} streams are the same work per frame"}
 
     steps_all = agg["cached_frames"] + agg["full_frames"]
+    out.update({
+        "config_detail": {"mean_block_reuse": float(np.mean(agg["reuse"])) if agg["reuse"] else 0.0,
+                          "full_frame_fraction": agg["full_frames"] / max(steps_all, 1),
+                          "mac_fraction_needed": agg["macs_needed"] / max(agg["macs_full"], 1),
+                          "mac_fraction_issued": agg["macs_issued"] / max(agg["macs_full"], 1)},
+        "effective_tflops": 2.0 * agg["macs_full"] / max(steps_all, 1) * steps / elapsed / 1e12,
+        "roofline": roofline, "cpu_baseline": cpu})
+    del runner
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=120)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--repeats", type=int, default=5, help="timed regions of K steps; the median is reported")
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="bf16")
+    ap.add_argument("--streams", type=int, default=64)
+    ap.add_argument("--expiry", type=int, default=10, help="full recompute every N frames (Section 5 default 10)")
+    ap.add_argument("--matcher", choices=["es", "ds"], default="es",
+                    help="Step 2 of the matching: exhaustive search, or the diamond search of Section 4")
+    ap.add_argument("--k-skip", type=int, default=1, help="search every k-th block row and column only (Section 4)")
+    ap.add_argument("--lookahead", action="store_true",
+                    help="start the matching of the next frame at the end of a step (dc_prefetch_match), as a decoder "
+                         "one frame ahead would allow")
+    ap.add_argument("--host-plan", action="store_true",
+                    help="merge / propagate / list the dirty units on the host (one wait per frame) instead of on the GPU")
+    ap.add_argument("--no-single", action="store_true", help="skip the single-stream fp32 sub-record")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-frames", type=int, default=30)
+    ap.add_argument("--traffic-calib", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (streams are independent and would shard "
+              "across GPUs without communication); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    torch.cuda.set_device(torch.device("cuda:0"))
+    if args.traffic_calib:
+        traffic_calib()
+        return
+
+    n = args.streams
+    main_rec = run_workload(args, n, args.dtype, args.steps, args.warmup, args.repeats, True, args.cpu_frames)
+    single = None
+    if not args.no_single and not (n == 1 and args.dtype == "f32"):
+        # configs[1]: the small configuration (one fp32 stream), frames/s and saving only
+        single = run_workload(args, 1, "f32", 300, 30, args.repeats, False, 0)
+        single["config"] = {"workload": "configs[1]: one 30-frame 224x224x3 synthetic panning video, VGG-16-style stack, fp32",
+                            "streams": 1, "steps": 300}
+    which = "configs[4]: 64 streams" if n == 64 else ("configs[1]: one stream" if n == 1 else f"{n} streams")
+    detail = main_rec.pop("config_detail")
     out = {
         "metric": "frames/s cache-aware CNN at fixed reuse ratio + % of MFMA/HBM peak",
-        "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "value": main_rec.pop("value"), "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_rec.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "configs[1]: 30-frame 224x224x3 synthetic panning video, VGG-16-style 13-conv stack, "
-                               "16x16 blocks, search +/-16, tau=20",
+        "config": {"workload": f"{which} x 30-frame 224x224x3 synthetic panning videos (per-stream seeds), one batch per "
+                               "time step, VGG-16-style 13-conv stack, 16x16 blocks, search +/-16, tau=20",
                    "streams": n, "matcher": ("exhaustive search" if args.matcher == "es" else "diamond search") + f", k-skip {args.k_skip}",
-                   "cache_expiry_frames": args.expiry, "frames_per_video": n_frames,
-                   "lookahead_frames": 1 if args.lookahead else 0,
-                   "mean_block_reuse": float(np.mean(agg["reuse"])) if agg["reuse"] else 0.0,
-                   "full_frame_fraction": agg["full_frames"] / max(steps_all, 1),
-                   "mac_fraction_needed": agg["macs_needed"] / max(agg["macs_full"], 1),
-                   "mac_fraction_issued": agg["macs_issued"] / max(agg["macs_full"], 1)},
-        "effective_tflops": 2.0 * agg["macs_full"] / max(steps_all, 1) * args.steps / elapsed / 1e12,
-        "no_cache": {"value": fps_full, "unit": "frames/s", "saving": 1.0 - fps_full / fps},
-        "roofline": roofline,
-        "cpu_baseline": cpu,
+                   "cache_expiry_frames": args.expiry, "frames_per_video": 30, "repeats": args.repeats,
+                   "planning": "host" if args.host_plan else "device",
+                   "lookahead_frames": 1 if args.lookahead else 0, **detail},
     }
+    out.update(main_rec)
+    if single is not None:
+        out["single_stream_f32"] = single
     print(json.dumps(out))
 
 

@@ -113,6 +113,8 @@ typedef struct {
     int32_t full;               /* 1: every pixel was computed (no cache used) */
     int32_t n_blocks;           /* blocks in the grid, all streams */
     int32_t n_reusable_blocks;  /* blocks that passed Step 4 */
+    int32_t n_overflow_streams; /* streams one of whose rectangle lists exceeded max_rects: they reuse nothing in this
+                                   frame (every pixel computed, always valid), their lists are reported empty */
     int64_t macs_full;          /* conv multiply-adds of a full frame */
     int64_t macs_needed;        /* multiply-adds of the non-reusable output pixels */
     int64_t macs_issued;        /* multiply-adds of every pixel of every dirty tile (what ran) */
@@ -387,9 +389,11 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
  *                   the caller passes the same two sets in the same roles for the next frame
  *                   instead of swapping them.  The values are the same as without it.  Otherwise 0.
  *   mv .. block_mask  dev buffers as in dc_match_blocks (written unless force_full)
- *   max_rects       capacity of each per-tensor rectangle list
- *   regions_out     optional host [n_streams][n_layers+1] with caller-provided rect storage,
- *                   receives every tensor's regions (for inspection); may be NULL
+ *   max_rects       most rectangles a tensor's list may hold; a stream one of whose lists would be longer reuses
+ *                   nothing in this frame (every pixel of it is computed; counted in stats->n_overflow_streams)
+ *   regions_out     optional host [n_streams][n_layers+1] with caller-provided rect storage of at least
+ *                   max_rects entries each (DC_ERR_CAPACITY otherwise, before anything is launched); receives
+ *                   every tensor's regions (for inspection); may be NULL
  *   ws_dev, ws_host workspaces of at least dc_stack_workspace_bytes; ws_host should be pinned
  *   stats           optional host
  *   overlap         optional dc_overlap handle; with it the frames must be visible to any stream

@@ -36,6 +36,8 @@
  * pooling) are pinned by hand-computed values, the printed LRN row of Table 2
  * and brute-force window containment, pixel-wise AND for the concat row, and
  * the torch / scipy / numpy routines for the cases those implement.
+ * The element-wise add and ReLU are pinned by hand values (exact binary
+ * fractions, bf16 ties rounded once to even, negative zero) and numpy.
  * Unpinned by the paper (pinned only by hand cases of the stated reading):
  * the merge decomposition, the rounding of fractional motion, and the source
  * offset when the motion is not a multiple of the cumulative stride.

@@ -288,6 +288,13 @@ def add(a, b, relu, bf16=False):
     return out
 
 
+def relu(a):
+    a = np.ascontiguousarray(a, np.float32)
+    out = np.zeros_like(a)
+    lib().oc_relu(_p(a), a.size, _p(out))
+    return out
+
+
 class Stream:
     """One video stream through one stack: holds the previous frame (cache key) and
     the previous feature maps (cache values), Section 3."""

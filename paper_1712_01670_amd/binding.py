@@ -57,7 +57,7 @@ DC_MATCH_EXHAUSTIVE, DC_MATCH_DIAMOND = 0, 1
 
 class StackStats(C.Structure):
     _fields_ = [("full", C.c_int32), ("n_blocks", C.c_int32), ("n_reusable_blocks", C.c_int32),
-                ("macs_full", C.c_int64), ("macs_needed", C.c_int64), ("macs_issued", C.c_int64),
+                ("n_overflow_streams", C.c_int32), ("macs_full", C.c_int64), ("macs_needed", C.c_int64), ("macs_issued", C.c_int64),
                 ("copy_bytes", C.c_int64), ("layer_reused_px", C.POINTER(C.c_int64)),
                 ("layer_issued_macs", C.POINTER(C.c_int64)), ("layer_kernel_id", C.POINTER(C.c_int32)),
                 ("profile", C.c_void_p)]
@@ -400,7 +400,9 @@ class StackRunner:
     def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
                  want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True,
-                 match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False, extend_borders=False):
+                 match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False, extend_borders=False, device_plan=False):
+        if device_plan:
+            raise NotImplementedError("device-side planning")
         self.in_place = bool(in_place)
         self.last_in_place = False
         self._in_place_flag = C.c_int32(0)
@@ -514,6 +516,9 @@ class StackRunner:
         self.prev_frames = frames
         self.last_full = full
         self.last_in_place = self.in_place and self._in_place_flag.value != 0
+        self.cur_other = 1 - cn
+        if not self.last_in_place:      # (an in-place frame updated the conv outputs in the previous frame's buffers)
+            self.cur = p
         if next_frames is not None and self.overlap and not (self.expiry > 0 and self.age >= self.expiry):
             assert next_frames.is_cuda and next_frames.dtype == torch.uint8 and next_frames.is_contiguous()
             assert tuple(next_frames.shape) == (self.n, self.H, self.W, self.Ch)
@@ -521,11 +526,13 @@ class StackRunner:
                 self.overlap, _ptr(next_frames), _ptr(frames), self.n, self.H, self.W, self.Ch, self.block, self.radius,
                 self.max_block_ssd, C.byref(self.match_options), _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv),
                 _ptr(self.n_pass), _ptr(self.mask), C.c_void_p(self.ws_host.data_ptr()), self.ws_host.numel()))
-        self.cur_other = 1 - cn
-        if self.last_in_place:      # the conv outputs were updated in the previous frame's buffers: no swap of those
+        if self.last_in_place:
             return [self.bufs[p if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]
-        self.cur = p
         return [self.bufs[c if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]
+
+    def read_stats(self):
+        """Work counters of the last step (call after the stream has been synchronised)."""
+        return self.stats
 
     def enable_profile(self, on=True):
         """Attach (or detach) HIP-event brackets around every conv GEMM and copy launch."""

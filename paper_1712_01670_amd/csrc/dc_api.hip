@@ -96,11 +96,14 @@ int check_conv_layer(const dc_layer* l) {
 }
 
 // Waits for an event by polling: the host thread is needed again within tens of microseconds, which a
-// blocking wait's wake-up latency would double.
+// blocking wait's wake-up latency would double.  After 2 ms of polling it blocks instead.
 hipError_t spin_wait(hipEvent_t e) {
-    for (;;) {
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int i = 0;; ++i) {
         const hipError_t q = hipEventQuery(e);
         if (q != hipErrorNotReady) return q;
+        if ((i & 63) == 63 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(2))
+            return hipEventSynchronize(e);
     }
 }
 
@@ -113,11 +116,9 @@ __global__ void __launch_bounds__(256) upload_kernel(const uint4* __restrict__ s
         dst[i] = src[i];
 }
 
-// Device address of a host buffer: nullptr if it is not pinned, or with DC_UPLOAD_KERNEL=0.  Asked on every
-// call: a caller may free a pinned buffer and pass pageable memory at the same address later.
+// Device address of a host buffer: nullptr if it is not pinned.  Asked on every call: a caller may free a
+// pinned buffer and pass pageable memory at the same address later.
 const unsigned char* device_alias(void* host) {
-    static const bool enabled = [] { const char* e = getenv("DC_UPLOAD_KERNEL"); return !(e && atoi(e) == 0); }();
-    if (!enabled) return nullptr;
     void* d = nullptr;
     if (hipHostGetDevicePointer(&d, host, 0) != hipSuccess) { d = nullptr; (void)hipGetLastError(); }
     return static_cast<const unsigned char*>(d);
@@ -282,7 +283,8 @@ int32_t dc_prefetch_match(void* overlap, const uint8_t* frames_next, const uint8
                           int16_t* mv, uint32_t* best_ssd, int32_t* global_mv, int32_t* n_pass,
                           uint8_t* block_mask, void* ws_host, size_t ws_host_bytes) {
     if (!overlap || !frames_next || !frames_cur || !global_mv || !block_mask || !ws_host) return DC_ERR_NULL_PTR;
-    if (n_streams < 1 || H < 1 || W < 1 || C < 1 || block < 1 || H % block || W % block) return DC_ERR_INVALID_ARG;
+    if (n_streams < 1 || H < 1 || W < 1 || C < 1 || block < 1) return DC_ERR_INVALID_ARG;
+    if (block > H || block > W) return DC_ERR_BAD_SHAPE;
     Overlap* ov = static_cast<Overlap*>(overlap);
     const size_t nb = (size_t)n_streams * (H / block) * (W / block);
     if (ws_host_bytes < align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256)) return DC_ERR_WORKSPACE;
@@ -709,30 +711,6 @@ struct FramePlan {
 FramePlan g_frame_plan;
 std::mutex g_frame_plan_mutex;
 
-// DC_HOST_TIMING=1: host time of a cached dc_run_stack call by phase, printed every 200 calls (experiments).
-struct HostTiming {
-    bool on = false;
-    double acc[7] = {0, 0, 0, 0, 0, 0, 0};
-    long calls = 0;
-    std::chrono::steady_clock::time_point last;
-    HostTiming() { const char* e = getenv("DC_HOST_TIMING"); on = e && atoi(e) != 0; }
-    void start() { if (on) last = std::chrono::steady_clock::now(); }
-    void mark(int phase) {
-        if (!on) return;
-        const auto now = std::chrono::steady_clock::now();
-        acc[phase] += std::chrono::duration<double, std::micro>(now - last).count();
-        last = now;
-    }
-    void end_call() {
-        if (!on || ++calls % 200) return;
-        fprintf(stderr, "[dc_run_stack host us/call] launch match %.1f | wait match %.1f | merge+propagate %.1f | "
-                        "wait for the staging half (GPU two frames back) %.1f | plans %.1f | copy tables+upload %.1f | "
-                        "layer launches %.1f\n",
-                acc[0] / 200, acc[1] / 200, acc[2] / 200, acc[6] / 200, acc[3] / 200, acc[4] / 200, acc[5] / 200);
-        for (double& a : acc) a = 0;
-    }
-};
-HostTiming g_host_timing;
 }  // namespace
 
 int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const* weights,
@@ -773,6 +751,9 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         if (rc) return rc;
         if (ws_dev_bytes < need_dev || ws_host_bytes < need_host) return DC_ERR_WORKSPACE;
     }
+    if (regions_out)      // checked before anything is launched: every list fits
+        for (size_t i = 0; i < (size_t)n_streams * (n_layers + 1); ++i)
+            if (regions_out[i].capacity < max_rects || !regions_out[i].rects) return DC_ERR_CAPACITY;
     Overlap* ov = static_cast<Overlap*>(overlap);
     hipStream_t caller_st = as_stream(stream);
     // a look-ahead match is for the very next call only (the caller may reuse its frame buffers after that)
@@ -881,7 +862,6 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     std::vector<std::vector<TensorRegions>> regs;  // [stream][tensor]
     unsigned char* hbase = static_cast<unsigned char*>(ws_host);
     if (cached) {
-        g_host_timing.start();
         // With an overlap handle the matching runs on its own stream, next to whatever the main stream
         // still holds of the previous frame; only that stream is waited for.
         hipStream_t mst = ov ? ov->aux : st;
@@ -908,14 +888,12 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         // the network input does not depend on the match: its conversion overlaps the readback
         DC_TRY_HIP(wait_readers(0));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
-        g_host_timing.mark(0);
         if (ov) {
             if (!prefetched) DC_TRY_HIP(hipEventRecord(ov->match_done, mst));
             DC_TRY_HIP(spin_wait(ov->match_done));
         } else {
             DC_TRY_HIP(hipStreamSynchronize(mst));
         }
-        g_host_timing.mark(1);
         if (in_place) {     // no stream moved: the previous frame's conv outputs can be updated where they are
             inplace = true;
             for (int s = 0; s < n_streams; ++s) inplace = inplace && h_gmv[2 * s] == 0 && h_gmv[2 * s + 1] == 0;
@@ -926,7 +904,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             return DC_ERR_WORKSPACE;
         }
         {   // per stream: count, merge (Step 5), propagate (Section 5); streams are independent
-            std::vector<int> stream_rc(n_streams, DC_OK), stream_reusable(n_streams, 0);
+            std::vector<int> stream_rc(n_streams, DC_OK), stream_reusable(n_streams, 0), stream_over(n_streams, 0);
             parallel_for(n_streams, [&](int s) {
                 try {
                     std::vector<dc_rect> rects0;
@@ -937,8 +915,13 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                     merge_blocks(m, gh, gw, block, rects0);
                     int r = propagate(layers, n_layers, H, W, rects0, h_gmv[2 * s], h_gmv[2 * s + 1], regs[s],
                                       match_options && match_options->extend_borders != 0);
-                    for (int t = 0; r == DC_OK && t <= n_layers; ++t)
-                        if ((int)regs[s][t].rects.size() > max_rects) r = DC_ERR_CAPACITY;
+                    // a list longer than the caller allows: the stream reuses nothing in this frame (always valid)
+                    bool over = false;
+                    for (int t = 0; r == DC_OK && t <= n_layers; ++t) over = over || (int)regs[s][t].rects.size() > max_rects;
+                    if (over) {
+                        for (int t = 0; t <= n_layers; ++t) regs[s][t].rects.clear();
+                        stream_over[s] = 1;
+                    }
                     stream_rc[s] = r;
                 } catch (const std::bad_alloc&) {
                     stream_rc[s] = DC_ERR_WORKSPACE;
@@ -947,9 +930,9 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             for (int s = 0; s < n_streams; ++s) {
                 if (stream_rc[s]) return stream_rc[s];
                 local.n_reusable_blocks += stream_reusable[s];
+                local.n_overflow_streams += stream_over[s];
             }
         }
-        g_host_timing.mark(2);
         hbase += align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
         if (ov) {
             // two staging halves: the upload of the frame before last must have left the half reused now
@@ -960,27 +943,22 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 ov->pending[ov->parity] = false;
             }
         }
-        g_host_timing.mark(6);
     } else {
         DC_TRY_HIP(wait_readers(0));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
     }
     if (regions_out) {
-        int status = DC_OK;
         for (int s = 0; s < n_streams; ++s)
             for (int t = 0; t <= n_layers; ++t) {
                 dc_regions& r = regions_out[(size_t)s * (n_layers + 1) + t];
                 if (cached) {
                     const TensorRegions& g = regs[s][t];
                     r.n = (int)g.rects.size(); r.dx = g.dx; r.dy = g.dy; r.cum_stride = g.cum_stride; r.h = g.h; r.w = g.w;
-                    int keep = r.n < r.capacity ? r.n : r.capacity;
-                    if (keep && r.rects) std::memcpy(r.rects, g.rects.data(), keep * sizeof(dc_rect));
-                    if (r.n > r.capacity) status = DC_ERR_CAPACITY;
+                    if (r.n) std::memcpy(r.rects, g.rects.data(), r.n * sizeof(dc_rect));     // n <= max_rects <= capacity
                 } else {
                     r.n = 0; r.dx = r.dy = 0; r.cum_stride = 0; r.h = hs[t]; r.w = ws[t];
                 }
             }
-        if (status) return status;
     }
 
     // ---- plans of all conv layers, one upload ----
@@ -1030,7 +1008,6 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         return DC_ERR_WORKSPACE;
     }
     if (cached) frame_plan.copy_tiles();
-    if (cached) g_host_timing.mark(3);
     // ---- the shifted copies of all layers in one launch (16-byte vector path only); pipelined: one launch per
     // run of consecutive conv layers, issued when the previous frame has finished that run ----
     std::vector<char> copy_fused(n_layers, 0);
@@ -1098,8 +1075,6 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                                            reinterpret_cast<const CopyLayerDev*>(plan_dev + copy_layers_off), g.max_vec, st));
         return DC_OK;
     };
-
-    if (cached) g_host_timing.mark(4);
     // Where each tensor of this frame lives: an in-place frame keeps the conv outputs in the previous frame's buffers.
     std::vector<void*> eff(n_layers + 1);
     for (int t = 0; t <= n_layers; ++t)
@@ -1181,7 +1156,6 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         DC_TRY_HIP(hipStreamWaitEvent(caller_st, ov->frame_done[fp], 0));
         ov->frame_parity ^= 1;
     }
-    if (cached) { g_host_timing.mark(5); g_host_timing.end_call(); }
     if (stats) *stats = local;
     return DC_OK;
 }

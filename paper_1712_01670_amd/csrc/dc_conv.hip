@@ -408,7 +408,6 @@ struct KernelEntry { KernelFn fn[2][4]; };
 const KernelEntry kTable[kNumShapes] = {DC_ENTRY(0), DC_ENTRY(1), DC_ENTRY(2), DC_ENTRY(3)};
 
 struct Choice { int shape, kci, kc, tg, pv, wv, patch_bytes, weight_bytes, dump_off; size_t lds; bool ok; int p_instr, w_instr; };
-bool tune_override(int& kci, int& tg);
 
 size_t reduce_bytes(const Shape& S) {
     return (size_t)(S.wk - 1) * S.wm * S.wn * (S.g / S.wm) * (S.nt / S.wn / 16) * 64 * 16;
@@ -467,8 +466,6 @@ Choice choose_direct_from(int shape, const ConvLaunch& c, int ph, int pw, bool f
 // 15-25 % faster: one kernel row of taps per stage where at most two wavefronts share a stage's K, about a
 // dozen taps where four do.  `wgs` is the number of workgroups the launch would have with this shape.
 Choice choose_direct(int shape, const ConvLaunch& c, int ph, int pw, long wgs) {
-    int f_kci = -1, f_tg = 0;
-    if (tune_override(f_kci, f_tg)) return choose_direct_from(shape, c, ph, pw, true, f_kci, f_tg);
     const int kk = c.k * c.k;
     if (wgs >= 384 && c.k > 1) {
         int tg = c.k;
@@ -504,18 +501,6 @@ Choice choose_staged(int shape, const ConvLaunch& c, int ph, int pw) {
     ch.weight_bytes = (int)(body_of(tg) - patch_bytes); ch.dump_off = dump_off;
     ch.lds = kHeaderBytes + body; ch.ok = ch.lds <= 150 * 1024;
     return ch;
-}
-
-// Optional override for experiments: DC_CONV_TUNE="kci,tg" forces the channel-chunk index and the
-// taps per stage of the direct kernel (ignored when the combination does not fit).
-bool tune_override(int& kci, int& tg) {
-    static int cached = -1, o_kci = 0, o_tg = 0;
-    if (cached < 0) {
-        const char* e = getenv("DC_CONV_TUNE");
-        cached = (e && sscanf(e, "%d,%d", &o_kci, &o_tg) == 2) ? 1 : 0;
-    }
-    if (cached == 1) { kci = o_kci; tg = o_tg; }
-    return cached == 1;
 }
 
 uint32_t magic_of(int d) { return (uint32_t)((0x100000000ull + (uint64_t)d - 1) / (uint64_t)d); }
@@ -554,13 +539,7 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     // smaller shapes split K among the wavefronts instead.
     int shape, g_rt;
     {
-        static int t1 = -1, xl_min = -1;
-        if (t1 < 0) {
-            const char* e1 = getenv("DC_CONV_T1");
-            const char* e2 = getenv("DC_CONV_XLMIN");
-            t1 = e1 ? atoi(e1) : 160;
-            xl_min = e2 ? atoi(e2) : 8;
-        }
+        constexpr int t1 = 160, xl_min = 8;
         const long r64 = (c.Cout + 63) / 64, r32 = (c.Cout + 31) / 32;
         const long rounds = (n_units * r64 + 256 * 16 - 1) / (256 * 16);
         const long g = (n_units * r64 + 256 * rounds - 1) / (256 * rounds);
@@ -617,13 +596,6 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     const long groups = (n_units + g_rt - 1) / g_rt;
     const long wgs = groups * P.R;
     if (wgs > 2147483647L) return hipErrorInvalidValue;
-    {   // DC_CONV_TRACE=1: one line per launch on stderr with the configuration chosen
-        static int trace = -1;
-        if (trace < 0) { const char* e = getenv("DC_CONV_TRACE"); trace = (e && atoi(e) > 0) ? 1 : 0; }
-        if (trace)
-            fprintf(stderr, "dc_conv: %dx%d %d->%d k%d s%d units %ld: shape %d g %d kc %d tg %d lds %zu wgs %ld\n",
-                    c.Hin, c.Win, c.Cin, c.Cout, c.k, c.s, n_units, ch.shape, g_rt, ch.kc, ch.tg, ch.lds, wgs);
-    }
     hipLaunchKernelGGL(fn, dim3((unsigned)wgs), dim3(S.wm * S.wn * S.wk * 64), ch.lds, st, P);
     return hipGetLastError();
 }

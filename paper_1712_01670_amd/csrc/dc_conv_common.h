@@ -21,6 +21,7 @@ constexpr int kMaxK = 15;              // largest kernel edge
 constexpr int kHeaderBytes = 1024;     // unit info and reuse mask at the start of LDS
 constexpr uint32_t kOob = 0x80000000u; // byte offset beyond any tensor: buffer loads return zero
 constexpr int kBufferFlags = 0x00020000;
+constexpr int kMaxLdsBytes = 160 * 1024;   // LDS of one CU: the most a workgroup can ask for
 
 struct ConvParams {
     const void* in;

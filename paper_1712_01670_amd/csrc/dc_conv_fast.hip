@@ -29,7 +29,9 @@
 // share of the weights, which is what bounds these layers.
 #include <algorithm>
 #include <cstdio>
+#include <atomic>
 #include <cstdlib>
+#include <mutex>
 #include <type_traits>
 
 #include "dc_conv_common.h"
@@ -972,11 +974,11 @@ inline int geom_nt(int geom) { return kGeom[geom].wn * kGeom[geom].nbw * 16; }
 template <typename T, int KC, int U, int WM, int WN, int NBW>
 hipError_t fast_launch_one(dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
     auto fn = conv_fast_kernel<T, 3, KC, U, WM, WN, NBW>;
-    static size_t allowed = 64 * 1024;      // per instantiation: the attribute is raised once, not per launch
-    if (lds > allowed) {
-        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static std::atomic<bool> raised{false};   // per instantiation: the attribute is raised once, to the CU's whole LDS
+    if (lds > 64 * 1024 && !raised.load()) {
+        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (a != hipSuccess) return a;
-        allowed = lds;
+        raised.store(true);
     }
     hipLaunchKernelGGL((conv_fast_kernel<T, 3, KC, U, WM, WN, NBW>), grid, dim3(WM * WN * 64), lds, st, P);
     return hipGetLastError();
@@ -1029,16 +1031,14 @@ size_t fast_lds_bytes(int geom, int kci, int upw) {
 
 struct FastChoice { int g, ks, kci; double cost; int geom; };
 
-// Overrides of the launch model (tests and experiments): arrangement, units per workgroup, K split,
-// channel chunk index; -1 = chosen by the model.  Initialised from DC_CONV_GEOM / DC_CONV_FORCE="g,ks,kci".
-int g_tune[4] = {-2, -1, -1, -1};
-void init_tuning() {
-    if (g_tune[0] != -2) return;
-    int geom = -1, g = -1, ks = -1, kci = -1;
-    if (const char* e = getenv("DC_CONV_GEOM")) geom = atoi(e);
-    if (const char* e = getenv("DC_CONV_FORCE")) sscanf(e, "%d,%d,%d", &g, &ks, &kci);
-    g_tune[1] = g > 0 ? g : -1; g_tune[2] = ks > 0 ? ks : -1; g_tune[3] = kci >= 0 ? kci : -1;
-    g_tune[0] = geom >= 0 ? geom : -1;
+// Overrides of the launch model (dc_conv_tuning: tests and experiments): arrangement, units per workgroup,
+// K split, channel chunk index; -1 = chosen by the model.  Process-wide; readers take a snapshot under the mutex.
+struct Tuning { int v[4]; };
+std::mutex g_tune_mutex;
+Tuning g_tune_shared{{-1, -1, -1, -1}};
+Tuning tuning_snapshot() {
+    std::lock_guard<std::mutex> g(g_tune_mutex);
+    return g_tune_shared;
 }
 
 // Cycle model of one launch.  A workgroup spends its stages (the longer of the MFMA time and the time to
@@ -1046,18 +1046,12 @@ void init_tuning() {
 // first loads, epilogue).  A CU runs ceil(workgroups / 256) of them; as many as LDS and registers allow
 // are resident together, and only the stage work of resident workgroups adds up, the fixed costs overlap.
 // ks > 1 adds the reduction kernel.
-FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes) {
-    static double bw = -1, stage_fix = 0, wg_fix = 0, red_fix = 0, occ1_penalty = 1.08, lds_cap_kb = 160;
-    if (bw < 0) {
-        const char* e = getenv("DC_CONV_MODEL");   // "bytes/clk/CU,stage,wg,reduce,penalty" (experiments)
-        bw = 32; stage_fix = 250; wg_fix = 4500; red_fix = 13000;
-        if (e) sscanf(e, "%lf,%lf,%lf,%lf,%lf,%lf", &bw, &stage_fix, &wg_fix, &red_fix, &occ1_penalty, &lds_cap_kb);
-    }
+FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes, int force_geom) {
+    // bytes per clock and CU from L2 to LDS, fixed cycles per stage / workgroup / reduction launch (fitted to sweeps)
+    constexpr double bw = 32, stage_fix = 250, wg_fix = 4500, red_fix = 13000, occ1_penalty = 1.08, lds_cap_kb = 160;
     const bool bf16 = c.dtype == DC_BF16;
     const int esz = bf16 ? 2 : 4, kg = bf16 ? 32 : 16;
     FastChoice best{0, 0, 0, 1e300, 0};
-    init_tuning();
-    const int force_geom = g_tune[0];
     for (int geom = 0; geom < kNumGeom; ++geom) {
         const Geom& G = kGeom[geom];
         const int nt = geom_nt(geom);
@@ -1149,8 +1143,8 @@ void conv_fast_kernel_name(int id, char* buf, size_t n) {
 }
 
 void conv_set_tuning(int geom, int g, int ks, int kci) {
-    init_tuning();
-    g_tune[0] = geom >= 0 ? geom : -1; g_tune[1] = g > 0 ? g : -1; g_tune[2] = ks > 0 ? ks : -1; g_tune[3] = kci >= 0 ? kci : -1;
+    std::lock_guard<std::mutex> guard(g_tune_mutex);
+    g_tune_shared = Tuning{{geom >= 0 ? geom : -1, g > 0 ? g : -1, ks > 0 ? ks : -1, kci >= 0 ? kci : -1}};
 }
 
 size_t packed_weights_bytes(int k, int s, int cin, int cout, int dtype) {
@@ -1170,12 +1164,12 @@ hipError_t launch_pack_weights(const void* w, void* packed, int cin, int cout, i
 template <int WM, int UPW>
 hipError_t regw_launch(dim3 grid, hipStream_t st, const ConvParams& P) {
     const size_t lds = 2 * (size_t)(WM * UPW) * 48 * 128;
-    static size_t allowed = 64 * 1024;
-    if (lds > allowed) {
+    static std::atomic<bool> raised{false};
+    if (lds > 64 * 1024 && !raised.load()) {
         hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_regw_kernel<WM, UPW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (a != hipSuccess) return a;
-        allowed = lds;
+        raised.store(true);
     }
     hipLaunchKernelGGL((conv_regw_kernel<WM, UPW>), grid, dim3(WM * 128), lds, st, P);
     return hipGetLastError();
@@ -1184,13 +1178,12 @@ hipError_t regw_launch(dim3 grid, hipStream_t st, const ConvParams& P) {
 // Launches the layer with the kernel of this file if its shape qualifies; returns false otherwise.
 template <typename T, int WM>
 hipError_t pw_launch_n(dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
-    static size_t allowed = 64 * 1024;
-    if (lds > allowed) {
-        const size_t most = kHeaderBytes + 4 * (size_t)(WM * 8192);
+    static std::atomic<bool> raised{false};
+    if (lds > 64 * 1024 && !raised.load()) {
         hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_pw_kernel<T, WM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (a != hipSuccess) return a;
-        allowed = most;
+        raised.store(true);
     }
     hipLaunchKernelGGL((conv_pw_kernel<T, WM>), grid, dim3(WM * 128), lds, st, P);
     return hipGetLastError();
@@ -1200,10 +1193,10 @@ hipError_t pw_launch(int wm, dim3 grid, size_t lds, hipStream_t st, const ConvPa
     return wm == 4 ? pw_launch_n<T, 4>(grid, lds, st, P) : pw_launch_n<T, 2>(grid, lds, st, P);
 }
 bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err) {
-    static int enabled = -1;
-    static int g_stem_wgs = -1;
-    if (g_stem_wgs < 0) { const char* e = getenv("DC_CONV_STEM_WGS"); g_stem_wgs = e && atoi(e) > 0 ? atoi(e) : 256; }
-    if (enabled < 0) { const char* e = getenv("DC_CONV_FAST"); enabled = e ? atoi(e) : 1; }
+    constexpr bool enabled = true;
+    constexpr int g_stem_wgs = 256;      // persistent workgroups of the 7x7 / 11x11 first-layer kernels
+    const Tuning tune = tuning_snapshot();
+    const int* g_tune = tune.v;
     const size_t esz = dtype_size(c.dtype);
     if (enabled && ((c.k == 3 && c.s == 1) || (c.k == 7 && c.s == 2) || (c.k == 11 && c.s == 4)) && c.Cin * esz == 16 && c.Cout % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
@@ -1239,11 +1232,9 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     if (enabled && c.k == 1 && c.p == 0 && (c.s == 1 || c.s == 2) && (c.Cin * esz) % 16 == 0 && c.Cout % 8 == 0 &&
         reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
-        static int pw_enabled = -1;
-        if (pw_enabled < 0) { const char* e = getenv("DC_CONV_PW"); pw_enabled = e ? atoi(e) : 1; }
+        constexpr bool pw_enabled = true;
         const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
         // Tile: 4 units x 64 channels; with enough of those to give every CU several, 8 units x 128 channels
-        init_tuning();
         const long small_tiles = (n_units + 3) / 4 * ((c.Cout + 63) / 64);
         const int wm = g_tune[1] == 8 ? 4 : (g_tune[1] == 4 ? 2 : (small_tiles >= 4096 && c.Cout >= 128 ? 4 : 2));
         const int g_units = 2 * wm, nt = 32 * wm;
@@ -1283,7 +1274,6 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         if ((double)c.n_streams * c.Hout * c.Wout * c.Cout >= 2147483648.0 || (double)n_units * units_map >= 4294967296.0)
             return false;
     }
-    init_tuning();
     // 64 input channels in bf16 and enough units to keep persistent workgroups busy: the weights go to registers
     if (c.dtype == DC_BF16 && c.Cin == 64 && c.relu != 2 && (g_tune[0] == 3 || (g_tune[0] < 0 && g_tune[1] < 0 && n_units >= 4096))) {
         ConvParams P{};
@@ -1312,15 +1302,19 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     // recently seen unit count, so its answers are kept in a small direct-mapped table.
     struct Memo { int dtype, cin, cout, tune[4]; long n_units; size_t scratch; FastChoice ch; bool used; };
     static Memo memo[256];
-    Memo& slot = memo[((unsigned long)n_units * 2654435761ul + (unsigned)c.Cin * 40503u + (unsigned)c.Cout * 97u + (unsigned)c.dtype) % 256];
+    static std::mutex memo_mutex;
     FastChoice ch;
-    if (slot.used && slot.dtype == c.dtype && slot.cin == c.Cin && slot.cout == c.Cout && slot.n_units == n_units &&
-        slot.scratch == scratch && slot.tune[0] == g_tune[0] && slot.tune[1] == g_tune[1] && slot.tune[2] == g_tune[2] &&
-        slot.tune[3] == g_tune[3]) {
-        ch = slot.ch;
-    } else {
-        ch = choose_fast(c, n_units, scratch);
-        slot = Memo{c.dtype, c.Cin, c.Cout, {g_tune[0], g_tune[1], g_tune[2], g_tune[3]}, n_units, scratch, ch, true};
+    {
+        std::lock_guard<std::mutex> guard(memo_mutex);
+        Memo& slot = memo[((unsigned long)n_units * 2654435761ul + (unsigned)c.Cin * 40503u + (unsigned)c.Cout * 97u + (unsigned)c.dtype) % 256];
+        if (slot.used && slot.dtype == c.dtype && slot.cin == c.Cin && slot.cout == c.Cout && slot.n_units == n_units &&
+            slot.scratch == scratch && slot.tune[0] == g_tune[0] && slot.tune[1] == g_tune[1] && slot.tune[2] == g_tune[2] &&
+            slot.tune[3] == g_tune[3]) {
+            ch = slot.ch;
+        } else {
+            ch = choose_fast(c, n_units, scratch, g_tune[0]);
+            slot = Memo{c.dtype, c.Cin, c.Cout, {g_tune[0], g_tune[1], g_tune[2], g_tune[3]}, n_units, scratch, ch, true};
+        }
     }
     if (g_tune[1] > 0 && ch.g > 0) {    // forced shape within the arrangement the model picked
         const int f_g = g_tune[1], f_ks = g_tune[2], f_kci = g_tune[3] < 0 ? ch.kci : g_tune[3];
@@ -1336,13 +1330,6 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         }
     }
     if (ch.g < 1) return false;
-    {
-        static int debug = -1;
-        if (debug < 0) { const char* e = getenv("DC_CONV_DEBUG"); debug = e ? atoi(e) : 0; }
-        if (debug)
-            fprintf(stderr, "[conv_fast] units=%ld %dx%d cin=%d cout=%d -> %s g=%d ks=%d kci=%d model=%.0f cycles\n", n_units,
-                    c.Hout, c.Wout, c.Cin, c.Cout, ch.geom == 0 ? "narrow" : (ch.geom == 1 ? "wide" : "wide64"), ch.g, ch.ks, ch.kci, ch.cost);
-    }
     const int upw = (ch.g + kGeom[ch.geom].wm - 1) / kGeom[ch.geom].wm;
     const int kc = (c.dtype == DC_BF16 ? 32 : 16) << ch.kci;
     const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;

@@ -716,8 +716,7 @@ hipError_t launch_match(const uint8_t* cur, const uint8_t* prev, int n_streams, 
     const int rows = B + 2 * R;
     const bool aligned = ((reinterpret_cast<uintptr_t>(prev) & 3) == 0) && ((W * C) % 4 == 0);
     dim3 grid(((gw + k_skip - 1) / k_skip) * ((gh + k_skip - 1) / k_skip), n_streams);   // the searched blocks
-    static int use_mfma = -1;
-    if (use_mfma < 0) { const char* e = getenv("DC_MATCH_MFMA"); use_mfma = e ? atoi(e) : 1; }
+    constexpr bool use_mfma = true;
     const int nt = (2 * R + 1 + 15) / 16, ksteps = (B * C + 63) / 64;
     bool done = false;
     if (use_mfma && nt <= 3 && ksteps <= 2 && B + 2 * R <= 255) {

@@ -80,11 +80,11 @@ void merge_blocks(const uint8_t* mask, int gh, int gw, int B, std::vector<dc_rec
 }
 
 int concat_inputs(const dc_layer& l, int* ids) {
-    int n = 0;
-    ids[n++] = l.in0;
-    ids[n++] = l.in1;
-    if (l.in2 >= 0) ids[n++] = l.in2;
-    if (l.in2 >= 0 && l.in3 >= 0) ids[n++] = l.in3;
+    // the first two producers always exist; the list ends at the first absent one after them
+    const int32_t all[4] = {l.in0, l.in1, l.in2, l.in3};
+    int n = 2;
+    while (n < 4 && all[n] >= 0) ++n;
+    std::copy(all, all + n, ids);
     return n;
 }
 

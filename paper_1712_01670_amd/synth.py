@@ -406,19 +406,81 @@ def panning_video(seed, n_frames=30, H=224, W=224, fg=((48, 48), (32, 64)),
     return frames
 
 
+def _sweep_dirty_fraction(boxes, pan, H, W, block, frames):
+    """Share of blocks that a foreground box touches in a frame or whose counterpart one frame earlier (the block
+    moved back along the pan) was touched or lay outside the frame, averaged over `frames` (index >= 1).  Geometry
+    only: it sizes the foreground, the matcher is not involved."""
+    gh, gw = H // block, W // block
+    by, bx = np.mgrid[0:gh, 0:gw]
+    x0, y0 = bx * block, by * block
+
+    def touched(f, xa, ya):       # blocks [xa, xa+block) x [ya, ya+block) that meet a box of frame f
+        hit = (xa < 0) | (ya < 0) | (xa + block > W) | (ya + block > H)
+        for (x, y, w, h) in boxes[f]:
+            hit |= (xa < x + w) & (xa + block > x) & (ya < y + h) & (ya + block > y)
+        return hit
+    tot = 0.0
+    for f in frames:
+        tot += float((touched(f, x0, y0) | touched(f - 1, x0 + pan[0], y0 + pan[1])).mean())
+    return tot / max(len(frames), 1)
+
+
 def reuse_sweep_video(seed, target_reuse, n_frames=60, H=416, W=416, block=16,
-                      pan=(2, 0), cut_at=30):
-    """Background panning `pan` px/frame with a band of fresh noise redrawn every
-    frame whose height (in whole block rows) sets the non-reusable fraction to
-    about 1 - target_reuse; a new background (scene cut) starts at frame `cut_at`.
+                      pan=(2, 0), cut_at=30, fg_speeds=(4, 5, 6)):
+    """The reuse-ratio sweep: a value-noise background panning `pan` px/frame under moving noise rectangles
+    (their texture is drawn afresh every frame, so they never match; they move `fg_speeds` px/frame and bounce at the
+    edges), a new background (scene cut) at frame `cut_at`.  The rectangles' sizes are scaled so that the share
+    of blocks they spoil (touched now, or touched one frame ago where the block came from) leaves about
+    `target_reuse` of the blocks reusable; the column of blocks that enters the frame caps the ratio near
+    1 - block/W per panned block column.  target_reuse <= 0: every frame is fresh noise.
 
     Returns uint8 [n_frames][H][W][3]."""
     rng = np.random.default_rng(seed)
     margin = abs(pan[0]) * n_frames + abs(pan[1]) * n_frames + 8
     size = ((max(H, W) + 2 * margin + 63) // 64) * 64
-    gh = H // block
-    dirty_rows = int(round((1.0 - target_reuse) * gh))
     frames = np.empty((n_frames, H, W, 3), dtype=np.uint8)
+    if target_reuse <= 0.0:
+        for f in range(n_frames):
+            frames[f] = rng.integers(0, 256, size=(H, W, 3), dtype=np.int64).astype(np.uint8)
+        return frames
+    # trajectories of the rectangles' centres and their base sizes (fractions of the frame edge)
+    n_box = 12
+    base = rng.uniform(0.10, 0.30, size=(n_box, 2))
+    centre = rng.uniform(0.2, 0.8, size=(n_box, 2)) * (W, H)
+    vel = np.array([np.array(_DIRS[int(rng.integers(0, 8))]) * int(rng.choice(fg_speeds)) for _ in range(n_box)], float)
+    centres = np.empty((n_frames, n_box, 2))
+    c, v = centre.copy(), vel.copy()
+    for f in range(n_frames):
+        if f > 0:
+            c = c + v
+            for a, lim in ((0, W), (1, H)):
+                out = (c[:, a] < 0) | (c[:, a] > lim)
+                v[out, a] = -v[out, a]
+                c[:, a] = np.clip(c[:, a], 0, lim)
+        centres[f] = c
+
+    def boxes_at(scale):
+        out = []
+        for f in range(n_frames):
+            bl = []
+            for i in range(n_box):
+                w, h = int(round(base[i, 0] * scale * W)), int(round(base[i, 1] * scale * H))
+                if w < 1 or h < 1:
+                    continue
+                x = int(np.clip(round(centres[f, i, 0] - w / 2), 0, max(W - w, 0)))
+                y = int(np.clip(round(centres[f, i, 1] - h / 2), 0, max(H - h, 0)))
+                bl.append((x, y, min(w, W), min(h, H)))
+            out.append(bl)
+        return out
+    sample = [f for f in range(1, n_frames) if f != cut_at]
+    lo, hi = 0.0, 4.0
+    for _ in range(24):                       # the spoiled share grows with the scale: bisection
+        mid = 0.5 * (lo + hi)
+        if 1.0 - _sweep_dirty_fraction(boxes_at(mid), pan, H, W, block, sample) > target_reuse:
+            lo = mid
+        else:
+            hi = mid
+    boxes = boxes_at(lo)
     canvas = None
     ox = oy = 0
     for f in range(n_frames):
@@ -429,10 +491,8 @@ def reuse_sweep_video(seed, target_reuse, n_frames=60, H=416, W=416, block=16,
             ox += pan[0]
             oy += pan[1]
         img = canvas[oy:oy + H, ox:ox + W].copy()
-        if dirty_rows > 0:
-            y0 = (gh - dirty_rows) // 2 * block
-            img[y0:y0 + dirty_rows * block] = rng.integers(
-                0, 256, size=(dirty_rows * block, W, 3), dtype=np.int64).astype(np.uint8)
+        for (x, y, w, h) in boxes[f]:
+            img[y:y + h, x:x + w] = rng.integers(0, 256, size=(h, w, 3), dtype=np.int64).astype(np.uint8)
         frames[f] = img
     return frames
 

@@ -16,6 +16,12 @@ def _rel_err(got, want):
     return float(np.abs(got - want).max()) / scale
 
 
+def _elem_err(got, want):
+    """Element-wise variant: |g - o| / max(|o|, 1e-3 * max|o|), the floor keeps values near zero from deciding."""
+    scale = max(float(np.abs(want).max()), 1e-30)
+    return float((np.abs(got - want) / np.maximum(np.abs(want), 1e-3 * scale)).max())
+
+
 def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
               residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False,
               extend_borders=False):
@@ -31,7 +37,7 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
                              diamond=diamond, k_skip=k_skip, extend_borders=extend_borders)
                for _ in range(n)]
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
-    worst = 0.0
+    worst = worst_elem = 0.0
     reuse = []
     runner.in_place_frames = []
     for t in range(T):
@@ -66,8 +72,10 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
                     g = g[..., :C]
                 e = _rel_err(g, want["tensors"][ti])
                 worst = max(worst, e)
+                worst_elem = max(worst_elem, _elem_err(g, want["tensors"][ti]))
                 assert e <= tol, (t, s, ti, e)
-    print(f"[stack] worst rel err {worst:.3e}, mean block reuse {np.mean(reuse) if reuse else 0:.3f}", flush=True)
+    print(f"[stack] worst error relative to the tensor's largest magnitude {worst:.3e} (bound {tol:g}); element-wise "
+          f"with floor 1e-3 of that magnitude {worst_elem:.3e}; mean block reuse {np.mean(reuse) if reuse else 0:.3f}", flush=True)
     return runner, reuse
 
 
@@ -290,28 +298,15 @@ def test_resnet50_trunk_224_bf16_full_size(oracle):
     _run_both(oracle, layers, video, 16, 16, True, bias_scale=0.0, residual_scale=0.5)
 
 
-def test_darknet19_416_bf16_sampled(oracle):
-    """configs[3] geometry at full size (416x416, 19 conv layers, bf16): match results and all rectangles
-    bit-exact on a cached frame; conv outputs checked on sampled pixels of the full frame."""
+def test_darknet19_416_bf16_cached_frame_and_scene_cut(oracle):
+    """configs[3] at full size (416x416, 19 conv layers, bf16, moving noise rectangles at half reuse): the last two
+    frames of the first scene and the first two of the second, with the cache dropped at the cut as the config
+    says.  Every tensor of the full frames and of the cached frames (reused pixels are the oracle's shifted cache,
+    the others its convolution), match results, masks and rectangles against the oracle's stream."""
     layers = synth.darknet19()
-    ws, bs = synth.he_weights(layers, 1)
-    video = synth.reuse_sweep_video(4002, 0.5, n_frames=2)
-    r = binding.StackRunner(layers, ws, bs, 1, 416, 416, 3, block=16, radius=16, dtype=binding.DC_BF16, want_regions=True)
-    dv = torch.from_numpy(video[:, None]).to(DEV)
-    t0 = r.step(dv[0])
-    torch.cuda.synchronize()
-    rng = np.random.default_rng(0)
-    for li, L in enumerate(layers):
-        if L["type"] == synth.CONV:
-            _sampled_conv_check(oracle, layers, ws, bs, t0, li, 0, True, 6, rng, 2e-2)
-    r.step(dv[1])
-    torch.cuda.synchronize()
-    m = oracle.match_blocks(video[1], video[0], 16, 16, synth.max_block_ssd(16))
-    assert np.array_equal(r.mask[0].cpu().numpy(), m["mask"]) and r.gmv[0].cpu().numpy().tolist() == m["gmv"].tolist()
-    want = oracle.propagate(layers, 416, 416, oracle.merge_blocks(m["mask"], 16), int(m["gmv"][0]), int(m["gmv"][1]))
-    for t, g in enumerate(r.regions(0)):
-        assert g["rects"].tolist() == want["rects"][t].tolist(), t
-    assert 0.3 < m["mask"].mean() < 0.7
+    video = synth.reuse_sweep_video(4002, 0.5, n_frames=60)[28:32][None]
+    runner, reuse = _run_both(oracle, layers, video, 16, 16, True, bias_scale=0.0, resets=(2,))
+    assert len(reuse) == 2 and all(0.45 < r < 0.6 for r in reuse)
 
 
 def test_throughput_mode_64_streams_bf16_sampled(oracle):

@@ -53,7 +53,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.dc_prefetch_match(None, one, one, 1, 64, 64, 3, 8, 8, 0, None, one, one, one, one, one, one, 4096) == -2
     assert L.dc_prefetch_match(one, one, one, 1, 64, 64, 3, 8, 8, 0, None, one, one, one, one, None, one, 4096) == -2
     assert L.dc_prefetch_match(one, one, one, 0, 64, 64, 3, 8, 8, 0, None, one, one, one, one, one, one, 4096) == -1
-    assert L.dc_prefetch_match(one, one, one, 1, 64, 60, 3, 8, 8, 0, None, one, one, one, one, one, one, 4096) == -1
+    assert L.dc_prefetch_match(one, one, one, 1, 64, 4, 3, 8, 8, 0, None, one, one, one, one, one, one, 4096) == -3   # block > frame
     assert L.dc_prefetch_match(one, one, one, 1, 64, 64, 3, 8, 8, 0, None, one, one, one, one, one, one, 16) == -5
     bad = binding.layers_to_c([dict(type=0, k=3, s=0, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
     assert L.dc_cached_conv_layer(bad, one, one, None, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -1
@@ -293,3 +293,21 @@ def test_host_regions_with_the_border_case_equal_oracle(oracle):
             assert area(b) >= area(a)
             grew += area(b) > area(a)
     assert grew > 10
+
+
+def test_reuse_sweep_generator_hits_its_target_ratio(oracle):
+    """The sweep's moving noise rectangles are sized so that the measured share of reusable blocks (Step 4 of the
+    oracle's matcher) is the target within 3 points; zero means fresh noise, and the entering column caps 0.95."""
+    from paper_1712_01670_amd import synth
+    for i, target in enumerate((0.0, 0.25, 0.5, 0.75, 0.95)):
+        v = synth.reuse_sweep_video(4000 + i, target, n_frames=8, cut_at=4)
+        got = []
+        for f in (1, 2, 3, 5, 6):
+            m = oracle.match_blocks(v[f], v[f - 1], 16, 16, synth.max_block_ssd(16))
+            got.append(float(m["mask"].mean()))
+            if target > 0:
+                assert m["gmv"].tolist() == [2, 0]
+        assert abs(np.mean(got) - target) <= 0.03, (target, got)
+    # across the cut nothing matches
+    v = synth.reuse_sweep_video(4003, 0.75, n_frames=8, cut_at=4)
+    assert oracle.match_blocks(v[4], v[3], 16, 16, synth.max_block_ssd(16))["mask"].sum() == 0

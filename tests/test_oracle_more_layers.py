@@ -244,3 +244,72 @@ def test_stack_with_every_layer_type_is_the_composition_of_its_layers(oracle):
     out2 = st.step(cur)
     for i in range(len(layers) + 1):
         assert np.array_equal(out2["tensors"][i], out1["tensors"][i]), i
+
+
+# ---- element-wise add and ReLU ------------------------------------------------------------------------------------
+def test_add_hand_values(oracle):
+    # exact binary fractions: every sum is exact in fp32, so the expected values are plain arithmetic
+    a = np.array([1.5, -2.0, 0.25, -0.5, 1e3, -0.0], np.float32)
+    b = np.array([2.0, 1.0, -0.25, -1.0, -1e3 + 0.5, 0.0], np.float32)
+    assert oracle.add(a, b, relu=False).tolist() == [3.5, -1.0, 0.0, -1.5, 0.5, 0.0]
+    assert oracle.add(a, b, relu=True).tolist() == [3.5, 0.0, 0.0, 0.0, 0.5, 0.0]
+    # the operands are not interchanged with anything else: a + b, not a - b or b alone
+    assert oracle.add(a, np.zeros_like(a), relu=False).tolist() == a.tolist()
+    assert oracle.add(np.zeros_like(b), b, relu=False).tolist() == b.tolist()
+
+
+def test_add_bf16_rounds_the_sum_once_to_nearest_even(oracle):
+    # bf16 keeps 8 significant bits: the spacing at 1.0 is 2^-7
+    e = lambda k: float(2.0 ** -k)
+    cases = [
+        (1.0, e(9), 1.0),                           # below half a step: down
+        (1.0, e(8), 1.0),                           # exactly half, lower neighbour even: down
+        (1.0 + e(7), e(8), 1.0 + e(6)),             # exactly half, lower neighbour odd: up
+        (1.0, e(8) + e(20), 1.0 + e(7)),            # just above half: up (the sum is not rounded to the tie first)
+        (-1.0, -e(8), -1.0),                        # ties behave the same for negative sums
+        (0.5, 0.25, 0.75),                          # representable: unchanged
+    ]
+    a = np.array([c[0] for c in cases], np.float32)
+    b = np.array([c[1] for c in cases], np.float32)
+    want = [c[2] for c in cases]
+    assert oracle.add(a, b, relu=False, bf16=True).tolist() == want
+    # ReLU acts on the sum, then the result is rounded
+    assert oracle.add(a, b, relu=True, bf16=True).tolist() == [max(w, 0.0) for w in want]
+    # without bf16 nothing is rounded beyond fp32
+    assert oracle.add(a, b, relu=False).tolist() == [float(np.float32(x) + np.float32(y)) for x, y, _ in cases]
+
+
+def test_add_matches_numpy_on_random_values(oracle):
+    rng = np.random.default_rng(5)
+    a = rng.standard_normal(4099).astype(np.float32) * 7
+    b = rng.standard_normal(4099).astype(np.float32) * 7
+    want = (a.astype(np.float64) + b.astype(np.float64))
+    assert np.array_equal(oracle.add(a, b, relu=False), want.astype(np.float32))
+    assert np.array_equal(oracle.add(a, b, relu=True), np.maximum(want, 0.0).astype(np.float32))
+    bf = torch.from_numpy(np.maximum(want, 0.0)).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(oracle.add(a, b, relu=True, bf16=True), bf)
+
+
+def test_relu_hand_values(oracle):
+    x = np.array([-1.0, 0.0, 2.5, -0.0, 1e-30, -1e-30, 3.0e38, -3.0e38], np.float32)
+    got = oracle.relu(x)
+    assert got.tolist() == [0.0, 0.0, 2.5, 0.0, float(np.float32(1e-30)), 0.0, float(np.float32(3.0e38)), 0.0]
+    assert not np.signbit(got).any()          # negative zero does not survive either
+    rng = np.random.default_rng(6)
+    y = rng.standard_normal(1000).astype(np.float32)
+    assert np.array_equal(oracle.relu(y), np.maximum(y, 0))      # positives pass unchanged, bit for bit
+
+
+def test_relu_and_add_layers_inside_a_stack(oracle):
+    # conv (identity weights) -> ReLU layer -> add(ReLU output, conv output): out = max(x, 0) + x, by hand per element
+    from paper_1712_01670_amd import synth
+    layers = [dict(type=synth.CONV, k=1, s=1, p=0, cin=2, cout=2, relu=0, in0=0, in1=-1),
+              dict(type=synth.RELU, k=1, s=1, p=0, cin=2, cout=2, relu=0, in0=1, in1=-1),
+              dict(type=synth.ADD, k=1, s=1, p=0, cin=2, cout=2, relu=0, in0=2, in1=1)]
+    w = [np.eye(2, dtype=np.float32).reshape(2, 1, 1, 2), None, None]
+    st = oracle.Stream(layers, w, [None, None, None], 4, 4, 2, block=2, radius=1)
+    frame = np.arange(32, dtype=np.uint8).reshape(4, 4, 2) * 8
+    res = st.step(frame)
+    x = (frame.astype(np.float64) - 128.0) / 128.0
+    assert np.array_equal(res["tensors"][2], np.maximum(x, 0).astype(np.float32))
+    assert np.array_equal(res["tensors"][3], (np.maximum(x, 0) + x).astype(np.float32))
