@@ -84,7 +84,7 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames):
     dt = binding.DC_BF16 if dtype == "bf16" else binding.DC_F32
     method = binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE
     runner = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
-                                 match_method=method, k_skip=args.k_skip, device_plan=False)
+                                 match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan)
 
     def run_steps(k, start, collect=None, force_full=False):
         """Run k steps through the cyclic video starting at global step `start`."""

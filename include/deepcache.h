@@ -106,6 +106,18 @@ typedef struct {
                               need not lie in the rectangle (they read zeros in both frames), so a rectangle that
                               touches a side of the map keeps the outputs along that side: an extension beyond
                               the paper's table for static cameras (dc_propagate_regions_opt) */
+    int32_t device_plan;   /* dc_run_stack only.  0: the call waits for the matching, then merges, propagates and lists
+                              the dirty units on the host.  1: three small kernels do that on the GPU from the block
+                              mask in device memory (Section 4 Step 5, Section 5 "Propagation": the same rules, the
+                              same lists), so that a cached frame needs no host wait; the convolutions are launched
+                              for the longest possible list and read its length from memory.  Then
+                               - a rectangle list may hold min(max_rects, 256) entries,
+                               - the work counters of the frame arrive later: see dc_stack_stats_fetch,
+                               - regions_out, if given, makes the call wait for the lists (inspection only),
+                               - in_place frames are not available (the request is ignored when in_place is given),
+                               - the tail of ws_host keeps the counters between the call and dc_stack_stats_fetch.
+                              Grids of more than 64 x 64 blocks and stacks of more than 191 layers or 128
+                              convolutions are planned on the host as with 0. */
 } dc_match_options;
 
 /* Work counters of one dc_run_stack call, summed over streams. */
@@ -395,7 +407,8 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
  *                   max_rects entries each (DC_ERR_CAPACITY otherwise, before anything is launched); receives
  *                   every tensor's regions (for inspection); may be NULL
  *   ws_dev, ws_host workspaces of at least dc_stack_workspace_bytes; ws_host should be pinned
- *   stats           optional host
+ *   stats           optional host; for a frame planned on the GPU (dc_match_options.device_plan) only full,
+ *                   n_blocks, macs_full and layer_kernel_id are filled by the call itself
  *   overlap         optional dc_overlap handle; with it the frames must be visible to any stream
  *                   when the call is made (the matching does not wait for the main stream)
  * The call waits once for the matching (the region logic runs on the host): for the main
@@ -416,6 +429,16 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers,
                      uint8_t* block_mask, int32_t max_rects, dc_regions* regions_out,
                      void* ws_dev, size_t ws_dev_bytes, void* ws_host, size_t ws_host_bytes,
                      dc_stack_stats* stats, void* overlap, void* stream);
+
+/*
+ * Work counters of the most recent dc_run_stack call that planned its frame on the GPU with this host workspace
+ * (Section 7.2 reports the saving per scenario; these are the quantities it depends on).  Call it after the stream
+ * has been synchronised: the planning kernels write the counters into ws_host (directly if it is pinned memory,
+ * else through a copy on the stream).  Fills every field of `stats` but `profile` and `layer_kernel_id`, and the
+ * per-layer arrays if their pointers are set (same ws_host and ws_host_bytes as in that call).
+ * DC_ERR_INVALID_ARG if the workspace holds no such frame.
+ */
+int32_t dc_stack_stats_fetch(const void* ws_host, size_t ws_host_bytes, dc_stack_stats* stats);
 
 #ifdef __cplusplus
 }

@@ -24,7 +24,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
            "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_prefetch_match", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_propagate_regions_opt", "dc_conv_workspace_bytes",
            "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer", "dc_avgpool_layer", "dc_lrn_layer", "dc_concat_layer", "dc_fc_layer", "dc_softmax_layer",
-           "dc_stack_workspace_bytes", "dc_run_stack"]
+           "dc_stack_workspace_bytes", "dc_run_stack", "dc_stack_stats_fetch"]
 
 
 class DcError(RuntimeError):
@@ -49,7 +49,7 @@ class Regions(C.Structure):
 
 
 class MatchOptions(C.Structure):
-    _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32), ("extend_borders", C.c_int32)]
+    _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32), ("extend_borders", C.c_int32), ("device_plan", C.c_int32)]
 
 
 DC_MATCH_EXHAUSTIVE, DC_MATCH_DIAMOND = 0, 1
@@ -107,6 +107,7 @@ def lib():
         L.dc_stack_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz)]
         L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, vp, i32, vp,
                                    vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp, vp]
+        L.dc_stack_stats_fetch.argtypes = [vp, sz, vp]
         for name in EXPORTS:
             if name != "dc_status_string":
                 getattr(L, name).restype = i32
@@ -401,8 +402,7 @@ class StackRunner:
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
                  want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True,
                  match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False, extend_borders=False, device_plan=False):
-        if device_plan:
-            raise NotImplementedError("device-side planning")
+        self.device_plan = bool(device_plan) and not in_place
         self.in_place = bool(in_place)
         self.last_in_place = False
         self._in_place_flag = C.c_int32(0)
@@ -413,7 +413,7 @@ class StackRunner:
         self.block, self.radius, self.dtype, self.expiry = block, radius, dtype, expiry
         self.max_block_ssd = int(max_block_ssd if max_block_ssd is not None else synth.max_block_ssd(block, Ch))
         self.max_rects = max_rects
-        self.match_options = MatchOptions(int(match_method), int(k_skip), int(extend_borders))
+        self.match_options = MatchOptions(int(match_method), int(k_skip), int(extend_borders), int(self.device_plan))
         self.device = torch.device(device)
         td = torch_dtype(dtype)
         self.Lc = layers_to_c(layers)
@@ -531,7 +531,11 @@ class StackRunner:
         return [self.bufs[c if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]
 
     def read_stats(self):
-        """Work counters of the last step (call after the stream has been synchronised)."""
+        """Work counters of the last step (call after the stream has been synchronised): a frame planned on the GPU
+        leaves them in the host workspace."""
+        if self.device_plan and not self.last_full:
+            _check("dc_stack_stats_fetch", lib().dc_stack_stats_fetch(C.c_void_p(self.ws_host.data_ptr()), self.ws_host.numel(),
+                                                                      C.byref(self.stats)))
         return self.stats
 
     def enable_profile(self, on=True):

@@ -154,7 +154,8 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
                      const ConvTiling& tiling, const LayerPlan* plan, const PlanAddr* addr, hipStream_t st,
                      Profile* prof = nullptr, int gemm_slot = -1, int copy_slot = -1, int* kernel_id = nullptr,
                      bool copy_done = false, void* scratch = nullptr, size_t scratch_bytes = 0,
-                     const void* w_packed = nullptr) {
+                     const void* w_packed = nullptr, const TileDev* dev_tiles = nullptr, int dev_capacity = 0,
+                     const int* dev_count = nullptr, long dev_hint = -1) {
     const int Hout = (Hin + 2 * l.p - l.k) / l.s + 1, Wout = (Win + 2 * l.p - l.k) / l.s + 1;
     ConvLaunch c;
     c.kernel_id = kernel_id;
@@ -164,6 +165,13 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
     c.Hout = Hout; c.Wout = Wout; c.Cout = l.cout; c.k = l.k; c.s = l.s; c.p = l.p; c.relu = l.relu;
     c.dtype = dtype; c.tiling = tiling;
     c.scratch = scratch; c.scratch_bytes = scratch_bytes;
+    if (dev_tiles) {      // a list the planning kernels built: its length is in device memory, the copies are done
+        c.tiles = dev_tiles; c.n_tiles = dev_capacity; c.n_tiles_dev = dev_count; c.n_tiles_hint = dev_hint;
+        c.rects = nullptr; c.ranges = nullptr;
+        Bracket b(prof, gemm_slot, st);
+        DC_TRY_HIP(launch_conv(c, st));
+        return DC_OK;
+    }
     if (!plan) {
         c.tiles = nullptr; c.n_tiles = 0; c.rects = nullptr; c.ranges = nullptr;
         Bracket b(prof, gemm_slot, st);
@@ -183,6 +191,94 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
         DC_TRY_HIP(launch_conv(c, st));
     }
     return DC_OK;
+}
+
+// ---- planning on the GPU: layout of the tables and of one frame's plan in the device workspace ----
+constexpr size_t kDevHostRegion = 64 * 1024;    // tail of the host workspace: header, two counter slots, table staging
+constexpr size_t kDevHostSlot = 4096;
+constexpr int kPlanMaxConvs = 128;
+constexpr uint64_t kDevHostMagic = 0x6463706c616e3031ull;
+struct DevHostConv { int32_t layer, cout_bytes; int64_t mac_px, px_total; };
+struct DevHostHeader {                          // host-only bookkeeping of the workspace pair
+    uint64_t magic, signature;
+    const void* ws_dev;
+    int32_t n_layers, n_convs, last_slot, n_blocks;
+    int64_t macs_full;
+    DevHostConv conv[kPlanMaxConvs];
+};
+static_assert(sizeof(DevHostHeader) <= kDevHostSlot, "header fits its slot");
+static_assert(sizeof(PlanStatsHead) + kPlanMaxConvs * sizeof(PlanStatsConv) <= kDevHostSlot, "counters fit their slot");
+
+struct DevPlanLayout {
+    std::vector<PlanLayerDev> layers;
+    std::vector<PlanTensorDev> tensors;
+    std::vector<PlanConvDev> convs;
+    std::vector<int> conv_layer;                // layer index of every conv
+    size_t table_bytes = 0, off_tensors = 0, off_convs = 0;
+    size_t frame_bytes = 0, off_nrect = 0, off_dxy = 0, off_info = 0, off_nunits = 0, off_stats = 0, off_area = 0;
+    int cap = 0, max_chunks = 0;
+    bool ok = false;
+};
+
+// Tables and sizes for n_streams streams of this stack; ok = false if the device kernels cannot take it (the host
+// path then plans the frame).
+void device_plan_layout(const dc_layer* L, int n_layers, const std::vector<int>& hs, const std::vector<int>& ws,
+                        int n_streams, int max_rects, DevPlanLayout& d) {
+    d.ok = false;
+    const int nt = n_layers + 1;
+    if (nt > kPlanMaxTensors) return;
+    d.cap = max_rects < kPlanMaxRects ? max_rects : kPlanMaxRects;
+    d.layers.resize(n_layers); d.tensors.resize(nt); d.convs.clear(); d.conv_layer.clear();
+    d.tensors[0] = PlanTensorDev{hs[0], ws[0], 1, 0};
+    for (int i = 0; i < n_layers; ++i) {
+        const dc_layer& l = L[i];
+        d.layers[i] = PlanLayerDev{l.type, l.k, l.s, l.p, l.in0, l.in1, l.in2, l.in3, l.within, 0, 0, 0};
+        const bool windowed = l.type == DC_CONV || l.type == DC_MAXPOOL || l.type == DC_AVGPOOL;
+        const int cum = d.tensors[l.in0].cum_stride * (windowed ? l.s : 1);
+        d.tensors[i + 1] = PlanTensorDev{hs[i + 1], ws[i + 1], cum, 0};
+        if (l.type == DC_ADD && d.tensors[l.in1].cum_stride != d.tensors[l.in0].cum_stride) return;
+        if (l.type == DC_CONCAT) {
+            int ids[4];
+            const int m = concat_inputs(l, ids);
+            for (int j = 1; j < m; ++j)
+                if (d.tensors[ids[j]].cum_stride != d.tensors[l.in0].cum_stride) return;
+        }
+        if (l.type == DC_CONV) d.conv_layer.push_back(i);
+    }
+    if ((int)d.conv_layer.size() > kPlanMaxConvs) return;
+    d.off_tensors = align_up((size_t)n_layers * sizeof(PlanLayerDev), 256);
+    d.off_convs = d.off_tensors + align_up((size_t)nt * sizeof(PlanTensorDev), 256);
+    d.table_bytes = d.off_convs + align_up(d.conv_layer.size() * sizeof(PlanConvDev), 256);
+    size_t off = align_up((size_t)n_streams * nt * d.cap * sizeof(dc_rect), 256);
+    d.off_nrect = off; off += align_up((size_t)n_streams * nt * sizeof(int32_t), 256);
+    d.off_dxy = off; off += align_up((size_t)n_streams * nt * 2 * sizeof(int32_t), 256);
+    d.off_info = off; off += align_up((size_t)n_streams * 2 * sizeof(int32_t), 256);
+    d.off_nunits = off; off += align_up(d.conv_layer.size() * sizeof(int32_t), 256);
+    d.off_stats = off; off += kDevHostSlot;
+    d.off_area = off;
+    size_t area = 0;
+    d.max_chunks = 0;
+    for (int layer : d.conv_layer) {
+        PlanConvDev c{};
+        c.tensor = layer + 1; c.Hout = hs[layer + 1]; c.Wout = ws[layer + 1];
+        c.units_x = (c.Wout + 3) / 4; c.units_y = (c.Hout + 3) / 4;
+        const size_t units = (size_t)c.units_x * c.units_y;
+        c.n_chunks = (int)((units + kPlanChunk - 1) / kPlanChunk);
+        d.max_chunks = c.n_chunks > d.max_chunks ? c.n_chunks : d.max_chunks;
+        c.umask_off = (int64_t)area; area += align_up((size_t)n_streams * units * sizeof(uint16_t), 256);
+        c.count_off = (int64_t)area; area += align_up((size_t)n_streams * c.n_chunks * 2 * sizeof(int32_t), 256);
+        c.list_off = (int64_t)area; area += align_up((size_t)n_streams * units * sizeof(TileDev), 256);
+        if (units * (size_t)n_streams > 0x7fffffffull) return;
+        d.convs.push_back(c);
+    }
+    d.frame_bytes = align_up(off + area, 256);
+    d.ok = true;
+}
+
+uint64_t fnv1a(uint64_t h, const void* p, size_t n) {
+    const unsigned char* b = static_cast<const unsigned char*>(p);
+    for (size_t i = 0; i < n; ++i) { h ^= b[i]; h *= 0x100000001b3ull; }
+    return h;
 }
 
 }  // namespace
@@ -252,6 +348,7 @@ int32_t dc_overlap_create(void** overlap) {
     for (int i = 0; i < 2 && ok; ++i) ok = hipStreamCreateWithFlags(&o->work[i], hipStreamNonBlocking) == hipSuccess;
     for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&o->frame_done[i], hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&o->match_done, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&o->plan_done[i], hipEventDisableTiming) == hipSuccess;
     if (!ok) {
         (void)dc_overlap_destroy(o);
         return DC_ERR_HIP;
@@ -268,6 +365,7 @@ int32_t dc_overlap_destroy(void* overlap) {
         if (o->work[i]) (void)hipStreamSynchronize(o->work[i]);
         if (o->upload_done[i]) (void)hipEventDestroy(o->upload_done[i]);
         if (o->frame_done[i]) (void)hipEventDestroy(o->frame_done[i]);
+        if (o->plan_done[i]) (void)hipEventDestroy(o->plan_done[i]);
         for (hipEvent_t e : o->layer_done[i]) (void)hipEventDestroy(e);
         if (o->work[i]) (void)hipStreamDestroy(o->work[i]);
     }
@@ -292,6 +390,9 @@ int32_t dc_prefetch_match(void* overlap, const uint8_t* frames_next, const uint8
         DC_TRY_HIP(hipStreamSynchronize(ov->aux));
         ov->prefetch.valid = false;
     }
+    // planning kernels of the last frame may not have read its mask and motion yet (planning on the GPU)
+    if (ov->last_plan >= 0 && ov->plan_recorded[ov->last_plan])
+        DC_TRY_HIP(hipStreamWaitEvent(ov->aux, ov->plan_done[ov->last_plan], 0));
     int rc = dc_match_blocks_opt(frames_next, frames_cur, n_streams, H, W, C, block, radius, match_options, max_block_ssd,
                                  mv, best_ssd, global_mv, n_pass, block_mask, ov->aux);
     if (rc) return rc;
@@ -319,7 +420,9 @@ int32_t dc_overlap_pipeline(void* overlap, int32_t frames_in_flight) {
         o->recorded[i].clear();
         o->last_cur[i].clear();
         o->frame_recorded[i] = false;
+        o->plan_recorded[i] = false;
     }
+    o->last_plan = -1;
     o->pipeline = frames_in_flight == 2;
     return DC_OK;
 }
@@ -629,8 +732,17 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
     total += align_up((size_t)n_layers * sizeof(CopyLayerDev), 256);
     const size_t nb = (size_t)n_streams * (H / block) * (W / block);
     size_t match_host = align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
-    *dev_bytes = 2 * align_up(total, 256) + 2 * kConvScratchBytes;   // two frames in flight: plans and K-split scratch for each
-    *host_bytes = 2 * total + match_host;   // two staging halves (used alternately with an overlap handle)
+    size_t plans = 2 * align_up(total, 256);       // two frames in flight: a set of plans for each
+    try {                                           // planning on the GPU lays the same area out differently
+        DevPlanLayout dl;
+        device_plan_layout(layers, n_layers, hs, ws, n_streams, max_rects, dl);
+        if (dl.ok && 2 * align_up(dl.table_bytes, 256) + 2 * dl.frame_bytes > plans) plans = 2 * align_up(dl.table_bytes, 256) + 2 * dl.frame_bytes;
+    } catch (const std::bad_alloc&) {
+        return DC_ERR_WORKSPACE;
+    }
+    *dev_bytes = plans + 2 * kConvScratchBytes;     // and K-split scratch for each
+    // two staging halves (used alternately with an overlap handle); the tail serves the planning on the GPU
+    *host_bytes = align_up(2 * total + match_host, 256) + kDevHostRegion;
     return DC_OK;
 }
 
@@ -861,7 +973,140 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     if (in_place) *in_place = 0;
     std::vector<std::vector<TensorRegions>> regs;  // [stream][tensor]
     unsigned char* hbase = static_cast<unsigned char*>(ws_host);
-    if (cached) {
+
+    // ---- planning on the GPU: no read-back of the mask, no host wait (when asked for and the kernels can take it) ----
+    DevPlanLayout dl;
+    bool devplan = false;
+    PlanDev pd{};
+    DevHostHeader* hdr = nullptr;
+    std::vector<long> unit_hint;
+    if (cached && match_options && match_options->device_plan && !in_place && gh >= 1 && gw >= 1 && gh <= 64 && gw <= 64 &&
+        ws_host_bytes >= kDevHostRegion + 256 && ws_dev_bytes >= 2 * kConvScratchBytes) {
+        try {
+            device_plan_layout(layers, n_layers, hs, ws, n_streams, max_rects, dl);
+            unit_hint.assign(dl.convs.size(), -1);
+        } catch (const std::bad_alloc&) {
+            return DC_ERR_WORKSPACE;
+        }
+        devplan = dl.ok && 2 * align_up(dl.table_bytes, 256) + 2 * dl.frame_bytes <= ws_dev_bytes - 2 * kConvScratchBytes &&
+                  dl.table_bytes <= kDevHostRegion - 3 * kDevHostSlot;
+    }
+    if (devplan) {
+        unsigned char* const region = hbase + ((ws_host_bytes - kDevHostRegion) & ~(size_t)255);
+        hdr = reinterpret_cast<DevHostHeader*>(region);
+        unsigned char* const slots = region + kDevHostSlot;
+        unsigned char* const staging = region + 3 * kDevHostSlot;
+        // The layer tables travel with every frame (a few KB, one small launch): what the device workspace holds
+        // from earlier calls is never trusted.  The staging copy is rewritten only when it differs, and then nothing
+        // may still be reading it.
+        uint64_t sig = fnv1a(0xcbf29ce484222325ull, layers, (size_t)n_layers * sizeof(dc_layer));
+        const int32_t shape[8] = {n_streams, H, W, C, block, dl.cap, dtype, n_layers};
+        sig = fnv1a(sig, shape, sizeof(shape));
+        try {
+            std::vector<unsigned char> tables(dl.table_bytes, 0);
+            std::memcpy(tables.data(), dl.layers.data(), dl.layers.size() * sizeof(PlanLayerDev));
+            std::memcpy(tables.data() + dl.off_tensors, dl.tensors.data(), dl.tensors.size() * sizeof(PlanTensorDev));
+            if (!dl.convs.empty()) std::memcpy(tables.data() + dl.off_convs, dl.convs.data(), dl.convs.size() * sizeof(PlanConvDev));
+            if (std::memcmp(staging, tables.data(), dl.table_bytes) != 0) {
+                if (pipe) { DC_TRY_HIP(hipStreamSynchronize(ov->work[0])); DC_TRY_HIP(hipStreamSynchronize(ov->work[1])); }
+                DC_TRY_HIP(hipStreamSynchronize(st));
+                std::memcpy(staging, tables.data(), dl.table_bytes);
+            }
+        } catch (const std::bad_alloc&) {
+            return DC_ERR_WORKSPACE;
+        }
+        if (hdr->magic != kDevHostMagic || hdr->signature != sig || hdr->ws_dev != ws_dev || (hdr->last_slot != 0 && hdr->last_slot != 1)) {
+            std::memset(region, 0, 3 * kDevHostSlot);          // other stack or workspace: the counters start afresh
+            hdr->last_slot = 1;
+        }
+        hdr->magic = kDevHostMagic; hdr->signature = sig; hdr->ws_dev = ws_dev;
+        hdr->n_layers = n_layers; hdr->n_convs = (int32_t)dl.convs.size();
+        for (size_t c = 0; c < dl.convs.size(); ++c) {
+            const dc_layer& l = layers[dl.conv_layer[c]];
+            hdr->conv[c] = DevHostConv{dl.conv_layer[c], (int32_t)(l.cout * dtype_size(dtype)), (int64_t)l.k * l.k * l.cin * l.cout,
+                                       (int64_t)n_streams * dl.convs[c].Hout * dl.convs[c].Wout};
+        }
+        // one copy of the tables per frame in flight, so that a frame never writes what the other one's kernels read
+        const size_t table_slot = align_up(dl.table_bytes, 256);
+        unsigned char* const table_dev = static_cast<unsigned char*>(ws_dev) + (size_t)fp * table_slot;
+        DC_TRY_HIP(upload_plans(table_dev, staging, dl.table_bytes, ws_host, st));
+        // list lengths of the last frame whose counters have arrived: a guess of this frame's, for the launch shapes only
+        {
+            const PlanStatsConv* seen = reinterpret_cast<const PlanStatsConv*>(slots + (size_t)hdr->last_slot * kDevHostSlot + sizeof(PlanStatsHead));
+            for (size_t c = 0; c < dl.convs.size(); ++c) {
+                const int32_t v = *reinterpret_cast<const volatile int32_t*>(&seen[c].n_units);
+                unit_hint[c] = v > 0 ? v : -1;
+            }
+        }
+        const int slot = hdr->last_slot ^ 1;
+        unsigned char* const frame = static_cast<unsigned char*>(ws_dev) + 2 * table_slot + (size_t)fp * dl.frame_bytes;
+        pd.layers = reinterpret_cast<const PlanLayerDev*>(table_dev);
+        pd.tensors = reinterpret_cast<const PlanTensorDev*>(table_dev + dl.off_tensors);
+        pd.convs = reinterpret_cast<const PlanConvDev*>(table_dev + dl.off_convs);
+        pd.n_layers = n_layers; pd.n_convs = (int32_t)dl.convs.size(); pd.n_streams = n_streams; pd.cap = dl.cap;
+        pd.rects = reinterpret_cast<dc_rect*>(frame);
+        pd.nrect = reinterpret_cast<int32_t*>(frame + dl.off_nrect);
+        pd.dxy = reinterpret_cast<int32_t*>(frame + dl.off_dxy);
+        pd.stream_info = reinterpret_cast<int32_t*>(frame + dl.off_info);
+        pd.n_units = reinterpret_cast<int32_t*>(frame + dl.off_nunits);
+        pd.area = frame + dl.off_area;
+        unsigned char* const slot_host = slots + (size_t)slot * kDevHostSlot;
+        const unsigned char* alias = device_alias(ws_host);
+        pd.stats = alias ? const_cast<unsigned char*>(alias) + (slot_host - static_cast<unsigned char*>(ws_host))
+                         : frame + dl.off_stats;
+        DC_TRY_HIP(wait_readers(0));
+        DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
+        // the match buffers are shared by consecutive frames: the other frame's planning kernels must have read them
+        if (pipe && ov->plan_recorded[1 - fp]) DC_TRY_HIP(hipStreamWaitEvent(st, ov->plan_done[1 - fp], 0));
+        bool prefetched = false;
+        if (ov) {
+            prefetched = pf.valid && pf.cur == frames_cur && pf.prev == frames_prev && pf.mv == mv &&
+                         pf.best_ssd == best_ssd && pf.gmv == global_mv && pf.n_pass == n_pass && pf.mask == block_mask &&
+                         pf.ws_host == ws_host && pf.n_streams == n_streams && pf.H == H && pf.W == W && pf.C == C &&
+                         pf.block == block && pf.radius == radius && pf.max_block_ssd == max_block_ssd &&
+                         pf.method == match_options->method && pf.k_skip == match_options->k_skip;
+            if (pf.valid && !prefetched) DC_TRY_HIP(hipStreamSynchronize(ov->aux));   // let the stale match finish first
+        }
+        if (prefetched) {
+            DC_TRY_HIP(hipStreamWaitEvent(st, ov->match_done, 0));
+        } else {
+            rc = dc_match_blocks_opt(frames_cur, frames_prev, n_streams, H, W, C, block, radius, match_options,
+                                     max_block_ssd, mv, best_ssd, global_mv, n_pass, block_mask, st);
+            if (rc) return rc;
+        }
+        DC_TRY_HIP(launch_plan(pd, block_mask, global_mv, gh, gw, block, match_options->extend_borders, dl.max_chunks, st));
+        if (!alias)
+            DC_TRY_HIP(hipMemcpyAsync(slot_host, frame + dl.off_stats, sizeof(PlanStatsHead) + dl.convs.size() * sizeof(PlanStatsConv),
+                                      hipMemcpyDeviceToHost, st));
+        if (ov) {
+            DC_TRY_HIP(hipEventRecord(ov->plan_done[fp], st));
+            ov->plan_recorded[fp] = true;
+            ov->last_plan = fp;
+        }
+        hdr->last_slot = slot;
+        hdr->n_blocks = (int32_t)nb;
+        if (regions_out) {      // for inspection only: wait for the lists and read them back
+            const int nt = n_layers + 1;
+            try {
+                std::vector<int32_t> h_n((size_t)n_streams * nt), h_d((size_t)n_streams * nt * 2);
+                std::vector<dc_rect> h_r((size_t)n_streams * nt * dl.cap);
+                DC_TRY_HIP(hipStreamSynchronize(st));
+                DC_TRY_HIP(hipMemcpy(h_n.data(), pd.nrect, h_n.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+                DC_TRY_HIP(hipMemcpy(h_d.data(), pd.dxy, h_d.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+                DC_TRY_HIP(hipMemcpy(h_r.data(), pd.rects, h_r.size() * sizeof(dc_rect), hipMemcpyDeviceToHost));
+                for (int s = 0; s < n_streams; ++s)
+                    for (int t = 0; t < nt; ++t) {
+                        dc_regions& r = regions_out[(size_t)s * nt + t];
+                        const size_t at = (size_t)s * nt + t;
+                        r.n = h_n[at]; r.dx = h_d[2 * at]; r.dy = h_d[2 * at + 1];
+                        r.cum_stride = dl.tensors[t].cum_stride; r.h = hs[t]; r.w = ws[t];
+                        if (r.n) std::memcpy(r.rects, h_r.data() + at * dl.cap, (size_t)r.n * sizeof(dc_rect));   // n <= cap <= capacity
+                    }
+            } catch (const std::bad_alloc&) {
+                return DC_ERR_WORKSPACE;
+            }
+        }
+    } else if (cached) {
         // With an overlap handle the matching runs on its own stream, next to whatever the main stream
         // still holds of the previous frame; only that stream is waited for.
         hipStream_t mst = ov ? ov->aux : st;
@@ -936,7 +1181,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         hbase += align_up(nb, 256) + align_up((size_t)n_streams * 3 * sizeof(int32_t), 256);
         if (ov) {
             // two staging halves: the upload of the frame before last must have left the half reused now
-            const size_t half = (ws_host_bytes - (size_t)(hbase - static_cast<unsigned char*>(ws_host))) / 2 / 256 * 256;
+            const size_t half = (ws_host_bytes - kDevHostRegion - (size_t)(hbase - static_cast<unsigned char*>(ws_host))) / 2 / 256 * 256;
             hbase += (size_t)ov->parity * half;
             if (ov->pending[ov->parity]) {
                 DC_TRY_HIP(spin_wait(ov->upload_done[ov->parity]));
@@ -947,7 +1192,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         DC_TRY_HIP(wait_readers(0));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
     }
-    if (regions_out) {
+    if (regions_out && !devplan) {
         for (int s = 0; s < n_streams; ++s)
             for (int t = 0; t <= n_layers; ++t) {
                 dc_regions& r = regions_out[(size_t)s * (n_layers + 1) + t];
@@ -971,7 +1216,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     // staging buffer, again in parallel (64 streams: 550 k tiles per frame).
     std::lock_guard<std::mutex> plan_guard(g_frame_plan_mutex);
     FramePlan& frame_plan = g_frame_plan;
-    if (cached) {
+    if (cached && !devplan) {
         int rc_plan = frame_plan.classify(layers, n_layers, n_streams, regs, hs, ws);
         if (rc_plan) return rc_plan;
     }
@@ -994,6 +1239,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 if (local.layer_issued_macs) local.layer_issued_macs[i] = issued;
                 continue;
             }
+            if (devplan) continue;       // the counters of a frame planned on the GPU arrive with dc_stack_stats_fetch
             LayerPlan& plan = plans[i];
             addrs[i] = frame_plan.finish_layer(i, plan, hbase + off, plan_dev + off);
             off += addrs[i].bytes;
@@ -1007,7 +1253,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     } catch (const std::bad_alloc&) {
         return DC_ERR_WORKSPACE;
     }
-    if (cached) frame_plan.copy_tiles();
+    if (cached && !devplan) frame_plan.copy_tiles();
+    if (devplan) hdr->macs_full = local.macs_full;
     // ---- the shifted copies of all layers in one launch (16-byte vector path only); pipelined: one launch per
     // run of consecutive conv layers, issued when the previous frame has finished that run ----
     std::vector<char> copy_fused(n_layers, 0);
@@ -1016,7 +1263,34 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     size_t all_rects_off = 0, copy_layers_off = 0, n_all_rects = 0;
     if (inplace)        // every reusable pixel already holds its value
         for (int i = 0; i < n_layers; ++i) copy_fused[i] = 1;
-    if (cached && !inplace) {
+    // planned on the GPU: one per-unit copy launch per run of conv layers (maps of one size), from the unit masks
+    struct DevCopyGroup { int first_layer, last_layer, vec_bytes; std::vector<CopyUnitsLayer> L; };
+    std::vector<DevCopyGroup> dev_groups;
+    if (devplan) {
+        try {
+            for (size_t c = 0; c < dl.convs.size(); ++c) {
+                const int i = dl.conv_layer[c];
+                copy_fused[i] = 1;
+                const size_t px_bytes = (size_t)layers[i].cout * dtype_size(dtype);
+                const bool vec16 = px_bytes % 16 == 0 && reinterpret_cast<uintptr_t>(tensors_prev[i + 1]) % 16 == 0 &&
+                                   reinterpret_cast<uintptr_t>(tensors_cur[i + 1]) % 16 == 0;
+                const int vb = vec16 ? 16 : (int)dtype_size(dtype);
+                bool fresh_group = dev_groups.empty() || dev_groups.back().vec_bytes != vb;
+                if (!fresh_group)
+                    for (int j = dev_groups.back().last_layer + 1; j < i; ++j) fresh_group |= layers[j].type != DC_CONV;
+                if (fresh_group) dev_groups.push_back(DevCopyGroup{i, i, vb, {}});
+                DevCopyGroup& g = dev_groups.back();
+                g.last_layer = i;
+                const PlanConvDev& cv = dl.convs[c];
+                g.L.push_back(CopyUnitsLayer{tensors_prev[i + 1], tensors_cur[i + 1],
+                                             reinterpret_cast<const uint16_t*>(pd.area + cv.umask_off), cv.tensor, cv.Hout, cv.Wout,
+                                             cv.units_x, cv.units_y, (int32_t)(px_bytes / vb), 0, 0});
+            }
+        } catch (const std::bad_alloc&) {
+            return DC_ERR_WORKSPACE;
+        }
+    }
+    if (cached && !inplace && !devplan) {
         try {
             std::vector<RectDev> all_rects;
             std::vector<CopyLayerDev> copy_layers;
@@ -1056,7 +1330,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             return DC_ERR_WORKSPACE;
         }
     }
-    if (cached && off) {
+    if (cached && off && !devplan) {
         DC_TRY_HIP(upload_plans(plan_dev, hbase, off, ws_host, st));
         if (ov) {
             DC_TRY_HIP(hipEventRecord(ov->upload_done[ov->parity], st));
@@ -1065,7 +1339,16 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         }
     }
     size_t next_group = 0;
+    size_t next_dev_group = 0;
     auto launch_copy_group = [&](int layer) -> int {     // the group that starts at `layer`, if any
+        if (devplan) {
+            if (next_dev_group >= dev_groups.size() || dev_groups[next_dev_group].first_layer != layer) return DC_OK;
+            const DevCopyGroup& g = dev_groups[next_dev_group++];
+            DC_TRY_HIP(wait_prev(run_end[g.last_layer]));
+            Bracket b(stats ? static_cast<Profile*>(stats->profile) : nullptr, n_layers + g.first_layer, st);
+            DC_TRY_HIP(launch_shifted_copy_units(g.L.data(), (int)g.L.size(), pd.dxy, n_layers + 1, n_streams, g.vec_bytes, st));
+            return DC_OK;
+        }
         if (next_group >= groups.size() || groups[next_group].first_layer != layer) return DC_OK;
         const CopyGroup& g = groups[next_group++];
         DC_TRY_HIP(wait_prev(run_end[g.last_layer]));
@@ -1081,11 +1364,13 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         eff[t] = (inplace && t > 0 && layers[t - 1].type == DC_CONV) ? tensors_prev[t] : tensors_cur[t];
     if (in_place) *in_place = inplace ? 1 : 0;
     // ---- layers ----
+    int conv_seen = 0;
     for (int i = 0; i < n_layers; ++i) {
         const dc_layer& l = layers[i];
         const int a = l.in0, t = i + 1;
         switch (l.type) {
-            case DC_CONV:
+            case DC_CONV: {
+                const int ci = conv_seen++;
                 rc = launch_copy_group(i);
                 if (rc) return rc;
                 DC_TRY_HIP(wait_prev(run_end[i]));   // its cache: the previous frame's output of this layer (whole run)
@@ -1096,9 +1381,13 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                                       stats ? static_cast<Profile*>(stats->profile) : nullptr, i, n_layers + i,
                                       local.layer_kernel_id ? &local.layer_kernel_id[i] : nullptr, copy_fused[i] != 0,
                                       conv_scratch, conv_scratch ? kConvScratchBytes : 0,
-                                      packed_weights ? packed_weights[i] : nullptr);
+                                      packed_weights ? packed_weights[i] : nullptr,
+                                      devplan ? reinterpret_cast<const TileDev*>(pd.area + dl.convs[ci].list_off) : nullptr,
+                                      devplan ? n_streams * dl.convs[ci].units_x * dl.convs[ci].units_y : 0,
+                                      devplan ? pd.n_units + ci : nullptr, devplan ? unit_hint[ci] : -1);
                 if (rc) return rc;
                 break;
+            }
             case DC_MAXPOOL:
                 DC_TRY_HIP(wait_readers(t));
                 DC_TRY_HIP(launch_maxpool(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
@@ -1157,6 +1446,33 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         ov->frame_parity ^= 1;
     }
     if (stats) *stats = local;
+    return DC_OK;
+}
+
+int32_t dc_stack_stats_fetch(const void* ws_host, size_t ws_host_bytes, dc_stack_stats* stats) {
+    if (!ws_host || !stats) return DC_ERR_NULL_PTR;
+    if (ws_host_bytes < kDevHostRegion + 256) return DC_ERR_WORKSPACE;
+    const unsigned char* region = static_cast<const unsigned char*>(ws_host) + ((ws_host_bytes - kDevHostRegion) & ~(size_t)255);
+    const DevHostHeader* hdr = reinterpret_cast<const DevHostHeader*>(region);
+    if (hdr->magic != kDevHostMagic || hdr->n_convs < 0 || hdr->n_convs > kPlanMaxConvs) return DC_ERR_INVALID_ARG;
+    const unsigned char* slot = region + kDevHostSlot + (size_t)hdr->last_slot * kDevHostSlot;
+    const PlanStatsHead* sh = reinterpret_cast<const PlanStatsHead*>(slot);
+    const PlanStatsConv* sc = reinterpret_cast<const PlanStatsConv*>(slot + sizeof(PlanStatsHead));
+    stats->full = 0;
+    stats->n_blocks = hdr->n_blocks;
+    stats->n_reusable_blocks = sh->n_reusable_blocks;
+    stats->n_overflow_streams = sh->n_overflow_streams;
+    stats->macs_full = hdr->macs_full;
+    stats->macs_needed = 0; stats->macs_issued = 0; stats->copy_bytes = 0;
+    for (int c = 0; c < hdr->n_convs; ++c) {
+        const DevHostConv& hc = hdr->conv[c];
+        const int64_t issued = (int64_t)sc[c].n_units * 16 * hc.mac_px;
+        stats->macs_needed += (hc.px_total - sc[c].reused_px) * hc.mac_px;
+        stats->macs_issued += issued;
+        stats->copy_bytes += 2 * sc[c].reused_px * hc.cout_bytes;
+        if (stats->layer_reused_px) stats->layer_reused_px[hc.layer] = sc[c].reused_px;
+        if (stats->layer_issued_macs) stats->layer_issued_macs[hc.layer] = issued;
+    }
     return DC_OK;
 }
 

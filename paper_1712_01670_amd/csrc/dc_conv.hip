@@ -33,6 +33,7 @@
 //
 // Epilogue: bias, ReLU, rounding to the storage type, and a per-pixel predicate: a pixel
 // inside a reusable rectangle keeps the value the shifted copy wrote.
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 
@@ -81,7 +82,9 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
     int ug, ntile;
     decode_workgroup(P.R, ug, ntile);
     const int n0 = ntile * NT;
-    decode_units<G, NTHREADS>(P, H, ug, tid);
+    const int n_units = unit_count(P);
+    if (ug * P.g_rt >= n_units) return;     // the launch is sized for the longest possible list (whole workgroup, before any barrier)
+    decode_units<G, NTHREADS>(P, H, ug, tid, n_units);
 
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.in))), 0, keep_scalar(P.in_bytes), kBufferFlags);
@@ -272,7 +275,9 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_staged_kernel(ConvParams
     int ug, ntile;
     decode_workgroup(P.R, ug, ntile);
     const int n0 = ntile * NT;
-    decode_units<G, NTHREADS>(P, H, ug, tid);
+    const int n_units = unit_count(P);
+    if (ug * P.g_rt >= n_units) return;     // the launch is sized for the longest possible list (whole workgroup, before any barrier)
+    decode_units<G, NTHREADS>(P, H, ug, tid, n_units);
 
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.in))), 0, keep_scalar(P.in_bytes), kBufferFlags);
@@ -525,6 +530,7 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
     const long n_units = c.tiles ? c.n_tiles : (long)c.n_streams * units_x * units_y;
     if (n_units <= 0) return hipSuccess;
+    const long n_hint = (c.tiles && c.n_tiles_dev && c.n_tiles_hint >= 0) ? std::max(1L, std::min(c.n_tiles_hint, n_units)) : n_units;
     if (c.k > kMaxK) return hipErrorInvalidValue;
     // buffer loads address each tensor with 31-bit byte offsets
     if ((double)c.n_streams * c.Hin * c.Win * c.Cin * dtype_size(c.dtype) >= 2147483648.0 ||
@@ -532,7 +538,7 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
         return hipErrorInvalidValue;
     {
         hipError_t fe = hipSuccess;
-        if (launch_conv_fast(c, n_units, st, &fe)) return fe;
+        if (launch_conv_fast(c, n_units, n_hint, st, &fe)) return fe;
     }
     // Shape by the amount of work.  With enough units a workgroup takes g of them (up to 16) and 64
     // channels, g chosen so that the launch fills the 256 CUs in whole rounds; with few units the
@@ -541,11 +547,11 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     {
         constexpr int t1 = 160, xl_min = 8;
         const long r64 = (c.Cout + 63) / 64, r32 = (c.Cout + 31) / 32;
-        const long rounds = (n_units * r64 + 256 * 16 - 1) / (256 * 16);
-        const long g = (n_units * r64 + 256 * rounds - 1) / (256 * rounds);
+        const long rounds = (n_hint * r64 + 256 * 16 - 1) / (256 * 16);
+        const long g = (n_hint * r64 + 256 * rounds - 1) / (256 * rounds);
         if (c.Cout > 32 && g >= xl_min) { shape = 3; g_rt = (int)(g > 16 ? 16 : g); }
-        else if (c.Cout > 32 && ((n_units + 3) / 4) * r64 >= 160) { shape = 0; g_rt = 4; }
-        else if (((n_units + 1) / 2) * r32 >= t1) { shape = 1; g_rt = 2; }
+        else if (c.Cout > 32 && ((n_hint + 3) / 4) * r64 >= 160) { shape = 0; g_rt = 4; }
+        else if (((n_hint + 1) / 2) * r32 >= t1) { shape = 1; g_rt = 2; }
         else { shape = 2; g_rt = 1; }
     }
     const int ph = 3 * c.s + c.k, pw = ph;
@@ -560,7 +566,7 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
         for (int s2 = shape; s2 < 4; s2 = (s2 == 3 ? 0 : (s2 == 2 ? 4 : s2 + 1))) {   // 3 -> 0 -> 1 -> 2
             if (pass == 0 && !vec_ok) break;
             const long g2 = s2 == shape ? g_rt : kShapes[s2].g;
-            const long wgs2 = ((n_units + g2 - 1) / g2) * ((c.Cout + kShapes[s2].nt - 1) / kShapes[s2].nt);
+            const long wgs2 = ((n_hint + g2 - 1) / g2) * ((c.Cout + kShapes[s2].nt - 1) / kShapes[s2].nt);
             ch = pass == 0 ? choose_direct(s2, c, ph, pw, wgs2) : choose_staged(s2, c, ph, pw);
             if (ch.ok && (s2 != shape || pass == 1)) g_rt = kShapes[s2].g;
             if (ch.ok) break;
@@ -572,7 +578,7 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
     P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
     P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
-    P.units = c.tiles; P.n_units = (int)n_units; P.rects = c.rects; P.ranges = c.ranges;
+    P.units = c.tiles; P.n_units = (int)n_units; P.n_units_dev = c.tiles ? c.n_tiles_dev : nullptr; P.rects = c.rects; P.ranges = c.ranges;
     P.units_x = units_x; P.units_y = units_y;
     P.ph = ph; P.pw = pw; P.npix_magic = magic_of(ph * pw); P.pw_magic = magic_of(pw);
     P.tg = ch.tg; P.pv = ch.pv; P.wv = ch.wv; P.g_rt = g_rt; P.p_instr = ch.p_instr; P.w_instr = ch.w_instr;

@@ -30,7 +30,8 @@ struct ConvParams {
     void* out;
     int Hin, Win, Cin, Hout, Wout, Cout, k, s, p, relu;
     const TileDev* units;   // nullptr: every unit of every stream in raster order
-    int n_units;
+    int n_units;            // length of the unit list; with n_units_dev the most it can be (the launch is sized for it)
+    const int* n_units_dev; // optional, device: the length of a list that was built on the GPU
     const RectDev* rects;
     const RangeDev* ranges;
     int units_x, units_y;
@@ -124,6 +125,11 @@ __device__ __forceinline__ void activate4(floatx4& v, int mode) {
 
 __device__ __forceinline__ int fast_div(int n, uint32_t magic) { return (int)__umulhi((uint32_t)n, magic); }
 
+// Number of units this launch works on: the host's count, or the one the planning kernels left in memory.
+__device__ __forceinline__ int unit_count(const ConvParams& P) {
+    return P.n_units_dev ? __builtin_amdgcn_readfirstlane(*P.n_units_dev) : P.n_units;
+}
+
 // ---- pieces shared by both kernels ------------------------------------------------
 
 // LDS header: uinfo[G][4] = {valid, stream, oy0, ox0}, tmask[G*16], umask[G] (reusable pixels of the unit)
@@ -153,10 +159,10 @@ __device__ __forceinline__ void decode_workgroup(int R, int& ug, int& ntile) {
 }
 
 template <int G, int NTHREADS>
-__device__ __forceinline__ void decode_units(const ConvParams& P, const Header<G>& H, int ug, int tid) {
+__device__ __forceinline__ void decode_units(const ConvParams& P, const Header<G>& H, int ug, int tid, int n_units) {
     if (tid < G) {
         const int u = ug * P.g_rt + tid;
-        int valid = tid < P.g_rt && u < P.n_units, stream = 0, uy = 0, ux = 0, mixed = 0;
+        int valid = tid < P.g_rt && u < n_units, stream = 0, uy = 0, ux = 0, mixed = 0;
         if (valid) {
             if (P.units) {
                 const TileDev t = P.units[u];

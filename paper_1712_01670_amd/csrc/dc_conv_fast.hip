@@ -56,11 +56,11 @@ struct FastHeader {
 };
 
 template <int G, int NTHREADS, int ES>
-__device__ __forceinline__ void decode_units_fast(const ConvParams& P, const FastHeader<G>& H, int ug, int tid) {
+__device__ __forceinline__ void decode_units_fast(const ConvParams& P, const FastHeader<G>& H, int ug, int tid, int n_units) {
     static_assert(G * 16 <= NTHREADS, "one thread per pixel of the unit table");
     if (tid < G) {
         const int u = ug * P.g_rt + tid;
-        const bool valid = tid < P.g_rt && u < P.n_units;
+        const bool valid = tid < P.g_rt && u < n_units;
         int stream = 0, uy = 0, ux = 0, mixed = 0;
         if (valid) {
             if (P.units) {
@@ -137,6 +137,8 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
 
     int ug, ntile;
     decode_workgroup(P.R, ug, ntile);
+    const int n_units = unit_count(P);
+    if (ug * P.g_rt >= n_units) return;     // the launch is sized for the longest possible list (whole workgroup, before any barrier)
     const int n0 = ntile * NT;
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<void*>(keep_scalar(reinterpret_cast<uintptr_t>(P.in))), 0, keep_scalar(P.in_bytes), kBufferFlags);
@@ -180,7 +182,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
 
     issue_w(cb, 0, 0);   // the first weights do not depend on the units: they travel while the unit table is decoded
 
-    decode_units_fast<G, NTHREADS, ES>(P, H, ug, tid);
+    decode_units_fast<G, NTHREADS, ES>(P, H, ug, tid, n_units);
 
     // patch: IPU instructions per unit; instruction j covers lines [(j % IPU) * RPI / 8, ...) of unit j / IPU,
     // so the slot column and the line within the instruction are fixed per lane
@@ -341,7 +343,7 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
         return;
     }
     // partial sums: [split][unit][pixel][channel]
-    float* part = P.partial + (size_t)blockIdx.y * P.n_units * 16 * P.Cout + (size_t)l16 * P.Cout + chan;
+    float* part = P.partial + (size_t)blockIdx.y * n_units * 16 * P.Cout + (size_t)l16 * P.Cout + chan;
 #pragma unroll
     for (int u = 0; u < UPW; ++u) {
         const int g = wave_m + u * WM;
@@ -359,7 +361,8 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     typedef Frag<T> F;
     const int c4n = P.Cout >> 2;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t total = (size_t)P.n_units * 16 * c4n;
+    const int n_units = unit_count(P);
+    const size_t total = (size_t)n_units * 16 * c4n;
     if (idx >= total) return;
     const int co = (int)(idx % c4n) * 4;
     const size_t pix = idx / c4n;
@@ -377,7 +380,7 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     const int y = uy * 4 + (l16 >> 2), x = ux * 4 + (l16 & 3);
     if (y >= P.Hout || x >= P.Wout) return;
     if ((mixed >> l16) & 1) return;   // keeps the copied value
-    const size_t split_stride = (size_t)P.n_units * 16 * P.Cout;
+    const size_t split_stride = (size_t)n_units * 16 * P.Cout;
     const float* p = P.partial + pix * P.Cout + co;
     floatx4 v = *reinterpret_cast<const floatx4*>(p);
     for (int s = 1; s < P.ks; ++s) v += *reinterpret_cast<const floatx4*>(p + s * split_stride);
@@ -406,9 +409,9 @@ struct UnitRegs {
 };
 
 // The unit list entry of unit u (or its raster position), not yet turned into offsets: fetched two steps ahead.
-__device__ __forceinline__ TileDev regw_fetch(const ConvParams& P, long u) {
+__device__ __forceinline__ TileDev regw_fetch(const ConvParams& P, long u, int n_units) {
     TileDev t{0, 0, 0, -1};                 // reuse_mask -1: no such unit
-    if (u >= P.n_units) return t;
+    if (u >= n_units) return t;
     if (P.units) return P.units[u];
     t.stream = fast_div((int)u, P.npix_magic);
     const int rem = (int)u - t.stream * (P.units_x * P.units_y);
@@ -508,7 +511,8 @@ __global__ __launch_bounds__(WM * 128) void conv_regw_kernel(ConvParams P) {
         }
     }
 
-    const long n_groups = ((long)P.n_units + G - 1) / G;
+    const int n_units = unit_count(P);
+    const long n_groups = ((long)n_units + G - 1) / G;
     const long stride = gridDim.x;
     // Workgroup b runs on XCD b % 8.  In every pass over the list the workgroups of one XCD take consecutive
     // groups, so that the units above and below (a row of units further in the list) are in the same L2 at about
@@ -516,7 +520,7 @@ __global__ __launch_bounds__(WM * 128) void conv_regw_kernel(ConvParams P) {
     const long first = (gridDim.x % 8 == 0) ? (long)(blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8 : (long)blockIdx.x;
     auto fetch = [&](long ug, TileDev (&raw)[UPW]) {
 #pragma unroll
-        for (int uu = 0; uu < UPW; ++uu) raw[uu] = regw_fetch(P, ug < n_groups ? ug * G + wave_m + uu * WM : (long)P.n_units);
+        for (int uu = 0; uu < UPW; ++uu) raw[uu] = regw_fetch(P, ug < n_groups ? ug * G + wave_m + uu * WM : (long)n_units, n_units);
     };
     auto decode = [&](const TileDev (&raw)[UPW], UnitRegs (&info)[UPW]) {
 #pragma unroll
@@ -652,8 +656,11 @@ __global__ __launch_bounds__(WM * 128) void conv_pw_kernel(ConvParams P) {
     const int wave_n = wave % WN, wave_m = wave / WN;
     const int l16 = lane & 15, q = lane >> 4;
 
-    const int t = (int)(blockIdx.x & 7) * P.tiles_per_xcd + (int)(blockIdx.x >> 3);
-    if (t >= P.n_wg_tiles) return;                  // the whole workgroup, before any barrier
+    // (unit group, channel tile) pairs of this launch, dealt to the XCDs in equal consecutive shares
+    const int n_units = unit_count(P);
+    const int n_wg_tiles = (n_units + G - 1) / G * P.R, tiles_per_xcd = (n_wg_tiles + 7) >> 3;
+    const int t = (int)(blockIdx.x & 7) * tiles_per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= tiles_per_xcd || t >= n_wg_tiles) return;    // the whole workgroup, before any barrier
     const int ug = t / P.R, ntile = t - ug * P.R;
     const int n0 = ntile * NT;
     const int CinES = P.Cin * ES;
@@ -664,7 +671,7 @@ __global__ __launch_bounds__(WM * 128) void conv_pw_kernel(ConvParams P) {
     // that output pixel, element offset of it in the output}
     if (tid < G) {
         const int u = ug * G + tid;
-        const bool valid = u < P.n_units;
+        const bool valid = u < n_units;
         int stream = 0, uy = 0, ux = 0, mixed = 0;
         if (valid) {
             if (P.units) {
@@ -881,12 +888,13 @@ __device__ __forceinline__ void conv_first_body(const ConvParams& P) {
     };
     const int step = gridDim.x * 4;
     int u = blockIdx.x * 4 + wave;
-    if (u >= P.n_units) return;
+    const int n_units = unit_count(P);
+    if (u >= n_units) return;
     UnitPos pos = locate(u), pos_next = pos;
     vec xv[K][TG], xv_next[K][TG];
     load_x(pos, xv);
-    for (; u < P.n_units; u += step) {
-        const bool more = u + step < P.n_units;          // wavefront-uniform
+    for (; u < n_units; u += step) {
+        const bool more = u + step < n_units;          // wavefront-uniform
         if (more) {
             pos_next = locate(u + step);
             load_x(pos_next, xv_next);
@@ -1046,7 +1054,8 @@ Tuning tuning_snapshot() {
 // first loads, epilogue).  A CU runs ceil(workgroups / 256) of them; as many as LDS and registers allow
 // are resident together, and only the stage work of resident workgroups adds up, the fixed costs overlap.
 // ks > 1 adds the reduction kernel.
-FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes, int force_geom) {
+// n_units: the list length to tune for; n_cap: the longest the list can be (bounds the partial sums of a K split)
+FastChoice choose_fast(const ConvLaunch& c, long n_units, long n_cap, size_t scratch_bytes, int force_geom) {
     // bytes per clock and CU from L2 to LDS, fixed cycles per stage / workgroup / reduction launch (fitted to sweeps)
     constexpr double bw = 32, stage_fix = 250, wg_fix = 4500, red_fix = 13000, occ1_penalty = 1.08, lds_cap_kb = 160;
     const bool bf16 = c.dtype == DC_BF16;
@@ -1074,7 +1083,7 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, size_t scratch_bytes, 
                     if (cps == last_cps) continue;        // same split as a smaller ks
                     last_cps = cps;
                     const int ks_eff = (n_chunks + cps - 1) / cps;
-                    if (ks_eff > 1 && (size_t)ks_eff * n_units * 16 * c.Cout * 4 > scratch_bytes) continue;
+                    if (ks_eff > 1 && (size_t)ks_eff * n_cap * 16 * c.Cout * 4 > scratch_bytes) continue;
                     // per stage: MFMA cycles of a SIMD (two wavefronts), LDS cycles of the CU (a 16-byte read of
                     // a wavefront takes 4), cycles to load the stage
                     // units per SIMD: the two wavefronts of a SIMD belong to wave_m groups 0/1 (narrow) or 0/2, 1/3
@@ -1192,7 +1201,10 @@ template <typename T>
 hipError_t pw_launch(int wm, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
     return wm == 4 ? pw_launch_n<T, 4>(grid, lds, st, P) : pw_launch_n<T, 2>(grid, lds, st, P);
 }
-bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err) {
+bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t st, hipError_t* err) {
+    // below, n_units is the length the launch is tuned for and n_cap the length it must cover; they differ only
+    // when the list is built on the GPU (then the kernels read the real length from memory)
+    const int* const n_dev = c.tiles ? c.n_tiles_dev : nullptr;
     constexpr bool enabled = true;
     constexpr int g_stem_wgs = 256;      // persistent workgroups of the 7x7 / 11x11 first-layer kernels
     const Tuning tune = tuning_snapshot();
@@ -1202,12 +1214,12 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
         const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
-        if ((double)c.n_streams * c.Hout * c.Wout * c.Cout < 2147483648.0 && (double)n_units * units_x * units_y < 4294967296.0) {
+        if ((double)c.n_streams * c.Hout * c.Wout * c.Cout < 2147483648.0 && (double)n_cap * units_x * units_y < 4294967296.0) {
             ConvParams P{};
             P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
             P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
             P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
-            P.units = c.tiles; P.n_units = (int)n_units; P.rects = c.rects; P.ranges = c.ranges;
+            P.units = c.tiles; P.n_units = (int)n_cap; P.n_units_dev = n_dev; P.rects = c.rects; P.ranges = c.ranges;
             P.units_x = units_x; P.units_y = units_y;
             P.npix_magic = (uint32_t)((0x100000000ull + (uint64_t)(units_x * units_y) - 1) / (uint64_t)(units_x * units_y));
             P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)units_x - 1) / (uint64_t)units_x);
@@ -1219,7 +1231,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
             // (registers) and pay 28 / 33 weight loads per wavefront before the first unit, so the launch is one
             // persistent workgroup per CU and channel block, each walking its share of the units.
             const long cap = c.k == 3 ? 2048 : std::max(1L, (long)g_stem_wgs / (c.Cout / (16 * nb)));
-            const long wgx = (n_units + 3) / 4 < cap ? (n_units + 3) / 4 : cap;
+            const long wgx = (n_cap + 3) / 4 < cap ? (n_cap + 3) / 4 : cap;
             if (c.kernel_id)
                 *c.kernel_id = c.k == 11 ? 106 + (c.dtype == DC_BF16 ? 1 : 0)
                              : c.k == 7 ? 102 + (c.dtype == DC_BF16 ? 2 : 0) + (nb == 2 ? 1 : 0)
@@ -1238,14 +1250,14 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         const long small_tiles = (n_units + 3) / 4 * ((c.Cout + 63) / 64);
         const int wm = g_tune[1] == 8 ? 4 : (g_tune[1] == 4 ? 2 : (small_tiles >= 4096 && c.Cout >= 128 ? 4 : 2));
         const int g_units = 2 * wm, nt = 32 * wm;
-        const long R = (c.Cout + nt - 1) / nt, tiles = (n_units + g_units - 1) / g_units * R;
+        const long R = (c.Cout + nt - 1) / nt, tiles = (n_cap + g_units - 1) / g_units * R;
         if (pw_enabled && (double)c.n_streams * c.Hout * c.Wout * c.Cout < 2147483648.0 &&
-            (double)n_units * units_x * units_y < 4294967296.0 && tiles + 8 < 2147483647L / (wm * 128)) {
+            (double)n_cap * units_x * units_y < 4294967296.0 && tiles + 8 < 2147483647L / (wm * 128)) {
             ConvParams P{};
             P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
             P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
             P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
-            P.units = c.tiles; P.n_units = (int)n_units;
+            P.units = c.tiles; P.n_units = (int)n_cap; P.n_units_dev = n_dev;
             P.units_x = units_x; P.units_y = units_y;
             P.npix_magic = (uint32_t)((0x100000000ull + (uint64_t)(units_x * units_y) - 1) / (uint64_t)(units_x * units_y));
             P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)units_x - 1) / (uint64_t)units_x);
@@ -1271,7 +1283,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     if (reinterpret_cast<uintptr_t>(c.out) % 16 || (c.bias && reinterpret_cast<uintptr_t>(c.bias) % 16)) return false;
     {   // 32-bit output offsets, exact magic-number division of the unit index
         const double units_map = (double)((c.Hout + 3) / 4) * ((c.Wout + 3) / 4);
-        if ((double)c.n_streams * c.Hout * c.Wout * c.Cout >= 2147483648.0 || (double)n_units * units_map >= 4294967296.0)
+        if ((double)c.n_streams * c.Hout * c.Wout * c.Cout >= 2147483648.0 || (double)n_cap * units_map >= 4294967296.0)
             return false;
     }
     // 64 input channels in bf16 and enough units to keep persistent workgroups busy: the weights go to registers
@@ -1280,7 +1292,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
         P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
         P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
-        P.units = c.tiles; P.n_units = (int)n_units;
+        P.units = c.tiles; P.n_units = (int)n_cap; P.n_units_dev = n_dev;
         P.units_x = (c.Wout + 3) / 4; P.units_y = (c.Hout + 3) / 4;
         P.npix_magic = (uint32_t)((0x100000000ull + (uint64_t)(P.units_x * P.units_y) - 1) / (uint64_t)(P.units_x * P.units_y));
         P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)P.units_x - 1) / (uint64_t)P.units_x);
@@ -1289,7 +1301,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
         // Two persistent workgroups of four wavefronts per CU (the registers allow two wavefronts per SIMD): they
         // drift apart, so that one's address work and epilogue overlap the other's MFMAs.
         const int R = c.Cout / 64;
-        const long groups = (n_units + 3) / 4;
+        const long groups = (n_cap + 3) / 4;
         long gx = 512 / R > 0 ? 512 / R : 1;
         if (gx > groups) gx = groups;
         if (c.kernel_id) *c.kernel_id = 126;
@@ -1300,20 +1312,20 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     if (scratch > kConvScratchBytes) scratch = kConvScratchBytes;
     // The model costs about 2 us per call on the host; the same layers come back every frame with the same or a
     // recently seen unit count, so its answers are kept in a small direct-mapped table.
-    struct Memo { int dtype, cin, cout, tune[4]; long n_units; size_t scratch; FastChoice ch; bool used; };
+    struct Memo { int dtype, cin, cout, tune[4]; long n_units, n_cap; size_t scratch; FastChoice ch; bool used; };
     static Memo memo[256];
     static std::mutex memo_mutex;
     FastChoice ch;
     {
         std::lock_guard<std::mutex> guard(memo_mutex);
         Memo& slot = memo[((unsigned long)n_units * 2654435761ul + (unsigned)c.Cin * 40503u + (unsigned)c.Cout * 97u + (unsigned)c.dtype) % 256];
-        if (slot.used && slot.dtype == c.dtype && slot.cin == c.Cin && slot.cout == c.Cout && slot.n_units == n_units &&
+        if (slot.used && slot.dtype == c.dtype && slot.cin == c.Cin && slot.cout == c.Cout && slot.n_units == n_units && slot.n_cap == n_cap &&
             slot.scratch == scratch && slot.tune[0] == g_tune[0] && slot.tune[1] == g_tune[1] && slot.tune[2] == g_tune[2] &&
             slot.tune[3] == g_tune[3]) {
             ch = slot.ch;
         } else {
-            ch = choose_fast(c, n_units, scratch, g_tune[0]);
-            slot = Memo{c.dtype, c.Cin, c.Cout, {g_tune[0], g_tune[1], g_tune[2], g_tune[3]}, n_units, scratch, ch, true};
+            ch = choose_fast(c, n_units, n_cap, scratch, g_tune[0]);
+            slot = Memo{c.dtype, c.Cin, c.Cout, {g_tune[0], g_tune[1], g_tune[2], g_tune[3]}, n_units, n_cap, scratch, ch, true};
         }
     }
     if (g_tune[1] > 0 && ch.g > 0) {    // forced shape within the arrangement the model picked
@@ -1326,7 +1338,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
             int ks = f_ks < 1 ? 1 : (f_ks > n_chunks ? n_chunks : f_ks);
             const int cps = (n_chunks + ks - 1) / ks;
             ks = (n_chunks + cps - 1) / cps;
-            if (ks == 1 || (size_t)ks * n_units * 16 * c.Cout * 4 <= scratch) ch = FastChoice{f_g, ks, f_kci, 0, ch.geom};
+            if (ks == 1 || (size_t)ks * n_cap * 16 * c.Cout * 4 <= scratch) ch = FastChoice{f_g, ks, f_kci, 0, ch.geom};
         }
     }
     if (ch.g < 1) return false;
@@ -1338,7 +1350,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
     P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
     P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
-    P.units = c.tiles; P.n_units = (int)n_units; P.rects = c.rects; P.ranges = c.ranges;
+    P.units = c.tiles; P.n_units = (int)n_cap; P.n_units_dev = n_dev; P.rects = c.rects; P.ranges = c.ranges;
     P.units_x = units_x; P.units_y = units_y;
     P.ph = 6; P.pw = 6;
     P.npix_magic = (uint32_t)((0x100000000ull + (uint64_t)(units_x * units_y) - 1) / (uint64_t)(units_x * units_y));
@@ -1355,13 +1367,13 @@ bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipErro
     if (c.w_packed && reinterpret_cast<uintptr_t>(c.w_packed) % 16 == 0) { P.w = c.w_packed; P.w_packed = 1; }
 
     if (c.kernel_id) *c.kernel_id = ch.geom ? 110 + (ch.geom - 1) * 8 + ch.kci * 4 + upw - 1 : 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
-    const long groups = (n_units + ch.g - 1) / ch.g;
+    const long groups = (n_cap + ch.g - 1) / ch.g;
     const long wgx = groups * P.R;
     if (wgx > 2147483647L || ch.ks > 65535) { *err = hipErrorInvalidValue; return true; }
     *err = fast_launch(c.dtype == DC_BF16, ch.geom, ch.kci, upw, dim3((unsigned)wgx, (unsigned)ch.ks),
                        fast_lds_bytes(ch.geom, ch.kci, upw), st, P);
     if (*err != hipSuccess || ch.ks == 1) return true;
-    const size_t total = (size_t)n_units * 16 * (c.Cout / 4);
+    const size_t total = (size_t)n_cap * 16 * (c.Cout / 4);
     if (c.dtype == DC_BF16)
         hipLaunchKernelGGL(conv_split_reduce_kernel<__hip_bfloat16>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, P);
     else

@@ -71,7 +71,9 @@ struct ConvLaunch {
     int n_streams, Hin, Win, Cin, Hout, Wout, Cout, k, s, p, relu, dtype;
     ConvTiling tiling;
     const TileDev* tiles;  // device; nullptr: every tile of every stream
-    int n_tiles;           // ignored when tiles == nullptr
+    int n_tiles;           // ignored when tiles == nullptr; with n_tiles_dev the capacity of the list
+    const int* n_tiles_dev = nullptr;   // device: length of a list built on the GPU (the launch is sized for n_tiles)
+    long n_tiles_hint = -1;             // with n_tiles_dev: a guess of that length for the launch heuristics (-1: none)
     const RectDev* rects;  // device
     const RangeDev* ranges;
     int* kernel_id = nullptr;  // out (host): which instantiation ran
@@ -81,7 +83,8 @@ struct ConvLaunch {
 
 // Upper bound of the scratch a convolution launch can make use of.
 constexpr size_t kConvScratchBytes = (size_t)32 << 20;
-bool launch_conv_fast(const ConvLaunch& c, long n_units, hipStream_t st, hipError_t* err);
+// n_units: list length the launch must cover; n_hint: the length to tune for (equal unless the list is built on the GPU)
+bool launch_conv_fast(const ConvLaunch& c, long n_units, long n_hint, hipStream_t st, hipError_t* err);
 // Packed weights of a layer the 3x3 stride-1 GEMM kernel runs: [cout/16][cin*es/64][9][16][64 bytes], i.e. the
 // 64-byte channel runs that one load instruction brings into LDS are contiguous.  0 bytes: no packed form.
 size_t packed_weights_bytes(int k, int s, int cin, int cout, int dtype);
@@ -129,6 +132,56 @@ hipError_t launch_fc(const void* x, const void* w, const float* bias, void* out,
 // Producer tensors of a DC_CONCAT layer in channel order; returns their number (2..4).
 int concat_inputs(const dc_layer& l, int* ids);
 
+// ---- planning on the GPU (dc_plan.hip): Step 5 of Section 4 and the propagation of Section 5 without the host ------
+// The host path above reads the block mask back, plans and uploads; here three small kernels do the same from the
+// mask in device memory, so that a cached frame needs no host wait:
+//   plan_regions_kernel  one wavefront per stream: merge (Step 5), then every layer's row of Table 2 in turn
+//   plan_masks_kernel    per conv layer, stream and 256 units: the 16-bit mask of reusable pixels of every 4x4 unit
+//   plan_lists_kernel    compacts the units with a non-reusable pixel into the layer's list (stream-major, raster
+//                        order: the order of the host path) and leaves the list lengths and the work counters
+// The convolutions are then launched for the longest possible list and read its length from memory; the reusable
+// pixels are copied per unit from the masks (shifted_copy_units_kernel).
+constexpr int kPlanMaxTensors = 192;     // tensors of a stack the device tables hold
+constexpr int kPlanMaxRects = 256;       // rectangles per list (a longer list: the stream reuses nothing)
+constexpr int kPlanChunk = 256;          // units per workgroup of the mask / list kernels
+struct PlanLayerDev {                    // one layer; tensor i + 1 is its output
+    int32_t type, k, s, p, in0, in1, in2, in3, within, pad0, pad1, pad2;
+};
+struct PlanTensorDev { int32_t h, w, cum_stride, pad; };
+struct PlanConvDev {                     // one conv layer's share of the plan area (offsets in bytes from its start)
+    int32_t tensor, Hout, Wout, units_x, units_y, n_chunks, pad0, pad1;
+    int64_t umask_off, count_off, list_off, pad2;
+};
+// What the list kernel leaves for the host, per frame: {reusable blocks, overflowed streams, 0, 0}, then per conv
+// layer {reused pixels (int64), list length (int32), 0}.
+struct PlanStatsHead { int32_t n_reusable_blocks, n_overflow_streams, pad0, pad1; };
+struct PlanStatsConv { int64_t reused_px; int32_t n_units, pad; };
+struct PlanDev {                         // device addresses of one frame's plan, handed to the kernels by value
+    const PlanLayerDev* layers;
+    const PlanTensorDev* tensors;
+    const PlanConvDev* convs;
+    int32_t n_layers, n_convs, n_streams, cap;
+    dc_rect* rects;                      // [stream][tensor][cap]
+    int32_t* nrect;                      // [stream][tensor]
+    int32_t* dxy;                        // [stream][tensor][2]
+    int32_t* stream_info;                // [stream][2]: reusable blocks, 1 if a list overflowed
+    unsigned char* area;                 // base of the per-layer arrays (PlanConvDev offsets)
+    int32_t* n_units;                    // [conv]
+    void* stats;                         // PlanStatsHead + n_convs x PlanStatsConv; device memory or pinned host memory
+};
+hipError_t launch_plan(const PlanDev& P, const uint8_t* block_mask, const int32_t* gmv, int gh, int gw, int block,
+                       int extend_borders, int max_chunks, hipStream_t st);
+// One conv layer of the per-unit copy: out[p] = prev[p + d] for every pixel whose bit is set in its unit's mask.
+struct CopyUnitsLayer {
+    const void* prev;
+    void* out;
+    const uint16_t* umask;               // [stream][units_y][units_x]
+    int32_t tensor, Hout, Wout, units_x, units_y, vec_per_px, pad0, pad1;
+};
+constexpr int kCopyUnitsMaxLayers = 32;
+hipError_t launch_shifted_copy_units(const CopyUnitsLayer* layers, int n_layers, const int32_t* dxy, int n_tensors,
+                                     int n_streams, int vec_bytes, hipStream_t st);
+
 // Event pairs for kernel timing (measurement aid).
 struct Profile {
     std::vector<hipEvent_t> ev;   // 2 per slot: start, stop
@@ -156,6 +209,10 @@ struct Overlap {
     bool frame_recorded[2] = {false, false};          // that frame recorded frame_done
     std::vector<const void*> last_cur[2];             // [frame parity]: tensors_cur of that stream's last frame
     int frame_parity = 0;
+    // planning on the GPU: the planning kernels of a frame have read the block mask and the motion
+    hipEvent_t plan_done[2] = {nullptr, nullptr};
+    bool plan_recorded[2] = {false, false};
+    int last_plan = -1;                               // which of the two was recorded last
     // look-ahead matching: the arguments of a match already started for the next frame
     struct Prefetch {
         bool valid = false;

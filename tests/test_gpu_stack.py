@@ -22,9 +22,23 @@ def _elem_err(got, want):
     return float((np.abs(got - want) / np.maximum(np.abs(want), 1e-3 * scale)).max())
 
 
-def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
-              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False,
-              extend_borders=False):
+def _run_both(oracle, layers, videos, block, radius, bf16, in_place=False, device_plan=None, **kw):
+    """Every frame of every stream against the oracle, with the frame planned on the host and (unless in-place frames
+    are asked for, which only the host plans) once more with the frame planned on the GPU."""
+    modes = [False] if in_place else ([False, True] if device_plan is None else [bool(device_plan)])
+    first = None
+    for dp in modes:
+        res = _run_one(oracle, layers, videos, block, radius, bf16, in_place=in_place, device_plan=dp, **kw)
+        if first is None:
+            first = res
+        else:
+            assert res[1] == first[1]
+    return first
+
+
+def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
+             residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False,
+             extend_borders=False, device_plan=False):
     """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
     n, T, H, W, C = videos.shape
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale, input_shape=(H, W, C))
@@ -32,7 +46,8 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
     dt = binding.DC_BF16 if bf16 else binding.DC_F32
     runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
                                  want_regions=True, k_skip=k_skip, in_place=in_place, extend_borders=extend_borders,
-                                 match_method=binding.DC_MATCH_DIAMOND if diamond else binding.DC_MATCH_EXHAUSTIVE)
+                                 match_method=binding.DC_MATCH_DIAMOND if diamond else binding.DC_MATCH_EXHAUSTIVE,
+                                 device_plan=device_plan)
     streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry,
                              diamond=diamond, k_skip=k_skip, extend_borders=extend_borders)
                for _ in range(n)]
@@ -40,8 +55,9 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
     worst = worst_elem = 0.0
     reuse = []
     runner.in_place_frames = []
+    shapes = runner.shapes
     for t in range(T):
-        print(f"[stack] frame {t}/{T} n={n} {H}x{W} bf16={bf16}", flush=True)
+        print(f"[stack] frame {t}/{T} n={n} {H}x{W} bf16={bf16} planned on the {'GPU' if device_plan else 'host'}", flush=True)
         if t in resets:
             runner.reset()
             for s in streams:
@@ -50,6 +66,7 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
         torch.cuda.synchronize()
         runner.in_place_frames.append(bool(runner.last_in_place))
         got = [x.float().cpu().numpy() for x in tensors]
+        blocks = needed = 0
         for s in range(n):
             want = streams[s].step(videos[s, t])
             assert bool(runner.last_full) == bool(want["full"])
@@ -65,6 +82,12 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
                     assert regs[ti]["rects"].tolist() == want["rects"][ti].tolist(), (t, s, ti)
                     assert list(regs[ti]["dxy"]) == want["dxy"][ti].tolist()
                 reuse.append(float(m["mask"].mean()))
+                blocks += int(m["mask"].sum())
+                for li, L in enumerate(layers):
+                    if L["type"] == synth.CONV:
+                        ho, wo, _ = shapes[li + 1]
+                        reused = int(sum(int(r[2]) * int(r[3]) for r in want["rects"][li + 1]))
+                        needed += (ho * wo - reused) * L["k"] * L["k"] * runner.layers[li]["cin"] * L["cout"]
             for ti in (check_tensors or range(len(layers) + 1)):
                 g = got[ti][s]
                 if ti == 0:          # tensor 0 may carry zero padding channels
@@ -74,6 +97,10 @@ def _run_both(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bia
                 worst = max(worst, e)
                 worst_elem = max(worst_elem, _elem_err(g, want["tensors"][ti]))
                 assert e <= tol, (t, s, ti, e)
+        if not runner.last_full:     # the library's work counters against the oracle's masks and rectangles
+            st = runner.read_stats()
+            assert st.n_reusable_blocks == blocks and st.n_overflow_streams == 0
+            assert st.macs_needed == needed and st.macs_issued >= st.macs_needed
     print(f"[stack] worst error relative to the tensor's largest magnitude {worst:.3e} (bound {tol:g}); element-wise "
           f"with floor 1e-3 of that magnitude {worst_elem:.3e}; mean block reuse {np.mean(reuse) if reuse else 0:.3f}", flush=True)
     return runner, reuse
@@ -99,7 +126,8 @@ def test_tiny_exact_shift_equals_full_forward_on_gpu(oracle):
     d1, d2 = torch.from_numpy(f1[None]).to(DEV), torch.from_numpy(f2[None]).to(DEV)
     r.step(d1)
     cached = [t.clone() for t in r.step(d2)]
-    assert r.stats.n_reusable_blocks >= 40
+    torch.cuda.synchronize()
+    assert r.read_stats().n_reusable_blocks >= 40
     r.reset()
     full = r.step(d2)
     for a, b in zip(cached, full):
@@ -309,7 +337,8 @@ def test_darknet19_416_bf16_cached_frame_and_scene_cut(oracle):
     assert len(reuse) == 2 and all(0.45 < r < 0.6 for r in reuse)
 
 
-def test_throughput_mode_64_streams_bf16_sampled(oracle):
+@pytest.mark.parametrize("device_plan", [False, True])
+def test_throughput_mode_64_streams_bf16_sampled(oracle, device_plan):
     """configs[4] launch configuration: 64 streams in one batch, VGG-16-style, bf16.  Three streams are
     followed by the oracle over three time steps (everything compared); the others are checked for
     bit-exact match results on the cached steps."""
@@ -317,7 +346,8 @@ def test_throughput_mode_64_streams_bf16_sampled(oracle):
     n, T = 64, 3
     videos = np.stack([synth.panning_video(5000 + s, n_frames=T) for s in range(n)])
     ws, bs = synth.he_weights(layers, 1)
-    r = binding.StackRunner(layers, ws, bs, n, 224, 224, 3, block=16, radius=16, dtype=binding.DC_BF16, want_regions=True)
+    r = binding.StackRunner(layers, ws, bs, n, 224, 224, 3, block=16, radius=16, dtype=binding.DC_BF16, want_regions=True,
+                            device_plan=device_plan)
     followed = [0, 31, 63]
     refs = {s: oracle.Stream(layers, ws, bs, 224, 224, 3, block=16, radius=16, bf16=True) for s in followed}
     dv = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
@@ -340,6 +370,48 @@ def test_throughput_mode_64_streams_bf16_sampled(oracle):
             for s in range(0, n, 7):
                 m = oracle.match_blocks(videos[s, t], videos[s, t - 1], 16, 16, synth.max_block_ssd(16))
                 assert np.array_equal(masks[s], m["mask"]) and gmv[s].tolist() == m["gmv"].tolist()
+
+
+def test_border_case_planned_on_the_gpu(oracle):
+    """extend_borders with the frame planned on the GPU (copy path: in-place frames are the host's)."""
+    layers = synth.vgg16()[:10]
+    video = np.stack([_static_then_moving(700 + s, 96, 96, 3, 2) for s in range(2)])
+    _run_both(oracle, layers, video, 16, 8, True, extend_borders=True, device_plan=True)
+
+
+@pytest.mark.parametrize("n_streams,bf16", [(1, False), (3, True)])
+def test_frames_planned_on_the_gpu_without_any_wait(oracle, n_streams, bf16):
+    """Frames planned on the GPU, two in flight, issued back to back: the host never waits for a frame (no regions
+    are asked for), expiry and a scene cut included; every tensor of every frame is cloned on the caller's stream and
+    compared with the oracle at the end, and the work counters of the last frame are read once everything is done."""
+    layers = synth.vgg16()[:10]
+    T, H, W = 9, 96, 96
+    videos = np.stack([synth.panning_video(6100 + s, n_frames=T, H=H, W=W, fg=((24, 24),), margin=32) for s in range(n_streams)])
+    ws, bs = synth.he_weights(layers, 1, bias_scale=0.05)
+    dt = binding.DC_BF16 if bf16 else binding.DC_F32
+    r = binding.StackRunner(layers, ws, bs, n_streams, H, W, 3, block=16, radius=8, dtype=dt, expiry=4, device_plan=True)
+    refs = [oracle.Stream(layers, ws, bs, H, W, 3, block=16, radius=8, bf16=bf16, expiry=4) for _ in range(n_streams)]
+    dv = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
+    torch.cuda.synchronize()
+    kept = []
+    for t in range(T):
+        if t == 6:
+            r.reset()
+        kept.append([x.clone() for x in r.step(dv[t])])
+    torch.cuda.synchronize()
+    tol = 2e-2 if bf16 else 1e-4
+    last_blocks = 0
+    for t in range(T):
+        for s in range(n_streams):
+            if t == 6:
+                refs[s].reset()
+            want = refs[s].step(videos[s, t])
+            for ti in range(1, len(layers) + 1):
+                assert _rel_err(kept[t][ti][s].float().cpu().numpy(), want["tensors"][ti]) <= tol, (t, s, ti)
+            if t == T - 1:
+                assert not want["full"]
+                last_blocks += int(want["match"]["mask"].sum())
+    assert r.read_stats().n_reusable_blocks == last_blocks
 
 
 @pytest.mark.parametrize("net,size,bf16", [("vgg16", 96, False), ("resnet", 64, True)])
