@@ -348,7 +348,8 @@ int32_t dc_overlap_create(void** overlap) {
     for (int i = 0; i < 2 && ok; ++i) ok = hipStreamCreateWithFlags(&o->work[i], hipStreamNonBlocking) == hipSuccess;
     for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&o->frame_done[i], hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&o->match_done, hipEventDisableTiming) == hipSuccess;
-    for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&o->plan_done[i], hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 3 && ok; ++i) ok = hipEventCreateWithFlags(&o->plan_done[i], hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 3 && ok; ++i) ok = hipEventCreateWithFlags(&o->area_free[i], hipEventDisableTiming) == hipSuccess;
     if (!ok) {
         (void)dc_overlap_destroy(o);
         return DC_ERR_HIP;
@@ -365,9 +366,12 @@ int32_t dc_overlap_destroy(void* overlap) {
         if (o->work[i]) (void)hipStreamSynchronize(o->work[i]);
         if (o->upload_done[i]) (void)hipEventDestroy(o->upload_done[i]);
         if (o->frame_done[i]) (void)hipEventDestroy(o->frame_done[i]);
-        if (o->plan_done[i]) (void)hipEventDestroy(o->plan_done[i]);
         for (hipEvent_t e : o->layer_done[i]) (void)hipEventDestroy(e);
         if (o->work[i]) (void)hipStreamDestroy(o->work[i]);
+    }
+    for (int i = 0; i < 3; ++i) {
+        if (o->plan_done[i]) (void)hipEventDestroy(o->plan_done[i]);
+        if (o->area_free[i]) (void)hipEventDestroy(o->area_free[i]);
     }
     if (o->match_done) (void)hipEventDestroy(o->match_done);
     if (o->aux) (void)hipStreamDestroy(o->aux);
@@ -390,9 +394,6 @@ int32_t dc_prefetch_match(void* overlap, const uint8_t* frames_next, const uint8
         DC_TRY_HIP(hipStreamSynchronize(ov->aux));
         ov->prefetch.valid = false;
     }
-    // planning kernels of the last frame may not have read its mask and motion yet (planning on the GPU)
-    if (ov->last_plan >= 0 && ov->plan_recorded[ov->last_plan])
-        DC_TRY_HIP(hipStreamWaitEvent(ov->aux, ov->plan_done[ov->last_plan], 0));
     int rc = dc_match_blocks_opt(frames_next, frames_cur, n_streams, H, W, C, block, radius, match_options, max_block_ssd,
                                  mv, best_ssd, global_mv, n_pass, block_mask, ov->aux);
     if (rc) return rc;
@@ -420,9 +421,9 @@ int32_t dc_overlap_pipeline(void* overlap, int32_t frames_in_flight) {
         o->recorded[i].clear();
         o->last_cur[i].clear();
         o->frame_recorded[i] = false;
-        o->plan_recorded[i] = false;
     }
-    o->last_plan = -1;
+    if (o->aux) DC_TRY_HIP(hipStreamSynchronize(o->aux));
+    for (int i = 0; i < 3; ++i) o->area_recorded[i] = false;
     o->pipeline = frames_in_flight == 2;
     return DC_OK;
 }
@@ -736,7 +737,7 @@ int32_t dc_stack_workspace_bytes(const dc_layer* layers, int32_t n_layers, int32
     try {                                           // planning on the GPU lays the same area out differently
         DevPlanLayout dl;
         device_plan_layout(layers, n_layers, hs, ws, n_streams, max_rects, dl);
-        if (dl.ok && 2 * align_up(dl.table_bytes, 256) + 2 * dl.frame_bytes > plans) plans = 2 * align_up(dl.table_bytes, 256) + 2 * dl.frame_bytes;
+        if (dl.ok && 3 * (align_up(dl.table_bytes, 256) + dl.frame_bytes) > plans) plans = 3 * (align_up(dl.table_bytes, 256) + dl.frame_bytes);
     } catch (const std::bad_alloc&) {
         return DC_ERR_WORKSPACE;
     }
@@ -988,7 +989,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         } catch (const std::bad_alloc&) {
             return DC_ERR_WORKSPACE;
         }
-        devplan = dl.ok && 2 * align_up(dl.table_bytes, 256) + 2 * dl.frame_bytes <= ws_dev_bytes - 2 * kConvScratchBytes &&
+        devplan = dl.ok && 3 * (align_up(dl.table_bytes, 256) + dl.frame_bytes) <= ws_dev_bytes - 2 * kConvScratchBytes &&
                   dl.table_bytes <= kDevHostRegion - 3 * kDevHostSlot;
     }
     if (devplan) {
@@ -1008,7 +1009,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             std::memcpy(tables.data() + dl.off_tensors, dl.tensors.data(), dl.tensors.size() * sizeof(PlanTensorDev));
             if (!dl.convs.empty()) std::memcpy(tables.data() + dl.off_convs, dl.convs.data(), dl.convs.size() * sizeof(PlanConvDev));
             if (std::memcmp(staging, tables.data(), dl.table_bytes) != 0) {
-                if (pipe) { DC_TRY_HIP(hipStreamSynchronize(ov->work[0])); DC_TRY_HIP(hipStreamSynchronize(ov->work[1])); }
+                if (ov) DC_TRY_HIP(hipStreamSynchronize(ov->aux));
                 DC_TRY_HIP(hipStreamSynchronize(st));
                 std::memcpy(staging, tables.data(), dl.table_bytes);
             }
@@ -1026,10 +1027,16 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             hdr->conv[c] = DevHostConv{dl.conv_layer[c], (int32_t)(l.cout * dtype_size(dtype)), (int64_t)l.k * l.k * l.cin * l.cout,
                                        (int64_t)n_streams * dl.convs[c].Hout * dl.convs[c].Wout};
         }
-        // one copy of the tables per frame in flight, so that a frame never writes what the other one's kernels read
+        // With an overlap handle the matching and the planning run on the handle's stream, ahead of the layers: they
+        // depend on the frames only, so they are done while the previous frame's layers still run, and the frame's
+        // own stream only waits for the plan.  Three plan areas (tables included) take turns: two frames in flight
+        // and the one being planned.
+        const int area = ov ? ov->plan_counter % 3 : 0;
+        hipStream_t pst = ov ? ov->aux : st;
+        if (ov && ov->area_recorded[area]) DC_TRY_HIP(hipStreamWaitEvent(pst, ov->area_free[area], 0));
         const size_t table_slot = align_up(dl.table_bytes, 256);
-        unsigned char* const table_dev = static_cast<unsigned char*>(ws_dev) + (size_t)fp * table_slot;
-        DC_TRY_HIP(upload_plans(table_dev, staging, dl.table_bytes, ws_host, st));
+        unsigned char* const table_dev = static_cast<unsigned char*>(ws_dev) + (size_t)area * (table_slot + dl.frame_bytes);
+        DC_TRY_HIP(upload_plans(table_dev, staging, dl.table_bytes, ws_host, pst));
         // list lengths of the last frame whose counters have arrived: a guess of this frame's, for the launch shapes only
         {
             const PlanStatsConv* seen = reinterpret_cast<const PlanStatsConv*>(slots + (size_t)hdr->last_slot * kDevHostSlot + sizeof(PlanStatsHead));
@@ -1039,7 +1046,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             }
         }
         const int slot = hdr->last_slot ^ 1;
-        unsigned char* const frame = static_cast<unsigned char*>(ws_dev) + 2 * table_slot + (size_t)fp * dl.frame_bytes;
+        unsigned char* const frame = table_dev + table_slot;
         pd.layers = reinterpret_cast<const PlanLayerDev*>(table_dev);
         pd.tensors = reinterpret_cast<const PlanTensorDev*>(table_dev + dl.off_tensors);
         pd.convs = reinterpret_cast<const PlanConvDev*>(table_dev + dl.off_convs);
@@ -1056,8 +1063,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                          : frame + dl.off_stats;
         DC_TRY_HIP(wait_readers(0));
         DC_TRY_HIP(launch_frame_to_tensor(frames_cur, tensors_cur[0], (size_t)n_streams * H * W, C, c_tensor, dtype, st));
-        // the match buffers are shared by consecutive frames: the other frame's planning kernels must have read them
-        if (pipe && ov->plan_recorded[1 - fp]) DC_TRY_HIP(hipStreamWaitEvent(st, ov->plan_done[1 - fp], 0));
+        // (the match buffers are shared by consecutive frames: their matching and planning kernels follow one another
+        // on one stream)
         bool prefetched = false;
         if (ov) {
             prefetched = pf.valid && pf.cur == frames_cur && pf.prev == frames_prev && pf.mv == mv &&
@@ -1065,23 +1072,19 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                          pf.ws_host == ws_host && pf.n_streams == n_streams && pf.H == H && pf.W == W && pf.C == C &&
                          pf.block == block && pf.radius == radius && pf.max_block_ssd == max_block_ssd &&
                          pf.method == match_options->method && pf.k_skip == match_options->k_skip;
-            if (pf.valid && !prefetched) DC_TRY_HIP(hipStreamSynchronize(ov->aux));   // let the stale match finish first
         }
-        if (prefetched) {
-            DC_TRY_HIP(hipStreamWaitEvent(st, ov->match_done, 0));
-        } else {
+        if (!prefetched) {     // (a match started ahead of time is on the same stream: the plan follows it)
             rc = dc_match_blocks_opt(frames_cur, frames_prev, n_streams, H, W, C, block, radius, match_options,
-                                     max_block_ssd, mv, best_ssd, global_mv, n_pass, block_mask, st);
+                                     max_block_ssd, mv, best_ssd, global_mv, n_pass, block_mask, pst);
             if (rc) return rc;
         }
-        DC_TRY_HIP(launch_plan(pd, block_mask, global_mv, gh, gw, block, match_options->extend_borders, dl.max_chunks, st));
+        DC_TRY_HIP(launch_plan(pd, block_mask, global_mv, gh, gw, block, match_options->extend_borders, dl.max_chunks, pst));
         if (!alias)
             DC_TRY_HIP(hipMemcpyAsync(slot_host, frame + dl.off_stats, sizeof(PlanStatsHead) + dl.convs.size() * sizeof(PlanStatsConv),
-                                      hipMemcpyDeviceToHost, st));
+                                      hipMemcpyDeviceToHost, pst));
         if (ov) {
-            DC_TRY_HIP(hipEventRecord(ov->plan_done[fp], st));
-            ov->plan_recorded[fp] = true;
-            ov->last_plan = fp;
+            DC_TRY_HIP(hipEventRecord(ov->plan_done[area], pst));
+            DC_TRY_HIP(hipStreamWaitEvent(st, ov->plan_done[area], 0));
         }
         hdr->last_slot = slot;
         hdr->n_blocks = (int32_t)nb;
@@ -1090,7 +1093,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             try {
                 std::vector<int32_t> h_n((size_t)n_streams * nt), h_d((size_t)n_streams * nt * 2);
                 std::vector<dc_rect> h_r((size_t)n_streams * nt * dl.cap);
-                DC_TRY_HIP(hipStreamSynchronize(st));
+                DC_TRY_HIP(hipStreamSynchronize(pst));
                 DC_TRY_HIP(hipMemcpy(h_n.data(), pd.nrect, h_n.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
                 DC_TRY_HIP(hipMemcpy(h_d.data(), pd.dxy, h_d.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
                 DC_TRY_HIP(hipMemcpy(h_r.data(), pd.rects, h_r.size() * sizeof(dc_rect), hipMemcpyDeviceToHost));
@@ -1436,6 +1439,12 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             DC_TRY_HIP(hipEventRecord(ov->layer_done[fp][i], st));
             ov->recorded[fp][i] = 1;
         }
+    }
+    if (devplan && ov) {      // the frame's layers are done with its plan area
+        const int area = ov->plan_counter % 3;
+        DC_TRY_HIP(hipEventRecord(ov->area_free[area], st));
+        ov->area_recorded[area] = true;
+        ov->plan_counter = (ov->plan_counter + 1) % 3;
     }
     if (pipe) {
         // the caller's stream sees the frame complete; the next frame goes to the other work stream

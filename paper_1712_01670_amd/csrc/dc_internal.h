@@ -176,7 +176,8 @@ struct CopyUnitsLayer {
     const void* prev;
     void* out;
     const uint16_t* umask;               // [stream][units_y][units_x]
-    int32_t tensor, Hout, Wout, units_x, units_y, vec_per_px, pad0, pad1;
+    int32_t tensor, Hout, Wout, units_x, units_y, vec_per_px;
+    int32_t units_per_group, vec_shift;   // set by the launcher: units per workgroup; log2(vec_per_px) or -1
 };
 constexpr int kCopyUnitsMaxLayers = 32;
 hipError_t launch_shifted_copy_units(const CopyUnitsLayer* layers, int n_layers, const int32_t* dxy, int n_tensors,
@@ -209,10 +210,12 @@ struct Overlap {
     bool frame_recorded[2] = {false, false};          // that frame recorded frame_done
     std::vector<const void*> last_cur[2];             // [frame parity]: tensors_cur of that stream's last frame
     int frame_parity = 0;
-    // planning on the GPU: the planning kernels of a frame have read the block mask and the motion
-    hipEvent_t plan_done[2] = {nullptr, nullptr};
-    bool plan_recorded[2] = {false, false};
-    int last_plan = -1;                               // which of the two was recorded last
+    // planning on the GPU: matching and planning kernels of consecutive frames run on `aux`, ahead of the layers;
+    // a frame's plan lives in one of three areas (two frames in flight and one being planned)
+    hipEvent_t plan_done[3] = {nullptr, nullptr, nullptr};   // the plan in that area is complete
+    hipEvent_t area_free[3] = {nullptr, nullptr, nullptr};   // the layers of the frame that used the area are done
+    bool area_recorded[3] = {false, false, false};
+    int plan_counter = 0;
     // look-ahead matching: the arguments of a match already started for the next frame
     struct Prefetch {
         bool valid = false;

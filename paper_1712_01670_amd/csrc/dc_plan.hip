@@ -11,6 +11,8 @@
 //   LRN over pixels: x + r, y + r, w - 2r, h - 2r;  add / concat: pairwise overlaps;  FC / softmax: nothing
 //   every tensor has one source offset round(M / cumulative stride); rectangles are clipped so that the source
 //   stays inside the map
+#include <atomic>
+
 #include "dc_internal.h"
 
 namespace dc {
@@ -19,7 +21,11 @@ namespace {
 
 struct SpanD { int lo, hi; };   // half-open [lo, hi)
 
-__device__ __forceinline__ int floor_div(int a, int b) {   // b > 0
+// floor(a / b), b > 0.  Strides are 1, 2 or 4 in every stack at hand: those divide by shifting (an arithmetic shift
+// rounds towards minus infinity), which keeps the integer division out of the layer loop's dependency chain.
+__device__ __forceinline__ int floor_div(int a, int b) {
+    if (b == 1) return a;
+    if ((b & (b - 1)) == 0) return a >> (__ffs(b) - 1);
     const int q = a / b, r = a % b;
     return r < 0 ? q - 1 : q;
 }
@@ -43,57 +49,90 @@ __device__ __forceinline__ SpanD windows_inside_ext(SpanD in, int k, int s, int 
 __device__ __forceinline__ SpanD source_inside(SpanD cur, int d, int size) {
     return both(both(cur, SpanD{0, size}), SpanD{-d, size - d});
 }
+// num / den rounded to nearest, halves away from zero (|num| and den are far below 2^30)
 __device__ __forceinline__ int round_half_away(int num, int den) {
-    const long long mag = num < 0 ? -(long long)num : num;
-    const long long q = (2 * mag + den) / (2 * (long long)den);
-    return (int)(num < 0 ? -q : q);
+    const unsigned mag = (unsigned)(num < 0 ? -num : num);
+    const unsigned q = (unsigned)floor_div((int)(2u * mag + (unsigned)den), 2 * den);
+    return num < 0 ? -(int)q : (int)q;
 }
 
-// A rectangle another lane of this wavefront stored earlier in this kernel: read at device scope, past the CU's
-// vector cache (the fence after every layer has made the stores visible there).
-__device__ __forceinline__ dc_rect load_rect(const dc_rect* p) {
-    const int* q = reinterpret_cast<const int*>(p);
-    dc_rect r;
-    r.x = __hip_atomic_load(q + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    r.y = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    r.w = __hip_atomic_load(q + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    r.h = __hip_atomic_load(q + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return r;
-}
-
-// Appends the rectangles (xs, ys) of the lanes with `ok` to `list` in lane order; returns the new length.
-__device__ __forceinline__ int append(dc_rect* list, int n, int cap, bool ok, SpanD xs, SpanD ys, int lane, bool& over) {
+// Appends the rectangles (xs, ys) of the lanes with `ok` to `list` (LDS) in lane order; returns the new length.
+// `room` is what the list may hold (the per-list bound, or what is left of the pool).
+__device__ __forceinline__ int append(dc_rect* list, int n, int room, bool ok, SpanD xs, SpanD ys, int lane, bool& over) {
     const unsigned long long b = __ballot(ok);
     const int pos = n + __popcll(b & ((1ull << lane) - 1ull));
-    if (ok && pos < cap) list[pos] = dc_rect{xs.lo, ys.lo, xs.hi - xs.lo, ys.hi - ys.lo};
+    if (ok && pos < room) list[pos] = dc_rect{xs.lo, ys.lo, xs.hi - xs.lo, ys.hi - ys.lo};
     n += __popcll(b);
-    if (n > cap) { over = true; n = cap; }
+    if (n > room) { over = true; n = room; }
     return n;
 }
 
+// One wavefront per stream.  All lists live in LDS while the stream is planned (a pool that the lists of the
+// tensors share, filled front to back: a list is complete before the next one starts, and a layer only reads the
+// lists of earlier tensors); every finished list is also written to its place in device memory for the kernels
+// that follow.  A stream whose lists do not fit (one list beyond `cap`, or all of them beyond the pool) reuses
+// nothing in this frame.
 __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8_t* __restrict__ block_mask,
-                                                          const int32_t* __restrict__ gmv, int gh, int gw, int B, int ext_opt) {
+                                                          const int32_t* __restrict__ gmv, int gh, int gw, int B, int ext_opt,
+                                                          int pool_rects) {
     const int stream = blockIdx.x, lane = threadIdx.x;
     const int nt = P.n_layers + 1, cap = P.cap;
-    __shared__ int s_n[kPlanMaxTensors];
+    __shared__ int s_n[kPlanMaxTensors], s_off[kPlanMaxTensors], s_dxy[2 * kPlanMaxTensors];
+    __shared__ unsigned long long s_flat[66];      // the block mask as one bit string, 64 blocks per word
     __shared__ dc_rect s_acc[2][kPlanMaxRects];
+    // the layer and tensor tables, fetched once: read from memory inside the layer loop, every layer would wait for
+    // two dependent loads
+    __shared__ PlanLayerDev s_layers[kPlanMaxTensors];
+    __shared__ PlanTensorDev s_tensors[kPlanMaxTensors];
+    extern __shared__ __align__(16) unsigned char s_dyn[];
+    dc_rect* const pool = reinterpret_cast<dc_rect*>(s_dyn);
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(P.layers);
+        uint4* dst = reinterpret_cast<uint4*>(s_layers);
+        for (int j = lane; j < P.n_layers * 3; j += 64) dst[j] = src[j];          // 48 bytes per layer
+        const uint4* tsrc = reinterpret_cast<const uint4*>(P.tensors);
+        uint4* tdst = reinterpret_cast<uint4*>(s_tensors);
+        for (int j = lane; j <= P.n_layers; j += 64) tdst[j] = tsrc[j];           // 16 bytes per tensor
+    }
     const int mx = gmv[2 * stream], my = gmv[2 * stream + 1];
     const bool ext = ext_opt != 0 && mx == 0 && my == 0;
-    dc_rect* const lists = P.rects + (size_t)stream * nt * cap;
-    int32_t* const dxy = P.dxy + (size_t)stream * nt * 2;
     bool over = false;
+    int top = 0;                                   // rectangles of the pool in use (wavefront-uniform)
 
     // ---- Step 5: lane r holds row r of the block grid as a bit string (gh, gw <= 64) ----
+    // (the mask bytes are read 64 at a time, one per lane, four loads in flight; lane r then cuts its gw bits out)
     unsigned long long open = 0;
-    if (lane < gh) {
-        const uint8_t* m = block_mask + ((size_t)stream * gh + lane) * gw;
-        for (int bx = 0; bx < gw; ++bx)
-            if (m[bx]) open |= 1ull << bx;
+    {
+        const uint8_t* m = block_mask + (size_t)stream * gh * gw;
+        const int nb = gh * gw;
+        for (int j0 = 0; j0 < nb; j0 += 256) {
+            uint8_t v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int at = j0 + q * 64 + lane;
+                v[q] = m[at < nb ? at : 0];
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int at = j0 + q * 64 + lane;
+                const unsigned long long bits = __ballot(at < nb && v[q] != 0);
+                if (lane == 0 && j0 + q * 64 < nb + 64) s_flat[(j0 >> 6) + q] = bits;
+            }
+        }
+        __syncthreads();
+        if (lane < gh) {
+            const int off = lane * gw, w = off >> 6, sh = off & 63;
+            unsigned long long bits = s_flat[w] >> sh;
+            if (sh) bits |= s_flat[w + 1] << (64 - sh);
+            open = gw >= 64 ? bits : bits & ((1ull << gw) - 1ull);
+        }
     }
     int reusable = __popcll(open);
     for (int off = 32; off > 0; off >>= 1) reusable += __shfl_xor(reusable, off);
-    const PlanTensorDev t0 = P.tensors[0];
+    __syncthreads();
+    const PlanTensorDev t0 = s_tensors[0];
     int n0 = 0;
+    const int room0 = cap < pool_rects ? cap : pool_rects;
     for (int by0 = 0; by0 < gh; ++by0) {
         const int by = __builtin_amdgcn_readfirstlane(by0);
         for (;;) {
@@ -114,8 +153,8 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
             const SpanD xs = source_inside(SpanD{bx * B, (bx + run) * B}, mx, t0.w);
             const SpanD ys = source_inside(SpanD{by * B, y1 * B}, my, t0.h);
             if (!none(xs) && !none(ys)) {
-                if (n0 < cap) {
-                    if (lane == 0) lists[n0] = dc_rect{xs.lo, ys.lo, xs.hi - xs.lo, ys.hi - ys.lo};
+                if (n0 < room0) {
+                    if (lane == 0) pool[n0] = dc_rect{xs.lo, ys.lo, xs.hi - xs.lo, ys.hi - ys.lo};
                     ++n0;
                 } else {
                     over = true;
@@ -123,37 +162,38 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
             }
         }
     }
-    if (lane == 0) { s_n[0] = n0; dxy[0] = mx; dxy[1] = my; }
-    __threadfence();
+    if (lane == 0) { s_n[0] = n0; s_off[0] = 0; s_dxy[0] = mx; s_dxy[1] = my; }
+    top = n0;
     __syncthreads();
 
     // ---- Table 2, layer by layer ----
     for (int i = 0; i < P.n_layers; ++i) {
-        const PlanLayerDev L = P.layers[i];
-        const PlanTensorDev ta = P.tensors[L.in0], tt = P.tensors[i + 1];
+        const PlanLayerDev L = s_layers[i];
+        const PlanTensorDev ta = s_tensors[L.in0], tt = s_tensors[i + 1];
         const int dx = round_half_away(mx, tt.cum_stride), dy = round_half_away(my, tt.cum_stride);
-        const dc_rect* la = lists + (size_t)L.in0 * cap;
-        dc_rect* lt = lists + (size_t)(i + 1) * cap;
+        const dc_rect* la = pool + s_off[L.in0];
+        dc_rect* lt = pool + top;
+        const int room = cap < pool_rects - top ? cap : pool_rects - top;
         const int na = s_n[L.in0];
         int n_out = 0;
         const bool windowed = L.type == DC_CONV || L.type == DC_MAXPOOL || L.type == DC_AVGPOOL;
         if (L.type == DC_FC || L.type == DC_SOFTMAX) {
             // every output depends on every input: nothing is reusable from here on
         } else if (L.type == DC_ADD) {
-            const dc_rect* lb = lists + (size_t)L.in1 * cap;
+            const dc_rect* lb = pool + s_off[L.in1];
             const int nb = s_n[L.in1];
             for (int ia = 0; ia < na; ++ia) {
-                const dc_rect ra = load_rect(la + ia);
+                const dc_rect ra = la[ia];
                 for (int base = 0; base < nb; base += 64) {
                     const int ib = base + lane;
                     bool ok = ib < nb;
-                    const dc_rect rb = ok ? load_rect(lb + ib) : dc_rect{0, 0, 0, 0};
+                    const dc_rect rb = ok ? lb[ib] : dc_rect{0, 0, 0, 0};
                     SpanD xs = both(SpanD{ra.x, ra.x + ra.w}, SpanD{rb.x, rb.x + rb.w});
                     SpanD ys = both(SpanD{ra.y, ra.y + ra.h}, SpanD{rb.y, rb.y + rb.h});
                     ok = ok && !none(xs) && !none(ys);
                     xs = source_inside(xs, dx, tt.w); ys = source_inside(ys, dy, tt.h);
                     ok = ok && !none(xs) && !none(ys);
-                    n_out = append(lt, n_out, cap, ok, xs, ys, lane, over);
+                    n_out = append(lt, n_out, room, ok, xs, ys, lane, over);
                 }
             }
         } else if (L.type == DC_CONCAT) {
@@ -163,10 +203,10 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
             int m = 2;
             while (m < 4 && ids[m] >= 0) ++m;
             int cur = 0, n_acc = na < kPlanMaxRects ? na : kPlanMaxRects;
-            for (int j = lane; j < n_acc; j += 64) s_acc[0][j] = load_rect(la + j);
+            for (int j = lane; j < n_acc; j += 64) s_acc[0][j] = la[j];
             __syncthreads();
             for (int j = 1; j < m; ++j) {
-                const dc_rect* lb = lists + (size_t)ids[j] * cap;
+                const dc_rect* lb = pool + s_off[ids[j]];
                 const int nb = s_n[ids[j]];
                 int nn = 0;
                 for (int ia = 0; ia < n_acc; ++ia) {
@@ -174,7 +214,7 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
                     for (int base = 0; base < nb; base += 64) {
                         const int ib = base + lane;
                         bool ok = ib < nb;
-                        const dc_rect rb = ok ? load_rect(lb + ib) : dc_rect{0, 0, 0, 0};
+                        const dc_rect rb = ok ? lb[ib] : dc_rect{0, 0, 0, 0};
                         const SpanD xs = both(SpanD{ra.x, ra.x + ra.w}, SpanD{rb.x, rb.x + rb.w});
                         const SpanD ys = both(SpanD{ra.y, ra.y + ra.h}, SpanD{rb.y, rb.y + rb.h});
                         ok = ok && !none(xs) && !none(ys);
@@ -192,7 +232,7 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
                 const SpanD xs = source_inside(SpanD{r.x, r.x + r.w}, dx, tt.w);
                 const SpanD ys = source_inside(SpanD{r.y, r.y + r.h}, dy, tt.h);
                 ok = ok && !none(xs) && !none(ys);
-                n_out = append(lt, n_out, cap, ok, xs, ys, lane, over);
+                n_out = append(lt, n_out, room, ok, xs, ys, lane, over);
             }
         } else {
             const int radius = (L.k - 1) / 2;
@@ -200,7 +240,7 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
             for (int base = 0; base < na; base += 64) {
                 const int ia = base + lane;
                 bool ok = ia < na;
-                const dc_rect r = ok ? load_rect(la + ia) : dc_rect{0, 0, 0, 0};
+                const dc_rect r = ok ? la[ia] : dc_rect{0, 0, 0, 0};
                 SpanD xs{r.x, r.x + r.w}, ys{r.y, r.y + r.h};
                 if (windowed) {
                     xs = ext ? windows_inside_ext(xs, L.k, L.s, L.p, ta.w) : windows_inside(xs, L.k, L.s, L.p);
@@ -217,15 +257,22 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
                 ok = ok && !none(xs) && !none(ys);
                 xs = source_inside(xs, dx, tt.w); ys = source_inside(ys, dy, tt.h);
                 ok = ok && !none(xs) && !none(ys);
-                n_out = append(lt, n_out, cap, ok, xs, ys, lane, over);
+                n_out = append(lt, n_out, room, ok, xs, ys, lane, over);
             }
         }
-        __threadfence();
-        __syncthreads();
-        if (lane == 0) { s_n[i + 1] = n_out; dxy[2 * (i + 1)] = dx; dxy[2 * (i + 1) + 1] = dy; }
-        __syncthreads();
+        if (lane == 0) { s_n[i + 1] = n_out; s_off[i + 1] = top; s_dxy[2 * (i + 1)] = dx; s_dxy[2 * (i + 1) + 1] = dy; }
+        __syncthreads();                               // the list is complete in LDS: later layers read it
+        top += n_out;
     }
-    // a stream one of whose lists did not fit reuses nothing in this frame
+    // Everything goes to device memory at the end, in one pass without a barrier (a store inside the layer loop would
+    // be waited for at the next barrier).  A stream one of whose lists did not fit reuses nothing in this frame.
+    dc_rect* const lists = P.rects + (size_t)stream * nt * cap;
+    for (int t = 0; t < nt && !over; ++t) {
+        const dc_rect* src = pool + s_off[t];
+        dc_rect* out = lists + (size_t)t * cap;
+        for (int j = lane; j < s_n[t]; j += 64) out[j] = src[j];
+    }
+    for (int t = lane; t < 2 * nt; t += 64) P.dxy[(size_t)stream * nt * 2 + t] = s_dxy[t];
     for (int t = lane; t < nt; t += 64) P.nrect[(size_t)stream * nt + t] = over ? 0 : s_n[t];
     if (lane == 0) { P.stream_info[2 * stream] = reusable; P.stream_info[2 * stream + 1] = over ? 1 : 0; }
 }
@@ -335,6 +382,7 @@ __global__ __launch_bounds__(kPlanChunk) void plan_lists_kernel(PlanDev P) {
     }
 }
 
+constexpr int kCopyUnitsPerGroup = 64;     // most units a workgroup of the per-unit copy takes (a power of two)
 struct CopyUnitsArgs {
     CopyUnitsLayer L[kCopyUnitsMaxLayers];
     const int32_t* dxy;
@@ -342,48 +390,58 @@ struct CopyUnitsArgs {
 };
 
 // Section 5 "Reuse", step 1, from the unit masks: every pixel whose bit is set receives the previous frame's
-// value at +(dx, dy).  A workgroup takes 16 units of one stream and layer; consecutive threads take consecutive
-// vectors of a pixel, then the next pixel of the unit's row (contiguous in memory), four items per thread in flight.
+// value at +(dx, dy).  A workgroup takes UPB consecutive units of one stream and layer (UPB chosen by the launcher so
+// that a thread has about four 16-byte items); consecutive threads take consecutive vectors of a pixel, then the
+// next pixel of the unit's row (contiguous in memory); the four items of a thread are loaded before any is stored.
 template <typename V>
 __global__ __launch_bounds__(256) void shifted_copy_units_kernel(CopyUnitsArgs A) {
     const CopyUnitsLayer& L = A.L[blockIdx.z];
     const int stream = blockIdx.y, tid = threadIdx.x;
-    const int units = L.units_x * L.units_y, u0 = blockIdx.x * 16;
+    const int units = L.units_x * L.units_y, upb = L.units_per_group, u0 = blockIdx.x * upb;
     if (u0 >= units) return;
-    __shared__ unsigned short s_m[16];
+    __shared__ unsigned short s_m[kCopyUnitsPerGroup];
+    __shared__ int s_px0[kCopyUnitsPerGroup];          // pixel index (within the stream's map) of the unit's first pixel
     __shared__ int s_any;
     if (tid == 0) s_any = 0;
     __syncthreads();
-    if (tid < 16) {
-        const unsigned short m = u0 + tid < units ? L.umask[(size_t)stream * units + u0 + tid] : (unsigned short)0;
+    if (tid < upb) {
+        const int u = u0 + tid;
+        const unsigned short m = u < units ? L.umask[(size_t)stream * units + u] : (unsigned short)0;
+        const int ty = u / L.units_x, tx = u - ty * L.units_x;
         s_m[tid] = m;
+        s_px0[tid] = ty * 4 * L.Wout + tx * 4;
         if (m) s_any = 1;
     }
     __syncthreads();
     if (!s_any) return;
-    const int dx = A.dxy[((size_t)stream * A.n_tensors + L.tensor) * 2], dy = A.dxy[((size_t)stream * A.n_tensors + L.tensor) * 2 + 1];
-    const int pv = L.vec_per_px, per_unit = 16 * pv, total = 16 * per_unit;
-    const V* __restrict__ prev = static_cast<const V*>(L.prev);
-    V* __restrict__ out = static_cast<V*>(L.out);
-    const size_t map = (size_t)stream * L.Hout * L.Wout;
+    const size_t at = ((size_t)stream * A.n_tensors + L.tensor) * 2;
+    const int dx = A.dxy[at], dy = A.dxy[at + 1];
+    const int pv = L.vec_per_px, sh = L.vec_shift, total = upb * 16 * pv;
+    const V* __restrict__ prev = static_cast<const V*>(L.prev) + (size_t)stream * L.Hout * L.Wout * pv;
+    V* __restrict__ out = static_cast<V*>(L.out) + (size_t)stream * L.Hout * L.Wout * pv;
+    const int shift_px = dy * L.Wout + dx;
+    // where item i goes (element index in `out`), whether it is copied at all, and where it comes from (element 0
+    // for an item that is off, so that the load is unconditional and the four loads of a turn go out together)
+    auto locate = [&](int i, int& dst, bool& on) -> size_t {
+        int pxi, v;                                    // pixel index over the group's units, vector within the pixel
+        if (sh >= 0) { pxi = i >> sh; v = i & (pv - 1); }
+        else { pxi = i / pv; v = i - pxi * pv; }
+        const int unit = (pxi >> 4) & (kCopyUnitsPerGroup - 1), px = pxi & 15;
+        on = i < total && ((s_m[unit] >> px) & 1);
+        const int pix = s_px0[unit] + (px >> 2) * L.Wout + (px & 3);
+        dst = pix * pv + v;
+        return on ? (size_t)(pix + shift_px) * pv + v : (size_t)0;
+    };
     for (int i0 = tid; i0 < total; i0 += 4 * 256) {
-        V val[4];
-        size_t dst[4];
-        bool on[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int i = i0 + j * 256;
-            const int unit = i / per_unit, rem = i - unit * per_unit;
-            const int px = rem / pv, v = rem - px * pv;
-            on[j] = i < total && ((s_m[unit & 15] >> px) & 1);
-            const int u = u0 + unit, ty = u / L.units_x, tx = u - ty * L.units_x;
-            const int y = ty * 4 + (px >> 2), x = tx * 4 + (px & 3);
-            dst[j] = (map + (size_t)y * L.Wout + x) * pv + v;
-            if (on[j]) val[j] = prev[(map + (size_t)(y + dy) * L.Wout + (x + dx)) * pv + v];
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (on[j]) out[dst[j]] = val[j];
+        int d0, d1, d2, d3;
+        bool on0, on1, on2, on3;
+        const size_t s0 = locate(i0, d0, on0), s1 = locate(i0 + 256, d1, on1), s2 = locate(i0 + 512, d2, on2),
+                     s3 = locate(i0 + 768, d3, on3);
+        const V v0 = prev[s0], v1 = prev[s1], v2 = prev[s2], v3 = prev[s3];
+        if (on0) out[d0] = v0;
+        if (on1) out[d1] = v1;
+        if (on2) out[d2] = v2;
+        if (on3) out[d3] = v3;
     }
 }
 
@@ -392,7 +450,17 @@ __global__ __launch_bounds__(256) void shifted_copy_units_kernel(CopyUnitsArgs A
 hipError_t launch_plan(const PlanDev& P, const uint8_t* block_mask, const int32_t* gmv, int gh, int gw, int block,
                        int extend_borders, int max_chunks, hipStream_t st) {
     if (gh > 64 || gw > 64 || P.n_layers + 1 > kPlanMaxTensors || P.cap > kPlanMaxRects || P.cap < 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(plan_regions_kernel, dim3(P.n_streams), dim3(64), 0, st, P, block_mask, gmv, gh, gw, block, extend_borders);
+    // LDS pool of the lists of one stream: 48 rectangles per tensor on average, 16 KiB .. 112 KiB
+    int pool_rects = (P.n_layers + 1) * 48;
+    pool_rects = pool_rects < 1024 ? 1024 : (pool_rects > 7168 ? 7168 : pool_rects);
+    const size_t lds = (size_t)pool_rects * sizeof(dc_rect);
+    static std::atomic<bool> raised{false};
+    if (lds > 48 * 1024 && !raised.load()) {
+        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(plan_regions_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 7168 * (int)sizeof(dc_rect));
+        if (a != hipSuccess) return a;
+        raised.store(true);
+    }
+    hipLaunchKernelGGL(plan_regions_kernel, dim3(P.n_streams), dim3(64), lds, st, P, block_mask, gmv, gh, gw, block, extend_borders, pool_rects);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || P.n_convs == 0) return e;
     const dim3 grid((unsigned)max_chunks, (unsigned)P.n_streams, (unsigned)P.n_convs);
@@ -411,7 +479,13 @@ hipError_t launch_shifted_copy_units(const CopyUnitsLayer* layers, int n_layers,
         int max_groups = 0;
         for (int i = 0; i < nl; ++i) {
             A.L[i] = layers[l0 + i];
-            const int groups = (A.L[i].units_x * A.L[i].units_y + 15) / 16;
+            // about sixteen items (vectors) per thread: 4096 per workgroup, 16 * vec_per_px per unit
+            const int pv = A.L[i].vec_per_px;
+            int upb = 256 / (pv > 0 ? pv : 1);
+            upb = upb < 1 ? 1 : (upb > kCopyUnitsPerGroup ? kCopyUnitsPerGroup : upb);
+            A.L[i].units_per_group = upb;
+            A.L[i].vec_shift = (pv & (pv - 1)) == 0 ? __builtin_ctz((unsigned)pv) : -1;
+            const int groups = (A.L[i].units_x * A.L[i].units_y + upb - 1) / upb;
             max_groups = groups > max_groups ? groups : max_groups;
         }
         A.dxy = dxy; A.n_tensors = n_tensors;
