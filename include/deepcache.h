@@ -341,6 +341,22 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
                              void* ws_dev, size_t ws_dev_bytes,
                              void* ws_host, size_t ws_host_bytes, void* stream);
 
+/*
+ * dc_cached_conv_layer for callers that cannot allocate device memory or keep workspaces for the library: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspaces,
+ * same result.  The call allocates nothing, on the device or the host: its scratch (the layer's plan and the partial
+ * sums of a split K) is a 16 MiB array in device memory that belongs to the library on every GPU it runs on, until
+ * the process ends; the rectangles travel as kernel arguments and the dirty-unit list is built on the GPU.  Limits
+ * (errors before anything is launched): n_streams <= 32 and at most 128 rectangles over all streams
+ * (DC_ERR_CAPACITY); a plan of at most 6 MiB, about 18 bytes per 4x4 output unit and stream, i.e. 340 k units
+ * (DC_ERR_WORKSPACE).  Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two
+ * streams, two threads) race on it; calls on one stream do not.
+ */
+int32_t dc_cached_conv_layer_noalloc(const dc_layer* layer, const void* in, const void* weights,
+                                     const void* packed_weights, const float* bias, const void* cache_prev, void* out,
+                                     int32_t n_streams, int32_t Hin, int32_t Win,
+                                     const dc_regions* regions, int32_t dtype, void* stream);
+
 /* Un-cached layers (Section 5: only convolutions use the cache), whole map every frame. */
 /* out[pixel][c] = (frames[pixel][c] - 128) / 128 for c < c_frame, 0 for c_frame <= c < c_tensor. */
 int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n_pixels, int32_t c_frame,

@@ -24,7 +24,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
            "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_prefetch_match", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_propagate_regions_opt", "dc_conv_workspace_bytes",
            "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer", "dc_avgpool_layer", "dc_lrn_layer", "dc_concat_layer", "dc_fc_layer", "dc_softmax_layer",
-           "dc_stack_workspace_bytes", "dc_run_stack", "dc_stack_stats_fetch"]
+           "dc_stack_workspace_bytes", "dc_run_stack", "dc_stack_stats_fetch", "dc_cached_conv_layer_noalloc"]
 
 
 class DcError(RuntimeError):
@@ -108,6 +108,7 @@ def lib():
         L.dc_run_stack.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, u32, vp, i32, vp,
                                    vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp, vp]
         L.dc_stack_stats_fetch.argtypes = [vp, sz, vp]
+        L.dc_cached_conv_layer_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp]
         for name in EXPORTS:
             if name != "dc_status_string":
                 getattr(L, name).restype = i32
@@ -297,6 +298,27 @@ def dc_cached_conv_layer(layer, x, weights, bias, cache_prev=None, regions=None,
         _ptr(wd), wd.numel(), C.c_void_p(wh.data_ptr()), wh.numel(), _stream()))
     _conv_ws.busy = torch.cuda.Event()
     _conv_ws.busy.record()
+    return out
+
+
+def dc_cached_conv_layer_noalloc(layer, x, weights, bias, out, cache_prev=None, regions=None, packed=None):
+    """dc_cached_conv_layer without workspaces (the library's static scratch); `out` is the caller's tensor."""
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 4 and out.is_cuda and out.is_contiguous()
+    dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
+    assert weights.dtype == x.dtype and weights.is_contiguous() and out.dtype == x.dtype
+    n, Hin, Win, cin = x.shape
+    Lc = layers_to_c([layer])
+    regs = keep = None
+    if regions is not None:
+        assert len(regions) == n
+        regs, keep = _alloc_regions(n, max(1, max(len(r[0]) for r in regions)))
+        for i, (rects, dxy) in enumerate(regions):
+            regs[i].n = len(rects)
+            regs[i].dx, regs[i].dy = int(dxy[0]), int(dxy[1])
+            for j, r in enumerate(rects):
+                keep[i][j] = Rect(*[int(v) for v in r])
+    _check("dc_cached_conv_layer_noalloc", lib().dc_cached_conv_layer_noalloc(
+        Lc, _ptr(x), _ptr(weights), _ptr(packed), _ptr(bias), _ptr(cache_prev), _ptr(out), n, Hin, Win, regs, dtype, _stream()))
     return out
 
 

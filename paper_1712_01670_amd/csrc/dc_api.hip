@@ -275,6 +275,31 @@ void device_plan_layout(const dc_layer* L, int n_layers, const std::vector<int>&
     d.ok = true;
 }
 
+// ---- scratch of the entry point that allocates nothing ----
+// Device memory that belongs to the library for the life of the process (one copy per GPU the library is loaded
+// on): the plan of one conv layer (rectangles, unit masks, counts, unit list) and the partial sums of a split K.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+constexpr size_t kStaticPlanBytes = (size_t)6 << 20;      // the plan's share; the rest takes partial sums
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};           // device address of `scratch` on each GPU, asked once
+
+// Address of this GPU's copy of the array (the array's name is not an address host code may use).
+int static_scratch(unsigned char** ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return DC_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return DC_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> guard(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DC_ERR_HIP;
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *ptr = g_scratch_ptr[dev];
+    return DC_OK;
+}
+
 uint64_t fnv1a(uint64_t h, const void* p, size_t n) {
     const unsigned char* b = static_cast<const unsigned char*>(p);
     for (size_t i = 0; i < n; ++i) { h ^= b[i]; h *= 0x100000001b3ull; }
@@ -629,6 +654,87 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
     return run_conv_planned(*layer, in, weights, bias, cache_prev, out, n_streams, Hin, Win, dtype, tiling, &plan,
                             &addr, st, nullptr, -1, -1, nullptr, false, scratch, scratch ? ws_dev_bytes - plan_end : 0,
                             packed_weights);
+}
+
+int32_t dc_cached_conv_layer_noalloc(const dc_layer* layer, const void* in, const void* weights, const void* packed_weights,
+                                     const float* bias, const void* cache_prev, void* out, int32_t n_streams, int32_t Hin,
+                                     int32_t Win, const dc_regions* regions, int32_t dtype, void* stream) {
+    if (!layer || !in || !weights || !out) return DC_ERR_NULL_PTR;
+    int rc = check_conv_layer(layer);
+    if (rc) return rc;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (n_streams < 1 || Hin < 1 || Win < 1) return DC_ERR_INVALID_ARG;
+    if (Hin + 2 * layer->p < layer->k || Win + 2 * layer->p < layer->k) return DC_ERR_BAD_SHAPE;
+    const int Hout = (Hin + 2 * layer->p - layer->k) / layer->s + 1, Wout = (Win + 2 * layer->p - layer->k) / layer->s + 1;
+    const ConvTiling tiling = pick_tiling(*layer, Hout, Wout, n_streams, dtype);
+    hipStream_t st = as_stream(stream);
+    const bool cached = regions && cache_prev;
+    if (cached && out == cache_prev) return DC_ERR_INVALID_ARG;
+    // sizes first: the plan of the layer must fit the library's scratch, the rectangles the kernel arguments
+    PlanConvDev cv{};
+    cv.tensor = 0; cv.Hout = Hout; cv.Wout = Wout; cv.units_x = (Wout + 3) / 4; cv.units_y = (Hout + 3) / 4;
+    const size_t units = (size_t)cv.units_x * cv.units_y;
+    cv.n_chunks = (int)((units + kPlanChunk - 1) / kPlanChunk);
+    PlanArgRects args{};
+    int cap = 1;
+    size_t off = 0;
+    size_t off_rects = 0, off_nrect = 0, off_dxy = 0, off_info = 0, off_nunits = 0, off_stats = 0, off_convs = 0;
+    if (cached) {
+        if (n_streams > kArgMaxStreams) return DC_ERR_CAPACITY;
+        int total = 0;
+        for (int s = 0; s < n_streams; ++s) {
+            if (regions[s].n < 0 || (regions[s].n > 0 && !regions[s].rects)) return DC_ERR_NULL_PTR;
+            if (!rects_disjoint_inside(regions[s].rects, regions[s].n, Wout, Hout, regions[s].dx, regions[s].dy))
+                return DC_ERR_BAD_SHAPE;
+            if (total + regions[s].n > kArgMaxRects) return DC_ERR_CAPACITY;
+            args.first[s] = total;
+            for (int j = 0; j < regions[s].n; ++j) args.r[total + j] = regions[s].rects[j];
+            total += regions[s].n;
+            args.dxy[s][0] = regions[s].dx; args.dxy[s][1] = regions[s].dy;
+            cap = regions[s].n > cap ? regions[s].n : cap;
+        }
+        for (int s = n_streams; s <= kArgMaxStreams; ++s) args.first[s] = total;
+        off_rects = off; off += align_up((size_t)n_streams * cap * sizeof(dc_rect), 256);
+        off_nrect = off; off += align_up((size_t)n_streams * sizeof(int32_t), 256);
+        off_dxy = off; off += align_up((size_t)n_streams * 2 * sizeof(int32_t), 256);
+        off_info = off; off += align_up((size_t)n_streams * 2 * sizeof(int32_t), 256);
+        off_nunits = off; off += 256;
+        off_stats = off; off += 256;
+        off_convs = off; off += 256;
+        cv.umask_off = (int64_t)off; off += align_up((size_t)n_streams * units * sizeof(uint16_t), 256);
+        cv.count_off = (int64_t)off; off += align_up((size_t)n_streams * cv.n_chunks * 2 * sizeof(int32_t), 256);
+        cv.list_off = (int64_t)off; off += align_up((size_t)n_streams * units * sizeof(TileDev), 256);
+        if (off > kStaticPlanBytes || (size_t)n_streams * units > 0x7fffffffull) return DC_ERR_WORKSPACE;
+    }
+    unsigned char* base = nullptr;
+    rc = static_scratch(&base);
+    if (rc) return rc;
+    unsigned char* const partial = base + kStaticPlanBytes;
+    const size_t partial_bytes = kStaticScratchBytes - kStaticPlanBytes;
+    if (!cached)
+        return run_conv_planned(*layer, in, weights, bias, nullptr, out, n_streams, Hin, Win, dtype, tiling, nullptr, nullptr,
+                                st, nullptr, -1, -1, nullptr, false, partial, partial_bytes, packed_weights);
+    PlanDev pd{};
+    pd.layers = nullptr; pd.tensors = nullptr;
+    pd.convs = reinterpret_cast<const PlanConvDev*>(base + off_convs);
+    pd.n_layers = 0; pd.n_convs = 1; pd.n_streams = n_streams; pd.cap = cap;
+    pd.rects = reinterpret_cast<dc_rect*>(base + off_rects);
+    pd.nrect = reinterpret_cast<int32_t*>(base + off_nrect);
+    pd.dxy = reinterpret_cast<int32_t*>(base + off_dxy);
+    pd.stream_info = reinterpret_cast<int32_t*>(base + off_info);
+    pd.n_units = reinterpret_cast<int32_t*>(base + off_nunits);
+    pd.stats = base + off_stats;
+    pd.area = base;
+    DC_TRY_HIP(launch_plan_from_args(pd, cv, args, st));
+    const size_t px_bytes = (size_t)layer->cout * dtype_size(dtype);
+    const bool vec16 = px_bytes % 16 == 0 && reinterpret_cast<uintptr_t>(cache_prev) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0;
+    const int vb = vec16 ? 16 : (int)dtype_size(dtype);
+    const CopyUnitsLayer cl{cache_prev, out, reinterpret_cast<const uint16_t*>(base + cv.umask_off), 0, Hout, Wout,
+                            cv.units_x, cv.units_y, (int32_t)(px_bytes / vb), 0, 0};
+    DC_TRY_HIP(launch_shifted_copy_units(&cl, 1, pd.dxy, 1, n_streams, vb, st));
+    return run_conv_planned(*layer, in, weights, bias, cache_prev, out, n_streams, Hin, Win, dtype, tiling, nullptr, nullptr, st,
+                            nullptr, -1, -1, nullptr, true, partial, partial_bytes, packed_weights,
+                            reinterpret_cast<const TileDev*>(base + cv.list_off), (int)((size_t)n_streams * units), pd.n_units, -1);
 }
 
 int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n_pixels, int32_t c_frame, int32_t c_tensor,

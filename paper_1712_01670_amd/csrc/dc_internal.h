@@ -171,6 +171,18 @@ struct PlanDev {                         // device addresses of one frame's plan
 };
 hipError_t launch_plan(const PlanDev& P, const uint8_t* block_mask, const int32_t* gmv, int gh, int gw, int block,
                        int extend_borders, int max_chunks, hipStream_t st);
+// The same for one conv layer whose rectangles come from the host and are small enough to travel as kernel arguments
+// (no staging buffer, no copy): a set-up kernel writes them where the mask and list kernels expect them.
+constexpr int kArgMaxRects = 128;        // rectangles of all streams together
+constexpr int kArgMaxStreams = 32;
+struct PlanArgRects {
+    dc_rect r[kArgMaxRects];             // stream after stream
+    int32_t first[kArgMaxStreams + 1];   // stream s owns r[first[s]] .. r[first[s + 1] - 1]
+    int32_t dxy[kArgMaxStreams][2];      // its source offset
+};
+// P describes a stack of no layers (the rectangles belong to tensor 0 = the conv output); P.convs must be writable.
+hipError_t launch_plan_from_args(const PlanDev& P, const PlanConvDev& conv, const PlanArgRects& R, hipStream_t st);
+
 // One conv layer of the per-unit copy: out[p] = prev[p + d] for every pixel whose bit is set in its unit's mask.
 struct CopyUnitsLayer {
     const void* prev;

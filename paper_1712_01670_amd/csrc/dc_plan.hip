@@ -471,6 +471,34 @@ hipError_t launch_plan(const PlanDev& P, const uint8_t* block_mask, const int32_
     return hipGetLastError();
 }
 
+namespace {
+__global__ __launch_bounds__(256) void plan_args_kernel(PlanDev P, PlanConvDev conv, PlanArgRects R) {
+    const int tid = threadIdx.x;
+    if (tid == 0) const_cast<PlanConvDev*>(P.convs)[0] = conv;
+    for (int s = tid; s < P.n_streams; s += 256) {
+        P.nrect[s] = R.first[s + 1] - R.first[s];
+        P.dxy[2 * s] = R.dxy[s][0]; P.dxy[2 * s + 1] = R.dxy[s][1];
+        P.stream_info[2 * s] = 0; P.stream_info[2 * s + 1] = 0;
+    }
+    for (int s = 0; s < P.n_streams; ++s)
+        for (int j = R.first[s] + tid; j < R.first[s + 1]; j += 256) P.rects[(size_t)s * P.cap + (j - R.first[s])] = R.r[j];
+}
+}  // namespace
+
+hipError_t launch_plan_from_args(const PlanDev& P, const PlanConvDev& conv, const PlanArgRects& R, hipStream_t st) {
+    if (P.n_layers != 0 || P.n_convs != 1 || P.n_streams < 1 || P.n_streams > kArgMaxStreams || P.cap < 1 || P.cap > kPlanMaxRects)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(plan_args_kernel, dim3(1), dim3(256), 0, st, P, conv, R);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)conv.n_chunks, (unsigned)P.n_streams, 1);
+    hipLaunchKernelGGL(plan_masks_kernel, grid, dim3(kPlanChunk), 0, st, P);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(plan_lists_kernel, grid, dim3(kPlanChunk), 0, st, P);
+    return hipGetLastError();
+}
+
 hipError_t launch_shifted_copy_units(const CopyUnitsLayer* layers, int n_layers, const int32_t* dxy, int n_tensors,
                                      int n_streams, int vec_bytes, hipStream_t st) {
     for (int l0 = 0; l0 < n_layers; l0 += kCopyUnitsMaxLayers) {
