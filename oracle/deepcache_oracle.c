@@ -598,6 +598,80 @@ int oc_propagate(const oc_layer* L, int n_layers, int H, int W,
     return oc_propagate_ext(L, n_layers, H, W, rects0, n0, mx, my, 0, rects, cap, n_rects, dxy, cum_stride, hw);
 }
 
+/*
+ * Exact reuse maps: Section 5's propagation applied to the set of reusable pixels itself instead of to the
+ * rectangles Step 5 cut it into (Section 5 keeps a boolean map per layer anyway; Section 4 shows with its 18- against
+ * 24-pixel example what every seam between two rectangles costs).  The rule per pixel is the rule Table 2 applies
+ * per rectangle, a window must lie wholly inside what is reusable:
+ *   tensor 0        a pixel is reusable iff its block passed Step 4 (pixels of the remainder strip never are);
+ *   conv / pool     an output pixel is reusable iff every tap of its k x k window lies inside the map and is
+ *                   reusable (reading: a tap in the zero padding makes it non-reusable, as a rectangle cannot reach
+ *                   there; with extend_borders and zero motion such taps are ignored, as in oc_propagate_ext);
+ *   LRN over pixels the same with the window of radius (k - 1) / 2; over channels: unchanged;
+ *   add / concat    reusable in every input;   FC / softmax: nothing;   others: unchanged;
+ * and in every tensor a pixel is only reusable if its source, the pixel at +(dx, dy) with the tensor's offset
+ * (the same one offset per tensor as in oc_propagate_ext), lies inside the map.
+ * masks[t] is tensor t's map [h][w] (1 = reusable), caller-allocated; dxy, cum_stride, hw as in oc_propagate_ext.
+ * By construction the union of oc_propagate_ext's rectangles is a subset of these maps, with equality where
+ * Step 5 yields a single rectangle.
+ */
+int oc_propagate_masks(const oc_layer* L, int n_layers, int H, int W, const uint8_t* block_mask, int gh, int gw,
+                       int B, int mx, int my, int extend_borders, uint8_t* const* masks, int32_t* dxy,
+                       int32_t* cum_stride, int32_t* hw)
+{
+    int ext = extend_borders && mx == 0 && my == 0;
+    hw[0] = H; hw[1] = W; cum_stride[0] = 1; dxy[0] = mx; dxy[1] = my;
+    for (int y = 0; y < H; ++y)
+        for (int x = 0; x < W; ++x) {
+            int by = y / B, bx = x / B;
+            int in_grid = by < gh && bx < gw;
+            int src_ok = x + mx >= 0 && x + mx < W && y + my >= 0 && y + my < H;
+            masks[0][(size_t)y * W + x] = (uint8_t)(in_grid && block_mask[(size_t)by * gw + bx] && src_ok);
+        }
+    for (int i = 0; i < n_layers; ++i) {
+        const oc_layer* l = &L[i];
+        int t = i + 1, a = l->in0;
+        int ha = hw[2 * a], wa = hw[2 * a + 1];
+        int windowed = l->type == OC_CONV || l->type == OC_MAXPOOL || l->type == OC_AVGPOOL;
+        int lrn_px = l->type == OC_LRN && l->within;
+        int k = windowed ? l->k : (lrn_px ? l->k : 1);
+        int s = windowed ? l->s : 1;
+        int p = windowed ? l->p : (lrn_px ? (l->k - 1) / 2 : 0);
+        int ho = windowed ? (ha + 2 * l->p - l->k) / l->s + 1 : (l->type == OC_FC ? 1 : ha);
+        int wo = windowed ? (wa + 2 * l->p - l->k) / l->s + 1 : (l->type == OC_FC ? 1 : wa);
+        hw[2 * t] = ho; hw[2 * t + 1] = wo;
+        cum_stride[t] = windowed ? cum_stride[a] * l->s : cum_stride[a];
+        int dx = round_div(mx, cum_stride[t]), dy = round_div(my, cum_stride[t]);
+        dxy[2 * t] = dx; dxy[2 * t + 1] = dy;
+        const uint8_t* ma = masks[a];
+        uint8_t* mt = masks[t];
+        for (int y = 0; y < ho; ++y)
+            for (int x = 0; x < wo; ++x) {
+                int ok;
+                if (l->type == OC_FC || l->type == OC_SOFTMAX) {
+                    ok = 0;
+                } else if (l->type == OC_ADD) {
+                    ok = ma[(size_t)y * wa + x] && masks[l->in1][(size_t)y * wa + x];
+                } else if (l->type == OC_CONCAT) {
+                    int ids[OC_MAX_CONCAT], m = concat_inputs(l, ids);
+                    ok = 1;
+                    for (int j = 0; j < m; ++j) ok = ok && masks[ids[j]][(size_t)y * wa + x];
+                } else {
+                    ok = 1;
+                    for (int ky = 0; ky < k && ok; ++ky)
+                        for (int kx = 0; kx < k && ok; ++kx) {
+                            int iy = y * s - p + ky, ix = x * s - p + kx;
+                            if (iy < 0 || iy >= ha || ix < 0 || ix >= wa) { if (!ext) ok = 0; continue; }
+                            ok = ma[(size_t)iy * wa + ix];
+                        }
+                }
+                int src_ok = x + dx >= 0 && x + dx < wo && y + dy >= 0 && y + dy < ho;
+                mt[(size_t)y * wo + x] = (uint8_t)(ok && src_ok);
+            }
+    }
+    return 0;
+}
+
 /* Boolean map of Section 5 "Reuse", step 2: 1 where the pixel lies in a rectangle. */
 void oc_rasterize(const oc_rect* rects, int n, int H, int W, uint8_t* mask)
 {
@@ -852,8 +926,10 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
                  int bf16, const oc_rect* rects0, int n0, int mx, int my,
                  float* const* cur, const float* const* prev,
                  oc_rect* rects, int cap, int32_t* n_rects, int32_t* dxy,
-                 int32_t* cum_stride, int32_t* hw, int extend_borders)
+                 int32_t* cum_stride, int32_t* hw, int extend_borders, const uint8_t* const* exact_masks)
 {
+    /* exact_masks (optional): the maps of oc_propagate_masks for this frame; the conv layers then reuse exactly
+     * those pixels instead of the rectangles' */
     int cached = n0 >= 0;
     int rc = oc_propagate_ext(L, n_layers, H, W, rects0, cached ? n0 : 0, cached ? mx : 0,
                               cached ? my : 0, extend_borders, rects, cap, n_rects, dxy, cum_stride, hw);
@@ -865,7 +941,10 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
         int ha = hw[2 * a], wa = hw[2 * a + 1], ho = hw[2 * t], wo = hw[2 * t + 1];
         if (l->type == OC_CONV) {
             uint8_t* mask = NULL;
-            if (cached && n_rects[t] > 0) {
+            if (cached && exact_masks) {
+                mask = (uint8_t*)malloc((size_t)ho * wo);
+                memcpy(mask, exact_masks[t], (size_t)ho * wo);
+            } else if (cached && n_rects[t] > 0) {
                 mask = (uint8_t*)malloc((size_t)ho * wo);
                 oc_rasterize(rects + (size_t)t * cap, n_rects[t], ho, wo, mask);
             }

@@ -185,6 +185,37 @@ def propagate(layers, H, W, rects0, mx, my, cap=1024, extend_borders=False):
                 cum_stride=cs, hw=hw)
 
 
+def tensor_hw(layers, H, W):
+    """Spatial size of every tensor of the stack."""
+    hw = [(int(H), int(W))]
+    for L in layers:
+        h, w_ = hw[L["in0"]]
+        if L["type"] in (0, 1, 8):
+            hw.append(((h + 2 * L["p"] - L["k"]) // L["s"] + 1, (w_ + 2 * L["p"] - L["k"]) // L["s"] + 1))
+        elif L["type"] == 6:
+            hw.append((1, 1))
+        else:
+            hw.append((h, w_))
+    return hw
+
+
+def propagate_masks(layers, H, W, block_mask, block, mx, my, extend_borders=False):
+    """Exact reuse maps of every tensor (uint8 [h][w], 1 = reusable).  Returns dict(masks, dxy, cum_stride, hw)."""
+    n = len(layers)
+    Lc = layers_to_c(layers)
+    bm = np.ascontiguousarray(block_mask, np.uint8)
+    gh, gw = bm.shape
+    masks = [np.zeros(s, np.uint8) for s in tensor_hw(layers, H, W)]
+    mp = (C.c_void_p * (n + 1))(*[m.ctypes.data for m in masks])
+    dxy = np.zeros((n + 1, 2), np.int32)
+    cs = np.zeros(n + 1, np.int32)
+    hw = np.zeros((n + 1, 2), np.int32)
+    rc = lib().oc_propagate_masks(Lc, n, int(H), int(W), _p(bm), gh, gw, int(block), int(mx), int(my), int(extend_borders),
+                                  mp, _p(dxy), _p(cs), _p(hw))
+    assert rc == 0
+    return dict(masks=masks, dxy=dxy, cum_stride=cs, hw=hw)
+
+
 def rasterize(rects, H, W):
     r = rects_to_np(rects)
     H, W = int(H), int(W)
@@ -300,8 +331,8 @@ class Stream:
     the previous feature maps (cache values), Section 3."""
 
     def __init__(self, layers, weights, biases, H, W, Ch=3, block=16, radius=16, max_ssd=None,
-                 bf16=False, expiry=0, cap=1024, diamond=False, k_skip=1, extend_borders=False):
-        self.diamond, self.k_skip, self.extend_borders = diamond, k_skip, extend_borders
+                 bf16=False, expiry=0, cap=1024, diamond=False, k_skip=1, extend_borders=False, exact_masks=False):
+        self.diamond, self.k_skip, self.extend_borders, self.exact_masks = diamond, k_skip, extend_borders, exact_masks
         self.layers, self.H, self.W, self.Ch = layers, H, W, Ch
         self.block, self.radius, self.bf16, self.expiry, self.cap = block, radius, bf16, expiry, cap
         self.max_ssd = max_ssd if max_ssd is not None else 20 * block * block * Ch
@@ -359,12 +390,16 @@ class Stream:
         hw = np.zeros((n + 1, 2), np.int32)
         curp = (C.c_void_p * (n + 1))(*[t.ctypes.data for t in cur])
         prevp = (C.c_void_p * (n + 1))(*[t.ctypes.data for t in prev])
+        masks = mp = None
+        if self.exact_masks and not full:
+            masks = propagate_masks(self.layers, self.H, self.W, m["mask"], self.block, mx, my, self.extend_borders)["masks"]
+            mp = (C.c_void_p * (n + 1))(*[a.ctypes.data for a in masks])
         rc = lib().oc_run_stack(self.Lc, n, self._wp, self._bp, _p(frame), self.H, self.W, self.Ch,
                                 int(self.bf16), _p(r0), n0, mx, my, curp, prevp, _p(rects),
-                                self.cap, _p(n_rects), _p(dxy), _p(cs), _p(hw), int(self.extend_borders))
+                                self.cap, _p(n_rects), _p(dxy), _p(cs), _p(hw), int(self.extend_borders), mp)
         assert rc == 0
         self.bufs = [prev, cur]  # cur becomes next frame's prev
         self.prev_frame = frame.copy()
-        return dict(tensors=cur, match=m, rects0=r0, full=full,
+        return dict(tensors=cur, match=m, rects0=r0, full=full, masks=masks,
                     rects=[rects[t, :n_rects[t]].copy() for t in range(n + 1)],
                     dxy=dxy, cum_stride=cs, hw=hw)

@@ -234,3 +234,131 @@ def test_border_extension_only_for_zero_motion(oracle):
         assert moved["rects"][t].tolist() == moved_plain["rects"][t].tolist()   # a moving stream: the printed rule
     # the printed rule loses a ring per layer: the last 14x14 maps keep almost nothing
     assert plain["rects"][len(layers)].size == 0 or np.prod(plain["rects"][len(layers)][0][2:]) <= 4
+
+
+# ---- exact reuse maps (Section 5's propagation applied per pixel instead of per rectangle) ------------------------
+def _np_window_and(mask, k, s, p, ignore_padding=False):
+    """out[o] = AND over the k x k window at o*s - p of `mask`; taps outside the map count as `ignore_padding`."""
+    H, W = mask.shape
+    Ho, Wo = (H + 2 * p - k) // s + 1, (W + 2 * p - k) // s + 1
+    pad = np.full((H + 2 * p + k, W + 2 * p + k), bool(ignore_padding))
+    pad[p:p + H, p:p + W] = mask.astype(bool)
+    out = np.ones((Ho, Wo), bool)
+    for ky in range(k):
+        for kx in range(k):
+            out &= pad[ky:ky + (Ho - 1) * s + 1:s, kx:kx + (Wo - 1) * s + 1:s]
+    return out
+
+
+def _np_source_inside(mask, dx, dy):
+    H, W = mask.shape
+    ys, xs = np.mgrid[0:H, 0:W]
+    return mask & (xs + dx >= 0) & (xs + dx < W) & (ys + dy >= 0) & (ys + dy < H)
+
+
+def _np_exact_masks(layers, H, W, block_mask, B, mx, my, ext=False):
+    from paper_1712_01670_amd import synth
+    ext = ext and mx == 0 and my == 0
+    rha = lambda m, d: int(np.sign(m)) * ((2 * abs(m) + d) // (2 * d))
+    full = np.zeros((H, W), bool)
+    px = np.kron(np.asarray(block_mask, bool), np.ones((B, B), bool))
+    full[:px.shape[0], :px.shape[1]] = px[:H, :W]
+    masks, cum = [_np_source_inside(full, mx, my)], [1]
+    for L in layers:
+        a = masks[L["in0"]]
+        c = cum[L["in0"]]
+        if L["type"] in (synth.CONV, synth.MAXPOOL, synth.AVGPOOL):
+            m = _np_window_and(a, L["k"], L["s"], L["p"], ext)
+            c *= L["s"]
+        elif L["type"] == synth.LRN and L.get("within", 0):
+            m = _np_window_and(a, L["k"], 1, (L["k"] - 1) // 2, ext)
+        elif L["type"] == synth.ADD:
+            m = a & masks[L["in1"]]
+        elif L["type"] == synth.CONCAT:
+            m = a.copy()
+            for key in ("in1", "in2", "in3"):
+                if L.get(key, -1) >= 0:
+                    m &= masks[L[key]]
+        elif L["type"] in (synth.FC, synth.SOFTMAX):
+            m = np.zeros((1, 1) if L["type"] == synth.FC else a.shape, bool)
+        else:
+            m = a.copy()
+        cum.append(c)
+        masks.append(_np_source_inside(m, rha(mx, c), rha(my, c)))
+    return masks
+
+
+def _mixed_stack():
+    from paper_1712_01670_amd import synth
+    C_ = lambda k, s, p, i: dict(type=synth.CONV, k=k, s=s, p=p, cin=4, cout=4, relu=1, in0=i, in1=-1)
+    return [C_(3, 1, 1, 0),                                                                   # 1
+            C_(5, 1, 2, 1),                                                                   # 2
+            dict(type=synth.MAXPOOL, k=2, s=2, p=0, cin=4, cout=4, relu=0, in0=2, in1=-1),    # 3
+            C_(3, 1, 1, 3),                                                                   # 4  branch a
+            C_(1, 1, 0, 3),                                                                   # 5  branch b
+            dict(type=synth.ADD, k=1, s=1, p=0, cin=4, cout=4, relu=1, in0=4, in1=5),         # 6
+            dict(type=synth.LRN, k=3, s=1, p=0, cin=4, cout=4, relu=0, in0=6, in1=-1, within=1, alpha=1e-4, beta=0.75, kappa=1.0),  # 7
+            C_(3, 2, 1, 7),                                                                   # 8
+            dict(type=synth.MAXPOOL, k=3, s=2, p=1, cin=4, cout=4, relu=0, in0=8, in1=-1),    # 9
+            dict(type=synth.RELU, k=1, s=1, p=0, cin=4, cout=4, relu=0, in0=9, in1=-1),       # 10
+            C_(7, 1, 3, 10),                                                                  # 11
+            dict(type=synth.CONCAT, k=1, s=1, p=0, cin=8, cout=8, relu=0, in0=10, in1=11, in2=-1, in3=-1)]  # 12
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_exact_masks_are_the_per_pixel_rule(oracle, seed):
+    # a pixel is reusable iff every tap of its window is reusable and inside the map, and its source is inside the
+    # map: an independent array formulation (shifted slices of a padded map) on random block masks and motions
+    rng = np.random.default_rng(seed)
+    layers = _mixed_stack()
+    H, W, B = 70, 92, 8                       # 8 x 11 blocks and a remainder strip on both axes
+    bm = (rng.random((H // B, W // B)) < 0.8).astype(np.uint8)
+    mx, my = (0, 0) if seed == 0 else (int(rng.integers(-9, 10)), int(rng.integers(-9, 10)))
+    for ext in (False, True):
+        got = oracle.propagate_masks(layers, H, W, bm, B, mx, my, extend_borders=ext)
+        want = _np_exact_masks(layers, H, W, bm, B, mx, my, ext)
+        for t, (g, w_) in enumerate(zip(got["masks"], want)):
+            assert np.array_equal(g.astype(bool), w_), (t, ext)
+        rects = oracle.propagate(layers, H, W, oracle.merge_blocks(bm, B), mx, my, extend_borders=ext)
+        assert np.array_equal(got["dxy"], rects["dxy"]) and np.array_equal(got["hw"], rects["hw"])
+        for t, m in enumerate(got["masks"]):   # the rectangles never claim a pixel the exact map does not
+            r = oracle.rasterize(rects["rects"][t], *m.shape).astype(bool)
+            assert not (r & ~m.astype(bool)).any(), t
+        assert got["masks"][1].sum() > 0
+
+
+def test_exact_masks_equal_the_rectangle_rule_for_a_single_rectangle(oracle):
+    from paper_1712_01670_amd import synth
+    layers = synth.vgg16()[:10]
+    bm = np.zeros((6, 6), np.uint8)
+    bm[1:5, 2:6] = 1                                                # one 4 x 4-block rectangle
+    for (mx, my) in ((0, 0), (3, -2), (-16, 8)):
+        got = oracle.propagate_masks(layers, 96, 96, bm, 16, mx, my)
+        rects = oracle.propagate(layers, 96, 96, oracle.merge_blocks(bm, 16), mx, my)
+        for t, m in enumerate(got["masks"]):
+            assert len(rects["rects"][t]) <= 1
+            assert np.array_equal(m, oracle.rasterize(rects["rects"][t], *m.shape)), (t, mx, my)
+
+
+def test_exact_masks_do_not_pay_for_seams(oracle):
+    # Section 4's arithmetic: two 5x5 blocks under a 3x3 kernel keep 3x3 pixels each (18) when they are propagated
+    # apart, 3x8 = 24 as one 5x10 rectangle.  The exact map of their union holds 24 however Step 5 cuts it.
+    from paper_1712_01670_amd import synth
+    conv = [dict(type=synth.CONV, k=3, s=1, p=1, cin=1, cout=1, relu=0, in0=0, in1=-1)]
+    bm = np.zeros((4, 5), np.uint8)
+    bm[1, 1:3] = 1
+    exact = oracle.propagate_masks(conv, 20, 25, bm, 5, 0, 0)["masks"][1]
+    assert int(exact.sum()) == 24 and exact[6:9, 6:14].all()
+    apart = oracle.propagate(conv, 20, 25, [(5, 5, 5, 5), (10, 5, 5, 5)], 0, 0)
+    assert sum(int(r[2]) * int(r[3]) for r in apart["rects"][1]) == 18
+    merged = oracle.propagate(conv, 20, 25, oracle.merge_blocks(bm, 5), 0, 0)
+    assert [tuple(int(v) for v in r) for r in merged["rects"][1]] == [(6, 6, 8, 3)]
+    # an L-shaped region: three rectangles' worth of seams in any decomposition, none in the exact map
+    bm = np.zeros((4, 5), np.uint8)
+    bm[0:3, 1] = 1
+    bm[2, 1:4] = 1
+    exact = oracle.propagate_masks(conv, 20, 25, bm, 5, 0, 0)["masks"][1]
+    rect = oracle.propagate(conv, 20, 25, oracle.merge_blocks(bm, 5), 0, 0)["rects"][1]
+    # column: x 6..8, y 1..13 (the map's top row is lost to the padding); bar: x 6..18, y 11..13
+    assert int(exact.sum()) == 3 * 13 + 13 * 3 - 9
+    assert sum(int(r[2]) * int(r[3]) for r in rect) < int(exact.sum())

@@ -109,10 +109,10 @@ def test_cached_conv_copies_exactly_where_masked(oracle):
     assert np.array_equal(out[2:6, 3:9], cache[1:5, 5:11])
 
 
-def _run_video(oracle, layers, frames, block, radius, bf16=False, expiry=0, seed=1, bias_scale=0.1):
+def _run_video(oracle, layers, frames, block, radius, bf16=False, expiry=0, seed=1, bias_scale=0.1, exact_masks=False):
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale)
     H, W, C = frames[0].shape
-    st = oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry)
+    st = oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry, exact_masks=exact_masks)
     outs = []
     for f in frames:
         r = st.step(f)
@@ -256,3 +256,66 @@ def test_leaky_relu_of_a_convolution(oracle):
     assert np.allclose(oracle.conv_cached(x, w, b, 3, 1, 1, 1), np.maximum(plain, 0), rtol=1e-6, atol=1e-7)
     one = np.full((1, 1, 1), -2.0, np.float32)                      # hand value: -2 * 3 = -6 -> -0.6
     assert abs(float(oracle.conv_cached(one, np.full((1, 1, 1, 1), 3.0, np.float32), None, 1, 1, 0, 2)[0, 0, 0]) + 0.6) < 1e-7
+
+
+# ---- the same invariants with exact reuse maps instead of rectangles ---------------------------------------------
+def test_exact_masks_zero_reuse_is_full_forward(oracle):
+    rng = np.random.default_rng(6)
+    layers = synth.tiny_net()
+    frames = [rng.integers(0, 256, (64, 64, 3)).astype(np.uint8) for _ in range(2)]
+    outs, (ws, bs) = _run_video(oracle, layers, frames, 8, 8, exact_masks=True)
+    assert outs[1]["match"]["n_pass"] == 0 and all(not m.any() for m in outs[1]["masks"])
+    for a, b in zip(outs[1]["tensors"], _full_forward(oracle, layers, ws, bs, frames[1])):
+        assert np.array_equal(a, b)
+
+
+def test_exact_masks_identical_frames_lose_only_the_padding_ring(oracle):
+    rng = np.random.default_rng(8)
+    layers = synth.tiny_net()           # 3x3 p1 s1; 3x3 p1 s2; 3x3 p1 s1
+    f = rng.integers(0, 256, (64, 64, 3)).astype(np.uint8)
+    outs, _ = _run_video(oracle, layers, [f, f], 8, 8, exact_masks=True)
+    m = outs[1]["masks"]
+    assert m[0].all()
+    want1 = np.zeros((64, 64), bool); want1[1:63, 1:63] = True          # windows inside the map
+    want2 = np.zeros((32, 32), bool); want2[1:31, 1:31] = True          # taps 2o-1 .. 2o+1 inside [1, 62]
+    want3 = np.zeros((32, 32), bool); want3[2:30, 2:30] = True
+    assert np.array_equal(m[1].astype(bool), want1) and np.array_equal(m[2].astype(bool), want2)
+    assert np.array_equal(m[3].astype(bool), want3)
+    for a, b in zip(outs[0]["tensors"], outs[1]["tensors"]):
+        assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_exact_masks_exact_shift_equals_full_forward(oracle, bf16):
+    # more pixels are copied than with rectangles, and every copied value still equals the recomputed one
+    layers = synth.tiny_net()
+    f1, f2 = synth.shifted_pair(10, 64, 64, (4, -2))
+    f2 = f2.copy()
+    f2[24:40, 8:24] = np.random.default_rng(3).integers(0, 256, (16, 16, 3))     # a hole: the region is not one rectangle
+    exact, (ws, bs) = _run_video(oracle, layers, [f1, f2], 8, 8, bf16=bf16, exact_masks=True)
+    rect, _ = _run_video(oracle, layers, [f1, f2], 8, 8, bf16=bf16)
+    full = _full_forward(oracle, layers, ws, bs, f2, bf16=bf16)
+    more = 0
+    for t in range(1, len(layers) + 1):
+        assert np.array_equal(exact[1]["tensors"][t], full[t]), t
+        reused_rect = sum(int(w) * int(h) for _, _, w, h in rect[1]["rects"][t])
+        assert int(exact[1]["masks"][t].sum()) >= reused_rect
+        more += int(exact[1]["masks"][t].sum()) - reused_rect
+    assert more > 100
+
+
+def test_exact_masks_values_come_from_the_cache(oracle):
+    # a noisy second frame: reused pixels are the previous frame's values at the offset, bit for bit, and differ
+    # from what a recomputation gives
+    layers = synth.tiny_net()
+    f1, f2 = synth.tiny_pair(0)
+    outs, (ws, bs) = _run_video(oracle, layers, [f1, f2], 8, 8, exact_masks=True)
+    full = _full_forward(oracle, layers, ws, bs, f2)
+    for t in (1, 2, 3):
+        m = outs[1]["masks"][t].astype(bool)
+        dx, dy = (int(v) for v in outs[1]["dxy"][t])
+        ys, xs = np.nonzero(m)
+        assert len(ys) > 50
+        assert np.array_equal(outs[1]["tensors"][t][ys, xs], outs[0]["tensors"][t][ys + dy, xs + dx])
+        assert np.array_equal(outs[1]["tensors"][t][~m], full[t][~m]) or t > 1      # layer 1 reads exact inputs
+        assert not np.array_equal(outs[1]["tensors"][t][m], full[t][m])
