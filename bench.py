@@ -84,7 +84,8 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames):
     dt = binding.DC_BF16 if dtype == "bf16" else binding.DC_F32
     method = binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE
     runner = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
-                                 match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan)
+                                 match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan,
+                                 exact_masks=args.exact_masks and not args.host_plan)
 
     def run_steps(k, start, collect=None, force_full=False):
         """Run k steps through the cyclic video starting at global step `start`."""
@@ -236,7 +237,7 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames):
     if not args.no_cpu_baseline:
         from oracle import oracle as oc
         ref = oc.Stream(layers, ws, bs, H, W, 3, block=16, radius=16, bf16=(dtype == "bf16"), expiry=args.expiry,
-                        diamond=(args.matcher == "ds"), k_skip=args.k_skip)
+                        diamond=(args.matcher == "ds"), k_skip=args.k_skip, exact_masks=args.exact_masks and not args.host_plan)
         k_cpu = min(cpu_frames, n_frames)
         t0 = time.perf_counter()
         for f in range(k_cpu):
@@ -276,6 +277,8 @@ def main():
                          "one frame ahead would allow")
     ap.add_argument("--host-plan", action="store_true",
                     help="merge / propagate / list the dirty units on the host (one wait per frame) instead of on the GPU")
+    ap.add_argument("--exact-masks", action="store_true",
+                    help="reuse the pixels of the exact reuse maps (the propagation rule per pixel) instead of the rectangles'")
     ap.add_argument("--no-single", action="store_true", help="skip the single-stream fp32 sub-record")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=30)
@@ -311,6 +314,7 @@ def main():
                    "streams": n, "matcher": ("exhaustive search" if args.matcher == "es" else "diamond search") + f", k-skip {args.k_skip}",
                    "cache_expiry_frames": args.expiry, "frames_per_video": 30, "repeats": args.repeats,
                    "planning": "host" if args.host_plan else "device",
+                   "reusable_regions": "exact maps" if (args.exact_masks and not args.host_plan) else "rectangles",
                    "lookahead_frames": 1 if args.lookahead else 0, **detail},
     }
     out.update(main_rec)

@@ -106,6 +106,10 @@ typedef struct {
                               need not lie in the rectangle (they read zeros in both frames), so a rectangle that
                               touches a side of the map keeps the outputs along that side: an extension beyond
                               the paper's table for static cameras (dc_propagate_regions_opt) */
+    int32_t exact_masks;   /* dc_run_stack only, with device_plan (DC_ERR_UNSUPPORTED without).  0: reusable regions are
+                              the rectangles of Step 5, propagated by Table 2.  1: the same rule per pixel (see
+                              dc_propagate_masks): exact reuse maps, which lose nothing at the seams between
+                              rectangles.  No rectangle lists exist then (regions_out reports empty lists). */
     int32_t device_plan;   /* dc_run_stack only.  0: the call waits for the matching, then merges, propagates and lists
                               the dirty units on the host.  1: three small kernels do that on the GPU from the block
                               mask in device memory (Section 4 Step 5, Section 5 "Propagation": the same rules, the
@@ -445,6 +449,30 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers,
                      uint8_t* block_mask, int32_t max_rects, dc_regions* regions_out,
                      void* ws_dev, size_t ws_dev_bytes, void* ws_host, size_t ws_host_bytes,
                      dc_stack_stats* stats, void* overlap, void* stream);
+
+/*
+ * Section 5 "Propagation" per pixel: exact reuse maps of every tensor of the stack, on the GPU.  Table 2 maps a
+ * reusable rectangle to the outputs whose windows lie wholly inside it; applied to the set of reusable pixels itself
+ * (the union of the blocks that passed Step 4) the rule reads: an output pixel is reusable iff every tap of its
+ * window lies inside the map and is reusable (taps in the zero padding are not; with extend_borders they are ignored
+ * for a stream whose motion is (0,0)); add / concat: reusable in every input; LRN over pixels: its window; FC and
+ * softmax: nothing; and in every tensor only pixels whose source at +(dx, dy) = round(M / cumulative stride) lies
+ * inside the map.  The maps contain Step 5's propagated rectangles and lose nothing at the seams between them
+ * (Section 4 counts 18 against 24 pixels for two 5x5 blocks under a 3x3 kernel).
+ *   block_mask, global_mv   dev, as written by dc_match_blocks
+ *   bitmaps    dev out [n_streams][words_per_stream]: tensor t of a stream starts at word tensor_offset[t]; row y is
+ *              (w + 31) / 32 words, pixel x is bit x % 32 of word x / 32; bits beyond the row are 0
+ *   dxy        dev out [n_streams][n_layers + 1][2]: source offset of every tensor
+ *   ws_dev     at least ws_dev_bytes of dc_propagate_masks_size plus 4 * n_streams * (n_layers + 3) bytes
+ * dc_propagate_masks_size: words of one stream's bitmaps, optionally every tensor's first word (host [n_layers + 1]),
+ * and the workspace bytes.  The call waits once for its layer tables to be on the device (it is meant for
+ * inspection and tests; dc_run_stack runs the same kernels without a wait when dc_match_options.exact_masks is set).
+ */
+int32_t dc_propagate_masks_size(const dc_layer* layers, int32_t n_layers, int32_t H, int32_t W, int32_t C,
+                                size_t* words_per_stream, int64_t* tensor_offset, size_t* ws_dev_bytes);
+int32_t dc_propagate_masks(const dc_layer* layers, int32_t n_layers, int32_t n_streams, int32_t H, int32_t W, int32_t C,
+                           int32_t block, const uint8_t* block_mask, const int32_t* global_mv, int32_t extend_borders,
+                           uint32_t* bitmaps, int32_t* dxy, void* ws_dev, size_t ws_dev_bytes, void* stream);
 
 /*
  * Work counters of the most recent dc_run_stack call that planned its frame on the GPU with this host workspace

@@ -24,7 +24,8 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
            "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_prefetch_match", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_propagate_regions_opt", "dc_conv_workspace_bytes",
            "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer", "dc_avgpool_layer", "dc_lrn_layer", "dc_concat_layer", "dc_fc_layer", "dc_softmax_layer",
-           "dc_stack_workspace_bytes", "dc_run_stack", "dc_stack_stats_fetch", "dc_cached_conv_layer_noalloc"]
+           "dc_stack_workspace_bytes", "dc_run_stack", "dc_stack_stats_fetch", "dc_cached_conv_layer_noalloc",
+           "dc_propagate_masks_size", "dc_propagate_masks"]
 
 
 class DcError(RuntimeError):
@@ -49,7 +50,8 @@ class Regions(C.Structure):
 
 
 class MatchOptions(C.Structure):
-    _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32), ("extend_borders", C.c_int32), ("device_plan", C.c_int32)]
+    _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32), ("extend_borders", C.c_int32), ("exact_masks", C.c_int32),
+                ("device_plan", C.c_int32)]
 
 
 DC_MATCH_EXHAUSTIVE, DC_MATCH_DIAMOND = 0, 1
@@ -109,6 +111,8 @@ def lib():
                                    vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp, vp]
         L.dc_stack_stats_fetch.argtypes = [vp, sz, vp]
         L.dc_cached_conv_layer_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp]
+        L.dc_propagate_masks_size.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz), vp, C.POINTER(sz)]
+        L.dc_propagate_masks.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
         for name in EXPORTS:
             if name != "dc_status_string":
                 getattr(L, name).restype = i32
@@ -322,6 +326,34 @@ def dc_cached_conv_layer_noalloc(layer, x, weights, bias, out, cache_prev=None, 
     return out
 
 
+def dc_propagate_masks(layers, H, W, Ch, block, block_mask, gmv, extend_borders=False):
+    """Exact reuse maps on the GPU.  block_mask: cuda uint8 [n][gh][gw]; gmv: cuda int32 [n][2].  Returns
+    (list per tensor of numpy bool [n][h][w], numpy int32 dxy [n][tensors][2])."""
+    n = block_mask.shape[0]
+    nl = len(layers)
+    Lc = layers_to_c(layers)
+    words, wsb = C.c_size_t(), C.c_size_t()
+    offs = (C.c_int64 * (nl + 1))()
+    _check("dc_propagate_masks_size", lib().dc_propagate_masks_size(Lc, nl, H, W, Ch, C.byref(words), offs, C.byref(wsb)))
+    dev = block_mask.device
+    bitmaps = torch.zeros((n, words.value), dtype=torch.int32, device=dev)
+    dxy = torch.zeros((n, nl + 1, 2), dtype=torch.int32, device=dev)
+    ws = torch.empty(wsb.value + 4 * n * (nl + 3) + 256, dtype=torch.uint8, device=dev)
+    _check("dc_propagate_masks", lib().dc_propagate_masks(Lc, nl, n, H, W, Ch, block, _ptr(block_mask), _ptr(gmv),
+                                                          int(extend_borders), _ptr(bitmaps), _ptr(dxy), _ptr(ws), ws.numel(), _stream()))
+    torch.cuda.synchronize()
+    raw = bitmaps.cpu().numpy().view(np.uint32)
+    shapes = synth.tensor_shapes(layers, H, W, Ch)
+    masks = []
+    for t, (h, w, _) in enumerate(shapes):
+        wpr = (w + 31) // 32
+        rows = raw[:, offs[t]:offs[t] + h * wpr].reshape(n, h, wpr)
+        bits = ((rows[..., None] >> np.arange(32, dtype=np.uint32)) & 1).astype(bool).reshape(n, h, wpr * 32)
+        assert not bits[..., w:].any()
+        masks.append(bits[..., :w])
+    return masks, dxy.cpu().numpy()
+
+
 def dc_frame_to_tensor(frames, dtype=DC_F32, c_tensor=None):
     cf = frames.shape[-1]
     ct = cf if c_tensor is None else int(c_tensor)
@@ -423,7 +455,8 @@ class StackRunner:
     def __init__(self, layers, weights, biases, n_streams, H, W, Ch=3, block=16, radius=16,
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
                  want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True,
-                 match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False, extend_borders=False, device_plan=False):
+                 match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False, extend_borders=False, device_plan=False,
+                 exact_masks=False):
         self.device_plan = bool(device_plan) and not in_place
         self.in_place = bool(in_place)
         self.last_in_place = False
@@ -435,7 +468,9 @@ class StackRunner:
         self.block, self.radius, self.dtype, self.expiry = block, radius, dtype, expiry
         self.max_block_ssd = int(max_block_ssd if max_block_ssd is not None else synth.max_block_ssd(block, Ch))
         self.max_rects = max_rects
-        self.match_options = MatchOptions(int(match_method), int(k_skip), int(extend_borders), int(self.device_plan))
+        self.exact_masks = bool(exact_masks)
+        self.match_options = MatchOptions(int(match_method), int(k_skip), int(extend_borders), int(self.exact_masks),
+                                          int(self.device_plan))
         self.device = torch.device(device)
         td = torch_dtype(dtype)
         self.Lc = layers_to_c(layers)

@@ -216,6 +216,8 @@ struct DevPlanLayout {
     std::vector<int> conv_layer;                // layer index of every conv
     size_t table_bytes = 0, off_tensors = 0, off_convs = 0;
     size_t frame_bytes = 0, off_nrect = 0, off_dxy = 0, off_info = 0, off_nunits = 0, off_stats = 0, off_area = 0;
+    size_t off_bitmaps = 0;
+    int64_t bm_words = 0;                       // words of all bitmaps of one stream (exact reuse maps)
     int cap = 0, max_chunks = 0;
     bool ok = false;
 };
@@ -230,12 +232,15 @@ void device_plan_layout(const dc_layer* L, int n_layers, const std::vector<int>&
     d.cap = max_rects < kPlanMaxRects ? max_rects : kPlanMaxRects;
     d.layers.resize(n_layers); d.tensors.resize(nt); d.convs.clear(); d.conv_layer.clear();
     d.tensors[0] = PlanTensorDev{hs[0], ws[0], 1, 0};
+    int64_t bm = ((int64_t)hs[0] * ((ws[0] + 31) / 32) + 63) / 64 * 64;          // every bitmap starts on a 256-byte line
     for (int i = 0; i < n_layers; ++i) {
         const dc_layer& l = L[i];
         d.layers[i] = PlanLayerDev{l.type, l.k, l.s, l.p, l.in0, l.in1, l.in2, l.in3, l.within, 0, 0, 0};
         const bool windowed = l.type == DC_CONV || l.type == DC_MAXPOOL || l.type == DC_AVGPOOL;
         const int cum = d.tensors[l.in0].cum_stride * (windowed ? l.s : 1);
-        d.tensors[i + 1] = PlanTensorDev{hs[i + 1], ws[i + 1], cum, 0};
+        if (bm > 0x7fffffffll) return;
+        d.tensors[i + 1] = PlanTensorDev{hs[i + 1], ws[i + 1], cum, (int32_t)bm};
+        bm += ((int64_t)hs[i + 1] * ((ws[i + 1] + 31) / 32) + 63) / 64 * 64;
         if (l.type == DC_ADD && d.tensors[l.in1].cum_stride != d.tensors[l.in0].cum_stride) return;
         if (l.type == DC_CONCAT) {
             int ids[4];
@@ -255,6 +260,8 @@ void device_plan_layout(const dc_layer* L, int n_layers, const std::vector<int>&
     d.off_info = off; off += align_up((size_t)n_streams * 2 * sizeof(int32_t), 256);
     d.off_nunits = off; off += align_up(d.conv_layer.size() * sizeof(int32_t), 256);
     d.off_stats = off; off += kDevHostSlot;
+    d.bm_words = bm;
+    d.off_bitmaps = off; off += align_up((size_t)n_streams * (size_t)bm * sizeof(uint32_t), 256);
     d.off_area = off;
     size_t area = 0;
     d.max_chunks = 0;
@@ -957,6 +964,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     if (match_options) {
         if (match_options->method != DC_MATCH_EXHAUSTIVE && match_options->method != DC_MATCH_DIAMOND) return DC_ERR_INVALID_ARG;
         if (match_options->k_skip < 1) return DC_ERR_INVALID_ARG;
+        if (match_options->exact_masks && (!match_options->device_plan || in_place)) return DC_ERR_UNSUPPORTED;   // planned on the GPU only
     }
     if (cached) {
         if (!frames_prev || !tensors_prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask || !ws_dev || !ws_host)
@@ -1163,6 +1171,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         pd.stream_info = reinterpret_cast<int32_t*>(frame + dl.off_info);
         pd.n_units = reinterpret_cast<int32_t*>(frame + dl.off_nunits);
         pd.area = frame + dl.off_area;
+        pd.bitmaps = reinterpret_cast<uint32_t*>(frame + dl.off_bitmaps);
+        pd.bm_words = dl.bm_words;
         unsigned char* const slot_host = slots + (size_t)slot * kDevHostSlot;
         const unsigned char* alias = device_alias(ws_host);
         pd.stats = alias ? const_cast<unsigned char*>(alias) + (slot_host - static_cast<unsigned char*>(ws_host))
@@ -1184,7 +1194,10 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                                      max_block_ssd, mv, best_ssd, global_mv, n_pass, block_mask, pst);
             if (rc) return rc;
         }
-        DC_TRY_HIP(launch_plan(pd, block_mask, global_mv, gh, gw, block, match_options->extend_borders, dl.max_chunks, pst));
+        if (match_options->exact_masks)
+            DC_TRY_HIP(launch_plan_exact(pd, block_mask, global_mv, gh, gw, block, match_options->extend_borders, dl.max_chunks, true, pst));
+        else
+            DC_TRY_HIP(launch_plan(pd, block_mask, global_mv, gh, gw, block, match_options->extend_borders, dl.max_chunks, pst));
         if (!alias)
             DC_TRY_HIP(hipMemcpyAsync(slot_host, frame + dl.off_stats, sizeof(PlanStatsHead) + dl.convs.size() * sizeof(PlanStatsConv),
                                       hipMemcpyDeviceToHost, pst));
@@ -1561,6 +1574,70 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         ov->frame_parity ^= 1;
     }
     if (stats) *stats = local;
+    return DC_OK;
+}
+
+int32_t dc_propagate_masks_size(const dc_layer* layers, int32_t n_layers, int32_t H, int32_t W, int32_t C,
+                                size_t* words_per_stream, int64_t* tensor_offset, size_t* ws_dev_bytes) {
+    if (!layers || !words_per_stream || !ws_dev_bytes) return DC_ERR_NULL_PTR;
+    if (n_layers < 1 || H < 1 || W < 1 || C < 1) return DC_ERR_INVALID_ARG;
+    std::vector<int> hs, ws, cs;
+    const int c_tensor = input_channels(layers, n_layers, C);
+    if (c_tensor < C) return DC_ERR_BAD_SHAPE;
+    int rc = validate_layers(layers, n_layers, H, W, c_tensor, &hs, &ws, &cs);
+    if (rc) return rc;
+    try {
+        DevPlanLayout dl;
+        device_plan_layout(layers, n_layers, hs, ws, 1, 1, dl);
+        if (!dl.ok) return DC_ERR_UNSUPPORTED;
+        *words_per_stream = (size_t)dl.bm_words;
+        *ws_dev_bytes = dl.table_bytes + 256;
+        if (tensor_offset)
+            for (int t = 0; t <= n_layers; ++t) tensor_offset[t] = dl.tensors[t].bm_off;
+    } catch (const std::bad_alloc&) {
+        return DC_ERR_WORKSPACE;
+    }
+    return DC_OK;
+}
+
+int32_t dc_propagate_masks(const dc_layer* layers, int32_t n_layers, int32_t n_streams, int32_t H, int32_t W, int32_t C,
+                           int32_t block, const uint8_t* block_mask, const int32_t* global_mv, int32_t extend_borders,
+                           uint32_t* bitmaps, int32_t* dxy, void* ws_dev, size_t ws_dev_bytes, void* stream) {
+    if (!layers || !block_mask || !global_mv || !bitmaps || !dxy || !ws_dev) return DC_ERR_NULL_PTR;
+    if (n_layers < 1 || n_streams < 1 || H < 1 || W < 1 || C < 1 || block < 1) return DC_ERR_INVALID_ARG;
+    if (block > H || block > W) return DC_ERR_BAD_SHAPE;
+    std::vector<int> hs, ws, cs;
+    const int c_tensor = input_channels(layers, n_layers, C);
+    if (c_tensor < C) return DC_ERR_BAD_SHAPE;
+    int rc = validate_layers(layers, n_layers, H, W, c_tensor, &hs, &ws, &cs);
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    try {
+        DevPlanLayout dl;
+        device_plan_layout(layers, n_layers, hs, ws, n_streams, 1, dl);
+        if (!dl.ok) return DC_ERR_UNSUPPORTED;
+        if (ws_dev_bytes < dl.table_bytes + 256) return DC_ERR_WORKSPACE;
+        std::vector<unsigned char> tables(dl.table_bytes, 0);
+        std::memcpy(tables.data(), dl.layers.data(), dl.layers.size() * sizeof(PlanLayerDev));
+        std::memcpy(tables.data() + dl.off_tensors, dl.tensors.data(), dl.tensors.size() * sizeof(PlanTensorDev));
+        unsigned char* const table_dev = static_cast<unsigned char*>(ws_dev);
+        DC_TRY_HIP(hipMemcpyAsync(table_dev, tables.data(), dl.table_bytes, hipMemcpyHostToDevice, st));
+        DC_TRY_HIP(hipStreamSynchronize(st));          // `tables` goes away with this scope
+        PlanDev pd{};
+        pd.layers = reinterpret_cast<const PlanLayerDev*>(table_dev);
+        pd.tensors = reinterpret_cast<const PlanTensorDev*>(table_dev + dl.off_tensors);
+        pd.n_layers = n_layers; pd.n_convs = 0; pd.n_streams = n_streams; pd.cap = 1;
+        pd.dxy = dxy;
+        // the kernel also leaves a block count and empty rectangle lists: into the tail of the workspace
+        int32_t* tail = reinterpret_cast<int32_t*>(table_dev + dl.table_bytes);
+        if (ws_dev_bytes < dl.table_bytes + 256 + (size_t)n_streams * (n_layers + 3) * sizeof(int32_t)) return DC_ERR_WORKSPACE;
+        pd.stream_info = tail + 64;
+        pd.nrect = tail + 64 + 2 * n_streams;
+        pd.bitmaps = bitmaps; pd.bm_words = dl.bm_words;
+        DC_TRY_HIP(launch_plan_exact(pd, block_mask, global_mv, H / block, W / block, block, extend_borders, 0, false, st));
+    } catch (const std::bad_alloc&) {
+        return DC_ERR_WORKSPACE;
+    }
     return DC_OK;
 }
 

@@ -147,7 +147,7 @@ constexpr int kPlanChunk = 256;          // units per workgroup of the mask / li
 struct PlanLayerDev {                    // one layer; tensor i + 1 is its output
     int32_t type, k, s, p, in0, in1, in2, in3, within, pad0, pad1, pad2;
 };
-struct PlanTensorDev { int32_t h, w, cum_stride, pad; };
+struct PlanTensorDev { int32_t h, w, cum_stride, bm_off; };   // bm_off: first word of the tensor's bitmap (exact maps)
 struct PlanConvDev {                     // one conv layer's share of the plan area (offsets in bytes from its start)
     int32_t tensor, Hout, Wout, units_x, units_y, n_chunks, pad0, pad1;
     int64_t umask_off, count_off, list_off, pad2;
@@ -168,9 +168,18 @@ struct PlanDev {                         // device addresses of one frame's plan
     unsigned char* area;                 // base of the per-layer arrays (PlanConvDev offsets)
     int32_t* n_units;                    // [conv]
     void* stats;                         // PlanStatsHead + n_convs x PlanStatsConv; device memory or pinned host memory
+    // exact reuse maps (optional): one bit per pixel, rows of (w + 31) / 32 words, tensor t of stream s at
+    // bitmaps + s * bm_words + tensors[t].bm_off
+    uint32_t* bitmaps;
+    int64_t bm_words;
 };
 hipError_t launch_plan(const PlanDev& P, const uint8_t* block_mask, const int32_t* gmv, int gh, int gw, int block,
                        int extend_borders, int max_chunks, hipStream_t st);
+// The same with exact reuse maps instead of rectangles: plan_erode_kernel (one workgroup per stream) derives every
+// tensor's bitmap from its producers' (a pixel is reusable iff every tap of its window is), then the unit masks are
+// cut out of the bitmaps and listed as above.  with_lists = false stops after the bitmaps.
+hipError_t launch_plan_exact(const PlanDev& P, const uint8_t* block_mask, const int32_t* gmv, int gh, int gw, int block,
+                             int extend_borders, int max_chunks, bool with_lists, hipStream_t st);
 // The same for one conv layer whose rectangles come from the host and are small enough to travel as kernel arguments
 // (no staging buffer, no copy): a set-up kernel writes them where the mask and list kernels expect them.
 constexpr int kArgMaxRects = 128;        // rectangles of all streams together

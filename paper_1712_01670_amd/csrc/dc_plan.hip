@@ -292,6 +292,187 @@ __device__ __forceinline__ unsigned inside_mask(int Hout, int Wout, int ty, int 
     return rows * ((1u << ww) - 1u);
 }
 
+// ---- exact reuse maps -------------------------------------------------------------------------------------
+// 64 bits of a bitmap row starting at bit `start` (which may be negative or reach beyond the row): bits outside
+// [0, w) read as `outside`; row == nullptr: the whole row lies outside the map.
+__device__ __forceinline__ unsigned long long row_bits(const uint32_t* row, int w, int start, bool outside) {
+    const int wpr = (w + 31) >> 5;
+    const int w0 = start >> 5, sh = start & 31;           // arithmetic shift: floor for negative starts
+    unsigned v[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        const int i = w0 + j;
+        unsigned x = outside ? ~0u : 0u;
+        if (row && i >= 0 && i < wpr) {
+            x = row[i];
+            const int valid = w - 32 * i;                  // bits of this word that lie inside the row
+            if (outside && valid < 32) x |= ~0u << valid;
+        }
+        v[j] = x;
+    }
+    unsigned long long r = (((unsigned long long)v[1] << 32) | v[0]) >> sh;
+    if (sh) r |= (unsigned long long)v[2] << (64 - sh);
+    return r;
+}
+// even bits of x packed into the low half
+__device__ __forceinline__ unsigned even_bits(unsigned long long x) {
+    x &= 0x5555555555555555ull;
+    x = (x | (x >> 1)) & 0x3333333333333333ull;
+    x = (x | (x >> 2)) & 0x0f0f0f0f0f0f0f0full;
+    x = (x | (x >> 4)) & 0x00ff00ff00ff00ffull;
+    x = (x | (x >> 8)) & 0x0000ffff0000ffffull;
+    x = (x | (x >> 16)) & 0x00000000ffffffffull;
+    return (unsigned)x;
+}
+// bits [lo, hi) of a 32-bit word that starts at pixel column x0
+__device__ __forceinline__ unsigned column_range(int x0, int lo, int hi) {
+    const int a = lo - x0 < 0 ? 0 : lo - x0, b = hi - x0 > 32 ? 32 : hi - x0;
+    if (b <= a) return 0u;
+    const unsigned upto_b = b >= 32 ? ~0u : ((1u << b) - 1u);
+    return upto_b & ~((1u << a) - 1u);
+}
+
+// One workgroup per stream.  Tensor after tensor (a barrier in between: a layer reads the bitmaps of earlier
+// tensors, which this workgroup wrote), every thread computes whole 32-pixel words of the output bitmap:
+//   windowed layers (conv, pooling, LRN over pixels)  AND over the k x k window, word-parallel for strides 1 and 2
+//     (the k shifted copies of an input row are ANDed, for stride 2 every second bit is kept), bit by bit otherwise;
+//     taps outside the map read 0, or 1 for a stream that did not move when the border case is on;
+//   add / concat  AND of the inputs;   FC / softmax  nothing;   others  a copy;
+// and every tensor is cut to the pixels whose source at +(dx, dy) lies inside the map.
+__global__ __launch_bounds__(256) void plan_erode_kernel(PlanDev P, const uint8_t* __restrict__ block_mask,
+                                                         const int32_t* __restrict__ gmv, int gh, int gw, int B, int ext_opt) {
+    const int stream = blockIdx.x, tid = threadIdx.x;
+    const int nt = P.n_layers + 1;
+    __shared__ PlanLayerDev s_layers[kPlanMaxTensors];
+    __shared__ PlanTensorDev s_tensors[kPlanMaxTensors];
+    __shared__ long long s_tmp[4];
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(P.layers);
+        uint4* dst = reinterpret_cast<uint4*>(s_layers);
+        for (int j = tid; j < P.n_layers * 3; j += 256) dst[j] = src[j];
+        const uint4* tsrc = reinterpret_cast<const uint4*>(P.tensors);
+        uint4* tdst = reinterpret_cast<uint4*>(s_tensors);
+        for (int j = tid; j < nt; j += 256) tdst[j] = tsrc[j];
+    }
+    const int mx = gmv[2 * stream], my = gmv[2 * stream + 1];
+    const bool ext = ext_opt != 0 && mx == 0 && my == 0;
+    uint32_t* const maps = P.bitmaps + (size_t)stream * P.bm_words;
+    int32_t* const dxy = P.dxy + (size_t)stream * nt * 2;
+    __syncthreads();
+    // tensor 0: the pixels of the blocks that passed Step 4
+    {
+        const PlanTensorDev t0 = s_tensors[0];
+        const int wpr = (t0.w + 31) >> 5;
+        const uint8_t* m = block_mask + (size_t)stream * gh * gw;
+        int reusable = 0;
+        for (int j = tid; j < gh * gw; j += 256) reusable += m[j] ? 1 : 0;
+        const long long total = block_sum(reusable, s_tmp);
+        if (tid == 0) { P.stream_info[2 * stream] = (int32_t)total; P.stream_info[2 * stream + 1] = 0; dxy[0] = mx; dxy[1] = my; }
+        for (int i = tid; i < t0.h * wpr; i += 256) {
+            const int y = i / wpr, x0 = (i - y * wpr) * 32;
+            const int by = y / B;
+            unsigned bits = 0;
+            if (by < gh && y + my >= 0 && y + my < t0.h)
+                for (int b = 0; b < 32; ++b) {
+                    const int x = x0 + b, bx = x / B;
+                    if (x < t0.w && bx < gw && m[by * gw + bx]) bits |= 1u << b;
+                }
+            maps[t0.bm_off + i] = bits & column_range(x0, -mx < 0 ? 0 : -mx, t0.w - mx < t0.w ? t0.w - mx : t0.w);
+        }
+    }
+    __syncthreads();
+    for (int li = 0; li < P.n_layers; ++li) {
+        const PlanLayerDev L = s_layers[li];
+        const PlanTensorDev ta = s_tensors[L.in0], tt = s_tensors[li + 1];
+        const int dx = round_half_away(mx, tt.cum_stride), dy = round_half_away(my, tt.cum_stride);
+        if (tid == 0) { dxy[2 * (li + 1)] = dx; dxy[2 * (li + 1) + 1] = dy; }
+        const uint32_t* in = maps + ta.bm_off;
+        uint32_t* out = maps + tt.bm_off;
+        const int wpr_in = (ta.w + 31) >> 5, wpr = (tt.w + 31) >> 5;
+        const bool windowed = L.type == DC_CONV || L.type == DC_MAXPOOL || L.type == DC_AVGPOOL;
+        const bool lrn_px = L.type == DC_LRN && L.within != 0;
+        const int k = (windowed || lrn_px) ? L.k : 1, s = windowed ? L.s : 1, p = windowed ? L.p : (lrn_px ? (L.k - 1) / 2 : 0);
+        const int col_lo = -dx < 0 ? 0 : -dx, col_hi = tt.w - dx < tt.w ? tt.w - dx : tt.w;
+        for (int i = tid; i < tt.h * wpr; i += 256) {
+            const int y = i / wpr, x0 = (i - y * wpr) * 32;
+            unsigned bits;
+            if (L.type == DC_FC || L.type == DC_SOFTMAX) {
+                bits = 0;
+            } else if (L.type == DC_ADD) {
+                bits = in[i] & maps[s_tensors[L.in1].bm_off + i];
+            } else if (L.type == DC_CONCAT) {
+                bits = in[i] & maps[s_tensors[L.in1].bm_off + i];
+                if (L.in2 >= 0) bits &= maps[s_tensors[L.in2].bm_off + i];
+                if (L.in2 >= 0 && L.in3 >= 0) bits &= maps[s_tensors[L.in3].bm_off + i];
+            } else if (k == 1 && s == 1 && p == 0) {
+                bits = in[i];
+            } else if (s <= 2 && k <= 32) {
+                unsigned long long acc = ~0ull;            // bit b: the whole window that starts at input column c0 + b
+                const int c0 = x0 * s - p;
+                for (int ky = 0; ky < k; ++ky) {
+                    const int iy = y * s - p + ky;
+                    const bool row_in = iy >= 0 && iy < ta.h;
+                    if (!row_in && ext) continue;           // taps in the padding are ignored
+                    const uint32_t* row = row_in ? in + (size_t)iy * wpr_in : nullptr;
+                    const unsigned long long lo = row_bits(row, ta.w, c0, ext), hi = row_bits(row, ta.w, c0 + 64, ext);
+                    unsigned long long r = lo;
+                    for (int kx = 1; kx < k; ++kx) r &= (lo >> kx) | (hi << (64 - kx));
+                    acc &= r;
+                }
+                bits = s == 1 ? (unsigned)acc : even_bits(acc);
+            } else {                                        // any stride: bit by bit
+                bits = 0;
+                for (int b = 0; b < 32 && x0 + b < tt.w; ++b) {
+                    bool ok = true;
+                    for (int ky = 0; ky < k && ok; ++ky)
+                        for (int kx = 0; kx < k && ok; ++kx) {
+                            const int iy = y * s - p + ky, ix = (x0 + b) * s - p + kx;
+                            if (iy < 0 || iy >= ta.h || ix < 0 || ix >= ta.w) { ok = ext; continue; }
+                            ok = (in[(size_t)iy * wpr_in + (ix >> 5)] >> (ix & 31)) & 1u;
+                        }
+                    if (ok) bits |= 1u << b;
+                }
+            }
+            const bool row_ok = y + dy >= 0 && y + dy < tt.h;
+            out[i] = row_ok ? (bits & column_range(x0, col_lo, col_hi)) : 0u;
+        }
+        __syncthreads();
+    }
+    for (int t = tid; t < nt; t += 256) P.nrect[(size_t)stream * nt + t] = 0;      // no rectangles in this mode
+}
+
+// The 16-bit unit masks of every conv layer cut out of the bitmaps (grid and outputs as plan_masks_kernel).
+__global__ __launch_bounds__(kPlanChunk) void plan_masks_exact_kernel(PlanDev P) {
+    const int chunk = blockIdx.x, stream = blockIdx.y, c = blockIdx.z, tid = threadIdx.x;
+    const PlanConvDev cv = P.convs[c];
+    if (chunk >= cv.n_chunks) return;
+    __shared__ long long s_tmp[4];
+    const PlanTensorDev tt = P.tensors[cv.tensor];
+    const uint32_t* map = P.bitmaps + (size_t)stream * P.bm_words + tt.bm_off;
+    const int wpr = (cv.Wout + 31) >> 5;
+    const int units = cv.units_x * cv.units_y;
+    const int u = chunk * kPlanChunk + tid;
+    unsigned mask = 0;
+    int dirty = 0;
+    if (u < units) {
+        const int ty = u / cv.units_x, tx = u - ty * cv.units_x;
+        const int x0 = tx * 4;                               // a unit's four columns lie in one word
+        for (int r = 0; r < 4; ++r) {
+            const int y = ty * 4 + r;
+            if (y < cv.Hout) mask |= ((map[(size_t)y * wpr + (x0 >> 5)] >> (x0 & 31)) & 0xfu) << (4 * r);
+        }
+        const unsigned inside = inside_mask(cv.Hout, cv.Wout, ty, tx);
+        dirty = (mask & inside) != inside ? 1 : 0;
+        reinterpret_cast<uint16_t*>(P.area + cv.umask_off)[(size_t)stream * units + u] = (uint16_t)mask;
+    }
+    const long long both_sums = block_sum(((long long)dirty << 32) | (long long)__popc(mask), s_tmp);
+    if (tid == 0) {
+        int32_t* cnt = reinterpret_cast<int32_t*>(P.area + cv.count_off) + ((size_t)stream * cv.n_chunks + chunk) * 2;
+        cnt[0] = (int32_t)(both_sums >> 32);
+        cnt[1] = (int32_t)(both_sums & 0xffffffffll);
+    }
+}
+
 __global__ __launch_bounds__(kPlanChunk) void plan_masks_kernel(PlanDev P) {
     const int chunk = blockIdx.x, stream = blockIdx.y, c = blockIdx.z, tid = threadIdx.x;
     const PlanConvDev cv = P.convs[c];
@@ -493,6 +674,20 @@ hipError_t launch_plan_from_args(const PlanDev& P, const PlanConvDev& conv, cons
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)conv.n_chunks, (unsigned)P.n_streams, 1);
     hipLaunchKernelGGL(plan_masks_kernel, grid, dim3(kPlanChunk), 0, st, P);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(plan_lists_kernel, grid, dim3(kPlanChunk), 0, st, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_exact(const PlanDev& P, const uint8_t* block_mask, const int32_t* gmv, int gh, int gw, int block,
+                             int extend_borders, int max_chunks, bool with_lists, hipStream_t st) {
+    if (P.n_layers + 1 > kPlanMaxTensors || !P.bitmaps || gh < 1 || gw < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(plan_erode_kernel, dim3(P.n_streams), dim3(256), 0, st, P, block_mask, gmv, gh, gw, block, extend_borders);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !with_lists || P.n_convs == 0) return e;
+    const dim3 grid((unsigned)max_chunks, (unsigned)P.n_streams, (unsigned)P.n_convs);
+    hipLaunchKernelGGL(plan_masks_exact_kernel, grid, dim3(kPlanChunk), 0, st, P);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(plan_lists_kernel, grid, dim3(kPlanChunk), 0, st, P);

@@ -22,13 +22,15 @@ def _elem_err(got, want):
     return float((np.abs(got - want) / np.maximum(np.abs(want), 1e-3 * scale)).max())
 
 
-def _run_both(oracle, layers, videos, block, radius, bf16, in_place=False, device_plan=None, **kw):
+def _run_both(oracle, layers, videos, block, radius, bf16, in_place=False, device_plan=None, exact_masks=False, **kw):
     """Every frame of every stream against the oracle, with the frame planned on the host and (unless in-place frames
     are asked for, which only the host plans) once more with the frame planned on the GPU."""
     modes = [False] if in_place else ([False, True] if device_plan is None else [bool(device_plan)])
+    if exact_masks:          # exact reuse maps exist on the GPU only
+        modes = [True]
     first = None
     for dp in modes:
-        res = _run_one(oracle, layers, videos, block, radius, bf16, in_place=in_place, device_plan=dp, **kw)
+        res = _run_one(oracle, layers, videos, block, radius, bf16, in_place=in_place, device_plan=dp, exact_masks=exact_masks, **kw)
         if first is None:
             first = res
         else:
@@ -38,7 +40,7 @@ def _run_both(oracle, layers, videos, block, radius, bf16, in_place=False, devic
 
 def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False,
-             extend_borders=False, device_plan=False):
+             extend_borders=False, device_plan=False, exact_masks=False):
     """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
     n, T, H, W, C = videos.shape
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale, input_shape=(H, W, C))
@@ -47,9 +49,9 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
     runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
                                  want_regions=True, k_skip=k_skip, in_place=in_place, extend_borders=extend_borders,
                                  match_method=binding.DC_MATCH_DIAMOND if diamond else binding.DC_MATCH_EXHAUSTIVE,
-                                 device_plan=device_plan)
+                                 device_plan=device_plan, exact_masks=exact_masks)
     streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry,
-                             diamond=diamond, k_skip=k_skip, extend_borders=extend_borders)
+                             diamond=diamond, k_skip=k_skip, extend_borders=extend_borders, exact_masks=exact_masks)
                for _ in range(n)]
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
     worst = worst_elem = 0.0
@@ -57,7 +59,8 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
     runner.in_place_frames = []
     shapes = runner.shapes
     for t in range(T):
-        print(f"[stack] frame {t}/{T} n={n} {H}x{W} bf16={bf16} planned on the {'GPU' if device_plan else 'host'}", flush=True)
+        print(f"[stack] frame {t}/{T} n={n} {H}x{W} bf16={bf16} planned on the {'GPU' if device_plan else 'host'}"
+              f"{', exact reuse maps' if exact_masks else ''}", flush=True)
         if t in resets:
             runner.reset()
             for s in streams:
@@ -79,6 +82,9 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
                 assert np.array_equal(runner.mask[s].cpu().numpy(), m["mask"])
                 regs = runner.regions(s)
                 for ti in range(len(layers) + 1):
+                    if exact_masks:              # no rectangle lists in this mode; the maps are checked by the counters below
+                        assert len(regs[ti]["rects"]) == 0
+                        continue
                     assert regs[ti]["rects"].tolist() == want["rects"][ti].tolist(), (t, s, ti)
                     assert list(regs[ti]["dxy"]) == want["dxy"][ti].tolist()
                 reuse.append(float(m["mask"].mean()))
@@ -86,7 +92,8 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
                 for li, L in enumerate(layers):
                     if L["type"] == synth.CONV:
                         ho, wo, _ = shapes[li + 1]
-                        reused = int(sum(int(r[2]) * int(r[3]) for r in want["rects"][li + 1]))
+                        reused = (int(want["masks"][li + 1].sum()) if exact_masks else
+                                  int(sum(int(r[2]) * int(r[3]) for r in want["rects"][li + 1])))
                         needed += (ho * wo - reused) * L["k"] * L["k"] * runner.layers[li]["cin"] * L["cout"]
             for ti in (check_tensors or range(len(layers) + 1)):
                 g = got[ti][s]
@@ -370,6 +377,37 @@ def test_throughput_mode_64_streams_bf16_sampled(oracle, device_plan):
             for s in range(0, n, 7):
                 m = oracle.match_blocks(videos[s, t], videos[s, t - 1], 16, 16, synth.max_block_ssd(16))
                 assert np.array_equal(masks[s], m["mask"]) and gmv[s].tolist() == m["gmv"].tolist()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_exact_reuse_maps_tiny_and_vgg(oracle, bf16):
+    """dc_match_options.exact_masks: the conv layers reuse the pixels of the exact maps; tensors and work counters
+    against the oracle's stream in the same mode."""
+    f1, f2 = synth.tiny_pair(0)
+    runner, reuse = _run_both(oracle, synth.tiny_net(), np.stack([f1, f2, f2, f1])[None], 8, 8, bf16, exact_masks=True)
+    assert abs(reuse[0] - 45 / 64) < 1e-9
+    v = np.stack([synth.panning_video(5000 + s, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
+    _run_both(oracle, synth.vgg16(), v, 16, 16, bf16, bias_scale=0.0, exact_masks=True)
+
+
+def test_exact_reuse_maps_other_stacks(oracle):
+    v = synth.panning_video(3000, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32)[None]
+    _run_both(oracle, synth.resnet50_trunk()[:23], v, 16, 16, True, bias_scale=0.0, residual_scale=0.5, exact_masks=True)
+    v = synth.reuse_sweep_video(4001, 0.75, n_frames=3, H=128, W=128, cut_at=2)[None]
+    _run_both(oracle, synth.darknet19()[:12], v, 16, 16, True, bias_scale=0.0, resets=(2,), exact_masks=True)
+    layers = synth.alexnet(n_classes=40, width=0.25)
+    video = np.stack([synth.panning_video(300 + s, n_frames=3, H=227, W=227) for s in range(2)])
+    _run_both(oracle, layers, video, 10, 8, False, exact_masks=True)
+    video = np.stack([_static_then_moving(700 + s, 96, 96, 3, 2) for s in range(2)])
+    _run_both(oracle, synth.vgg16()[:10], video, 16, 8, True, extend_borders=True, exact_masks=True)
+
+
+def test_exact_reuse_maps_vgg16_224_save_more(oracle):
+    """configs[1] with exact maps: parity on the first frames, and fewer multiply-adds needed than with rectangles."""
+    video = synth.panning_video(2000, n_frames=3)[None]
+    exact, _ = _run_both(oracle, synth.vgg16(), video, 16, 16, False, bias_scale=0.0, exact_masks=True)
+    rect, _ = _run_both(oracle, synth.vgg16(), video, 16, 16, False, bias_scale=0.0, device_plan=True)
+    assert exact.read_stats().macs_needed < rect.read_stats().macs_needed
 
 
 def test_border_case_planned_on_the_gpu(oracle):
