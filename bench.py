@@ -68,7 +68,7 @@ def traffic_calib():
     print(json.dumps({"traffic_calib": "device copy", "bytes_read": n, "bytes_written": n, "launches": 5}))
 
 
-def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames):
+def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exact_masks=None):
     import numpy as np
     import torch
     from paper_1712_01670_amd import binding, synth
@@ -83,9 +83,10 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames):
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(dev)
     dt = binding.DC_BF16 if dtype == "bf16" else binding.DC_F32
     method = binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE
+    exact = (args.regions == "exact" if exact_masks is None else exact_masks) and not args.host_plan
     runner = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
                                  match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan,
-                                 exact_masks=args.exact_masks and not args.host_plan)
+                                 exact_masks=exact)
 
     def run_steps(k, start, collect=None, force_full=False):
         """Run k steps through the cyclic video starting at global step `start`."""
@@ -199,6 +200,14 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames):
                  "avg_launch_us": (copy["ms"] / copy["launches"] * 1e3) if copy["launches"] else None},
     }
 
+    if dtype == "bf16":     # what the matrix cores sustain on this GPU under its power limit, measured now
+        regs, lds = binding.dc_probe_mfma_rate(0), binding.dc_probe_mfma_rate(1)
+        roofline["sustained_mfma"] = {
+            "registers_only": regs, "with_lds_reads": lds, "unit": "TFLOP/s",
+            "frac_of_with_lds_reads": roofline["achieved"] / lds,
+            "note": "v_mfma_f32_16x16x32_bf16, 4x4 tiles per wavefront, 8 wavefronts on every CU, 30 launches of 0.3 ms back to "
+                    "back, the last one timed: operands in registers, and re-read from LDS every step as the conv kernels do"}
+
     # ---- the matching alone (Steps 1-4), HIP events on the launch stream; allocations are outside the events ----
     torch.cuda.synchronize()
     mbs = synth.max_block_ssd(16, 3)
@@ -237,7 +246,7 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames):
     if not args.no_cpu_baseline:
         from oracle import oracle as oc
         ref = oc.Stream(layers, ws, bs, H, W, 3, block=16, radius=16, bf16=(dtype == "bf16"), expiry=args.expiry,
-                        diamond=(args.matcher == "ds"), k_skip=args.k_skip, exact_masks=args.exact_masks and not args.host_plan)
+                        diamond=(args.matcher == "ds"), k_skip=args.k_skip, exact_masks=exact)
         k_cpu = min(cpu_frames, n_frames)
         t0 = time.perf_counter()
         for f in range(k_cpu):
@@ -277,8 +286,9 @@ def main():
                          "one frame ahead would allow")
     ap.add_argument("--host-plan", action="store_true",
                     help="merge / propagate / list the dirty units on the host (one wait per frame) instead of on the GPU")
-    ap.add_argument("--exact-masks", action="store_true",
-                    help="reuse the pixels of the exact reuse maps (the propagation rule per pixel) instead of the rectangles'")
+    ap.add_argument("--regions", choices=["exact", "rect"], default="exact",
+                    help="what is reused: the pixels of the exact reuse maps (Table 2's rule per pixel, planned on the GPU), or "
+                         "the rectangles of Step 5 propagated by Table 2 as the paper prints it")
     ap.add_argument("--no-single", action="store_true", help="skip the single-stream fp32 sub-record")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=30)
@@ -314,12 +324,18 @@ def main():
                    "streams": n, "matcher": ("exhaustive search" if args.matcher == "es" else "diamond search") + f", k-skip {args.k_skip}",
                    "cache_expiry_frames": args.expiry, "frames_per_video": 30, "repeats": args.repeats,
                    "planning": "host" if args.host_plan else "device",
-                   "reusable_regions": "exact maps" if (args.exact_masks and not args.host_plan) else "rectangles",
+                   "reusable_regions": "exact maps (Table 2's rule per pixel)" if (args.regions == "exact" and not args.host_plan)
+                                       else "rectangles (Table 2 as printed)",
                    "lookahead_frames": 1 if args.lookahead else 0, **detail},
     }
     out.update(main_rec)
     if single is not None:
         out["single_stream_f32"] = single
+    if args.regions == "exact" and not args.host_plan and not args.no_single:
+        # the paper's own form of the regions (rectangles) on the same workload: frames/s and saving only
+        rect = run_workload(args, n, args.dtype, args.steps, args.warmup, args.repeats, False, 0, exact_masks=False)
+        rect["config"] = {"reusable_regions": "rectangles (Table 2 as printed)", "streams": n, "steps": args.steps}
+        out["rectangles"] = rect
     print(json.dumps(out))
 
 

@@ -158,6 +158,16 @@ int32_t dc_profile_reset(void* profile);
 int32_t dc_profile_elapsed_ms(void* profile, int32_t slot, float* ms);
 
 /*
+ * Measurement aid: the bf16 matrix-core rate this GPU sustains (TFLOP/s) for the instruction stream of the
+ * convolution kernels' inner loop, v_mfma_f32_16x16x32_bf16 on 4 x 4 tiles per wavefront, eight wavefronts on each
+ * of 256 CUs, operands in registers (lds_reads = 0) or re-read from LDS every step as the kernels do (1).  Thirty
+ * launches of about 0.3 ms run back to back and the last one is timed with HIP events, so the figure is the rate at
+ * the clock the part settles at under its power limit, which is what a kernel can reach instead of the published
+ * peak.  scratch_dev: at least 4 MiB of device memory (overwritten).  The call waits for the launches.
+ */
+int32_t dc_probe_mfma_rate(int32_t lds_reads, void* scratch_dev, size_t scratch_bytes, double* tflops, void* stream);
+
+/*
  * Overlap handle (Section 7.6: matching and inference can run asynchronously): streams and
  * events owned by the library object.  Passed to dc_run_stack,
  *  - the matching of a frame runs on a stream of its own, next to whatever is still queued of

@@ -25,7 +25,7 @@ EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_pr
            "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_prefetch_match", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_propagate_regions_opt", "dc_conv_workspace_bytes",
            "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer", "dc_avgpool_layer", "dc_lrn_layer", "dc_concat_layer", "dc_fc_layer", "dc_softmax_layer",
            "dc_stack_workspace_bytes", "dc_run_stack", "dc_stack_stats_fetch", "dc_cached_conv_layer_noalloc",
-           "dc_propagate_masks_size", "dc_propagate_masks"]
+           "dc_propagate_masks_size", "dc_propagate_masks", "dc_probe_mfma_rate"]
 
 
 class DcError(RuntimeError):
@@ -111,6 +111,7 @@ def lib():
                                    vp, vp, vp, vp, vp, i32, vp, vp, sz, vp, sz, vp, vp, vp]
         L.dc_stack_stats_fetch.argtypes = [vp, sz, vp]
         L.dc_cached_conv_layer_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp]
+        L.dc_probe_mfma_rate.argtypes = [i32, vp, sz, C.POINTER(C.c_double), vp]
         L.dc_propagate_masks_size.argtypes = [vp, i32, i32, i32, i32, C.POINTER(sz), vp, C.POINTER(sz)]
         L.dc_propagate_masks.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
         for name in EXPORTS:
@@ -638,6 +639,14 @@ class StackRunner:
         nl = len(self.layers)
         return dict(reused_px=[self._reused[i] for i in range(nl)], issued_macs=[self._issued[i] for i in range(nl)],
                     kernel_id=[self._kid[i] for i in range(nl)])
+
+
+def dc_probe_mfma_rate(lds_reads, device="cuda:0"):
+    """Sustained bf16 MFMA rate in TFLOP/s (operands in registers, or re-read from LDS as the conv kernels do)."""
+    scratch = torch.empty(4 << 20, dtype=torch.uint8, device=device)
+    tf = C.c_double()
+    _check("dc_probe_mfma_rate", lib().dc_probe_mfma_rate(int(lds_reads), _ptr(scratch), scratch.numel(), C.byref(tf), _stream()))
+    return tf.value
 
 
 def dc_conv_tuning(arrangement=-1, units_per_workgroup=-1, k_split=-1, chunk_index=-1):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdeepcache.so")
-SOURCES = ["dc_api.hip", "dc_conv.hip", "dc_conv_fast.hip", "dc_layers.hip", "dc_match.hip", "dc_plan.hip", "dc_regions.cpp"]
+SOURCES = ["dc_api.hip", "dc_conv.hip", "dc_conv_fast.hip", "dc_layers.hip", "dc_match.hip", "dc_plan.hip", "dc_probe.hip", "dc_regions.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

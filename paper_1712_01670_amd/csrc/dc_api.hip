@@ -371,6 +371,18 @@ int32_t dc_profile_elapsed_ms(void* profile, int32_t slot, float* ms) {
     return DC_OK;
 }
 
+int32_t dc_probe_mfma_rate(int32_t lds_reads, void* scratch_dev, size_t scratch_bytes, double* tflops, void* stream) {
+    if (!scratch_dev || !tflops) return DC_ERR_NULL_PTR;
+    if (scratch_bytes < ((size_t)4 << 20)) return DC_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(scratch_dev) % 16) return DC_ERR_INVALID_ARG;
+    const int wgs = 256, steps = 1024, launches = 30;       // about 0.3 ms per launch
+    float ms = 0.f;
+    DC_TRY_HIP(probe_mfma_rate(lds_reads != 0, scratch_dev, wgs, steps, launches, &ms, as_stream(stream)));
+    if (!(ms > 0.f)) return DC_ERR_HIP;
+    *tflops = (double)wgs * 8 * steps * 16 * 16384.0 / (ms * 1e-3) / 1e12;
+    return DC_OK;
+}
+
 int32_t dc_overlap_create(void** overlap) {
     if (!overlap) return DC_ERR_NULL_PTR;
     Overlap* o = new (std::nothrow) Overlap();

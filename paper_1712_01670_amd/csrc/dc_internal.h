@@ -204,6 +204,10 @@ constexpr int kCopyUnitsMaxLayers = 32;
 hipError_t launch_shifted_copy_units(const CopyUnitsLayer* layers, int n_layers, const int32_t* dxy, int n_tensors,
                                      int n_streams, int vec_bytes, hipStream_t st);
 
+// Sustained bf16 MFMA rate (dc_probe.hip): `launches` back-to-back launches of wgs workgroups x 8 wavefronts x steps x
+// 16 MFMAs (16x16x32); the duration of the last one.  scratch: 4 MiB of device memory.
+hipError_t probe_mfma_rate(int lds_reads, void* scratch, int wgs, int steps, int launches, float* last_ms, hipStream_t st);
+
 // Event pairs for kernel timing (measurement aid).
 struct Profile {
     std::vector<hipEvent_t> ev;   // 2 per slot: start, stop

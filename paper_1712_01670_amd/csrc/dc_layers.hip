@@ -345,6 +345,43 @@ __global__ __launch_bounds__(kThreads) void pool_vec_kernel(const uint4* __restr
     }
 }
 
+// The pooling of the VGG- and Darknet-style stacks, 2x2 windows with stride 2 and no padding: every window lies
+// inside the map, so a thread's four loads have fixed offsets and go out together (two outputs per thread: eight
+// loads in flight).  grid.y = (stream, output row), grid.x covers the Wout * CV vectors of the row.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void maxpool2x2_vec_kernel(const uint4* __restrict__ in, uint4* __restrict__ out,
+                                                                  int Hin, int Win, int CV, int Hout, int Wout) {
+    constexpr int VE = Vec16<T>::VE;
+    const int row = blockIdx.y;                     // stream * Hout + y
+    const int stream = row / Hout, y = row - stream * Hout;
+    const int row_vecs = Wout * CV;
+    const uint4* __restrict__ r0 = in + ((size_t)stream * Hin + 2 * y) * Win * CV;
+    const uint4* __restrict__ r1 = r0 + (size_t)Win * CV;
+    uint4* __restrict__ o = out + (size_t)row * row_vecs;
+    const int j0 = (int)blockIdx.x * (2 * kThreads) + (int)threadIdx.x, j1 = j0 + kThreads;
+    float a[2][4][VE];
+    bool on[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int j = q ? j1 : j0;
+        on[q] = j < row_vecs;
+        const int x = on[q] ? j / CV : 0, cv = on[q] ? j - x * CV : 0;
+        const int at = 2 * x * CV + cv;
+        Vec16<T>::load(r0 + at, a[q][0]);
+        Vec16<T>::load(r0 + at + CV, a[q][1]);
+        Vec16<T>::load(r1 + at, a[q][2]);
+        Vec16<T>::load(r1 + at + CV, a[q][3]);
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        if (!on[q]) continue;
+        float m[VE];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) m[e] = fmaxf(fmaxf(a[q][0][e], a[q][1][e]), fmaxf(a[q][2][e], a[q][3][e]));
+        Vec16<T>::store(o + (q ? j1 : j0), m);
+    }
+}
+
 // out = a + b (b == nullptr: out = a), optional ReLU, 16 bytes per thread.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void add_vec_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b,
@@ -523,6 +560,16 @@ hipError_t launch_pool(const void* in, void* out, int n_streams, int Hin, int Wi
     if ((C * dtype_size(dtype)) % 16 == 0 && reinterpret_cast<uintptr_t>(in) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0) {
         const int cv = (int)(C * dtype_size(dtype) / 16);
         const size_t nv = (size_t)n_streams * Hout * Wout * cv;
+        if (!AVG && k == 2 && s == 2 && p == 0 && (size_t)n_streams * Hout <= 65535 && (size_t)Hin * Win * cv < 0x7fffffffull) {
+            const dim3 grid((unsigned)((Wout * cv + 2 * kThreads - 1) / (2 * kThreads)), (unsigned)(n_streams * Hout));
+            if (dtype == DC_BF16)
+                hipLaunchKernelGGL(maxpool2x2_vec_kernel<__hip_bfloat16>, grid, dim3(kThreads), 0, st, (const uint4*)in, (uint4*)out,
+                                   Hin, Win, cv, Hout, Wout);
+            else
+                hipLaunchKernelGGL(maxpool2x2_vec_kernel<float>, grid, dim3(kThreads), 0, st, (const uint4*)in, (uint4*)out, Hin,
+                                   Win, cv, Hout, Wout);
+            return hipGetLastError();
+        }
         if (dtype == DC_BF16)
             hipLaunchKernelGGL((pool_vec_kernel<__hip_bfloat16, AVG>), dim3(grid_for(nv)), dim3(kThreads), 0, st,
                                (const uint4*)in, (uint4*)out, n_streams, Hin, Win, cv, Hout, Wout, k, s, p);
