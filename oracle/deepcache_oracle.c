@@ -926,10 +926,14 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
                  int bf16, const oc_rect* rects0, int n0, int mx, int my,
                  float* const* cur, const float* const* prev,
                  oc_rect* rects, int cap, int32_t* n_rects, int32_t* dxy,
-                 int32_t* cum_stride, int32_t* hw, int extend_borders, const uint8_t* const* exact_masks)
+                 int32_t* cum_stride, int32_t* hw, int extend_borders, const uint8_t* const* exact_masks,
+                 int cache_pool_add)
 {
     /* exact_masks (optional): the maps of oc_propagate_masks for this frame; the conv layers then reuse exactly
-     * those pixels instead of the rectangles' */
+     * those pixels instead of the rectangles'.
+     * cache_pool_add (with exact_masks): max-pooling and add layers use the cache like the conv layers (Section 5
+     * notes that the cache extends to other layer types): where the layer's map is set the output is the previous
+     * frame's output of that layer at the tensor's offset, elsewhere it is computed. */
     int cached = n0 >= 0;
     int rc = oc_propagate_ext(L, n_layers, H, W, rects0, cached ? n0 : 0, cached ? mx : 0,
                               cached ? my : 0, extend_borders, rects, cap, n_rects, dxy, cum_stride, hw);
@@ -956,6 +960,17 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
             oc_maxpool(cur[a], ha, wa, l->cin, l->k, l->s, l->p, cur[t]);
         } else if (l->type == OC_ADD) {
             oc_add(cur[a], cur[l->in1], (size_t)ho * wo * l->cout, l->relu, bf16, cur[t]);
+        }
+        if (cached && exact_masks && cache_pool_add && (l->type == OC_MAXPOOL || l->type == OC_ADD)) {
+            int dx = dxy[2 * t], dy = dxy[2 * t + 1];
+            for (int y = 0; y < ho; ++y)
+                for (int x = 0; x < wo; ++x)
+                    if (exact_masks[t][(size_t)y * wo + x])
+                        memcpy(cur[t] + ((size_t)y * wo + x) * l->cout,
+                               prev[t] + ((size_t)(y + dy) * wo + (x + dx)) * l->cout, (size_t)l->cout * sizeof(float));
+        }
+        if (l->type == OC_CONV || l->type == OC_MAXPOOL || l->type == OC_ADD) {
+            /* done above */
         } else if (l->type == OC_AVGPOOL) {
             oc_avgpool(cur[a], ha, wa, l->cin, l->k, l->s, l->p, bf16, cur[t]);
         } else if (l->type == OC_LRN) {

@@ -331,8 +331,9 @@ class Stream:
     the previous feature maps (cache values), Section 3."""
 
     def __init__(self, layers, weights, biases, H, W, Ch=3, block=16, radius=16, max_ssd=None,
-                 bf16=False, expiry=0, cap=1024, diamond=False, k_skip=1, extend_borders=False, exact_masks=False):
+                 bf16=False, expiry=0, cap=1024, diamond=False, k_skip=1, extend_borders=False, exact_masks=False, cache_pool_add=False):
         self.diamond, self.k_skip, self.extend_borders, self.exact_masks = diamond, k_skip, extend_borders, exact_masks
+        self.cache_pool_add = bool(cache_pool_add) and bool(exact_masks)
         self.layers, self.H, self.W, self.Ch = layers, H, W, Ch
         self.block, self.radius, self.bf16, self.expiry, self.cap = block, radius, bf16, expiry, cap
         self.max_ssd = max_ssd if max_ssd is not None else 20 * block * block * Ch
@@ -396,7 +397,8 @@ class Stream:
             mp = (C.c_void_p * (n + 1))(*[a.ctypes.data for a in masks])
         rc = lib().oc_run_stack(self.Lc, n, self._wp, self._bp, _p(frame), self.H, self.W, self.Ch,
                                 int(self.bf16), _p(r0), n0, mx, my, curp, prevp, _p(rects),
-                                self.cap, _p(n_rects), _p(dxy), _p(cs), _p(hw), int(self.extend_borders), mp)
+                                self.cap, _p(n_rects), _p(dxy), _p(cs), _p(hw), int(self.extend_borders), mp,
+                                int(self.cache_pool_add))
         assert rc == 0
         self.bufs = [prev, cur]  # cur becomes next frame's prev
         self.prev_frame = frame.copy()

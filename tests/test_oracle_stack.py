@@ -109,10 +109,12 @@ def test_cached_conv_copies_exactly_where_masked(oracle):
     assert np.array_equal(out[2:6, 3:9], cache[1:5, 5:11])
 
 
-def _run_video(oracle, layers, frames, block, radius, bf16=False, expiry=0, seed=1, bias_scale=0.1, exact_masks=False):
+def _run_video(oracle, layers, frames, block, radius, bf16=False, expiry=0, seed=1, bias_scale=0.1, exact_masks=False,
+               cache_pool_add=False):
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale)
     H, W, C = frames[0].shape
-    st = oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry, exact_masks=exact_masks)
+    st = oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry, exact_masks=exact_masks,
+                       cache_pool_add=cache_pool_add)
     outs = []
     for f in frames:
         r = st.step(f)
@@ -319,3 +321,52 @@ def test_exact_masks_values_come_from_the_cache(oracle):
         assert np.array_equal(outs[1]["tensors"][t][ys, xs], outs[0]["tensors"][t][ys + dy, xs + dx])
         assert np.array_equal(outs[1]["tensors"][t][~m], full[t][~m]) or t > 1      # layer 1 reads exact inputs
         assert not np.array_equal(outs[1]["tensors"][t][m], full[t][m])
+
+
+# ---- max-pooling and add layers that use the cache too (Section 5: the cache extends to other layer types) ---------
+def _pool_add_stack():
+    C_ = lambda cin, cout, i, relu=1: dict(type=synth.CONV, k=3, s=1, p=1, cin=cin, cout=cout, relu=relu, in0=i, in1=-1)
+    return [C_(3, 8, 0), dict(type=synth.MAXPOOL, k=2, s=2, p=0, cin=8, cout=8, relu=0, in0=1, in1=-1),
+            C_(8, 8, 2), C_(8, 8, 3, 0), dict(type=synth.ADD, k=1, s=1, p=0, cin=8, cout=8, relu=1, in0=4, in1=2),
+            dict(type=synth.MAXPOOL, k=3, s=2, p=1, cin=8, cout=8, relu=0, in0=5, in1=-1), C_(8, 8, 6)]
+
+
+def test_cached_pool_and_add_exact_shift_equals_full_forward(oracle):
+    layers = _pool_add_stack()           # total stride 4
+    f1, f2 = synth.shifted_pair(10, 64, 64, (8, -4))
+    f2 = f2.copy()
+    f2[24:40, 8:24] = np.random.default_rng(3).integers(0, 256, (16, 16, 3))
+    outs, (ws, bs) = _run_video(oracle, layers, [f1, f2], 8, 8, exact_masks=True, cache_pool_add=True)
+    assert outs[1]["match"]["gmv"].tolist() == [-8, 4]
+    full = _full_forward(oracle, layers, ws, bs, f2)
+    for t in range(1, len(layers) + 1):
+        assert np.array_equal(outs[1]["tensors"][t], full[t]), t
+    for t in (2, 5, 6):                  # the pooling and add outputs were really taken from the cache
+        m = outs[1]["masks"][t].astype(bool)
+        dx, dy = (int(v) for v in outs[1]["dxy"][t])
+        ys, xs = np.nonzero(m)
+        assert len(ys) > 20
+        assert np.array_equal(outs[1]["tensors"][t][ys, xs], outs[0]["tensors"][t][ys + dy, xs + dx])
+
+
+def test_cached_pool_and_add_take_their_values_from_the_cache(oracle):
+    # a noisy frame moved by (3, -2): not a multiple of the strides, so a pooled value from the cache differs from
+    # the pooling of the current (copied) conv output; the option decides which one the stream holds
+    layers = _pool_add_stack()
+    f1, f2 = synth.tiny_pair(0)
+    on, _ = _run_video(oracle, layers, [f1, f2], 8, 8, exact_masks=True, cache_pool_add=True)
+    off, _ = _run_video(oracle, layers, [f1, f2], 8, 8, exact_masks=True)
+    for t in (2, 5, 6):
+        m = on[1]["masks"][t].astype(bool)
+        dx, dy = (int(v) for v in on[1]["dxy"][t])
+        ys, xs = np.nonzero(m)
+        assert len(ys) > 10
+        assert np.array_equal(on[1]["tensors"][t][ys, xs], on[0]["tensors"][t][ys + dy, xs + dx])
+    assert np.array_equal(on[1]["tensors"][1], off[1]["tensors"][1])            # nothing changes before the first pooling
+    assert not np.array_equal(on[1]["tensors"][2], off[1]["tensors"][2])
+    # without any reuse the option changes nothing
+    rng = np.random.default_rng(6)
+    frames = [rng.integers(0, 256, (64, 64, 3)).astype(np.uint8) for _ in range(2)]
+    a, (ws, bs) = _run_video(oracle, layers, frames, 8, 8, exact_masks=True, cache_pool_add=True)
+    for x, y in zip(a[1]["tensors"], _full_forward(oracle, layers, ws, bs, frames[1])):
+        assert np.array_equal(x, y)
