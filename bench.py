@@ -86,7 +86,7 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
     exact = (args.regions == "exact" if exact_masks is None else exact_masks) and not args.host_plan
     runner = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
                                  match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan,
-                                 exact_masks=exact)
+                                 exact_masks=exact, cache_pool_add=exact and args.cache_pool_add)
 
     def run_steps(k, start, collect=None, force_full=False):
         """Run k steps through the cyclic video starting at global step `start`."""
@@ -246,7 +246,8 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
     if not args.no_cpu_baseline:
         from oracle import oracle as oc
         ref = oc.Stream(layers, ws, bs, H, W, 3, block=16, radius=16, bf16=(dtype == "bf16"), expiry=args.expiry,
-                        diamond=(args.matcher == "ds"), k_skip=args.k_skip, exact_masks=exact)
+                        diamond=(args.matcher == "ds"), k_skip=args.k_skip, exact_masks=exact,
+                        cache_pool_add=exact and args.cache_pool_add)
         k_cpu = min(cpu_frames, n_frames)
         t0 = time.perf_counter()
         for f in range(k_cpu):
@@ -289,6 +290,8 @@ def main():
     ap.add_argument("--regions", choices=["exact", "rect"], default="exact",
                     help="what is reused: the pixels of the exact reuse maps (Table 2's rule per pixel, planned on the GPU), or "
                          "the rectangles of Step 5 propagated by Table 2 as the paper prints it")
+    ap.add_argument("--cache-pool-add", action="store_true",
+                    help="with exact maps: max-pooling layers take their outputs from the cache too (Section 5)")
     ap.add_argument("--no-single", action="store_true", help="skip the single-stream fp32 sub-record")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=30)
@@ -326,6 +329,8 @@ def main():
                    "planning": "host" if args.host_plan else "device",
                    "reusable_regions": "exact maps (Table 2's rule per pixel)" if (args.regions == "exact" and not args.host_plan)
                                        else "rectangles (Table 2 as printed)",
+                   "cached_layers": "conv, max-pooling, add" if (args.cache_pool_add and args.regions == "exact" and not args.host_plan)
+                                    else "conv",
                    "lookahead_frames": 1 if args.lookahead else 0, **detail},
     }
     out.update(main_rec)

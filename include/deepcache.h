@@ -110,6 +110,11 @@ typedef struct {
                               the rectangles of Step 5, propagated by Table 2.  1: the same rule per pixel (see
                               dc_propagate_masks): exact reuse maps, which lose nothing at the seams between
                               rectangles.  No rectangle lists exist then (regions_out reports empty lists). */
+    int32_t cache_pool_add; /* dc_run_stack only, with exact_masks (DC_ERR_UNSUPPORTED without).  1: max-pooling and add layers
+                              use the cache like the conv layers (Section 5: the cache extends to other layer types): where
+                              the layer's map is set the output is the previous frame's output of that layer at the tensor's
+                              offset, elsewhere it is computed.  tensors_prev must then hold those layers' previous outputs
+                              (distinct buffers), and their channel runs must be whole 16-byte vectors. */
     int32_t device_plan;   /* dc_run_stack only.  0: the call waits for the matching, then merges, propagates and lists
                               the dirty units on the host.  1: three small kernels do that on the GPU from the block
                               mask in device memory (Section 4 Step 5, Section 5 "Propagation": the same rules, the

@@ -51,7 +51,7 @@ class Regions(C.Structure):
 
 class MatchOptions(C.Structure):
     _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32), ("extend_borders", C.c_int32), ("exact_masks", C.c_int32),
-                ("device_plan", C.c_int32)]
+                ("cache_pool_add", C.c_int32), ("device_plan", C.c_int32)]
 
 
 DC_MATCH_EXHAUSTIVE, DC_MATCH_DIAMOND = 0, 1
@@ -457,7 +457,7 @@ class StackRunner:
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
                  want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True,
                  match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False, extend_borders=False, device_plan=False,
-                 exact_masks=False):
+                 exact_masks=False, cache_pool_add=False):
         self.device_plan = bool(device_plan) and not in_place
         self.in_place = bool(in_place)
         self.last_in_place = False
@@ -470,8 +470,9 @@ class StackRunner:
         self.max_block_ssd = int(max_block_ssd if max_block_ssd is not None else synth.max_block_ssd(block, Ch))
         self.max_rects = max_rects
         self.exact_masks = bool(exact_masks)
+        self.cache_pool_add = bool(cache_pool_add) and self.exact_masks
         self.match_options = MatchOptions(int(match_method), int(k_skip), int(extend_borders), int(self.exact_masks),
-                                          int(self.device_plan))
+                                          int(self.cache_pool_add), int(self.device_plan))
         self.device = torch.device(device)
         td = torch_dtype(dtype)
         self.Lc = layers_to_c(layers)
@@ -489,7 +490,7 @@ class StackRunner:
         # two frames in flight: alternating those tensors too spares the library its cross-stream waits for them.
         is_conv = [False] + [L["type"] == synth.CONV for L in layers]
         self._is_conv_out = is_conv
-        both = bool(overlap and pipeline)
+        both = bool(overlap and pipeline) or bool(cache_pool_add and exact_masks)
         self.bufs = [[], []]
         for t, (h, w, c) in enumerate(self.shapes):
             a = torch.empty((n_streams, h, w, c), dtype=td, device=self.device)
@@ -564,7 +565,7 @@ class StackRunner:
         full = force_full or not self.have_prev or (self.expiry > 0 and self.age >= self.expiry)
         _check("dc_run_stack", lib().dc_run_stack(
             self.Lc, len(self.layers), self._wp, self._wpp, self._bp, _ptr(frames), _ptr(self.prev_frames),
-            self._tp[c][cn], self._tp[p][cn], self.n, self.H, self.W, self.Ch, self.dtype, self.block, self.radius,
+            self._tp[c][cn], self._tp[p][1 - cn if self.cache_pool_add else cn], self.n, self.H, self.W, self.Ch, self.dtype, self.block, self.radius,
             self.max_block_ssd, C.byref(self.match_options), int(full),
             C.byref(self._in_place_flag) if self.in_place else None, _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
             _ptr(self.mask), self.max_rects, self.regs, _ptr(self.ws_dev), self.ws_dev.numel(),

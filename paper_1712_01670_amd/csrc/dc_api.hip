@@ -977,6 +977,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         if (match_options->method != DC_MATCH_EXHAUSTIVE && match_options->method != DC_MATCH_DIAMOND) return DC_ERR_INVALID_ARG;
         if (match_options->k_skip < 1) return DC_ERR_INVALID_ARG;
         if (match_options->exact_masks && (!match_options->device_plan || in_place)) return DC_ERR_UNSUPPORTED;   // planned on the GPU only
+        if (match_options->cache_pool_add && !match_options->exact_masks) return DC_ERR_UNSUPPORTED;
     }
     if (cached) {
         if (!frames_prev || !tensors_prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask || !ws_dev || !ws_host)
@@ -993,6 +994,17 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     if (regions_out)      // checked before anything is launched: every list fits
         for (size_t i = 0; i < (size_t)n_streams * (n_layers + 1); ++i)
             if (regions_out[i].capacity < max_rects || !regions_out[i].rects) return DC_ERR_CAPACITY;
+    // max-pooling and add layers that use the cache: their outputs are cache values like the conv outputs
+    const bool cache_other = cached && match_options && match_options->cache_pool_add && match_options->exact_masks;
+    auto uses_cache = [&](int i) { return cache_other && (layers[i].type == DC_MAXPOOL || layers[i].type == DC_ADD); };
+    if (cache_other)
+        for (int i = 0; i < n_layers; ++i)
+            if (uses_cache(i)) {
+                if (!tensors_prev[i + 1] || tensors_prev[i + 1] == tensors_cur[i + 1]) return DC_ERR_NULL_PTR;
+                if ((cs[i + 1] * dtype_size(dtype)) % 16 || (size_t)n_streams * hs[i + 1] > 65535 ||
+                    reinterpret_cast<uintptr_t>(tensors_prev[i + 1]) % 16 || reinterpret_cast<uintptr_t>(tensors_cur[i + 1]) % 16)
+                    return DC_ERR_UNSUPPORTED;
+            }
     Overlap* ov = static_cast<Overlap*>(overlap);
     hipStream_t caller_st = as_stream(stream);
     // a look-ahead match is for the very next call only (the caller may reuse its frame buffers after that)
@@ -1047,6 +1059,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         if (last_reader[0] >= 0 && !fresh[0]) is_target[last_reader[0]] = 1;
         for (int i = 0; i < n_layers; ++i) {
             if (layers[i].type == DC_CONV) is_target[run_end[i]] = 1;
+            if (uses_cache(i)) is_target[i] = 1;          // the next frame reads this layer's output as its cache
             if ((layers[i].type != DC_CONV || in_place) && last_reader[i + 1] >= 0 && !fresh[i + 1])
                 is_target[last_reader[i + 1]] = 1;
         }
@@ -1524,11 +1537,25 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             }
             case DC_MAXPOOL:
                 DC_TRY_HIP(wait_readers(t));
+                if (devplan && uses_cache(i)) {
+                    DC_TRY_HIP(wait_prev(i));                 // its cache: the previous frame's output of this layer
+                    const CachedMap cm{pd.bitmaps, pd.bm_words, dl.tensors[t].bm_off, pd.dxy, n_layers + 1, t};
+                    DC_TRY_HIP(launch_maxpool_cached(eff[a], tensors_prev[t], eff[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
+                                                     dtype, cm, st));
+                    break;
+                }
                 DC_TRY_HIP(launch_maxpool(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], l.k, l.s, l.p,
                                           dtype, st));
                 break;
             case DC_ADD:
                 DC_TRY_HIP(wait_readers(t));
+                if (devplan && uses_cache(i)) {
+                    DC_TRY_HIP(wait_prev(i));
+                    const CachedMap cm{pd.bitmaps, pd.bm_words, dl.tensors[t].bm_off, pd.dxy, n_layers + 1, t};
+                    DC_TRY_HIP(launch_add_cached(eff[a], eff[l.in1], tensors_prev[t], eff[t], n_streams, hs[t], ws[t], cs[t], l.relu,
+                                                 dtype, cm, st));
+                    break;
+                }
                 DC_TRY_HIP(launch_add(eff[a], eff[l.in1], eff[t],
                                       (size_t)n_streams * hs[t] * ws[t] * cs[t], l.relu, dtype, st));
                 break;

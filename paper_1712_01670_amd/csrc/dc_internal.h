@@ -118,6 +118,19 @@ hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int
                           int s, int p, int dtype, hipStream_t st);
 hipError_t launch_add(const void* a, const void* b, void* out, size_t n, int relu, int dtype,
                       hipStream_t st);
+// Max-pooling and add layers that use the cache (exact reuse maps): where the output tensor's bitmap is set the
+// output is prev at +(dx, dy), elsewhere it is computed.  16-byte vectors of channels only (C * element size % 16 == 0).
+struct CachedMap {
+    const uint32_t* bitmaps;   // all streams' bitmaps
+    int64_t bm_words;          // words per stream
+    int32_t bm_off;            // first word of this tensor's bitmap
+    const int32_t* dxy;        // [stream][n_tensors][2]
+    int32_t n_tensors, tensor;
+};
+hipError_t launch_maxpool_cached(const void* in, const void* prev, void* out, int n_streams, int Hin, int Win, int C, int k,
+                                 int s, int p, int dtype, const CachedMap& M, hipStream_t st);
+hipError_t launch_add_cached(const void* a, const void* b, const void* prev, void* out, int n_streams, int H, int W, int C,
+                             int relu, int dtype, const CachedMap& M, hipStream_t st);
 hipError_t launch_avgpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k,
                           int s, int p, int dtype, hipStream_t st);
 hipError_t launch_lrn(const void* in, void* out, int n_streams, int H, int W, int C, int size, int within,

@@ -382,6 +382,64 @@ __global__ __launch_bounds__(kThreads) void maxpool2x2_vec_kernel(const uint4* _
     }
 }
 
+// Max-pooling and add with the cache: grid.y = (stream, output row), a thread takes one 16-byte vector of one pixel;
+// a pixel whose bit is set in the tensor's reuse bitmap receives the previous frame's output at the tensor's offset.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void maxpool_cached_kernel(const uint4* __restrict__ in, const uint4* __restrict__ prev,
+                                                                  uint4* __restrict__ out, int Hin, int Win, int CV, int Hout,
+                                                                  int Wout, int k, int s, int p, CachedMap M) {
+    constexpr int VE = Vec16<T>::VE;
+    const int row = blockIdx.y, stream = row / Hout, y = row - stream * Hout;
+    const int j = (int)blockIdx.x * kThreads + (int)threadIdx.x;
+    if (j >= Wout * CV) return;
+    const int x = j / CV, cv = j - x * CV;
+    const uint32_t* bits = M.bitmaps + (size_t)stream * M.bm_words + M.bm_off + (size_t)y * ((Wout + 31) >> 5);
+    uint4* o = out + (size_t)row * Wout * CV + j;
+    if ((bits[x >> 5] >> (x & 31)) & 1u) {
+        const size_t at = ((size_t)stream * M.n_tensors + M.tensor) * 2;
+        const int dx = M.dxy[at], dy = M.dxy[at + 1];
+        *o = prev[(((size_t)stream * Hout + (y + dy)) * Wout + (x + dx)) * CV + cv];
+        return;
+    }
+    float acc[VE];
+#pragma unroll
+    for (int e = 0; e < VE; ++e) acc[e] = -INFINITY;
+    const int y0 = max(y * s - p, 0), y1 = min(y * s - p + k, Hin), x0 = max(x * s - p, 0), x1 = min(x * s - p + k, Win);
+    for (int iy = y0; iy < y1; ++iy)
+        for (int ix = x0; ix < x1; ++ix) {
+            float f[VE];
+            Vec16<T>::load(in + (((size_t)stream * Hin + iy) * Win + ix) * CV + cv, f);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) acc[e] = fmaxf(acc[e], f[e]);
+        }
+    Vec16<T>::store(o, acc);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void add_cached_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b,
+                                                              const uint4* __restrict__ prev, uint4* __restrict__ out, int H, int W,
+                                                              int CV, int relu, CachedMap M) {
+    constexpr int VE = Vec16<T>::VE;
+    const int row = blockIdx.y, stream = row / H, y = row - stream * H;
+    const int j = (int)blockIdx.x * kThreads + (int)threadIdx.x;
+    if (j >= W * CV) return;
+    const int x = j / CV, cv = j - x * CV;
+    const uint32_t* bits = M.bitmaps + (size_t)stream * M.bm_words + M.bm_off + (size_t)y * ((W + 31) >> 5);
+    const size_t i = (size_t)row * W * CV + j;
+    if ((bits[x >> 5] >> (x & 31)) & 1u) {
+        const size_t at = ((size_t)stream * M.n_tensors + M.tensor) * 2;
+        const int dx = M.dxy[at], dy = M.dxy[at + 1];
+        out[i] = prev[(((size_t)stream * H + (y + dy)) * W + (x + dx)) * CV + cv];
+        return;
+    }
+    float u[VE], v[VE];
+    Vec16<T>::load(a + i, u);
+    Vec16<T>::load(b + i, v);
+#pragma unroll
+    for (int e = 0; e < VE; ++e) { u[e] += v[e]; if (relu) u[e] = u[e] > 0.f ? u[e] : 0.f; }
+    Vec16<T>::store(out + i, u);
+}
+
 // out = a + b (b == nullptr: out = a), optional ReLU, 16 bytes per thread.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void add_vec_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b,
@@ -591,6 +649,35 @@ hipError_t launch_pool(const void* in, void* out, int n_streams, int Hin, int Wi
 hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k, int s,
                           int p, int dtype, hipStream_t st) {
     return launch_pool<false>(in, out, n_streams, Hin, Win, C, k, s, p, dtype, st);
+}
+
+hipError_t launch_maxpool_cached(const void* in, const void* prev, void* out, int n_streams, int Hin, int Win, int C, int k,
+                                 int s, int p, int dtype, const CachedMap& M, hipStream_t st) {
+    const int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
+    if ((C * dtype_size(dtype)) % 16 || (size_t)n_streams * Hout > 65535) return hipErrorInvalidValue;
+    const int cv = (int)(C * dtype_size(dtype) / 16);
+    const dim3 grid((unsigned)((Wout * cv + kThreads - 1) / kThreads), (unsigned)(n_streams * Hout));
+    if (dtype == DC_BF16)
+        hipLaunchKernelGGL(maxpool_cached_kernel<__hip_bfloat16>, grid, dim3(kThreads), 0, st, (const uint4*)in, (const uint4*)prev,
+                           (uint4*)out, Hin, Win, cv, Hout, Wout, k, s, p, M);
+    else
+        hipLaunchKernelGGL(maxpool_cached_kernel<float>, grid, dim3(kThreads), 0, st, (const uint4*)in, (const uint4*)prev,
+                           (uint4*)out, Hin, Win, cv, Hout, Wout, k, s, p, M);
+    return hipGetLastError();
+}
+
+hipError_t launch_add_cached(const void* a, const void* b, const void* prev, void* out, int n_streams, int H, int W, int C,
+                             int relu, int dtype, const CachedMap& M, hipStream_t st) {
+    if ((C * dtype_size(dtype)) % 16 || (size_t)n_streams * H > 65535) return hipErrorInvalidValue;
+    const int cv = (int)(C * dtype_size(dtype) / 16);
+    const dim3 grid((unsigned)((W * cv + kThreads - 1) / kThreads), (unsigned)(n_streams * H));
+    if (dtype == DC_BF16)
+        hipLaunchKernelGGL(add_cached_kernel<__hip_bfloat16>, grid, dim3(kThreads), 0, st, (const uint4*)a, (const uint4*)b,
+                           (const uint4*)prev, (uint4*)out, H, W, cv, relu, M);
+    else
+        hipLaunchKernelGGL(add_cached_kernel<float>, grid, dim3(kThreads), 0, st, (const uint4*)a, (const uint4*)b,
+                           (const uint4*)prev, (uint4*)out, H, W, cv, relu, M);
+    return hipGetLastError();
 }
 
 hipError_t launch_avgpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k, int s,

@@ -23,6 +23,7 @@ def _elem_err(got, want):
 
 
 def _run_both(oracle, layers, videos, block, radius, bf16, in_place=False, device_plan=None, exact_masks=False, **kw):
+    exact_masks = exact_masks or bool(kw.get("cache_pool_add"))
     """Every frame of every stream against the oracle, with the frame planned on the host and (unless in-place frames
     are asked for, which only the host plans) once more with the frame planned on the GPU."""
     modes = [False] if in_place else ([False, True] if device_plan is None else [bool(device_plan)])
@@ -40,7 +41,7 @@ def _run_both(oracle, layers, videos, block, radius, bf16, in_place=False, devic
 
 def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False,
-             extend_borders=False, device_plan=False, exact_masks=False):
+             extend_borders=False, device_plan=False, exact_masks=False, cache_pool_add=False):
     """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
     n, T, H, W, C = videos.shape
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale, input_shape=(H, W, C))
@@ -49,9 +50,10 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
     runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
                                  want_regions=True, k_skip=k_skip, in_place=in_place, extend_borders=extend_borders,
                                  match_method=binding.DC_MATCH_DIAMOND if diamond else binding.DC_MATCH_EXHAUSTIVE,
-                                 device_plan=device_plan, exact_masks=exact_masks)
+                                 device_plan=device_plan, exact_masks=exact_masks, cache_pool_add=cache_pool_add)
     streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry,
-                             diamond=diamond, k_skip=k_skip, extend_borders=extend_borders, exact_masks=exact_masks)
+                             diamond=diamond, k_skip=k_skip, extend_borders=extend_borders, exact_masks=exact_masks,
+                             cache_pool_add=cache_pool_add)
                for _ in range(n)]
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
     worst = worst_elem = 0.0
@@ -408,6 +410,56 @@ def test_exact_reuse_maps_vgg16_224_save_more(oracle):
     exact, _ = _run_both(oracle, synth.vgg16(), video, 16, 16, False, bias_scale=0.0, exact_masks=True)
     rect, _ = _run_both(oracle, synth.vgg16(), video, 16, 16, False, bias_scale=0.0, device_plan=True)
     assert exact.read_stats().macs_needed < rect.read_stats().macs_needed
+
+
+def _pool_add_stack(c=8):
+    conv = lambda cin, cout, i, relu=1: dict(type=synth.CONV, k=3, s=1, p=1, cin=cin, cout=cout, relu=relu, in0=i, in1=-1)
+    return [conv(3, c, 0), dict(type=synth.MAXPOOL, k=2, s=2, p=0, cin=c, cout=c, relu=0, in0=1, in1=-1),
+            conv(c, c, 2), conv(c, c, 3, 0), dict(type=synth.ADD, k=1, s=1, p=0, cin=c, cout=c, relu=1, in0=4, in1=2),
+            dict(type=synth.MAXPOOL, k=3, s=2, p=1, cin=c, cout=c, relu=0, in0=5, in1=-1), conv(c, c, 6)]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_cached_pool_and_add_layers(oracle, bf16):
+    """dc_match_options.cache_pool_add: max-pooling and add outputs come from the cache where their maps are set
+    (Section 5).  The case is one where the option changes the result, so a library that ignored it would fail."""
+    layers = _pool_add_stack()
+    f1, f2 = synth.tiny_pair(0)                   # a noisy frame moved by (3, -2): not a multiple of the strides
+    video = np.stack([f1, f2, f2, f1])[None]
+    H, W, C = f1.shape
+    ws, bs = synth.he_weights(layers, 1, bias_scale=0.05, input_shape=(H, W, C))
+    on = oracle.Stream(layers, ws, bs, H, W, C, block=8, radius=8, bf16=bf16, exact_masks=True, cache_pool_add=True)
+    off = oracle.Stream(layers, ws, bs, H, W, C, block=8, radius=8, bf16=bf16, exact_masks=True)
+    a = [on.step(f) for f in (f1, f2)][1]["tensors"][2]
+    b = [off.step(f) for f in (f1, f2)][1]["tensors"][2]
+    assert _rel_err(a, b) > 0.05
+    _run_both(oracle, layers, video, 8, 8, bf16, cache_pool_add=True)
+    # several streams, a scene cut and a forced full frame in between
+    video = np.stack([synth.reuse_sweep_video(4100 + s, 0.75, n_frames=5, H=96, W=96, cut_at=3) for s in range(3)])
+    _run_both(oracle, layers, video, 8, 8, bf16, cache_pool_add=True, resets=(2,))
+
+
+def test_cached_pool_and_add_in_the_model_stacks(oracle):
+    v = np.stack([synth.panning_video(5000 + s, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
+    _run_both(oracle, synth.vgg16(), v, 16, 16, True, bias_scale=0.0, cache_pool_add=True)
+    v = synth.panning_video(3000, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32)[None]
+    _run_both(oracle, synth.resnet50_trunk()[:23], v, 16, 16, True, bias_scale=0.0, residual_scale=0.5, cache_pool_add=True)
+    v = synth.reuse_sweep_video(4001, 0.75, n_frames=3, H=128, W=128)[None]
+    _run_both(oracle, synth.darknet19()[:12], v, 16, 16, False, bias_scale=0.0, cache_pool_add=True)
+
+
+def test_cache_pool_add_needs_exact_maps_and_previous_outputs(oracle):
+    layers = _pool_add_stack()
+    f1, f2 = synth.tiny_pair(0)
+    H, W, C = f1.shape
+    ws, bs = synth.he_weights(layers, 1, input_shape=(H, W, C))
+    r = binding.StackRunner(layers, ws, bs, 1, H, W, C, block=8, radius=8, dtype=binding.DC_F32, device_plan=True,
+                            exact_masks=True, cache_pool_add=True)
+    r.match_options.exact_masks = 0
+    with pytest.raises(binding.DcError) as e:
+        r.step(torch.from_numpy(f1[None]).to(DEV))
+    assert e.value.status == -4
+    torch.cuda.synchronize()
 
 
 def test_border_case_planned_on_the_gpu(oracle):
