@@ -293,26 +293,19 @@ __device__ __forceinline__ unsigned inside_mask(int Hout, int Wout, int ty, int 
 }
 
 // ---- exact reuse maps -------------------------------------------------------------------------------------
-// 64 bits of a bitmap row starting at bit `start` (which may be negative or reach beyond the row): bits outside
-// [0, w) read as `outside`; row == nullptr: the whole row lies outside the map.
-__device__ __forceinline__ unsigned long long row_bits(const uint32_t* row, int w, int start, bool outside) {
-    const int wpr = (w + 31) >> 5;
-    const int w0 = start >> 5, sh = start & 31;           // arithmetic shift: floor for negative starts
-    unsigned v[3];
-#pragma unroll
-    for (int j = 0; j < 3; ++j) {
-        const int i = w0 + j;
-        unsigned x = outside ? ~0u : 0u;
-        if (row && i >= 0 && i < wpr) {
-            x = row[i];
-            const int valid = w - 32 * i;                  // bits of this word that lie inside the row
-            if (outside && valid < 32) x |= ~0u << valid;
-        }
-        v[j] = x;
+constexpr int kErodeThreads = 1024;
+constexpr int kErodeLdsWords = 32 * 1024;      // bitmaps of one stream up to this size (128 KB) stay in LDS
+
+// word i of a bitmap row of w pixels; words outside the row, and bits beyond w, read as `outside`;
+// row == nullptr: the whole row lies outside the map
+__device__ __forceinline__ unsigned row_word(const uint32_t* row, int wpr, int w, int i, bool outside) {
+    unsigned x = outside ? ~0u : 0u;
+    if (row && i >= 0 && i < wpr) {
+        x = row[i];
+        const int valid = w - 32 * i;                      // bits of this word that lie inside the row
+        if (outside && valid < 32) x |= ~0u << valid;
     }
-    unsigned long long r = (((unsigned long long)v[1] << 32) | v[0]) >> sh;
-    if (sh) r |= (unsigned long long)v[2] << (64 - sh);
-    return r;
+    return x;
 }
 // even bits of x packed into the low half
 __device__ __forceinline__ unsigned even_bits(unsigned long long x) {
@@ -332,56 +325,36 @@ __device__ __forceinline__ unsigned column_range(int x0, int lo, int hi) {
     return upto_b & ~((1u << a) - 1u);
 }
 
-// One workgroup per stream.  Tensor after tensor (a barrier in between: a layer reads the bitmaps of earlier
-// tensors, which this workgroup wrote), every thread computes whole 32-pixel words of the output bitmap:
+// The maps of one stream, tensor after tensor (a barrier in between: a layer reads the bitmaps of earlier tensors).
+// Every thread computes whole 32-pixel words of the output bitmap:
 //   windowed layers (conv, pooling, LRN over pixels)  AND over the k x k window, word-parallel for strides 1 and 2
 //     (the k shifted copies of an input row are ANDed, for stride 2 every second bit is kept), bit by bit otherwise;
 //     taps outside the map read 0, or 1 for a stream that did not move when the border case is on;
 //   add / concat  AND of the inputs;   FC / softmax  nothing;   others  a copy;
 // and every tensor is cut to the pixels whose source at +(dx, dy) lies inside the map.
-__global__ __launch_bounds__(256) void plan_erode_kernel(PlanDev P, const uint8_t* __restrict__ block_mask,
-                                                         const int32_t* __restrict__ gmv, int gh, int gw, int B, int ext_opt) {
-    const int stream = blockIdx.x, tid = threadIdx.x;
-    const int nt = P.n_layers + 1;
-    __shared__ PlanLayerDev s_layers[kPlanMaxTensors];
-    __shared__ PlanTensorDev s_tensors[kPlanMaxTensors];
-    __shared__ long long s_tmp[4];
-    {
-        const uint4* src = reinterpret_cast<const uint4*>(P.layers);
-        uint4* dst = reinterpret_cast<uint4*>(s_layers);
-        for (int j = tid; j < P.n_layers * 3; j += 256) dst[j] = src[j];
-        const uint4* tsrc = reinterpret_cast<const uint4*>(P.tensors);
-        uint4* tdst = reinterpret_cast<uint4*>(s_tensors);
-        for (int j = tid; j < nt; j += 256) tdst[j] = tsrc[j];
-    }
-    const int mx = gmv[2 * stream], my = gmv[2 * stream + 1];
-    const bool ext = ext_opt != 0 && mx == 0 && my == 0;
-    uint32_t* const maps = P.bitmaps + (size_t)stream * P.bm_words;
-    int32_t* const dxy = P.dxy + (size_t)stream * nt * 2;
-    __syncthreads();
-    // tensor 0: the pixels of the blocks that passed Step 4
-    {
+// `maps` is the stream's bitmap area: LDS when it fits (a layer is a few LDS round trips then, not a few trips to
+// the L2), the workspace otherwise.
+__device__ __forceinline__ void erode_stream(uint32_t* maps, const PlanLayerDev* s_layers, const PlanTensorDev* s_tensors,
+                                             int n_layers, int32_t* dxy, const uint8_t* m, int gh, int gw, int B, int mx, int my,
+                                             bool ext, int tid) {
+    {   // tensor 0: the pixels of the blocks that passed Step 4
         const PlanTensorDev t0 = s_tensors[0];
         const int wpr = (t0.w + 31) >> 5;
-        const uint8_t* m = block_mask + (size_t)stream * gh * gw;
-        int reusable = 0;
-        for (int j = tid; j < gh * gw; j += 256) reusable += m[j] ? 1 : 0;
-        const long long total = block_sum(reusable, s_tmp);
-        if (tid == 0) { P.stream_info[2 * stream] = (int32_t)total; P.stream_info[2 * stream + 1] = 0; dxy[0] = mx; dxy[1] = my; }
-        for (int i = tid; i < t0.h * wpr; i += 256) {
+        const int col_lo = -mx < 0 ? 0 : -mx, col_hi = t0.w - mx < t0.w ? t0.w - mx : t0.w;
+        for (int i = tid; i < t0.h * wpr; i += kErodeThreads) {
             const int y = i / wpr, x0 = (i - y * wpr) * 32;
             const int by = y / B;
             unsigned bits = 0;
-            if (by < gh && y + my >= 0 && y + my < t0.h)
-                for (int b = 0; b < 32; ++b) {
-                    const int x = x0 + b, bx = x / B;
-                    if (x < t0.w && bx < gw && m[by * gw + bx]) bits |= 1u << b;
-                }
-            maps[t0.bm_off + i] = bits & column_range(x0, -mx < 0 ? 0 : -mx, t0.w - mx < t0.w ? t0.w - mx : t0.w);
+            if (by < gh && y + my >= 0 && y + my < t0.h) {
+                const int bx_hi = (x0 + 31) / B < gw - 1 ? (x0 + 31) / B : gw - 1;
+                for (int bx = x0 / B; bx <= bx_hi; ++bx)
+                    if (m[by * gw + bx]) bits |= column_range(x0, bx * B, bx * B + B);
+            }
+            maps[t0.bm_off + i] = bits & column_range(x0, col_lo, col_hi);
         }
     }
     __syncthreads();
-    for (int li = 0; li < P.n_layers; ++li) {
+    for (int li = 0; li < n_layers; ++li) {
         const PlanLayerDev L = s_layers[li];
         const PlanTensorDev ta = s_tensors[L.in0], tt = s_tensors[li + 1];
         const int dx = round_half_away(mx, tt.cum_stride), dy = round_half_away(my, tt.cum_stride);
@@ -393,7 +366,7 @@ __global__ __launch_bounds__(256) void plan_erode_kernel(PlanDev P, const uint8_
         const bool lrn_px = L.type == DC_LRN && L.within != 0;
         const int k = (windowed || lrn_px) ? L.k : 1, s = windowed ? L.s : 1, p = windowed ? L.p : (lrn_px ? (L.k - 1) / 2 : 0);
         const int col_lo = -dx < 0 ? 0 : -dx, col_hi = tt.w - dx < tt.w ? tt.w - dx : tt.w;
-        for (int i = tid; i < tt.h * wpr; i += 256) {
+        for (int i = tid; i < tt.h * wpr; i += kErodeThreads) {
             const int y = i / wpr, x0 = (i - y * wpr) * 32;
             unsigned bits;
             if (L.type == DC_FC || L.type == DC_SOFTMAX) {
@@ -407,14 +380,22 @@ __global__ __launch_bounds__(256) void plan_erode_kernel(PlanDev P, const uint8_
             } else if (k == 1 && s == 1 && p == 0) {
                 bits = in[i];
             } else if (s <= 2 && k <= 32) {
-                unsigned long long acc = ~0ull;            // bit b: the whole window that starts at input column c0 + b
+                // bit b of acc: the whole window that starts at input column c0 + b.  Stride 1 needs 32 + k - 1 input
+                // columns from c0 (three words), stride 2 needs 64 + k - 1 (four).
+                unsigned long long acc = ~0ull;
                 const int c0 = x0 * s - p;
+                const int w0 = c0 >> 5, sh = c0 & 31;           // arithmetic shift: floor for negative starts
                 for (int ky = 0; ky < k; ++ky) {
                     const int iy = y * s - p + ky;
                     const bool row_in = iy >= 0 && iy < ta.h;
-                    if (!row_in && ext) continue;           // taps in the padding are ignored
+                    if (!row_in && ext) continue;               // taps in the padding are ignored
                     const uint32_t* row = row_in ? in + (size_t)iy * wpr_in : nullptr;
-                    const unsigned long long lo = row_bits(row, ta.w, c0, ext), hi = row_bits(row, ta.w, c0 + 64, ext);
+                    const unsigned v0 = row_word(row, wpr_in, ta.w, w0, ext), v1 = row_word(row, wpr_in, ta.w, w0 + 1, ext);
+                    const unsigned v2 = row_word(row, wpr_in, ta.w, w0 + 2, ext);
+                    const unsigned v3 = s == 2 ? row_word(row, wpr_in, ta.w, w0 + 3, ext) : 0u;
+                    const unsigned long long a = ((unsigned long long)v1 << 32) | v0, b = ((unsigned long long)v3 << 32) | v2;
+                    const unsigned long long lo = sh ? (a >> sh) | (b << (64 - sh)) : a;    // columns c0 .. c0 + 63
+                    const unsigned long long hi = b >> sh;                                  // columns c0 + 64 .. (at least 33 of them)
                     unsigned long long r = lo;
                     for (int kx = 1; kx < k; ++kx) r &= (lo >> kx) | (hi << (64 - kx));
                     acc &= r;
@@ -438,7 +419,51 @@ __global__ __launch_bounds__(256) void plan_erode_kernel(PlanDev P, const uint8_
         }
         __syncthreads();
     }
-    for (int t = tid; t < nt; t += 256) P.nrect[(size_t)stream * nt + t] = 0;      // no rectangles in this mode
+}
+
+// One workgroup per stream.  IN_LDS: the stream's bitmaps are built in dynamic LDS (bm_words words) and written to
+// the workspace in one pass at the end.
+template <bool IN_LDS>
+__global__ __launch_bounds__(kErodeThreads) void plan_erode_kernel(PlanDev P, const uint8_t* __restrict__ block_mask,
+                                                                   const int32_t* __restrict__ gmv, int gh, int gw, int B, int ext_opt) {
+    const int stream = blockIdx.x, tid = threadIdx.x;
+    const int nt = P.n_layers + 1;
+    __shared__ PlanLayerDev s_layers[kPlanMaxTensors];
+    __shared__ PlanTensorDev s_tensors[kPlanMaxTensors];
+    __shared__ int s_cnt[kErodeThreads / 64];
+    extern __shared__ uint32_t s_maps[];
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(P.layers);
+        uint4* dst = reinterpret_cast<uint4*>(s_layers);
+        for (int j = tid; j < P.n_layers * 3; j += kErodeThreads) dst[j] = src[j];
+        const uint4* tsrc = reinterpret_cast<const uint4*>(P.tensors);
+        uint4* tdst = reinterpret_cast<uint4*>(s_tensors);
+        for (int j = tid; j < nt; j += kErodeThreads) tdst[j] = tsrc[j];
+    }
+    const int mx = gmv[2 * stream], my = gmv[2 * stream + 1];
+    const bool ext = ext_opt != 0 && mx == 0 && my == 0;
+    uint32_t* const g_maps = P.bitmaps + (size_t)stream * P.bm_words;
+    int32_t* const dxy = P.dxy + (size_t)stream * nt * 2;
+    const uint8_t* m = block_mask + (size_t)stream * gh * gw;
+    {   // the stream's number of reusable blocks
+        int reusable = 0;
+        for (int j = tid; j < gh * gw; j += kErodeThreads) reusable += m[j] ? 1 : 0;
+        for (int off = 32; off > 0; off >>= 1) reusable += __shfl_xor(reusable, off);
+        if ((tid & 63) == 0) s_cnt[tid >> 6] = reusable;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int total = 0;
+        for (int j = 0; j < kErodeThreads / 64; ++j) total += s_cnt[j];
+        P.stream_info[2 * stream] = total; P.stream_info[2 * stream + 1] = 0; dxy[0] = mx; dxy[1] = my;
+    }
+    if (IN_LDS) {
+        erode_stream(s_maps, s_layers, s_tensors, P.n_layers, dxy, m, gh, gw, B, mx, my, ext, tid);
+        for (int64_t j = tid; j < P.bm_words; j += kErodeThreads) g_maps[j] = s_maps[j];
+    } else {
+        erode_stream(g_maps, s_layers, s_tensors, P.n_layers, dxy, m, gh, gw, B, mx, my, ext, tid);
+    }
+    for (int t = tid; t < nt; t += kErodeThreads) P.nrect[(size_t)stream * nt + t] = 0;      // no rectangles in this mode
 }
 
 // The 16-bit unit masks of every conv layer cut out of the bitmaps (grid and outputs as plan_masks_kernel).
@@ -683,8 +708,22 @@ hipError_t launch_plan_from_args(const PlanDev& P, const PlanConvDev& conv, cons
 hipError_t launch_plan_exact(const PlanDev& P, const uint8_t* block_mask, const int32_t* gmv, int gh, int gw, int block,
                              int extend_borders, int max_chunks, bool with_lists, hipStream_t st) {
     if (P.n_layers + 1 > kPlanMaxTensors || !P.bitmaps || gh < 1 || gw < 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(plan_erode_kernel, dim3(P.n_streams), dim3(256), 0, st, P, block_mask, gmv, gh, gw, block, extend_borders);
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (P.bm_words <= kErodeLdsWords) {
+        static std::atomic<bool> raised{false};       // more than 64 KB of dynamic LDS has to be asked for once
+        if (!raised.load(std::memory_order_acquire)) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&plan_erode_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kErodeLdsWords * (int)sizeof(uint32_t));
+            if (e != hipSuccess) return e;
+            raised.store(true, std::memory_order_release);
+        }
+        hipLaunchKernelGGL(plan_erode_kernel<true>, dim3(P.n_streams), dim3(kErodeThreads), (size_t)P.bm_words * sizeof(uint32_t), st,
+                           P, block_mask, gmv, gh, gw, block, extend_borders);
+    } else {
+        hipLaunchKernelGGL(plan_erode_kernel<false>, dim3(P.n_streams), dim3(kErodeThreads), 0, st, P, block_mask, gmv, gh, gw, block,
+                           extend_borders);
+    }
+    e = hipGetLastError();
     if (e != hipSuccess || !with_lists || P.n_convs == 0) return e;
     const dim3 grid((unsigned)max_chunks, (unsigned)P.n_streams, (unsigned)P.n_convs);
     hipLaunchKernelGGL(plan_masks_exact_kernel, grid, dim3(kPlanChunk), 0, st, P);

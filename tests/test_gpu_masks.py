@@ -58,3 +58,9 @@ def test_model_stacks(oracle):
     _check(oracle, synth.alexnet(n_classes=40, width=0.25), 227, 227, 3, 10, 3, 23, density=0.9, max_motion=12)
     _check(oracle, synth.darknet19(), 416, 416, 3, 16, 2, 24, density=0.9, max_motion=16)
     _check(oracle, synth.dave_orig(), 66, 200, 3, 10, 3, 25, density=0.9)
+
+
+def test_large_frame_maps_built_in_the_workspace(oracle):
+    """A frame whose bitmaps (more than 128 KB per stream) do not fit the workgroup's LDS: the same maps, built in the
+    workspace instead."""
+    _check(oracle, _mixed_stack()[:6], 1000, 1100, 4, 16, 2, 30, density=0.9, max_motion=20)
