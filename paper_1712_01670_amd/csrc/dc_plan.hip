@@ -401,7 +401,39 @@ __device__ __forceinline__ void erode_stream(uint32_t* maps, const PlanLayerDev*
                     acc &= r;
                 }
                 bits = s == 1 ? (unsigned)acc : even_bits(acc);
-            } else {                                        // any stride: bit by bit
+            } else if (s <= 8 && k <= 32) {
+                // larger strides: the same AND of shifted rows for all 32 s start columns of the word (up to four
+                // 64-column pieces), then every s-th bit is kept
+                unsigned long long acc[4] = {~0ull, ~0ull, ~0ull, ~0ull};
+                const int c0 = x0 * s - p;
+                const int pieces = (32 * s + 63) >> 6;
+                for (int ky = 0; ky < k; ++ky) {
+                    const int iy = y * s - p + ky;
+                    const bool row_in = iy >= 0 && iy < ta.h;
+                    if (!row_in && ext) continue;
+                    const uint32_t* row = row_in ? in + (size_t)iy * wpr_in : nullptr;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (j >= pieces) continue;
+                        const int c = c0 + 64 * j, w0 = c >> 5, sh = c & 31;
+                        unsigned v[5];
+#pragma unroll
+                        for (int q = 0; q < 5; ++q) v[q] = row_word(row, wpr_in, ta.w, w0 + q, ext);
+                        const unsigned long long a = ((unsigned long long)v[1] << 32) | v[0], b = ((unsigned long long)v[3] << 32) | v[2];
+                        const unsigned long long lo = sh ? (a >> sh) | (b << (64 - sh)) : a;
+                        const unsigned long long hi = sh ? (b >> sh) | ((unsigned long long)v[4] << (64 - sh)) : b;
+                        unsigned long long r = lo;
+                        for (int kx = 1; kx < k; ++kx) r &= (lo >> kx) | (hi << (64 - kx));
+                        acc[j] &= r;
+                    }
+                }
+                bits = 0;
+                for (int b = 0; b < 32; ++b) {
+                    const int at = b * s, piece = at >> 6;
+                    const unsigned long long word = piece == 0 ? acc[0] : (piece == 1 ? acc[1] : (piece == 2 ? acc[2] : acc[3]));
+                    bits |= (unsigned)((word >> (at & 63)) & 1ull) << b;
+                }
+            } else {                                        // anything else: bit by bit
                 bits = 0;
                 for (int b = 0; b < 32 && x0 + b < tt.w; ++b) {
                     bool ok = true;

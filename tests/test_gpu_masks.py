@@ -22,7 +22,8 @@ def _mixed_stack():
             dict(type=synth.RELU, k=1, s=1, p=0, cin=4, cout=4, relu=0, in0=9, in1=-1),
             C_(7, 1, 3, 10),
             dict(type=synth.CONCAT, k=1, s=1, p=0, cin=8, cout=8, relu=0, in0=10, in1=11, in2=-1, in3=-1),
-            dict(type=synth.CONV, k=3, s=3, p=0, cin=8, cout=4, relu=0, in0=12, in1=-1)]     # a stride the word path does not take
+            dict(type=synth.CONV, k=3, s=3, p=0, cin=8, cout=4, relu=0, in0=12, in1=-1),     # word path in two 64-column pieces
+            dict(type=synth.CONV, k=3, s=9, p=1, cin=4, cout=4, relu=0, in0=7, in1=-1)]      # a stride only the bit-by-bit path takes
 
 
 def _check(oracle, layers, H, W, Ch, block, n, seed, density=0.8, max_motion=9):
