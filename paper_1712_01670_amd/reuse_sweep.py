@@ -2,9 +2,9 @@
 """Frame time of the cache-aware path against the input reuse ratio (Section 7.2 reports the
 saving per scenario; here the scenario is synthetic and the reuse ratio is the knob).
 
-For every target reuse ratio a 60-frame video is generated (panning background, a band of fresh
-noise sized to the non-reusable fraction, scene cut at frame 30), resident in HBM, and run three
-ways on one GPU:
+For every target reuse ratio a 60-frame video is generated (panning background under moving
+rectangles of fresh noise whose sizes are calibrated to the non-reusable fraction, scene cut at
+the middle), resident in HBM, and run three ways on one GPU:
   cached   every frame but the first of a scene goes through matching + cached convolution
            (no expiry), which isolates the cost of a cached frame;
   expiry   as deployed: a full frame every N frames (Section 5, N = 10);
