@@ -212,8 +212,9 @@ int32_t dc_overlap_pipeline(void* overlap, int32_t frames_in_flight /* 1 or 2 */
  * Overrides the launch heuristics of the 3x3 stride-1 GEMM kernels for the whole process (tests and
  * experiments; results do not depend on it beyond fp32 summation order): wavefront arrangement
  * (0: 64 channels per workgroup; bf16 only: 1: 128 channels, 2: 64 channels in two blocks per wavefront,
- * 3: the persistent kernel with the weights in registers, 64 input channels only), units per workgroup
- * (1..16; for the 1x1 kernel 4 or 8 selects its 64 x 64 or 128 x 128 tile), number of workgroups that split K,
+ * 3: the persistent kernel with the weights in registers, 64 input channels only, 4: 128 channels on twelve
+ * wavefronts with 13..18 units per workgroup), units per workgroup
+ * (1..18; for the 1x1 kernel 4 or 8 selects its 64 x 64 or 128 x 128 tile), number of workgroups that split K,
  * channel chunk index (0, 1).  A negative value leaves that choice to the library; values a layer cannot use are
  * ignored for that layer.
  */

@@ -473,14 +473,14 @@ int32_t dc_overlap_pipeline(void* overlap, int32_t frames_in_flight) {
 }
 
 int32_t dc_conv_tuning(int32_t arrangement, int32_t units_per_workgroup, int32_t k_split, int32_t chunk_index) {
-    if (arrangement > 3 || units_per_workgroup > 16 || chunk_index > 1) return DC_ERR_INVALID_ARG;
+    if (arrangement > 4 || units_per_workgroup > 18 || chunk_index > 1) return DC_ERR_INVALID_ARG;
     conv_set_tuning(arrangement, units_per_workgroup, k_split, chunk_index);
     return DC_OK;
 }
 
 int32_t dc_conv_kernel_name(int32_t kernel_id, char* buf, size_t n) {
     if (!buf) return DC_ERR_NULL_PTR;
-    if (n < 2 || kernel_id < 0 || kernel_id >= 129) return DC_ERR_INVALID_ARG;
+    if (n < 2 || kernel_id < 0 || kernel_id > 129) return DC_ERR_INVALID_ARG;
     conv_kernel_name(kernel_id, buf, n);
     return DC_OK;
 }

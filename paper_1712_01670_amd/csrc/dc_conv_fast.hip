@@ -974,9 +974,14 @@ hipError_t first_launch(int k, int nb, dim3 grid, hipStream_t st, const ConvPara
 //           of its bandwidth, where the narrow shape (u + 1 reads for u MFMAs) is bound by it.
 //   wide64: 4 x 2 wavefronts, a wavefront = up to 4 units x 32 channels, 64 channels per workgroup: the bf16
 //           shape for layers whose channel count is not a multiple of 128 (u + 2 reads for 2u MFMAs).
+//   tall:   6 x 2 wavefronts (three per SIMD, 168 registers), a wavefront = 3 units x 64 channels, 18 units x 128
+//           channels per workgroup: the same LDS reads per MFMA as wide with 3 units (7 for 12), but 18 units per
+//           workgroup instead of 16.  A launch runs in rounds of 256 workgroups (one per CU: the LDS), and the last
+//           round costs a whole one however few workgroups it holds; with 18 units the list of a layer often needs one
+//           round less (28x28 x 64 streams: 700 workgroups instead of 784, three rounds instead of four).
 struct Geom { int wm, wn, nbw, max_upw; };
-constexpr int kNumGeom = 3;
-constexpr Geom kGeom[kNumGeom] = {{2, 4, 1, 8}, {4, 2, 4, 4}, {4, 2, 2, 4}};
+constexpr int kNumGeom = 4;
+constexpr Geom kGeom[kNumGeom] = {{2, 4, 1, 8}, {4, 2, 4, 4}, {4, 2, 2, 4}, {6, 2, 4, 3}};
 inline int geom_nt(int geom) { return kGeom[geom].wn * kGeom[geom].nbw * 16; }
 
 template <typename T, int KC, int U, int WM, int WN, int NBW>
@@ -1026,6 +1031,7 @@ hipError_t fast_launch_wide64(int upw, dim3 grid, size_t lds, hipStream_t st, co
 hipError_t fast_launch(bool bf16, int geom, int kci, int upw, dim3 grid, size_t lds, hipStream_t st, const ConvParams& P) {
     if (bf16 && geom == 1)
         return kci ? fast_launch_wide<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_wide<__hip_bfloat16, 32>(upw, grid, lds, st, P);
+    if (bf16 && geom == 3) return fast_launch_one<__hip_bfloat16, 32, 3, 6, 2, 4>(grid, lds, st, P);   // (only this shape is built)
     if (bf16 && geom == 2)
         return kci ? fast_launch_wide64<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_wide64<__hip_bfloat16, 32>(upw, grid, lds, st, P);
     if (bf16) return kci ? fast_launch_narrow<__hip_bfloat16, 64>(upw, grid, lds, st, P) : fast_launch_narrow<__hip_bfloat16, 32>(upw, grid, lds, st, P);
@@ -1074,6 +1080,7 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, long n_cap, size_t scr
             const int n_chunks = c.Cin / kc, gpc = 1 << kci, rb = kc * esz;
             for (int g = 1; g <= G.wm * G.max_upw; ++g) {
                 const int upw = (g + G.wm - 1) / G.wm;
+                if (geom == 3 && (upw != 3 || kci != 0)) continue;      // the one instantiation of the tall arrangement
                 if (fast_lds_bytes(geom, kci, upw) > 160 * 1024) continue;
                 if (geom == 0 && !bf16 && fast_lds_bytes(geom, kci, upw) > (size_t)(lds_cap_kb * 1024)) continue;
                 const long groups = (n_units + g - 1) / g;
@@ -1088,9 +1095,12 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, long n_cap, size_t scr
                     // a wavefront takes 4), cycles to load the stage
                     // units per SIMD: the two wavefronts of a SIMD belong to wave_m groups 0/1 (narrow) or 0/2, 1/3
                     auto nu = [&](int m) { return (g - m + G.wm - 1) / G.wm; };
-                    const int su = G.wm == 2 ? nu(0) + nu(1) : (nu(0) + nu(2) > nu(1) + nu(3) ? nu(0) + nu(2) : nu(1) + nu(3));
-                    const double mfma = 1.12 * (bf16 ? 16.0 : 128.0) * su * G.nbw * 3 * gpc;
-                    const double ldsr = 8.0 * (upw + G.nbw) * 3 * gpc * 4 * 1.3;
+                    const int su = G.wm == 2 ? nu(0) + nu(1)
+                                 : G.wm == 6 ? (nu(0) + nu(2) + nu(4) > nu(1) + nu(3) + nu(5) ? nu(0) + nu(2) + nu(4) : nu(1) + nu(3) + nu(5))
+                                             : (nu(0) + nu(2) > nu(1) + nu(3) ? nu(0) + nu(2) : nu(1) + nu(3));
+                    // (the tall arrangement needs 5 % more per unit than the wide one when both fill their rounds: measured)
+                    const double mfma = (geom == 3 ? 1.18 : 1.12) * (bf16 ? 16.0 : 128.0) * su * G.nbw * 3 * gpc;
+                    const double ldsr = (double)(G.wm * G.wn) * (upw + G.nbw) * 3 * gpc * 4 * 1.3;
                     const double load = ((double)g * 36 * rb / 3 + 3.0 * nt * rb) / bw;
                     double stage = mfma > load ? mfma : load;
                     if (ldsr > stage) stage = ldsr;
@@ -1106,7 +1116,9 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, long n_cap, size_t scr
                     // Workgroups that are all resident from the start share their CU to the end: the fullest CU
                     // sets the time.  With more rounds than that the dispatcher balances the CUs and only the last
                     // round is not a whole one.
-                    const double rounds = (wgs <= 512 || wgs <= 256 * occ) ? (double)per_cu : wgs / 256.0 + 0.5;
+                    // (measured for one workgroup per CU: 28x28 512->512 takes 179 us with 760 workgroups, 203 us with 772,
+                    // 238 us with 1020 and 257 us with 1032, so up to eight rounds the last one counts as a whole one)
+                    const double rounds = (wgs <= 512 || wgs <= 256 * occ || (occ == 1 && geom != 0 && wgs <= 2048)) ? (double)per_cu : wgs / 256.0 + 0.5;
                     double cost = rounds * work + (double)((per_cu + occ - 1) / occ) * fixed;
                     // a lone workgroup per CU leaves the matrix cores idle during its barriers, prologue and epilogue,
                     // and leaves no room for the workgroups of the other frame in flight (measured: 5 % per frame)
@@ -1126,6 +1138,7 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, long n_cap, size_t scr
 // 110.. the wide arrangement.
 void conv_fast_kernel_name(int id, char* buf, size_t n) {
     if (id == 126) { snprintf(buf, n, "conv_regw_kernel<2, 2>"); return; }
+    if (id == 129) { snprintf(buf, n, "conv_fast_kernel<__hip_bfloat16, 3, 32, 3, 6, 2, 4>"); return; }     // the tall arrangement
     if (id == 127 || id == 128 || id == 108 || id == 109) {      // 108 + bf16 (64 x 64 tile), 127 + bf16 (128 x 128): conv_pw_kernel (1x1)
         snprintf(buf, n, "conv_pw_kernel<%s, %d>", id == 109 || id == 128 ? "__hip_bfloat16" : "float", id >= 127 ? 4 : 2);
         return;
@@ -1324,7 +1337,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
             slot.tune[3] == g_tune[3]) {
             ch = slot.ch;
         } else {
-            ch = choose_fast(c, n_units, n_cap, scratch, g_tune[0]);
+            ch = choose_fast(c, n_units, n_cap, scratch, g_tune[0] == 4 ? 3 : g_tune[0]);    // tuning 3 names another kernel
             slot = Memo{c.dtype, c.Cin, c.Cout, {g_tune[0], g_tune[1], g_tune[2], g_tune[3]}, n_units, n_cap, scratch, ch, true};
         }
     }
@@ -1333,7 +1346,8 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
         const Geom& G = kGeom[ch.geom];
         const int kc = (c.dtype == DC_BF16 ? 32 : 16) << f_kci;
         const int upw = (f_g + G.wm - 1) / G.wm;
-        if (f_g <= G.wm * G.max_upw && f_kci < 2 && c.Cin % kc == 0 && fast_lds_bytes(ch.geom, f_kci, upw) <= 160 * 1024) {
+        if (f_g <= G.wm * G.max_upw && f_kci < 2 && c.Cin % kc == 0 && fast_lds_bytes(ch.geom, f_kci, upw) <= 160 * 1024 &&
+            (ch.geom != 3 || (upw == 3 && f_kci == 0))) {
             const int n_chunks = c.Cin / kc;
             int ks = f_ks < 1 ? 1 : (f_ks > n_chunks ? n_chunks : f_ks);
             const int cps = (n_chunks + ks - 1) / ks;
@@ -1366,7 +1380,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
     P.partial = ch.ks > 1 ? static_cast<float*>(c.scratch) : nullptr;
     if (c.w_packed && reinterpret_cast<uintptr_t>(c.w_packed) % 16 == 0) { P.w = c.w_packed; P.w_packed = 1; }
 
-    if (c.kernel_id) *c.kernel_id = ch.geom ? 110 + (ch.geom - 1) * 8 + ch.kci * 4 + upw - 1 : 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
+    if (c.kernel_id) *c.kernel_id = ch.geom == 3 ? 129 : ch.geom ? 110 + (ch.geom - 1) * 8 + ch.kci * 4 + upw - 1 : 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;
     const long groups = (n_cap + ch.g - 1) / ch.g;
     const long wgx = groups * P.R;
     if (wgx > 2147483647L || ch.ks > 65535) { *err = hipErrorInvalidValue; return true; }

@@ -155,6 +155,9 @@ FAST_CASES = [
     (19, 23, 128, 128, (-1, -1, -1, -1)),  # the library's own choice
     (22, 30, 64, 64, (3, -1, -1, -1)),    # bf16: persistent kernel with the weights in registers (plain weights)
     (37, 41, 64, 128, (3, -1, -1, -1)),   # ... two channel tiles, more unit groups than one step, ragged map
+    (22, 30, 64, 128, (4, 18, 1, 0)),     # bf16: twelve wavefronts, 18 units per workgroup (96 units: the last group holds 6)
+    (45, 61, 32, 256, (4, 13, 1, 0)),     # ... 13 units: one row of wavefronts with three units, five with two
+    (30, 34, 96, 128, (4, 17, 3, 0)),     # ... with a K split
 ]
 
 

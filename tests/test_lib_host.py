@@ -83,8 +83,9 @@ def test_argument_errors_are_reported_before_any_launch():
     assert binding.conv_kernel_name(110 + 3) == "conv_fast_kernel<__hip_bfloat16, 3, 32, 4, 4, 2, 4>"
     assert binding.conv_kernel_name(110 + 8 + 4) == "conv_fast_kernel<__hip_bfloat16, 3, 64, 1, 4, 2, 2>"
     assert binding.conv_kernel_name(126) == "conv_regw_kernel<2, 2>"
+    assert binding.conv_kernel_name(129) == "conv_fast_kernel<__hip_bfloat16, 3, 32, 3, 6, 2, 4>"
     with pytest.raises(binding.DcError):
-        binding.conv_kernel_name(129)
+        binding.conv_kernel_name(130)
     # overlapping rectangles are rejected
     regs, keep = binding._alloc_regions(1, 2)
     keep[0][0] = binding.Rect(0, 0, 4, 4)
