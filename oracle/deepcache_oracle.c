@@ -927,13 +927,18 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
                  float* const* cur, const float* const* prev,
                  oc_rect* rects, int cap, int32_t* n_rects, int32_t* dxy,
                  int32_t* cum_stride, int32_t* hw, int extend_borders, const uint8_t* const* exact_masks,
-                 int cache_pool_add)
+                 int cache_pool_add, const uint8_t* no_reuse)
 {
     /* exact_masks (optional): the maps of oc_propagate_masks for this frame; the conv layers then reuse exactly
      * those pixels instead of the rectangles'.
      * cache_pool_add (with exact_masks): max-pooling and add layers use the cache like the conv layers (Section 5
      * notes that the cache extends to other layer types): where the layer's map is set the output is the previous
-     * frame's output of that layer at the tensor's offset, elsewhere it is computed. */
+     * frame's output of that layer at the tensor's offset, elsewhere it is computed.
+     * no_reuse (optional, [n_layers]): which conv layers use the cache is a setting of the engine (Section 6 lists
+     * the cache's configuration among its knobs); a conv layer whose entry is non-zero is computed in full on every
+     * frame.  NULL: every conv layer uses the cache, as in Section 5.  The regions are propagated through such a
+     * layer as through any other conv layer: they describe what could be reused, and the layers behind it still
+     * reuse it from their own caches. */
     int cached = n0 >= 0;
     int rc = oc_propagate_ext(L, n_layers, H, W, rects0, cached ? n0 : 0, cached ? mx : 0,
                               cached ? my : 0, extend_borders, rects, cap, n_rects, dxy, cum_stride, hw);
@@ -945,7 +950,10 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
         int ha = hw[2 * a], wa = hw[2 * a + 1], ho = hw[2 * t], wo = hw[2 * t + 1];
         if (l->type == OC_CONV) {
             uint8_t* mask = NULL;
-            if (cached && exact_masks) {
+            int uses_cache = cached && !(no_reuse && no_reuse[li]);
+            if (!uses_cache) {
+                /* computed in full */
+            } else if (cached && exact_masks) {
                 mask = (uint8_t*)malloc((size_t)ho * wo);
                 memcpy(mask, exact_masks[t], (size_t)ho * wo);
             } else if (cached && n_rects[t] > 0) {

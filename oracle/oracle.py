@@ -331,7 +331,11 @@ class Stream:
     the previous feature maps (cache values), Section 3."""
 
     def __init__(self, layers, weights, biases, H, W, Ch=3, block=16, radius=16, max_ssd=None,
-                 bf16=False, expiry=0, cap=1024, diamond=False, k_skip=1, extend_borders=False, exact_masks=False, cache_pool_add=False):
+                 bf16=False, expiry=0, cap=1024, diamond=False, k_skip=1, extend_borders=False, exact_masks=False, cache_pool_add=False,
+                 no_reuse=None):
+        # no_reuse: per layer, non-zero = that conv layer is computed in full on every frame (None: all use the cache)
+        self.no_reuse = None if no_reuse is None else np.ascontiguousarray(no_reuse, np.uint8)
+        assert self.no_reuse is None or self.no_reuse.shape == (len(layers),)
         self.diamond, self.k_skip, self.extend_borders, self.exact_masks = diamond, k_skip, extend_borders, exact_masks
         self.cache_pool_add = bool(cache_pool_add) and bool(exact_masks)
         self.layers, self.H, self.W, self.Ch = layers, H, W, Ch
@@ -398,7 +402,7 @@ class Stream:
         rc = lib().oc_run_stack(self.Lc, n, self._wp, self._bp, _p(frame), self.H, self.W, self.Ch,
                                 int(self.bf16), _p(r0), n0, mx, my, curp, prevp, _p(rects),
                                 self.cap, _p(n_rects), _p(dxy), _p(cs), _p(hw), int(self.extend_borders), mp,
-                                int(self.cache_pool_add))
+                                int(self.cache_pool_add), None if self.no_reuse is None else _p(self.no_reuse))
         assert rc == 0
         self.bufs = [prev, cur]  # cur becomes next frame's prev
         self.prev_frame = frame.copy()

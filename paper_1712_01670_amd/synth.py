@@ -75,6 +75,12 @@ def _chain(spec, cin):
     return layers
 
 
+def no_reuse_flags(layers, min_macs):
+    """A cache setting for a stack: flag [n_layers] (uint8) the conv layers with fewer than min_macs multiply-adds per
+    output element (k * k * cin of the layer table as given); flagged layers are computed in full on every frame."""
+    return np.array([1 if (L["type"] == CONV and L["k"] * L["k"] * L["cin"] < min_macs) else 0 for L in layers], np.uint8)
+
+
 def tiny_net():
     """3 conv layers: 3->16 s1, 16->32 s2, 32->32 s1, all 3x3 p1 + ReLU."""
     return _chain([("c", 16, 3, 1, 1), ("c", 32, 3, 2, 1), ("c", 32, 3, 1, 1)], 3)

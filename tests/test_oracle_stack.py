@@ -110,11 +110,11 @@ def test_cached_conv_copies_exactly_where_masked(oracle):
 
 
 def _run_video(oracle, layers, frames, block, radius, bf16=False, expiry=0, seed=1, bias_scale=0.1, exact_masks=False,
-               cache_pool_add=False):
+               cache_pool_add=False, no_reuse=None):
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale)
     H, W, C = frames[0].shape
     st = oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry, exact_masks=exact_masks,
-                       cache_pool_add=cache_pool_add)
+                       cache_pool_add=cache_pool_add, no_reuse=no_reuse)
     outs = []
     for f in frames:
         r = st.step(f)
@@ -370,3 +370,42 @@ def test_cached_pool_and_add_take_their_values_from_the_cache(oracle):
     a, (ws, bs) = _run_video(oracle, layers, frames, 8, 8, exact_masks=True, cache_pool_add=True)
     for x, y in zip(a[1]["tensors"], _full_forward(oracle, layers, ws, bs, frames[1])):
         assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("exact", [False, True])
+def test_conv_layers_that_do_not_use_the_cache(oracle, exact):
+    """no_reuse: a flagged conv layer is computed in full from whatever its input holds; the others keep reusing
+    from their own caches, and the regions do not change."""
+    layers = synth.tiny_net()
+    f1, f2 = synth.tiny_pair(0)
+    base, (ws, bs) = _run_video(oracle, layers, [f1, f2], 8, 8, exact_masks=exact)
+    conv = [i for i, L in enumerate(layers) if L["type"] == synth.CONV]
+    # every conv layer flagged: the cached frame is the full forward, bit for bit
+    all_off, _ = _run_video(oracle, layers, [f1, f2], 8, 8, exact_masks=exact, no_reuse=[1] * len(layers))
+    for x, y in zip(all_off[1]["tensors"], _full_forward(oracle, layers, ws, bs, f2)):
+        assert np.array_equal(x, y)
+    # no layer flagged: the default
+    none_off, _ = _run_video(oracle, layers, [f1, f2], 8, 8, exact_masks=exact, no_reuse=[0] * len(layers))
+    for x, y in zip(none_off[1]["tensors"], base[1]["tensors"]):
+        assert np.array_equal(x, y)
+    # only the second conv layer flagged
+    flags = [0] * len(layers)
+    flags[conv[1]] = 1
+    mixed, _ = _run_video(oracle, layers, [f1, f2], 8, 8, exact_masks=exact, no_reuse=flags)
+    t1, t2, t3 = conv[0] + 1, conv[1] + 1, conv[2] + 1
+    assert np.array_equal(mixed[1]["tensors"][t1], base[1]["tensors"][t1])          # before it nothing changes
+    L = layers[conv[1]]
+    want = oracle.conv_cached(mixed[1]["tensors"][L["in0"]], ws[conv[1]], bs[conv[1]], L["k"], L["s"], L["p"], bool(L["relu"]))
+    assert np.array_equal(mixed[1]["tensors"][t2], want)                             # the layer itself: a plain convolution of its input
+    assert not np.array_equal(mixed[1]["tensors"][t2], base[1]["tensors"][t2])      # which is not what the cache held
+    # the layer behind it still takes its reusable pixels from its own cache
+    m = (mixed[1]["masks"][t3].astype(bool) if exact else oracle.rasterize(mixed[1]["rects"][t3], *mixed[1]["tensors"][t3].shape[:2]).astype(bool))
+    dx, dy = (int(v) for v in mixed[1]["dxy"][t3])
+    ys, xs = np.nonzero(m)
+    assert len(ys) > 10
+    assert np.array_equal(mixed[1]["tensors"][t3][ys, xs], mixed[0]["tensors"][t3][ys + dy, xs + dx])
+    # the regions are the same with and without flags
+    for t in range(len(layers) + 1):
+        assert np.array_equal(mixed[1]["rects"][t], base[1]["rects"][t])
+        if exact:
+            assert np.array_equal(mixed[1]["masks"][t], base[1]["masks"][t])
