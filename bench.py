@@ -86,7 +86,8 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
     exact = (args.regions == "exact" if exact_masks is None else exact_masks) and not args.host_plan
     runner = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
                                  match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan,
-                                 exact_masks=exact, cache_pool_add=exact and args.cache_pool_add)
+                                 exact_masks=exact, cache_pool_add=exact and args.cache_pool_add,
+                                 no_reuse=synth.no_reuse_flags(layers, args.min_reuse_macs) if args.min_reuse_macs > 0 else None)
 
     def run_steps(k, start, collect=None, force_full=False):
         """Run k steps through the cyclic video starting at global step `start`."""
@@ -247,7 +248,8 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
         from oracle import oracle as oc
         ref = oc.Stream(layers, ws, bs, H, W, 3, block=16, radius=16, bf16=(dtype == "bf16"), expiry=args.expiry,
                         diamond=(args.matcher == "ds"), k_skip=args.k_skip, exact_masks=exact,
-                        cache_pool_add=exact and args.cache_pool_add)
+                        cache_pool_add=exact and args.cache_pool_add,
+                        no_reuse=synth.no_reuse_flags(layers, args.min_reuse_macs) if args.min_reuse_macs > 0 else None)
         k_cpu = min(cpu_frames, n_frames)
         t0 = time.perf_counter()
         for f in range(k_cpu):
@@ -292,6 +294,9 @@ def main():
                          "the rectangles of Step 5 propagated by Table 2 as the paper prints it")
     ap.add_argument("--cache-pool-add", action="store_true",
                     help="with exact maps: max-pooling layers take their outputs from the cache too (Section 5)")
+    ap.add_argument("--min-reuse-macs", type=int, default=0,
+                    help="conv layers with fewer multiply-adds per output element (k*k*cin) are computed in full on every "
+                         "frame instead of using the cache (0: every conv layer uses the cache, as in the paper)")
     ap.add_argument("--no-single", action="store_true", help="skip the single-stream fp32 sub-record")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=30)
@@ -331,6 +336,7 @@ def main():
                                        else "rectangles (Table 2 as printed)",
                    "cached_layers": "conv, max-pooling, add" if (args.cache_pool_add and args.regions == "exact" and not args.host_plan)
                                     else "conv",
+                   "min_reuse_macs": args.min_reuse_macs,
                    "lookahead_frames": 1 if args.lookahead else 0, **detail},
     }
     out.update(main_rec)

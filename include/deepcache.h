@@ -115,6 +115,12 @@ typedef struct {
                               the layer's map is set the output is the previous frame's output of that layer at the tensor's
                               offset, elsewhere it is computed.  tensors_prev must then hold those layers' previous outputs
                               (distinct buffers), and their channel runs must be whole 16-byte vectors. */
+    const uint8_t* no_reuse; /* dc_run_stack only.  NULL, or host [n_layers]: a conv layer whose entry is non-zero does not use
+                              the cache: it is computed in full on every frame (nothing copied, every unit listed).  The
+                              regions are propagated through it as through any conv layer, and the layers behind it
+                              still reuse from their own caches.  Section 5 restricts the cache to the layer type where
+                              it pays; this carries that choice down to single layers (on this GPU a 1x1 layer or a
+                              layer with few input channels costs less to compute than to copy). */
     int32_t device_plan;   /* dc_run_stack only.  0: the call waits for the matching, then merges, propagates and lists
                               the dirty units on the host.  1: three small kernels do that on the GPU from the block
                               mask in device memory (Section 4 Step 5, Section 5 "Propagation": the same rules, the

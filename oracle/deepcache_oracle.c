@@ -934,9 +934,10 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
      * cache_pool_add (with exact_masks): max-pooling and add layers use the cache like the conv layers (Section 5
      * notes that the cache extends to other layer types): where the layer's map is set the output is the previous
      * frame's output of that layer at the tensor's offset, elsewhere it is computed.
-     * no_reuse (optional, [n_layers]): which conv layers use the cache is a setting of the engine (Section 6 lists
-     * the cache's configuration among its knobs); a conv layer whose entry is non-zero is computed in full on every
-     * frame.  NULL: every conv layer uses the cache, as in Section 5.  The regions are propagated through such a
+     * no_reuse (optional, [n_layers]): Section 5 restricts the cache to the layer type where it pays (a trade-off of
+     * latency against overhead) and Section 6 exposes cache parameters to the application; this setting carries that
+     * choice down to single layers: a conv layer whose entry is non-zero is computed in full on every frame.
+     * NULL: every conv layer uses the cache, as in Section 5.  The regions are propagated through such a
      * layer as through any other conv layer: they describe what could be reused, and the layers behind it still
      * reuse it from their own caches. */
     int cached = n0 >= 0;

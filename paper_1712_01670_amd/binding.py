@@ -51,7 +51,7 @@ class Regions(C.Structure):
 
 class MatchOptions(C.Structure):
     _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32), ("extend_borders", C.c_int32), ("exact_masks", C.c_int32),
-                ("cache_pool_add", C.c_int32), ("device_plan", C.c_int32)]
+                ("cache_pool_add", C.c_int32), ("no_reuse", C.c_void_p), ("device_plan", C.c_int32)]
 
 
 DC_MATCH_EXHAUSTIVE, DC_MATCH_DIAMOND = 0, 1
@@ -457,7 +457,7 @@ class StackRunner:
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
                  want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True,
                  match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False, extend_borders=False, device_plan=False,
-                 exact_masks=False, cache_pool_add=False):
+                 exact_masks=False, cache_pool_add=False, no_reuse=None):
         self.device_plan = bool(device_plan) and not in_place
         self.in_place = bool(in_place)
         self.last_in_place = False
@@ -471,8 +471,12 @@ class StackRunner:
         self.max_rects = max_rects
         self.exact_masks = bool(exact_masks)
         self.cache_pool_add = bool(cache_pool_add) and self.exact_masks
+        # no_reuse: per layer, non-zero = that conv layer is computed in full on every frame (host array kept alive here)
+        self._no_reuse = None if no_reuse is None else np.ascontiguousarray(no_reuse, np.uint8)
+        assert self._no_reuse is None or self._no_reuse.shape == (len(layers),)
         self.match_options = MatchOptions(int(match_method), int(k_skip), int(extend_borders), int(self.exact_masks),
-                                          int(self.cache_pool_add), int(self.device_plan))
+                                          int(self.cache_pool_add),
+                                          None if self._no_reuse is None else self._no_reuse.ctypes.data, int(self.device_plan))
         self.device = torch.device(device)
         td = torch_dtype(dtype)
         self.Lc = layers_to_c(layers)

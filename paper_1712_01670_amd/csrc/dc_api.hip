@@ -225,7 +225,7 @@ struct DevPlanLayout {
 // Tables and sizes for n_streams streams of this stack; ok = false if the device kernels cannot take it (the host
 // path then plans the frame).
 void device_plan_layout(const dc_layer* L, int n_layers, const std::vector<int>& hs, const std::vector<int>& ws,
-                        int n_streams, int max_rects, DevPlanLayout& d) {
+                        int n_streams, int max_rects, DevPlanLayout& d, const uint8_t* no_reuse = nullptr) {
     d.ok = false;
     const int nt = n_layers + 1;
     if (nt > kPlanMaxTensors) return;
@@ -268,6 +268,7 @@ void device_plan_layout(const dc_layer* L, int n_layers, const std::vector<int>&
     for (int layer : d.conv_layer) {
         PlanConvDev c{};
         c.tensor = layer + 1; c.Hout = hs[layer + 1]; c.Wout = ws[layer + 1];
+        c.no_reuse = no_reuse && no_reuse[layer] ? 1 : 0;
         c.units_x = (c.Wout + 3) / 4; c.units_y = (c.Hout + 3) / 4;
         const size_t units = (size_t)c.units_x * c.units_y;
         c.n_chunks = (int)((units + kPlanChunk - 1) / kPlanChunk);
@@ -881,8 +882,9 @@ struct FramePlan {
     std::vector<unsigned char*> tile_dst;  // [conv layer]: the layer's tile list in the staging buffer
     int n_streams = 0;
 
+    // no_reuse (optional): conv layers that are computed in full (planned as if their lists were empty)
     int classify(const dc_layer* layers, int n_layers, int streams, const std::vector<std::vector<TensorRegions>>& regs,
-                 const std::vector<int>& hs, const std::vector<int>& ws) {
+                 const std::vector<int>& hs, const std::vector<int>& ws, const uint8_t* no_reuse) {
         n_streams = streams;
         conv_layers.clear();
         for (int i = 0; i < n_layers; ++i)
@@ -903,7 +905,7 @@ struct FramePlan {
                     LayerPlan& lp = part[(size_t)s * nc + c];
                     lp.rects.clear(); lp.ranges.clear(); lp.tiles.clear(); lp.reused_px = 0;
                     const TensorRegions& g = regs[s][i + 1];
-                    plan_stream(g.rects.data(), (int)g.rects.size(), g.dx, g.dy, s, hs[i + 1], ws[i + 1], 4, 4, lp);
+                    plan_stream(g.rects.data(), (no_reuse && no_reuse[i]) ? 0 : (int)g.rects.size(), g.dx, g.dy, s, hs[i + 1], ws[i + 1], 4, 4, lp);
                 }
             } catch (const std::bad_alloc&) {
                 ok[s] = 0;
@@ -995,6 +997,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         for (size_t i = 0; i < (size_t)n_streams * (n_layers + 1); ++i)
             if (regions_out[i].capacity < max_rects || !regions_out[i].rects) return DC_ERR_CAPACITY;
     // max-pooling and add layers that use the cache: their outputs are cache values like the conv outputs
+    const uint8_t* const no_reuse = match_options ? match_options->no_reuse : nullptr;
     const bool cache_other = cached && match_options && match_options->cache_pool_add && match_options->exact_masks;
     auto uses_cache = [&](int i) { return cache_other && (layers[i].type == DC_MAXPOOL || layers[i].type == DC_ADD); };
     if (cache_other)
@@ -1123,7 +1126,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     if (cached && match_options && match_options->device_plan && !in_place && gh >= 1 && gw >= 1 && gh <= 64 && gw <= 64 &&
         ws_host_bytes >= kDevHostRegion + 256 && ws_dev_bytes >= 2 * kConvScratchBytes) {
         try {
-            device_plan_layout(layers, n_layers, hs, ws, n_streams, max_rects, dl);
+            device_plan_layout(layers, n_layers, hs, ws, n_streams, max_rects, dl, no_reuse);
             unit_hint.assign(dl.convs.size(), -1);
         } catch (const std::bad_alloc&) {
             return DC_ERR_WORKSPACE;
@@ -1364,7 +1367,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     std::lock_guard<std::mutex> plan_guard(g_frame_plan_mutex);
     FramePlan& frame_plan = g_frame_plan;
     if (cached && !devplan) {
-        int rc_plan = frame_plan.classify(layers, n_layers, n_streams, regs, hs, ws);
+        int rc_plan = frame_plan.classify(layers, n_layers, n_streams, regs, hs, ws, no_reuse);
         if (rc_plan) return rc_plan;
     }
 
@@ -1418,6 +1421,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             for (size_t c = 0; c < dl.convs.size(); ++c) {
                 const int i = dl.conv_layer[c];
                 copy_fused[i] = 1;
+                if (no_reuse && no_reuse[i]) continue;          // nothing of this layer comes from the cache
                 const size_t px_bytes = (size_t)layers[i].cout * dtype_size(dtype);
                 const bool vec16 = px_bytes % 16 == 0 && reinterpret_cast<uintptr_t>(tensors_prev[i + 1]) % 16 == 0 &&
                                    reinterpret_cast<uintptr_t>(tensors_cur[i + 1]) % 16 == 0;

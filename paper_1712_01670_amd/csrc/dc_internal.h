@@ -162,7 +162,9 @@ struct PlanLayerDev {                    // one layer; tensor i + 1 is its outpu
 };
 struct PlanTensorDev { int32_t h, w, cum_stride, bm_off; };   // bm_off: first word of the tensor's bitmap (exact maps)
 struct PlanConvDev {                     // one conv layer's share of the plan area (offsets in bytes from its start)
-    int32_t tensor, Hout, Wout, units_x, units_y, n_chunks, pad0, pad1;
+    int32_t tensor, Hout, Wout, units_x, units_y, n_chunks;
+    int32_t no_reuse;                    // 1: this layer is computed in full on every frame (its unit masks are all zero)
+    int32_t pad1;
     int64_t umask_off, count_off, list_off, pad2;
 };
 // What the list kernel leaves for the host, per frame: {reusable blocks, overflowed streams, 0, 0}, then per conv

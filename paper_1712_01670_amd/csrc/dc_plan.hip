@@ -518,6 +518,7 @@ __global__ __launch_bounds__(kPlanChunk) void plan_masks_exact_kernel(PlanDev P)
             const int y = ty * 4 + r;
             if (y < cv.Hout) mask |= ((map[(size_t)y * wpr + (x0 >> 5)] >> (x0 & 31)) & 0xfu) << (4 * r);
         }
+        if (cv.no_reuse) mask = 0;                           // a layer that does not use the cache
         const unsigned inside = inside_mask(cv.Hout, cv.Wout, ty, tx);
         dirty = (mask & inside) != inside ? 1 : 0;
         reinterpret_cast<uint16_t*>(P.area + cv.umask_off)[(size_t)stream * units + u] = (uint16_t)mask;
@@ -558,6 +559,7 @@ __global__ __launch_bounds__(kPlanChunk) void plan_masks_kernel(PlanDev P) {
                 mask |= rows * cols;
             }
         }
+        if (cv.no_reuse) mask = 0;                           // a layer that does not use the cache
         const unsigned inside = inside_mask(cv.Hout, cv.Wout, ty, tx);
         dirty = (mask & inside) != inside ? 1 : 0;
         reinterpret_cast<uint16_t*>(P.area + cv.umask_off)[(size_t)stream * units + u] = (uint16_t)mask;

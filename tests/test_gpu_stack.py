@@ -41,7 +41,7 @@ def _run_both(oracle, layers, videos, block, radius, bf16, in_place=False, devic
 
 def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False,
-             extend_borders=False, device_plan=False, exact_masks=False, cache_pool_add=False):
+             extend_borders=False, device_plan=False, exact_masks=False, cache_pool_add=False, no_reuse=None):
     """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
     n, T, H, W, C = videos.shape
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale, input_shape=(H, W, C))
@@ -50,10 +50,10 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
     runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
                                  want_regions=True, k_skip=k_skip, in_place=in_place, extend_borders=extend_borders,
                                  match_method=binding.DC_MATCH_DIAMOND if diamond else binding.DC_MATCH_EXHAUSTIVE,
-                                 device_plan=device_plan, exact_masks=exact_masks, cache_pool_add=cache_pool_add)
+                                 device_plan=device_plan, exact_masks=exact_masks, cache_pool_add=cache_pool_add, no_reuse=no_reuse)
     streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry,
                              diamond=diamond, k_skip=k_skip, extend_borders=extend_borders, exact_masks=exact_masks,
-                             cache_pool_add=cache_pool_add)
+                             cache_pool_add=cache_pool_add, no_reuse=no_reuse)
                for _ in range(n)]
     dev_video = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
     worst = worst_elem = 0.0
@@ -96,6 +96,8 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
                         ho, wo, _ = shapes[li + 1]
                         reused = (int(want["masks"][li + 1].sum()) if exact_masks else
                                   int(sum(int(r[2]) * int(r[3]) for r in want["rects"][li + 1])))
+                        if no_reuse is not None and no_reuse[li]:
+                            reused = 0
                         needed += (ho * wo - reused) * L["k"] * L["k"] * runner.layers[li]["cin"] * L["cout"]
             for ti in (check_tensors or range(len(layers) + 1)):
                 g = got[ti][s]
@@ -460,6 +462,27 @@ def test_cache_pool_add_needs_exact_maps_and_previous_outputs(oracle):
         r.step(torch.from_numpy(f1[None]).to(DEV))
     assert e.value.status == -4
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("exact", [False, True])
+def test_conv_layers_that_do_not_use_the_cache(oracle, exact):
+    """dc_match_options.no_reuse: flagged conv layers are computed in full, the others reuse; planned on the host and on
+    the GPU, rectangles and exact maps."""
+    layers = synth.tiny_net()
+    f1, f2 = synth.tiny_pair(0)
+    video = np.stack([f1, f2, f2, f1])[None]
+    for flags in ([0, 1, 0], [1, 0, 1], [1, 1, 1]):
+        _run_both(oracle, layers, video, 8, 8, False, exact_masks=exact, no_reuse=np.array(flags, np.uint8))
+    # the break-even policy on a model stack: layers with few multiply-adds per output are not cached
+    v = np.stack([synth.panning_video(5000 + s, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
+    layers = synth.vgg16()
+    flags = synth.no_reuse_flags(layers, 600)
+    assert flags.tolist()[:5] == [1, 1, 0, 1, 0] and flags.sum() == 3
+    _run_both(oracle, layers, v, 16, 16, True, bias_scale=0.0, exact_masks=exact, no_reuse=flags)
+    layers = synth.resnet50_trunk()[:23]
+    v = synth.panning_video(3000, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32)[None]
+    _run_both(oracle, layers, v, 16, 16, True, bias_scale=0.0, residual_scale=0.5, exact_masks=exact,
+              no_reuse=synth.no_reuse_flags(layers, 600))
 
 
 def test_border_case_planned_on_the_gpu(oracle):
