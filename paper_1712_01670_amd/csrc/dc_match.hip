@@ -477,20 +477,21 @@ __global__ __launch_bounds__(64) void motion_retest_kernel(
     for (int base = 0; base < nb; base += 4 * 64) {     // four independent loads per lane at a time
         uint32_t bs[4];
         int vx[4], vy[4];
+        bool has[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = base + u * 64 + lane;
-            const bool in = i < nb;
+            // with k-skip only the blocks on every k-th grid row and column carry a vector; the entries of the others
+            // are written further down by their own workgroups and are not read here
+            const bool in = i < nb && (k_skip == 1 || ((i / gw) % k_skip == 0 && (i % gw) % k_skip == 0));
+            has[u] = in;
             bs[u] = in ? sbest[i] : 0xffffffffu;
             vx[u] = in ? smv[2 * i] : 0;
             vy[u] = in ? smv[2 * i + 1] : 0;
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int i = base + u * 64 + lane;
-            // with k-skip only the blocks on every k-th grid row and column carry a vector
-            const bool searched = k_skip == 1 || ((i / gw) % k_skip == 0 && (i % gw) % k_skip == 0);
-            const bool pass = i < nb && searched && bs[u] <= max_ssd;
+            const bool pass = has[u] && bs[u] <= max_ssd;
             sx += pass ? vx[u] : 0;
             sy += pass ? vy[u] : 0;
             K += pass ? 1 : 0;
@@ -511,7 +512,7 @@ __global__ __launch_bounds__(64) void motion_retest_kernel(
     }
     const int bx = blk_id % gw, by = blk_id / gw;
     if (k_skip > 1 && (bx % k_skip != 0 || by % k_skip != 0) && lane == 0) {
-        // not searched: no vector (nobody reads these entries, the mean above skips them)
+        // not searched: no vector (no workgroup reads these entries: the mean above leaves them out)
         smv[2 * blk_id] = 0; smv[2 * blk_id + 1] = 0;
         sbest[blk_id] = 0xffffffffu;
     }
