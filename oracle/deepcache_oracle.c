@@ -61,7 +61,20 @@ typedef struct {
     int32_t in2, in3;      /* further producers of a concat, -1: none */
     int32_t within;        /* LRN: 0 = window over channels at one pixel, 1 = k x k pixels of one channel */
     float alpha, beta, kappa;   /* LRN constants */
+    /* conv layers only (Table 2's conv row speaks of a kernel of size k; these generalise it per axis):
+     * k2 > 0: the kernel is k rows x k2 columns with padding p along y and p2 along x; k2 == 0: k x k, padding p.
+     * dil > 1: taps are dil pixels apart, the kernel spans (k - 1) * dil + 1 pixels. */
+    int32_t k2, p2, dil;
 } oc_layer;
+
+/* kernel rows / columns, padding along y / x, dilation, and the span of the kernel in pixels */
+static int l_kh(const oc_layer* l) { return l->k; }
+static int l_kw(const oc_layer* l) { return (l->type == OC_CONV && l->k2 > 0) ? l->k2 : l->k; }
+static int l_ph(const oc_layer* l) { return l->p; }
+static int l_pw(const oc_layer* l) { return (l->type == OC_CONV && l->k2 > 0) ? l->p2 : l->p; }
+static int l_dil(const oc_layer* l) { return (l->type == OC_CONV && l->dil > 1) ? l->dil : 1; }
+static int l_eh(const oc_layer* l) { return (l_kh(l) - 1) * l_dil(l) + 1; }
+static int l_ew(const oc_layer* l) { return (l_kw(l) - 1) * l_dil(l) + 1; }
 
 #define OC_MAX_CONCAT 4
 /* producers of a concat layer, in channel order; returns their number */
@@ -417,10 +430,18 @@ static int ceil_div(int a, int b) { return -floor_div(-a, b); }
  * rectangle whose kxk windows lie wholly inside the input rectangle, which
  * reproduces both examples: last output column = floor((x+w-k+p)/s).
  * Returns 0 if nothing is left. */
+int oc_dt_window2(oc_rect in, int ew, int eh, int s, int pw, int ph, oc_rect* out);
 int oc_dt_window(oc_rect in, int k, int s, int p, oc_rect* out)
 {
-    int x0 = ceil_div(in.x + p, s), x1 = floor_div(in.x + in.w - k + p, s);
-    int y0 = ceil_div(in.y + p, s), y1 = floor_div(in.y + in.h - k + p, s);
+    return oc_dt_window2(in, k, k, s, p, p, out);
+}
+/* The same row for a window that spans ew columns and eh rows with paddings pw, ph (a kernel that is not square,
+ * or dilated: its span is (k - 1) * dilation + 1; the whole span must lie inside the rectangle, which is what a
+ * rectangle can guarantee for the taps). */
+int oc_dt_window2(oc_rect in, int ew, int eh, int s, int pw, int ph, oc_rect* out)
+{
+    int x0 = ceil_div(in.x + pw, s), x1 = floor_div(in.x + in.w - ew + pw, s);
+    int y0 = ceil_div(in.y + ph, s), y1 = floor_div(in.y + in.h - eh + ph, s);
     if (x1 < x0 || y1 < y0) return 0;
     out->x = x0; out->y = y0; out->w = x1 - x0 + 1; out->h = y1 - y0 + 1;
     return 1;
@@ -432,13 +453,18 @@ int oc_dt_window(oc_rect in, int k, int s, int p, oc_rect* out)
  * therefore extends, for this rule, beyond that side: the first output column is 0 if x == 0, the last one is
  * the last of the map if x + w == wa; likewise for rows.  (An optional extension beyond the paper; off = the
  * printed rule.) */
+int oc_dt_window_ext2(oc_rect in, int ew, int eh, int s, int pw, int ph, int wa, int ha, oc_rect* out);
 int oc_dt_window_ext(oc_rect in, int k, int s, int p, int wa, int ha, oc_rect* out)
 {
-    int wo = (wa + 2 * p - k) / s + 1, ho = (ha + 2 * p - k) / s + 1;
-    int x0 = in.x == 0 ? 0 : ceil_div(in.x + p, s);
-    int x1 = in.x + in.w == wa ? wo - 1 : floor_div(in.x + in.w - k + p, s);
-    int y0 = in.y == 0 ? 0 : ceil_div(in.y + p, s);
-    int y1 = in.y + in.h == ha ? ho - 1 : floor_div(in.y + in.h - k + p, s);
+    return oc_dt_window_ext2(in, k, k, s, p, p, wa, ha, out);
+}
+int oc_dt_window_ext2(oc_rect in, int ew, int eh, int s, int pw, int ph, int wa, int ha, oc_rect* out)
+{
+    int wo = (wa + 2 * pw - ew) / s + 1, ho = (ha + 2 * ph - eh) / s + 1;
+    int x0 = in.x == 0 ? 0 : ceil_div(in.x + pw, s);
+    int x1 = in.x + in.w == wa ? wo - 1 : floor_div(in.x + in.w - ew + pw, s);
+    int y0 = in.y == 0 ? 0 : ceil_div(in.y + ph, s);
+    int y1 = in.y + in.h == ha ? ho - 1 : floor_div(in.y + in.h - eh + ph, s);
     if (x1 > wo - 1) x1 = wo - 1;
     if (y1 > ho - 1) y1 = ho - 1;
     if (x1 < x0 || y1 < y0) return 0;
@@ -520,8 +546,8 @@ int oc_propagate_ext(const oc_layer* L, int n_layers, int H, int W,
         int ho = ha, wo = wa, S = cum_stride[a];
         int windowed = l->type == OC_CONV || l->type == OC_MAXPOOL || l->type == OC_AVGPOOL;
         if (windowed) {
-            ho = (ha + 2 * l->p - l->k) / l->s + 1;
-            wo = (wa + 2 * l->p - l->k) / l->s + 1;
+            ho = (ha + 2 * l_ph(l) - l_eh(l)) / l->s + 1;
+            wo = (wa + 2 * l_pw(l) - l_ew(l)) / l->s + 1;
             S *= l->s;
         }
         if (l->type == OC_FC) { ho = 1; wo = 1; }
@@ -559,7 +585,8 @@ int oc_propagate_ext(const oc_layer* L, int n_layers, int H, int W,
         } else if (windowed) {
             for (int i = 0; i < na; ++i) {
                 oc_rect r, c;
-                if (!(ext ? oc_dt_window_ext(ra[i], l->k, l->s, l->p, wa, ha, &r) : oc_dt_window(ra[i], l->k, l->s, l->p, &r))) continue;
+                if (!(ext ? oc_dt_window_ext2(ra[i], l_ew(l), l_eh(l), l->s, l_pw(l), l_ph(l), wa, ha, &r)
+                          : oc_dt_window2(ra[i], l_ew(l), l_eh(l), l->s, l_pw(l), l_ph(l), &r))) continue;
                 if (!clip_to_source(r, dx, dy, wo, ho, &c)) continue;
                 if (n < cap) ro[n] = c; else overflow = 1;
                 ++n;
@@ -634,11 +661,13 @@ int oc_propagate_masks(const oc_layer* L, int n_layers, int H, int W, const uint
         int ha = hw[2 * a], wa = hw[2 * a + 1];
         int windowed = l->type == OC_CONV || l->type == OC_MAXPOOL || l->type == OC_AVGPOOL;
         int lrn_px = l->type == OC_LRN && l->within;
-        int k = windowed ? l->k : (lrn_px ? l->k : 1);
+        /* taps of the window: kh x kw, dil pixels apart (a conv layer may have a kernel that is not square, or dilated) */
+        int kh = windowed ? l_kh(l) : (lrn_px ? l->k : 1), kw = windowed ? l_kw(l) : (lrn_px ? l->k : 1);
+        int dil = windowed ? l_dil(l) : 1;
         int s = windowed ? l->s : 1;
-        int p = windowed ? l->p : (lrn_px ? (l->k - 1) / 2 : 0);
-        int ho = windowed ? (ha + 2 * l->p - l->k) / l->s + 1 : (l->type == OC_FC ? 1 : ha);
-        int wo = windowed ? (wa + 2 * l->p - l->k) / l->s + 1 : (l->type == OC_FC ? 1 : wa);
+        int ph = windowed ? l_ph(l) : (lrn_px ? (l->k - 1) / 2 : 0), pw = windowed ? l_pw(l) : (lrn_px ? (l->k - 1) / 2 : 0);
+        int ho = windowed ? (ha + 2 * l_ph(l) - l_eh(l)) / l->s + 1 : (l->type == OC_FC ? 1 : ha);
+        int wo = windowed ? (wa + 2 * l_pw(l) - l_ew(l)) / l->s + 1 : (l->type == OC_FC ? 1 : wa);
         hw[2 * t] = ho; hw[2 * t + 1] = wo;
         cum_stride[t] = windowed ? cum_stride[a] * l->s : cum_stride[a];
         int dx = round_div(mx, cum_stride[t]), dy = round_div(my, cum_stride[t]);
@@ -658,9 +687,9 @@ int oc_propagate_masks(const oc_layer* L, int n_layers, int H, int W, const uint
                     for (int j = 0; j < m; ++j) ok = ok && masks[ids[j]][(size_t)y * wa + x];
                 } else {
                     ok = 1;
-                    for (int ky = 0; ky < k && ok; ++ky)
-                        for (int kx = 0; kx < k && ok; ++kx) {
-                            int iy = y * s - p + ky, ix = x * s - p + kx;
+                    for (int ky = 0; ky < kh && ok; ++ky)
+                        for (int kx = 0; kx < kw && ok; ++kx) {
+                            int iy = y * s - ph + ky * dil, ix = x * s - pw + kx * dil;
                             if (iy < 0 || iy >= ha || ix < 0 || ix >= wa) { if (!ext) ok = 0; continue; }
                             ok = ma[(size_t)iy * wa + ix];
                         }
@@ -730,12 +759,25 @@ void oc_frame_to_tensor(const uint8_t* frame, size_t n, float* out)
  * mask == NULL (or cache_prev == NULL) means: compute every pixel.
  * in [Hin][Win][cin], out [Hout][Wout][cout], w [cout][k][k][cin].
  */
+void oc_conv_cached2(const float* in, int Hin, int Win, int cin,
+                     const float* w, const float* bias, int cout, int kh, int kw, int s, int ph, int pw, int dil, int relu,
+                     const float* cache_prev, const uint8_t* mask, int dx, int dy,
+                     int bf16, float* out);
 void oc_conv_cached(const float* in, int Hin, int Win, int cin,
                     const float* w, const float* bias, int cout, int k, int s, int p, int relu,
                     const float* cache_prev, const uint8_t* mask, int dx, int dy,
                     int bf16, float* out)
 {
-    int Hout = (Hin + 2 * p - k) / s + 1, Wout = (Win + 2 * p - k) / s + 1;
+    oc_conv_cached2(in, Hin, Win, cin, w, bias, cout, k, k, s, p, p, 1, relu, cache_prev, mask, dx, dy, bf16, out);
+}
+/* The same with a kernel of kh rows x kw columns, paddings ph / pw and taps dil pixels apart: w [cout][kh][kw][cin],
+ * out[y][x] = sum over (ky, kx) of in[y s - ph + ky dil][x s - pw + kx dil] * w[.][ky][kx]. */
+void oc_conv_cached2(const float* in, int Hin, int Win, int cin,
+                     const float* w, const float* bias, int cout, int kh, int kw, int s, int ph, int pw, int dil, int relu,
+                     const float* cache_prev, const uint8_t* mask, int dx, int dy,
+                     int bf16, float* out)
+{
+    int Hout = (Hin + 2 * ph - ((kh - 1) * dil + 1)) / s + 1, Wout = (Win + 2 * pw - ((kw - 1) * dil + 1)) / s + 1;
 #pragma omp parallel for schedule(dynamic)
     for (int y = 0; y < Hout; ++y)
         for (int x = 0; x < Wout; ++x) {
@@ -747,14 +789,14 @@ void oc_conv_cached(const float* in, int Hin, int Win, int cin,
             }
             for (int co = 0; co < cout; ++co) {
                 double acc = bias ? (double)bias[co] : 0.0;
-                for (int ky = 0; ky < k; ++ky) {
-                    int iy = y * s - p + ky;
+                for (int ky = 0; ky < kh; ++ky) {
+                    int iy = y * s - ph + ky * dil;
                     if (iy < 0 || iy >= Hin) continue;
-                    for (int kx = 0; kx < k; ++kx) {
-                        int ix = x * s - p + kx;
+                    for (int kx = 0; kx < kw; ++kx) {
+                        int ix = x * s - pw + kx * dil;
                         if (ix < 0 || ix >= Win) continue;
                         const float* ip = in + ((size_t)iy * Win + ix) * cin;
-                        const float* wp = w + (((size_t)co * k + ky) * k + kx) * cin;
+                        const float* wp = w + (((size_t)co * kh + ky) * kw + kx) * cin;
                         for (int ci = 0; ci < cin; ++ci) acc += (double)ip[ci] * (double)wp[ci];
                     }
                 }
@@ -961,9 +1003,9 @@ int oc_run_stack(const oc_layer* L, int n_layers, const float* const* weights,
                 mask = (uint8_t*)malloc((size_t)ho * wo);
                 oc_rasterize(rects + (size_t)t * cap, n_rects[t], ho, wo, mask);
             }
-            oc_conv_cached(cur[a], ha, wa, l->cin, weights[li], bias ? bias[li] : NULL, l->cout,
-                           l->k, l->s, l->p, l->relu, mask ? prev[t] : NULL, mask,
-                           dxy[2 * t], dxy[2 * t + 1], bf16, cur[t]);
+            oc_conv_cached2(cur[a], ha, wa, l->cin, weights[li], bias ? bias[li] : NULL, l->cout,
+                            l_kh(l), l_kw(l), l->s, l_ph(l), l_pw(l), l_dil(l), l->relu, mask ? prev[t] : NULL, mask,
+                            dxy[2 * t], dxy[2 * t + 1], bf16, cur[t]);
             free(mask);
         } else if (l->type == OC_MAXPOOL) {
             oc_maxpool(cur[a], ha, wa, l->cin, l->k, l->s, l->p, cur[t]);

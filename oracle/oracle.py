@@ -30,11 +30,13 @@ class Rect(C.Structure):
 
 class Layer(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("type", "k", "s", "p", "cin", "cout", "relu", "in0", "in1", "in2", "in3",
-                                         "within")] + [(n, C.c_float) for n in ("alpha", "beta", "kappa")]
+                                         "within")] + [(n, C.c_float) for n in ("alpha", "beta", "kappa")] + \
+               [(n, C.c_int32) for n in ("k2", "p2", "dil")]
 
 
 # value of a field that a layer's dict leaves out
-_LAYER_DEFAULTS = dict(k=1, s=1, p=0, relu=0, in1=-1, in2=-1, in3=-1, within=0, alpha=0.0, beta=0.0, kappa=1.0)
+_LAYER_DEFAULTS = dict(k=1, s=1, p=0, relu=0, in1=-1, in2=-1, in3=-1, within=0, alpha=0.0, beta=0.0, kappa=1.0,
+                       k2=0, p2=0, dil=1)
 
 
 _lib = None
@@ -63,6 +65,16 @@ def _p(a):
 
 def num_threads():
     return int(lib().oc_num_threads())
+
+
+def window_out_hw(L, h, w):
+    """Output size of a windowed layer (conv, pooling): a conv layer may carry k2 / p2 (kernel columns, their
+    padding) and dil (distance between taps)."""
+    conv = L["type"] == 0
+    kh, kw = L["k"], (L["k2"] if conv and L.get("k2", 0) > 0 else L["k"])
+    ph, pw = L["p"], (L.get("p2", 0) if conv and L.get("k2", 0) > 0 else L["p"])
+    dil = L.get("dil", 1) if conv and L.get("dil", 1) > 1 else 1
+    return (h + 2 * ph - ((kh - 1) * dil + 1)) // L["s"] + 1, (w + 2 * pw - ((kw - 1) * dil + 1)) // L["s"] + 1
 
 
 def layers_to_c(layers):
@@ -161,6 +173,13 @@ def dt_lrn(rect, r):
     return (out.x, out.y, out.w, out.h) if ok else None
 
 
+def dt_window2(rect, ew, eh, s, pw, ph):
+    """Table 2's conv / pooling row for a window that spans ew columns and eh rows, paddings pw / ph."""
+    out = Rect()
+    ok = lib().oc_dt_window2(Rect(*[int(v) for v in rect]), int(ew), int(eh), int(s), int(pw), int(ph), C.byref(out))
+    return (out.x, out.y, out.w, out.h) if ok else None
+
+
 def dt_window_ext(rect, k, s, p, wa, ha):
     """Conv/pool row with the border case (a rectangle touching a side of the wa x ha map extends beyond it)."""
     out = Rect()
@@ -191,7 +210,7 @@ def tensor_hw(layers, H, W):
     for L in layers:
         h, w_ = hw[L["in0"]]
         if L["type"] in (0, 1, 8):
-            hw.append(((h + 2 * L["p"] - L["k"]) // L["s"] + 1, (w_ + 2 * L["p"] - L["k"]) // L["s"] + 1))
+            hw.append(window_out_hw(L, h, w_))
         elif L["type"] == 6:
             hw.append((1, 1))
         else:
@@ -237,14 +256,16 @@ def frame_to_tensor(frame):
     return out
 
 
-def conv_cached(x, w, bias, k, s, p, relu, cache_prev=None, mask=None, dxy=(0, 0), bf16=False):
-    """Section 5 "Reuse".  x [H][W][cin] fp32, w [cout][k][k][cin]."""
+def conv_cached(x, w, bias, k, s, p, relu, cache_prev=None, mask=None, dxy=(0, 0), bf16=False, k2=0, p2=0, dil=1):
+    """Section 5 "Reuse".  x [H][W][cin] fp32, w [cout][k][k][cin]; k2 > 0: a kernel of k rows x k2 columns with paddings
+    p (rows) and p2 (columns), w [cout][k][k2][cin]; dil: distance between taps."""
     x = np.ascontiguousarray(x, np.float32)
     w = np.ascontiguousarray(w, np.float32)
     Hin, Win, cin = x.shape
     cout = w.shape[0]
-    assert w.shape == (cout, k, k, cin)
-    Ho, Wo = (Hin + 2 * p - k) // s + 1, (Win + 2 * p - k) // s + 1
+    kh, kw, ph, pw = k, (k2 if k2 > 0 else k), p, (p2 if k2 > 0 else p)
+    assert w.shape == (cout, kh, kw, cin)
+    Ho, Wo = (Hin + 2 * ph - ((kh - 1) * dil + 1)) // s + 1, (Win + 2 * pw - ((kw - 1) * dil + 1)) // s + 1
     out = np.zeros((Ho, Wo, cout), np.float32)
     if bias is not None:
         bias = np.ascontiguousarray(bias, np.float32)
@@ -252,8 +273,8 @@ def conv_cached(x, w, bias, k, s, p, relu, cache_prev=None, mask=None, dxy=(0, 0
         mask = np.ascontiguousarray(mask, np.uint8)
         cache_prev = np.ascontiguousarray(cache_prev, np.float32)
         assert mask.shape == (Ho, Wo) and cache_prev.shape == out.shape
-    lib().oc_conv_cached(_p(x), Hin, Win, cin, _p(w), _p(bias), cout, k, s, p, int(relu),
-                         _p(cache_prev), _p(mask), int(dxy[0]), int(dxy[1]), int(bf16), _p(out))
+    lib().oc_conv_cached2(_p(x), Hin, Win, cin, _p(w), _p(bias), cout, kh, kw, s, ph, pw, int(dil), int(relu),
+                          _p(cache_prev), _p(mask), int(dxy[0]), int(dxy[1]), int(bf16), _p(out))
     return out
 
 
@@ -353,8 +374,7 @@ class Stream:
         for L in layers:
             h, w_, _ = shapes[L["in0"]]
             if L["type"] in (0, 1, 8):
-                shapes.append(((h + 2 * L["p"] - L["k"]) // L["s"] + 1,
-                               (w_ + 2 * L["p"] - L["k"]) // L["s"] + 1, L["cout"]))
+                shapes.append((*window_out_hw(L, h, w_), L["cout"]))
             elif L["type"] == 6:
                 shapes.append((1, 1, L["cout"]))
             else:

@@ -28,6 +28,15 @@ def _conv(cin, cout, k, s, p, relu, in0):
     return dict(type=CONV, k=k, s=s, p=p, cin=cin, cout=cout, relu=int(relu), in0=in0, in1=-1)
 
 
+def conv_geometry(L):
+    """(kernel rows, kernel columns, padding rows, padding columns, dilation) of a conv layer: k2 > 0 gives the kernel
+    k rows x k2 columns with paddings p / p2, dil > 1 puts the taps dil pixels apart."""
+    if L["type"] != CONV:
+        return L["k"], L["k"], L["p"], L["p"], 1
+    k2 = L.get("k2", 0)
+    return L["k"], (k2 if k2 > 0 else L["k"]), L["p"], (L.get("p2", 0) if k2 > 0 else L["p"]), max(1, L.get("dil", 1))
+
+
 def _pool(c, k, s, p, in0):
     return dict(type=MAXPOOL, k=k, s=s, p=p, cin=c, cout=c, relu=0, in0=in0, in1=-1)
 
@@ -78,7 +87,23 @@ def _chain(spec, cin):
 def no_reuse_flags(layers, min_macs):
     """A cache setting for a stack: flag [n_layers] (uint8) the conv layers with fewer than min_macs multiply-adds per
     output element (k * k * cin of the layer table as given); flagged layers are computed in full on every frame."""
-    return np.array([1 if (L["type"] == CONV and L["k"] * L["k"] * L["cin"] < min_macs) else 0 for L in layers], np.uint8)
+    return np.array([1 if (L["type"] == CONV and conv_geometry(L)[0] * conv_geometry(L)[1] * L["cin"] < min_macs) else 0
+                     for L in layers], np.uint8)
+
+
+def factorised_net(c=16):
+    """A small stack with kernels that are not square and with dilated ones (the 1 x 7 / 7 x 1 pairs of later
+    inception-style networks, the dilated 3 x 3 of segmentation networks): 3 -> c 3x3, c -> c 1x7, c -> c 7x1,
+    max-pooling 2x2, c -> 2c 3x3 dilated by 2, 2c -> 2c 3x1 stride 2, 2c -> 2c 5x3 dilated by 2, 2c -> 2c 1x1."""
+    C_ = lambda cin, cout, k, s, p, i, **kw: dict(type=CONV, k=k, s=s, p=p, cin=cin, cout=cout, relu=1, in0=i, in1=-1, **kw)
+    return [C_(3, c, 3, 1, 1, 0),
+            C_(c, c, 1, 1, 0, 1, k2=7, p2=3),
+            C_(c, c, 7, 1, 3, 2, k2=1, p2=0),
+            _pool(c, 2, 2, 0, 3),
+            C_(c, 2 * c, 3, 1, 2, 4, dil=2),
+            C_(2 * c, 2 * c, 3, 2, 1, 5, k2=1, p2=0),
+            C_(2 * c, 2 * c, 5, 1, 4, 6, k2=3, p2=2, dil=2),
+            C_(2 * c, 2 * c, 1, 1, 0, 7)]
 
 
 def tiny_net():
@@ -251,8 +276,9 @@ def tensor_shapes(layers, H, W, C):
     for L in layers:
         h, w, _ = shapes[L["in0"]]
         if L["type"] in (CONV, MAXPOOL, AVGPOOL):
-            ho = (h + 2 * L["p"] - L["k"]) // L["s"] + 1
-            wo = (w + 2 * L["p"] - L["k"]) // L["s"] + 1
+            kh, kw, ph, pw, dil = conv_geometry(L)
+            ho = (h + 2 * ph - ((kh - 1) * dil + 1)) // L["s"] + 1
+            wo = (w + 2 * pw - ((kw - 1) * dil + 1)) // L["s"] + 1
             shapes.append((ho, wo, L["cout"]))
         elif L["type"] == FC:
             shapes.append((1, 1, L["cout"]))
@@ -282,8 +308,9 @@ def he_weights(layers, seed, bias_scale=0.0, residual_scale=1.0, input_shape=Non
             ws.append(None)
             bs.append(None)
             continue
-        k, cin, cout = L["k"], L["cin"], L["cout"]
-        w = rng.standard_normal((cout, k, k, cin)) * np.sqrt(2.0 / (cin * k * k))
+        cin, cout = L["cin"], L["cout"]
+        kh, kw = conv_geometry(L)[:2]
+        w = rng.standard_normal((cout, kh, kw, cin)) * np.sqrt(2.0 / (cin * kh * kw))
         if i in feeds_add:
             w = w * residual_scale
         b = rng.standard_normal(cout) * bias_scale
