@@ -156,7 +156,8 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
         for li, (g_ms, c_ms) in runner.profile_ms().items():
             L = layers[li]
             ho, wo, co = shapes[li + 1]
-            mac_px = L["k"] * L["k"] * L["cin"] * L["cout"]
+            kh, kw = synth.conv_geometry(L)[:2]
+            mac_px = kh * kw * L["cin"] * L["cout"]
             reused = 0 if st.full else ls["reused_px"][li]
             if g_ms is not None:
                 name = binding.conv_kernel_name(ls["kernel_id"][li])

@@ -83,6 +83,11 @@ typedef struct {
     int32_t in2, in3;      /* DC_CONCAT: third and fourth producer, -1: none (other types ignore them) */
     int32_t within;        /* DC_LRN: 0 = window over channels, 1 = window over pixels */
     float alpha, beta, kappa;   /* DC_LRN */
+    /* DC_CONV only (other types ignore them).  k2 > 0: the kernel has k rows and k2 columns, with padding p along y
+     * and p2 along x (weights [cout][k][k2][cin]); k2 == 0: k x k with padding p on both axes.  dil > 1: the taps are
+     * dil pixels apart (the kernel spans (k - 1) dil + 1 pixels).  Table 2's conv row applies with that span per axis;
+     * the exact maps look at the taps themselves. */
+    int32_t k2, p2, dil;
 } dc_layer;
 
 /* Reusable regions of one tensor of one stream (Section 5 "Propagation"):

@@ -40,7 +40,8 @@ class Rect(C.Structure):
 
 class Layer(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("type", "k", "s", "p", "cin", "cout", "relu", "in0", "in1", "in2", "in3",
-                                         "within")] + [(n, C.c_float) for n in ("alpha", "beta", "kappa")]
+                                         "within")] + [(n, C.c_float) for n in ("alpha", "beta", "kappa")] + \
+               [(n, C.c_int32) for n in ("k2", "p2", "dil")]
 
 
 class Regions(C.Structure):
@@ -278,8 +279,7 @@ def dc_cached_conv_layer(layer, x, weights, bias, cache_prev=None, regions=None,
     dtype = DC_BF16 if x.dtype == torch.bfloat16 else DC_F32
     assert weights.dtype == x.dtype and weights.is_contiguous()
     n, Hin, Win, cin = x.shape
-    k, s, p = layer["k"], layer["s"], layer["p"]
-    Ho, Wo = (Hin + 2 * p - k) // s + 1, (Win + 2 * p - k) // s + 1
+    Ho, Wo, _ = synth.tensor_shapes([dict(layer, in0=0)], Hin, Win, cin)[1]
     if out is None:
         out = torch.empty((n, Ho, Wo, layer["cout"]), dtype=x.dtype, device=x.device)
     Lc = layers_to_c([layer])

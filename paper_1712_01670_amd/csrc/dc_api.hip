@@ -90,8 +90,10 @@ int input_channels(const dc_layer* L, int n_layers, int c_frame) {
 
 int check_conv_layer(const dc_layer* l) {
     if (l->type != DC_CONV) return DC_ERR_INVALID_ARG;
-    if (l->k < 1 || l->s < 1 || l->p < 0 || l->p >= l->k || l->cin < 1 || l->cout < 1) return DC_ERR_INVALID_ARG;
-    if (l->relu < 0 || l->relu > 2) return DC_ERR_INVALID_ARG;
+    const WindowGeom g = window_geom(*l);
+    if (g.kh < 1 || g.kw < 1 || l->s < 1 || g.ph < 0 || g.pw < 0 || g.ph >= g.eh || g.pw >= g.ew || l->cin < 1 || l->cout < 1)
+        return DC_ERR_INVALID_ARG;
+    if (l->relu < 0 || l->relu > 2 || l->k2 < 0 || l->dil < 0 || l->dil > 64 || g.kh > 64 || g.kw > 64) return DC_ERR_INVALID_ARG;
     return DC_OK;
 }
 
@@ -156,13 +158,15 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
                      bool copy_done = false, void* scratch = nullptr, size_t scratch_bytes = 0,
                      const void* w_packed = nullptr, const TileDev* dev_tiles = nullptr, int dev_capacity = 0,
                      const int* dev_count = nullptr, long dev_hint = -1) {
-    const int Hout = (Hin + 2 * l.p - l.k) / l.s + 1, Wout = (Win + 2 * l.p - l.k) / l.s + 1;
+    const WindowGeom wg = window_geom(l);
+    const int Hout = (Hin + 2 * wg.ph - wg.eh) / l.s + 1, Wout = (Win + 2 * wg.pw - wg.ew) / l.s + 1;
     ConvLaunch c;
     c.kernel_id = kernel_id;
     if (kernel_id) *kernel_id = -1;
     c.in = in; c.w = w; c.w_packed = w_packed; c.bias = bias; c.out = out;
     c.n_streams = n_streams; c.Hin = Hin; c.Win = Win; c.Cin = l.cin;
     c.Hout = Hout; c.Wout = Wout; c.Cout = l.cout; c.k = l.k; c.s = l.s; c.p = l.p; c.relu = l.relu;
+    if (!plain_square(l)) { c.kw = wg.kw; c.pw = wg.pw; c.dil = wg.dil; }
     c.dtype = dtype; c.tiling = tiling;
     c.scratch = scratch; c.scratch_bytes = scratch_bytes;
     if (dev_tiles) {      // a list the planning kernels built: its length is in device memory, the copies are done
@@ -235,7 +239,8 @@ void device_plan_layout(const dc_layer* L, int n_layers, const std::vector<int>&
     int64_t bm = ((int64_t)hs[0] * ((ws[0] + 31) / 32) + 63) / 64 * 64;          // every bitmap starts on a 256-byte line
     for (int i = 0; i < n_layers; ++i) {
         const dc_layer& l = L[i];
-        d.layers[i] = PlanLayerDev{l.type, l.k, l.s, l.p, l.in0, l.in1, l.in2, l.in3, l.within, 0, 0, 0};
+        const WindowGeom wg = window_geom(l);
+        d.layers[i] = PlanLayerDev{l.type, l.k, l.s, l.p, l.in0, l.in1, l.in2, l.in3, l.within, wg.kw, wg.pw, wg.dil};
         const bool windowed = l.type == DC_CONV || l.type == DC_MAXPOOL || l.type == DC_AVGPOOL;
         const int cum = d.tensors[l.in0].cum_stride * (windowed ? l.s : 1);
         if (bm > 0x7fffffffll) return;
@@ -492,8 +497,9 @@ int32_t dc_conv_tile_shape(const dc_layer* layer, int32_t n_streams, int32_t Hin
     int rc = check_conv_layer(layer);
     if (rc) return rc;
     if (n_streams < 1 || Hin < 1 || Win < 1) return DC_ERR_INVALID_ARG;
-    if (Hin + 2 * layer->p < layer->k || Win + 2 * layer->p < layer->k) return DC_ERR_BAD_SHAPE;
-    const int Hout = (Hin + 2 * layer->p - layer->k) / layer->s + 1, Wout = (Win + 2 * layer->p - layer->k) / layer->s + 1;
+    const WindowGeom lg = window_geom(*layer);
+    if (Hin + 2 * lg.ph < lg.eh || Win + 2 * lg.pw < lg.ew) return DC_ERR_BAD_SHAPE;
+    const int Hout = (Hin + 2 * lg.ph - lg.eh) / layer->s + 1, Wout = (Win + 2 * lg.pw - lg.ew) / layer->s + 1;
     ConvTiling t = pick_tiling(*layer, Hout, Wout, n_streams, dtype);
     *th = t.th; *tw = t.tw; *nt = t.nt; *cfg = t.cfg;
     return DC_OK;
@@ -597,8 +603,9 @@ int32_t dc_conv_workspace_bytes(const dc_layer* layer, int32_t n_streams, int32_
     int rc = check_conv_layer(layer);
     if (rc) return rc;
     if (n_streams < 1 || Hin < 1 || Win < 1 || max_rects < 0) return DC_ERR_INVALID_ARG;
-    if (Hin + 2 * layer->p < layer->k || Win + 2 * layer->p < layer->k) return DC_ERR_BAD_SHAPE;
-    const int Hout = (Hin + 2 * layer->p - layer->k) / layer->s + 1, Wout = (Win + 2 * layer->p - layer->k) / layer->s + 1;
+    const WindowGeom lg = window_geom(*layer);
+    if (Hin + 2 * lg.ph < lg.eh || Win + 2 * lg.pw < lg.ew) return DC_ERR_BAD_SHAPE;
+    const int Hout = (Hin + 2 * lg.ph - lg.eh) / layer->s + 1, Wout = (Win + 2 * lg.pw - lg.ew) / layer->s + 1;
     size_t worst = 0;
     for (int dtype = 0; dtype < 2; ++dtype) {
         size_t b = plan_bytes(n_streams, Hout, Wout, pick_tiling(*layer, Hout, Wout, n_streams, dtype), max_rects);
@@ -614,7 +621,7 @@ int32_t dc_packed_weights_bytes(const dc_layer* layer, int32_t dtype, size_t* by
     if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
     int rc = check_conv_layer(layer);
     if (rc) return rc;
-    *bytes = packed_weights_bytes(layer->k, layer->s, layer->cin, layer->cout, dtype);
+    *bytes = plain_square(*layer) ? packed_weights_bytes(layer->k, layer->s, layer->cin, layer->cout, dtype) : 0;
     return DC_OK;
 }
 
@@ -623,7 +630,7 @@ int32_t dc_pack_conv_weights(const dc_layer* layer, const void* weights, int32_t
     if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
     int rc = check_conv_layer(layer);
     if (rc) return rc;
-    if (!packed_weights_bytes(layer->k, layer->s, layer->cin, layer->cout, dtype)) return DC_ERR_BAD_SHAPE;
+    if (!plain_square(*layer) || !packed_weights_bytes(layer->k, layer->s, layer->cin, layer->cout, dtype)) return DC_ERR_BAD_SHAPE;
     if (reinterpret_cast<uintptr_t>(weights) % 16 || reinterpret_cast<uintptr_t>(packed) % 16 || weights == packed)
         return DC_ERR_INVALID_ARG;
     DC_TRY_HIP(launch_pack_weights(weights, packed, layer->cin, layer->cout, dtype, as_stream(stream)));
@@ -639,8 +646,9 @@ int32_t dc_cached_conv_layer(const dc_layer* layer, const void* in, const void* 
     if (rc) return rc;
     if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
     if (n_streams < 1 || Hin < 1 || Win < 1) return DC_ERR_INVALID_ARG;
-    if (Hin + 2 * layer->p < layer->k || Win + 2 * layer->p < layer->k) return DC_ERR_BAD_SHAPE;
-    const int Hout = (Hin + 2 * layer->p - layer->k) / layer->s + 1, Wout = (Win + 2 * layer->p - layer->k) / layer->s + 1;
+    const WindowGeom lg = window_geom(*layer);
+    if (Hin + 2 * lg.ph < lg.eh || Win + 2 * lg.pw < lg.ew) return DC_ERR_BAD_SHAPE;
+    const int Hout = (Hin + 2 * lg.ph - lg.eh) / layer->s + 1, Wout = (Win + 2 * lg.pw - lg.ew) / layer->s + 1;
     const ConvTiling tiling = pick_tiling(*layer, Hout, Wout, n_streams, dtype);
     hipStream_t st = as_stream(stream);
     if (!regions || !cache_prev)
@@ -684,8 +692,9 @@ int32_t dc_cached_conv_layer_noalloc(const dc_layer* layer, const void* in, cons
     if (rc) return rc;
     if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
     if (n_streams < 1 || Hin < 1 || Win < 1) return DC_ERR_INVALID_ARG;
-    if (Hin + 2 * layer->p < layer->k || Win + 2 * layer->p < layer->k) return DC_ERR_BAD_SHAPE;
-    const int Hout = (Hin + 2 * layer->p - layer->k) / layer->s + 1, Wout = (Win + 2 * layer->p - layer->k) / layer->s + 1;
+    const WindowGeom lg = window_geom(*layer);
+    if (Hin + 2 * lg.ph < lg.eh || Win + 2 * lg.pw < lg.ew) return DC_ERR_BAD_SHAPE;
+    const int Hout = (Hin + 2 * lg.ph - lg.eh) / layer->s + 1, Wout = (Win + 2 * lg.pw - lg.ew) / layer->s + 1;
     const ConvTiling tiling = pick_tiling(*layer, Hout, Wout, n_streams, dtype);
     hipStream_t st = as_stream(stream);
     const bool cached = regions && cache_prev;
@@ -1166,7 +1175,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         hdr->n_layers = n_layers; hdr->n_convs = (int32_t)dl.convs.size();
         for (size_t c = 0; c < dl.convs.size(); ++c) {
             const dc_layer& l = layers[dl.conv_layer[c]];
-            hdr->conv[c] = DevHostConv{dl.conv_layer[c], (int32_t)(l.cout * dtype_size(dtype)), (int64_t)l.k * l.k * l.cin * l.cout,
+            hdr->conv[c] = DevHostConv{dl.conv_layer[c], (int32_t)(l.cout * dtype_size(dtype)), (int64_t)window_geom(l).kh * window_geom(l).kw * l.cin * l.cout,
                                        (int64_t)n_streams * dl.convs[c].Hout * dl.convs[c].Wout};
         }
         // With an overlap handle the matching and the planning run on the handle's stream, ahead of the layers: they
@@ -1377,7 +1386,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             if (l.type != DC_CONV) continue;
             tilings[i] = pick_tiling(l, hs[i + 1], ws[i + 1], n_streams, dtype);
             const int64_t px = (int64_t)hs[i + 1] * ws[i + 1] * n_streams;
-            const int64_t mac_px = (int64_t)l.k * l.k * l.cin * l.cout;
+            const int64_t mac_px = (int64_t)window_geom(l).kh * window_geom(l).kw * l.cin * l.cout;
             local.macs_full += px * mac_px;
             if (!cached) {
                 local.macs_needed += px * mac_px;

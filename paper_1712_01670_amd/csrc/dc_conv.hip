@@ -77,7 +77,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave id in a scalar register
     const int wave_k = wave % WK, wave_n = (wave / WK) % WN, wave_m = wave / (WK * WN);
     const int l16 = lane & 15, q = lane >> 4;
-    const int kk = P.k * P.k;
+    const int kk = P.k * P.kx;
 
     int ug, ntile;
     decode_workgroup(P.R, ug, ntile);
@@ -115,7 +115,8 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
     }
 
     // loop-invariant scalars, pinned in SGPRs
-    const int Cin = keep_scalar(P.Cin), kdim = keep_scalar(P.k), pwid = keep_scalar(P.pw), tgs = keep_scalar(P.tg);
+    const int Cin = keep_scalar(P.Cin), kdim = keep_scalar(P.kx), pwid = keep_scalar(P.pw), tgs = keep_scalar(P.tg);
+    const int dil = keep_scalar(P.dil);
     const int n_tapgroups = keep_scalar(P.n_tapgroups), patch_bytes = keep_scalar(P.patch_bytes);
     const int weight_bytes = keep_scalar(P.weight_bytes);
     const int np_slots = keep_scalar((P.p_instr - wave + NWAVES - 1) / NWAVES);   // load instructions of this wavefront
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_direct_kernel(ConvParams
             int ky = (tap0 + tl) / kdim, kx = (tap0 + tl) - ky * kdim;
             vec x0[UPW], w0[NBW], x1[UPW], w1[NBW];
             auto frag = [&](vec (&xv)[UPW], vec (&wv)[NBW]) {
-                const int trow = ky * pwid + kx, c = g * 4 + q;
+                const int trow = (ky * pwid + kx) * dil, c = g * 4 + q;
 #pragma unroll
                 for (int u0 = 0; u0 < UPW; u0 += UC) {
                     if (u0 < n_u) {     // units are handled in groups of UC: one uniform branch per group
@@ -270,7 +271,7 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_staged_kernel(ConvParams
     const int lane = tid & 63, wave = tid >> 6;
     const int wave_k = wave % WK, wave_n = (wave / WK) % WN, wave_m = wave / (WK * WN);
     const int l16 = lane & 15, q = lane >> 4;
-    const int kk = P.k * P.k;
+    const int kk = P.k * P.kx;
 
     int ug, ntile;
     decode_workgroup(P.R, ug, ntile);
@@ -369,8 +370,8 @@ __global__ __launch_bounds__(WM* WN* WK * 64) void conv_staged_kernel(ConvParams
         const int steps = ntap * GPC;
         for (int sidx = wave_k; sidx < steps; sidx += WK) {
             const int tl = sidx / GPC, g = sidx - tl * GPC;
-            const int ky = (tap0 + tl) / P.k, kx = (tap0 + tl) - ky * P.k;
-            const int xoff = (ky * P.pw + kx) * KCP + g * KG;
+            const int ky = (tap0 + tl) / P.kx, kx = (tap0 + tl) - ky * P.kx;
+            const int xoff = (ky * P.pw + kx) * P.dil * KCP + g * KG;
             const int woff = tl * (NT * KCP) + g * KG;
             vec xv[UPW], wv[NBW];
 #pragma unroll
@@ -421,12 +422,16 @@ size_t reduce_bytes(const Shape& S) {
 // Direct kernel: pick the channel chunk KC and taps per stage TG.  With `f_tg` > 0 only that stage shape
 // (chunk index f_kci, f_tg taps) is considered; otherwise the deepest stage (TG*KC useful K) whose two LDS
 // buffers fit wins.
+// kernel columns and taps of a launch (c.k rows; c.kw > 0: that many columns)
+inline int tap_cols(const ConvLaunch& c) { return c.kw > 0 ? c.kw : c.k; }
+inline int tap_count(const ConvLaunch& c) { return c.k * tap_cols(c); }
+
 Choice choose_direct_from(int shape, const ConvLaunch& c, int ph, int pw, bool forced, int f_kci, int f_tg) {
     const Shape& S = kShapes[shape];
     const int nwaves = S.wm * S.wn * S.wk;
     const size_t esz = dtype_size(c.dtype);
     const int ve = (int)(16 / esz), kg = 4 * ve;
-    const int kk = c.k * c.k;
+    const int kk = tap_count(c);
     Choice best{shape, 0, 0, 0, 0, 0, 0, 0, 0, 0, false, 0, 0};
     long best_score = -1;
     for (int kci = 0; kci < 3; ++kci) {
@@ -471,9 +476,9 @@ Choice choose_direct_from(int shape, const ConvLaunch& c, int ph, int pw, bool f
 // 15-25 % faster: one kernel row of taps per stage where at most two wavefronts share a stage's K, about a
 // dozen taps where four do.  `wgs` is the number of workgroups the launch would have with this shape.
 Choice choose_direct(int shape, const ConvLaunch& c, int ph, int pw, long wgs) {
-    const int kk = c.k * c.k;
-    if (wgs >= 384 && c.k > 1) {
-        int tg = c.k;
+    const int kk = tap_count(c);
+    if (wgs >= 384 && kk > 1) {
+        int tg = tap_cols(c) > 1 ? tap_cols(c) : c.k;      // one kernel row of taps (the column of a k x 1 kernel)
         if (kShapes[shape].wk > 2) { const int m = (kk + 12) / 13; tg = (kk + m - 1) / m; }
         Choice ch = choose_direct_from(shape, c, ph, pw, true, 0, tg);
         if (ch.ok) return ch;
@@ -486,7 +491,7 @@ Choice choose_staged(int shape, const ConvLaunch& c, int ph, int pw) {
     const int nth = S.wm * S.wn * S.wk * 64;
     const size_t esz = dtype_size(c.dtype);
     const int ve = (int)(16 / esz), kc = 4 * ve;
-    const int kk = c.k * c.k;
+    const int kk = tap_count(c);
     const int nvec = kc / ve, rs = nth / nvec, kcp = kc + ve;
     Choice ch{shape, 3, kc, 0, 0, 0, 0, 0, 0, 0, false, 0, 0};
     const int pv = (S.g * ph * pw + rs - 1) / rs;
@@ -531,12 +536,13 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     const long n_units = c.tiles ? c.n_tiles : (long)c.n_streams * units_x * units_y;
     if (n_units <= 0) return hipSuccess;
     const long n_hint = (c.tiles && c.n_tiles_dev && c.n_tiles_hint >= 0) ? std::max(1L, std::min(c.n_tiles_hint, n_units)) : n_units;
-    if (c.k > kMaxK) return hipErrorInvalidValue;
+    const int kh = c.k, kw = tap_cols(c), dil = c.dil > 1 ? c.dil : 1;
+    if (kh > kMaxK || kw > kMaxK) return hipErrorInvalidValue;
     // buffer loads address each tensor with 31-bit byte offsets
     if ((double)c.n_streams * c.Hin * c.Win * c.Cin * dtype_size(c.dtype) >= 2147483648.0 ||
-        (double)c.Cout * c.k * c.k * c.Cin * dtype_size(c.dtype) >= 2147483648.0)
+        (double)c.Cout * kh * kw * c.Cin * dtype_size(c.dtype) >= 2147483648.0)
         return hipErrorInvalidValue;
-    {
+    if (c.kw == 0 && dil == 1) {      // the kernels for the common shapes take square kernels without dilation
         hipError_t fe = hipSuccess;
         if (launch_conv_fast(c, n_units, n_hint, st, &fe)) return fe;
     }
@@ -554,7 +560,8 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
         else if (((n_hint + 1) / 2) * r32 >= t1) { shape = 1; g_rt = 2; }
         else { shape = 2; g_rt = 1; }
     }
-    const int ph = 3 * c.s + c.k, pw = ph;
+    // patch of a unit: its 4 x 4 outputs see 3 s + (kernel span) input rows and columns
+    const int ph = 3 * c.s + (kh - 1) * dil + 1, pw = 3 * c.s + (kw - 1) * dil + 1;
     const size_t esz = dtype_size(c.dtype);
     const bool vec_ok = (c.Cin % (16 / esz)) == 0 && reinterpret_cast<uintptr_t>(c.in) % 16 == 0 &&
                         reinterpret_cast<uintptr_t>(c.w) % 16 == 0;
@@ -578,18 +585,19 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
     P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
     P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
     P.k = c.k; P.s = c.s; P.p = c.p; P.relu = c.relu;
+    P.kx = kw; P.px = c.kw > 0 ? c.pw : c.p; P.dil = dil;
     P.units = c.tiles; P.n_units = (int)n_units; P.n_units_dev = c.tiles ? c.n_tiles_dev : nullptr; P.rects = c.rects; P.ranges = c.ranges;
     P.units_x = units_x; P.units_y = units_y;
     P.ph = ph; P.pw = pw; P.npix_magic = magic_of(ph * pw); P.pw_magic = magic_of(pw);
     P.tg = ch.tg; P.pv = ch.pv; P.wv = ch.wv; P.g_rt = g_rt; P.p_instr = ch.p_instr; P.w_instr = ch.w_instr;
-    P.chan_tail = (c.Cin % ch.kc) != 0; P.tap_tail = ((c.k * c.k) % ch.tg) != 0;
+    P.chan_tail = (c.Cin % ch.kc) != 0; P.tap_tail = ((kh * kw) % ch.tg) != 0;
     P.patch_bytes = ch.patch_bytes; P.weight_bytes = ch.weight_bytes; P.dump_off = ch.dump_off;
     P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * c.Cin * esz);
-    P.w_bytes = (uint32_t)((size_t)c.Cout * c.k * c.k * c.Cin * esz);
+    P.w_bytes = (uint32_t)((size_t)c.Cout * kh * kw * c.Cin * esz);
     P.out_vec = (c.Cout % 4 == 0) && reinterpret_cast<uintptr_t>(c.out) % 16 == 0 &&
                 (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0);
     P.ks = 1; P.chunks_per_split = 0; P.partial = nullptr;
-    P.n_tapgroups = (c.k * c.k + ch.tg - 1) / ch.tg;
+    P.n_tapgroups = (kh * kw + ch.tg - 1) / ch.tg;
     P.n_chunks = (c.Cin + ch.kc - 1) / ch.kc;
     P.R = (c.Cout + S.nt - 1) / S.nt;
     KernelFn fn = kTable[ch.shape].fn[c.dtype == DC_BF16 ? 1 : 0][ch.kci];

@@ -29,6 +29,7 @@ struct ConvParams {
     const float* bias;
     void* out;
     int Hin, Win, Cin, Hout, Wout, Cout, k, s, p, relu;
+    int kx, px, dil;        // general kernels: kernel columns (k: rows), padding along x (p: along y), distance between taps
     const TileDev* units;   // nullptr: every unit of every stream in raster order
     int n_units;            // length of the unit list; with n_units_dev the most it can be (the launch is sized for it)
     const int* n_units_dev; // optional, device: the length of a list that was built on the GPU
@@ -192,7 +193,7 @@ __device__ __forceinline__ uint32_t patch_pixel_offset(const ConvParams& P, cons
     if (prow >= G * npix) return kOob;
     const int g = fast_div(prow, P.npix_magic), pix = prow - g * npix;
     const int py = fast_div(pix, P.pw_magic), px = pix - py * P.pw;
-    const int iy = H.uinfo[4 * g + 2] * P.s - P.p + py, ix = H.uinfo[4 * g + 3] * P.s - P.p + px;
+    const int iy = H.uinfo[4 * g + 2] * P.s - P.p + py, ix = H.uinfo[4 * g + 3] * P.s - P.px + px;
     if (!H.uinfo[4 * g] || iy < 0 || iy >= P.Hin || ix < 0 || ix >= P.Win) return kOob;
     return (uint32_t)(((H.uinfo[4 * g + 1] * P.Hin + iy) * P.Win + ix) * P.Cin) * ES;
 }

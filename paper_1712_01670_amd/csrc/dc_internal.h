@@ -62,6 +62,21 @@ void plan_stream(const dc_rect* rects, int n, int dx, int dy, int stream, int Ho
                  int th, int tw, LayerPlan& plan);
 
 // ---- kernel launchers -----------------------------------------------------------
+// Kernel rows / columns, paddings along y / x, distance between taps and the kernel's span in pixels, for a conv
+// layer (k2, p2, dil of dc_layer); any other windowed layer: k x k, p, 1.
+struct WindowGeom { int kh, kw, ph, pw, dil, eh, ew; };
+inline WindowGeom window_geom(const dc_layer& l) {
+    WindowGeom g{l.k, l.k, l.p, l.p, 1, l.k, l.k};
+    if (l.type == DC_CONV) {
+        if (l.k2 > 0) { g.kw = l.k2; g.pw = l.p2; }
+        if (l.dil > 1) g.dil = l.dil;
+        g.eh = (g.kh - 1) * g.dil + 1;
+        g.ew = (g.kw - 1) * g.dil + 1;
+    }
+    return g;
+}
+inline bool plain_square(const dc_layer& l) { return !(l.type == DC_CONV && (l.k2 > 0 || l.dil > 1)); }
+
 struct ConvLaunch {
     const void* in;
     const void* w;
@@ -69,6 +84,7 @@ struct ConvLaunch {
     const float* bias;
     void* out;
     int n_streams, Hin, Win, Cin, Hout, Wout, Cout, k, s, p, relu, dtype;
+    int kw = 0, pw = 0, dil = 1;      // kw > 0: k rows x kw columns, paddings p / pw; dil: distance between taps
     ConvTiling tiling;
     const TileDev* tiles;  // device; nullptr: every tile of every stream
     int n_tiles;           // ignored when tiles == nullptr; with n_tiles_dev the capacity of the list
@@ -158,7 +174,8 @@ constexpr int kPlanMaxTensors = 192;     // tensors of a stack the device tables
 constexpr int kPlanMaxRects = 256;       // rectangles per list (a longer list: the stream reuses nothing)
 constexpr int kPlanChunk = 256;          // units per workgroup of the mask / list kernels
 struct PlanLayerDev {                    // one layer; tensor i + 1 is its output
-    int32_t type, k, s, p, in0, in1, in2, in3, within, pad0, pad1, pad2;
+    int32_t type, k, s, p, in0, in1, in2, in3, within;
+    int32_t kw, pw, dil;                 // conv layers: kernel columns, their padding, distance between taps (k, p: rows)
 };
 struct PlanTensorDev { int32_t h, w, cum_stride, bm_off; };   // bm_off: first word of the tensor's bitmap (exact maps)
 struct PlanConvDev {                     // one conv layer's share of the plan area (offsets in bytes from its start)

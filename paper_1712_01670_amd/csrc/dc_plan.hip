@@ -242,9 +242,10 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
                 bool ok = ia < na;
                 const dc_rect r = ok ? la[ia] : dc_rect{0, 0, 0, 0};
                 SpanD xs{r.x, r.x + r.w}, ys{r.y, r.y + r.h};
-                if (windowed) {
-                    xs = ext ? windows_inside_ext(xs, L.k, L.s, L.p, ta.w) : windows_inside(xs, L.k, L.s, L.p);
-                    ys = ext ? windows_inside_ext(ys, L.k, L.s, L.p, ta.h) : windows_inside(ys, L.k, L.s, L.p);
+                if (windowed) {          // the kernel's span per axis (a conv kernel may be not square, or dilated)
+                    const int ew = (L.kw - 1) * L.dil + 1, eh = (L.k - 1) * L.dil + 1;
+                    xs = ext ? windows_inside_ext(xs, ew, L.s, L.pw, ta.w) : windows_inside(xs, ew, L.s, L.pw);
+                    ys = ext ? windows_inside_ext(ys, eh, L.s, L.p, ta.h) : windows_inside(ys, eh, L.s, L.p);
                 } else if (lrn_px) {
                     if (ext) {
                         xs = windows_inside_ext(xs, L.k, 1, radius, ta.w);
@@ -364,7 +365,11 @@ __device__ __forceinline__ void erode_stream(uint32_t* maps, const PlanLayerDev*
         const int wpr_in = (ta.w + 31) >> 5, wpr = (tt.w + 31) >> 5;
         const bool windowed = L.type == DC_CONV || L.type == DC_MAXPOOL || L.type == DC_AVGPOOL;
         const bool lrn_px = L.type == DC_LRN && L.within != 0;
-        const int k = (windowed || lrn_px) ? L.k : 1, s = windowed ? L.s : 1, p = windowed ? L.p : (lrn_px ? (L.k - 1) / 2 : 0);
+        // taps of the window: kh x kw, dil pixels apart, paddings ph / pw
+        const int kh = (windowed || lrn_px) ? L.k : 1, kw = windowed ? L.kw : (lrn_px ? L.k : 1), dil = windowed ? L.dil : 1;
+        const int s = windowed ? L.s : 1;
+        const int ph = windowed ? L.p : (lrn_px ? (L.k - 1) / 2 : 0), pw = windowed ? L.pw : (lrn_px ? (L.k - 1) / 2 : 0);
+        const int ew = (kw - 1) * dil + 1;
         const int col_lo = -dx < 0 ? 0 : -dx, col_hi = tt.w - dx < tt.w ? tt.w - dx : tt.w;
         for (int i = tid; i < tt.h * wpr; i += kErodeThreads) {
             const int y = i / wpr, x0 = (i - y * wpr) * 32;
@@ -377,16 +382,16 @@ __device__ __forceinline__ void erode_stream(uint32_t* maps, const PlanLayerDev*
                 bits = in[i] & maps[s_tensors[L.in1].bm_off + i];
                 if (L.in2 >= 0) bits &= maps[s_tensors[L.in2].bm_off + i];
                 if (L.in2 >= 0 && L.in3 >= 0) bits &= maps[s_tensors[L.in3].bm_off + i];
-            } else if (k == 1 && s == 1 && p == 0) {
+            } else if (kh == 1 && kw == 1 && s == 1 && ph == 0 && pw == 0) {
                 bits = in[i];
-            } else if (s <= 2 && k <= 32) {
+            } else if (s <= 2 && ew <= 32) {
                 // bit b of acc: the whole window that starts at input column c0 + b.  Stride 1 needs 32 + k - 1 input
                 // columns from c0 (three words), stride 2 needs 64 + k - 1 (four).
                 unsigned long long acc = ~0ull;
-                const int c0 = x0 * s - p;
+                const int c0 = x0 * s - pw;
                 const int w0 = c0 >> 5, sh = c0 & 31;           // arithmetic shift: floor for negative starts
-                for (int ky = 0; ky < k; ++ky) {
-                    const int iy = y * s - p + ky;
+                for (int ky = 0; ky < kh; ++ky) {
+                    const int iy = y * s - ph + ky * dil;
                     const bool row_in = iy >= 0 && iy < ta.h;
                     if (!row_in && ext) continue;               // taps in the padding are ignored
                     const uint32_t* row = row_in ? in + (size_t)iy * wpr_in : nullptr;
@@ -397,18 +402,18 @@ __device__ __forceinline__ void erode_stream(uint32_t* maps, const PlanLayerDev*
                     const unsigned long long lo = sh ? (a >> sh) | (b << (64 - sh)) : a;    // columns c0 .. c0 + 63
                     const unsigned long long hi = b >> sh;                                  // columns c0 + 64 .. (at least 33 of them)
                     unsigned long long r = lo;
-                    for (int kx = 1; kx < k; ++kx) r &= (lo >> kx) | (hi << (64 - kx));
+                    for (int kx = 1; kx < kw; ++kx) r &= (lo >> (kx * dil)) | (hi << (64 - kx * dil));
                     acc &= r;
                 }
                 bits = s == 1 ? (unsigned)acc : even_bits(acc);
-            } else if (s <= 8 && k <= 32) {
+            } else if (s <= 8 && ew <= 32) {
                 // larger strides: the same AND of shifted rows for all 32 s start columns of the word (up to four
                 // 64-column pieces), then every s-th bit is kept
                 unsigned long long acc[4] = {~0ull, ~0ull, ~0ull, ~0ull};
-                const int c0 = x0 * s - p;
+                const int c0 = x0 * s - pw;
                 const int pieces = (32 * s + 63) >> 6;
-                for (int ky = 0; ky < k; ++ky) {
-                    const int iy = y * s - p + ky;
+                for (int ky = 0; ky < kh; ++ky) {
+                    const int iy = y * s - ph + ky * dil;
                     const bool row_in = iy >= 0 && iy < ta.h;
                     if (!row_in && ext) continue;
                     const uint32_t* row = row_in ? in + (size_t)iy * wpr_in : nullptr;
@@ -423,7 +428,7 @@ __device__ __forceinline__ void erode_stream(uint32_t* maps, const PlanLayerDev*
                         const unsigned long long lo = sh ? (a >> sh) | (b << (64 - sh)) : a;
                         const unsigned long long hi = sh ? (b >> sh) | ((unsigned long long)v[4] << (64 - sh)) : b;
                         unsigned long long r = lo;
-                        for (int kx = 1; kx < k; ++kx) r &= (lo >> kx) | (hi << (64 - kx));
+                        for (int kx = 1; kx < kw; ++kx) r &= (lo >> (kx * dil)) | (hi << (64 - kx * dil));
                         acc[j] &= r;
                     }
                 }
@@ -437,9 +442,9 @@ __device__ __forceinline__ void erode_stream(uint32_t* maps, const PlanLayerDev*
                 bits = 0;
                 for (int b = 0; b < 32 && x0 + b < tt.w; ++b) {
                     bool ok = true;
-                    for (int ky = 0; ky < k && ok; ++ky)
-                        for (int kx = 0; kx < k && ok; ++kx) {
-                            const int iy = y * s - p + ky, ix = (x0 + b) * s - p + kx;
+                    for (int ky = 0; ky < kh && ok; ++ky)
+                        for (int kx = 0; kx < kw && ok; ++kx) {
+                            const int iy = y * s - ph + ky * dil, ix = (x0 + b) * s - pw + kx * dil;
                             if (iy < 0 || iy >= ta.h || ix < 0 || ix >= ta.w) { ok = ext; continue; }
                             ok = (in[(size_t)iy * wpr_in + (ix >> 5)] >> (ix & 31)) & 1u;
                         }

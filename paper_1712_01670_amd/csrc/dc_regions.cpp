@@ -100,15 +100,19 @@ int validate_layers(const dc_layer* L, int n_layers, int H, int W, int C, std::v
             case DC_CONV:
             case DC_MAXPOOL:
             case DC_AVGPOOL:
-                if (l.k < 1 || l.s < 1 || l.p < 0 || l.p >= l.k) return DC_ERR_INVALID_ARG;
-                if (l.type == DC_CONV && (l.relu < 0 || l.relu > 2)) return DC_ERR_INVALID_ARG;
+            {
+                const WindowGeom g = window_geom(l);
+                if (g.kh < 1 || g.kw < 1 || l.s < 1 || g.ph < 0 || g.pw < 0 || g.ph >= g.eh || g.pw >= g.ew) return DC_ERR_INVALID_ARG;
+                if (l.type == DC_CONV && (l.relu < 0 || l.relu > 2 || l.k2 < 0 || l.dil < 0 || l.dil > 64 || g.kh > 64 || g.kw > 64))
+                    return DC_ERR_INVALID_ARG;
                 if (l.cin != c[a] || l.cout < 1) return DC_ERR_BAD_SHAPE;
                 if (l.type != DC_CONV && l.cout != l.cin) return DC_ERR_BAD_SHAPE;
-                if (h[a] + 2 * l.p < l.k || w[a] + 2 * l.p < l.k) return DC_ERR_BAD_SHAPE;
-                h[i + 1] = (h[a] + 2 * l.p - l.k) / l.s + 1;
-                w[i + 1] = (w[a] + 2 * l.p - l.k) / l.s + 1;
+                if (h[a] + 2 * g.ph < g.eh || w[a] + 2 * g.pw < g.ew) return DC_ERR_BAD_SHAPE;
+                h[i + 1] = (h[a] + 2 * g.ph - g.eh) / l.s + 1;
+                w[i + 1] = (w[a] + 2 * g.pw - g.ew) / l.s + 1;
                 c[i + 1] = l.cout;
                 break;
+            }
             case DC_ADD:
                 if (l.in1 < 0 || l.in1 > i) return DC_ERR_BAD_SHAPE;
                 if (h[a] != h[l.in1] || w[a] != w[l.in1] || c[a] != c[l.in1] || l.cin != c[a] ||
@@ -163,8 +167,9 @@ int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<d
         const TensorRegions& a = out[l.in0];
         TensorRegions& t = out[i + 1];
         const bool windowed = (l.type == DC_CONV || l.type == DC_MAXPOOL || l.type == DC_AVGPOOL);
-        t.h = windowed ? (a.h + 2 * l.p - l.k) / l.s + 1 : (l.type == DC_FC ? 1 : a.h);
-        t.w = windowed ? (a.w + 2 * l.p - l.k) / l.s + 1 : (l.type == DC_FC ? 1 : a.w);
+        const WindowGeom wg = window_geom(l);       // a conv kernel may span another extent per axis
+        t.h = windowed ? (a.h + 2 * wg.ph - wg.eh) / l.s + 1 : (l.type == DC_FC ? 1 : a.h);
+        t.w = windowed ? (a.w + 2 * wg.pw - wg.ew) / l.s + 1 : (l.type == DC_FC ? 1 : a.w);
         t.cum_stride = windowed ? a.cum_stride * l.s : a.cum_stride;
         t.dx = round_half_away(mx, t.cum_stride);
         t.dy = round_half_away(my, t.cum_stride);
@@ -204,8 +209,8 @@ int propagate(const dc_layer* L, int n_layers, int H, int W, const std::vector<d
             for (const auto& r : acc) push_clipped(t.rects, r.first, r.second, t);
         } else if (windowed) {
             for (const dc_rect& r : a.rects) {
-                Span xs = ext ? window_span_ext(Span{r.x, r.x + r.w}, l.k, l.s, l.p, a.w) : window_span(Span{r.x, r.x + r.w}, l.k, l.s, l.p);
-                Span ys = ext ? window_span_ext(Span{r.y, r.y + r.h}, l.k, l.s, l.p, a.h) : window_span(Span{r.y, r.y + r.h}, l.k, l.s, l.p);
+                Span xs = ext ? window_span_ext(Span{r.x, r.x + r.w}, wg.ew, l.s, wg.pw, a.w) : window_span(Span{r.x, r.x + r.w}, wg.ew, l.s, wg.pw);
+                Span ys = ext ? window_span_ext(Span{r.y, r.y + r.h}, wg.eh, l.s, wg.ph, a.h) : window_span(Span{r.y, r.y + r.h}, wg.eh, l.s, wg.ph);
                 if (xs.empty() || ys.empty()) continue;
                 push_clipped(t.rects, xs, ys, t);
             }

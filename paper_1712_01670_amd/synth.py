@@ -18,7 +18,8 @@ import numpy as np
 CONV, MAXPOOL, RELU, ADD, LRN, CONCAT, FC, SOFTMAX, AVGPOOL = 0, 1, 2, 3, 4, 5, 6, 7, 8
 
 # fields a layer's dict may leave out
-LAYER_DEFAULTS = dict(k=1, s=1, p=0, relu=0, in1=-1, in2=-1, in3=-1, within=0, alpha=0.0, beta=0.0, kappa=1.0)
+LAYER_DEFAULTS = dict(k=1, s=1, p=0, relu=0, in1=-1, in2=-1, in3=-1, within=0, alpha=0.0, beta=0.0, kappa=1.0,
+                      k2=0, p2=0, dil=1)
 
 
 # --------------------------------------------------------------------------- #

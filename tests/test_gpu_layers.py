@@ -522,3 +522,50 @@ def test_general_kernel_short_stages(oracle, case, bf16, cached):
         else:
             want = oracle.conv_cached(x[i], w, b, k, s, p, True, bf16=bf16)
         assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
+
+
+KERNEL_SHAPE_CASES = [
+    # H, W, cin, cout, kh, kw, s, ph, pw, dil
+    (23, 31, 16, 32, 1, 7, 1, 0, 3, 1),      # a row kernel
+    (23, 31, 16, 32, 7, 1, 1, 3, 0, 1),      # a column kernel
+    (26, 30, 32, 64, 3, 3, 1, 2, 2, 2),      # dilated by 2, same size
+    (33, 29, 32, 32, 3, 1, 2, 1, 0, 1),      # column kernel with stride 2
+    (24, 28, 16, 48, 5, 3, 1, 4, 2, 2),      # not square and dilated
+    (19, 21, 5, 7, 2, 5, 3, 0, 1, 1),        # odd channel counts (element loads), stride 3
+    (30, 30, 8, 16, 3, 3, 1, 3, 3, 3),       # dilated by 3
+]
+
+
+@pytest.mark.parametrize("cached", [False, True])
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("case", KERNEL_SHAPE_CASES)
+def test_kernels_that_are_not_square_or_dilated(oracle, case, bf16, cached):
+    """dc_layer.k2 / p2 / dil: the general conv kernels with a kernel of k rows x k2 columns and taps dil pixels apart."""
+    H, W, cin, cout, kh, kw, s, ph, pw, dil = case
+    print(f"[kernel shapes] case={case} bf16={bf16} cached={cached}", flush=True)
+    rng = np.random.default_rng(sum(case))
+    n = 2
+    x = rng.standard_normal((n, H, W, cin)).astype(np.float32)
+    w = (rng.standard_normal((cout, kh, kw, cin)) * np.sqrt(2.0 / (cin * kh * kw))).astype(np.float32)
+    b = (rng.standard_normal(cout) * 0.1).astype(np.float32)
+    layer = dict(type=synth.CONV, k=kh, s=s, p=ph, cin=cin, cout=cout, relu=1, in0=0, in1=-1, k2=kw, p2=pw, dil=dil)
+    Ho, Wo, _ = synth.tensor_shapes([layer], H, W, cin)[1]
+    cache = rng.standard_normal((n, Ho, Wo, cout)).astype(np.float32)
+    if bf16:
+        x, w, cache = oracle.round_bf16(x), oracle.round_bf16(w), oracle.round_bf16(cache)
+    regions = None
+    if cached:
+        regions = [(np.array([[1, 2, Wo - 4, Ho - 5]], np.int32), (1, -1)), (np.array([[0, 0, Wo - 2, Ho - 1]], np.int32), (1, 0))]
+    got = _to_np(binding.dc_cached_conv_layer(layer, _to_dev(x, bf16), _to_dev(w, bf16), torch.from_numpy(b).to(DEV),
+                                              cache_prev=_to_dev(cache, bf16) if cached else None, regions=regions))
+    assert got.shape == (n, Ho, Wo, cout)
+    for i in range(n):
+        if cached:
+            mask = oracle.rasterize(regions[i][0], Ho, Wo)
+            want = oracle.conv_cached(x[i], w, b, kh, s, ph, True, cache_prev=cache[i], mask=mask, dxy=regions[i][1], bf16=bf16,
+                                      k2=kw, p2=pw, dil=dil)
+            m = mask.astype(bool)
+            assert np.array_equal(got[i][m], want[m])
+        else:
+            want = oracle.conv_cached(x[i], w, b, kh, s, ph, True, bf16=bf16, k2=kw, p2=pw, dil=dil)
+        assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)

@@ -59,6 +59,7 @@ def test_model_stacks(oracle):
     _check(oracle, synth.alexnet(n_classes=40, width=0.25), 227, 227, 3, 10, 3, 23, density=0.9, max_motion=12)
     _check(oracle, synth.darknet19(), 416, 416, 3, 16, 2, 24, density=0.9, max_motion=16)
     _check(oracle, synth.dave_orig(), 66, 200, 3, 10, 3, 25, density=0.9)
+    _check(oracle, synth.factorised_net(8), 96, 128, 3, 8, 4, 26, density=0.9)      # kernels that are not square, dilation
 
 
 def test_large_frame_maps_built_in_the_workspace(oracle):

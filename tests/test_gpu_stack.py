@@ -98,7 +98,8 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
                                   int(sum(int(r[2]) * int(r[3]) for r in want["rects"][li + 1])))
                         if no_reuse is not None and no_reuse[li]:
                             reused = 0
-                        needed += (ho * wo - reused) * L["k"] * L["k"] * runner.layers[li]["cin"] * L["cout"]
+                        kh, kw = synth.conv_geometry(L)[:2]
+                        needed += (ho * wo - reused) * kh * kw * runner.layers[li]["cin"] * L["cout"]
             for ti in (check_tensors or range(len(layers) + 1)):
                 g = got[ti][s]
                 if ti == 0:          # tensor 0 may carry zero padding channels
@@ -483,6 +484,19 @@ def test_conv_layers_that_do_not_use_the_cache(oracle, exact):
     v = synth.panning_video(3000, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32)[None]
     _run_both(oracle, layers, v, 16, 16, True, bias_scale=0.0, residual_scale=0.5, exact_masks=exact,
               no_reuse=synth.no_reuse_flags(layers, 600))
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_stack_with_kernels_that_are_not_square_or_dilated(oracle, bf16):
+    """1 x 7 / 7 x 1 pairs, dilated 3 x 3 and 5 x 3 kernels (dc_layer.k2 / p2 / dil) through the whole path: regions,
+    exact maps, copies and the general conv kernels, planned on the host and on the GPU."""
+    layers = synth.factorised_net(16)
+    video = np.stack([synth.panning_video(900 + s, n_frames=3, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
+    runner, reuse = _run_both(oracle, layers, video, 8, 8, bf16)
+    assert max(reuse) > 0.3
+    _run_both(oracle, layers, video, 8, 8, bf16, exact_masks=True)
+    f1, f2 = synth.tiny_pair(0)
+    _run_both(oracle, layers, np.stack([f1, f2, f2])[None], 8, 8, bf16, extend_borders=True)
 
 
 def test_border_case_planned_on_the_gpu(oracle):
