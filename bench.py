@@ -68,7 +68,7 @@ def traffic_calib():
     print(json.dumps({"traffic_calib": "device copy", "bytes_read": n, "bytes_written": n, "launches": 5}))
 
 
-def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exact_masks=None):
+def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exact_masks=None, torus=None):
     import numpy as np
     import torch
     from paper_1712_01670_amd import binding, synth
@@ -84,12 +84,17 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
     dt = binding.DC_BF16 if dtype == "bf16" else binding.DC_F32
     method = binding.DC_MATCH_DIAMOND if args.matcher == "ds" else binding.DC_MATCH_EXHAUSTIVE
     exact = (args.regions == "exact" if exact_masks is None else exact_masks) and not args.host_plan
-    runner = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
-                                 match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan,
-                                 exact_masks=exact, cache_pool_add=exact and args.cache_pool_add,
-                                 no_reuse=synth.no_reuse_flags(layers, args.min_reuse_macs) if args.min_reuse_macs > 0 else None)
+    torus = args.torus if torus is None else torus
 
-    def run_steps(k, start, collect=None, force_full=False):
+    def make_runner(on_torus):
+        return binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
+                                   match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan,
+                                   exact_masks=exact, cache_pool_add=exact and args.cache_pool_add,
+                                   no_reuse=synth.no_reuse_flags(layers, args.min_reuse_macs) if args.min_reuse_macs > 0 else None,
+                                   torus=on_torus)
+    runner = make_runner(torus)
+
+    def run_steps(k, start, collect=None, force_full=False, runner=runner):
         """Run k steps through the cyclic video starting at global step `start`."""
         for i in range(start, start + k):
             f = i % n_frames
@@ -117,15 +122,20 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
     fps = steps * n / elapsed
 
     # ---- every frame in full (no cache): same number of steps, same repeats ----
-    run_steps(min(warmup, 5), 0, force_full=True)
+    # A stack that computes every frame in full has no reason to keep one buffer per tensor: it alternates two, so
+    # that a layer of the next frame only waits for the same layer of this one.  The baseline gets that arrangement.
+    full_runner = make_runner(False) if torus else runner
+    run_steps(min(warmup, 5), 0, force_full=True, runner=full_runner)
     times_full = []
     for _ in range(repeats):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        run_steps(steps, 0, force_full=True)
+        run_steps(steps, 0, force_full=True, runner=full_runner)
         torch.cuda.synchronize()
         times_full.append(time.perf_counter() - t0)
     fps_full = steps * n / statistics.median(times_full)
+    if full_runner is not runner:
+        del full_runner
 
     out = {"value": fps, "ms_per_step": elapsed / steps * 1e3, "repeat_ms_per_step": [t / steps * 1e3 for t in times],
            "no_cache": {"value": fps_full, "unit": "frames/s", "steps": steps, "repeats": repeats,
@@ -201,6 +211,9 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
                  "frac": (copy["bytes"] / (copy["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS) if copy["ms"] else None,
                  "avg_launch_us": (copy["ms"] / copy["launches"] * 1e3) if copy["launches"] else None},
     }
+    if not copy["launches"]:
+        roofline["copy"]["note"] = ("nothing is copied: every conv output stays in one buffer and its origin moves "
+                                    "(see shifted_copies for the same workload with the copies)")
 
     if dtype == "bf16":     # what the matrix cores sustain on this GPU under its power limit, measured now
         regs, lds = binding.dc_probe_mfma_rate(0), binding.dc_probe_mfma_rate(1)
@@ -295,6 +308,9 @@ def main():
                          "the rectangles of Step 5 propagated by Table 2 as the paper prints it")
     ap.add_argument("--cache-pool-add", action="store_true",
                     help="with exact maps: max-pooling layers take their outputs from the cache too (Section 5)")
+    ap.add_argument("--copies", action="store_true",
+                    help="reuse by shifted copies into a second buffer per tensor; the default keeps every conv "
+                         "output in one buffer addressed from a moving origin (a torus), so that nothing is copied")
     ap.add_argument("--min-reuse-macs", type=int, default=0,
                     help="conv layers with fewer multiply-adds per output element (k*k*cin) are computed in full on every "
                          "frame instead of using the cache (0: every conv layer uses the cache, as in the paper)")
@@ -303,6 +319,7 @@ def main():
     ap.add_argument("--cpu-frames", type=int, default=30)
     ap.add_argument("--traffic-calib", action="store_true")
     args = ap.parse_args()
+    args.torus = not args.copies and not args.host_plan
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (streams are independent and would shard "
               "across GPUs without communication); run with --gpus 1", file=sys.stderr)
@@ -337,7 +354,7 @@ def main():
                                        else "rectangles (Table 2 as printed)",
                    "cached_layers": "conv, max-pooling, add" if (args.cache_pool_add and args.regions == "exact" and not args.host_plan)
                                     else "conv",
-                   "min_reuse_macs": args.min_reuse_macs,
+                   "min_reuse_macs": args.min_reuse_macs, "reuse_by": "moving origins (conv outputs on a torus, no copies)" if args.torus else "shifted copies",
                    "lookahead_frames": 1 if args.lookahead else 0, **detail},
     }
     out.update(main_rec)
@@ -348,6 +365,11 @@ def main():
         rect = run_workload(args, n, args.dtype, args.steps, args.warmup, args.repeats, False, 0, exact_masks=False)
         rect["config"] = {"reusable_regions": "rectangles (Table 2 as printed)", "streams": n, "steps": args.steps}
         out["rectangles"] = rect
+    if args.torus and not args.no_single:
+        # the same workload with reuse by shifted copies into a second buffer per tensor: frames/s and saving only
+        cp = run_workload(args, n, args.dtype, args.steps, args.warmup, args.repeats, False, 0, torus=False)
+        cp["config"] = {"reuse_by": "shifted copies", "streams": n, "steps": args.steps}
+        out["shifted_copies"] = cp
     print(json.dumps(out))
 
 

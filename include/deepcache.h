@@ -126,6 +126,19 @@ typedef struct {
                               still reuse from their own caches.  Section 5 restricts the cache to the layer type where
                               it pays; this carries that choice down to single layers (on this GPU a 1x1 layer or a
                               layer with few input channels costs less to compute than to copy). */
+    int32_t torus;         /* dc_run_stack only, with device_plan.  1: the conv outputs are kept on a torus and never copied.
+                              Every conv output is ONE buffer for all frames (tensors_prev[t] == tensors_cur[t]); pixel
+                              (x, y) of stream s lies at ((x + ox) mod w, (y + oy) mod h) of it, and the origin (ox, oy)
+                              moves with every cached frame by the tensor's offset (dx, dy), so that a reusable pixel
+                              already lies where this frame looks for it: a cached frame writes its non-reusable
+                              pixels only (Section 5 "Reuse" without step 1).  A full frame writes every tensor at
+                              its buffer's start (origins (0, 0)).  The values are those of the copying path.  Only
+                              stacks whose conv layers are 3x3 / stride 1 with whole 64-byte channel rows (or a
+                              first layer on a 16-byte pixel vector) and whose conv outputs are read by such layers or by
+                              2x2 / stride-2 max-pooling qualify (DC_ERR_UNSUPPORTED otherwise); every other tensor
+                              is stored as always. */
+    int32_t* origins_out;  /* optional with torus: host [n_streams][n_layers + 1][2], receives (ox, oy) of every tensor
+                              after a cached frame (for inspection: the call then waits for the planning) */
     int32_t device_plan;   /* dc_run_stack only.  0: the call waits for the matching, then merges, propagates and lists
                               the dirty units on the host.  1: three small kernels do that on the GPU from the block
                               mask in device memory (Section 4 Step 5, Section 5 "Propagation": the same rules, the

@@ -52,7 +52,8 @@ class Regions(C.Structure):
 
 class MatchOptions(C.Structure):
     _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32), ("extend_borders", C.c_int32), ("exact_masks", C.c_int32),
-                ("cache_pool_add", C.c_int32), ("no_reuse", C.c_void_p), ("device_plan", C.c_int32)]
+                ("cache_pool_add", C.c_int32), ("no_reuse", C.c_void_p), ("torus", C.c_int32), ("origins_out", C.c_void_p),
+                ("device_plan", C.c_int32)]
 
 
 DC_MATCH_EXHAUSTIVE, DC_MATCH_DIAMOND = 0, 1
@@ -457,7 +458,7 @@ class StackRunner:
                  max_block_ssd=None, dtype=DC_F32, expiry=0, max_rects=1024, device="cuda:0",
                  want_regions=False, pad_input=True, overlap=True, pipeline=True, pack_weights=True,
                  match_method=DC_MATCH_EXHAUSTIVE, k_skip=1, in_place=False, extend_borders=False, device_plan=False,
-                 exact_masks=False, cache_pool_add=False, no_reuse=None):
+                 exact_masks=False, cache_pool_add=False, no_reuse=None, torus=False, want_origins=False):
         self.device_plan = bool(device_plan) and not in_place
         self.in_place = bool(in_place)
         self.last_in_place = False
@@ -474,9 +475,15 @@ class StackRunner:
         # no_reuse: per layer, non-zero = that conv layer is computed in full on every frame (host array kept alive here)
         self._no_reuse = None if no_reuse is None else np.ascontiguousarray(no_reuse, np.uint8)
         assert self._no_reuse is None or self._no_reuse.shape == (len(layers),)
+        # torus: the conv outputs are one buffer each, addressed from an origin that moves with every cached frame; nothing
+        # is copied.  origins [n][tensor][2] = (ox, oy) is filled after every step when want_origins (the call then waits
+        # for the planning): logical_tensors() needs it.
+        self.torus = bool(torus) and self.device_plan
+        self.origins = np.zeros((n_streams, len(layers) + 1, 2), np.int32) if (self.torus and want_origins) else None
         self.match_options = MatchOptions(int(match_method), int(k_skip), int(extend_borders), int(self.exact_masks),
                                           int(self.cache_pool_add),
-                                          None if self._no_reuse is None else self._no_reuse.ctypes.data, int(self.device_plan))
+                                          None if self._no_reuse is None else self._no_reuse.ctypes.data, int(self.torus),
+                                          None if self.origins is None else self.origins.ctypes.data, int(self.device_plan))
         self.device = torch.device(device)
         td = torch_dtype(dtype)
         self.Lc = layers_to_c(layers)
@@ -498,7 +505,7 @@ class StackRunner:
         self.bufs = [[], []]
         for t, (h, w, c) in enumerate(self.shapes):
             a = torch.empty((n_streams, h, w, c), dtype=td, device=self.device)
-            b = torch.empty_like(a) if (is_conv[t] or both) else a
+            b = a if (self.torus and is_conv[t]) else (torch.empty_like(a) if (is_conv[t] or both) else a)
             self.bufs[0].append(a)
             self.bufs[1].append(b)
         # pointer tables [set of the conv outputs][set of the other tensors]: the two only differ after in-place frames
@@ -574,6 +581,8 @@ class StackRunner:
             C.byref(self._in_place_flag) if self.in_place else None, _ptr(self.mv), _ptr(self.best_ssd), _ptr(self.gmv), _ptr(self.n_pass),
             _ptr(self.mask), self.max_rects, self.regs, _ptr(self.ws_dev), self.ws_dev.numel(),
             C.c_void_p(self.ws_host.data_ptr()), self.ws_host.numel(), C.byref(self.stats), self.overlap, _stream()))
+        if full and self.origins is not None:
+            self.origins[:] = 0          # a full frame writes every tensor at its buffer's start
         self.age = 1 if full else self.age + 1
         self.have_prev = True
         self.prev_frames = frames
@@ -592,6 +601,21 @@ class StackRunner:
         if self.last_in_place:
             return [self.bufs[p if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]
         return [self.bufs[c if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]
+
+    def logical_tensors(self, tensors):
+        """With torus: the tensors of the last step in their logical layout (copies; needs want_origins and a synchronised
+        stream).  Pixel (x, y) of stream s of a conv output lies at ((x + ox) mod w, (y + oy) mod h) of its buffer."""
+        if not self.torus:
+            return tensors
+        assert self.origins is not None
+        out = []
+        for t, x in enumerate(tensors):
+            if not self._is_conv_out[t] or not self.origins[:, t].any():
+                out.append(x)
+                continue
+            out.append(torch.stack([torch.roll(x[s], shifts=(-int(self.origins[s, t, 1]), -int(self.origins[s, t, 0])), dims=(0, 1))
+                                    for s in range(self.n)]))
+        return out
 
     def read_stats(self):
         """Work counters of the last step (call after the stream has been synchronised): a frame planned on the GPU

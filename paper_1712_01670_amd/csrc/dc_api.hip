@@ -157,7 +157,8 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
                      Profile* prof = nullptr, int gemm_slot = -1, int copy_slot = -1, int* kernel_id = nullptr,
                      bool copy_done = false, void* scratch = nullptr, size_t scratch_bytes = 0,
                      const void* w_packed = nullptr, const TileDev* dev_tiles = nullptr, int dev_capacity = 0,
-                     const int* dev_count = nullptr, long dev_hint = -1) {
+                     const int* dev_count = nullptr, long dev_hint = -1, const int32_t* in_origin = nullptr,
+                     const int32_t* out_origin = nullptr, int origin_stride = 0) {
     const WindowGeom wg = window_geom(l);
     const int Hout = (Hin + 2 * wg.ph - wg.eh) / l.s + 1, Wout = (Win + 2 * wg.pw - wg.ew) / l.s + 1;
     ConvLaunch c;
@@ -169,6 +170,7 @@ int run_conv_planned(const dc_layer& l, const void* in, const void* w, const flo
     if (!plain_square(l)) { c.kw = wg.kw; c.pw = wg.pw; c.dil = wg.dil; }
     c.dtype = dtype; c.tiling = tiling;
     c.scratch = scratch; c.scratch_bytes = scratch_bytes;
+    c.in_origin = in_origin; c.out_origin = out_origin; c.origin_stride = origin_stride;
     if (dev_tiles) {      // a list the planning kernels built: its length is in device memory, the copies are done
         c.tiles = dev_tiles; c.n_tiles = dev_capacity; c.n_tiles_dev = dev_count; c.n_tiles_hint = dev_hint;
         c.rects = nullptr; c.ranges = nullptr;
@@ -208,6 +210,8 @@ struct DevHostHeader {                          // host-only bookkeeping of the 
     const void* ws_dev;
     int32_t n_layers, n_convs, last_slot, n_blocks;
     int64_t macs_full;
+    int32_t origin_area;                        // torus frames: the plan area that holds the previous frame's origins (-1: none)
+    int32_t torus;                              // 1: the last frame planned here copied nothing
     DevHostConv conv[kPlanMaxConvs];
 };
 static_assert(sizeof(DevHostHeader) <= kDevHostSlot, "header fits its slot");
@@ -219,7 +223,7 @@ struct DevPlanLayout {
     std::vector<PlanConvDev> convs;
     std::vector<int> conv_layer;                // layer index of every conv
     size_t table_bytes = 0, off_tensors = 0, off_convs = 0;
-    size_t frame_bytes = 0, off_nrect = 0, off_dxy = 0, off_info = 0, off_nunits = 0, off_stats = 0, off_area = 0;
+    size_t frame_bytes = 0, off_nrect = 0, off_dxy = 0, off_origin = 0, off_info = 0, off_nunits = 0, off_stats = 0, off_area = 0;
     size_t off_bitmaps = 0;
     int64_t bm_words = 0;                       // words of all bitmaps of one stream (exact reuse maps)
     int cap = 0, max_chunks = 0;
@@ -262,6 +266,7 @@ void device_plan_layout(const dc_layer* L, int n_layers, const std::vector<int>&
     size_t off = align_up((size_t)n_streams * nt * d.cap * sizeof(dc_rect), 256);
     d.off_nrect = off; off += align_up((size_t)n_streams * nt * sizeof(int32_t), 256);
     d.off_dxy = off; off += align_up((size_t)n_streams * nt * 2 * sizeof(int32_t), 256);
+    d.off_origin = off; off += align_up((size_t)n_streams * nt * 2 * sizeof(int32_t), 256);
     d.off_info = off; off += align_up((size_t)n_streams * 2 * sizeof(int32_t), 256);
     d.off_nunits = off; off += align_up(d.conv_layer.size() * sizeof(int32_t), 256);
     d.off_stats = off; off += kDevHostSlot;
@@ -486,7 +491,7 @@ int32_t dc_conv_tuning(int32_t arrangement, int32_t units_per_workgroup, int32_t
 
 int32_t dc_conv_kernel_name(int32_t kernel_id, char* buf, size_t n) {
     if (!buf) return DC_ERR_NULL_PTR;
-    if (n < 2 || kernel_id < 0 || kernel_id > 129) return DC_ERR_INVALID_ARG;
+    if (n < 2 || kernel_id < 0 || kernel_id > 130) return DC_ERR_INVALID_ARG;
     conv_kernel_name(kernel_id, buf, n);
     return DC_OK;
 }
@@ -989,14 +994,15 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         if (match_options->k_skip < 1) return DC_ERR_INVALID_ARG;
         if (match_options->exact_masks && (!match_options->device_plan || in_place)) return DC_ERR_UNSUPPORTED;   // planned on the GPU only
         if (match_options->cache_pool_add && !match_options->exact_masks) return DC_ERR_UNSUPPORTED;
+        if (match_options->torus && (!match_options->device_plan || in_place || match_options->cache_pool_add)) return DC_ERR_UNSUPPORTED;
     }
     if (cached) {
         if (!frames_prev || !tensors_prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask || !ws_dev || !ws_host)
             return DC_ERR_NULL_PTR;
         if (block > H || block > W) return DC_ERR_BAD_SHAPE;
         for (int i = 0; i < n_layers; ++i)
-            if (layers[i].type == DC_CONV && (!tensors_prev[i + 1] || tensors_prev[i + 1] == tensors_cur[i + 1]))
-                return DC_ERR_NULL_PTR;
+            if (layers[i].type == DC_CONV && (!tensors_prev[i + 1] || (tensors_prev[i + 1] == tensors_cur[i + 1]) != (match_options && match_options->torus)))
+                return DC_ERR_NULL_PTR;     // two buffers per conv output, or the one buffer of a torus
         size_t need_dev = 0, need_host = 0;
         rc = dc_stack_workspace_bytes(layers, n_layers, n_streams, H, W, C, block, max_rects, &need_dev, &need_host);
         if (rc) return rc;
@@ -1007,6 +1013,34 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             if (regions_out[i].capacity < max_rects || !regions_out[i].rects) return DC_ERR_CAPACITY;
     // max-pooling and add layers that use the cache: their outputs are cache values like the conv outputs
     const uint8_t* const no_reuse = match_options ? match_options->no_reuse : nullptr;
+    // Conv outputs on a torus: single-buffered, never copied (see dc_match_options.torus).  Only the layers whose kernels
+    // address a torus may touch a conv output.
+    const bool torus = match_options && match_options->torus;
+    if (torus) {
+        const size_t esz = dtype_size(dtype);
+        auto conv_output = [&](int t) { return t > 0 && layers[t - 1].type == DC_CONV; };
+        for (int i = 0; i < n_layers; ++i) {
+            const dc_layer& l = layers[i];
+            const int t = i + 1;
+            if (l.type == DC_CONV) {
+                const bool first = l.in0 == 0 && cs[0] * esz == 16 && l.cout % 16 == 0 &&
+                                   ((l.k == 3 && l.s == 1) || (l.k == 7 && l.s == 2) || (l.k == 11 && l.s == 4));
+                const bool gemm3 = l.k == 3 && l.s == 1 && l.cout % 64 == 0 && (l.cin * esz) % 64 == 0;
+                if (!plain_square(l) || !(first || gemm3)) return DC_ERR_UNSUPPORTED;
+                if (!tensors_prev || tensors_prev[t] != tensors_cur[t]) return DC_ERR_INVALID_ARG;     // one buffer per conv output
+            } else if (l.type == DC_MAXPOOL) {
+                if (conv_output(l.in0) && !(l.k == 2 && l.s == 2 && l.p == 0 && (cs[l.in0] * esz) % 16 == 0 &&
+                                            (size_t)n_streams * hs[t] <= 65535))
+                    return DC_ERR_UNSUPPORTED;
+            } else {
+                int ids[4] = {l.in0, l.type == DC_ADD ? l.in1 : -1, -1, -1};
+                int m = l.type == DC_ADD ? 2 : 1;
+                if (l.type == DC_CONCAT) m = concat_inputs(l, ids);
+                for (int j = 0; j < m; ++j)
+                    if (conv_output(ids[j])) return DC_ERR_UNSUPPORTED;
+            }
+        }
+    }
     const bool cache_other = cached && match_options && match_options->cache_pool_add && match_options->exact_masks;
     auto uses_cache = [&](int i) { return cache_other && (layers[i].type == DC_MAXPOOL || layers[i].type == DC_ADD); };
     if (cache_other)
@@ -1072,7 +1106,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         for (int i = 0; i < n_layers; ++i) {
             if (layers[i].type == DC_CONV) is_target[run_end[i]] = 1;
             if (uses_cache(i)) is_target[i] = 1;          // the next frame reads this layer's output as its cache
-            if ((layers[i].type != DC_CONV || in_place) && last_reader[i + 1] >= 0 && !fresh[i + 1])
+            if ((layers[i].type != DC_CONV || in_place || torus) && last_reader[i + 1] >= 0 && !fresh[i + 1])
                 is_target[last_reader[i + 1]] = 1;
         }
     }
@@ -1143,6 +1177,12 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         devplan = dl.ok && 3 * (align_up(dl.table_bytes, 256) + dl.frame_bytes) <= ws_dev_bytes - 2 * kConvScratchBytes &&
                   dl.table_bytes <= kDevHostRegion - 3 * kDevHostSlot;
     }
+    if (torus && cached && !devplan) return DC_ERR_UNSUPPORTED;      // a torus frame is planned on the GPU or not at all
+    if (torus && !cached && ws_host && ws_host_bytes >= kDevHostRegion + 256) {
+        // a full frame writes every tensor at its buffer's start: the next cached frame starts from origins (0, 0)
+        DevHostHeader* h = reinterpret_cast<DevHostHeader*>(hbase + ((ws_host_bytes - kDevHostRegion) & ~(size_t)255));
+        if (h->magic == kDevHostMagic) h->origin_area = -1;
+    }
     if (devplan) {
         unsigned char* const region = hbase + ((ws_host_bytes - kDevHostRegion) & ~(size_t)255);
         hdr = reinterpret_cast<DevHostHeader*>(region);
@@ -1170,6 +1210,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         if (hdr->magic != kDevHostMagic || hdr->signature != sig || hdr->ws_dev != ws_dev || (hdr->last_slot != 0 && hdr->last_slot != 1)) {
             std::memset(region, 0, 3 * kDevHostSlot);          // other stack or workspace: the counters start afresh
             hdr->last_slot = 1;
+            hdr->origin_area = -1;
         }
         hdr->magic = kDevHostMagic; hdr->signature = sig; hdr->ws_dev = ws_dev;
         hdr->n_layers = n_layers; hdr->n_convs = (int32_t)dl.convs.size();
@@ -1210,6 +1251,17 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         pd.area = frame + dl.off_area;
         pd.bitmaps = reinterpret_cast<uint32_t*>(frame + dl.off_bitmaps);
         pd.bm_words = dl.bm_words;
+        pd.origin = nullptr; pd.origin_prev = nullptr;
+        if (torus) {          // this frame's origins follow from the previous frame's, which its plan area still holds
+            pd.origin = reinterpret_cast<int32_t*>(frame + dl.off_origin);
+            if (hdr->origin_area >= 0 && hdr->origin_area < 3)
+                pd.origin_prev = reinterpret_cast<const int32_t*>(static_cast<unsigned char*>(ws_dev) +
+                                                                  (size_t)hdr->origin_area * (table_slot + dl.frame_bytes) + table_slot + dl.off_origin);
+            hdr->origin_area = area;
+        } else {
+            hdr->origin_area = -1;
+        }
+        hdr->torus = torus ? 1 : 0;
         unsigned char* const slot_host = slots + (size_t)slot * kDevHostSlot;
         const unsigned char* alias = device_alias(ws_host);
         pd.stats = alias ? const_cast<unsigned char*>(alias) + (slot_host - static_cast<unsigned char*>(ws_host))
@@ -1244,6 +1296,11 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         }
         hdr->last_slot = slot;
         hdr->n_blocks = (int32_t)nb;
+        if (torus && match_options->origins_out) {      // for inspection only: wait for the plan and read the origins back
+            DC_TRY_HIP(hipStreamSynchronize(pst));
+            DC_TRY_HIP(hipMemcpy(match_options->origins_out, pd.origin, (size_t)n_streams * (n_layers + 1) * 2 * sizeof(int32_t),
+                                 hipMemcpyDeviceToHost));
+        }
         if (regions_out) {      // for inspection only: wait for the lists and read them back
             const int nt = n_layers + 1;
             try {
@@ -1431,6 +1488,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 const int i = dl.conv_layer[c];
                 copy_fused[i] = 1;
                 if (no_reuse && no_reuse[i]) continue;          // nothing of this layer comes from the cache
+                if (torus) continue;                            // the reusable pixels already lie where this frame looks for them
                 const size_t px_bytes = (size_t)layers[i].cout * dtype_size(dtype);
                 const bool vec16 = px_bytes % 16 == 0 && reinterpret_cast<uintptr_t>(tensors_prev[i + 1]) % 16 == 0 &&
                                    reinterpret_cast<uintptr_t>(tensors_cur[i + 1]) % 16 == 0;
@@ -1523,6 +1581,11 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     for (int t = 0; t <= n_layers; ++t)
         eff[t] = (inplace && t > 0 && layers[t - 1].type == DC_CONV) ? tensors_prev[t] : tensors_cur[t];
     if (in_place) *in_place = inplace ? 1 : 0;
+    // torus frames: where the origins of tensor t start (a stream's are 2 (n_layers + 1) ints apart); nullptr: the
+    // tensor starts at its buffer's start (every tensor of a full frame, everything but conv outputs otherwise)
+    auto origin_of = [&](int t) -> const int32_t* {
+        return (torus && devplan && t > 0 && layers[t - 1].type == DC_CONV) ? pd.origin + 2 * t : nullptr;
+    };
     // ---- layers ----
     int conv_seen = 0;
     for (int i = 0; i < n_layers; ++i) {
@@ -1534,7 +1597,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 rc = launch_copy_group(i);
                 if (rc) return rc;
                 DC_TRY_HIP(wait_prev(run_end[i]));   // its cache: the previous frame's output of this layer (whole run)
-                if (inplace) DC_TRY_HIP(wait_prev(last_reader[t]));   // and the previous frame's readers of the buffer it updates
+                if (inplace || torus) DC_TRY_HIP(wait_prev(last_reader[t]));   // and the previous frame's readers of the buffer it updates
                 rc = run_conv_planned(l, eff[a], weights[i], bias ? bias[i] : nullptr,
                                       cached ? tensors_prev[t] : nullptr, eff[t], n_streams, hs[a], ws[a], dtype,
                                       tilings[i], cached ? &plans[i] : nullptr, cached ? &addrs[i] : nullptr, st,
@@ -1544,12 +1607,18 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                                       packed_weights ? packed_weights[i] : nullptr,
                                       devplan ? reinterpret_cast<const TileDev*>(pd.area + dl.convs[ci].list_off) : nullptr,
                                       devplan ? n_streams * dl.convs[ci].units_x * dl.convs[ci].units_y : 0,
-                                      devplan ? pd.n_units + ci : nullptr, devplan ? unit_hint[ci] : -1);
+                                      devplan ? pd.n_units + ci : nullptr, devplan ? unit_hint[ci] : -1,
+                                      origin_of(a), origin_of(t), 2 * (n_layers + 1));
                 if (rc) return rc;
                 break;
             }
             case DC_MAXPOOL:
                 DC_TRY_HIP(wait_readers(t));
+                if (origin_of(a)) {          // its input lies on a torus
+                    DC_TRY_HIP(launch_maxpool2x2_torus(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], dtype, origin_of(a),
+                                                       2 * (n_layers + 1), st));
+                    break;
+                }
                 if (devplan && uses_cache(i)) {
                     DC_TRY_HIP(wait_prev(i));                 // its cache: the previous frame's output of this layer
                     const CachedMap cm{pd.bitmaps, pd.bm_words, dl.tensors[t].bm_off, pd.dxy, n_layers + 1, t};
@@ -1713,7 +1782,7 @@ int32_t dc_stack_stats_fetch(const void* ws_host, size_t ws_host_bytes, dc_stack
         const int64_t issued = (int64_t)sc[c].n_units * 16 * hc.mac_px;
         stats->macs_needed += (hc.px_total - sc[c].reused_px) * hc.mac_px;
         stats->macs_issued += issued;
-        stats->copy_bytes += 2 * sc[c].reused_px * hc.cout_bytes;
+        if (!hdr->torus) stats->copy_bytes += 2 * sc[c].reused_px * hc.cout_bytes;
         if (stats->layer_reused_px) stats->layer_reused_px[hc.layer] = sc[c].reused_px;
         if (stats->layer_issued_macs) stats->layer_issued_macs[hc.layer] = issued;
     }

@@ -546,6 +546,7 @@ hipError_t launch_conv(const ConvLaunch& c, hipStream_t st) {
         hipError_t fe = hipSuccess;
         if (launch_conv_fast(c, n_units, n_hint, st, &fe)) return fe;
     }
+    if (c.in_origin || c.out_origin) return hipErrorInvalidValue;      // only those kernels address a torus
     // Shape by the amount of work.  With enough units a workgroup takes g of them (up to 16) and 64
     // channels, g chosen so that the launch fills the 256 CUs in whole rounds; with few units the
     // smaller shapes split K among the wavefronts instead.

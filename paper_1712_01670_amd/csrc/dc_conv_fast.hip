@@ -50,9 +50,11 @@ struct FastHeader {
     int* ustream;
     int* ukind;             // -1: no unit, otherwise the 16-bit mask of the unit's reusable pixels
     unsigned char* skip;
+    int4* uorg;             // tensors on a torus: {input ox, oy, output ox, oy} of the unit's stream
     __device__ __forceinline__ explicit FastHeader(unsigned char* smem)
         : uq(reinterpret_cast<int4*>(smem)), ustream(reinterpret_cast<int*>(smem + 16 * G)),
-          ukind(reinterpret_cast<int*>(smem + 20 * G)), skip(smem + 24 * G) {}   // 40 G <= 640 bytes
+          ukind(reinterpret_cast<int*>(smem + 20 * G)), skip(smem + 24 * G),
+          uorg(reinterpret_cast<int4*>(smem + 40 * G)) {}   // 56 G <= 1008 bytes (G <= 18)
 };
 
 template <int G, int NTHREADS, int ES>
@@ -81,6 +83,13 @@ __device__ __forceinline__ void decode_units_fast(const ConvParams& P, const Fas
         H.uq[tid] = v;
         H.ustream[tid] = stream;
         H.ukind[tid] = valid ? mixed : -1;
+        if (P.in_origin || P.out_origin) {
+            int4 og{0, 0, 0, 0};
+            const size_t at = (size_t)stream * P.origin_stride;
+            if (P.in_origin) { og.x = P.in_origin[at]; og.y = P.in_origin[at + 1]; }
+            if (P.out_origin) { og.z = P.out_origin[at]; og.w = P.out_origin[at + 1]; }
+            H.uorg[tid] = og;
+        }
     }
     __syncthreads();
     if (tid < G * 16) {
@@ -202,7 +211,13 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
             const int py = part * (RPI / PWP) + pyl;
             const int sw = patch_swizzle<RB>(py, px);
             const bool ok = px < PH && (unsigned)(uq.y + py) < (unsigned)P.Hin && (unsigned)(uq.z + px) < (unsigned)P.Win;
-            pgo[i] = ok ? (uint32_t)(uq.x + py * (P.Win * CinES) + pxoff + ((lpos ^ sw) << 4)) : kOob;
+            uint32_t off = (uint32_t)(uq.x + py * (P.Win * CinES) + pxoff + ((lpos ^ sw) << 4));
+            if (P.in_origin && ok) {      // the input lies on a torus: the patch may cross its seams
+                const int4 og = H.uorg[unit];
+                const int iy = torus_wrap(uq.y + py, og.y, P.Hin), ix = torus_wrap(uq.z + px, og.x, P.Win);
+                off = (uint32_t)(((H.ustream[unit] * P.Hin + iy) * P.Win + ix) * CinES + ((lpos ^ sw) << 4));
+            }
+            pgo[i] = ok ? off : kOob;
         }
     }
     // part < 0: the whole patch; otherwise the instructions with index % KSZ == part
@@ -333,6 +348,11 @@ __global__ __launch_bounds__(WM* WN * 64) void conv_fast_kernel(ConvParams P) {
             const int g = wave_m + u * WM;
             if (H.skip[g * 16 + l16]) continue;
             T* px = out + H.uq[g].w;
+            if (P.out_origin) {           // the output lies on a torus: the unit may cross its seams
+                const int4 og = H.uorg[g];
+                const int y = torus_wrap(H.uq[g].y + P.p + (l16 >> 2), og.w, P.Hout), x = torus_wrap(H.uq[g].z + P.p + (l16 & 3), og.z, P.Wout);
+                px = reinterpret_cast<T*>(P.out) + ((H.ustream[g] * P.Hout + y) * P.Wout + x) * P.Cout + chan;
+            }
 #pragma unroll
             for (int j = 0; j < NBW; ++j) {
                 floatx4 v = acc[u][j] + bias[j];
@@ -386,7 +406,12 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     for (int s = 1; s < P.ks; ++s) v += *reinterpret_cast<const floatx4*>(p + s * split_stride);
     if (P.bias) v += *reinterpret_cast<const floatx4*>(P.bias + co);
     if (P.relu) activate4(v, P.relu);
-    T* out = reinterpret_cast<T*>(P.out) + (((size_t)stream * P.Hout + y) * P.Wout + x) * P.Cout + co;
+    int yo = y, xo = x;
+    if (P.out_origin) {
+        xo = torus_wrap(x, P.out_origin[(size_t)stream * P.origin_stride], P.Wout);
+        yo = torus_wrap(y, P.out_origin[(size_t)stream * P.origin_stride + 1], P.Hout);
+    }
+    T* out = reinterpret_cast<T*>(P.out) + (((size_t)stream * P.Hout + yo) * P.Wout + xo) * P.Cout + co;
     F::store4(out, v);
 }
 
@@ -406,6 +431,9 @@ struct UnitRegs {
     int oy, ox;     // row / column of that origin (may be negative); oy = -2^24 for a missing unit
     int out_base;   // element offset in the output of the unit's first pixel
     int kind;       // -1: missing unit, else the 16-bit mask of reusable pixels
+    // tensors on a torus only (in_base and out_base are not used then): the unit's stream and the origins of that
+    // stream in the input and in the output, column | row << 16
+    int stream, iorg, oorg;
 };
 
 // The unit list entry of unit u (or its raster position), not yet turned into offsets: fetched two steps ahead.
@@ -419,8 +447,15 @@ __device__ __forceinline__ TileDev regw_fetch(const ConvParams& P, long u, int n
     t.reuse_mask = 0;
     return t;
 }
+template <bool TORUS>
 __device__ __forceinline__ UnitRegs regw_unit(const ConvParams& P, const TileDev& t) {
     UnitRegs r;
+    if (TORUS) {
+        const size_t at = (size_t)t.stream * P.origin_stride;
+        r.iorg = P.in_origin ? P.in_origin[at] | (P.in_origin[at + 1] << 16) : 0;
+        r.oorg = P.out_origin ? P.out_origin[at] | (P.out_origin[at + 1] << 16) : 0;
+        r.stream = t.stream;
+    }
     const bool valid = t.reuse_mask != -1;
     const int oy = t.ty * 4 - P.p, ox = t.tx * 4 - P.p;
     r.in_base = ((t.stream * P.Hin + oy) * P.Win + ox) * P.Cin * 2;
@@ -431,8 +466,8 @@ __device__ __forceinline__ UnitRegs regw_unit(const ConvParams& P, const TileDev
     return r;
 }
 
-template <int WM, int UPW>
-__global__ __launch_bounds__(WM * 128) void conv_regw_kernel(ConvParams P) {
+template <int WM, int UPW, bool TORUS>
+__global__ __launch_bounds__(WM * 128) __attribute__((amdgpu_waves_per_eu(2))) void conv_regw_kernel(ConvParams P) {
     typedef Frag<__hip_bfloat16> F;
     typedef F::vec vec;
     constexpr int WN = 2, NBW = 2, G = WM * UPW;
@@ -476,11 +511,11 @@ __global__ __launch_bounds__(WM * 128) void conv_regw_kernel(ConvParams P) {
     const int px_l = lane >> 3, lpos = lane & 7;
     const int CinES = 128;
     const int line_bytes = P.Win * CinES;
-    int lane_off[3];
+    int lane_off[3];   // on a torus without the line and the column: they depend on the stream's origin
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
         const int py = wave_n * 3 + i;
-        lane_off[i] = py * line_bytes + px_l * CinES + ((lpos ^ patch_swizzle<RB>(py, px_l)) << 4);
+        lane_off[i] = (TORUS ? 0 : py * line_bytes + px_l * CinES) + ((lpos ^ patch_swizzle<RB>(py, px_l)) << 4);
     }
     const int Hin = keep_scalar(P.Hin), Win = keep_scalar(P.Win);
     auto issue_p = [&](const UnitRegs (&info)[UPW], int buf) {
@@ -488,11 +523,15 @@ __global__ __launch_bounds__(WM * 128) void conv_regw_kernel(ConvParams P) {
         for (int uu = 0; uu < UPW; ++uu) {
             // columns: slot px_l is inside the map iff 0 <= ox + px_l < Win (slots 6 and 7 are never used)
             const bool col_ok = px_l < 6 && (unsigned)(info[uu].ox + px_l) < (unsigned)Win;
+            int col_off = 0;
+            if (TORUS) col_off = torus_wrap(info[uu].ox + px_l, info[uu].iorg & 0xffff, Win) * CinES;
 #pragma unroll
             for (int i = 0; i < 3; ++i) {
                 const int py = wave_n * 3 + i;
                 const bool row_ok = (unsigned)(info[uu].oy + py) < (unsigned)Hin;       // wavefront-uniform
-                const uint32_t off = (col_ok && row_ok) ? (uint32_t)(info[uu].in_base + lane_off[i]) : kOob;
+                int base = info[uu].in_base;
+                if (TORUS) base = (info[uu].stream * Hin + torus_wrap(info[uu].oy + py, info[uu].iorg >> 16, Hin)) * line_bytes + col_off;
+                const uint32_t off = (col_ok && row_ok) ? (uint32_t)(base + lane_off[i]) : kOob;
                 unsigned char* dst = smem + buf * PBYTES + ((wave_m + uu * WM) * PR + py * PWP) * RB;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(in_rsrc, (__attribute__((address_space(3))) void*)dst, 16, off, 0, 0, 0);
             }
@@ -524,7 +563,7 @@ __global__ __launch_bounds__(WM * 128) void conv_regw_kernel(ConvParams P) {
     };
     auto decode = [&](const TileDev (&raw)[UPW], UnitRegs (&info)[UPW]) {
 #pragma unroll
-        for (int uu = 0; uu < UPW; ++uu) info[uu] = regw_unit(P, raw[uu]);
+        for (int uu = 0; uu < UPW; ++uu) info[uu] = regw_unit<TORUS>(P, raw[uu]);
     };
     UnitRegs cur[UPW], nxt[UPW];
     TileDev raw[UPW];
@@ -587,6 +626,10 @@ __global__ __launch_bounds__(WM * 128) void conv_regw_kernel(ConvParams P) {
         for (int uu = 0; uu < UPW; ++uu) {
             const int y = cur[uu].oy + P.p + (l16 >> 2), x = cur[uu].ox + P.p + (l16 & 3);
             pend_on[uu] = !(cur[uu].kind < 0 || y >= P.Hout || x >= P.Wout || ((cur[uu].kind >> l16) & 1));
+            if (TORUS) {
+                const int yw = torus_wrap(pend_on[uu] ? y : 0, cur[uu].oorg >> 16, P.Hout), xw = torus_wrap(pend_on[uu] ? x : 0, cur[uu].oorg & 0xffff, P.Wout);
+                pend_px[uu] = reinterpret_cast<__hip_bfloat16*>(P.out) + ((cur[uu].stream * P.Hout + yw) * P.Wout + xw) * P.Cout + chan;
+            } else
             pend_px[uu] = reinterpret_cast<__hip_bfloat16*>(P.out) + cur[uu].out_base +
                           ((l16 >> 2) * P.Wout + (l16 & 3)) * P.Cout + chan;
 #pragma unroll
@@ -913,7 +956,12 @@ __device__ __forceinline__ void conv_first_body(const ConvParams& P) {
         const int y = pos.uy * 4 + (l16 >> 2), x = pos.ux * 4 + (l16 & 3);
         const bool keep = y < P.Hout && x < P.Wout && !((pos.mixed >> l16) & 1);   // a reusable pixel holds the copied value
         if (keep) {
-            T* px = reinterpret_cast<T*>(P.out) + ((pos.stream * P.Hout + y) * P.Wout + x) * P.Cout + chan;
+            int yo = y, xo = x;
+            if (P.out_origin) {       // the output lies on a torus
+                xo = torus_wrap(x, P.out_origin[(size_t)pos.stream * P.origin_stride], P.Wout);
+                yo = torus_wrap(y, P.out_origin[(size_t)pos.stream * P.origin_stride + 1], P.Hout);
+            }
+            T* px = reinterpret_cast<T*>(P.out) + ((pos.stream * P.Hout + yo) * P.Wout + xo) * P.Cout + chan;
             floatx4 v[NB];
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
@@ -1137,7 +1185,8 @@ FastChoice choose_fast(const ConvLaunch& c, long n_units, long n_cap, size_t scr
 // Ids 64.. name the instantiations of this file: 64 + ((bf16 * 2 + kci) * 8 + UPW - 1), 96.. the first-layer kernel,
 // 110.. the wide arrangement.
 void conv_fast_kernel_name(int id, char* buf, size_t n) {
-    if (id == 126) { snprintf(buf, n, "conv_regw_kernel<2, 2>"); return; }
+    if (id == 126) { snprintf(buf, n, "conv_regw_kernel<2, 2, false>"); return; }
+    if (id == 130) { snprintf(buf, n, "conv_regw_kernel<2, 2, true>"); return; }      // tensors on a torus
     if (id == 129) { snprintf(buf, n, "conv_fast_kernel<__hip_bfloat16, 3, 32, 3, 6, 2, 4>"); return; }     // the tall arrangement
     if (id == 127 || id == 128 || id == 108 || id == 109) {      // 108 + bf16 (64 x 64 tile), 127 + bf16 (128 x 128): conv_pw_kernel (1x1)
         snprintf(buf, n, "conv_pw_kernel<%s, %d>", id == 109 || id == 128 ? "__hip_bfloat16" : "float", id >= 127 ? 4 : 2);
@@ -1183,17 +1232,17 @@ hipError_t launch_pack_weights(const void* w, void* packed, int cin, int cout, i
     return hipGetLastError();
 }
 
-template <int WM, int UPW>
-hipError_t regw_launch(dim3 grid, hipStream_t st, const ConvParams& P) {
+template <int WM, int UPW, bool TORUS>
+hipError_t regw_launch_t(dim3 grid, hipStream_t st, const ConvParams& P) {
     const size_t lds = 2 * (size_t)(WM * UPW) * 48 * 128;
     static std::atomic<bool> raised{false};
     if (lds > 64 * 1024 && !raised.load()) {
-        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_regw_kernel<WM, UPW>),
+        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_regw_kernel<WM, UPW, TORUS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
         if (a != hipSuccess) return a;
         raised.store(true);
     }
-    hipLaunchKernelGGL((conv_regw_kernel<WM, UPW>), grid, dim3(WM * 128), lds, st, P);
+    hipLaunchKernelGGL((conv_regw_kernel<WM, UPW, TORUS>), grid, dim3(WM * 128), lds, st, P);
     return hipGetLastError();
 }
 
@@ -1223,7 +1272,8 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
     const Tuning tune = tuning_snapshot();
     const int* g_tune = tune.v;
     const size_t esz = dtype_size(c.dtype);
-    if (enabled && ((c.k == 3 && c.s == 1) || (c.k == 7 && c.s == 2) || (c.k == 11 && c.s == 4)) && c.Cin * esz == 16 && c.Cout % 16 == 0 &&
+    const bool torus = c.in_origin || c.out_origin;     // only the first-layer kernels (output) and the 3x3 GEMM kernel take origins
+    if (enabled && !c.in_origin && ((c.k == 3 && c.s == 1) || (c.k == 7 && c.s == 2) || (c.k == 11 && c.s == 4)) && c.Cin * esz == 16 && c.Cout % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
         const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
@@ -1238,6 +1288,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
             P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)units_x - 1) / (uint64_t)units_x);
             P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * 16);
             P.w_bytes = (uint32_t)((size_t)c.Cout * c.k * c.k * 16);
+            P.out_origin = c.out_origin; P.origin_stride = c.origin_stride;
             // the 7x7 kernel keeps 14 weight vectors per channel block in registers: two blocks at most
             const int nb = c.k == 11 ? 1 : (c.Cout % 64 == 0 && c.k == 3 ? 4 : (c.Cout % 32 == 0 ? 2 : 1));
             // four units at a time.  3x3: at most 8 workgroups per CU.  The large kernels hold one workgroup per CU
@@ -1254,7 +1305,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
             return true;
         }
     }
-    if (enabled && c.k == 1 && c.p == 0 && (c.s == 1 || c.s == 2) && (c.Cin * esz) % 16 == 0 && c.Cout % 8 == 0 &&
+    if (enabled && !torus && c.k == 1 && c.p == 0 && (c.s == 1 || c.s == 2) && (c.Cin * esz) % 16 == 0 && c.Cout % 8 == 0 &&
         reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
         constexpr bool pw_enabled = true;
@@ -1311,14 +1362,16 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
         P.pw_magic = (uint32_t)((0x100000000ull + (uint64_t)P.units_x - 1) / (uint64_t)P.units_x);
         P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * c.Cin * esz);
         P.w_bytes = (uint32_t)((size_t)c.Cout * 9 * c.Cin * esz);
+        P.in_origin = c.in_origin; P.out_origin = c.out_origin; P.origin_stride = c.origin_stride;
         // Two persistent workgroups of four wavefronts per CU (the registers allow two wavefronts per SIMD): they
         // drift apart, so that one's address work and epilogue overlap the other's MFMAs.
         const int R = c.Cout / 64;
         const long groups = (n_cap + 3) / 4;
         long gx = 512 / R > 0 ? 512 / R : 1;
         if (gx > groups) gx = groups;
-        if (c.kernel_id) *c.kernel_id = 126;
-        *err = regw_launch<2, 2>(dim3((unsigned)gx, (unsigned)R), st, P);
+        if (c.kernel_id) *c.kernel_id = torus ? 130 : 126;
+        *err = torus ? regw_launch_t<2, 2, true>(dim3((unsigned)gx, (unsigned)R), st, P)
+                     : regw_launch_t<2, 2, false>(dim3((unsigned)gx, (unsigned)R), st, P);
         return true;
     }
     size_t scratch = c.scratch && reinterpret_cast<uintptr_t>(c.scratch) % 16 == 0 ? c.scratch_bytes : 0;
@@ -1378,6 +1431,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
     P.ks = ch.ks;
     P.chunks_per_split = (P.n_chunks + ch.ks - 1) / ch.ks;
     P.partial = ch.ks > 1 ? static_cast<float*>(c.scratch) : nullptr;
+    P.in_origin = c.in_origin; P.out_origin = c.out_origin; P.origin_stride = c.origin_stride;
     if (c.w_packed && reinterpret_cast<uintptr_t>(c.w_packed) % 16 == 0) { P.w = c.w_packed; P.w_packed = 1; }
 
     if (c.kernel_id) *c.kernel_id = ch.geom == 3 ? 129 : ch.geom ? 110 + (ch.geom - 1) * 8 + ch.kci * 4 + upw - 1 : 64 + ((c.dtype == DC_BF16 ? 2 : 0) + ch.kci) * 8 + upw - 1;

@@ -85,6 +85,11 @@ struct ConvLaunch {
     void* out;
     int n_streams, Hin, Win, Cin, Hout, Wout, Cout, k, s, p, relu, dtype;
     int kw = 0, pw = 0, dil = 1;      // kw > 0: k rows x kw columns, paddings p / pw; dil: distance between taps
+    // Tensors on a torus (optional, device): (ox, oy) of stream s at origin[s * origin_stride + 0 / 1]; nullptr: none.
+    // Only the 3x3 stride-1 GEMM kernel and the first-layer kernels take them (the launch fails otherwise).
+    const int32_t* in_origin = nullptr;
+    const int32_t* out_origin = nullptr;
+    int origin_stride = 0;
     ConvTiling tiling;
     const TileDev* tiles;  // device; nullptr: every tile of every stream
     int n_tiles;           // ignored when tiles == nullptr; with n_tiles_dev the capacity of the list
@@ -143,6 +148,9 @@ struct CachedMap {
     const int32_t* dxy;        // [stream][n_tensors][2]
     int32_t n_tensors, tensor;
 };
+// 2 x 2 / stride 2 max-pooling of a tensor stored on a torus (origin [stream * origin_stride + 0 / 1] = ox, oy)
+hipError_t launch_maxpool2x2_torus(const void* in, void* out, int n_streams, int Hin, int Win, int C, int dtype,
+                                   const int32_t* origin, int origin_stride, hipStream_t st);
 hipError_t launch_maxpool_cached(const void* in, const void* prev, void* out, int n_streams, int Hin, int Win, int C, int k,
                                  int s, int p, int dtype, const CachedMap& M, hipStream_t st);
 hipError_t launch_add_cached(const void* a, const void* b, const void* prev, void* out, int n_streams, int H, int W, int C,
@@ -204,7 +212,14 @@ struct PlanDev {                         // device addresses of one frame's plan
     // bitmaps + s * bm_words + tensors[t].bm_off
     uint32_t* bitmaps;
     int64_t bm_words;
+    // Conv outputs kept on a torus (optional): origin [stream][tensor][2] = (ox, oy), the buffer position of the
+    // tensor's pixel (0, 0); this frame's = the previous frame's + the tensor's offset, modulo the map's size, for
+    // conv outputs, (0, 0) for every other tensor.  origin_prev == nullptr: the previous frame left none (all zero).
+    int32_t* origin;
+    const int32_t* origin_prev;
 };
+// Position in the buffer of pixel v of a tensor axis of n pixels whose origin is o (0 <= o < n, 0 <= v < n).
+__host__ __device__ inline int torus_wrap(int v, int o, int n) { const int p = v + o; return p >= n ? p - n : p; }
 hipError_t launch_plan(const PlanDev& P, const uint8_t* block_mask, const int32_t* gmv, int gh, int gw, int block,
                        int extend_borders, int max_chunks, hipStream_t st);
 // The same with exact reuse maps instead of rectangles: plan_erode_kernel (one workgroup per stream) derives every

@@ -382,6 +382,32 @@ __global__ __launch_bounds__(kThreads) void maxpool2x2_vec_kernel(const uint4* _
     }
 }
 
+// The same pooling of a conv output that lies on a torus: pixel (x, y) of stream s is stored at
+// ((x + ox) mod Win, (y + oy) mod Hin) with (ox, oy) = origin[s * origin_stride + 0 / 1]; the output has no origin.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void maxpool2x2_torus_kernel(const uint4* __restrict__ in, uint4* __restrict__ out,
+                                                                    int Hin, int Win, int CV, int Hout, int Wout,
+                                                                    const int32_t* __restrict__ origin, int origin_stride) {
+    constexpr int VE = Vec16<T>::VE;
+    const int row = blockIdx.y;                     // stream * Hout + y
+    const int stream = row / Hout, y = row - stream * Hout;
+    const int ox = origin[(size_t)stream * origin_stride], oy = origin[(size_t)stream * origin_stride + 1];
+    const int j = (int)blockIdx.x * kThreads + (int)threadIdx.x;
+    if (j >= Wout * CV) return;
+    const int x = j / CV, cv = j - x * CV;
+    const uint4* __restrict__ base = in + (size_t)stream * Hin * Win * CV + cv;
+    const size_t r0 = (size_t)torus_wrap(2 * y, oy, Hin) * Win, r1 = (size_t)torus_wrap(2 * y + 1, oy, Hin) * Win;
+    const int c0 = torus_wrap(2 * x, ox, Win), c1 = torus_wrap(2 * x + 1, ox, Win);
+    float a[4][VE], m[VE];
+    Vec16<T>::load(base + (r0 + c0) * CV, a[0]);
+    Vec16<T>::load(base + (r0 + c1) * CV, a[1]);
+    Vec16<T>::load(base + (r1 + c0) * CV, a[2]);
+    Vec16<T>::load(base + (r1 + c1) * CV, a[3]);
+#pragma unroll
+    for (int e = 0; e < VE; ++e) m[e] = fmaxf(fmaxf(a[0][e], a[1][e]), fmaxf(a[2][e], a[3][e]));
+    Vec16<T>::store(out + (size_t)row * Wout * CV + j, m);
+}
+
 // Max-pooling and add with the cache: grid.y = (stream, output row), a thread takes one 16-byte vector of one pixel;
 // a pixel whose bit is set in the tensor's reuse bitmap receives the previous frame's output at the tensor's offset.
 template <typename T>
@@ -649,6 +675,21 @@ hipError_t launch_pool(const void* in, void* out, int n_streams, int Hin, int Wi
 hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k, int s,
                           int p, int dtype, hipStream_t st) {
     return launch_pool<false>(in, out, n_streams, Hin, Win, C, k, s, p, dtype, st);
+}
+
+hipError_t launch_maxpool2x2_torus(const void* in, void* out, int n_streams, int Hin, int Win, int C, int dtype,
+                                   const int32_t* origin, int origin_stride, hipStream_t st) {
+    const int Hout = Hin / 2, Wout = Win / 2;
+    if ((C * dtype_size(dtype)) % 16 || (size_t)n_streams * Hout > 65535 || !origin || Hout < 1 || Wout < 1) return hipErrorInvalidValue;
+    const int cv = (int)(C * dtype_size(dtype) / 16);
+    const dim3 grid((unsigned)((Wout * cv + kThreads - 1) / kThreads), (unsigned)(n_streams * Hout));
+    if (dtype == DC_BF16)
+        hipLaunchKernelGGL(maxpool2x2_torus_kernel<__hip_bfloat16>, grid, dim3(kThreads), 0, st, (const uint4*)in, (uint4*)out, Hin, Win,
+                           cv, Hout, Wout, origin, origin_stride);
+    else
+        hipLaunchKernelGGL(maxpool2x2_torus_kernel<float>, grid, dim3(kThreads), 0, st, (const uint4*)in, (uint4*)out, Hin, Win, cv,
+                           Hout, Wout, origin, origin_stride);
+    return hipGetLastError();
 }
 
 hipError_t launch_maxpool_cached(const void* in, const void* prev, void* out, int n_streams, int Hin, int Win, int C, int k,

@@ -56,6 +56,20 @@ __device__ __forceinline__ int round_half_away(int num, int den) {
     return num < 0 ? -(int)q : (int)q;
 }
 
+// The torus origin of tensor t of a stream for this frame (see PlanDev): a conv output moves by its offset.
+__device__ __forceinline__ void write_origin(const PlanDev& P, int stream, int nt, int t, bool conv_output, int dx, int dy, int w, int h) {
+    const size_t at = ((size_t)stream * nt + t) * 2;
+    int ox = 0, oy = 0;
+    if (conv_output) {
+        ox = ((P.origin_prev ? P.origin_prev[at] : 0) + dx) % w;
+        oy = ((P.origin_prev ? P.origin_prev[at + 1] : 0) + dy) % h;
+        if (ox < 0) ox += w;
+        if (oy < 0) oy += h;
+    }
+    P.origin[at] = ox;
+    P.origin[at + 1] = oy;
+}
+
 // Appends the rectangles (xs, ys) of the lanes with `ok` to `list` (LDS) in lane order; returns the new length.
 // `room` is what the list may hold (the per-list bound, or what is left of the pool).
 __device__ __forceinline__ int append(dc_rect* list, int n, int room, bool ok, SpanD xs, SpanD ys, int lane, bool& over) {
@@ -274,6 +288,9 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
         for (int j = lane; j < s_n[t]; j += 64) out[j] = src[j];
     }
     for (int t = lane; t < 2 * nt; t += 64) P.dxy[(size_t)stream * nt * 2 + t] = s_dxy[t];
+    if (P.origin)
+        for (int t = lane; t < nt; t += 64) write_origin(P, stream, nt, t, t > 0 && s_layers[t - 1].type == DC_CONV, s_dxy[2 * t], s_dxy[2 * t + 1],
+                                                          s_tensors[t].w, s_tensors[t].h);
     for (int t = lane; t < nt; t += 64) P.nrect[(size_t)stream * nt + t] = over ? 0 : s_n[t];
     if (lane == 0) { P.stream_info[2 * stream] = reusable; P.stream_info[2 * stream + 1] = over ? 1 : 0; }
 }
@@ -501,6 +518,11 @@ __global__ __launch_bounds__(kErodeThreads) void plan_erode_kernel(PlanDev P, co
         erode_stream(g_maps, s_layers, s_tensors, P.n_layers, dxy, m, gh, gw, B, mx, my, ext, tid);
     }
     for (int t = tid; t < nt; t += kErodeThreads) P.nrect[(size_t)stream * nt + t] = 0;      // no rectangles in this mode
+    if (P.origin) {
+        __syncthreads();          // the offsets of all tensors are written
+        for (int t = tid; t < nt; t += kErodeThreads)
+            write_origin(P, stream, nt, t, t > 0 && s_layers[t - 1].type == DC_CONV, dxy[2 * t], dxy[2 * t + 1], s_tensors[t].w, s_tensors[t].h);
+    }
 }
 
 // The 16-bit unit masks of every conv layer cut out of the bitmaps (grid and outputs as plan_masks_kernel).

@@ -50,6 +50,7 @@ def main():
                     help="merge / propagate / list the dirty units on the host (one wait per frame) instead of on the GPU")
     ap.add_argument("--exact-masks", action="store_true", help="exact reuse maps instead of rectangles (planned on the GPU)")
     ap.add_argument("--cache-pool-add", action="store_true", help="with --exact-masks: max-pooling and add layers use the cache too")
+    ap.add_argument("--torus", action="store_true", help="conv outputs on a torus: nothing is copied (planned on the GPU)")
     ap.add_argument("--min-reuse-macs", type=int, default=0,
                     help="conv layers with fewer multiply-adds per output element (k*k*cin) do not use the cache")
     ap.add_argument("--in-place", action="store_true",
@@ -104,7 +105,7 @@ def main():
         video = torch.from_numpy(np.ascontiguousarray(vids.transpose(1, 0, 2, 3, 4))).to(dev)
         out = {"target_reuse": r, "net": args.net, "size": args.size, "dtype": args.dtype, "frames": args.frames,
                "streams": args.streams, "matcher": args.matcher, "k_skip": args.k_skip, "pan": list(pan), "in_place": bool(args.in_place), "extend_borders": bool(args.extend_borders),
-               "lookahead": bool(args.lookahead), "planning": "host" if (args.host_plan or args.in_place) else "device", "exact_masks": bool(args.exact_masks), "cache_pool_add": bool(args.cache_pool_add and args.exact_masks), "min_reuse_macs": args.min_reuse_macs,
+               "lookahead": bool(args.lookahead), "planning": "host" if (args.host_plan or args.in_place) else "device", "exact_masks": bool(args.exact_masks), "cache_pool_add": bool(args.cache_pool_add and args.exact_masks), "min_reuse_macs": args.min_reuse_macs, "torus": bool(args.torus),
                "video": "panning background under moving noise rectangles sized for the target ratio, scene cut at the middle"}
         for mode, expiry in (("cached", 1 << 30), ("expiry", args.expiry), ("full", 1 << 30)):
             runner = binding.StackRunner(layers, ws, bs, args.streams, H, W, 3, block=16, radius=16, dtype=dt, expiry=expiry,
@@ -112,7 +113,8 @@ def main():
                                          k_skip=args.k_skip, in_place=args.in_place, extend_borders=args.extend_borders,
                                          device_plan=not args.host_plan, exact_masks=args.exact_masks and not args.host_plan and not args.in_place,
                                          cache_pool_add=args.cache_pool_add and args.exact_masks and not args.host_plan and not args.in_place,
-                                         no_reuse=synth.no_reuse_flags(layers, args.min_reuse_macs) if args.min_reuse_macs > 0 else None)
+                                         no_reuse=synth.no_reuse_flags(layers, args.min_reuse_macs) if args.min_reuse_macs > 0 else None,
+                                         torus=args.torus and not args.host_plan and not args.in_place)
             t, macs, reuse = timed(runner, video, mode)
             out[mode] = {"frames_per_s": args.streams / t, "ms_per_frame": t * 1e3 / args.streams}
             if mode != "full":

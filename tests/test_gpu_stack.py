@@ -24,6 +24,8 @@ def _elem_err(got, want):
 
 def _run_both(oracle, layers, videos, block, radius, bf16, in_place=False, device_plan=None, exact_masks=False, **kw):
     exact_masks = exact_masks or bool(kw.get("cache_pool_add"))
+    if kw.get("torus"):      # torus frames are planned on the GPU
+        device_plan = True
     """Every frame of every stream against the oracle, with the frame planned on the host and (unless in-place frames
     are asked for, which only the host plans) once more with the frame planned on the GPU."""
     modes = [False] if in_place else ([False, True] if device_plan is None else [bool(device_plan)])
@@ -41,7 +43,7 @@ def _run_both(oracle, layers, videos, block, radius, bf16, in_place=False, devic
 
 def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias_scale=0.05,
              residual_scale=1.0, check_tensors=None, resets=(), diamond=False, k_skip=1, in_place=False,
-             extend_borders=False, device_plan=False, exact_masks=False, cache_pool_add=False, no_reuse=None):
+             extend_borders=False, device_plan=False, exact_masks=False, cache_pool_add=False, no_reuse=None, torus=False):
     """videos: uint8 [n_streams][T][H][W][C].  Compares every frame of every stream."""
     n, T, H, W, C = videos.shape
     ws, bs = synth.he_weights(layers, seed, bias_scale=bias_scale, residual_scale=residual_scale, input_shape=(H, W, C))
@@ -50,7 +52,8 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
     runner = binding.StackRunner(layers, ws, bs, n, H, W, C, block=block, radius=radius, dtype=dt, expiry=expiry,
                                  want_regions=True, k_skip=k_skip, in_place=in_place, extend_borders=extend_borders,
                                  match_method=binding.DC_MATCH_DIAMOND if diamond else binding.DC_MATCH_EXHAUSTIVE,
-                                 device_plan=device_plan, exact_masks=exact_masks, cache_pool_add=cache_pool_add, no_reuse=no_reuse)
+                                 device_plan=device_plan, exact_masks=exact_masks, cache_pool_add=cache_pool_add, no_reuse=no_reuse,
+                                 torus=torus, want_origins=torus)
     streams = [oracle.Stream(layers, ws, bs, H, W, C, block=block, radius=radius, bf16=bf16, expiry=expiry,
                              diamond=diamond, k_skip=k_skip, extend_borders=extend_borders, exact_masks=exact_masks,
                              cache_pool_add=cache_pool_add, no_reuse=no_reuse)
@@ -70,7 +73,7 @@ def _run_one(oracle, layers, videos, block, radius, bf16, expiry=0, seed=1, bias
         tensors = runner.step(dev_video[t])
         torch.cuda.synchronize()
         runner.in_place_frames.append(bool(runner.last_in_place))
-        got = [x.float().cpu().numpy() for x in tensors]
+        got = [x.float().cpu().numpy() for x in runner.logical_tensors(tensors)]
         blocks = needed = 0
         for s in range(n):
             want = streams[s].step(videos[s, t])
@@ -499,6 +502,46 @@ def test_stack_with_kernels_that_are_not_square_or_dilated(oracle, bf16):
     _run_both(oracle, layers, video, 8, 8, bf16, exact_masks=True)
     f1, f2 = synth.tiny_pair(0)
     _run_both(oracle, layers, np.stack([f1, f2, f2])[None], 8, 8, bf16, extend_borders=True)
+
+
+def _torus_stack(c=64):
+    """first layer on a padded pixel vector, 3x3 layers with whole 64-byte rows, 2x2 poolings: what the torus mode takes"""
+    return synth._chain([("c", c, 3, 1, 1), ("c", c, 3, 1, 1), ("p", 2, 2, 0), ("c", 2 * c, 3, 1, 1), ("c", 2 * c, 3, 1, 1),
+                         ("p", 2, 2, 0), ("c", 2 * c, 3, 1, 1)], 3)
+
+
+@pytest.mark.parametrize("exact", [False, True])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_conv_outputs_on_a_torus(oracle, bf16, exact):
+    """dc_match_options.torus: nothing is copied, every conv output is one buffer whose origin moves with the frames; the
+    tensors, read from their origins, are those of the oracle's stream (and of the copying path)."""
+    layers = _torus_stack()
+    # a pan that crosses the seams several times, streams that move differently, a scene cut, an expiry in between
+    video = np.stack([synth.panning_video(7000 + s, n_frames=7, H=96, W=96, fg=((24, 24),), margin=32) for s in range(3)])
+    runner, reuse = _run_one(oracle, layers, video, 16, 16, bf16, device_plan=True, exact_masks=exact, torus=True, resets=(4,),
+                             expiry=3, bias_scale=0.0)
+    assert max(reuse) > 0.3 and runner.torus
+    # the tiny pair: motion (-3, +2), then a frame that does not move, then back
+    f1, f2 = synth.tiny_pair(0)
+    _run_one(oracle, _torus_stack(64), np.stack([f1, f2, f2, f1, f2])[None], 8, 8, bf16, device_plan=True, exact_masks=exact, torus=True)
+
+
+def test_torus_vgg16_two_streams(oracle):
+    v = np.stack([synth.panning_video(5000 + s, n_frames=4, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
+    runner, _ = _run_one(oracle, synth.vgg16(), v, 16, 16, True, device_plan=True, exact_masks=True, torus=True, bias_scale=0.0)
+    assert runner.origins.any()          # some origin moved
+    assert runner.read_stats().copy_bytes == 0
+
+
+def test_torus_is_refused_for_stacks_it_cannot_take(oracle):
+    layers = synth.resnet50_trunk()[:10]         # 1x1 and strided layers, adds
+    H = W = 64
+    ws, bs = synth.he_weights(layers, 1, input_shape=(H, W, 3))
+    r = binding.StackRunner(layers, ws, bs, 1, H, W, 3, block=16, radius=8, dtype=binding.DC_BF16, device_plan=True, torus=True)
+    with pytest.raises(binding.DcError) as e:
+        r.step(torch.zeros((1, H, W, 3), dtype=torch.uint8, device=DEV))
+    assert e.value.status == -4
+    torch.cuda.synchronize()
 
 
 def test_border_case_planned_on_the_gpu(oracle):

@@ -82,10 +82,11 @@ def test_argument_errors_are_reported_before_any_launch():
     assert binding.conv_kernel_name(128) == "conv_pw_kernel<__hip_bfloat16, 4>"
     assert binding.conv_kernel_name(110 + 3) == "conv_fast_kernel<__hip_bfloat16, 3, 32, 4, 4, 2, 4>"
     assert binding.conv_kernel_name(110 + 8 + 4) == "conv_fast_kernel<__hip_bfloat16, 3, 64, 1, 4, 2, 2>"
-    assert binding.conv_kernel_name(126) == "conv_regw_kernel<2, 2>"
+    assert binding.conv_kernel_name(126) == "conv_regw_kernel<2, 2, false>"
+    assert binding.conv_kernel_name(130) == "conv_regw_kernel<2, 2, true>"
     assert binding.conv_kernel_name(129) == "conv_fast_kernel<__hip_bfloat16, 3, 32, 3, 6, 2, 4>"
     with pytest.raises(binding.DcError):
-        binding.conv_kernel_name(130)
+        binding.conv_kernel_name(131)
     # overlapping rectangles are rejected
     regs, keep = binding._alloc_regions(1, 2)
     keep[0][0] = binding.Rect(0, 0, 4, 4)
