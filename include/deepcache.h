@@ -136,7 +136,10 @@ typedef struct {
                               stacks whose conv layers are 3x3 / stride 1 with whole 64-byte channel rows (or a
                               first layer on a 16-byte pixel vector) and whose conv outputs are read by such layers or by
                               2x2 / stride-2 max-pooling qualify (DC_ERR_UNSUPPORTED otherwise); every other tensor
-                              is stored as always. */
+                              is stored as always.  Together with cache_pool_add the outputs of the max-pooling layers
+                              (every one of them must then be such a 2x2 pooling of a conv output, read by conv layers
+                              only; no add layers) are single buffers on a torus as well, and a pooled pixel whose map
+                              bit is set is simply left alone; a caller that reads such a tensor needs origins_out. */
     int32_t* origins_out;  /* optional with torus: host [n_streams][n_layers + 1][2], receives (ox, oy) of every tensor
                               after a cached frame (for inspection: the call then waits for the planning) */
     int32_t device_plan;   /* dc_run_stack only.  0: the call waits for the matching, then merges, propagates and lists

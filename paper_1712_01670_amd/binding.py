@@ -502,10 +502,13 @@ class StackRunner:
         is_conv = [False] + [L["type"] == synth.CONV for L in layers]
         self._is_conv_out = is_conv
         both = bool(overlap and pipeline) or bool(cache_pool_add and exact_masks)
+        # on a torus: the conv outputs, and the max-pooling outputs too when those layers use the cache
+        single = [self.torus and (is_conv[t] or (self.cache_pool_add and t > 0 and layers[t - 1]["type"] == synth.MAXPOOL))
+                  for t in range(nl + 1)]
         self.bufs = [[], []]
         for t, (h, w, c) in enumerate(self.shapes):
             a = torch.empty((n_streams, h, w, c), dtype=td, device=self.device)
-            b = a if (self.torus and is_conv[t]) else (torch.empty_like(a) if (is_conv[t] or both) else a)
+            b = a if single[t] else (torch.empty_like(a) if (is_conv[t] or both) else a)
             self.bufs[0].append(a)
             self.bufs[1].append(b)
         # pointer tables [set of the conv outputs][set of the other tensors]: the two only differ after in-place frames
@@ -604,13 +607,13 @@ class StackRunner:
 
     def logical_tensors(self, tensors):
         """With torus: the tensors of the last step in their logical layout (copies; needs want_origins and a synchronised
-        stream).  Pixel (x, y) of stream s of a conv output lies at ((x + ox) mod w, (y + oy) mod h) of its buffer."""
+        stream).  Pixel (x, y) of stream s of a tensor on the torus lies at ((x + ox) mod w, (y + oy) mod h) of its buffer."""
         if not self.torus:
             return tensors
         assert self.origins is not None
         out = []
         for t, x in enumerate(tensors):
-            if not self._is_conv_out[t] or not self.origins[:, t].any():
+            if not self.origins[:, t].any():
                 out.append(x)
                 continue
             out.append(torch.stack([torch.roll(x[s], shifts=(-int(self.origins[s, t, 1]), -int(self.origins[s, t, 0])), dims=(0, 1))

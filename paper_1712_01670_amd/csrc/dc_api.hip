@@ -994,7 +994,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         if (match_options->k_skip < 1) return DC_ERR_INVALID_ARG;
         if (match_options->exact_masks && (!match_options->device_plan || in_place)) return DC_ERR_UNSUPPORTED;   // planned on the GPU only
         if (match_options->cache_pool_add && !match_options->exact_masks) return DC_ERR_UNSUPPORTED;
-        if (match_options->torus && (!match_options->device_plan || in_place || match_options->cache_pool_add)) return DC_ERR_UNSUPPORTED;
+        if (match_options->torus && (!match_options->device_plan || in_place)) return DC_ERR_UNSUPPORTED;
     }
     if (cached) {
         if (!frames_prev || !tensors_prev || !mv || !best_ssd || !global_mv || !n_pass || !block_mask || !ws_dev || !ws_host)
@@ -1016,6 +1016,11 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     // Conv outputs on a torus: single-buffered, never copied (see dc_match_options.torus).  Only the layers whose kernels
     // address a torus may touch a conv output.
     const bool torus = match_options && match_options->torus;
+    // with cache_pool_add the poolings' outputs are cache values too and lie on a torus like the conv outputs
+    const bool pool_torus = torus && match_options->cache_pool_add;
+    auto on_torus = [&](int t) {
+        return torus && t > 0 && (layers[t - 1].type == DC_CONV || (pool_torus && layers[t - 1].type == DC_MAXPOOL));
+    };
     if (torus) {
         const size_t esz = dtype_size(dtype);
         auto conv_output = [&](int t) { return t > 0 && layers[t - 1].type == DC_CONV; };
@@ -1029,15 +1034,18 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 if (!plain_square(l) || !(first || gemm3)) return DC_ERR_UNSUPPORTED;
                 if (!tensors_prev || tensors_prev[t] != tensors_cur[t]) return DC_ERR_INVALID_ARG;     // one buffer per conv output
             } else if (l.type == DC_MAXPOOL) {
-                if (conv_output(l.in0) && !(l.k == 2 && l.s == 2 && l.p == 0 && (cs[l.in0] * esz) % 16 == 0 &&
-                                            (size_t)n_streams * hs[t] <= 65535))
+                if ((conv_output(l.in0) || pool_torus) &&
+                    !(conv_output(l.in0) && l.k == 2 && l.s == 2 && l.p == 0 && (cs[l.in0] * esz) % 16 == 0 &&
+                      (size_t)n_streams * hs[t] <= 65535))
                     return DC_ERR_UNSUPPORTED;
+                if (pool_torus && (!tensors_prev || tensors_prev[t] != tensors_cur[t])) return DC_ERR_INVALID_ARG;   // one buffer
             } else {
+                if (pool_torus && l.type == DC_ADD) return DC_ERR_UNSUPPORTED;       // an add layer that uses the cache copies
                 int ids[4] = {l.in0, l.type == DC_ADD ? l.in1 : -1, -1, -1};
                 int m = l.type == DC_ADD ? 2 : 1;
                 if (l.type == DC_CONCAT) m = concat_inputs(l, ids);
                 for (int j = 0; j < m; ++j)
-                    if (conv_output(ids[j])) return DC_ERR_UNSUPPORTED;
+                    if (on_torus(ids[j])) return DC_ERR_UNSUPPORTED;
             }
         }
     }
@@ -1046,7 +1054,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     if (cache_other)
         for (int i = 0; i < n_layers; ++i)
             if (uses_cache(i)) {
-                if (!tensors_prev[i + 1] || tensors_prev[i + 1] == tensors_cur[i + 1]) return DC_ERR_NULL_PTR;
+                if (!tensors_prev[i + 1] || (tensors_prev[i + 1] == tensors_cur[i + 1]) != pool_torus) return DC_ERR_NULL_PTR;
                 if ((cs[i + 1] * dtype_size(dtype)) % 16 || (size_t)n_streams * hs[i + 1] > 65535 ||
                     reinterpret_cast<uintptr_t>(tensors_prev[i + 1]) % 16 || reinterpret_cast<uintptr_t>(tensors_cur[i + 1]) % 16)
                     return DC_ERR_UNSUPPORTED;
@@ -1251,7 +1259,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         pd.area = frame + dl.off_area;
         pd.bitmaps = reinterpret_cast<uint32_t*>(frame + dl.off_bitmaps);
         pd.bm_words = dl.bm_words;
-        pd.origin = nullptr; pd.origin_prev = nullptr;
+        pd.origin = nullptr; pd.origin_prev = nullptr; pd.pool_torus = pool_torus ? 1 : 0;
         if (torus) {          // this frame's origins follow from the previous frame's, which its plan area still holds
             pd.origin = reinterpret_cast<int32_t*>(frame + dl.off_origin);
             if (hdr->origin_area >= 0 && hdr->origin_area < 3)
@@ -1584,7 +1592,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
     // torus frames: where the origins of tensor t start (a stream's are 2 (n_layers + 1) ints apart); nullptr: the
     // tensor starts at its buffer's start (every tensor of a full frame, everything but conv outputs otherwise)
     auto origin_of = [&](int t) -> const int32_t* {
-        return (torus && devplan && t > 0 && layers[t - 1].type == DC_CONV) ? pd.origin + 2 * t : nullptr;
+        return (devplan && on_torus(t)) ? pd.origin + 2 * t : nullptr;
     };
     // ---- layers ----
     int conv_seen = 0;
@@ -1614,9 +1622,12 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
             }
             case DC_MAXPOOL:
                 DC_TRY_HIP(wait_readers(t));
-                if (origin_of(a)) {          // its input lies on a torus
+                if (origin_of(a)) {          // its input lies on a torus, and with the cache its output too
+                    const CachedMap cm{pd.bitmaps, pd.bm_words, dl.tensors[t].bm_off, pd.dxy, n_layers + 1, t};
+                    const bool through_cache = origin_of(t) && uses_cache(i);
+                    if (through_cache) DC_TRY_HIP(wait_prev(i));     // its cache: the previous frame's output of this layer
                     DC_TRY_HIP(launch_maxpool2x2_torus(eff[a], eff[t], n_streams, hs[a], ws[a], cs[a], dtype, origin_of(a),
-                                                       2 * (n_layers + 1), st));
+                                                       origin_of(t), 2 * (n_layers + 1), through_cache ? &cm : nullptr, st));
                     break;
                 }
                 if (devplan && uses_cache(i)) {

@@ -148,9 +148,12 @@ struct CachedMap {
     const int32_t* dxy;        // [stream][n_tensors][2]
     int32_t n_tensors, tensor;
 };
-// 2 x 2 / stride 2 max-pooling of a tensor stored on a torus (origin [stream * origin_stride + 0 / 1] = ox, oy)
+// 2 x 2 / stride 2 max-pooling of a tensor stored on a torus (origin [stream * origin_stride + 0 / 1] = ox, oy).
+// out_origin != nullptr: the output lies on a torus too.  M != nullptr: the layer uses the cache, which on a torus
+// means that a pixel whose bit is set in the output's reuse bitmap is left as it is.
 hipError_t launch_maxpool2x2_torus(const void* in, void* out, int n_streams, int Hin, int Win, int C, int dtype,
-                                   const int32_t* origin, int origin_stride, hipStream_t st);
+                                   const int32_t* origin, const int32_t* out_origin, int origin_stride, const CachedMap* M,
+                                   hipStream_t st);
 hipError_t launch_maxpool_cached(const void* in, const void* prev, void* out, int n_streams, int Hin, int Win, int C, int k,
                                  int s, int p, int dtype, const CachedMap& M, hipStream_t st);
 hipError_t launch_add_cached(const void* a, const void* b, const void* prev, void* out, int n_streams, int H, int W, int C,
@@ -217,6 +220,7 @@ struct PlanDev {                         // device addresses of one frame's plan
     // conv outputs, (0, 0) for every other tensor.  origin_prev == nullptr: the previous frame left none (all zero).
     int32_t* origin;
     const int32_t* origin_prev;
+    int pool_torus;          // 1: the outputs of max-pooling layers lie on a torus as well (they use the cache too)
 };
 // Position in the buffer of pixel v of a tensor axis of n pixels whose origin is o (0 <= o < n, 0 <= v < n).
 __host__ __device__ inline int torus_wrap(int v, int o, int n) { const int p = v + o; return p >= n ? p - n : p; }

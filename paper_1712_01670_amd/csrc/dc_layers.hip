@@ -383,11 +383,15 @@ __global__ __launch_bounds__(kThreads) void maxpool2x2_vec_kernel(const uint4* _
 }
 
 // The same pooling of a conv output that lies on a torus: pixel (x, y) of stream s is stored at
-// ((x + ox) mod Win, (y + oy) mod Hin) with (ox, oy) = origin[s * origin_stride + 0 / 1]; the output has no origin.
-template <typename T>
+// ((x + ox) mod Win, (y + oy) mod Hin) with (ox, oy) = origin[s * origin_stride + 0 / 1]; the output has an origin of
+// its own or none.  CACHED: the output is a cache value as well, and a pixel whose bit is set in its reuse bitmap
+// keeps what the buffer holds (the previous frame's value, which the moved origin has put in its place).
+template <typename T, bool CACHED>
 __global__ __launch_bounds__(kThreads) void maxpool2x2_torus_kernel(const uint4* __restrict__ in, uint4* __restrict__ out,
                                                                     int Hin, int Win, int CV, int Hout, int Wout,
-                                                                    const int32_t* __restrict__ origin, int origin_stride) {
+                                                                    const int32_t* __restrict__ origin,
+                                                                    const int32_t* __restrict__ out_origin, int origin_stride,
+                                                                    CachedMap M) {
     constexpr int VE = Vec16<T>::VE;
     const int row = blockIdx.y;                     // stream * Hout + y
     const int stream = row / Hout, y = row - stream * Hout;
@@ -395,6 +399,10 @@ __global__ __launch_bounds__(kThreads) void maxpool2x2_torus_kernel(const uint4*
     const int j = (int)blockIdx.x * kThreads + (int)threadIdx.x;
     if (j >= Wout * CV) return;
     const int x = j / CV, cv = j - x * CV;
+    if (CACHED) {
+        const uint32_t* bits = M.bitmaps + (size_t)stream * M.bm_words + M.bm_off + (size_t)y * ((Wout + 31) >> 5);
+        if ((bits[x >> 5] >> (x & 31)) & 1u) return;
+    }
     const uint4* __restrict__ base = in + (size_t)stream * Hin * Win * CV + cv;
     const size_t r0 = (size_t)torus_wrap(2 * y, oy, Hin) * Win, r1 = (size_t)torus_wrap(2 * y + 1, oy, Hin) * Win;
     const int c0 = torus_wrap(2 * x, ox, Win), c1 = torus_wrap(2 * x + 1, ox, Win);
@@ -405,7 +413,13 @@ __global__ __launch_bounds__(kThreads) void maxpool2x2_torus_kernel(const uint4*
     Vec16<T>::load(base + (r1 + c1) * CV, a[3]);
 #pragma unroll
     for (int e = 0; e < VE; ++e) m[e] = fmaxf(fmaxf(a[0][e], a[1][e]), fmaxf(a[2][e], a[3][e]));
-    Vec16<T>::store(out + (size_t)row * Wout * CV + j, m);
+    size_t at = (size_t)row * Wout * CV + j;
+    if (out_origin) {
+        const int xo = torus_wrap(x, out_origin[(size_t)stream * origin_stride], Wout);
+        const int yo = torus_wrap(y, out_origin[(size_t)stream * origin_stride + 1], Hout);
+        at = (((size_t)stream * Hout + yo) * Wout + xo) * CV + cv;
+    }
+    Vec16<T>::store(out + at, m);
 }
 
 // Max-pooling and add with the cache: grid.y = (stream, output row), a thread takes one 16-byte vector of one pixel;
@@ -677,18 +691,29 @@ hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int
     return launch_pool<false>(in, out, n_streams, Hin, Win, C, k, s, p, dtype, st);
 }
 
+template <typename T>
+static void maxpool2x2_torus_go(dim3 grid, hipStream_t st, const void* in, void* out, int Hin, int Win, int cv, int Hout, int Wout,
+                                const int32_t* origin, const int32_t* out_origin, int origin_stride, const CachedMap* M) {
+    if (M)
+        hipLaunchKernelGGL((maxpool2x2_torus_kernel<T, true>), grid, dim3(kThreads), 0, st, (const uint4*)in, (uint4*)out, Hin, Win,
+                           cv, Hout, Wout, origin, out_origin, origin_stride, *M);
+    else
+        hipLaunchKernelGGL((maxpool2x2_torus_kernel<T, false>), grid, dim3(kThreads), 0, st, (const uint4*)in, (uint4*)out, Hin, Win,
+                           cv, Hout, Wout, origin, out_origin, origin_stride, CachedMap{});
+}
+
 hipError_t launch_maxpool2x2_torus(const void* in, void* out, int n_streams, int Hin, int Win, int C, int dtype,
-                                   const int32_t* origin, int origin_stride, hipStream_t st) {
+                                   const int32_t* origin, const int32_t* out_origin, int origin_stride, const CachedMap* M,
+                                   hipStream_t st) {
     const int Hout = Hin / 2, Wout = Win / 2;
     if ((C * dtype_size(dtype)) % 16 || (size_t)n_streams * Hout > 65535 || !origin || Hout < 1 || Wout < 1) return hipErrorInvalidValue;
+    if (M && (!M->bitmaps || !out_origin)) return hipErrorInvalidValue;     // a cached pooling output lies on a torus
     const int cv = (int)(C * dtype_size(dtype) / 16);
     const dim3 grid((unsigned)((Wout * cv + kThreads - 1) / kThreads), (unsigned)(n_streams * Hout));
     if (dtype == DC_BF16)
-        hipLaunchKernelGGL(maxpool2x2_torus_kernel<__hip_bfloat16>, grid, dim3(kThreads), 0, st, (const uint4*)in, (uint4*)out, Hin, Win,
-                           cv, Hout, Wout, origin, origin_stride);
+        maxpool2x2_torus_go<__hip_bfloat16>(grid, st, in, out, Hin, Win, cv, Hout, Wout, origin, out_origin, origin_stride, M);
     else
-        hipLaunchKernelGGL(maxpool2x2_torus_kernel<float>, grid, dim3(kThreads), 0, st, (const uint4*)in, (uint4*)out, Hin, Win, cv,
-                           Hout, Wout, origin, origin_stride);
+        maxpool2x2_torus_go<float>(grid, st, in, out, Hin, Win, cv, Hout, Wout, origin, out_origin, origin_stride, M);
     return hipGetLastError();
 }
 

@@ -56,7 +56,11 @@ __device__ __forceinline__ int round_half_away(int num, int den) {
     return num < 0 ? -(int)q : (int)q;
 }
 
-// The torus origin of tensor t of a stream for this frame (see PlanDev): a conv output moves by its offset.
+// Whether tensor t (the output of a layer of this type) lies on a torus.
+__device__ __forceinline__ bool torus_tensor(const PlanDev& P, int t, int producer_type) {
+    return t > 0 && (producer_type == DC_CONV || (P.pool_torus && producer_type == DC_MAXPOOL));
+}
+// The torus origin of tensor t of a stream for this frame (see PlanDev): a tensor on a torus moves by its offset.
 __device__ __forceinline__ void write_origin(const PlanDev& P, int stream, int nt, int t, bool conv_output, int dx, int dy, int w, int h) {
     const size_t at = ((size_t)stream * nt + t) * 2;
     int ox = 0, oy = 0;
@@ -289,7 +293,7 @@ __global__ __launch_bounds__(64) void plan_regions_kernel(PlanDev P, const uint8
     }
     for (int t = lane; t < 2 * nt; t += 64) P.dxy[(size_t)stream * nt * 2 + t] = s_dxy[t];
     if (P.origin)
-        for (int t = lane; t < nt; t += 64) write_origin(P, stream, nt, t, t > 0 && s_layers[t - 1].type == DC_CONV, s_dxy[2 * t], s_dxy[2 * t + 1],
+        for (int t = lane; t < nt; t += 64) write_origin(P, stream, nt, t, torus_tensor(P, t, t > 0 ? s_layers[t - 1].type : -1), s_dxy[2 * t], s_dxy[2 * t + 1],
                                                           s_tensors[t].w, s_tensors[t].h);
     for (int t = lane; t < nt; t += 64) P.nrect[(size_t)stream * nt + t] = over ? 0 : s_n[t];
     if (lane == 0) { P.stream_info[2 * stream] = reusable; P.stream_info[2 * stream + 1] = over ? 1 : 0; }
@@ -521,7 +525,7 @@ __global__ __launch_bounds__(kErodeThreads) void plan_erode_kernel(PlanDev P, co
     if (P.origin) {
         __syncthreads();          // the offsets of all tensors are written
         for (int t = tid; t < nt; t += kErodeThreads)
-            write_origin(P, stream, nt, t, t > 0 && s_layers[t - 1].type == DC_CONV, dxy[2 * t], dxy[2 * t + 1], s_tensors[t].w, s_tensors[t].h);
+            write_origin(P, stream, nt, t, torus_tensor(P, t, t > 0 ? s_layers[t - 1].type : -1), dxy[2 * t], dxy[2 * t + 1], s_tensors[t].w, s_tensors[t].h);
     }
 }
 

@@ -533,6 +533,28 @@ def test_torus_vgg16_two_streams(oracle):
     assert runner.read_stats().copy_bytes == 0
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_poolings_on_the_torus_too(oracle, bf16):
+    """torus with cache_pool_add: the poolings' outputs are cache values on a torus of their own, a pooled pixel whose map
+    bit is set is not touched; the oracle's stream with max-pooling through the cache gives the logical tensors."""
+    video = np.stack([synth.panning_video(7100 + s, n_frames=7, H=96, W=96, fg=((24, 24),), margin=32) for s in range(3)])
+    runner, reuse = _run_one(oracle, _torus_stack(), video, 16, 16, bf16, device_plan=True, exact_masks=True, cache_pool_add=True,
+                             torus=True, resets=(4,), expiry=3)
+    assert max(reuse) > 0.3 and runner.origins[:, 3].any()       # tensor 3 is the first pooling's output
+    v = np.stack([synth.panning_video(5000 + s, n_frames=4, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
+    _run_one(oracle, synth.vgg16(), v, 16, 16, bf16, device_plan=True, exact_masks=True, cache_pool_add=True, torus=True, bias_scale=0.0)
+
+
+def test_torus_with_the_border_case_and_layers_outside_the_cache(oracle):
+    layers = _torus_stack()
+    video = np.stack([_static_then_moving(700 + s, 96, 96, 3, 2) for s in range(2)])
+    _run_one(oracle, layers, video, 16, 8, True, extend_borders=True, device_plan=True, exact_masks=True, torus=True)
+    flags = np.zeros(len(layers), np.uint8)
+    flags[1] = flags[4] = 1
+    v = np.stack([synth.panning_video(7200 + s, n_frames=5, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
+    _run_one(oracle, layers, v, 16, 16, False, device_plan=True, exact_masks=False, torus=True, no_reuse=flags)
+
+
 def test_torus_is_refused_for_stacks_it_cannot_take(oracle):
     layers = synth.resnet50_trunk()[:10]         # 1x1 and strided layers, adds
     H = W = 64
