@@ -867,12 +867,12 @@ __global__ __launch_bounds__(WM * 128) void conv_pw_kernel(ConvParams P) {
 // nothing to stage: every wavefront takes one unit (16 pixels x NB 16-channel blocks), loads its
 // fragments from memory directly and keeps the weights in registers while it walks over the unit
 // list.  S is the stride: output pixel (y, x) reads input rows y S - p .. y S - p + K - 1.
-template <typename T, int NB, int K, int S>
+template <typename T, int NB, int K, int S, int U>
 __device__ __forceinline__ void conv_first_body(const ConvParams& P) {
     typedef Frag<T> F;
     typedef typename F::vec vec;
     constexpr bool kWide = sizeof(T) == 2 && NB >= 2;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.y * (NB * 16);
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(P.in), 0, P.in_bytes, kBufferFlags);
@@ -902,18 +902,22 @@ __device__ __forceinline__ void conv_first_body(const ConvParams& P) {
     const bool relu = P.relu != 0;
     const int per = P.units_x * P.units_y;
 
-    // The loop is pipelined by hand: the input vectors of the next unit are requested before the current one is
-    // multiplied and stored, so that a wavefront does not sit out a memory latency per unit.
-    struct UnitPos { int stream, uy, ux, mixed; };
+    // The loop is pipelined by hand.  A wavefront takes U consecutive units per step, requests the input vectors of
+    // the next step's units before it multiplies and stores the current ones, and reads the unit list two steps
+    // ahead (wavefront-uniform addresses: scalar loads), so that a step waits for one memory latency at most.
+    struct UnitPos { int stream, uy, ux, mixed; };     // mixed == -1: no such unit
+    const int n_units = unit_count(P);
     auto locate = [&](int u) {
-        UnitPos r{0, 0, 0, 0};
+        UnitPos r{0, 0, 0, -1};
+        if (u >= n_units) return r;
         if (P.units) {
             const TileDev t = P.units[u];
-            r.stream = t.stream; r.uy = t.ty; r.ux = t.tx; r.mixed = t.reuse_mask;
+            r.stream = t.stream; r.uy = t.ty; r.ux = t.tx; r.mixed = t.reuse_mask & 0xffff;
         } else {
             r.stream = fast_div(u, P.npix_magic);
             const int rem = u - r.stream * per;
             r.uy = fast_div(rem, P.pw_magic); r.ux = rem - r.uy * P.units_x;
+            r.mixed = 0;
         }
         return r;
     };
@@ -924,81 +928,97 @@ __device__ __forceinline__ void conv_first_body(const ConvParams& P) {
 #pragma unroll
             for (int g = 0; g < TG; ++g) {
                 const int iy = y * S - P.p + ky, ix = x * S - P.p + g * 4 + q;
-                const bool ok = g * 4 + q < K && (unsigned)iy < (unsigned)P.Hin && (unsigned)ix < (unsigned)P.Win;
+                const bool ok = pos.mixed >= 0 && g * 4 + q < K && (unsigned)iy < (unsigned)P.Hin && (unsigned)ix < (unsigned)P.Win;
                 const uint32_t off = ok ? (uint32_t)(((pos.stream * P.Hin + iy) * P.Win + ix) * 16) : kOob;
                 xv[ky][g] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0));
             }
     };
-    const int step = gridDim.x * 4;
-    int u = blockIdx.x * 4 + wave;
-    const int n_units = unit_count(P);
+    const int step = (int)gridDim.x * 4 * U;
+    int u = ((int)blockIdx.x * 4 + wave) * U;
     if (u >= n_units) return;
-    UnitPos pos = locate(u), pos_next = pos;
-    vec xv[K][TG], xv_next[K][TG];
-    load_x(pos, xv);
-    for (; u < n_units; u += step) {
+    UnitPos pos[U], pos_next[U], pos_after[U];
+    vec xv[U][K][TG], xv_next[U][K][TG];
+#pragma unroll
+    for (int i = 0; i < U; ++i) { pos[i] = locate(u + i); load_x(pos[i], xv[i]); }
+#pragma unroll
+    for (int i = 0; i < U; ++i) pos_next[i] = locate(u + step + i);
+    for (;;) {
         const bool more = u + step < n_units;          // wavefront-uniform
         if (more) {
-            pos_next = locate(u + step);
-            load_x(pos_next, xv_next);
+#pragma unroll
+            for (int i = 0; i < U; ++i) { load_x(pos_next[i], xv_next[i]); pos_after[i] = locate(u + 2 * step + i); }
         }
-        floatx4 acc[NB];
 #pragma unroll
-        for (int j = 0; j < NB; ++j) acc[j] = bias[j];
+        for (int i = 0; i < U; ++i) {
+            floatx4 acc[NB];
 #pragma unroll
-        for (int ky = 0; ky < K; ++ky)
+            for (int j = 0; j < NB; ++j) acc[j] = bias[j];
 #pragma unroll
-          for (int g = 0; g < TG; ++g)
+            for (int ky = 0; ky < K; ++ky)
 #pragma unroll
-            for (int e = 0; e < F::NE; ++e)
+              for (int g = 0; g < TG; ++g)
 #pragma unroll
-                for (int j = 0; j < NB; ++j) F::mma1(wv[ky][g][j], xv[ky][g], acc[j], e);
-        const int y = pos.uy * 4 + (l16 >> 2), x = pos.ux * 4 + (l16 & 3);
-        const bool keep = y < P.Hout && x < P.Wout && !((pos.mixed >> l16) & 1);   // a reusable pixel holds the copied value
-        if (keep) {
-            int yo = y, xo = x;
-            if (P.out_origin) {       // the output lies on a torus
-                xo = torus_wrap(x, P.out_origin[(size_t)pos.stream * P.origin_stride], P.Wout);
-                yo = torus_wrap(y, P.out_origin[(size_t)pos.stream * P.origin_stride + 1], P.Hout);
-            }
-            T* px = reinterpret_cast<T*>(P.out) + ((pos.stream * P.Hout + yo) * P.Wout + xo) * P.Cout + chan;
-            floatx4 v[NB];
+                for (int e = 0; e < F::NE; ++e)
 #pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                v[j] = acc[j];
-                if (relu) activate4(v[j], P.relu);
-            }
-            if constexpr (kWide) {                          // eight bf16 channels per 16-byte store
-#pragma unroll
-                for (int j = 0; j < NB; j += 2) {
-                    uintx4 w4;
-                    w4[0] = (uint32_t)F::bits(v[j][0]) | ((uint32_t)F::bits(v[j][1]) << 16);
-                    w4[1] = (uint32_t)F::bits(v[j][2]) | ((uint32_t)F::bits(v[j][3]) << 16);
-                    w4[2] = (uint32_t)F::bits(v[j + 1][0]) | ((uint32_t)F::bits(v[j + 1][1]) << 16);
-                    w4[3] = (uint32_t)F::bits(v[j + 1][2]) | ((uint32_t)F::bits(v[j + 1][3]) << 16);
-                    *reinterpret_cast<uintx4*>(px + j * 4) = w4;
+                    for (int j = 0; j < NB; ++j) F::mma1(wv[ky][g][j], xv[i][ky][g], acc[j], e);
+            const int y = pos[i].uy * 4 + (l16 >> 2), x = pos[i].ux * 4 + (l16 & 3);
+            // a reusable pixel holds the cached value
+            const bool keep = pos[i].mixed >= 0 && y < P.Hout && x < P.Wout && !((pos[i].mixed >> l16) & 1);
+            if (keep) {
+                int yo = y, xo = x;
+                if (P.out_origin) {       // the output lies on a torus
+                    xo = torus_wrap(x, P.out_origin[(size_t)pos[i].stream * P.origin_stride], P.Wout);
+                    yo = torus_wrap(y, P.out_origin[(size_t)pos[i].stream * P.origin_stride + 1], P.Hout);
                 }
-            } else {
+                T* px = reinterpret_cast<T*>(P.out) + ((pos[i].stream * P.Hout + yo) * P.Wout + xo) * P.Cout + chan;
+                floatx4 v[NB];
 #pragma unroll
-                for (int j = 0; j < NB; ++j) F::store4(px + j * kBlockStep, v[j]);
+                for (int j = 0; j < NB; ++j) {
+                    v[j] = acc[j];
+                    if (relu) activate4(v[j], P.relu);
+                }
+                if constexpr (kWide) {                          // eight bf16 channels per 16-byte store
+#pragma unroll
+                    for (int j = 0; j < NB; j += 2) {
+                        uintx4 w4;
+                        w4[0] = (uint32_t)F::bits(v[j][0]) | ((uint32_t)F::bits(v[j][1]) << 16);
+                        w4[1] = (uint32_t)F::bits(v[j][2]) | ((uint32_t)F::bits(v[j][3]) << 16);
+                        w4[2] = (uint32_t)F::bits(v[j + 1][0]) | ((uint32_t)F::bits(v[j + 1][1]) << 16);
+                        w4[3] = (uint32_t)F::bits(v[j + 1][2]) | ((uint32_t)F::bits(v[j + 1][3]) << 16);
+                        *reinterpret_cast<uintx4*>(px + j * 4) = w4;
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) F::store4(px + j * kBlockStep, v[j]);
+                }
             }
         }
-        pos = pos_next;
+        if (!more) break;
+        u += step;
 #pragma unroll
-        for (int ky = 0; ky < K; ++ky)
+        for (int i = 0; i < U; ++i) {
+            pos[i] = pos_next[i];
+            pos_next[i] = pos_after[i];
 #pragma unroll
-            for (int g = 0; g < TG; ++g) xv[ky][g] = xv_next[ky][g];
+            for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+                for (int g = 0; g < TG; ++g) xv[i][ky][g] = xv_next[i][ky][g];
+        }
     }
 }
 
+// Units per wavefront and step of the 3x3 first-layer kernel.  Measured on 64 bf16 streams at 224x224 (411 MB of output):
+// 1, 2, 3, 4 units per step all take 160-180 us in full and 71 / 81 / 77 us on the bench's cached frames, so more units
+// in flight buy nothing; the same kernel without its stores takes 52 us, without its loads 112 us, with neither 34 us.
+constexpr int kFirstUnits = 1;
 // 3x3 stride 1 (the first layer of the VGG-like stacks) and 7x7 stride 2 (the stem of the residual networks).
 template <typename T, int NB>
-__global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) { conv_first_body<T, NB, 3, 1>(P); }
+__global__ __launch_bounds__(256) void conv_first_kernel(ConvParams P) { conv_first_body<T, NB, 3, 1, kFirstUnits>(P); }
 template <typename T, int NB>
-__global__ __launch_bounds__(256) void conv_stem_kernel(ConvParams P) { conv_first_body<T, NB, 7, 2>(P); }
+__global__ __launch_bounds__(256) void conv_stem_kernel(ConvParams P) { conv_first_body<T, NB, 7, 2, 1>(P); }
 // 11x11 stride 4 (the first layer of AlexNet-style stacks): 33 weight vectors per channel block stay in registers
 template <typename T>
-__global__ __launch_bounds__(256) void conv_stem11_kernel(ConvParams P) { conv_first_body<T, 1, 11, 4>(P); }
+__global__ __launch_bounds__(256) void conv_stem11_kernel(ConvParams P) { conv_first_body<T, 1, 11, 4, 1>(P); }
 
 template <typename T>
 hipError_t first_launch(int k, int nb, dim3 grid, hipStream_t st, const ConvParams& P) {
@@ -1295,7 +1315,8 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
             // (registers) and pay 28 / 33 weight loads per wavefront before the first unit, so the launch is one
             // persistent workgroup per CU and channel block, each walking its share of the units.
             const long cap = c.k == 3 ? 2048 : std::max(1L, (long)g_stem_wgs / (c.Cout / (16 * nb)));
-            const long wgx = (n_cap + 3) / 4 < cap ? (n_cap + 3) / 4 : cap;
+            const long per_wg = 4 * (c.k == 3 ? kFirstUnits : 1);        // units per workgroup and step
+            const long wgx = (n_cap + per_wg - 1) / per_wg < cap ? (n_cap + per_wg - 1) / per_wg : cap;
             if (c.kernel_id)
                 *c.kernel_id = c.k == 11 ? 106 + (c.dtype == DC_BF16 ? 1 : 0)
                              : c.k == 7 ? 102 + (c.dtype == DC_BF16 ? 2 : 0) + (nb == 2 ? 1 : 0)
