@@ -352,17 +352,19 @@ def test_darknet19_416_bf16_cached_frame_and_scene_cut(oracle):
     assert len(reuse) == 2 and all(0.45 < r < 0.6 for r in reuse)
 
 
-@pytest.mark.parametrize("device_plan,exact", [(False, False), (True, False), (True, True)])
-def test_throughput_mode_64_streams_bf16_sampled(oracle, device_plan, exact):
-    """configs[4] launch configuration: 64 streams in one batch, VGG-16-style, bf16, planned on the host, on the GPU, and
-    on the GPU with exact reuse maps (what bench.py times).  Three streams are followed by the oracle over three time
-    steps (everything compared); the others are checked for bit-exact match results on the cached steps."""
+@pytest.mark.parametrize("device_plan,exact,torus", [(False, False, False), (True, False, False), (True, True, False),
+                                                     (True, True, True)])
+def test_throughput_mode_64_streams_bf16_sampled(oracle, device_plan, exact, torus):
+    """configs[4] launch configuration: 64 streams in one batch, VGG-16-style, bf16, planned on the host, on the GPU, on
+    the GPU with exact reuse maps, and the same with the conv outputs on a torus (what bench.py times).  Three streams
+    are followed by the oracle over four time steps (everything compared); the others are checked for bit-exact match
+    results on the cached steps."""
     layers = synth.vgg16()
-    n, T = 64, 3
+    n, T = 64, 4 if torus else 3
     videos = np.stack([synth.panning_video(5000 + s, n_frames=T) for s in range(n)])
     ws, bs = synth.he_weights(layers, 1)
     r = binding.StackRunner(layers, ws, bs, n, 224, 224, 3, block=16, radius=16, dtype=binding.DC_BF16, want_regions=True,
-                            device_plan=device_plan, exact_masks=exact)
+                            device_plan=device_plan, exact_masks=exact, torus=torus, want_origins=torus)
     followed = [0, 31, 63]
     refs = {s: oracle.Stream(layers, ws, bs, 224, 224, 3, block=16, radius=16, bf16=True, exact_masks=exact) for s in followed}
     dv = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
@@ -370,6 +372,11 @@ def test_throughput_mode_64_streams_bf16_sampled(oracle, device_plan, exact):
         print(f"[batch64] step {t}", flush=True)
         tensors = r.step(dv[t])
         torch.cuda.synchronize()
+        if torus:       # only the followed streams are rolled back to their logical layout
+            moved = r.origins.copy()
+            tensors = [x if not moved[followed, ti].any() else
+                       {s: torch.roll(x[s], shifts=(-int(moved[s, ti, 1]), -int(moved[s, ti, 0])), dims=(0, 1)) for s in followed}
+                       for ti, x in enumerate(tensors)]
         for s in followed:
             want = refs[s].step(videos[s, t])
             for ti in range(1, len(layers) + 1):
