@@ -112,6 +112,13 @@ def tiny_net():
     return _chain([("c", 16, 3, 1, 1), ("c", 32, 3, 2, 1), ("c", 32, 3, 1, 1)], 3)
 
 
+def small_vgg(c=64):
+    """Five 3x3 conv layers of c, c, 2c, 2c, 2c channels with 2x2 poolings after the second and the fourth: the
+    smallest stack with the layer shapes of the VGG-style trunk (whole 64-byte channel rows for c = 64)."""
+    return _chain([("c", c, 3, 1, 1), ("c", c, 3, 1, 1), ("p", 2, 2, 0), ("c", 2 * c, 3, 1, 1), ("c", 2 * c, 3, 1, 1),
+                   ("p", 2, 2, 0), ("c", 2 * c, 3, 1, 1)], 3)
+
+
 def vgg16():
     """VGG-16-style trunk: 13 conv3x3 p1 ReLU and 4 maxpool 2x2 s2."""
     spec = []

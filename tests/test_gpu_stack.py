@@ -513,8 +513,7 @@ def test_stack_with_kernels_that_are_not_square_or_dilated(oracle, bf16):
 
 def _torus_stack(c=64):
     """first layer on a padded pixel vector, 3x3 layers with whole 64-byte rows, 2x2 poolings: what the torus mode takes"""
-    return synth._chain([("c", c, 3, 1, 1), ("c", c, 3, 1, 1), ("p", 2, 2, 0), ("c", 2 * c, 3, 1, 1), ("c", 2 * c, 3, 1, 1),
-                         ("p", 2, 2, 0), ("c", 2 * c, 3, 1, 1)], 3)
+    return synth.small_vgg(c)
 
 
 @pytest.mark.parametrize("exact", [False, True])
