@@ -447,13 +447,15 @@ __device__ __forceinline__ TileDev regw_fetch(const ConvParams& P, long u, int n
     t.reuse_mask = 0;
     return t;
 }
+// origins: the streams' origins in LDS, {input, output} as column | row << 16 (a load from memory here would depend on
+// the list entry and stall every step for a round trip)
 template <bool TORUS>
-__device__ __forceinline__ UnitRegs regw_unit(const ConvParams& P, const TileDev& t) {
+__device__ __forceinline__ UnitRegs regw_unit(const ConvParams& P, const TileDev& t, const int2* origins) {
     UnitRegs r;
     if (TORUS) {
-        const size_t at = (size_t)t.stream * P.origin_stride;
-        r.iorg = P.in_origin ? P.in_origin[at] | (P.in_origin[at + 1] << 16) : 0;
-        r.oorg = P.out_origin ? P.out_origin[at] | (P.out_origin[at + 1] << 16) : 0;
+        const int2 og = origins[t.stream];
+        r.iorg = __builtin_amdgcn_readfirstlane(og.x);
+        r.oorg = __builtin_amdgcn_readfirstlane(og.y);
         r.stream = t.stream;
     }
     const bool valid = t.reuse_mask != -1;
@@ -550,6 +552,16 @@ __global__ __launch_bounds__(WM * 128) __attribute__((amdgpu_waves_per_eu(2))) v
         }
     }
 
+    const int2* const origins = reinterpret_cast<const int2*>(smem + 2 * PBYTES);
+    if (TORUS) {
+        int2* const table = reinterpret_cast<int2*>(smem + 2 * PBYTES);
+        for (int s = tid; s < P.n_streams; s += WM * 128) {
+            const size_t at = (size_t)s * P.origin_stride;
+            table[s] = int2{P.in_origin ? P.in_origin[at] | (P.in_origin[at + 1] << 16) : 0,
+                            P.out_origin ? P.out_origin[at] | (P.out_origin[at + 1] << 16) : 0};
+        }
+        __syncthreads();
+    }
     const int n_units = unit_count(P);
     const long n_groups = ((long)n_units + G - 1) / G;
     const long stride = gridDim.x;
@@ -563,7 +575,7 @@ __global__ __launch_bounds__(WM * 128) __attribute__((amdgpu_waves_per_eu(2))) v
     };
     auto decode = [&](const TileDev (&raw)[UPW], UnitRegs (&info)[UPW]) {
 #pragma unroll
-        for (int uu = 0; uu < UPW; ++uu) info[uu] = regw_unit<TORUS>(P, raw[uu]);
+        for (int uu = 0; uu < UPW; ++uu) info[uu] = regw_unit<TORUS>(P, raw[uu], origins);
     };
     UnitRegs cur[UPW], nxt[UPW];
     TileDev raw[UPW];
@@ -1252,9 +1264,10 @@ hipError_t launch_pack_weights(const void* w, void* packed, int cin, int cout, i
     return hipGetLastError();
 }
 
+constexpr int kRegwTorusStreams = 2048;      // streams whose origins fit the LDS table of the kernel (16 KB)
 template <int WM, int UPW, bool TORUS>
 hipError_t regw_launch_t(dim3 grid, hipStream_t st, const ConvParams& P) {
-    const size_t lds = 2 * (size_t)(WM * UPW) * 48 * 128;
+    const size_t lds = 2 * (size_t)(WM * UPW) * 48 * 128 + (TORUS ? (size_t)P.n_streams * sizeof(int2) : 0);
     static std::atomic<bool> raised{false};
     if (lds > 64 * 1024 && !raised.load()) {
         hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_regw_kernel<WM, UPW, TORUS>),
@@ -1372,7 +1385,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
             return false;
     }
     // 64 input channels in bf16 and enough units to keep persistent workgroups busy: the weights go to registers
-    if (c.dtype == DC_BF16 && c.Cin == 64 && c.relu != 2 && (g_tune[0] == 3 || (g_tune[0] < 0 && g_tune[1] < 0 && n_units >= 4096))) {
+    if (c.dtype == DC_BF16 && c.Cin == 64 && c.relu != 2 && (!torus || c.n_streams <= kRegwTorusStreams) && (g_tune[0] == 3 || (g_tune[0] < 0 && g_tune[1] < 0 && n_units >= 4096))) {
         ConvParams P{};
         P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
         P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
@@ -1384,6 +1397,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
         P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * c.Cin * esz);
         P.w_bytes = (uint32_t)((size_t)c.Cout * 9 * c.Cin * esz);
         P.in_origin = c.in_origin; P.out_origin = c.out_origin; P.origin_stride = c.origin_stride;
+        P.n_streams = c.n_streams;
         // Two persistent workgroups of four wavefronts per CU (the registers allow two wavefronts per SIMD): they
         // drift apart, so that one's address work and epilogue overlap the other's MFMAs.
         const int R = c.Cout / 64;
