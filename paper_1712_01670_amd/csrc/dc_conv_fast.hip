@@ -535,7 +535,10 @@ __global__ __launch_bounds__(WM * 128) __attribute__((amdgpu_waves_per_eu(2))) v
                 if (TORUS) base = (info[uu].stream * Hin + torus_wrap(info[uu].oy + py, info[uu].iorg >> 16, Hin)) * line_bytes + col_off;
                 const uint32_t off = (col_ok && row_ok) ? (uint32_t)(base + lane_off[i]) : kOob;
                 unsigned char* dst = smem + buf * PBYTES + ((wave_m + uu * WM) * PR + py * PWP) * RB;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(in_rsrc, (__attribute__((address_space(3))) void*)dst, 16, off, 0, 0, 0);
+                // the lanes of slots 6 and 7 sit the load out: a quarter less for the address unit, whose queue
+                // is what the wavefronts of this kernel wait for when they issue their loads
+                if (px_l < 6)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(in_rsrc, (__attribute__((address_space(3))) void*)dst, 16, off, 0, 0, 0);
             }
         }
     };
