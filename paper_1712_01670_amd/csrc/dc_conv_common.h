@@ -32,7 +32,7 @@ struct ConvParams {
     const int32_t* in_origin;    // tensors on a torus (3x3 stride-1 and first-layer kernels only): (ox, oy) of stream s at
     const int32_t* out_origin;   // origin[s * origin_stride + 0 / 1]; nullptr: the tensor starts at its buffer's start
     int origin_stride;
-    int n_streams;               // conv_regw_kernel on a torus only: entries of its LDS table of origins
+    int n_streams;               // conv_regw_kernel and the first-layer kernels on a torus: entries of their LDS table of origins (0: none)
     int kx, px, dil;        // general kernels: kernel columns (k: rows), padding along x (p: along y), distance between taps
     const TileDev* units;   // nullptr: every unit of every stream in raster order
     int n_units;            // length of the unit list; with n_units_dev the most it can be (the launch is sized for it)

@@ -415,6 +415,8 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(ConvParams P) {
     F::store4(out, v);
 }
 
+constexpr int kRegwTorusStreams = 2048;      // streams whose origins fit a kernel's LDS table (16 KB)
+
 // ---- 3x3, 64 input channels, bf16: the weights live in registers -----------------------------
 // K is only 576, so a workgroup of the kernel above spends more time on its prologue and epilogue than on its
 // six stages.  Here a wavefront keeps the weights of its 32 output channels for the whole K in registers
@@ -921,6 +923,14 @@ __device__ __forceinline__ void conv_first_body(const ConvParams& P) {
     // the next step's units before it multiplies and stores the current ones, and reads the unit list two steps
     // ahead (wavefront-uniform addresses: scalar loads), so that a step waits for one memory latency at most.
     struct UnitPos { int stream, uy, ux, mixed; };     // mixed == -1: no such unit
+    // Output on a torus: the streams' origins wait in LDS (P.n_streams of them; 0: too many, they are loaded from
+    // memory where they are needed, a load that depends on the list entry and stalls the step)
+    extern __shared__ int2 first_origins[];
+    if (P.out_origin && P.n_streams > 0) {
+        for (int s = threadIdx.x; s < P.n_streams; s += 256)
+            first_origins[s] = int2{P.out_origin[(size_t)s * P.origin_stride], P.out_origin[(size_t)s * P.origin_stride + 1]};
+        __syncthreads();
+    }
     const int n_units = unit_count(P);
     auto locate = [&](int u) {
         UnitPos r{0, 0, 0, -1};
@@ -982,8 +992,11 @@ __device__ __forceinline__ void conv_first_body(const ConvParams& P) {
             if (keep) {
                 int yo = y, xo = x;
                 if (P.out_origin) {       // the output lies on a torus
-                    xo = torus_wrap(x, P.out_origin[(size_t)pos[i].stream * P.origin_stride], P.Wout);
-                    yo = torus_wrap(y, P.out_origin[(size_t)pos[i].stream * P.origin_stride + 1], P.Hout);
+                    const int2 og = P.n_streams > 0 ? first_origins[pos[i].stream]
+                                                    : int2{P.out_origin[(size_t)pos[i].stream * P.origin_stride],
+                                                           P.out_origin[(size_t)pos[i].stream * P.origin_stride + 1]};
+                    xo = torus_wrap(x, og.x, P.Wout);
+                    yo = torus_wrap(y, og.y, P.Hout);
                 }
                 T* px = reinterpret_cast<T*>(P.out) + ((pos[i].stream * P.Hout + yo) * P.Wout + xo) * P.Cout + chan;
                 floatx4 v[NB];
@@ -1037,14 +1050,15 @@ __global__ __launch_bounds__(256) void conv_stem11_kernel(ConvParams P) { conv_f
 
 template <typename T>
 hipError_t first_launch(int k, int nb, dim3 grid, hipStream_t st, const ConvParams& P) {
-    if (k == 11) hipLaunchKernelGGL((conv_stem11_kernel<T>), grid, dim3(256), 0, st, P);
+    const size_t lds = P.out_origin ? (size_t)P.n_streams * sizeof(int2) : 0;      // the table of origins
+    if (k == 11) hipLaunchKernelGGL((conv_stem11_kernel<T>), grid, dim3(256), lds, st, P);
     else if (k == 7) {
-        if (nb == 2) hipLaunchKernelGGL((conv_stem_kernel<T, 2>), grid, dim3(256), 0, st, P);
-        else hipLaunchKernelGGL((conv_stem_kernel<T, 1>), grid, dim3(256), 0, st, P);
+        if (nb == 2) hipLaunchKernelGGL((conv_stem_kernel<T, 2>), grid, dim3(256), lds, st, P);
+        else hipLaunchKernelGGL((conv_stem_kernel<T, 1>), grid, dim3(256), lds, st, P);
     }
-    else if (nb == 4) hipLaunchKernelGGL((conv_first_kernel<T, 4>), grid, dim3(256), 0, st, P);
-    else if (nb == 2) hipLaunchKernelGGL((conv_first_kernel<T, 2>), grid, dim3(256), 0, st, P);
-    else hipLaunchKernelGGL((conv_first_kernel<T, 1>), grid, dim3(256), 0, st, P);
+    else if (nb == 4) hipLaunchKernelGGL((conv_first_kernel<T, 4>), grid, dim3(256), lds, st, P);
+    else if (nb == 2) hipLaunchKernelGGL((conv_first_kernel<T, 2>), grid, dim3(256), lds, st, P);
+    else hipLaunchKernelGGL((conv_first_kernel<T, 1>), grid, dim3(256), lds, st, P);
     return hipGetLastError();
 }
 
@@ -1267,7 +1281,6 @@ hipError_t launch_pack_weights(const void* w, void* packed, int cin, int cout, i
     return hipGetLastError();
 }
 
-constexpr int kRegwTorusStreams = 2048;      // streams whose origins fit the LDS table of the kernel (16 KB)
 template <int WM, int UPW, bool TORUS>
 hipError_t regw_launch_t(dim3 grid, hipStream_t st, const ConvParams& P) {
     const size_t lds = 2 * (size_t)(WM * UPW) * 48 * 128 + (TORUS ? (size_t)P.n_streams * sizeof(int2) : 0);
@@ -1325,6 +1338,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
             P.in_bytes = (uint32_t)((size_t)c.n_streams * c.Hin * c.Win * 16);
             P.w_bytes = (uint32_t)((size_t)c.Cout * c.k * c.k * 16);
             P.out_origin = c.out_origin; P.origin_stride = c.origin_stride;
+            P.n_streams = c.out_origin && c.n_streams <= kRegwTorusStreams ? c.n_streams : 0;
             // the 7x7 kernel keeps 14 weight vectors per channel block in registers: two blocks at most
             const int nb = c.k == 11 ? 1 : (c.Cout % 64 == 0 && c.k == 3 ? 4 : (c.Cout % 32 == 0 ? 2 : 1));
             // four units at a time.  3x3: at most 8 workgroups per CU.  The large kernels hold one workgroup per CU
