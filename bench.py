@@ -149,7 +149,7 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
     shapes = runner.shapes
     per_kernel = {}      # kernel name -> [flops_alg, ms, launches, flops_issued]
     copy = dict(ms=0.0, bytes=0.0, launches=0)
-    agg = dict(reuse=[], macs_full=0, macs_needed=0, macs_issued=0, cached_frames=0, full_frames=0)
+    agg = dict(reuse=[], macs_full=0, macs_needed=0, macs_issued=0, cached_frames=0, full_frames=0, layer_reuse={})
 
     def collect(i, f):
         torch.cuda.synchronize()
@@ -163,6 +163,12 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
         else:
             agg["cached_frames"] += 1
             agg["reuse"].append(st.n_reusable_blocks / st.n_blocks)
+            for li, L in enumerate(layers):          # reusable output pixels per conv layer on the cached frames
+                if L["type"] == synth.CONV:
+                    ho, wo, _ = shapes[li + 1]
+                    rec = agg["layer_reuse"].setdefault(li, [0, 0])
+                    rec[0] += ls["reused_px"][li]
+                    rec[1] += n * ho * wo
         for li, (g_ms, c_ms) in runner.profile_ms().items():
             L = layers[li]
             ho, wo, co = shapes[li + 1]
@@ -279,7 +285,9 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
         "config_detail": {"mean_block_reuse": float(np.mean(agg["reuse"])) if agg["reuse"] else 0.0,
                           "full_frame_fraction": agg["full_frames"] / max(steps_all, 1),
                           "mac_fraction_needed": agg["macs_needed"] / max(agg["macs_full"], 1),
-                          "mac_fraction_issued": agg["macs_issued"] / max(agg["macs_full"], 1)},
+                          "mac_fraction_issued": agg["macs_issued"] / max(agg["macs_full"], 1),
+                          # rho_l: share of a conv layer's output pixels that are reused, cached frames only
+                          "conv_layer_reuse": {str(li): round(r[0] / max(r[1], 1), 4) for li, r in sorted(agg["layer_reuse"].items())}},
         "effective_tflops": 2.0 * agg["macs_full"] / max(steps_all, 1) * steps / elapsed / 1e12,
         "roofline": roofline, "cpu_baseline": cpu})
     del runner
