@@ -240,6 +240,17 @@ __global__ __launch_bounds__(kMfmaThreads, 7) void match_mfma_kernel(
     // ---- stage the window (signed bytes; out-of-frame bytes are never part of a valid candidate).  Only the
     // dwords that hold window bytes are fetched (the rest of a row is only read for candidates beyond the
     // search range); the loads of a thread are issued eight at a time before any of them is used ----
+    // The block of the current frame is requested first and used after the window is in place, so that its load
+    // travels together with the window's instead of after them (one memory latency less per block).  One dword per
+    // thread; only when the block's rows are whole aligned dwords.
+    const int blk_bytes = B * C;
+    const bool blk_early = kFused && ALIGNED && BT * (BS / 4) <= kMfmaThreads && (reinterpret_cast<uintptr_t>(cf) & 3) == 0;
+    uint32_t blk_raw = 0x80808080u;
+    if (blk_early && tid < B * (BS / 4)) {
+        const int r = tid / (BS / 4), j = tid - r * (BS / 4);
+        if (4 * j < blk_bytes)
+            blk_raw = *reinterpret_cast<const uint32_t*>(cf + (size_t)(y0 + r) * row_bytes + (size_t)x0 * C + 4 * j);
+    }
     const int wdw = ws / 4;
     const int ldw = (skew + cols * C + 3) / 4;        // dwords per row that hold window bytes
     for (int base = 0; base < rows * ldw; base += 8 * kMfmaThreads) {
@@ -278,22 +289,29 @@ __global__ __launch_bounds__(kMfmaThreads, 7) void match_mfma_kernel(
         reinterpret_cast<uint32_t*>(win)[r * wdw + j] = 0;
     }
     // ---- stage the block: signed bytes, true zeros behind the row so that the padding adds nothing ----
-    const int blk_bytes = B * C;
     int saa = 0;
-    for (int i = tid; i < B * (BS / 4); i += kMfmaThreads) {
-        const int r = i / (BS / 4), j = i - r * (BS / 4);
-        const uint8_t* src = cf + (size_t)(y0 + r) * row_bytes + (size_t)x0 * C;
-        uint32_t v = 0;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int f = 4 * j + b;
-            if (f < blk_bytes) {
-                const int a = (int)src[f] - 128;
-                saa += a * a;
-                v |= (uint32_t)(a & 0xff) << (8 * b);
-            }
+    if (blk_early) {
+        if (tid < B * (BS / 4)) {       // a dword outside the row arrives as 0x80808080: zeros once the offset is taken off
+            const uint32_t v = blk_raw ^ 0x80808080u;
+            saa = __builtin_amdgcn_sdot4((int)v, (int)v, 0, false);
+            reinterpret_cast<uint32_t*>(blk)[tid] = v;
         }
-        reinterpret_cast<uint32_t*>(blk)[i] = v;
+    } else {
+        for (int i = tid; i < B * (BS / 4); i += kMfmaThreads) {
+            const int r = i / (BS / 4), j = i - r * (BS / 4);
+            const uint8_t* src = cf + (size_t)(y0 + r) * row_bytes + (size_t)x0 * C;
+            uint32_t v = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int f = 4 * j + b;
+                if (f < blk_bytes) {
+                    const int a = (int)src[f] - 128;
+                    saa += a * a;
+                    v |= (uint32_t)(a & 0xff) << (8 * b);
+                }
+            }
+            reinterpret_cast<uint32_t*>(blk)[i] = v;
+        }
     }
     saa = wave_sum_i32(saa);
     __syncthreads();
@@ -352,12 +370,30 @@ __global__ __launch_bounds__(kMfmaThreads, 7) void match_mfma_kernel(
         }
     }
     __syncthreads();
-    for (int i = tid; i < nd * nd; i += kMfmaThreads) {
-        const int dyi = i / nd, dxi = i - dyi * nd;
-        int s = 0;
+    if constexpr (BT > 0) {
+        // a thread takes eight candidates dy of one dx: the first sum over its B rows, then seven steps down the column
+        // (one row enters, one leaves): 2 B - 2 + 16 reads for eight sums instead of 8 B
+        const int nch = (nd + 7) / 8;
+        for (int i = tid; i < nd * nch; i += kMfmaThreads) {
+            const int ch = i / nd, dxi = i - ch * nd, dy0 = 8 * ch;
+            int s = 0;
 #pragma unroll
-        for (int r = 0; r < B; ++r) s += h2[(dyi + r) * nd + dxi];
-        v2[i] = s;
+            for (int r = 0; r < BT; ++r) s += h2[(dy0 + r) * nd + dxi];
+            v2[dy0 * nd + dxi] = s;
+#pragma unroll
+            for (int q = 1; q < 8; ++q) {
+                if (dy0 + q >= nd) break;
+                s += h2[(dy0 + q + BT - 1) * nd + dxi] - h2[(dy0 + q - 1) * nd + dxi];
+                v2[(dy0 + q) * nd + dxi] = s;
+            }
+        }
+    } else {
+        for (int i = tid; i < nd * nd; i += kMfmaThreads) {
+            const int dyi = i / nd, dxi = i - dyi * nd;
+            int s = 0;
+            for (int r = 0; r < B; ++r) s += h2[(dyi + r) * nd + dxi];
+            v2[i] = s;
+        }
     }
 
     // ---- cross terms: this wavefront's share of the window rows ----
