@@ -561,6 +561,35 @@ def test_torus_with_the_border_case_and_layers_outside_the_cache(oracle):
     _run_one(oracle, layers, v, 16, 16, False, device_plan=True, exact_masks=False, torus=True, no_reuse=flags)
 
 
+def test_torus_with_more_streams_than_the_origin_tables_hold(oracle):
+    """Beyond 2048 streams the persistent kernels do not keep the origins in LDS: the first layer loads them from memory
+    and the 64-channel layers take the tiled GEMM kernel.  2100 small streams (three videos, repeated); six are compared."""
+    layers = synth.small_vgg()
+    n, T, H, W = 2100, 3, 32, 32
+    base = np.stack([synth.panning_video(7300 + s, n_frames=T, H=H, W=W, fg=((8, 8),), margin=16) for s in range(3)])
+    videos = base[np.arange(n) % 3]
+    ws, bs = synth.he_weights(layers, 1, bias_scale=0.05)
+    r = binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=8, dtype=binding.DC_BF16, device_plan=True,
+                            exact_masks=True, torus=True, want_origins=True)
+    followed = [0, 1, 2, 1037, 2098, 2099]
+    refs = {s: oracle.Stream(layers, ws, bs, H, W, 3, block=16, radius=8, bf16=True, exact_masks=True) for s in followed}
+    dv = torch.from_numpy(np.ascontiguousarray(videos.transpose(1, 0, 2, 3, 4))).to(DEV)
+    reused = 0
+    for t in range(T):
+        print(f"[many streams] step {t}", flush=True)
+        tensors = r.step(dv[t])
+        torch.cuda.synchronize()
+        org = r.origins.copy()
+        for s in followed:
+            want = refs[s].step(videos[s, t])
+            for ti in range(1, len(layers) + 1):
+                g = torch.roll(tensors[ti][s], shifts=(-int(org[s, ti, 1]), -int(org[s, ti, 0])), dims=(0, 1)).float().cpu().numpy()
+                assert _rel_err(g, want["tensors"][ti]) <= 2e-2, (t, s, ti)
+        if t > 0:
+            reused += int(r.read_stats().n_reusable_blocks)
+    assert reused > 0
+
+
 def test_torus_is_refused_for_stacks_it_cannot_take(oracle):
     layers = synth.resnet50_trunk()[:10]         # 1x1 and strided layers, adds
     H = W = 64
