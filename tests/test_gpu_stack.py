@@ -561,6 +561,15 @@ def test_torus_with_the_border_case_and_layers_outside_the_cache(oracle):
     _run_one(oracle, layers, v, 16, 16, False, device_plan=True, exact_masks=False, torus=True, no_reuse=flags)
 
 
+def test_torus_on_a_frame_whose_maps_do_not_fit_the_lds(oracle):
+    """640 x 480: the reuse bitmaps of the stack (more than 128 KB) are built in the workspace; the origins come from the
+    same planning kernel.  One full and two cached frames of one stream."""
+    video = synth.panning_video(7400, n_frames=3, H=480, W=640, fg=((96, 96),), margin=64)[None]
+    runner, reuse = _run_one(oracle, synth.small_vgg(), video, 16, 16, True, device_plan=True, exact_masks=True, torus=True,
+                             bias_scale=0.0)
+    assert max(reuse) > 0.5 and runner.origins.any()
+
+
 def test_torus_with_more_streams_than_the_origin_tables_hold(oracle):
     """Beyond 2048 streams the persistent kernels do not keep the origins in LDS: the first layer loads them from memory
     and the 64-channel layers take the tiled GEMM kernel.  2100 small streams (three videos, repeated); six are compared."""
