@@ -133,7 +133,8 @@ typedef struct {
                               already lies where this frame looks for it: a cached frame writes its non-reusable
                               pixels only (Section 5 "Reuse" without step 1).  A full frame writes every tensor at
                               its buffer's start (origins (0, 0)).  The values are those of the copying path.  Only
-                              stacks whose conv layers are 3x3 / stride 1 with whole 64-byte channel rows (or a
+                              stacks whose conv layers are 3x3 / stride 1 with whole 64-byte channel rows, 1x1 /
+                              stride 1 with whole 16-byte channel rows and a multiple of 8 output channels (or a
                               first layer on a 16-byte pixel vector) and whose conv outputs are read by such layers or by
                               2x2 / stride-2 max-pooling qualify (DC_ERR_UNSUPPORTED otherwise); every other tensor
                               is stored as always.  Together with cache_pool_add the outputs of the max-pooling layers

@@ -1031,7 +1031,8 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                 const bool first = l.in0 == 0 && cs[0] * esz == 16 && l.cout % 16 == 0 &&
                                    ((l.k == 3 && l.s == 1) || (l.k == 7 && l.s == 2) || (l.k == 11 && l.s == 4));
                 const bool gemm3 = l.k == 3 && l.s == 1 && l.cout % 64 == 0 && (l.cin * esz) % 64 == 0;
-                if (!plain_square(l) || !(first || gemm3)) return DC_ERR_UNSUPPORTED;
+                const bool point = l.k == 1 && l.s == 1 && l.p == 0 && l.cout % 8 == 0 && (l.cin * esz) % 16 == 0;
+                if (!plain_square(l) || !(first || gemm3 || point)) return DC_ERR_UNSUPPORTED;
                 if (!tensors_prev || tensors_prev[t] != tensors_cur[t]) return DC_ERR_INVALID_ARG;     // one buffer per conv output
             } else if (l.type == DC_MAXPOOL) {
                 if ((conv_output(l.in0) || pool_torus) &&

@@ -750,6 +750,14 @@ __global__ __launch_bounds__(WM * 128) void conv_pw_kernel(ConvParams P) {
         v.w = ((stream * P.Hout + uy * 4) * P.Wout + ux * 4) * P.Cout;
         H.uq[tid] = v;
         H.ukind[tid] = valid ? mixed : -1;
+        if (P.in_origin || P.out_origin) {      // tensors on a torus (stride 1 only: the launcher sees to it)
+            int4 og{0, 0, 0, 0};
+            const size_t at = (size_t)stream * P.origin_stride;
+            if (P.in_origin) { og.x = P.in_origin[at]; og.y = P.in_origin[at + 1]; }
+            if (P.out_origin) { og.z = P.out_origin[at]; og.w = P.out_origin[at + 1]; }
+            H.uorg[tid] = og;
+            H.ustream[tid] = stream;
+        }
     }
     __syncthreads();
     if (tid < G * 16) {
@@ -773,6 +781,11 @@ __global__ __launch_bounds__(WM * 128) void conv_pw_kernel(ConvParams P) {
         const int4 uq = H.uq[g];
         const bool ok = uq.y + oy < P.Hout && uq.z + ox < P.Wout;
         pgo[i] = ok ? (uint32_t)(uq.x + (oy * P.Win + ox) * P.s * CinES + (c << 4)) : kOob;
+        if (P.in_origin && ok) {        // the input lies on a torus: the pixel's place follows from the stream's origin
+            const int4 og = H.uorg[g];
+            const int iy = torus_wrap(uq.y + oy, og.y, P.Hin), ix = torus_wrap(uq.z + ox, og.x, P.Win);
+            pgo[i] = (uint32_t)(((H.ustream[g] * P.Hin + iy) * P.Win + ix) * CinES + (c << 4));
+        }
         const int ch = n0 + row / (NBW * 16) * (NBW * 16) + ((row & 15) >> 2) * (4 * NBW) + ((row >> 4) % NBW) * 4 + (row & 3);
         wgo[i] = ch < P.Cout ? (uint32_t)(ch * CinES + (c << 4)) : kOob;
     }
@@ -856,6 +869,11 @@ __global__ __launch_bounds__(WM * 128) void conv_pw_kernel(ConvParams P) {
         const int g = wave_m * UPW + u;
         if (H.skip[g * 16 + l16]) continue;
         T* px = reinterpret_cast<T*>(P.out) + H.uq[g].w + ((l16 >> 2) * P.Wout + (l16 & 3)) * P.Cout + chan0;
+        if (P.out_origin) {               // the output lies on a torus
+            const int4 og = H.uorg[g];
+            const int y = torus_wrap(H.uq[g].y + (l16 >> 2), og.w, P.Hout), x = torus_wrap(H.uq[g].z + (l16 & 3), og.z, P.Wout);
+            px = reinterpret_cast<T*>(P.out) + ((H.ustream[g] * P.Hout + y) * P.Wout + x) * P.Cout + chan0;
+        }
 #pragma unroll
         for (int j = 0; j < NBW; j += 2) {          // eight channels at a time (Cout is a multiple of 8)
             if (chan0 + j * 4 >= P.Cout) break;
@@ -1356,7 +1374,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
             return true;
         }
     }
-    if (enabled && !torus && c.k == 1 && c.p == 0 && (c.s == 1 || c.s == 2) && (c.Cin * esz) % 16 == 0 && c.Cout % 8 == 0 &&
+    if (enabled && (!torus || c.s == 1) && c.k == 1 && c.p == 0 && (c.s == 1 || c.s == 2) && (c.Cin * esz) % 16 == 0 && c.Cout % 8 == 0 &&
         reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
         constexpr bool pw_enabled = true;
@@ -1380,6 +1398,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
             P.w_bytes = (uint32_t)((size_t)c.Cout * c.Cin * esz);
             const int kc = (int)(128 / esz);
             P.n_chunks = (c.Cin + kc - 1) / kc;
+            P.in_origin = c.in_origin; P.out_origin = c.out_origin; P.origin_stride = c.origin_stride;
             P.R = (int)R;
             P.n_wg_tiles = (int)tiles;
             P.tiles_per_xcd = (int)((tiles + 7) / 8);

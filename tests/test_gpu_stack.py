@@ -561,6 +561,16 @@ def test_torus_with_the_border_case_and_layers_outside_the_cache(oracle):
     _run_one(oracle, layers, v, 16, 16, False, device_plan=True, exact_masks=False, torus=True, no_reuse=flags)
 
 
+@pytest.mark.parametrize("bf16,leaky", [(True, False), (False, True)])
+def test_torus_darknet_with_1x1_layers(oracle, bf16, leaky):
+    """The Darknet-19-style stack on a torus: 3x3 layers, 1x1 bottlenecks (the 1x1 kernel reads and writes through
+    origins), 2x2 poolings, maps with ragged units (13 x 13 at the end), ReLU or leaky ReLU."""
+    video = np.stack([synth.panning_video(7500 + s, n_frames=5, H=208, W=208, fg=((48, 48),), margin=32) for s in range(2)])
+    runner, reuse = _run_one(oracle, synth.darknet19(leaky=leaky)[:17], video, 16, 8, bf16, device_plan=True, exact_masks=True,
+                             torus=True, resets=(3,), bias_scale=0.02)
+    assert max(reuse) > 0.3 and runner.origins.any() and runner.shapes[-1][0] == 13
+
+
 def test_torus_on_a_frame_whose_maps_do_not_fit_the_lds(oracle):
     """640 x 480: the reuse bitmaps of the stack (more than 128 KB) are built in the workspace; the origins come from the
     same planning kernel.  One full and two cached frames of one stream."""
