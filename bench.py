@@ -68,7 +68,7 @@ def traffic_calib():
     print(json.dumps({"traffic_calib": "device copy", "bytes_read": n, "bytes_written": n, "launches": 5}))
 
 
-def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exact_masks=None, torus=None):
+def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exact_masks=None, torus=None, pool_cache=None):
     import numpy as np
     import torch
     from paper_1712_01670_amd import binding, synth
@@ -89,7 +89,8 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
     def make_runner(on_torus):
         return binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
                                    match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan,
-                                   exact_masks=exact, cache_pool_add=exact and args.cache_pool_add,
+                                   exact_masks=exact,
+                                   cache_pool_add=exact and (args.cache_pool_add if pool_cache is None else pool_cache),
                                    no_reuse=synth.no_reuse_flags(layers, args.min_reuse_macs) if args.min_reuse_macs > 0 else None,
                                    torus=on_torus)
     runner = make_runner(torus)
@@ -378,6 +379,12 @@ def main():
         cp = run_workload(args, n, args.dtype, args.steps, args.warmup, args.repeats, False, 0, torus=False)
         cp["config"] = {"reuse_by": "shifted copies", "streams": n, "steps": args.steps}
         out["shifted_copies"] = cp
+    if args.torus and args.regions == "exact" and not args.cache_pool_add and not args.no_single:
+        # the same workload with the max-pooling layers through the cache as well (their outputs on a torus of their
+        # own): another reading of the method's values (Section 5: the cache extends to other layer types)
+        pc = run_workload(args, n, args.dtype, args.steps, args.warmup, args.repeats, False, 0, pool_cache=True)
+        pc["config"] = {"cached_layers": "conv, max-pooling", "streams": n, "steps": args.steps}
+        out["poolings_cached"] = pc
     print(json.dumps(out))
 
 
