@@ -143,6 +143,12 @@ typedef struct {
                               bit is set is simply left alone; a caller that reads such a tensor needs origins_out. */
     int32_t* origins_out;  /* optional with torus: host [n_streams][n_layers + 1][2], receives (ox, oy) of every tensor
                               after a cached frame (for inspection: the call then waits for the planning) */
+    const int32_t** origins_dev_out; /* optional with torus: host pointer that receives the DEVICE address of this frame's
+                              origins, [n_streams][n_layers + 1][2] inside ws_dev (NULL after a full frame: every origin
+                              is (0, 0)).  Nothing waits.  The array is written by the frame's planning, which precedes
+                              its layers, and stays in place until the third dc_run_stack call from this one: pass
+                              it (plus 2 * tensor) to dc_torus_read on the call's stream to get a tensor in its
+                              logical layout. */
     int32_t device_plan;   /* dc_run_stack only.  0: the call waits for the matching, then merges, propagates and lists
                               the dirty units on the host.  1: three small kernels do that on the GPU from the block
                               mask in device memory (Section 4 Step 5, Section 5 "Propagation": the same rules, the
@@ -409,6 +415,15 @@ int32_t dc_cached_conv_layer_noalloc(const dc_layer* layer, const void* in, cons
 /* out[pixel][c] = (frames[pixel][c] - 128) / 128 for c < c_frame, 0 for c_frame <= c < c_tensor. */
 int32_t dc_frame_to_tensor(const uint8_t* frames, void* out, size_t n_pixels, int32_t c_frame,
                            int32_t c_tensor, int32_t dtype, void* stream);
+/* A tensor kept on a torus (dc_match_options.torus) in its logical layout:
+ * out[s][y][x][:] = in[s][(y + oy) mod H][(x + ox) mod W][:] with (ox, oy) = origins_dev[s * origin_stride + 0 / 1].
+ * in, out: dev [n_streams][H][W][C] in `dtype`, distinct buffers; origins_dev: dev, or NULL for a plain copy (the
+ * tensors of a full frame); origin_stride: ints between the entries of consecutive streams (2 * (n_layers + 1) for
+ * the array dc_run_stack reports through origins_dev_out, offset by 2 * tensor).  n_streams * H <= 65535.
+ * For the callers of dc_run_stack with torus: Section 5's cached feature maps stay where they are, this is the one
+ * place where a reader gets them as the paper's layout has them. */
+int32_t dc_torus_read(const void* in, void* out, const int32_t* origins_dev, int32_t origin_stride, int32_t n_streams,
+                      int32_t H, int32_t W, int32_t C, int32_t dtype, void* stream);
 int32_t dc_maxpool_layer(const void* in, void* out, int32_t n_streams, int32_t Hin, int32_t Win,
                          int32_t C, int32_t k, int32_t s, int32_t p, int32_t dtype, void* stream);
 int32_t dc_add_layer(const void* a, const void* b, void* out, size_t n, int32_t relu,

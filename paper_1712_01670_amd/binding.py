@@ -23,7 +23,7 @@ STATUS = {0: "DC_OK", -1: "DC_ERR_INVALID_ARG", -2: "DC_ERR_NULL_PTR", -3: "DC_E
 
 EXPORTS = ["dc_status_string", "dc_profile_create", "dc_profile_destroy", "dc_profile_reset",
            "dc_profile_elapsed_ms", "dc_overlap_create", "dc_overlap_destroy", "dc_overlap_pipeline", "dc_prefetch_match", "dc_conv_tuning", "dc_conv_kernel_name", "dc_conv_tile_shape", "dc_match_blocks", "dc_match_blocks_ds", "dc_match_blocks_opt", "dc_propagate_regions", "dc_propagate_regions_opt", "dc_conv_workspace_bytes",
-           "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_maxpool_layer", "dc_add_layer", "dc_avgpool_layer", "dc_lrn_layer", "dc_concat_layer", "dc_fc_layer", "dc_softmax_layer",
+           "dc_packed_weights_bytes", "dc_pack_conv_weights", "dc_cached_conv_layer", "dc_frame_to_tensor", "dc_torus_read", "dc_maxpool_layer", "dc_add_layer", "dc_avgpool_layer", "dc_lrn_layer", "dc_concat_layer", "dc_fc_layer", "dc_softmax_layer",
            "dc_stack_workspace_bytes", "dc_run_stack", "dc_stack_stats_fetch", "dc_cached_conv_layer_noalloc",
            "dc_propagate_masks_size", "dc_propagate_masks", "dc_probe_mfma_rate"]
 
@@ -53,7 +53,7 @@ class Regions(C.Structure):
 class MatchOptions(C.Structure):
     _fields_ = [("method", C.c_int32), ("k_skip", C.c_int32), ("extend_borders", C.c_int32), ("exact_masks", C.c_int32),
                 ("cache_pool_add", C.c_int32), ("no_reuse", C.c_void_p), ("torus", C.c_int32), ("origins_out", C.c_void_p),
-                ("device_plan", C.c_int32)]
+                ("origins_dev_out", C.POINTER(C.c_void_p)), ("device_plan", C.c_int32)]
 
 
 DC_MATCH_EXHAUSTIVE, DC_MATCH_DIAMOND = 0, 1
@@ -101,6 +101,7 @@ def lib():
         L.dc_cached_conv_layer.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp, sz, vp, sz, vp]
         L.dc_frame_to_tensor.argtypes = [vp, vp, sz, i32, i32, i32, vp]
         L.dc_maxpool_layer.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+        L.dc_torus_read.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
         L.dc_add_layer.argtypes = [vp, vp, vp, sz, i32, i32, vp]
         f32 = C.c_float
         L.dc_avgpool_layer.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
@@ -480,10 +481,12 @@ class StackRunner:
         # for the planning): logical_tensors() needs it.
         self.torus = bool(torus) and self.device_plan
         self.origins = np.zeros((n_streams, len(layers) + 1, 2), np.int32) if (self.torus and want_origins) else None
+        self._origins_dev = C.c_void_p(None)      # device address of the last frame's origins (torus), set by every step
         self.match_options = MatchOptions(int(match_method), int(k_skip), int(extend_borders), int(self.exact_masks),
                                           int(self.cache_pool_add),
                                           None if self._no_reuse is None else self._no_reuse.ctypes.data, int(self.torus),
-                                          None if self.origins is None else self.origins.ctypes.data, int(self.device_plan))
+                                          None if self.origins is None else self.origins.ctypes.data,
+                                          C.pointer(self._origins_dev) if self.torus else None, int(self.device_plan))
         self.device = torch.device(device)
         td = torch_dtype(dtype)
         self.Lc = layers_to_c(layers)
@@ -604,6 +607,19 @@ class StackRunner:
         if self.last_in_place:
             return [self.bufs[p if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]
         return [self.bufs[c if self._is_conv_out[t] else cn][t] for t in range(len(self.bufs[c]))]
+
+    def read_tensor(self, t, tensors):
+        """With torus: tensor t of the last step in its logical layout, written by dc_torus_read on the current stream
+        (no wait for anything; without torus the tensor itself)."""
+        x = tensors[t]
+        if not self.torus:
+            return x
+        out = torch.empty_like(x)
+        n, h, w, c = x.shape
+        base = self._origins_dev.value
+        _check("dc_torus_read", lib().dc_torus_read(_ptr(x), _ptr(out), C.c_void_p(base + 8 * t) if base else None,
+                                                    2 * (len(self.layers) + 1), n, h, w, c, self.dtype, _stream()))
+        return out
 
     def logical_tensors(self, tensors):
         """With torus: the tensors of the last step in their logical layout (copies; needs want_origins and a synchronised

@@ -790,6 +790,17 @@ int32_t dc_maxpool_layer(const void* in, void* out, int32_t n_streams, int32_t H
     return DC_OK;
 }
 
+int32_t dc_torus_read(const void* in, void* out, const int32_t* origins_dev, int32_t origin_stride, int32_t n_streams,
+                      int32_t H, int32_t W, int32_t C, int32_t dtype, void* stream) {
+    if (!in || !out) return DC_ERR_NULL_PTR;
+    if (in == out) return DC_ERR_INVALID_ARG;
+    if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
+    if (n_streams < 1 || H < 1 || W < 1 || C < 1 || (origins_dev && origin_stride < 2)) return DC_ERR_INVALID_ARG;
+    if ((size_t)n_streams * H > 65535) return DC_ERR_UNSUPPORTED;
+    DC_TRY_HIP(launch_torus_read(in, out, n_streams, H, W, (size_t)C * dtype_size(dtype), origins_dev, origin_stride, as_stream(stream)));
+    return DC_OK;
+}
+
 int32_t dc_add_layer(const void* a, const void* b, void* out, size_t n, int32_t relu, int32_t dtype, void* stream) {
     if (!a || !b || !out) return DC_ERR_NULL_PTR;
     if (dtype != DC_F32 && dtype != DC_BF16) return DC_ERR_INVALID_ARG;
@@ -1187,6 +1198,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
                   dl.table_bytes <= kDevHostRegion - 3 * kDevHostSlot;
     }
     if (torus && cached && !devplan) return DC_ERR_UNSUPPORTED;      // a torus frame is planned on the GPU or not at all
+    if (torus && !cached && match_options->origins_dev_out) *match_options->origins_dev_out = nullptr;
     if (torus && !cached && ws_host && ws_host_bytes >= kDevHostRegion + 256) {
         // a full frame writes every tensor at its buffer's start: the next cached frame starts from origins (0, 0)
         DevHostHeader* h = reinterpret_cast<DevHostHeader*>(hbase + ((ws_host_bytes - kDevHostRegion) & ~(size_t)255));
@@ -1305,6 +1317,7 @@ int32_t dc_run_stack(const dc_layer* layers, int32_t n_layers, const void* const
         }
         hdr->last_slot = slot;
         hdr->n_blocks = (int32_t)nb;
+        if (torus && match_options->origins_dev_out) *match_options->origins_dev_out = pd.origin;
         if (torus && match_options->origins_out) {      // for inspection only: wait for the plan and read the origins back
             DC_TRY_HIP(hipStreamSynchronize(pst));
             DC_TRY_HIP(hipMemcpy(match_options->origins_out, pd.origin, (size_t)n_streams * (n_layers + 1) * 2 * sizeof(int32_t),

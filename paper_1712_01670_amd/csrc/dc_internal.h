@@ -135,6 +135,9 @@ hipError_t launch_match_diamond(const uint8_t* cur, const uint8_t* prev, int n_s
                                 int32_t* n_pass, uint8_t* mask, hipStream_t st);
 hipError_t launch_frame_to_tensor(const uint8_t* f, void* out, size_t n_pixels, int cf, int ct, int dtype,
                                   hipStream_t st);
+// out[s][y][x] = in[s][(y + oy) mod H][(x + ox) mod W], (ox, oy) = origin[s * origin_stride + 0 / 1] (nullptr: a copy)
+hipError_t launch_torus_read(const void* in, void* out, int n_streams, int H, int W, size_t pixel_bytes,
+                             const int32_t* origin, int origin_stride, hipStream_t st);
 hipError_t launch_maxpool(const void* in, void* out, int n_streams, int Hin, int Win, int C, int k,
                           int s, int p, int dtype, hipStream_t st);
 hipError_t launch_add(const void* a, const void* b, void* out, size_t n, int relu, int dtype,

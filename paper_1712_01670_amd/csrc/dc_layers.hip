@@ -626,6 +626,36 @@ hipError_t launch_shifted_copy_all(const RectDev* rects_dev, int n_rects, const 
     return hipSuccess;
 }
 
+// A tensor that lies on a torus, written out from its origin: out[s][y][x] = in[s][(y + oy) mod H][(x + ox) mod W].
+// A thread moves one vector of V bytes; grid.y = (stream, row).
+template <typename V>
+__global__ __launch_bounds__(kThreads) void torus_read_kernel(const V* __restrict__ in, V* __restrict__ out, int H, int W, int PV,
+                                                              const int32_t* __restrict__ origin, int origin_stride) {
+    const int row = blockIdx.y, stream = row / H, y = row - stream * H;
+    const int j = (int)blockIdx.x * kThreads + (int)threadIdx.x;
+    if (j >= W * PV) return;
+    const int x = j / PV, v = j - x * PV;
+    const int ox = origin ? origin[(size_t)stream * origin_stride] : 0, oy = origin ? origin[(size_t)stream * origin_stride + 1] : 0;
+    out[(size_t)row * W * PV + j] = in[(((size_t)stream * H + torus_wrap(y, oy, H)) * W + torus_wrap(x, ox, W)) * PV + v];
+}
+
+hipError_t launch_torus_read(const void* in, void* out, int n_streams, int H, int W, size_t pixel_bytes,
+                             const int32_t* origin, int origin_stride, hipStream_t st) {
+    if ((size_t)n_streams * H > 65535) return hipErrorInvalidValue;
+    const bool v16 = pixel_bytes % 16 == 0 && reinterpret_cast<uintptr_t>(in) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0;
+    const bool v4 = pixel_bytes % 4 == 0 && reinterpret_cast<uintptr_t>(in) % 4 == 0 && reinterpret_cast<uintptr_t>(out) % 4 == 0;
+    const int vb = v16 ? 16 : (v4 ? 4 : 1);
+    const int pv = (int)(pixel_bytes / vb);
+    const dim3 grid((unsigned)(((size_t)W * pv + kThreads - 1) / kThreads), (unsigned)(n_streams * H));
+    if (v16)
+        hipLaunchKernelGGL(torus_read_kernel<uint4>, grid, dim3(kThreads), 0, st, (const uint4*)in, (uint4*)out, H, W, pv, origin, origin_stride);
+    else if (v4)
+        hipLaunchKernelGGL(torus_read_kernel<uint32_t>, grid, dim3(kThreads), 0, st, (const uint32_t*)in, (uint32_t*)out, H, W, pv, origin, origin_stride);
+    else
+        hipLaunchKernelGGL(torus_read_kernel<uint8_t>, grid, dim3(kThreads), 0, st, (const uint8_t*)in, (uint8_t*)out, H, W, pv, origin, origin_stride);
+    return hipGetLastError();
+}
+
 hipError_t launch_frame_to_tensor(const uint8_t* f, void* out, size_t n_pixels, int cf, int ct, int dtype,
                                   hipStream_t st) {
     const size_t n = n_pixels * ct;

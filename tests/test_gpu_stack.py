@@ -539,6 +539,39 @@ def test_torus_vgg16_two_streams(oracle):
     assert runner.read_stats().copy_bytes == 0
 
 
+def test_torus_tensors_read_without_a_wait(oracle):
+    """dc_torus_read with the device address of the frame's origins (origins_dev_out): the logical tensors without any
+    host wait, equal to those rolled on the host from origins_out; full frames (no origins) included."""
+    layers = synth.small_vgg()
+    video = np.stack([synth.panning_video(7600 + s, n_frames=6, H=96, W=96, fg=((24, 24),), margin=32) for s in range(3)])
+    ws, bs = synth.he_weights(layers, 1, bias_scale=0.05)
+    r = binding.StackRunner(layers, ws, bs, 3, 96, 96, 3, block=16, radius=16, dtype=binding.DC_BF16, device_plan=True,
+                            exact_masks=True, cache_pool_add=True, torus=True, want_origins=True, expiry=4)
+    dv = torch.from_numpy(np.ascontiguousarray(video.transpose(1, 0, 2, 3, 4))).to(DEV)
+    moved = False
+    for t in range(6):
+        tensors = r.step(dv[t])
+        got = [r.read_tensor(ti, tensors) for ti in range(len(layers) + 1)]      # queued behind the frame, nothing waited for
+        torch.cuda.synchronize()
+        want = r.logical_tensors(tensors)
+        moved = moved or bool(r.origins.any())
+        for ti in range(len(layers) + 1):
+            assert torch.equal(got[ti], want[ti]), (t, ti)
+    assert moved
+    # odd channel counts and element sizes take the narrower vectors
+    x = torch.randn((2, 5, 7, 3), device=DEV)
+    org = torch.tensor([[3, 1], [6, 4]], dtype=torch.int32, device=DEV)
+    out = torch.empty_like(x)
+    L = binding.lib()
+    import ctypes as C
+    assert L.dc_torus_read(C.c_void_p(x.data_ptr()), C.c_void_p(out.data_ptr()), C.c_void_p(org.data_ptr()), 2, 2, 5, 7, 3,
+                           binding.DC_F32, None) == 0
+    torch.cuda.synchronize()
+    for s in range(2):
+        assert torch.equal(out[s], torch.roll(x[s], shifts=(-int(org[s, 1]), -int(org[s, 0])), dims=(0, 1)))
+    assert L.dc_torus_read(C.c_void_p(x.data_ptr()), C.c_void_p(x.data_ptr()), None, 2, 2, 5, 7, 3, binding.DC_F32, None) == -1
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_poolings_on_the_torus_too(oracle, bf16):
     """torus with cache_pool_add: the poolings' outputs are cache values on a torus of their own, a pooled pixel whose map
