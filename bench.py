@@ -68,7 +68,8 @@ def traffic_calib():
     print(json.dumps({"traffic_calib": "device copy", "bytes_read": n, "bytes_written": n, "launches": 5}))
 
 
-def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exact_masks=None, torus=None, pool_cache=None):
+def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exact_masks=None, torus=None, pool_cache=None,
+                 k_skip=None):
     import numpy as np
     import torch
     from paper_1712_01670_amd import binding, synth
@@ -88,7 +89,8 @@ def run_workload(args, n, dtype, steps, warmup, repeats, detail, cpu_frames, exa
 
     def make_runner(on_torus):
         return binding.StackRunner(layers, ws, bs, n, H, W, 3, block=16, radius=16, dtype=dt, expiry=args.expiry,
-                                   match_method=method, k_skip=args.k_skip, device_plan=not args.host_plan,
+                                   match_method=method, k_skip=args.k_skip if k_skip is None else k_skip,
+                                   device_plan=not args.host_plan,
                                    exact_masks=exact,
                                    cache_pool_add=exact and (args.cache_pool_add if pool_cache is None else pool_cache),
                                    no_reuse=synth.no_reuse_flags(layers, args.min_reuse_macs) if args.min_reuse_macs > 0 else None,
@@ -385,6 +387,12 @@ def main():
         pc = run_workload(args, n, args.dtype, args.steps, args.warmup, args.repeats, False, 0, pool_cache=True)
         pc["config"] = {"cached_layers": "conv, max-pooling", "streams": n, "steps": args.steps}
         out["poolings_cached"] = pc
+    if args.k_skip == 1 and not args.no_single:
+        # the same workload with Step 2 on every second block row and column only (Section 4's k-skip, k = 2)
+        ks = run_workload(args, n, args.dtype, args.steps, args.warmup, args.repeats, False, 0, k_skip=2)
+        ks["config"] = {"matcher": ("exhaustive search" if args.matcher == "es" else "diamond search") + ", k-skip 2",
+                        "streams": n, "steps": args.steps}
+        out["k_skip_2"] = ks
     print(json.dumps(out))
 
 
