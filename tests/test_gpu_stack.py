@@ -582,6 +582,11 @@ def test_poolings_on_the_torus_too(oracle, bf16):
     assert max(reuse) > 0.3 and runner.origins[:, 3].any()       # tensor 3 is the first pooling's output
     v = np.stack([synth.panning_video(5000 + s, n_frames=4, H=96, W=96, fg=((24, 24),), margin=32) for s in range(2)])
     _run_one(oracle, synth.vgg16(), v, 16, 16, bf16, device_plan=True, exact_masks=True, cache_pool_add=True, torus=True, bias_scale=0.0)
+    if bf16:     # enough units for the register-weight kernel in the second layer, whose output the first pooling reads
+        v32 = np.stack([synth.panning_video(7700 + s, n_frames=4, H=96, W=96, fg=((24, 24),), margin=32) for s in range(32)])
+        runner, _ = _run_one(oracle, synth.small_vgg(), v32, 16, 16, True, device_plan=True, exact_masks=True, cache_pool_add=True,
+                             torus=True, resets=(2,))
+        assert runner.layer_stats()["kernel_id"][1] == 130
 
 
 def test_torus_with_the_border_case_and_layers_outside_the_cache(oracle):
