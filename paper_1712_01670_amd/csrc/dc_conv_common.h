@@ -129,6 +129,12 @@ __device__ __forceinline__ void activate4(floatx4& v, int mode) {
 }
 
 __device__ __forceinline__ int fast_div(int n, uint32_t magic) { return (int)__umulhi((uint32_t)n, magic); }
+// floor(n / d) for any 0 <= n < 2^31 with magic = ceil(2^32 / d): the product above is exact while n d < 2^32 and one
+// too large at most beyond that (the stream of a raster position in a large batch).
+__device__ __forceinline__ int fast_div_any(int n, uint32_t magic, int d) {
+    const uint32_t q = __umulhi((uint32_t)n, magic);
+    return (int)(q * (uint32_t)d > (uint32_t)n ? q - 1 : q);
+}
 
 // Number of units this launch works on: the host's count, or the one the planning kernels left in memory.
 __device__ __forceinline__ int unit_count(const ConvParams& P) {

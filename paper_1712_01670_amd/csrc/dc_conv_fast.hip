@@ -68,8 +68,8 @@ __device__ __forceinline__ void decode_units_fast(const ConvParams& P, const Fas
             if (P.units) {
                 const TileDev t = P.units[u];
                 stream = t.stream; uy = t.ty; ux = t.tx; mixed = t.reuse_mask;
-            } else {   // raster order; exact for u * (units per map) < 2^32 (checked by the launcher)
-                stream = fast_div(u, P.npix_magic);
+            } else {   // raster order
+                stream = fast_div_any(u, P.npix_magic, P.units_x * P.units_y);
                 const int r = u - stream * (P.units_x * P.units_y);
                 uy = fast_div(r, P.pw_magic); ux = r - uy * P.units_x;
             }
@@ -443,7 +443,7 @@ __device__ __forceinline__ TileDev regw_fetch(const ConvParams& P, long u, int n
     TileDev t{0, 0, 0, -1};                 // reuse_mask -1: no such unit
     if (u >= n_units) return t;
     if (P.units) return P.units[u];
-    t.stream = fast_div((int)u, P.npix_magic);
+    t.stream = fast_div_any((int)u, P.npix_magic, P.units_x * P.units_y);
     const int rem = (int)u - t.stream * (P.units_x * P.units_y);
     t.ty = fast_div(rem, P.pw_magic); t.tx = rem - t.ty * P.units_x;
     t.reuse_mask = 0;
@@ -738,7 +738,7 @@ __global__ __launch_bounds__(WM * 128) void conv_pw_kernel(ConvParams P) {
                 const TileDev td = P.units[u];
                 stream = td.stream; uy = td.ty; ux = td.tx; mixed = td.reuse_mask;
             } else {
-                stream = fast_div(u, P.npix_magic);
+                stream = fast_div_any(u, P.npix_magic, P.units_x * P.units_y);
                 const int r = u - stream * (P.units_x * P.units_y);
                 uy = fast_div(r, P.pw_magic); ux = r - uy * P.units_x;
             }
@@ -957,7 +957,7 @@ __device__ __forceinline__ void conv_first_body(const ConvParams& P) {
             const TileDev t = P.units[u];
             r.stream = t.stream; r.uy = t.ty; r.ux = t.tx; r.mixed = t.reuse_mask & 0xffff;
         } else {
-            r.stream = fast_div(u, P.npix_magic);
+            r.stream = fast_div_any(u, P.npix_magic, P.units_x * P.units_y);
             const int rem = u - r.stream * per;
             r.uy = fast_div(rem, P.pw_magic); r.ux = rem - r.uy * P.units_x;
             r.mixed = 0;
@@ -1344,7 +1344,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
         reinterpret_cast<uintptr_t>(c.in) % 16 == 0 && reinterpret_cast<uintptr_t>(c.w) % 16 == 0 &&
         reinterpret_cast<uintptr_t>(c.out) % 16 == 0 && (!c.bias || reinterpret_cast<uintptr_t>(c.bias) % 16 == 0)) {
         const int units_y = (c.Hout + 3) / 4, units_x = (c.Wout + 3) / 4;
-        if ((double)c.n_streams * c.Hout * c.Wout * c.Cout < 2147483648.0 && (double)n_cap * units_x * units_y < 4294967296.0) {
+        if ((double)c.n_streams * c.Hout * c.Wout * c.Cout < 2147483648.0) {
             ConvParams P{};
             P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
             P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
@@ -1385,7 +1385,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
         const int g_units = 2 * wm, nt = 32 * wm;
         const long R = (c.Cout + nt - 1) / nt, tiles = (n_cap + g_units - 1) / g_units * R;
         if (pw_enabled && (double)c.n_streams * c.Hout * c.Wout * c.Cout < 2147483648.0 &&
-            (double)n_cap * units_x * units_y < 4294967296.0 && tiles + 8 < 2147483647L / (wm * 128)) {
+            tiles + 8 < 2147483647L / (wm * 128)) {
             ConvParams P{};
             P.in = c.in; P.w = c.w; P.bias = c.bias; P.out = c.out;
             P.Hin = c.Hin; P.Win = c.Win; P.Cin = c.Cin; P.Hout = c.Hout; P.Wout = c.Wout; P.Cout = c.Cout;
@@ -1415,11 +1415,7 @@ bool launch_conv_fast(const ConvLaunch& c, long n_cap, long n_units, hipStream_t
     if (!enabled || c.k != 3 || c.s != 1 || c.Cout % geom_nt(0) != 0 || c.Cin % (64 / esz) != 0) return false;
     if (reinterpret_cast<uintptr_t>(c.in) % 16 || reinterpret_cast<uintptr_t>(c.w) % 16) return false;
     if (reinterpret_cast<uintptr_t>(c.out) % 16 || (c.bias && reinterpret_cast<uintptr_t>(c.bias) % 16)) return false;
-    {   // 32-bit output offsets, exact magic-number division of the unit index
-        const double units_map = (double)((c.Hout + 3) / 4) * ((c.Wout + 3) / 4);
-        if ((double)c.n_streams * c.Hout * c.Wout * c.Cout >= 2147483648.0 || (double)n_cap * units_map >= 4294967296.0)
-            return false;
-    }
+    if ((double)c.n_streams * c.Hout * c.Wout * c.Cout >= 2147483648.0) return false;      // 32-bit output offsets
     // 64 input channels in bf16 and enough units to keep persistent workgroups busy: the weights go to registers
     if (c.dtype == DC_BF16 && c.Cin == 64 && c.relu != 2 && (!torus || c.n_streams <= kRegwTorusStreams) && (g_tune[0] == 3 || (g_tune[0] < 0 && g_tune[1] < 0 && n_units >= 4096))) {
         ConvParams P{};

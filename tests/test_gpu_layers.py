@@ -569,3 +569,19 @@ def test_kernels_that_are_not_square_or_dilated(oracle, case, bf16, cached):
         else:
             want = oracle.conv_cached(x[i], w, b, kh, s, ph, True, bf16=bf16, k2=kw, p2=pw, dil=dil)
         assert _rel_err(got[i], want) <= (2e-2 if bf16 else 1e-4), (case, i)
+
+
+def test_raster_positions_of_a_large_batch(oracle):
+    """40 streams of 416 x 416: the product of a unit's raster position and the units per map passes 2^32, where the
+    kernels' division by a magic number is one too large and is corrected.  First-layer shape and a 3x3 layer; the first
+    and the last stream against the oracle."""
+    n, H, W = 40, 416, 416
+    for cin, cout in ((8, 32), (32, 64)):
+        rng = np.random.default_rng(cin)
+        x = oracle.round_bf16(rng.standard_normal((n, H, W, cin)).astype(np.float32))
+        w = oracle.round_bf16((rng.standard_normal((cout, 3, 3, cin)) * np.sqrt(2.0 / (cin * 9))).astype(np.float32))
+        got = binding.dc_cached_conv_layer(_layer(cin, cout, 3, 1, 1, True), _to_dev(x, True), _to_dev(w, True), None)
+        torch.cuda.synchronize()
+        for s in (0, n - 1):
+            want = oracle.conv_cached(x[s], w, None, 3, 1, 1, True, bf16=True)
+            assert _rel_err(got[s].float().cpu().numpy(), want) <= 2e-2, (cin, s)
