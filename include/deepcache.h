@@ -140,7 +140,10 @@ typedef struct {
                               is stored as always.  Together with cache_pool_add the outputs of the max-pooling layers
                               (every one of them must then be such a 2x2 pooling of a conv output, read by conv layers
                               only; no add layers) are single buffers on a torus as well, and a pooled pixel whose map
-                              bit is set is simply left alone; a caller that reads such a tensor needs origins_out. */
+                              bit is set is simply left alone.  A caller that reads a tensor kept on a torus (the stack's
+                              output, if a conv layer ends it) goes through dc_torus_read (origins_dev_out) or
+                              origins_out.  Calls on one workspace pair must not overlap: the next frame starts from
+                              the origins this one leaves there. */
     int32_t* origins_out;  /* optional with torus: host [n_streams][n_layers + 1][2], receives (ox, oy) of every tensor
                               after a cached frame (for inspection: the call then waits for the planning) */
     const int32_t** origins_dev_out; /* optional with torus: host pointer that receives the DEVICE address of this frame's
