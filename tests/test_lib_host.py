@@ -56,6 +56,12 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.dc_prefetch_match(one, one, one, 1, 64, 4, 3, 8, 8, 0, None, one, one, one, one, one, one, 4096) == -3   # block > frame
     assert L.dc_prefetch_match(one, one, one, 1, 64, 64, 3, 8, 8, 0, None, one, one, one, one, one, one, 16) == -5
     bad = binding.layers_to_c([dict(type=0, k=3, s=0, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
+    two = C.c_void_p(32)
+    assert L.dc_torus_read(None, one, None, 2, 1, 8, 8, 4, 0, None) == -2
+    assert L.dc_torus_read(one, one, None, 2, 1, 8, 8, 4, 0, None) == -1          # in place
+    assert L.dc_torus_read(one, two, None, 2, 1, 8, 8, 4, 7, None) == -1          # dtype
+    assert L.dc_torus_read(one, two, one, 1, 1, 8, 8, 4, 0, None) == -1           # stride below one entry
+    assert L.dc_torus_read(one, two, None, 2, 70000, 8, 8, 4, 0, None) == -4      # rows beyond the grid
     assert L.dc_cached_conv_layer(bad, one, one, None, None, None, one, 1, 8, 8, None, 0, None, 0, None, 0, None) == -1
     ok = binding.layers_to_c([dict(type=0, k=3, s=1, p=1, cin=3, cout=8, relu=1, in0=0, in1=-1)])
     assert L.dc_cached_conv_layer(ok, one, one, None, None, None, one, 1, 8, 8, None, 7, None, 0, None, 0, None) == -1
